@@ -1,0 +1,128 @@
+/*
+ * distal.h - C ABI of the MI355X (gfx950) leaf-kernel library for the dense
+ * tensor-algebra expressions of DISTAL (Yadav, Aiken, Kjolstad, PLDI 2022).
+ *
+ * A distributed schedule in the paper ends in a leaf: the code one processor
+ * runs on the tiles it holds, either generated loops or a substituted
+ * optimised kernel (the `substitute` command of the introductory SUMMA
+ * listing).  This library is that leaf for five expressions, each stated in the
+ * paper's tensor index notation, where an index that appears only on the
+ * right-hand side is summed over its whole extent (background section).
+ *
+ * Common rules for every call
+ *   - All tensor pointers are DEVICE pointers (HBM of the current HIP device)
+ *     to dense row-major data, last index fastest (evaluation section: inputs
+ *     are laid out row-major).  Element type is given by `dt`.
+ *   - The caller owns every buffer, including workspaces.  The library never
+ *     allocates, frees or synchronises inside these calls.  Inputs are only read.
+ *   - `stream` is a hipStream_t passed as void*; NULL is the default stream.
+ *     Calls are asynchronous: outputs are valid once the stream reaches the
+ *     point of the call.
+ *   - Return value: DISTAL_OK (0) or a distal_status error code.  All argument
+ *     checks happen on the host before anything is launched, so a call that
+ *     returns an argument error has touched no device memory.
+ *   - Extents are int64_t.  An extent of zero in a summed index gives a zero
+ *     output (or leaves C unchanged under `accumulate`); an extent of zero in an
+ *     output index is a successful no-op.  Negative extents are an error.
+ *   - An output that starts at the same address as an input is rejected
+ *     (DISTAL_ERR_ALIAS); partial overlaps are not detected and are undefined.
+ *   - Arithmetic: binary64 expressions multiply and accumulate in binary64;
+ *     binary32 expressions multiply and accumulate in binary32 or wider.  No
+ *     reduced-precision emulation.  Summation order is fixed for a given call
+ *     signature, so results are bitwise reproducible run to run.
+ */
+#ifndef DISTAL_H
+#define DISTAL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { DISTAL_F32 = 0, DISTAL_F64 = 1 } distal_dtype;
+
+typedef enum {
+    DISTAL_OK = 0,
+    DISTAL_ERR_NULL = 1,      /* a required pointer is NULL                      */
+    DISTAL_ERR_SHAPE = 2,     /* negative extent, or extents whose product overflows */
+    DISTAL_ERR_DTYPE = 3,     /* dt is not DISTAL_F32 / DISTAL_F64               */
+    DISTAL_ERR_STRIDE = 4,    /* a leading dimension is smaller than its row     */
+    DISTAL_ERR_ALIAS = 5,     /* output pointer equals an input pointer          */
+    DISTAL_ERR_WORKSPACE = 6, /* workspace missing, misaligned or too small      */
+    DISTAL_ERR_LAUNCH = 7     /* the HIP runtime refused a kernel launch         */
+} distal_status;
+
+/*
+ * Matrix-multiply tile step:  C(i,j) = [C(i,j) +] sum_k A(i,k) * B(k,j).
+ * This is the local update every matrix-multiplication schedule of the paper
+ * issues once per k-step ("A += B_l x C_l" in the SUMMA pseudocode, the tile
+ * product of the Cannon and Johnson pseudocode; the paper names the output A
+ * and the inputs B and C).
+ *   A: M x K, row i starts at A + i*lda.   B: K x N, row k at B + k*ldb.
+ *   C: M x N, row i at C + i*ldc.  lda >= K, ldb >= N, ldc >= N, in elements,
+ *   so operands may be sub-blocks (k-chunks, tiles) of larger matrices.
+ *   accumulate == 0: C is overwritten (its old contents are not read).
+ *   accumulate != 0: the k-sum is added to the old C (SUMMA / Cannon k-steps).
+ */
+int distal_gemm(distal_dtype dt, int64_t M, int64_t N, int64_t K,
+                const void *A, int64_t lda, const void *B, int64_t ldb,
+                void *C, int64_t ldc, int accumulate, void *stream);
+
+/*
+ * Tensor times matrix:  A(i,j,l) = sum_k B(i,j,k) * C(k,l)
+ * (evaluation section, list of higher-order expressions).
+ *   B: I x J x K, C: K x L, A: I x J x L, all dense.  A is overwritten.
+ */
+int distal_ttm(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L,
+               const void *B, const void *C, void *A, void *stream);
+
+/*
+ * Matricized tensor times Khatri-Rao product:
+ *   A(i,l) = sum_j sum_k B(i,j,k) * C(j,l) * D(k,l)
+ * (evaluation section, list of higher-order expressions).
+ *   B: I x J x K, C: J x L, D: K x L, A: I x L, all dense.  A is overwritten.
+ *   workspace: device scratch of at least distal_mttkrp_workspace_bytes(...)
+ *   bytes, 256-byte aligned; may be NULL when that size is 0.  Its contents on
+ *   entry are ignored and on exit are unspecified.
+ */
+int distal_mttkrp(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L,
+                  const void *B, const void *C, const void *D, void *A,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Tensor times vector:  A(i,j) = sum_k B(i,j,k) * c(k)
+ * (background section on tensor index notation; evaluation list).
+ *   B: I x J x K, c: K, A: I x J, all dense.  A is overwritten.
+ */
+int distal_ttv(distal_dtype dt, int64_t I, int64_t J, int64_t K,
+               const void *B, const void *c, void *A, void *stream);
+
+/*
+ * Tensor inner product:  a = sum_i sum_j sum_k B(i,j,k) * C(i,j,k)
+ * (evaluation list).  B, C: I x J x K dense.  `a` is a DEVICE pointer to one
+ * element of type dt, overwritten.  Products are summed in binary64 for both
+ * dtypes (per-block partial sums, then one fixed-order final pass - the
+ * on-device part of the paper's "node-level reduction"), and rounded once to dt.
+ *   workspace: device scratch of at least distal_innerprod_workspace_bytes(...)
+ *   bytes, 256-byte aligned.
+ */
+int distal_innerprod(distal_dtype dt, int64_t I, int64_t J, int64_t K,
+                     const void *B, const void *C, void *a,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/* Scratch sizes for the two calls above (0 for invalid arguments). */
+size_t distal_mttkrp_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L);
+size_t distal_innerprod_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, int64_t K);
+
+/* Static, human-readable text for a distal_status value. */
+const char *distal_status_string(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int distal_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DISTAL_H */

@@ -1,0 +1,346 @@
+// C ABI of the leaf-kernel library: argument checks on the host, then launches.
+// Nothing here allocates, frees or synchronises; see include/distal.h.
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cstdint>
+#include <limits>
+
+#include "../../include/distal.h"
+#include "gemm_kernel.hpp"
+#include "stream_kernels.hpp"
+
+using namespace distal;
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+constexpr int kInnerprodMaxBlocks = 2048;   // fixed: the summation order must not depend on the device
+constexpr size_t kWorkspaceAlign = 256;
+
+bool mul_ok(int64_t a, int64_t b, int64_t *out) { return !__builtin_mul_overflow(a, b, out); }
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int current_device() {
+    int d = 0;
+    if (hipGetDevice(&d) != hipSuccess || d < 0 || d >= kMaxDevices) d = 0;
+    return d;
+}
+
+int compute_units() {
+    static std::atomic<int> cached[kMaxDevices];
+    const int d = current_device();
+    int cu = cached[d].load(std::memory_order_relaxed);
+    if (cu == 0) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, d) != hipSuccess || v <= 0)
+            v = 256;
+        cached[d].store(v, std::memory_order_relaxed);
+        cu = v;
+    }
+    return cu;
+}
+
+template <typename T, int BM, int BN, int BK, int WM, int WN, int EPI>
+int launch_contract(const ContractArgs<T> &a, hipStream_t stream) {
+    typedef ContractCfg<T, BM, BN, BK, WM, WN, EPI> Cfg;
+    auto kern = contract_kernel<T, BM, BN, BK, WM, WN, EPI>;
+    if (Cfg::LDS_BYTES > 48 * 1024) {
+        // opt in to large dynamic LDS once per device for this instantiation
+        static std::atomic<bool> done[kMaxDevices];
+        const int d = current_device();
+        if (!done[d].load(std::memory_order_acquire)) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    Cfg::LDS_BYTES) != hipSuccess) {
+                (void)hipGetLastError();
+                return DISTAL_ERR_LAUNCH;
+            }
+            done[d].store(true, std::memory_order_release);
+        }
+    }
+    const int64_t nblocks = (int64_t)a.tiles_m * a.tiles_n;
+    hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
+    return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
+}
+
+template <typename T>
+int launch_fill(T *out, int64_t rows, int64_t cols, int64_t ld, hipStream_t stream) {
+    const int64_t n = rows * cols;
+    if (n == 0) return DISTAL_OK;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(fill_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream, out, rows, cols, ld, T(0));
+    return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
+}
+
+// ---- matrix multiply ------------------------------------------------------
+template <typename T>
+int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B, int64_t ldb,
+           T *C, int64_t ldc, int accumulate, hipStream_t stream) {
+    constexpr int BM = 128, BN = 128, BK = 16;
+    constexpr int VEC = 16 / (int)sizeof(T);
+    if (M == 0 || N == 0) return DISTAL_OK;
+    if (K == 0) return accumulate ? DISTAL_OK : launch_fill<T>(C, M, N, ldc, stream);
+    const int64_t tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
+    int64_t nblocks;
+    if (!mul_ok(tm, tn, &nblocks) || nblocks > std::numeric_limits<int>::max()) return DISTAL_ERR_SHAPE;
+    ContractArgs<T> a{};
+    a.A = A; a.B = B; a.C = C;
+    a.M = M; a.N = N; a.K = K;
+    a.lda = lda; a.ldb = ldb; a.ldc = ldc;
+    a.accumulate = accumulate ? 1 : 0;
+    a.tiles_m = (int)tm; a.tiles_n = (int)tn;
+    a.a_vec_ok = aligned16(A) && lda % VEC == 0;
+    a.b_vec_ok = aligned16(B) && ldb % VEC == 0;
+    a.c_vec_ok = aligned16(C) && ldc % VEC == 0;
+    return launch_contract<T, BM, BN, BK, 2, 2, EPI_STORE>(a, stream);
+}
+
+int check_dtype(int dt) { return (dt == DISTAL_F32 || dt == DISTAL_F64) ? DISTAL_OK : DISTAL_ERR_DTYPE; }
+
+size_t elem_size(int dt) { return dt == DISTAL_F64 ? 8 : 4; }
+
+// ---- MTTKRP ---------------------------------------------------------------
+template <typename T> struct MttkrpTile;
+template <> struct MttkrpTile<float>  { static constexpr int BM = 256, BN = 32, BK = 16, WM = 4; };
+template <> struct MttkrpTile<double> { static constexpr int BM = 128, BN = 32, BK = 16, WM = 2; };
+
+int64_t mttkrp_jtiles(int dt, int64_t J) {
+    const int64_t bm = dt == DISTAL_F64 ? MttkrpTile<double>::BM : MttkrpTile<float>::BM;
+    return (J + bm - 1) / bm;
+}
+
+template <typename T>
+int mttkrp_t(int64_t I, int64_t J, int64_t K, int64_t L, const T *B, const T *C, const T *D, T *A,
+             void *workspace, hipStream_t stream) {
+    typedef MttkrpTile<T> Tile;
+    constexpr int VEC = 16 / (int)sizeof(T);
+    if (I == 0 || L == 0) return DISTAL_OK;
+    if (J == 0 || K == 0) return launch_fill<T>(A, I, L, L, stream);
+    const int64_t jtiles = (J + Tile::BM - 1) / Tile::BM;
+    const int64_t tn = (L + Tile::BN - 1) / Tile::BN;
+    int64_t tm, nblocks;
+    if (!mul_ok(I, jtiles, &tm) || !mul_ok(tm, tn, &nblocks) ||
+        nblocks > std::numeric_limits<int>::max())
+        return DISTAL_ERR_SHAPE;
+    ContractArgs<T> a{};
+    a.A = B; a.B = D; a.C = nullptr;
+    a.M = I * J; a.N = L; a.K = K;
+    a.lda = K; a.ldb = L; a.ldc = L;
+    a.tiles_m = (int)tm; a.tiles_n = (int)tn;
+    a.a_vec_ok = aligned16(B) && K % VEC == 0;
+    a.b_vec_ok = aligned16(D) && L % VEC == 0;
+    a.c_vec_ok = 0;
+    a.F = C;
+    a.J = J;
+    a.jtiles = (int)jtiles;
+    a.partial = jtiles == 1 ? A : static_cast<T *>(workspace);
+    int rc = launch_contract<T, Tile::BM, Tile::BN, Tile::BK, Tile::WM, 1, EPI_MTTKRP>(a, stream);
+    if (rc != DISTAL_OK || jtiles == 1) return rc;
+    int64_t blocks = (I * L + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(mttkrp_reduce_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                       static_cast<const T *>(workspace), A, I, L, (int)jtiles);
+    return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
+}
+
+// ---- TTV ------------------------------------------------------------------
+template <typename T>
+int ttv_t(int64_t rows, int64_t K, const T *B, const T *c, T *A, hipStream_t stream) {
+    constexpr int VEC = 16 / (int)sizeof(T);
+    if (rows == 0) return DISTAL_OK;
+    if (K == 0) return launch_fill<T>(A, rows, 1, 1, stream);
+    int64_t blocks = (rows + 15) / 16;
+    const int64_t cap = (int64_t)compute_units() * 8;
+    if (blocks > cap) blocks = cap;
+    const bool vec = aligned16(B) && aligned16(c) && K % VEC == 0;
+    if (!vec) {
+        hipLaunchKernelGGL(ttv_generic_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream, B, c, A, rows, K);
+    } else if (K * (int64_t)sizeof(T) <= 32 * 1024) {
+        hipLaunchKernelGGL((ttv_vec_kernel<T, 8, true>), dim3((unsigned)blocks), dim3(256),
+                           (size_t)K * sizeof(T), stream, B, c, A, rows, K);
+    } else {
+        hipLaunchKernelGGL((ttv_vec_kernel<T, 8, false>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                           B, c, A, rows, K);
+    }
+    return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
+}
+
+// ---- innerprod ------------------------------------------------------------
+template <typename T>
+int innerprod_t(int64_t n, const T *B, const T *C, T *out, double *partial, hipStream_t stream) {
+    constexpr int VEC = 16 / (int)sizeof(T);
+    int nparts = 0;
+    int64_t tail_lo = 0;
+    if (n > 0 && aligned16(B) && aligned16(C)) {
+        const int64_t nvec = n / VEC;
+        if (nvec > 0) {
+            int64_t blocks = (nvec + 255) / 256;
+            if (blocks > kInnerprodMaxBlocks) blocks = kInnerprodMaxBlocks;
+            int64_t per = (nvec + blocks - 1) / blocks;
+            per = (per + 255) / 256 * 256;
+            blocks = (nvec + per - 1) / per;
+            hipLaunchKernelGGL((innerprod_pass1_kernel<T, 4>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                               B, C, partial, nvec, per);
+            if (hipGetLastError() != hipSuccess) return DISTAL_ERR_LAUNCH;
+            nparts = (int)blocks;
+        }
+        tail_lo = nvec * VEC;
+    } else if (n > 0) {
+        int64_t blocks = (n + 1023) / 1024;
+        if (blocks > kInnerprodMaxBlocks) blocks = kInnerprodMaxBlocks;
+        int64_t per = (n + blocks - 1) / blocks;
+        per = (per + 255) / 256 * 256;
+        blocks = (n + per - 1) / per;
+        hipLaunchKernelGGL(innerprod_pass1_generic_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                           B, C, partial, n, per);
+        if (hipGetLastError() != hipSuccess) return DISTAL_ERR_LAUNCH;
+        nparts = (int)blocks;
+        tail_lo = n;
+    }
+    hipLaunchKernelGGL(innerprod_pass2_kernel<T>, dim3(1), dim3(256), 0, stream,
+                       (const double *)partial, nparts, B, C, tail_lo, n, out);
+    return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
+}
+
+bool tensor_elems(int64_t I, int64_t J, int64_t K, int64_t *n) {
+    int64_t ij;
+    // keep byte offsets inside int64 as well
+    return mul_ok(I, J, &ij) && mul_ok(ij, K, n) && *n <= std::numeric_limits<int64_t>::max() / 8;
+}
+
+}  // namespace
+
+extern "C" {
+
+int distal_version(void) { return 100; }
+
+const char *distal_status_string(int status) {
+    switch (status) {
+        case DISTAL_OK: return "ok";
+        case DISTAL_ERR_NULL: return "a required pointer is NULL";
+        case DISTAL_ERR_SHAPE: return "negative or overflowing extent";
+        case DISTAL_ERR_DTYPE: return "unknown dtype";
+        case DISTAL_ERR_STRIDE: return "leading dimension smaller than the row length";
+        case DISTAL_ERR_ALIAS: return "output aliases an input";
+        case DISTAL_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case DISTAL_ERR_LAUNCH: return "kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+int distal_gemm(distal_dtype dt, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
+                const void *B, int64_t ldb, void *C, int64_t ldc, int accumulate, void *stream) {
+    if (check_dtype(dt) != DISTAL_OK) return DISTAL_ERR_DTYPE;
+    if (M < 0 || N < 0 || K < 0) return DISTAL_ERR_SHAPE;
+    int64_t t;
+    if (!mul_ok(M, N, &t) || !mul_ok(M, K, &t) || !mul_ok(K, N, &t)) return DISTAL_ERR_SHAPE;
+    if (lda < K || ldb < N || ldc < N) return DISTAL_ERR_STRIDE;
+    if ((M > 1 && (!mul_ok(M, lda, &t) || !mul_ok(M, ldc, &t) || t > INT64_MAX / 8)) ||
+        (K > 1 && (!mul_ok(K, ldb, &t) || t > INT64_MAX / 8)))
+        return DISTAL_ERR_SHAPE;
+    const bool need_a = M > 0 && K > 0 && N > 0, need_b = need_a, need_c = M > 0 && N > 0;
+    if ((need_a && !A) || (need_b && !B) || (need_c && !C)) return DISTAL_ERR_NULL;
+    if (need_c && (C == A || C == B)) return DISTAL_ERR_ALIAS;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dt == DISTAL_F64)
+        return gemm_t<double>(M, N, K, (const double *)A, lda, (const double *)B, ldb, (double *)C, ldc,
+                              accumulate, s);
+    return gemm_t<float>(M, N, K, (const float *)A, lda, (const float *)B, ldb, (float *)C, ldc,
+                         accumulate, s);
+}
+
+int distal_ttm(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L, const void *B,
+               const void *C, void *A, void *stream) {
+    if (check_dtype(dt) != DISTAL_OK) return DISTAL_ERR_DTYPE;
+    if (I < 0 || J < 0 || K < 0 || L < 0) return DISTAL_ERR_SHAPE;
+    int64_t nb, na, ij, t;
+    if (!tensor_elems(I, J, K, &nb) || !tensor_elems(I, J, L, &na) || !mul_ok(K, L, &t) ||
+        !mul_ok(I, J, &ij))
+        return DISTAL_ERR_SHAPE;
+    if ((nb > 0 && L > 0 && !B) || (t > 0 && ij > 0 && !C) || (na > 0 && !A)) return DISTAL_ERR_NULL;
+    if (na > 0 && (A == B || A == C)) return DISTAL_ERR_ALIAS;
+    // The contraction over the last mode is one matrix product on the (I*J) x K view.
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t ldk = K > 0 ? K : 1, ldl = L > 0 ? L : 1;
+    if (dt == DISTAL_F64)
+        return gemm_t<double>(ij, L, K, (const double *)B, ldk, (const double *)C, ldl, (double *)A, ldl, 0, s);
+    return gemm_t<float>(ij, L, K, (const float *)B, ldk, (const float *)C, ldl, (float *)A, ldl, 0, s);
+}
+
+size_t distal_mttkrp_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L) {
+    if (check_dtype(dt) != DISTAL_OK || I < 0 || J < 0 || K < 0 || L < 0) return 0;
+    const int64_t jt = mttkrp_jtiles(dt, J);
+    if (jt <= 1) return 0;
+    int64_t a, b;
+    if (!mul_ok(I, jt, &a) || !mul_ok(a, L, &b) || b > INT64_MAX / 8) return 0;
+    return (size_t)b * elem_size(dt);
+}
+
+int distal_mttkrp(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L, const void *B,
+                  const void *C, const void *D, void *A, void *workspace, size_t workspace_bytes,
+                  void *stream) {
+    if (check_dtype(dt) != DISTAL_OK) return DISTAL_ERR_DTYPE;
+    if (I < 0 || J < 0 || K < 0 || L < 0) return DISTAL_ERR_SHAPE;
+    int64_t nb, nc, nd, na, t;
+    if (!tensor_elems(I, J, K, &nb) || !mul_ok(J, L, &nc) || !mul_ok(K, L, &nd) || !mul_ok(I, L, &na) ||
+        !mul_ok(I, mttkrp_jtiles(dt, J), &t) || !mul_ok(t, L, &t) || t > INT64_MAX / 8)
+        return DISTAL_ERR_SHAPE;
+    const bool work = nb > 0 && L > 0;
+    if ((work && (!B || !C || !D)) || (na > 0 && !A)) return DISTAL_ERR_NULL;
+    if (na > 0 && (A == B || A == C || A == D)) return DISTAL_ERR_ALIAS;
+    const size_t need = work ? distal_mttkrp_workspace_bytes(dt, I, J, K, L) : 0;
+    if (need > 0 && (!workspace || workspace_bytes < need ||
+                     (reinterpret_cast<uintptr_t>(workspace) % kWorkspaceAlign) != 0))
+        return DISTAL_ERR_WORKSPACE;
+    if (need > 0 && (workspace == A || workspace == B || workspace == C || workspace == D))
+        return DISTAL_ERR_ALIAS;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dt == DISTAL_F64)
+        return mttkrp_t<double>(I, J, K, L, (const double *)B, (const double *)C, (const double *)D,
+                                (double *)A, workspace, s);
+    return mttkrp_t<float>(I, J, K, L, (const float *)B, (const float *)C, (const float *)D, (float *)A,
+                           workspace, s);
+}
+
+int distal_ttv(distal_dtype dt, int64_t I, int64_t J, int64_t K, const void *B, const void *c,
+               void *A, void *stream) {
+    if (check_dtype(dt) != DISTAL_OK) return DISTAL_ERR_DTYPE;
+    if (I < 0 || J < 0 || K < 0) return DISTAL_ERR_SHAPE;
+    int64_t nb, rows;
+    if (!tensor_elems(I, J, K, &nb) || !mul_ok(I, J, &rows)) return DISTAL_ERR_SHAPE;
+    if ((nb > 0 && (!B || !c)) || (rows > 0 && !A)) return DISTAL_ERR_NULL;
+    if (rows > 0 && (A == B || A == c)) return DISTAL_ERR_ALIAS;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dt == DISTAL_F64) return ttv_t<double>(rows, K, (const double *)B, (const double *)c, (double *)A, s);
+    return ttv_t<float>(rows, K, (const float *)B, (const float *)c, (float *)A, s);
+}
+
+size_t distal_innerprod_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, int64_t K) {
+    int64_t n;
+    if (check_dtype(dt) != DISTAL_OK || I < 0 || J < 0 || K < 0 || !tensor_elems(I, J, K, &n)) return 0;
+    return (size_t)kInnerprodMaxBlocks * sizeof(double);
+}
+
+int distal_innerprod(distal_dtype dt, int64_t I, int64_t J, int64_t K, const void *B, const void *C,
+                     void *a, void *workspace, size_t workspace_bytes, void *stream) {
+    if (check_dtype(dt) != DISTAL_OK) return DISTAL_ERR_DTYPE;
+    if (I < 0 || J < 0 || K < 0) return DISTAL_ERR_SHAPE;
+    int64_t n;
+    if (!tensor_elems(I, J, K, &n)) return DISTAL_ERR_SHAPE;
+    if (!a || (n > 0 && (!B || !C))) return DISTAL_ERR_NULL;
+    if (a == B || a == C) return DISTAL_ERR_ALIAS;
+    const size_t need = distal_innerprod_workspace_bytes(dt, I, J, K);
+    if (!workspace || workspace_bytes < need ||
+        (reinterpret_cast<uintptr_t>(workspace) % kWorkspaceAlign) != 0)
+        return DISTAL_ERR_WORKSPACE;
+    if (workspace == a || workspace == B || workspace == C) return DISTAL_ERR_ALIAS;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dt == DISTAL_F64)
+        return innerprod_t<double>(n, (const double *)B, (const double *)C, (double *)a, (double *)workspace, s);
+    return innerprod_t<float>(n, (const float *)B, (const float *)C, (float *)a, (double *)workspace, s);
+}
+
+}  // extern "C"

@@ -1,0 +1,360 @@
+// MFMA contraction kernel for gfx950: one template serves the matrix-multiply
+// tile step, TTM (the same contraction on the (I*J) x K view of the tensor) and
+// the matrix-product stage of MTTKRP with its element-wise reduction fused in.
+//
+// Work decomposition
+//   grid   : one workgroup per BM x BN output tile, block ids remapped so that
+//            each of the 8 XCDs (one L2 each) works a compact group of tiles
+//   block  : WAVES_M x WAVES_N wavefronts of 64 lanes, each owning a
+//            (BM/WAVES_M) x (BN/WAVES_N) sub-tile held in MFMA accumulators
+//   k-loop : BK-deep slabs of both operands, global -> registers -> LDS, two LDS
+//            buffers, one barrier per slab; the next slab's global loads are in
+//            flight while the current one is multiplied
+//
+// Operand-to-lane assignment.  An MFMA contracts KS "k-slots" held by different
+// lane groups.  Which k a slot carries is free as long as both operands agree,
+// so slot s of the t-th MFMA of a group of KG = KS*KV k-values carries
+// k = s*KV + t: a lane then reads its KV values for KV consecutive MFMAs as ONE
+// 16-byte LDS read of the row-major A slab.  In the same way the CV column
+// blocks that share an LDS read take interleaved columns (lane jj of block q
+// owns column jj*CV + q), so a lane reads CV neighbouring B values at once and
+// finally owns CV neighbouring outputs, which it stores as one vector.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace distal {
+
+typedef double v2d __attribute__((ext_vector_type(2)));
+typedef double v4d __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+template <typename T, int N> struct VecOf;
+template <> struct VecOf<double, 1> { typedef double type; };
+template <> struct VecOf<double, 2> { typedef v2d type; };
+template <> struct VecOf<float, 1> { typedef float type; };
+template <> struct VecOf<float, 2> { typedef v2f type; };
+template <> struct VecOf<float, 4> { typedef v4f type; };
+
+// Per-dtype MFMA shape and register layout.
+//   lane -> (row-or-column index within the block, k-slot) for the operands;
+//   accumulator register v of a lane -> output row within the block.
+template <typename T> struct Mfma;
+
+template <> struct Mfma<double> {          // v_mfma_f64_16x16x4_f64
+    static constexpr int MB = 16, NB = 16, KS = 4, NACC = 4;
+    typedef v4d acc_t;
+    static __device__ __forceinline__ acc_t run(double a, double b, acc_t c) {
+        return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int out_row(int v, int lane) { return 4 * (lane >> 4) + v; }
+};
+
+template <> struct Mfma<float> {           // v_mfma_f32_32x32x2_f32
+    static constexpr int MB = 32, NB = 32, KS = 2, NACC = 16;
+    typedef v16f acc_t;
+    static __device__ __forceinline__ acc_t run(float a, float b, acc_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int out_row(int v, int lane) {
+        return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+    }
+};
+
+enum { EPI_STORE = 0, EPI_MTTKRP = 1 };
+
+template <typename T>
+struct ContractArgs {
+    const T *A;          // left operand rows (M x K view), row stride lda
+    const T *B;          // right operand (K x N), row stride ldb
+    T *C;                // EPI_STORE: output (M x N), row stride ldc
+    int64_t M, N, K;
+    int64_t lda, ldb, ldc;
+    int accumulate;
+    int tiles_m, tiles_n;
+    int a_vec_ok, b_vec_ok, c_vec_ok;   // 16-byte vector access is legal on that operand
+    // EPI_MTTKRP: rows are (i, j) pairs of an I x J x K tensor, tile row-blocks never
+    // cross an i boundary: tile_m = i * jtiles + jt covers j in [jt*BM, min(J, (jt+1)*BM)).
+    const T *F;          // factor matrix C(j, l), J x N dense
+    T *partial;          // (I * jtiles) x N partial column sums, or the output itself if jtiles == 1
+    int64_t J;
+    int jtiles;
+};
+
+// Block id -> output tile.  Hardware hands consecutive workgroup ids to the 8
+// XCDs in turn; give each XCD one contiguous range of logical ids, and walk
+// that range in bands of GROUP_M tile rows so that tiles resident together
+// share A row-panels and B column-panels in that XCD's L2.
+__device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m, int tiles_n,
+                                              int &tm, int &tn) {
+    constexpr int NXCD = 8, GROUP_M = 8;
+    const int per = nblocks / NXCD, rem = nblocks % NXCD;
+    const int x = bid % NXCD, q = bid / NXCD;
+    const int p = x * per + (x < rem ? x : rem) + q;
+    const int width = GROUP_M * tiles_n;
+    const int g = p / width, r = p % width;
+    const int first = g * GROUP_M;
+    const int gs = (tiles_m - first) < GROUP_M ? (tiles_m - first) : GROUP_M;
+    tm = first + r % gs;
+    tn = r / gs;
+}
+
+template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int EPI>
+struct ContractCfg {
+    typedef Mfma<T> MF;
+    static constexpr int NT = 64 * WAVES_M * WAVES_N;
+    static constexpr int VEC = 16 / (int)sizeof(T);      // elements per 16-byte access
+    static constexpr int KV = VEC;                        // consecutive k per lane per A read
+    static constexpr int KG = MF::KS * KV;                // k-values per MFMA group
+    static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+    static constexpr int MI = WTM / MF::MB, NI = WTN / MF::NB;
+    static constexpr int CV = (NI % 2 == 0) ? 2 : 1;      // column blocks sharing one B read
+    static constexpr int NG = NI / CV;
+    static constexpr int LDA_S = BK + VEC;                // LDS row strides (elements): +16 B
+    static constexpr int LDB_S = BN + VEC;
+    static constexpr int A_ELEMS = BM * LDA_S, B_ELEMS = BK * LDB_S;
+    static constexpr int STAGE_ELEMS = A_ELEMS + B_ELEMS;
+    static constexpr int LDS_BYTES = 2 * STAGE_ELEMS * (int)sizeof(T);
+    static constexpr int A_VECS = BM * (BK / VEC), B_VECS = BK * (BN / VEC);
+    static constexpr int A_PER_T = (A_VECS + NT - 1) / NT, B_PER_T = (B_VECS + NT - 1) / NT;
+    static_assert(BM % (WAVES_M * MF::MB) == 0 && BN % (WAVES_N * MF::NB) == 0, "tile shape");
+    static_assert(BK % KG == 0, "BK must hold whole MFMA k-groups");
+    static_assert(EPI == EPI_STORE || (WAVES_N == 1), "reduction epilogue keeps all columns in one wave column");
+};
+
+template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int EPI>
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N, 2)
+contract_kernel(const ContractArgs<T> args) {
+    typedef ContractCfg<T, BM, BN, BK, WAVES_M, WAVES_N, EPI> Cfg;
+    typedef Mfma<T> MF;
+    typedef typename VecOf<T, Cfg::VEC>::type vec_t;
+    typedef typename VecOf<T, Cfg::CV>::type cvec_t;
+    constexpr int VEC = Cfg::VEC, KV = Cfg::KV, KG = Cfg::KG, MI = Cfg::MI, NI = Cfg::NI;
+    constexpr int CV = Cfg::CV, NG = Cfg::NG, NT = Cfg::NT;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    T *lds = reinterpret_cast<T *>(lds_raw);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int li = lane % MF::MB;          // row (A) / column (B) index inside an MFMA block
+    const int ls = lane / MF::MB;          // k-slot
+
+    int tm, tn;
+    tile_of_block(blockIdx.x, gridDim.x, args.tiles_m, args.tiles_n, tm, tn);
+
+    int64_t m0, mlimit;
+    if (EPI == EPI_MTTKRP) {
+        const int64_t i = tm / args.jtiles, jt = tm % args.jtiles;
+        m0 = i * args.J + jt * BM;
+        mlimit = (i + 1) * args.J;
+    } else {
+        m0 = (int64_t)tm * BM;
+        mlimit = args.M;
+    }
+    const int64_t n0 = (int64_t)tn * BN;
+    const int64_t K = args.K;
+
+    const bool a_fast = args.a_vec_ok && (m0 + BM <= mlimit);
+    const bool b_fast = args.b_vec_ok && (n0 + BN <= args.N);
+
+    vec_t ra[Cfg::A_PER_T], rb[Cfg::B_PER_T];
+
+    auto load_global = [&](int64_t k0) {
+        const bool kfull = (k0 + BK <= K);
+        if (a_fast && kfull) {
+#pragma unroll
+            for (int p = 0; p < Cfg::A_PER_T; ++p) {
+                const int v = tid + p * NT;
+                if (Cfg::A_VECS % NT != 0 && v >= Cfg::A_VECS) break;
+                const int r = v / (BK / VEC), kv = v % (BK / VEC);
+                ra[p] = *reinterpret_cast<const vec_t *>(args.A + (m0 + r) * args.lda + k0 + kv * VEC);
+            }
+        } else {
+#pragma unroll
+            for (int p = 0; p < Cfg::A_PER_T; ++p) {
+                const int v = tid + p * NT;
+                if (Cfg::A_VECS % NT != 0 && v >= Cfg::A_VECS) break;
+                const int r = v / (BK / VEC), kv = v % (BK / VEC);
+                T tmp[VEC];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const int64_t row = m0 + r, k = k0 + kv * VEC + e;
+                    tmp[e] = (row < mlimit && k < K) ? args.A[row * args.lda + k] : T(0);
+                }
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) ra[p][e] = tmp[e];
+            }
+        }
+        if (b_fast && kfull) {
+#pragma unroll
+            for (int p = 0; p < Cfg::B_PER_T; ++p) {
+                const int v = tid + p * NT;
+                if (Cfg::B_VECS % NT != 0 && v >= Cfg::B_VECS) break;
+                const int r = v / (BN / VEC), cv = v % (BN / VEC);
+                rb[p] = *reinterpret_cast<const vec_t *>(args.B + (k0 + r) * args.ldb + n0 + cv * VEC);
+            }
+        } else {
+#pragma unroll
+            for (int p = 0; p < Cfg::B_PER_T; ++p) {
+                const int v = tid + p * NT;
+                if (Cfg::B_VECS % NT != 0 && v >= Cfg::B_VECS) break;
+                const int r = v / (BN / VEC), cv = v % (BN / VEC);
+                T tmp[VEC];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const int64_t k = k0 + r, col = n0 + cv * VEC + e;
+                    tmp[e] = (k < K && col < args.N) ? args.B[k * args.ldb + col] : T(0);
+                }
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) rb[p][e] = tmp[e];
+            }
+        }
+    };
+
+    auto store_lds = [&](int stage) {
+        T *as = lds + stage * Cfg::STAGE_ELEMS;
+        T *bs = as + Cfg::A_ELEMS;
+#pragma unroll
+        for (int p = 0; p < Cfg::A_PER_T; ++p) {
+            const int v = tid + p * NT;
+            if (Cfg::A_VECS % NT != 0 && v >= Cfg::A_VECS) break;
+            const int r = v / (BK / VEC), kv = v % (BK / VEC);
+            *reinterpret_cast<vec_t *>(as + r * Cfg::LDA_S + kv * VEC) = ra[p];
+        }
+#pragma unroll
+        for (int p = 0; p < Cfg::B_PER_T; ++p) {
+            const int v = tid + p * NT;
+            if (Cfg::B_VECS % NT != 0 && v >= Cfg::B_VECS) break;
+            const int r = v / (BN / VEC), cv = v % (BN / VEC);
+            *reinterpret_cast<vec_t *>(bs + r * Cfg::LDB_S + cv * VEC) = rb[p];
+        }
+    };
+
+    typename MF::acc_t acc[MI][NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int v = 0; v < MF::NACC; ++v) acc[mi][ni][v] = T(0);
+
+    auto compute = [&](int stage) {
+        const T *as = lds + stage * Cfg::STAGE_ELEMS + (wm * Cfg::WTM + li) * Cfg::LDA_S + ls * KV;
+        const T *bs = lds + stage * Cfg::STAGE_ELEMS + Cfg::A_ELEMS + (ls * KV) * Cfg::LDB_S
+                      + wn * Cfg::WTN + li * CV;
+#pragma unroll
+        for (int kg = 0; kg < BK / KG; ++kg) {
+            vec_t a[MI];
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+                a[mi] = *reinterpret_cast<const vec_t *>(as + mi * MF::MB * Cfg::LDA_S + kg * KG);
+            cvec_t b[KV][NG];
+#pragma unroll
+            for (int t = 0; t < KV; ++t)
+#pragma unroll
+                for (int g = 0; g < NG; ++g)
+                    b[t][g] = *reinterpret_cast<const cvec_t *>(bs + (kg * KG + t) * Cfg::LDB_S
+                                                                + g * MF::NB * CV);
+#pragma unroll
+            for (int t = 0; t < KV; ++t)
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni) {
+                        T bv;
+                        if constexpr (CV == 1) bv = b[t][ni];
+                        else bv = b[t][ni / CV][ni % CV];
+                        acc[mi][ni] = MF::run(a[mi][t], bv, acc[mi][ni]);
+                    }
+        }
+    };
+
+    const int64_t nk = (K + BK - 1) / BK;
+    if (nk > 0) {
+        load_global(0);
+        store_lds(0);
+    }
+    __syncthreads();
+    for (int64_t t = 0; t < nk; ++t) {
+        const int stage = (int)(t & 1);
+        if (t + 1 < nk) load_global((t + 1) * BK);
+        compute(stage);
+        if (t + 1 < nk) store_lds(stage ^ 1);
+        __syncthreads();
+    }
+
+    if constexpr (EPI == EPI_STORE) {
+        const bool c_fast = args.c_vec_ok && (m0 + BM <= args.M) && (n0 + BN <= args.N);
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int g = 0; g < NG; ++g)
+#pragma unroll
+                for (int v = 0; v < MF::NACC; ++v) {
+                    const int64_t row = m0 + wm * Cfg::WTM + mi * MF::MB + MF::out_row(v, lane);
+                    const int64_t col = n0 + wn * Cfg::WTN + g * (MF::NB * CV) + li * CV;
+                    T *cp = args.C + row * args.ldc + col;
+                    if (c_fast) {
+                        cvec_t o;
+                        if constexpr (CV == 1) {
+                            o = acc[mi][g][v];
+                            if (args.accumulate) o += *cp;
+                            *cp = o;
+                        } else {
+#pragma unroll
+                            for (int q = 0; q < CV; ++q) o[q] = acc[mi][g * CV + q][v];
+                            if (args.accumulate) o += *reinterpret_cast<const cvec_t *>(cp);
+                            *reinterpret_cast<cvec_t *>(cp) = o;
+                        }
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < CV; ++q) {
+                            if (row < args.M && col + q < args.N) {
+                                T o = acc[mi][g * CV + q][v];
+                                if (args.accumulate) o += cp[q];
+                                cp[q] = o;
+                            }
+                        }
+                    }
+                }
+    } else {
+        // MTTKRP: scale T(j,l) by the factor C(j,l) and sum over the tile's j rows.
+        // Each lane first sums its own rows per owned column; the per-lane sums then
+        // meet in LDS and are added in a fixed order.
+        const int64_t i_row0 = (tm / args.jtiles) * args.J;   // first tensor row of this i
+        T colsum[NI];
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) colsum[ni] = T(0);
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int v = 0; v < MF::NACC; ++v) {
+                    const int64_t row = m0 + wm * Cfg::WTM + mi * MF::MB + MF::out_row(v, lane);
+                    const int64_t col = n0 + (ni / CV) * (MF::NB * CV) + li * CV + (ni % CV);
+                    if (row < mlimit && col < args.N)
+                        colsum[ni] += acc[mi][ni][v] * args.F[(row - i_row0) * args.N + col];
+                }
+        // red[wm][ls][column-in-tile]; the operand buffers are idle after the final barrier
+        T *red = lds;
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+            const int c = (ni / CV) * (MF::NB * CV) + li * CV + (ni % CV);
+            red[(wm * MF::KS + ls) * BN + c] = colsum[ni];
+        }
+        __syncthreads();
+        if (tid < BN && n0 + tid < args.N) {
+            T s = T(0);
+#pragma unroll
+            for (int w = 0; w < WAVES_M * MF::KS; ++w) s += red[w * BN + tid];
+            args.partial[(int64_t)tm * args.N + n0 + tid] = s;
+        }
+    }
+}
+
+}  // namespace distal

@@ -1,0 +1,227 @@
+// Bandwidth-bound kernels for gfx950: TTV and the tensor inner product.
+// Both stream their tensor operands from HBM exactly once with 16-byte loads
+// per lane; arithmetic and reductions are arranged so that nothing but the
+// loads sits on the critical path.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gemm_kernel.hpp"   // vector typedefs only
+
+namespace distal {
+
+// Rotate within rows of 16 lanes (DPP row_ror:n) - the cross-lane step of the
+// 16-lane reductions below; costs one VALU slot and no LDS traffic.
+template <int N>
+__device__ __forceinline__ float row_ror(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x),
+                                                                  0x120 + N, 0xf, 0xf, false));
+}
+template <int N>
+__device__ __forceinline__ double row_ror(double x) {
+    const unsigned long long u = __builtin_bit_cast(unsigned long long, x);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned)u, 0x120 + N, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(unsigned)(u >> 32), 0x120 + N, 0xf, 0xf, false);
+    return __builtin_bit_cast(double, ((unsigned long long)(unsigned)hi << 32) | (unsigned)lo);
+}
+
+// Sum over each aligned group of 16 lanes; every lane of the group gets the sum.
+// The order of additions is fixed by the lane numbers.
+template <typename T>
+__device__ __forceinline__ T sum16(T x) {
+    x += row_ror<8>(x);
+    x += row_ror<4>(x);
+    x += row_ror<2>(x);
+    x += row_ror<1>(x);
+    return x;
+}
+
+// Sum over the 64 lanes of a wavefront; valid in every lane.
+__device__ __forceinline__ double sum64(double x) {
+    x = sum16(x);
+    x += __shfl_xor(x, 16);
+    x += __shfl_xor(x, 32);
+    return x;
+}
+
+// ---------------------------------------------------------------------------
+// TTV   A(r) = sum_k B(r, k) * c(k),  r = i*J + j  (rows of K contiguous values)
+//
+// 16 lanes share a row: lane q of the group reads 16-byte pieces q, q+16, ...
+// of the row, so the four groups of a wavefront stream four rows at once and a
+// wavefront load touches four 256-byte runs.  c is staged in LDS once per block.
+// UNROLL row pieces are in flight per lane before the first multiply.
+// ---------------------------------------------------------------------------
+template <typename T, int UNROLL, bool C_IN_LDS>
+__global__ void __launch_bounds__(256)
+ttv_vec_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict__ A,
+               int64_t rows, int64_t K) {
+    constexpr int VEC = 16 / (int)sizeof(T);
+    typedef typename VecOf<T, VEC>::type vec_t;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    const vec_t *cv;
+    const int64_t kvecs = K / VEC;
+    if (C_IN_LDS) {
+        vec_t *cl = reinterpret_cast<vec_t *>(lds_raw);
+        for (int64_t v = threadIdx.x; v < kvecs; v += 256)
+            cl[v] = reinterpret_cast<const vec_t *>(c)[v];
+        __syncthreads();
+        cv = cl;
+    } else {
+        cv = reinterpret_cast<const vec_t *>(c);
+    }
+    const int q = threadIdx.x & 15;
+    const int64_t group = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int64_t stride = (int64_t)gridDim.x * 16;
+    for (int64_t r = group; r < rows; r += stride) {
+        const vec_t *row = reinterpret_cast<const vec_t *>(B + r * K);
+        T acc = T(0);
+        int64_t v = q;
+        for (; v + 16 * (UNROLL - 1) < kvecs; v += 16 * UNROLL) {
+            vec_t b[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) b[u] = __builtin_nontemporal_load(row + v + 16 * u);
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const vec_t cc = cv[v + 16 * u];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc = __builtin_fma(b[u][e], cc[e], acc);
+            }
+        }
+        for (; v < kvecs; v += 16) {
+            const vec_t b = __builtin_nontemporal_load(row + v);
+            const vec_t cc = cv[v];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc = __builtin_fma(b[e], cc[e], acc);
+        }
+        acc = sum16(acc);
+        if (q == 0) A[r] = acc;
+    }
+}
+
+// Any K, any alignment: same 16-lanes-per-row shape with element loads.
+template <typename T>
+__global__ void __launch_bounds__(256)
+ttv_generic_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict__ A,
+                   int64_t rows, int64_t K) {
+    const int q = threadIdx.x & 15;
+    const int64_t group = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int64_t stride = (int64_t)gridDim.x * 16;
+    for (int64_t r = group; r < rows; r += stride) {
+        const T *row = B + r * K;
+        T acc = T(0);
+        for (int64_t k = q; k < K; k += 16) acc = __builtin_fma(row[k], c[k], acc);
+        acc = sum16(acc);
+        if (q == 0) A[r] = acc;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// innerprod   a = sum_n B(n) * C(n)   over the n = I*J*K elements, two passes.
+//
+// Pass 1: block b owns the contiguous run of 16-byte pieces [b*per, (b+1)*per);
+// each lane widens its operands to binary64 (a binary32 product is then exact)
+// and keeps a binary64 running sum; the extra VALU work hides under the loads.  Lanes -> wavefront -> block are combined in a fixed order and the
+// block's binary64 partial goes to the workspace.  Pass 2: one block adds the
+// partials and the (< VEC) trailing elements in a fixed order and rounds once.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ double piece_dot(const v4f b, const v4f c) {
+    // binary32 x binary32 is exact in binary64
+    double p = (double)b[0] * (double)c[0];
+    p = __builtin_fma((double)b[1], (double)c[1], p);
+    p = __builtin_fma((double)b[2], (double)c[2], p);
+    p = __builtin_fma((double)b[3], (double)c[3], p);
+    return p;
+}
+__device__ __forceinline__ double piece_dot(const v2d b, const v2d c) {
+    return __builtin_fma(b[1], c[1], b[0] * c[0]);
+}
+
+template <typename T, int UNROLL>
+__global__ void __launch_bounds__(256)
+innerprod_pass1_kernel(const T *__restrict__ B, const T *__restrict__ C, double *__restrict__ partial,
+                       int64_t nvec, int64_t per_block) {
+    constexpr int VEC = 16 / (int)sizeof(T);
+    typedef typename VecOf<T, VEC>::type vec_t;
+    const vec_t *bv = reinterpret_cast<const vec_t *>(B);
+    const vec_t *cv = reinterpret_cast<const vec_t *>(C);
+    const int64_t lo = (int64_t)blockIdx.x * per_block;
+    const int64_t hi = lo + per_block < nvec ? lo + per_block : nvec;
+    double acc = 0.0;
+    int64_t v = lo + threadIdx.x;
+    for (; v + 256 * (UNROLL - 1) < hi; v += 256 * UNROLL) {
+        vec_t b[UNROLL], c[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            b[u] = __builtin_nontemporal_load(bv + v + 256 * u);
+            c[u] = __builtin_nontemporal_load(cv + v + 256 * u);
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) acc += piece_dot(b[u], c[u]);
+    }
+    for (; v < hi; v += 256) acc += piece_dot(bv[v], cv[v]);
+
+    __shared__ double wsum[4];
+    acc = sum64(acc);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) partial[blockIdx.x] = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
+}
+
+// Element-wise pass 1 for operands that are not 16-byte aligned.
+template <typename T>
+__global__ void __launch_bounds__(256)
+innerprod_pass1_generic_kernel(const T *__restrict__ B, const T *__restrict__ C,
+                               double *__restrict__ partial, int64_t n, int64_t per_block) {
+    const int64_t lo = (int64_t)blockIdx.x * per_block;
+    const int64_t hi = lo + per_block < n ? lo + per_block : n;
+    double acc = 0.0;
+    for (int64_t m = lo + threadIdx.x; m < hi; m += 256) acc = __builtin_fma((double)B[m], (double)C[m], acc);
+    __shared__ double wsum[4];
+    acc = sum64(acc);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) partial[blockIdx.x] = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+innerprod_pass2_kernel(const double *__restrict__ partial, int nparts,
+                       const T *__restrict__ B, const T *__restrict__ C,
+                       int64_t tail_lo, int64_t n, T *__restrict__ out) {
+    double acc = 0.0;
+    for (int p = threadIdx.x; p < nparts; p += 256) acc += partial[p];
+    __shared__ double wsum[4];
+    acc = sum64(acc);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double s = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
+        for (int64_t m = tail_lo; m < n; ++m) s += (double)B[m] * (double)C[m];
+        *out = (T)s;
+    }
+}
+
+// Row-strided fill, used where an empty sum must still define its output.
+template <typename T>
+__global__ void __launch_bounds__(256)
+fill_kernel(T *__restrict__ out, int64_t rows, int64_t cols, int64_t ld, T value) {
+    const int64_t n = rows * cols;
+    for (int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x; m < n; m += (int64_t)gridDim.x * 256)
+        out[(m / cols) * ld + (m % cols)] = value;
+}
+
+// Pass 2 of MTTKRP: A(i,l) = sum over the j-tiles' partial column sums, in tile order.
+template <typename T>
+__global__ void __launch_bounds__(256)
+mttkrp_reduce_kernel(const T *__restrict__ partial, T *__restrict__ A, int64_t I, int64_t L, int jtiles) {
+    const int64_t n = I * L;
+    for (int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x; m < n; m += (int64_t)gridDim.x * 256) {
+        const int64_t i = m / L, l = m % L;
+        T s = T(0);
+        for (int t = 0; t < jtiles; ++t) s += partial[(i * jtiles + t) * L + l];
+        A[m] = s;
+    }
+}
+
+}  // namespace distal

@@ -1,0 +1,130 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol that
+include/distal.h declares, and turns bad arguments into status codes before
+anything is launched (so these run without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2203_08069_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build_library()
+    return binding.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "distal.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(distal_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree():
+    from paper_2203_08069_amd import binding
+    assert declared_symbols() == sorted(binding.EXPORTS)
+
+
+def test_exports_every_declared_symbol(lib):
+    for name in declared_symbols():
+        assert hasattr(lib, name), name
+
+
+def test_version_and_status_strings(lib):
+    assert lib.distal_version() >= 100
+    seen = set()
+    for code in range(0, 8):
+        s = lib.distal_status_string(code).decode()
+        assert s and s not in seen
+        seen.add(s)
+    assert lib.distal_status_string(99).decode() == "unknown status"
+
+
+P = ctypes.c_void_p
+FAKE = 0x1000   # never dereferenced: every call below must fail validation first
+
+
+def test_gemm_argument_errors(lib):
+    g = lib.distal_gemm
+    assert g(7, 4, 4, 4, P(FAKE), 4, P(FAKE + 256), 4, P(FAKE + 512), 4, 0, None) == 3
+    assert g(0, -1, 4, 4, P(FAKE), 4, P(FAKE + 256), 4, P(FAKE + 512), 4, 0, None) == 2
+    assert g(0, 1 << 40, 1 << 40, 4, P(FAKE), 4, P(FAKE + 256), 1 << 40, P(FAKE + 512), 1 << 40, 0, None) == 2
+    assert g(0, 4, 4, 4, P(FAKE), 3, P(FAKE + 256), 4, P(FAKE + 512), 4, 0, None) == 4
+    assert g(0, 4, 4, 4, P(FAKE), 4, P(FAKE + 256), 3, P(FAKE + 512), 4, 0, None) == 4
+    assert g(0, 4, 4, 4, P(FAKE), 4, P(FAKE + 256), 4, P(FAKE + 512), 2, 0, None) == 4
+    assert g(1, 4, 4, 4, None, 4, P(FAKE + 256), 4, P(FAKE + 512), 4, 0, None) == 1
+    assert g(1, 4, 4, 4, P(FAKE), 4, P(FAKE + 256), 4, None, 4, 0, None) == 1
+    assert g(1, 4, 4, 4, P(FAKE), 4, P(FAKE + 256), 4, P(FAKE), 4, 1, None) == 5
+    # empty output: nothing to do, pointers are not needed
+    assert g(1, 0, 4, 4, None, 4, None, 4, None, 4, 0, None) == 0
+    assert g(1, 4, 0, 4, None, 4, None, 1, None, 1, 0, None) == 0
+
+
+def test_tensor_call_argument_errors(lib):
+    a, b, c, d, w = (P(FAKE + 256 * i) for i in range(5))
+    assert lib.distal_ttm(2, 2, 2, 2, 2, a, b, c, None) == 3
+    assert lib.distal_ttm(0, 2, -2, 2, 2, a, b, c, None) == 2
+    assert lib.distal_ttm(0, 1 << 31, 1 << 31, 1 << 31, 2, a, b, c, None) == 2
+    assert lib.distal_ttm(0, 2, 2, 2, 2, None, b, c, None) == 1
+    assert lib.distal_ttm(0, 2, 2, 2, 2, a, b, a, None) == 5
+    assert lib.distal_ttv(0, 2, 2, 2, a, None, c, None) == 1
+    assert lib.distal_ttv(0, 2, 2, -1, a, b, c, None) == 2
+    assert lib.distal_ttv(1, 2, 2, 2, a, b, b, None) == 5
+    assert lib.distal_ttv(5, 2, 2, 2, a, b, c, None) == 3
+    assert lib.distal_ttv(0, 0, 2, 2, None, None, None, None) == 0
+    assert lib.distal_mttkrp(0, 2, 2, 2, 2, a, b, c, None, w, 1 << 20, None) == 1
+    assert lib.distal_mttkrp(0, 2, 2, 2, 2, a, b, c, a, w, 1 << 20, None) == 5
+    assert lib.distal_mttkrp(0, 2, 2, 2, -2, a, b, c, d, w, 1 << 20, None) == 2
+    assert lib.distal_mttkrp(9, 2, 2, 2, 2, a, b, c, d, w, 1 << 20, None) == 3
+    # J large enough to need j-tiles: workspace is then mandatory, big enough and aligned
+    need = lib.distal_mttkrp_workspace_bytes(0, 4, 1000, 8, 32)
+    assert need == 4 * 4 * 32 * 4
+    assert lib.distal_mttkrp(0, 4, 1000, 8, 32, a, b, c, d, None, 0, None) == 6
+    assert lib.distal_mttkrp(0, 4, 1000, 8, 32, a, b, c, d, w, need - 1, None) == 6
+    assert lib.distal_mttkrp(0, 4, 1000, 8, 32, a, b, c, d, P(FAKE + 8), need, None) == 6
+    assert lib.distal_mttkrp(0, 0, 1000, 8, 32, None, None, None, None, None, 0, None) == 0
+    need = lib.distal_innerprod_workspace_bytes(0, 2, 2, 2)
+    assert need > 0 and need % 8 == 0
+    assert lib.distal_innerprod(0, 2, 2, 2, a, b, None, w, need, None) == 1
+    assert lib.distal_innerprod(0, 2, 2, 2, a, b, a, w, need, None) == 5
+    assert lib.distal_innerprod(0, 2, 2, 2, a, b, c, None, 0, None) == 6
+    assert lib.distal_innerprod(0, 2, 2, 2, a, b, c, w, need - 8, None) == 6
+    assert lib.distal_innerprod(0, 2, 2, 2, a, b, c, P(FAKE + 4), need, None) == 6
+    assert lib.distal_innerprod(0, 2, 2, 2, a, b, c, c, need, None) == 5
+    assert lib.distal_innerprod(0, 2, -2, 2, a, b, c, w, need, None) == 2
+    assert lib.distal_innerprod(3, 2, 2, 2, a, b, c, w, need, None) == 3
+    assert lib.distal_mttkrp_workspace_bytes(7, 1, 1, 1, 1) == 0
+    assert lib.distal_innerprod_workspace_bytes(0, -1, 1, 1) == 0
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    from paper_2203_08069_amd import binding
+    x = torch.zeros(2, 2)
+    with pytest.raises((ValueError, TypeError)):
+        binding.distal_gemm(x, x, torch.zeros(2, 2))
+    with pytest.raises(TypeError):
+        binding._dtype_code(torch.zeros(2, dtype=torch.int32))
+
+
+def test_missing_library_is_an_error(tmp_path):
+    from paper_2203_08069_amd import binding
+    with pytest.raises(RuntimeError, match="no fallback"):
+        binding.load_library(str(tmp_path / "libdistal.so"))
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2203_08069_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f
+                assert "distal_oracle" not in text, f
+    otext = open(os.path.join(ROOT, "oracle", "__init__.py")).read() + \
+        open(os.path.join(ROOT, "oracle", "distal_oracle.c")).read()
+    assert "paper_2203_08069_amd" not in otext and "distal.h" not in otext

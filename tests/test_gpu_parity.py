@@ -1,0 +1,339 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle, element by element,
+on the same seeded inputs.  Sizes span several tiles and ragged tails."""
+import numpy as np
+import pytest
+
+from paper_2203_08069_amd import inputs
+
+import _util as U
+
+pytestmark = pytest.mark.gpu
+
+DT = [np.float32, np.float64]
+KINDS = [inputs.UNIFORM, inputs.SMALLINT]
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2203_08069_amd import binding
+    binding.load_library()          # raises if the HIP library was not built
+    return binding
+
+
+def empty(shape, dtype):
+    import torch
+    return torch.full(tuple(shape), float("nan"), dtype=getattr(torch, np.dtype(dtype).name), device="cuda:0")
+
+
+def compare(got, ref, dtype, kind, klen):
+    if kind == inputs.SMALLINT:
+        U.assert_exact(got, ref)
+    else:
+        U.assert_close(got, ref, dtype, klen)
+
+
+# ------------------------------------------------------------------ gemm
+
+GEMM_SHAPES = [(1, 1, 1), (256, 256, 256), (127, 129, 17), (130, 260, 33), (300, 200, 100),
+               (128, 128, 16), (64, 384, 1000), (513, 31, 8)]
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm(lib, oracle, dtype, kind, M, N, K):
+    seed = 0 if (M, N, K) == (256, 256, 256) else 100 + M
+    A, B = U.gen(seed, 0, (M, K), dtype, kind), U.gen(seed, 1, (K, N), dtype, kind)
+    C = empty((M, N), dtype)
+    lib.distal_gemm(U.dev(A), U.dev(B), C)
+    compare(U.host(C), oracle.gemm(A, B), dtype, kind, K)
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("off", [0, 1, 2, 3])
+def test_gemm_strided_views_accumulate(lib, oracle, dtype, kind, off):
+    """Operands are sub-blocks of larger matrices (k-chunks of a tile), some misaligned."""
+    M, N, K = 150, 141, 70
+    big_a, big_b, big_c = (U.gen(7, 0, (M + 5, K + 9), dtype, kind), U.gen(7, 1, (K + 4, N + 7), dtype, kind),
+                           U.gen(7, 2, (M + 3, N + 6), dtype, kind))
+    dA, dB, dC = U.dev(big_a), U.dev(big_b), U.dev(big_c)
+    vA, vB, vC = dA[2:2 + M, off:off + K], dB[1:1 + K, off:off + N], dC[3:3 + M, off:off + N]
+    ref = oracle.gemm(big_a[2:2 + M, off:off + K], big_b[1:1 + K, off:off + N],
+                      init=big_c[3:3 + M, off:off + N])
+    lib.distal_gemm(vA, vB, vC, accumulate=True)
+    out = U.host(dC)
+    compare(out[3:3 + M, off:off + N], ref, dtype, kind, K + 1)
+    # nothing outside the output block was written
+    mask = np.ones_like(big_c, dtype=bool)
+    mask[3:3 + M, off:off + N] = False
+    assert np.array_equal(out[mask], big_c[mask])
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_gemm_identity_returns_input(lib, dtype):
+    A = U.gen(8, 0, (200, 136), dtype)
+    C = empty((200, 136), dtype)
+    lib.distal_gemm(U.dev(A), U.dev(np.eye(136, dtype=dtype)), C)
+    assert np.array_equal(U.host(C), A)
+    C2 = empty((200, 136), dtype)
+    lib.distal_gemm(U.dev(np.eye(200, dtype=dtype)), U.dev(A), C2)
+    assert np.array_equal(U.host(C2), A)
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_gemm_schedules_bit_exact(lib, oracle, dtype):
+    """SUMMA k-chunks with accumulate, Cannon's rotated chunk order and Johnson's
+    independent partial products all reproduce the one-shot product (paper:
+    matrix-multiplication case studies)."""
+    import torch
+    n, g = 384, 3
+    t = n // g
+    A, B = U.gen(9, 0, (n, n), dtype, inputs.SMALLINT), U.gen(9, 1, (n, n), dtype, inputs.SMALLINT)
+    ref = oracle.gemm(A, B)
+    dA, dB = U.dev(A), U.dev(B)
+    # SUMMA: chunkSize 48, A += B_l x C_l
+    C = torch.zeros((n, n), dtype=dA.dtype, device="cuda:0")
+    for kc in range(0, n, 48):
+        lib.distal_gemm(dA[:, kc:kc + 48], dB[kc:kc + 48, :], C, accumulate=True)
+    U.assert_exact(U.host(C), ref)
+    # Cannon on a 3x3 grid: tile (io,jo) takes k-tile (ko+io+jo) mod 3 at step ko
+    C = torch.zeros((n, n), dtype=dA.dtype, device="cuda:0")
+    for io in range(g):
+        for jo in range(g):
+            for ko in range(g):
+                kos = (ko + io + jo) % g
+                lib.distal_gemm(dA[io * t:(io + 1) * t, kos * t:(kos + 1) * t],
+                                dB[kos * t:(kos + 1) * t, jo * t:(jo + 1) * t],
+                                C[io * t:(io + 1) * t, jo * t:(jo + 1) * t], accumulate=True)
+    U.assert_exact(U.host(C), ref)
+    # Johnson: independent partial products, then a sum over k
+    parts = []
+    for k in range(g):
+        P = empty((n, n), dtype)
+        lib.distal_gemm(dA[:, k * t:(k + 1) * t], dB[k * t:(k + 1) * t, :], P)
+        parts.append(U.host(P).astype(np.float64))
+    U.assert_exact(sum(parts), ref)
+
+
+# ------------------------------------------------------------------ ttm
+
+TTM_SHAPES = [(3, 5, 7, 4), (16, 16, 64, 32), (9, 33, 129, 130), (2, 70, 256, 256), (1, 1, 1, 1), (5, 3, 40, 1)]
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("I,J,K,L", TTM_SHAPES)
+def test_ttm(lib, oracle, dtype, kind, I, J, K, L):
+    B, C = U.gen(3, 0, (I, J, K), dtype, kind), U.gen(3, 1, (K, L), dtype, kind)
+    A = empty((I, J, L), dtype)
+    lib.distal_ttm(U.dev(B), U.dev(C), A)
+    compare(U.host(A), oracle.ttm(B, C), dtype, kind, K)
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_ttm_equals_gemm_on_view_and_identity(lib, dtype):
+    I, J, K, L = 6, 50, 96, 72
+    B, C = U.gen(30, 0, (I, J, K), dtype), U.gen(30, 1, (K, L), dtype)
+    dB, dC = U.dev(B), U.dev(C)
+    A, G = empty((I, J, L), dtype), empty((I * J, L), dtype)
+    lib.distal_ttm(dB, dC, A)
+    lib.distal_gemm(dB.view(I * J, K), dC, G)
+    assert np.array_equal(U.host(A).reshape(I * J, L), U.host(G))
+    A2 = empty((I, J, K), dtype)
+    lib.distal_ttm(dB, U.dev(np.eye(K, dtype=dtype)), A2)
+    assert np.array_equal(U.host(A2), B)
+
+
+# ------------------------------------------------------------------ ttv
+
+TTV_SHAPES = [(4, 8, 1024), (3, 7, 1000), (5, 5, 7), (2, 9, 1), (1, 1, 64), (6, 11, 520), (2, 3, 8200),
+              (33, 17, 128), (2, 2, 16388)]
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("I,J,K", TTV_SHAPES)
+def test_ttv(lib, oracle, dtype, kind, I, J, K):
+    B, c = U.gen(2, 0, (I, J, K), dtype, kind), U.gen(2, 1, (K,), dtype, kind)
+    A = empty((I, J), dtype)
+    lib.distal_ttv(U.dev(B), U.dev(c), A)
+    compare(U.host(A), oracle.ttv(B, c), dtype, kind, K)
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_ttv_closed_forms(lib, dtype):
+    I, J, K = 7, 13, 256
+    B = U.gen(21, 0, (I, J, K), dtype, inputs.SMALLINT)
+    A = empty((I, J), dtype)
+    lib.distal_ttv(U.dev(B), U.dev(np.ones(K, dtype=dtype)), A)
+    assert np.array_equal(U.host(A).astype(np.int64), B.astype(np.int64).sum(axis=2))
+    Bu = U.gen(21, 0, (I, J, K), dtype)
+    for m in (0, 77, 255):
+        e = np.zeros(K, dtype=dtype)
+        e[m] = 1
+        lib.distal_ttv(U.dev(Bu), U.dev(e), A)
+        assert np.array_equal(U.host(A), Bu[:, :, m])
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_ttv_misaligned_operands(lib, oracle, dtype):
+    import torch
+    I, J, K = 3, 5, 64
+    flat = U.gen(22, 0, (I * J * K + 1,), dtype)
+    cc = U.gen(22, 1, (K + 1,), dtype)
+    dB = U.dev(flat)[1:].view(I, J, K)
+    dc = U.dev(cc)[1:]
+    A = empty((I, J), dtype)
+    lib.distal_ttv(dB, dc, A)
+    U.assert_close(U.host(A), oracle.ttv(flat[1:].reshape(I, J, K), cc[1:]), dtype, K)
+
+
+# ------------------------------------------------------------------ innerprod
+
+IP_SHAPES = [(1, 1, 1), (1, 1, 3), (2, 3, 5), (4, 8, 1024), (3, 1 << 10, 1027), (7, 333, 1 << 10), (1, 1, (3 << 20) + 12345)]
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("I,J,K", IP_SHAPES)
+def test_innerprod(lib, oracle, dtype, kind, I, J, K):
+    B, C = U.gen(2, 0, (I, J, K), dtype, kind), U.gen(2, 2, (I, J, K), dtype, kind)
+    a = empty((1,), dtype)
+    lib.distal_innerprod(U.dev(B), U.dev(C), a)
+    ref = oracle.innerprod(B, C)
+    got = float(U.host(a)[0])
+    if kind == inputs.SMALLINT:
+        assert got == ref
+    else:
+        # binary64 accumulation on both sides: only the final rounding to dtype differs
+        scale = float(np.sum(np.abs(B.astype(np.float64) * C.astype(np.float64))))
+        eps = np.finfo(dtype).eps
+        assert abs(got - ref) <= eps * abs(ref) + 1e-15 * scale, (got, ref)
+        assert abs(got - ref) <= U.tol(dtype, I * J * K) * abs(ref) or abs(ref) < 1e-3 * scale
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_innerprod_closed_forms(lib, dtype):
+    n = 200003
+    B, C = U.gen(23, 0, (1, 1, n), dtype), U.gen(23, 2, (1, 1, n), dtype)
+    dB, dC = U.dev(B), U.dev(C)
+    a, b = empty((1,), dtype), empty((1,), dtype)
+    lib.distal_innerprod(dB, dC, a)
+    lib.distal_innerprod(dC, dB, b)
+    assert U.host(a)[0] == U.host(b)[0]                       # symmetric, bit for bit
+    lib.distal_innerprod(dB, dB, a)
+    sq = float(np.sum(B.astype(np.float64) ** 2))
+    assert U.host(a)[0] > 0 and abs(float(U.host(a)[0]) - sq) <= 2 * np.finfo(dtype).eps * sq
+    Bi = U.gen(23, 0, (1, 1, n), dtype, inputs.SMALLINT)
+    lib.distal_innerprod(U.dev(Bi), U.dev(np.ones_like(Bi)), a)
+    assert float(U.host(a)[0]) == float(Bi.astype(np.int64).sum())
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_innerprod_misaligned(lib, oracle, dtype):
+    n = 70001
+    fb, fc = U.gen(24, 0, (n + 1,), dtype, inputs.SMALLINT), U.gen(24, 2, (n + 1,), dtype, inputs.SMALLINT)
+    a = empty((1,), dtype)
+    lib.distal_innerprod(U.dev(fb)[1:].view(1, 1, n), U.dev(fc)[1:].view(1, 1, n), a)
+    assert float(U.host(a)[0]) == oracle.innerprod(fb[1:].reshape(1, 1, n), fc[1:].reshape(1, 1, n))
+
+
+# ------------------------------------------------------------------ mttkrp
+
+MTTKRP_SHAPES = [(1, 1, 1, 1), (3, 4, 5, 2), (4, 64, 64, 32), (5, 300, 40, 32), (3, 130, 129, 5),
+                 (2, 257, 33, 40), (6, 32, 1024, 32), (2, 600, 16, 33)]
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("I,J,K,L", MTTKRP_SHAPES)
+def test_mttkrp(lib, oracle, dtype, kind, I, J, K, L):
+    r = 2 if kind == inputs.SMALLINT else 3     # keeps every partial sum exactly representable
+    B = U.gen(4, 0, (I, J, K), dtype, kind, r)
+    C, D = U.gen(4, 1, (J, L), dtype, kind, r), U.gen(4, 2, (K, L), dtype, kind, r)
+    A = empty((I, L), dtype)
+    lib.distal_mttkrp(U.dev(B), U.dev(C), U.dev(D), A)
+    compare(U.host(A), oracle.mttkrp(B, C, D), dtype, kind, J * K)
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_mttkrp_rank1_and_selection(lib, dtype):
+    I, J, K = 5, 70, 48
+    B = U.gen(25, 0, (I, J, K), dtype, inputs.SMALLINT)
+    A = empty((I, 1), dtype)
+    lib.distal_mttkrp(U.dev(B), U.dev(np.ones((J, 1), dtype)), U.dev(np.ones((K, 1), dtype)), A)
+    assert np.array_equal(U.host(A)[:, 0].astype(np.int64), B.astype(np.int64).sum(axis=(1, 2)))
+    Bu = U.gen(25, 0, (I, J, K), dtype)
+    ps, qs = [3, 0, 69], [1, 47, 20]
+    C, D = np.zeros((J, 3), dtype), np.zeros((K, 3), dtype)
+    for l, (p, q) in enumerate(zip(ps, qs)):
+        C[p, l] = 1
+        D[q, l] = 1
+    A = empty((I, 3), dtype)
+    lib.distal_mttkrp(U.dev(Bu), U.dev(C), U.dev(D), A)
+    for l, (p, q) in enumerate(zip(ps, qs)):
+        assert np.array_equal(U.host(A)[:, l], Bu[:, p, q])
+
+
+# ------------------------------------------------------------------ degenerate extents, determinism
+
+@pytest.mark.parametrize("dtype", DT)
+def test_zero_extents(lib, dtype):
+    import torch
+    td = getattr(torch, np.dtype(dtype).name)
+    z = lambda *s: torch.zeros(s, dtype=td, device="cuda:0")
+    C = empty((3, 4), dtype)
+    lib.distal_gemm(z(3, 0), z(0, 4), C)
+    assert np.array_equal(U.host(C), np.zeros((3, 4)))
+    keep = U.gen(26, 2, (3, 4), dtype)
+    C = U.dev(keep)
+    lib.distal_gemm(z(3, 0), z(0, 4), C, accumulate=True)
+    assert np.array_equal(U.host(C), keep)
+    lib.distal_gemm(z(0, 5), z(5, 4), z(0, 4))
+    A = empty((2, 3), dtype)
+    lib.distal_ttv(z(2, 3, 0), z(0), A)
+    assert np.array_equal(U.host(A), np.zeros((2, 3)))
+    a = empty((1,), dtype)
+    lib.distal_innerprod(z(2, 0, 3), z(2, 0, 3), a)
+    assert float(U.host(a)[0]) == 0.0
+    A = empty((2, 3, 4), dtype)
+    lib.distal_ttm(z(2, 3, 0), z(0, 4), A)
+    assert np.array_equal(U.host(A), np.zeros((2, 3, 4)))
+    A = empty((2, 4), dtype)
+    lib.distal_mttkrp(z(2, 0, 3), z(0, 4), z(3, 4), A)
+    assert np.array_equal(U.host(A), np.zeros((2, 4)))
+    A = empty((2, 4), dtype)
+    lib.distal_mttkrp(z(2, 3, 0), z(3, 4), z(0, 4), A)
+    assert np.array_equal(U.host(A), np.zeros((2, 4)))
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_bitwise_reproducible(lib, dtype):
+    B = U.dev(U.gen(27, 0, (8, 96, 200), dtype))
+    C, D = U.dev(U.gen(27, 1, (96, 32), dtype)), U.dev(U.gen(27, 2, (200, 32), dtype))
+    c = U.dev(U.gen(27, 1, (200,), dtype))
+    outs = []
+    for _ in range(2):
+        A1, A2, A3, a = empty((8, 32), dtype), empty((8, 96), dtype), empty((8, 96, 32), dtype), empty((1,), dtype)
+        lib.distal_mttkrp(B, C, D, A1)
+        lib.distal_ttv(B, c, A2)
+        lib.distal_ttm(B, D, A3)
+        lib.distal_innerprod(B, B, a)
+        outs.append([U.host(x).tobytes() for x in (A1, A2, A3, a)])
+    assert outs[0] == outs[1]
+
+
+def test_runs_on_a_side_stream(lib, oracle):
+    import torch
+    A, B = U.gen(28, 0, (200, 64), np.float32), U.gen(28, 1, (64, 136), np.float32)
+    dA, dB = U.dev(A), U.dev(B)
+    C = empty((200, 136), np.float32)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        lib.distal_gemm(dA, dB, C)
+    s.synchronize()
+    U.assert_close(U.host(C), oracle.gemm(A, B), np.float32, 64)
