@@ -49,7 +49,7 @@ template <> struct Mfma<double> {          // v_mfma_f64_16x16x4_f64
     static __device__ __forceinline__ acc_t run(double a, double b, acc_t c) {
         return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
     }
-    static __device__ __forceinline__ int out_row(int v, int lane) { return 4 * (lane >> 4) + v; }
+    static __device__ __forceinline__ int out_row(int v, int lane) { return 4 * v + (lane >> 4); }
 };
 
 template <> struct Mfma<float> {           // v_mfma_f32_32x32x2_f32
