@@ -48,12 +48,18 @@ def _load():
             lib.oracle_ttm.argtypes = [ci, i64, i64, i64, i64, vp, vp, vp]
             lib.oracle_mttkrp.argtypes = [ci, i64, i64, i64, i64, vp, vp, vp, vp]
             for f in (lib.oracle_gemm, lib.oracle_ttv, lib.oracle_innerprod, lib.oracle_ttm,
-                      lib.oracle_mttkrp, lib.oracle_version, lib.oracle_long_double_digits):
+                      lib.oracle_mttkrp, lib.oracle_version, lib.oracle_long_double_digits,
+                      lib.oracle_max_threads):
                 f.restype = ci
             if lib.oracle_long_double_digits() < 64:
                 raise RuntimeError("oracle needs a long double with a 64-bit significand")
             _lib = lib
     return _lib
+
+
+def max_threads() -> int:
+    """OpenMP threads the oracle's loops use on this host."""
+    return int(_load().oracle_max_threads())
 
 
 def _dt(*arrays) -> int:

@@ -51,6 +51,9 @@
  */
 #include <stddef.h>
 #include <stdint.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 #define ORACLE_F32 0
 #define ORACLE_F64 1
@@ -69,6 +72,16 @@ static inline acc_t ld_elem(const void *p, int dt, int64_t n)
 int oracle_version(void) { return 1; }
 
 int oracle_long_double_digits(void) { return __LDBL_MANT_DIG__; }
+
+/* Number of OpenMP threads the loops below will use (1 when built without OpenMP). */
+int oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 /*
  * out(i,j) = [init(i,j) +] sum_k A(i,k) * B(k,j)     (operand names as in the
