@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdistal.so")
 SOURCES = ["distal_api.hip"]
-HEADERS = ["gemm_kernel.hpp", "stream_kernels.hpp"]
+HEADERS = ["gemm_kernel.hpp", "mttkrp_kernel.hpp", "stream_kernels.hpp"]
 
 # Packed-FP32 VALU forms are switched off for every kernel of this library.
 HIPCC_FLAGS = [

@@ -8,6 +8,7 @@
 
 #include "../../include/distal.h"
 #include "gemm_kernel.hpp"
+#include "mttkrp_kernel.hpp"
 #include "stream_kernels.hpp"
 
 using namespace distal;
@@ -42,24 +43,27 @@ int compute_units() {
     return cu;
 }
 
-template <typename T, int BM, int BN, int BK, int WM, int WN, int EPI>
-int launch_contract(const ContractArgs<T> &a, hipStream_t stream) {
-    typedef ContractCfg<T, BM, BN, BK, WM, WN, EPI> Cfg;
-    auto kern = contract_kernel<T, BM, BN, BK, WM, WN, EPI>;
-    if (Cfg::LDS_BYTES > 48 * 1024) {
-        // opt in to large dynamic LDS once per device for this instantiation
-        static std::atomic<bool> done[kMaxDevices];
-        const int d = current_device();
-        if (!done[d].load(std::memory_order_acquire)) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    Cfg::LDS_BYTES) != hipSuccess) {
-                (void)hipGetLastError();
-                return DISTAL_ERR_LAUNCH;
-            }
-            done[d].store(true, std::memory_order_release);
-        }
+// Opt in, once per device and kernel, to dynamic LDS beyond the default limit.
+template <typename Kern>
+bool allow_lds(Kern kern, int bytes, std::atomic<bool> (&done)[kMaxDevices]) {
+    if (bytes <= 48 * 1024) return true;
+    const int d = current_device();
+    if (done[d].load(std::memory_order_acquire)) return true;
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
     }
+    done[d].store(true, std::memory_order_release);
+    return true;
+}
+
+template <typename T, int BM, int BN, int BK, int WM, int WN, int PF = 1>
+int launch_contract(const ContractArgs<T> &a, hipStream_t stream) {
+    typedef ContractCfg<T, BM, BN, BK, WM, WN> Cfg;
+    auto kern = contract_kernel<T, BM, BN, BK, WM, WN, PF>;
+    static std::atomic<bool> done[kMaxDevices];
+    if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
     const int64_t nblocks = (int64_t)a.tiles_m * a.tiles_n;
     hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
     return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
@@ -95,7 +99,7 @@ int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
     a.a_vec_ok = aligned16(A) && lda % VEC == 0;
     a.b_vec_ok = aligned16(B) && ldb % VEC == 0;
     a.c_vec_ok = aligned16(C) && ldc % VEC == 0;
-    return launch_contract<T, BM, BN, BK, 2, 2, EPI_STORE>(a, stream);
+    return launch_contract<T, BM, BN, BK, 2, 2>(a, stream);
 }
 
 int check_dtype(int dt) { return (dt == DISTAL_F32 || dt == DISTAL_F64) ? DISTAL_OK : DISTAL_ERR_DTYPE; }
@@ -103,46 +107,92 @@ int check_dtype(int dt) { return (dt == DISTAL_F32 || dt == DISTAL_F64) ? DISTAL
 size_t elem_size(int dt) { return dt == DISTAL_F64 ? 8 : 4; }
 
 // ---- MTTKRP ---------------------------------------------------------------
-template <typename T> struct MttkrpTile;
-template <> struct MttkrpTile<float>  { static constexpr int BM = 256, BN = 32, BK = 16, WM = 4; };
-template <> struct MttkrpTile<double> { static constexpr int BM = 128, BN = 32, BK = 16, WM = 2; };
+constexpr int kMttkrpBM = 64;             // j rows per tile
+constexpr int64_t kMttkrpTargetWGs = 8192;
 
-int64_t mttkrp_jtiles(int dt, int64_t J) {
-    const int64_t bm = dt == DISTAL_F64 ? MttkrpTile<double>::BM : MttkrpTile<float>::BM;
-    return (J + bm - 1) / bm;
+// Rows of j per workgroup: whole tiles, sized so that a large problem yields a few
+// thousand workgroups.  A function of the shape only, never of the device, so the
+// summation order is reproducible.
+int64_t mttkrp_jc(int64_t I, int64_t J) {
+    const int64_t tiles_j = (J + kMttkrpBM - 1) / kMttkrpBM;
+    int64_t total;
+    if (!mul_ok(I > 0 ? I : 1, tiles_j, &total)) total = std::numeric_limits<int64_t>::max();
+    int64_t tpc = total / kMttkrpTargetWGs;
+    if (tpc < 1) tpc = 1;
+    if (tpc > tiles_j) tpc = tiles_j;
+    return tpc * kMttkrpBM;
+}
+
+int64_t mttkrp_nchunks(int64_t I, int64_t J) {
+    const int64_t jc = mttkrp_jc(I, J);
+    return J > 0 ? (J + jc - 1) / jc : 1;
+}
+
+// Workspace layout: [Dt: 32*tiles_n rows x Kpad][partials: I*nchunks x L, only if nchunks > 1]
+struct MttkrpPlan {
+    int64_t nchunks, tiles_n, kpad, dt_elems, partial_elems;
+    bool ok;
+};
+
+MttkrpPlan mttkrp_plan(int dt, int64_t I, int64_t J, int64_t K, int64_t L) {
+    MttkrpPlan p{};
+    const int64_t bk = 512 / (int64_t)(dt == DISTAL_F64 ? 8 : 4);
+    p.nchunks = mttkrp_nchunks(I, J);
+    p.tiles_n = (L + 31) / 32;
+    p.kpad = (K + bk - 1) / bk * bk;
+    int64_t t;
+    p.ok = mul_ok(p.tiles_n * 32, p.kpad, &p.dt_elems) && mul_ok(I, p.nchunks, &t) &&
+           mul_ok(t, L, &p.partial_elems) && p.dt_elems <= INT64_MAX / 16 && p.partial_elems <= INT64_MAX / 16;
+    if (p.nchunks <= 1) p.partial_elems = 0;
+    return p;
 }
 
 template <typename T>
 int mttkrp_t(int64_t I, int64_t J, int64_t K, int64_t L, const T *B, const T *C, const T *D, T *A,
              void *workspace, hipStream_t stream) {
-    typedef MttkrpTile<T> Tile;
-    constexpr int VEC = 16 / (int)sizeof(T);
+    typedef MttkrpCfg<T, kMttkrpBM> Cfg;
     if (I == 0 || L == 0) return DISTAL_OK;
     if (J == 0 || K == 0) return launch_fill<T>(A, I, L, L, stream);
-    const int64_t jtiles = (J + Tile::BM - 1) / Tile::BM;
-    const int64_t tn = (L + Tile::BN - 1) / Tile::BN;
-    int64_t tm, nblocks;
-    if (!mul_ok(I, jtiles, &tm) || !mul_ok(tm, tn, &nblocks) ||
+    const MttkrpPlan plan = mttkrp_plan(sizeof(T) == 8 ? DISTAL_F64 : DISTAL_F32, I, J, K, L);
+    int64_t ic, nblocks;
+    if (!plan.ok || !mul_ok(I, plan.nchunks, &ic) || !mul_ok(ic, plan.tiles_n, &nblocks) ||
         nblocks > std::numeric_limits<int>::max())
         return DISTAL_ERR_SHAPE;
-    ContractArgs<T> a{};
-    a.A = B; a.B = D; a.C = nullptr;
-    a.M = I * J; a.N = L; a.K = K;
-    a.lda = K; a.ldb = L; a.ldc = L;
-    a.tiles_m = (int)tm; a.tiles_n = (int)tn;
-    a.a_vec_ok = aligned16(B) && K % VEC == 0;
-    a.b_vec_ok = aligned16(D) && L % VEC == 0;
-    a.c_vec_ok = 0;
-    a.F = C;
-    a.J = J;
-    a.jtiles = (int)jtiles;
-    a.partial = jtiles == 1 ? A : static_cast<T *>(workspace);
-    int rc = launch_contract<T, Tile::BM, Tile::BN, Tile::BK, Tile::WM, 1, EPI_MTTKRP>(a, stream);
-    if (rc != DISTAL_OK || jtiles == 1) return rc;
+    T *dt_buf = static_cast<T *>(workspace);
+    T *partial = dt_buf + plan.dt_elems;
+    {
+        int64_t blocks = (plan.dt_elems + 255) / 256;
+        if (blocks > 1024) blocks = 1024;
+        hipLaunchKernelGGL(mttkrp_transpose_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream, D, dt_buf,
+                           K, L, plan.kpad, plan.tiles_n * 32);
+        if (hipGetLastError() != hipSuccess) return DISTAL_ERR_LAUNCH;
+    }
+    MttkrpArgs<T> a{};
+    a.B = B; a.C = C; a.Dt = dt_buf;
+    a.I = I; a.J = J; a.K = K; a.L = L;
+    a.Kpad = plan.kpad;
+    a.jc = mttkrp_jc(I, J);
+    a.nchunks = (int)plan.nchunks;
+    a.tiles_n = (int)plan.tiles_n;
+    a.partial = plan.nchunks == 1 ? A : partial;
+    const bool full = aligned16(B) && aligned16(C) && J % kMttkrpBM == 0 && K % Cfg::BK == 0 &&
+                      L % Cfg::BN == 0;
+    static std::atomic<bool> done_fast[kMaxDevices], done_guard[kMaxDevices];
+    if (full) {
+        auto kern = mttkrp_kernel<T, kMttkrpBM, false>;
+        if (!allow_lds(kern, Cfg::LDS_BYTES, done_fast)) return DISTAL_ERR_LAUNCH;
+        hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
+    } else {
+        auto kern = mttkrp_kernel<T, kMttkrpBM, true>;
+        if (!allow_lds(kern, Cfg::LDS_BYTES, done_guard)) return DISTAL_ERR_LAUNCH;
+        hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
+    }
+    if (hipGetLastError() != hipSuccess) return DISTAL_ERR_LAUNCH;
+    if (plan.nchunks == 1) return DISTAL_OK;
     int64_t blocks = (I * L + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(mttkrp_reduce_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream,
-                       static_cast<const T *>(workspace), A, I, L, (int)jtiles);
+                       static_cast<const T *>(partial), A, I, L, (int)plan.nchunks);
     return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
 }
 
@@ -272,11 +322,10 @@ int distal_ttm(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L, cons
 
 size_t distal_mttkrp_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L) {
     if (check_dtype(dt) != DISTAL_OK || I < 0 || J < 0 || K < 0 || L < 0) return 0;
-    const int64_t jt = mttkrp_jtiles(dt, J);
-    if (jt <= 1) return 0;
-    int64_t a, b;
-    if (!mul_ok(I, jt, &a) || !mul_ok(a, L, &b) || b > INT64_MAX / 8) return 0;
-    return (size_t)b * elem_size(dt);
+    if (I == 0 || J == 0 || K == 0 || L == 0) return 0;
+    const MttkrpPlan p = mttkrp_plan(dt, I, J, K, L);
+    if (!p.ok) return 0;
+    return (size_t)(p.dt_elems + p.partial_elems) * elem_size(dt);
 }
 
 int distal_mttkrp(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L, const void *B,
@@ -286,7 +335,7 @@ int distal_mttkrp(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L, c
     if (I < 0 || J < 0 || K < 0 || L < 0) return DISTAL_ERR_SHAPE;
     int64_t nb, nc, nd, na, t;
     if (!tensor_elems(I, J, K, &nb) || !mul_ok(J, L, &nc) || !mul_ok(K, L, &nd) || !mul_ok(I, L, &na) ||
-        !mul_ok(I, mttkrp_jtiles(dt, J), &t) || !mul_ok(t, L, &t) || t > INT64_MAX / 8)
+        !mttkrp_plan(dt, I, J, K, L).ok)
         return DISTAL_ERR_SHAPE;
     const bool work = nb > 0 && L > 0;
     if ((work && (!B || !C || !D)) || (na > 0 && !A)) return DISTAL_ERR_NULL;

@@ -1,6 +1,5 @@
 // MFMA contraction kernel for gfx950: one template serves the matrix-multiply
-// tile step, TTM (the same contraction on the (I*J) x K view of the tensor) and
-// the matrix-product stage of MTTKRP with its element-wise reduction fused in.
+// tile step and TTM (the same contraction on the (I*J) x K view of the tensor).
 //
 // Work decomposition
 //   grid   : one workgroup per BM x BN output tile, block ids remapped so that
@@ -38,6 +37,10 @@ template <> struct VecOf<float, 1> { typedef float type; };
 template <> struct VecOf<float, 2> { typedef v2f type; };
 template <> struct VecOf<float, 4> { typedef v4f type; };
 
+// Fused multiply-add in the element type (the unsuffixed builtin is binary64 only).
+__device__ __forceinline__ float fma_t(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+__device__ __forceinline__ double fma_t(double a, double b, double c) { return __builtin_fma(a, b, c); }
+
 // Per-dtype MFMA shape and register layout.
 //   lane -> (row-or-column index within the block, k-slot) for the operands;
 //   accumulator register v of a lane -> output row within the block.
@@ -63,24 +66,16 @@ template <> struct Mfma<float> {           // v_mfma_f32_32x32x2_f32
     }
 };
 
-enum { EPI_STORE = 0, EPI_MTTKRP = 1 };
-
 template <typename T>
 struct ContractArgs {
     const T *A;          // left operand rows (M x K view), row stride lda
     const T *B;          // right operand (K x N), row stride ldb
-    T *C;                // EPI_STORE: output (M x N), row stride ldc
+    T *C;                // output (M x N), row stride ldc
     int64_t M, N, K;
     int64_t lda, ldb, ldc;
     int accumulate;
     int tiles_m, tiles_n;
     int a_vec_ok, b_vec_ok, c_vec_ok;   // 16-byte vector access is legal on that operand
-    // EPI_MTTKRP: rows are (i, j) pairs of an I x J x K tensor, tile row-blocks never
-    // cross an i boundary: tile_m = i * jtiles + jt covers j in [jt*BM, min(J, (jt+1)*BM)).
-    const T *F;          // factor matrix C(j, l), J x N dense
-    T *partial;          // (I * jtiles) x N partial column sums, or the output itself if jtiles == 1
-    int64_t J;
-    int jtiles;
 };
 
 // Block id -> output tile.  Hardware hands consecutive workgroup ids to the 8
@@ -101,7 +96,7 @@ __device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m,
     tn = r / gs;
 }
 
-template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int EPI>
+template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N>
 struct ContractCfg {
     typedef Mfma<T> MF;
     static constexpr int NT = 64 * WAVES_M * WAVES_N;
@@ -121,13 +116,12 @@ struct ContractCfg {
     static constexpr int A_PER_T = (A_VECS + NT - 1) / NT, B_PER_T = (B_VECS + NT - 1) / NT;
     static_assert(BM % (WAVES_M * MF::MB) == 0 && BN % (WAVES_N * MF::NB) == 0, "tile shape");
     static_assert(BK % KG == 0, "BK must hold whole MFMA k-groups");
-    static_assert(EPI == EPI_STORE || (WAVES_N == 1), "reduction epilogue keeps all columns in one wave column");
 };
 
-template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int EPI>
+template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int PF = 1>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N, 2)
 contract_kernel(const ContractArgs<T> args) {
-    typedef ContractCfg<T, BM, BN, BK, WAVES_M, WAVES_N, EPI> Cfg;
+    typedef ContractCfg<T, BM, BN, BK, WAVES_M, WAVES_N> Cfg;
     typedef Mfma<T> MF;
     typedef typename VecOf<T, Cfg::VEC>::type vec_t;
     typedef typename VecOf<T, Cfg::CV>::type cvec_t;
@@ -146,24 +140,17 @@ contract_kernel(const ContractArgs<T> args) {
     int tm, tn;
     tile_of_block(blockIdx.x, gridDim.x, args.tiles_m, args.tiles_n, tm, tn);
 
-    int64_t m0, mlimit;
-    if (EPI == EPI_MTTKRP) {
-        const int64_t i = tm / args.jtiles, jt = tm % args.jtiles;
-        m0 = i * args.J + jt * BM;
-        mlimit = (i + 1) * args.J;
-    } else {
-        m0 = (int64_t)tm * BM;
-        mlimit = args.M;
-    }
+    const int64_t m0 = (int64_t)tm * BM, mlimit = args.M;
     const int64_t n0 = (int64_t)tn * BN;
     const int64_t K = args.K;
 
     const bool a_fast = args.a_vec_ok && (m0 + BM <= mlimit);
     const bool b_fast = args.b_vec_ok && (n0 + BN <= args.N);
 
-    vec_t ra[Cfg::A_PER_T], rb[Cfg::B_PER_T];
+    // PF register sets hold the next PF slabs while they are in flight from HBM/L2.
+    vec_t ra_all[PF][Cfg::A_PER_T], rb_all[PF][Cfg::B_PER_T];
 
-    auto load_global = [&](int64_t k0) {
+    auto load_global = [&](vec_t (&ra)[Cfg::A_PER_T], vec_t (&rb)[Cfg::B_PER_T], int64_t k0) {
         const bool kfull = (k0 + BK <= K);
         if (a_fast && kfull) {
 #pragma unroll
@@ -215,7 +202,7 @@ contract_kernel(const ContractArgs<T> args) {
         }
     };
 
-    auto store_lds = [&](int stage) {
+    auto store_lds = [&](const vec_t (&ra)[Cfg::A_PER_T], const vec_t (&rb)[Cfg::B_PER_T], int stage) {
         T *as = lds + stage * Cfg::STAGE_ELEMS;
         T *bs = as + Cfg::A_ELEMS;
 #pragma unroll
@@ -273,88 +260,67 @@ contract_kernel(const ContractArgs<T> args) {
         }
     };
 
+    // Slab t+1 sits in register set (t+1) % PF while slab t is multiplied; once it has
+    // been written to the idle LDS buffer, that register set is refilled with slab
+    // t+1+PF.  Slab indices past the end are clamped to the last slab: those loads are
+    // redundant cache hits, never out of bounds, and keep the loop free of divergence.
     const int64_t nk = (K + BK - 1) / BK;
+    auto k_of = [&](int64_t t) { return (t < nk ? t : nk - 1) * BK; };
     if (nk > 0) {
-        load_global(0);
-        store_lds(0);
+#pragma unroll
+        for (int u = 0; u < PF; ++u) load_global(ra_all[u], rb_all[u], k_of(u));
+        store_lds(ra_all[0], rb_all[0], 0);
+        load_global(ra_all[0], rb_all[0], k_of(PF));
     }
     __syncthreads();
-    for (int64_t t = 0; t < nk; ++t) {
-        const int stage = (int)(t & 1);
-        if (t + 1 < nk) load_global((t + 1) * BK);
-        compute(stage);
-        if (t + 1 < nk) store_lds(stage ^ 1);
-        __syncthreads();
+    for (int64_t t0 = 0; t0 < nk; t0 += PF) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            const int64_t t = t0 + u;
+            if (t < nk) {
+                const int stage = (int)(t & 1);
+                compute(stage);
+                if (t + 1 < nk) store_lds(ra_all[(u + 1) % PF], rb_all[(u + 1) % PF], stage ^ 1);
+                load_global(ra_all[(u + 1) % PF], rb_all[(u + 1) % PF], k_of(t + 1 + PF));
+                __syncthreads();
+            }
+        }
     }
 
-    if constexpr (EPI == EPI_STORE) {
-        const bool c_fast = args.c_vec_ok && (m0 + BM <= args.M) && (n0 + BN <= args.N);
+    // epilogue: accumulators -> C, CV neighbouring columns per store
+    const bool c_fast = args.c_vec_ok && (m0 + BM <= args.M) && (n0 + BN <= args.N);
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
+    for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-            for (int g = 0; g < NG; ++g)
+        for (int g = 0; g < NG; ++g)
 #pragma unroll
-                for (int v = 0; v < MF::NACC; ++v) {
-                    const int64_t row = m0 + wm * Cfg::WTM + mi * MF::MB + MF::out_row(v, lane);
-                    const int64_t col = n0 + wn * Cfg::WTN + g * (MF::NB * CV) + li * CV;
-                    T *cp = args.C + row * args.ldc + col;
-                    if (c_fast) {
-                        cvec_t o;
-                        if constexpr (CV == 1) {
-                            o = acc[mi][g][v];
-                            if (args.accumulate) o += *cp;
-                            *cp = o;
-                        } else {
-#pragma unroll
-                            for (int q = 0; q < CV; ++q) o[q] = acc[mi][g * CV + q][v];
-                            if (args.accumulate) o += *reinterpret_cast<const cvec_t *>(cp);
-                            *reinterpret_cast<cvec_t *>(cp) = o;
-                        }
+            for (int v = 0; v < MF::NACC; ++v) {
+                const int64_t row = m0 + wm * Cfg::WTM + mi * MF::MB + MF::out_row(v, lane);
+                const int64_t col = n0 + wn * Cfg::WTN + g * (MF::NB * CV) + li * CV;
+                T *cp = args.C + row * args.ldc + col;
+                if (c_fast) {
+                    cvec_t o;
+                    if constexpr (CV == 1) {
+                        o = acc[mi][g][v];
+                        if (args.accumulate) o += *cp;
+                        *cp = o;
                     } else {
 #pragma unroll
-                        for (int q = 0; q < CV; ++q) {
-                            if (row < args.M && col + q < args.N) {
-                                T o = acc[mi][g * CV + q][v];
-                                if (args.accumulate) o += cp[q];
-                                cp[q] = o;
-                            }
+                        for (int q = 0; q < CV; ++q) o[q] = acc[mi][g * CV + q][v];
+                        if (args.accumulate) o += *reinterpret_cast<const cvec_t *>(cp);
+                        *reinterpret_cast<cvec_t *>(cp) = o;
+                    }
+                } else {
+#pragma unroll
+                    for (int q = 0; q < CV; ++q) {
+                        if (row < args.M && col + q < args.N) {
+                            T o = acc[mi][g * CV + q][v];
+                            if (args.accumulate) o += cp[q];
+                            cp[q] = o;
                         }
                     }
                 }
-    } else {
-        // MTTKRP: scale T(j,l) by the factor C(j,l) and sum over the tile's j rows.
-        // Each lane first sums its own rows per owned column; the per-lane sums then
-        // meet in LDS and are added in a fixed order.
-        const int64_t i_row0 = (tm / args.jtiles) * args.J;   // first tensor row of this i
-        T colsum[NI];
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni) colsum[ni] = T(0);
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                for (int v = 0; v < MF::NACC; ++v) {
-                    const int64_t row = m0 + wm * Cfg::WTM + mi * MF::MB + MF::out_row(v, lane);
-                    const int64_t col = n0 + (ni / CV) * (MF::NB * CV) + li * CV + (ni % CV);
-                    if (row < mlimit && col < args.N)
-                        colsum[ni] += acc[mi][ni][v] * args.F[(row - i_row0) * args.N + col];
-                }
-        // red[wm][ls][column-in-tile]; the operand buffers are idle after the final barrier
-        T *red = lds;
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni) {
-            const int c = (ni / CV) * (MF::NB * CV) + li * CV + (ni % CV);
-            red[(wm * MF::KS + ls) * BN + c] = colsum[ni];
-        }
-        __syncthreads();
-        if (tid < BN && n0 + tid < args.N) {
-            T s = T(0);
-#pragma unroll
-            for (int w = 0; w < WAVES_M * MF::KS; ++w) s += red[w * BN + tid];
-            args.partial[(int64_t)tm * args.N + n0 + tid] = s;
-        }
-    }
+            }
 }
 
 }  // namespace distal

@@ -85,14 +85,14 @@ ttv_vec_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict__
             for (int u = 0; u < UNROLL; ++u) {
                 const vec_t cc = cv[v + 16 * u];
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) acc = __builtin_fma(b[u][e], cc[e], acc);
+                for (int e = 0; e < VEC; ++e) acc = fma_t(b[u][e], cc[e], acc);
             }
         }
         for (; v < kvecs; v += 16) {
             const vec_t b = __builtin_nontemporal_load(row + v);
             const vec_t cc = cv[v];
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc = __builtin_fma(b[e], cc[e], acc);
+            for (int e = 0; e < VEC; ++e) acc = fma_t(b[e], cc[e], acc);
         }
         acc = sum16(acc);
         if (q == 0) A[r] = acc;
@@ -110,7 +110,7 @@ ttv_generic_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restri
     for (int64_t r = group; r < rows; r += stride) {
         const T *row = B + r * K;
         T acc = T(0);
-        for (int64_t k = q; k < K; k += 16) acc = __builtin_fma(row[k], c[k], acc);
+        for (int64_t k = q; k < K; k += 16) acc = fma_t(row[k], c[k], acc);
         acc = sum16(acc);
         if (q == 0) A[r] = acc;
     }
