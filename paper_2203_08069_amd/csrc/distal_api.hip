@@ -107,56 +107,84 @@ int check_dtype(int dt) { return (dt == DISTAL_F32 || dt == DISTAL_F64) ? DISTAL
 size_t elem_size(int dt) { return dt == DISTAL_F64 ? 8 : 4; }
 
 // ---- MTTKRP ---------------------------------------------------------------
-constexpr int kMttkrpBM = 64;             // j rows per tile
-constexpr int64_t kMttkrpTargetWGs = 8192;
+constexpr int64_t kMttkrpBlocksPerItem = 8;   // 32-row blocks of j per work item
 
-// Rows of j per workgroup: whole tiles, sized so that a large problem yields a few
-// thousand workgroups.  A function of the shape only, never of the device, so the
-// summation order is reproducible.
-int64_t mttkrp_jc(int64_t I, int64_t J) {
-    const int64_t tiles_j = (J + kMttkrpBM - 1) / kMttkrpBM;
-    int64_t total;
-    if (!mul_ok(I > 0 ? I : 1, tiles_j, &total)) total = std::numeric_limits<int64_t>::max();
-    int64_t tpc = total / kMttkrpTargetWGs;
-    if (tpc < 1) tpc = 1;
-    if (tpc > tiles_j) tpc = tiles_j;
-    return tpc * kMttkrpBM;
-}
-
-int64_t mttkrp_nchunks(int64_t I, int64_t J) {
-    const int64_t jc = mttkrp_jc(I, J);
-    return J > 0 ? (J + jc - 1) / jc : 1;
-}
-
-// Workspace layout: [Dt: 32*tiles_n rows x Kpad][partials: I*nchunks x L, only if nchunks > 1]
+// Work decomposition and workspace layout, a function of the shape only (never of the
+// device), so the summation order is reproducible.
+// Workspace: [Dt: 32*tiles_n rows x Kpad][partial rows: I*nchunks*nslices x L, unless that is I]
 struct MttkrpPlan {
-    int64_t nchunks, tiles_n, kpad, dt_elems, partial_elems;
+    int64_t jc, nchunks, nslices, kgroups, tiles_n, kpad, dt_elems, partial_rows, partial_elems;
     bool ok;
 };
 
 MttkrpPlan mttkrp_plan(int dt, int64_t I, int64_t J, int64_t K, int64_t L) {
     MttkrpPlan p{};
-    const int64_t bk = 512 / (int64_t)(dt == DISTAL_F64 ? 8 : 4);
-    p.nchunks = mttkrp_nchunks(I, J);
+    const int64_t sl = 256 / (int64_t)(dt == DISTAL_F64 ? 8 : 4);       // k values per wavefront slice
+    const int64_t rb = 32;
+    p.nslices = (K + sl - 1) / sl;
+    if (p.nslices < 1) p.nslices = 1;
+    p.kgroups = (p.nslices + 3) / 4;
+    p.kpad = p.kgroups * 4 * sl;
     p.tiles_n = (L + 31) / 32;
-    p.kpad = (K + bk - 1) / bk * bk;
+    const int64_t blocks_j = (J + rb - 1) / rb;
+    const int64_t bpc = blocks_j < kMttkrpBlocksPerItem ? (blocks_j > 0 ? blocks_j : 1) : kMttkrpBlocksPerItem;
+    p.jc = bpc * rb;
+    p.nchunks = J > 0 ? (J + p.jc - 1) / p.jc : 1;
     int64_t t;
     p.ok = mul_ok(p.tiles_n * 32, p.kpad, &p.dt_elems) && mul_ok(I, p.nchunks, &t) &&
-           mul_ok(t, L, &p.partial_elems) && p.dt_elems <= INT64_MAX / 16 && p.partial_elems <= INT64_MAX / 16;
-    if (p.nchunks <= 1) p.partial_elems = 0;
+           mul_ok(t, p.nslices, &p.partial_rows) && mul_ok(p.partial_rows, L, &p.partial_elems) &&
+           p.dt_elems <= INT64_MAX / 16 && p.partial_elems <= INT64_MAX / 16;
+    if (p.nchunks * p.nslices <= 1) p.partial_elems = 0;
     return p;
+}
+
+template <typename Kern>
+int resident_blocks_per_cu(Kern kern, int lds_bytes, std::atomic<int> (&cache)[kMaxDevices]) {
+    const int d = current_device();
+    int v = cache[d].load(std::memory_order_relaxed);
+    if (v == 0) {
+        int nb = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, reinterpret_cast<const void *>(kern), 256,
+                                                         (size_t)lds_bytes) != hipSuccess || nb < 1) {
+            (void)hipGetLastError();
+            nb = 1;
+        }
+        cache[d].store(nb, std::memory_order_relaxed);
+        v = nb;
+    }
+    return v;
+}
+
+template <typename T, bool GUARD>
+int launch_mttkrp(MttkrpArgs<T> &a, int64_t nitems, hipStream_t stream) {
+    typedef MttkrpCfg<T> Cfg;
+    auto kern = mttkrp_kernel<T, GUARD>;
+    static std::atomic<bool> done[kMaxDevices];
+    static std::atomic<int> occ[kMaxDevices];
+    if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
+    // persistent grid: as many workgroups as stay resident, shared out over the k-groups
+    const int64_t resident = (int64_t)resident_blocks_per_cu(kern, Cfg::LDS_BYTES, occ) * compute_units();
+    const int64_t lanes = (int64_t)a.kgroups * a.tiles_n;
+    int64_t groups = resident / lanes;
+    if (groups < 1) groups = 1;
+    if (groups > nitems) groups = nitems;
+    int64_t nblocks;
+    if (!mul_ok(groups, lanes, &nblocks) || nblocks > std::numeric_limits<int>::max()) return DISTAL_ERR_SHAPE;
+    a.groups = (int)groups;
+    hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
+    return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
 }
 
 template <typename T>
 int mttkrp_t(int64_t I, int64_t J, int64_t K, int64_t L, const T *B, const T *C, const T *D, T *A,
              void *workspace, hipStream_t stream) {
-    typedef MttkrpCfg<T, kMttkrpBM> Cfg;
+    typedef MttkrpCfg<T> Cfg;
     if (I == 0 || L == 0) return DISTAL_OK;
     if (J == 0 || K == 0) return launch_fill<T>(A, I, L, L, stream);
     const MttkrpPlan plan = mttkrp_plan(sizeof(T) == 8 ? DISTAL_F64 : DISTAL_F32, I, J, K, L);
-    int64_t ic, nblocks;
-    if (!plan.ok || !mul_ok(I, plan.nchunks, &ic) || !mul_ok(ic, plan.tiles_n, &nblocks) ||
-        nblocks > std::numeric_limits<int>::max())
+    if (!plan.ok || plan.kgroups * plan.tiles_n > std::numeric_limits<int>::max() / 2 ||
+        plan.nslices > std::numeric_limits<int>::max() / 8 ||
+        plan.nchunks * plan.nslices > std::numeric_limits<int>::max())
         return DISTAL_ERR_SHAPE;
     T *dt_buf = static_cast<T *>(workspace);
     T *partial = dt_buf + plan.dt_elems;
@@ -167,32 +195,28 @@ int mttkrp_t(int64_t I, int64_t J, int64_t K, int64_t L, const T *B, const T *C,
                            K, L, plan.kpad, plan.tiles_n * 32);
         if (hipGetLastError() != hipSuccess) return DISTAL_ERR_LAUNCH;
     }
+    const int64_t per_i = plan.nchunks * plan.nslices;
     MttkrpArgs<T> a{};
     a.B = B; a.C = C; a.Dt = dt_buf;
     a.I = I; a.J = J; a.K = K; a.L = L;
     a.Kpad = plan.kpad;
-    a.jc = mttkrp_jc(I, J);
+    a.jc = plan.jc;
     a.nchunks = (int)plan.nchunks;
+    a.nslices = (int)plan.nslices;
+    a.kgroups = (int)plan.kgroups;
     a.tiles_n = (int)plan.tiles_n;
-    a.partial = plan.nchunks == 1 ? A : partial;
-    const bool full = aligned16(B) && aligned16(C) && J % kMttkrpBM == 0 && K % Cfg::BK == 0 &&
-                      L % Cfg::BN == 0;
-    static std::atomic<bool> done_fast[kMaxDevices], done_guard[kMaxDevices];
-    if (full) {
-        auto kern = mttkrp_kernel<T, kMttkrpBM, false>;
-        if (!allow_lds(kern, Cfg::LDS_BYTES, done_fast)) return DISTAL_ERR_LAUNCH;
-        hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
-    } else {
-        auto kern = mttkrp_kernel<T, kMttkrpBM, true>;
-        if (!allow_lds(kern, Cfg::LDS_BYTES, done_guard)) return DISTAL_ERR_LAUNCH;
-        hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
-    }
-    if (hipGetLastError() != hipSuccess) return DISTAL_ERR_LAUNCH;
-    if (plan.nchunks == 1) return DISTAL_OK;
+    a.partial = per_i == 1 ? A : partial;
+    const int64_t nitems = I * plan.nchunks;
+    if (nitems > std::numeric_limits<int>::max()) return DISTAL_ERR_SHAPE;
+    // the unguarded kernel addresses a 32-row block with 32-bit byte offsets
+    const bool full = aligned16(B) && aligned16(C) && J % Cfg::RB == 0 && K % Cfg::SL == 0 &&
+                      L % Cfg::BN == 0 && K <= (1 << 22) && L <= (1 << 22);
+    const int rc = full ? launch_mttkrp<T, false>(a, nitems, stream) : launch_mttkrp<T, true>(a, nitems, stream);
+    if (rc != DISTAL_OK || per_i == 1) return rc;
     int64_t blocks = (I * L + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(mttkrp_reduce_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream,
-                       static_cast<const T *>(partial), A, I, L, (int)plan.nchunks);
+                       static_cast<const T *>(partial), A, I, L, (int)per_i);
     return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
 }
 
@@ -202,14 +226,14 @@ int ttv_t(int64_t rows, int64_t K, const T *B, const T *c, T *A, hipStream_t str
     constexpr int VEC = 16 / (int)sizeof(T);
     if (rows == 0) return DISTAL_OK;
     if (K == 0) return launch_fill<T>(A, rows, 1, 1, stream);
+    // one 16-row group per workgroup; very large grids fall back to the grid-stride loop
     int64_t blocks = (rows + 15) / 16;
-    const int64_t cap = (int64_t)compute_units() * 8;
-    if (blocks > cap) blocks = cap;
+    if (blocks > (1 << 22)) blocks = 1 << 22;
     const bool vec = aligned16(B) && aligned16(c) && K % VEC == 0;
     if (!vec) {
         hipLaunchKernelGGL(ttv_generic_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream, B, c, A, rows, K);
     } else if (K * (int64_t)sizeof(T) <= 32 * 1024) {
-        hipLaunchKernelGGL((ttv_vec_kernel<T, 8, true>), dim3((unsigned)blocks), dim3(256),
+        hipLaunchKernelGGL((ttv_vec_kernel<T, 16, true>), dim3((unsigned)blocks), dim3(256),
                            (size_t)K * sizeof(T), stream, B, c, A, rows, K);
     } else {
         hipLaunchKernelGGL((ttv_vec_kernel<T, 8, false>), dim3((unsigned)blocks), dim3(256), 0, stream,
@@ -333,7 +357,7 @@ int distal_mttkrp(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L, c
                   void *stream) {
     if (check_dtype(dt) != DISTAL_OK) return DISTAL_ERR_DTYPE;
     if (I < 0 || J < 0 || K < 0 || L < 0) return DISTAL_ERR_SHAPE;
-    int64_t nb, nc, nd, na, t;
+    int64_t nb, nc, nd, na;
     if (!tensor_elems(I, J, K, &nb) || !mul_ok(J, L, &nc) || !mul_ok(K, L, &nd) || !mul_ok(I, L, &na) ||
         !mttkrp_plan(dt, I, J, K, L).ok)
         return DISTAL_ERR_SHAPE;

@@ -2,33 +2,38 @@
 //
 // The paper's leaf casts MTTKRP to matrix multiplications followed by an
 // element-wise reduction (evaluation section, leaf kernels).  Here both happen
-// in one pass over B, which is read from HBM exactly once:
+// in one pass over B, which is read from HBM exactly once, and every wavefront
+// runs on its own - there is no workgroup barrier in the streaming loop:
 //
 //   * A small pre-kernel writes D transposed and zero-padded (Dt: 32*tiles_n rows
 //     of Kpad values), so that k is the contiguous index of BOTH MFMA operands.
-//   * A workgroup owns one i and a chunk of j.  It walks that chunk in tiles of
-//     BM rows (j) and each tile in slabs of BK = 512 bytes of k, so every global
-//     read of B is a 512-byte contiguous run - the run length at which HBM
-//     streaming reaches its plateau on this part.
-//   * A slab is (BM + 32) rows of BK values: BM rows of B and the 32 rows of Dt
-//     for this column tile.  It goes global -> registers -> LDS (one LDS buffer;
-//     the next slab's loads are in flight while the current one is multiplied).
-//   * MFMA forms the TRANSPOSED product Tt(l,j) = sum_k Dt(l,k) B(j,k): a lane then
-//     owns one j and several l, so the factor values C(j, l..) it needs are
-//     contiguous in memory.  The four wavefronts split the slab's k range
-//     ("split-k"), each holding a partial Tt_w.
-//   * The reduction over j is linear, so no wavefront needs the others' partial
-//     Tt: at the end of a tile each lane scales its own accumulators by C(j,l)
-//     and folds them into running sums, one per owned l.  Only when the whole
-//     chunk is done do the lane sums meet in LDS, in a fixed order.
-//   * One partial row of L values per (i, chunk) goes to the workspace; a last
-//     tiny kernel adds the chunks in order.  Nothing is atomic: results are
+//   * The grid is persistent (a few workgroups per CU).  A wavefront owns ONE k-slice
+//     of SL = 256 bytes for its whole life and walks a strided list of work items,
+//     an item being one i and a chunk of j.  The Dt values of its slice (32 l x SL
+//     k) are loaded into registers once, so D costs no further traffic.  The four
+//     wavefronts of a workgroup take four neighbouring slices of the same rows
+//     (1 KiB contiguous per row).
+//   * The wavefront walks its chunk in blocks of RB = 32 rows.  A block's RB x SL
+//     piece of B goes global -> registers (coalesced 16-byte loads, the next
+//     block's loads are in flight during the multiply) -> a wavefront-private LDS
+//     patch -> back in MFMA operand layout.  Only the wavefront that wrote the
+//     patch reads it, so ordering inside the wavefront suffices.
+//   * MFMA forms the TRANSPOSED partial product Tt(l,j) = sum_{k in slice} Dt(l,k)
+//     B(j,k): a lane owns one j and several l, so the factor values C(j, l..) it
+//     needs are contiguous.  The sums over j and over k-slices are both linear:
+//     after every block the lane scales its accumulators by C(j,l) and adds them
+//     to running sums, one per owned l.
+//   * At the end of an item the lanes that own the same l are added with DPP
+//     rotations in a fixed order and the wavefront writes its own partial row of 32
+//     values to the workspace; a last tiny kernel adds the partial rows of each i in
+//     order.  Nothing is atomic and no sum depends on the grid size: results are
 //     bitwise reproducible.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include "gemm_kernel.hpp"
+#include "stream_kernels.hpp"   // sum16 (DPP row rotations)
 
 namespace distal {
 
@@ -37,34 +42,35 @@ struct MttkrpArgs {
     const T *B;        // I x J x K
     const T *C;        // J x L
     const T *Dt;       // (32 * tiles_n) x Kpad, transposed zero-padded D
-    T *partial;        // (I * nchunks) x L, or the output itself when nchunks == 1
+    T *partial;        // (I * nchunks * nslices) x L: row (item * nslices + slice); the output
+                       // itself when nchunks * nslices == 1
     int64_t I, J, K, L;
-    int64_t Kpad;      // K rounded up to a multiple of BK
-    int64_t jc;        // rows of j per chunk (a multiple of BM)
+    int64_t Kpad;      // K rounded up to a multiple of 4 * SL
+    int64_t jc;        // rows of j per chunk (a multiple of RB)
     int nchunks;       // ceil(J / jc)
+    int nslices;       // ceil(K / SL)
+    int kgroups;       // ceil(nslices / 4): k-slices are handed out four per workgroup
     int tiles_n;       // ceil(L / 32)
+    int groups;        // gridDim.x / (kgroups * tiles_n): workgroups sharing the item list
 };
 
-template <typename T, int BM>
+template <typename T>
 struct MttkrpCfg {
     typedef Mfma<T> MF;
-    static constexpr int NT = 256, NW = 4, BN = 32;
+    static constexpr int NT = 256, NW = 4, BN = 32, RB = 32;
     static constexpr int VEC = 16 / (int)sizeof(T);
-    static constexpr int BK = 512 / (int)sizeof(T);
-    static constexpr int KV = VEC, KG = MF::KS * KV;
-    static constexpr int KG_PER_WAVE = BK / KG / NW;
-    static constexpr int MI = BM / MF::NB;                // j blocks (MFMA columns)
+    static constexpr int SL = 256 / (int)sizeof(T);       // k values per slice
+    static constexpr int KV = VEC, KG = MF::KS * KV, NKG = SL / KG;
+    static constexpr int MI = RB / MF::NB;                // j blocks (MFMA columns)
     static constexpr int LB = BN / MF::MB;                // l blocks (MFMA rows): 1 (f32) or 2 (f64)
     static constexpr int NSUM = LB * MF::NACC;            // running sums per lane
-    static constexpr int ROWS = BM + BN;                  // slab rows: B tile, then Dt tile
-    static constexpr int LD_S = BK + VEC;                 // LDS row stride (elements): +16 B
-    static constexpr int LDS_BYTES = ROWS * LD_S * (int)sizeof(T);
-    static constexpr int VECS = ROWS * (BK / VEC);
-    static constexpr int PER_T = VECS / NT;
-    static constexpr int B_PER_T = BM * (BK / VEC) / NT;  // of which from B
-    static_assert(BM % MF::NB == 0 && BK % (KG * NW) == 0 && LB <= 2, "tile shape");
-    static_assert(VECS % NT == 0 && (BM * (BK / VEC)) % NT == 0, "slab vectors must divide over threads");
-    static_assert(NT * NSUM * (int)sizeof(T) <= LDS_BYTES, "final reduction fits the slab buffer");
+    static constexpr int CPR = SL / VEC;                  // 16-byte pieces per patch row (16)
+    static constexpr int RPI = 64 / CPR;                  // rows covered by one wavefront load (4)
+    static constexpr int PER_T = RB / RPI;                // loads per lane per block (8)
+    static constexpr int LDW = SL + VEC;                  // patch row stride (elements): +16 B
+    static constexpr int PATCH = RB * LDW;                // elements per wavefront patch
+    static constexpr int LDS_BYTES = NW * PATCH * (int)sizeof(T);
+    static_assert(SL % KG == 0 && RB % MF::NB == 0 && LB <= 2 && 64 % CPR == 0, "tile shape");
 };
 
 // Dt(l, k) = D(k, l), zero outside K x L.
@@ -88,143 +94,182 @@ __device__ __forceinline__ int mttkrp_l_of(int v, int lb, int lane) {
     return 2 * Mfma<T>::out_row(v, lane) + lb;
 }
 
-// GUARD = false: every tile and slab of B is full and 16-byte aligned (J % BM == 0,
-// K % BK == 0, L % 32 == 0, aligned bases) - vector loads only.  GUARD = true: any
-// shape and alignment, element loads with bounds checks and zero fill.
-template <typename T, int BM, bool GUARD>
+// GUARD = false: every row block and k-slice of B is full and 16-byte aligned
+// (J % 32 == 0, K % (4*SL) == 0, L % 32 == 0, aligned bases) - vector loads only.
+// GUARD = true: any shape and alignment, element loads with bounds checks, zero fill.
+template <typename T, bool GUARD>
 __global__ void __launch_bounds__(256, GUARD ? 1 : (sizeof(T) == 4 ? 3 : 2))
 mttkrp_kernel(const MttkrpArgs<T> args) {
-    typedef MttkrpCfg<T, BM> Cfg;
+    typedef MttkrpCfg<T> Cfg;
     typedef Mfma<T> MF;
     typedef typename VecOf<T, Cfg::VEC>::type vec_t;
-    constexpr int VEC = Cfg::VEC, KV = Cfg::KV, KG = Cfg::KG, MI = Cfg::MI, LB = Cfg::LB;
-    constexpr int NT = Cfg::NT, BK = Cfg::BK, BN = Cfg::BN;
+    constexpr int VEC = Cfg::VEC, KV = Cfg::KV, KG = Cfg::KG, NKG = Cfg::NKG, MI = Cfg::MI, LB = Cfg::LB;
+    constexpr int SL = Cfg::SL, BN = Cfg::BN, RB = Cfg::RB;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    T *slab = reinterpret_cast<T *>(lds_raw);
+    T *lds = reinterpret_cast<T *>(lds_raw);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int li = lane % MF::MB, ls = lane / MF::MB;
+    T *patch = lds + wave * Cfg::PATCH;
 
-    const int tn = blockIdx.x % args.tiles_n;
-    const int64_t ic = blockIdx.x / args.tiles_n;          // i * nchunks + chunk
-    const int64_t i = ic / args.nchunks, chunk = ic % args.nchunks;
-    const int64_t j_begin = chunk * args.jc;
-    const int64_t j_end = (j_begin + args.jc < args.J) ? j_begin + args.jc : args.J;
+    int bid = blockIdx.x;
+    const int tn = bid % args.tiles_n;   bid /= args.tiles_n;
+    const int kgp = bid % args.kgroups;  bid /= args.kgroups;
+    const int group = bid;                                     // first item of this workgroup
+    const int nitems = (int)(args.I * args.nchunks);           // the host keeps this below 2^31
     const int64_t n0 = (int64_t)tn * BN;
     const int64_t J = args.J, K = args.K, L = args.L;
-    const T *Bi = args.B + i * J * K;
-    const T *Dt = args.Dt + n0 * args.Kpad;
+    const int slice = kgp * Cfg::NW + wave;
+    const int64_t k0 = (int64_t)slice * SL;                    // this wavefront's k-slice
+    if (k0 >= K) return;                  // wavefront-uniform; no barrier anywhere below
 
-    const int nks = (int)((K + BK - 1) / BK);
-    const int ntiles = (int)((j_end - j_begin + BM - 1) / BM);
+    // Dt operand of this slice, kept in registers: d[lb][g] holds k = k0 + g*KG + ls*KV + (0..KV-1)
+    vec_t d[LB][NKG];
+#pragma unroll
+    for (int lb = 0; lb < LB; ++lb)
+#pragma unroll
+        for (int g = 0; g < NKG; ++g)
+            d[lb][g] = *reinterpret_cast<const vec_t *>(
+                args.Dt + (n0 + (LB == 1 ? li : 2 * li + lb)) * args.Kpad + k0 + g * KG + ls * KV);
 
-    vec_t rs[Cfg::PER_T];
-
-    // slab (jt, ks): rows [0, BM) from B(i, j0.., k0..), rows [BM, BM+32) from Dt(.., k0..)
-    auto load_global = [&](int jt, int ks) {
-        const int64_t j0 = j_begin + (int64_t)jt * BM, k0 = (int64_t)ks * BK;
-#pragma unroll
-        for (int p = 0; p < Cfg::PER_T; ++p) {
-            const int v = tid + p * NT;
-            const int r = v / (BK / VEC), kv = v % (BK / VEC);
-            if (p < Cfg::B_PER_T) {
-                if constexpr (!GUARD) {
-                    rs[p] = __builtin_nontemporal_load(
-                        reinterpret_cast<const vec_t *>(Bi + (j0 + r) * K + k0 + kv * VEC));
-                } else {
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) {
-                        const int64_t j = j0 + r, k = k0 + kv * VEC + e;
-                        rs[p][e] = (j < J && k < K) ? Bi[j * K + k] : T(0);
-                    }
-                }
-            } else {
-                rs[p] = *reinterpret_cast<const vec_t *>(Dt + (int64_t)(r - BM) * args.Kpad + k0 + kv * VEC);
-            }
-        }
-    };
-
-    auto store_lds = [&]() {
-#pragma unroll
-        for (int p = 0; p < Cfg::PER_T; ++p) {
-            const int v = tid + p * NT;
-            const int r = v / (BK / VEC), kv = v % (BK / VEC);
-            *reinterpret_cast<vec_t *>(slab + r * Cfg::LD_S + kv * VEC) = rs[p];
-        }
-    };
-
-    typename MF::acc_t acc[LB][MI];
-    auto zero_acc = [&]() {
-#pragma unroll
-        for (int lb = 0; lb < LB; ++lb)
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int v = 0; v < MF::NACC; ++v) acc[lb][mi][v] = T(0);
-    };
-    zero_acc();
     T lsum[LB][MF::NACC];                 // running sum for l = mttkrp_l_of(v, lb, lane)
 #pragma unroll
     for (int lb = 0; lb < LB; ++lb)
 #pragma unroll
         for (int v = 0; v < MF::NACC; ++v) lsum[lb][v] = T(0);
 
-    // this wavefront's quarter of the slab's k range; lane (li, ls) reads k-slot ls
-    const int koff = wave * Cfg::KG_PER_WAVE * KG + ls * KV;
-    const T *b_rd = slab + li * Cfg::LD_S + koff;                               // B rows (j)
-    const T *d_rd = slab + (BM + (LB == 1 ? li : 2 * li)) * Cfg::LD_S + koff;   // Dt rows (l)
-
-    auto compute = [&]() {
+    vec_t rs[Cfg::PER_T];
+    const int prow = lane / Cfg::CPR, pcol = (lane % Cfg::CPR) * VEC;
+    // Per-lane byte offsets inside a row block; the block base is wavefront-uniform.  The host
+    // sends shapes whose block spans exceed 32-bit offsets to the guarded kernel.
+    uint32_t boff[Cfg::PER_T];
 #pragma unroll
-        for (int g = 0; g < Cfg::KG_PER_WAVE; ++g) {
-            vec_t b[MI], d[LB];
+    for (int p = 0; p < Cfg::PER_T; ++p)
+        boff[p] = (uint32_t)(((int64_t)(prow + p * Cfg::RPI) * K + pcol) * (int64_t)sizeof(T));
+    uint32_t coff[MI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+        coff[mi] = (uint32_t)(((int64_t)(mi * MF::NB + li) * L + (sizeof(T) == 4 ? 4 * ls : 2 * ls)) *
+                              (int64_t)sizeof(T));
+
+    // An item is (i, chunk): rows [jb, je) of slice i.  Its first-row pointers are uniform.
+    struct Item { const char *b; const char *c; int64_t jb; int nrb; };
+    auto open_item = [&](int it) {
+        Item x;
+        const int i = it / args.nchunks, ch = it - i * args.nchunks;
+        x.jb = (int64_t)ch * args.jc;
+        const int64_t je = (x.jb + args.jc < J) ? x.jb + args.jc : J;
+        x.nrb = (int)((je - x.jb + RB - 1) / RB);
+        x.b = reinterpret_cast<const char *>(args.B + ((int64_t)i * J + x.jb) * K + k0);
+        x.c = reinterpret_cast<const char *>(args.C + x.jb * L + n0);
+        return x;
+    };
+    auto load_rows = [&](const Item &x, int rb) {
+        if constexpr (!GUARD) {
+            const char *base = x.b + (int64_t)rb * RB * K * (int64_t)sizeof(T);
+#pragma unroll
+            for (int p = 0; p < Cfg::PER_T; ++p)
+                rs[p] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(base + boff[p]));
+        } else {
+            const T *base = reinterpret_cast<const T *>(x.b) - k0;
+#pragma unroll
+            for (int p = 0; p < Cfg::PER_T; ++p) {
+                const int64_t jr = (int64_t)rb * RB + prow + p * Cfg::RPI;      // row within the item
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const int64_t k = k0 + pcol + e;
+                    rs[p][e] = (x.jb + jr < J && k < K) ? base[jr * K + k] : T(0);
+                }
+            }
+        }
+    };
+
+    int item = group;
+    if (item >= nitems) return;
+    Item cur = open_item(item);
+    int rb = 0;
+    load_rows(cur, 0);
+    while (true) {
+        // what comes after this block: the item's next block, or the first block of the next item
+        const bool last_rb = (rb + 1 == cur.nrb);
+        const int next_item = last_rb ? item + args.groups : item;
+        const bool more = next_item < nitems;
+        Item nxt = cur;
+        int next_rb = rb + 1;
+        if (last_rb) {
+            next_rb = 0;
+            if (more) nxt = open_item(next_item);
+        }
+
+        // registers -> private patch (row-major, k contiguous)
+#pragma unroll
+        for (int p = 0; p < Cfg::PER_T; ++p)
+            *reinterpret_cast<vec_t *>(patch + (prow + p * Cfg::RPI) * Cfg::LDW + pcol) = rs[p];
+
+        // factor values for this block, requested before the next block's B loads so
+        // that waiting for them does not wait for those loads
+        vec_t c[MI][4];
+        if constexpr (!GUARD) {
+            const char *cb = cur.c + (int64_t)rb * RB * L * (int64_t)sizeof(T);
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
-                b[mi] = *reinterpret_cast<const vec_t *>(b_rd + mi * MF::NB * Cfg::LD_S + g * KG);
 #pragma unroll
-            for (int lb = 0; lb < LB; ++lb)
-                d[lb] = *reinterpret_cast<const vec_t *>(d_rd + lb * Cfg::LD_S + g * KG);
+                for (int q = 0; q < 4; ++q)
+                    c[mi][q] = *reinterpret_cast<const vec_t *>(cb + coff[mi] + q * 8 * (int)sizeof(T));
+        }
+        // past the end: a redundant reload of the current block, never out of bounds
+        if (more) load_rows(nxt, next_rb); else load_rows(cur, rb);
+
+        // the patch is written and read by this wavefront only
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        typename MF::acc_t acc[LB][MI];
+#pragma unroll
+        for (int lb = 0; lb < LB; ++lb)
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int v = 0; v < MF::NACC; ++v) acc[lb][mi][v] = T(0);
+#pragma unroll
+        for (int g = 0; g < NKG; ++g) {
+            vec_t b[MI];
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+                b[mi] = *reinterpret_cast<const vec_t *>(patch + (mi * MF::NB + li) * Cfg::LDW
+                                                         + g * KG + ls * KV);
 #pragma unroll
             for (int t = 0; t < KV; ++t)
 #pragma unroll
                 for (int lb = 0; lb < LB; ++lb)
 #pragma unroll
                     for (int mi = 0; mi < MI; ++mi)
-                        acc[lb][mi] = MF::run(d[lb][t], b[mi][t], acc[lb][mi]);
+                        acc[lb][mi] = MF::run(d[lb][g][t], b[mi][t], acc[lb][mi]);
         }
-    };
+        // all reads of the patch are done before the next block overwrites it
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-    // Scale this tile's Tt(l, j) by C(j, l) and add into the lane's running sums.
-    auto fold_tile = [&](int jt) {
-        const int64_t j0 = j_begin + (int64_t)jt * BM;
+        // scale Tt(l, j) by C(j, l) and add into the lane's running sums
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
-            const int64_t j = j0 + mi * MF::NB + li;
             if constexpr (!GUARD) {
-                const T *crow = args.C + j * L + n0;
-                vec_t c[4];
-                if constexpr (sizeof(T) == 4) {
-                    // lane owns l = 8q + 4*ls + r: four neighbours per q
 #pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        c[q] = *reinterpret_cast<const vec_t *>(crow + 8 * q + 4 * ls);
+                for (int v = 0; v < MF::NACC; ++v)
 #pragma unroll
-                    for (int v = 0; v < MF::NACC; ++v)
-                        lsum[0][v] = fma_t(acc[0][mi][v], c[v >> 2][v & 3], lsum[0][v]);
-                } else {
-                    // lane owns l = 2*(4v + ls) + lb: two neighbours per v
-#pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        c[v] = *reinterpret_cast<const vec_t *>(crow + 2 * (4 * v + ls));
-#pragma unroll
-                    for (int v = 0; v < MF::NACC; ++v)
-#pragma unroll
-                        for (int lb = 0; lb < LB; ++lb)
-                            lsum[lb][v] = fma_t(acc[lb][mi][v], c[v][lb], lsum[lb][v]);
-                }
+                    for (int lb = 0; lb < LB; ++lb) {
+                        // binary32: l = 8q + 4*ls + r, v = 4q + r;  binary64: l = 2*(4v + ls) + lb
+                        T f;
+                        if constexpr (sizeof(T) == 4) f = c[mi][v >> 2][v & 3];
+                        else f = c[mi][v][lb];
+                        lsum[lb][v] = fma_t(acc[lb][mi][v], f, lsum[lb][v]);
+                    }
             } else {
+                const int64_t j = cur.jb + (int64_t)rb * RB + mi * MF::NB + li;
 #pragma unroll
                 for (int lb = 0; lb < LB; ++lb)
 #pragma unroll
@@ -235,56 +280,37 @@ mttkrp_kernel(const MttkrpArgs<T> args) {
                     }
             }
         }
-        zero_acc();
-    };
 
-    int jt = 0, ks = 0;
-    if (ntiles > 0 && nks > 0) load_global(0, 0);
-    while (jt < ntiles && nks > 0) {
-        int njt = jt, nks_next = ks + 1;
-        if (nks_next == nks) { nks_next = 0; njt = jt + 1; }
-        const bool more = njt < ntiles;
-        __syncthreads();                 // everyone is done reading the previous slab
-        store_lds();
-        // past the end: a redundant reload of the last slab, never out of bounds
-        load_global(more ? njt : jt, more ? nks_next : ks);
-        __syncthreads();                 // slab visible
-        compute();
-        if (nks_next == 0) fold_tile(jt);
-        jt = njt;
-        ks = nks_next;
-    }
-
-    // lane sums -> LDS -> one sum per l, in a fixed order (two stages)
-    __syncthreads();
-    T *red = slab;                        // [NSUM][256]
+        if (last_rb) {
+            // Item done: add the lanes that own the same l (same k-slot ls, all li) in a fixed
+            // order and write this wavefront's partial row.
+            T *prow_out = args.partial + ((int64_t)item * args.nslices + slice) * L + n0;
 #pragma unroll
-    for (int lb = 0; lb < LB; ++lb)
+            for (int lb = 0; lb < LB; ++lb)
 #pragma unroll
-        for (int v = 0; v < MF::NACC; ++v) red[(lb * MF::NACC + v) * NT + tid] = lsum[lb][v];
-    __syncthreads();
-    // thread (part, l): l = tid % 32 is owned by the lanes of one k-slot, in one element (lb, v)
-    const int l = tid & 31, part = tid >> 5;                  // 8 parts
-    int ls_l, v_l, lb_l;
-    if (sizeof(T) == 4) { ls_l = (l >> 2) & 1; v_l = 4 * (l >> 3) + (l & 3); lb_l = 0; }
-    else { lb_l = l & 1; ls_l = (l >> 1) & 3; v_l = l >> 3; }
-    const T *src = red + (lb_l * MF::NACC + v_l) * NT;
-    // owners: wave w, lane ls_l*MB + x; each part adds a fixed eighth of them, in order
-    constexpr int OWNERS = 4 * MF::MB, PER_PART = OWNERS / 8;
-    T s = T(0);
+                for (int v = 0; v < MF::NACC; ++v) {
+                    T s = sum16(lsum[lb][v]);
+                    if (MF::MB == 32) s += __shfl_xor(s, 16);
+                    lsum[lb][v] = s;
+                }
+            if (li == 0) {
 #pragma unroll
-    for (int o = 0; o < PER_PART; ++o) {
-        const int idx = part * PER_PART + o;
-        s += src[(idx / MF::MB) * 64 + ls_l * MF::MB + (idx % MF::MB)];
-    }
-    __syncthreads();
-    red[tid] = s;                                              // [8 parts][32]
-    __syncthreads();
-    if (tid < BN && n0 + tid < L) {
-        T tot = T(0);
+                for (int lb = 0; lb < LB; ++lb)
 #pragma unroll
-        for (int p = 0; p < 8; ++p) tot += red[p * 32 + tid];
-        args.partial[ic * L + n0 + tid] = tot;
+                    for (int v = 0; v < MF::NACC; ++v) {
+                        const int l = mttkrp_l_of<T>(v, lb, lane);
+                        if (!GUARD || n0 + l < L) prow_out[l] = lsum[lb][v];
+                    }
+            }
+#pragma unroll
+            for (int lb = 0; lb < LB; ++lb)
+#pragma unroll
+                for (int v = 0; v < MF::NACC; ++v) lsum[lb][v] = T(0);
+            if (!more) break;
+        }
+        item = next_item;
+        cur = nxt;
+        rb = next_rb;
     }
 }
 
