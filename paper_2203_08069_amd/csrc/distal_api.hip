@@ -107,29 +107,24 @@ int check_dtype(int dt) { return (dt == DISTAL_F32 || dt == DISTAL_F64) ? DISTAL
 size_t elem_size(int dt) { return dt == DISTAL_F64 ? 8 : 4; }
 
 // ---- MTTKRP ---------------------------------------------------------------
-constexpr int64_t kMttkrpBlocksPerItem = 8;   // 32-row blocks of j per work item
-
 // Work decomposition and workspace layout, a function of the shape only (never of the
 // device), so the summation order is reproducible.
 // Workspace: [Dt: 32*tiles_n rows x Kpad][partial rows: I*nchunks*nslices x L, unless that is I]
 struct MttkrpPlan {
-    int64_t jc, nchunks, nslices, kgroups, tiles_n, kpad, dt_elems, partial_rows, partial_elems;
+    int64_t nchunks, nslices, kgroups, tiles_n, kpad, dt_elems, partial_rows, partial_elems;
     bool ok;
 };
 
 MttkrpPlan mttkrp_plan(int dt, int64_t I, int64_t J, int64_t K, int64_t L) {
     MttkrpPlan p{};
     const int64_t sl = 256 / (int64_t)(dt == DISTAL_F64 ? 8 : 4);       // k values per wavefront slice
-    const int64_t rb = 32;
+    const int64_t cj = MttkrpCfg<float>::CJ;                              // rows of j per chunk
     p.nslices = (K + sl - 1) / sl;
     if (p.nslices < 1) p.nslices = 1;
     p.kgroups = (p.nslices + 3) / 4;
     p.kpad = p.kgroups * 4 * sl;
     p.tiles_n = (L + 31) / 32;
-    const int64_t blocks_j = (J + rb - 1) / rb;
-    const int64_t bpc = blocks_j < kMttkrpBlocksPerItem ? (blocks_j > 0 ? blocks_j : 1) : kMttkrpBlocksPerItem;
-    p.jc = bpc * rb;
-    p.nchunks = J > 0 ? (J + p.jc - 1) / p.jc : 1;
+    p.nchunks = J > 0 ? (J + cj - 1) / cj : 1;
     int64_t t;
     p.ok = mul_ok(p.tiles_n * 32, p.kpad, &p.dt_elems) && mul_ok(I, p.nchunks, &t) &&
            mul_ok(t, p.nslices, &p.partial_rows) && mul_ok(p.partial_rows, L, &p.partial_elems) &&
@@ -156,21 +151,22 @@ int resident_blocks_per_cu(Kern kern, int lds_bytes, std::atomic<int> (&cache)[k
 }
 
 template <typename T, bool GUARD>
-int launch_mttkrp(MttkrpArgs<T> &a, int64_t nitems, hipStream_t stream) {
+int launch_mttkrp(MttkrpArgs<T> &a, hipStream_t stream) {
     typedef MttkrpCfg<T> Cfg;
     auto kern = mttkrp_kernel<T, GUARD>;
     static std::atomic<bool> done[kMaxDevices];
     static std::atomic<int> occ[kMaxDevices];
     if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
-    // persistent grid: as many workgroups as stay resident, shared out over the k-groups
+    // persistent grid: as many workgroups as stay resident, shared out over (chunk, k-group, tile)
     const int64_t resident = (int64_t)resident_blocks_per_cu(kern, Cfg::LDS_BYTES, occ) * compute_units();
-    const int64_t lanes = (int64_t)a.kgroups * a.tiles_n;
-    int64_t groups = resident / lanes;
-    if (groups < 1) groups = 1;
-    if (groups > nitems) groups = nitems;
+    int64_t lanes;
+    if (!mul_ok((int64_t)a.kgroups * a.tiles_n, (int64_t)a.nchunks, &lanes)) return DISTAL_ERR_SHAPE;
+    int64_t igroups = resident / lanes;
+    if (igroups < 1) igroups = 1;
+    if (igroups > a.I) igroups = a.I;
     int64_t nblocks;
-    if (!mul_ok(groups, lanes, &nblocks) || nblocks > std::numeric_limits<int>::max()) return DISTAL_ERR_SHAPE;
-    a.groups = (int)groups;
+    if (!mul_ok(igroups, lanes, &nblocks) || nblocks > std::numeric_limits<int>::max()) return DISTAL_ERR_SHAPE;
+    a.igroups = (int)igroups;
     hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
     return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
 }
@@ -182,9 +178,9 @@ int mttkrp_t(int64_t I, int64_t J, int64_t K, int64_t L, const T *B, const T *C,
     if (I == 0 || L == 0) return DISTAL_OK;
     if (J == 0 || K == 0) return launch_fill<T>(A, I, L, L, stream);
     const MttkrpPlan plan = mttkrp_plan(sizeof(T) == 8 ? DISTAL_F64 : DISTAL_F32, I, J, K, L);
-    if (!plan.ok || plan.kgroups * plan.tiles_n > std::numeric_limits<int>::max() / 2 ||
-        plan.nslices > std::numeric_limits<int>::max() / 8 ||
-        plan.nchunks * plan.nslices > std::numeric_limits<int>::max())
+    const int64_t imax = std::numeric_limits<int>::max();
+    if (!plan.ok || plan.kgroups > imax / 8 || plan.tiles_n > imax / 8 || plan.nchunks > imax / 8 ||
+        plan.nchunks * plan.nslices > imax)
         return DISTAL_ERR_SHAPE;
     T *dt_buf = static_cast<T *>(workspace);
     T *partial = dt_buf + plan.dt_elems;
@@ -200,21 +196,17 @@ int mttkrp_t(int64_t I, int64_t J, int64_t K, int64_t L, const T *B, const T *C,
     a.B = B; a.C = C; a.Dt = dt_buf;
     a.I = I; a.J = J; a.K = K; a.L = L;
     a.Kpad = plan.kpad;
-    a.jc = plan.jc;
     a.nchunks = (int)plan.nchunks;
     a.nslices = (int)plan.nslices;
     a.kgroups = (int)plan.kgroups;
     a.tiles_n = (int)plan.tiles_n;
     a.partial = per_i == 1 ? A : partial;
-    const int64_t nitems = I * plan.nchunks;
-    if (nitems > std::numeric_limits<int>::max()) return DISTAL_ERR_SHAPE;
     // the unguarded kernel addresses a 32-row block with 32-bit byte offsets
     const bool full = aligned16(B) && aligned16(C) && J % Cfg::RB == 0 && K % Cfg::SL == 0 &&
-                      L % Cfg::BN == 0 && K <= (1 << 22) && L <= (1 << 22);
-    const int rc = full ? launch_mttkrp<T, false>(a, nitems, stream) : launch_mttkrp<T, true>(a, nitems, stream);
+                      L % Cfg::BN == 0 && K <= (1 << 22);
+    const int rc = full ? launch_mttkrp<T, false>(a, stream) : launch_mttkrp<T, true>(a, stream);
     if (rc != DISTAL_OK || per_i == 1) return rc;
-    int64_t blocks = (I * L + 255) / 256;
-    if (blocks > 4096) blocks = 4096;
+    const int64_t blocks = I < 4096 ? I : 4096;
     hipLaunchKernelGGL(mttkrp_reduce_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream,
                        static_cast<const T *>(partial), A, I, L, (int)per_i);
     return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;

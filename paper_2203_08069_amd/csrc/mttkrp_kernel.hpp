@@ -2,31 +2,35 @@
 //
 // The paper's leaf casts MTTKRP to matrix multiplications followed by an
 // element-wise reduction (evaluation section, leaf kernels).  Here both happen
-// in one pass over B, which is read from HBM exactly once, and every wavefront
-// runs on its own - there is no workgroup barrier in the streaming loop:
+// in one pass over B, which is read from HBM exactly once.  After a one-time
+// set-up every wavefront is an independent stream: there is no workgroup barrier
+// in the streaming loop, and the only global loads in it are fully coalesced
+// 16-byte loads of B (the address unit, not HBM or the matrix pipe, is the first
+// thing lane-scattered loads exhaust here).
 //
 //   * A small pre-kernel writes D transposed and zero-padded (Dt: 32*tiles_n rows
 //     of Kpad values), so that k is the contiguous index of BOTH MFMA operands.
-//   * The grid is persistent (a few workgroups per CU).  A wavefront owns ONE k-slice
-//     of SL = 256 bytes for its whole life and walks a strided list of work items,
-//     an item being one i and a chunk of j.  The Dt values of its slice (32 l x SL
-//     k) are loaded into registers once, so D costs no further traffic.  The four
-//     wavefronts of a workgroup take four neighbouring slices of the same rows
-//     (1 KiB contiguous per row).
-//   * The wavefront walks its chunk in blocks of RB = 32 rows.  A block's RB x SL
-//     piece of B goes global -> registers (coalesced 16-byte loads, the next
-//     block's loads are in flight during the multiply) -> a wavefront-private LDS
-//     patch -> back in MFMA operand layout.  Only the wavefront that wrote the
-//     patch reads it, so ordering inside the wavefront suffices.
+//   * The grid is persistent.  A workgroup is pinned to one chunk of j (CJ rows),
+//     one group of four k-slices and one column tile, and walks a strided list of
+//     i.  The factor rows C(chunk, tile) are copied to LDS once, at set-up.
+//   * A wavefront owns ONE k-slice of SL = 256 bytes for its whole life.  The Dt
+//     values of its slice (32 l x SL k) are loaded into registers once, so D costs
+//     no further traffic.  The four wavefronts of a workgroup take neighbouring
+//     slices of the same rows (1 KiB contiguous per row).
+//   * The wavefront walks (i, block of RB = 32 rows).  A block's RB x SL piece of B
+//     goes global -> registers (the next block's loads are in flight during the
+//     multiply) -> a wavefront-private LDS patch -> back in MFMA operand layout.
+//     Only the wavefront that wrote the patch reads it, so ordering inside the
+//     wavefront suffices.
 //   * MFMA forms the TRANSPOSED partial product Tt(l,j) = sum_{k in slice} Dt(l,k)
 //     B(j,k): a lane owns one j and several l, so the factor values C(j, l..) it
-//     needs are contiguous.  The sums over j and over k-slices are both linear:
-//     after every block the lane scales its accumulators by C(j,l) and adds them
-//     to running sums, one per owned l.
-//   * At the end of an item the lanes that own the same l are added with DPP
+//     needs are neighbours in the LDS copy.  The sums over j and over k-slices are
+//     both linear: after every block the lane scales its accumulators by C(j,l) and
+//     adds them to running sums, one per owned l.
+//   * At the end of an (i, chunk) the lanes that own the same l are added with DPP
 //     rotations in a fixed order and the wavefront writes its own partial row of 32
-//     values to the workspace; a last tiny kernel adds the partial rows of each i in
-//     order.  Nothing is atomic and no sum depends on the grid size: results are
+//     values to the workspace; a last small kernel adds the partial rows of each i
+//     in order.  Nothing is atomic and no sum depends on the grid size: results are
 //     bitwise reproducible.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -42,35 +46,36 @@ struct MttkrpArgs {
     const T *B;        // I x J x K
     const T *C;        // J x L
     const T *Dt;       // (32 * tiles_n) x Kpad, transposed zero-padded D
-    T *partial;        // (I * nchunks * nslices) x L: row (item * nslices + slice); the output
-                       // itself when nchunks * nslices == 1
+    T *partial;        // (I * nchunks * nslices) x L: row ((i * nchunks + chunk) * nslices + slice);
+                       // the output itself when nchunks * nslices == 1
     int64_t I, J, K, L;
     int64_t Kpad;      // K rounded up to a multiple of 4 * SL
-    int64_t jc;        // rows of j per chunk (a multiple of RB)
-    int nchunks;       // ceil(J / jc)
+    int nchunks;       // ceil(J / CJ)
     int nslices;       // ceil(K / SL)
     int kgroups;       // ceil(nslices / 4): k-slices are handed out four per workgroup
     int tiles_n;       // ceil(L / 32)
-    int groups;        // gridDim.x / (kgroups * tiles_n): workgroups sharing the item list
+    int igroups;       // gridDim.x / (tiles_n * kgroups * nchunks): workgroups sharing the list of i
 };
 
 template <typename T>
 struct MttkrpCfg {
     typedef Mfma<T> MF;
     static constexpr int NT = 256, NW = 4, BN = 32, RB = 32;
+    static constexpr int CJ = 128;                        // rows of j per chunk
     static constexpr int VEC = 16 / (int)sizeof(T);
     static constexpr int SL = 256 / (int)sizeof(T);       // k values per slice
     static constexpr int KV = VEC, KG = MF::KS * KV, NKG = SL / KG;
     static constexpr int MI = RB / MF::NB;                // j blocks (MFMA columns)
     static constexpr int LB = BN / MF::MB;                // l blocks (MFMA rows): 1 (f32) or 2 (f64)
-    static constexpr int NSUM = LB * MF::NACC;            // running sums per lane
     static constexpr int CPR = SL / VEC;                  // 16-byte pieces per patch row (16)
     static constexpr int RPI = 64 / CPR;                  // rows covered by one wavefront load (4)
     static constexpr int PER_T = RB / RPI;                // loads per lane per block (8)
     static constexpr int LDW = SL + VEC;                  // patch row stride (elements): +16 B
     static constexpr int PATCH = RB * LDW;                // elements per wavefront patch
-    static constexpr int LDS_BYTES = NW * PATCH * (int)sizeof(T);
-    static_assert(SL % KG == 0 && RB % MF::NB == 0 && LB <= 2 && 64 % CPR == 0, "tile shape");
+    static constexpr int LDC = BN + VEC;                  // factor-copy row stride (elements): +16 B
+    static constexpr int C_ELEMS = CJ * LDC;
+    static constexpr int LDS_BYTES = (NW * PATCH + C_ELEMS) * (int)sizeof(T);
+    static_assert(SL % KG == 0 && RB % MF::NB == 0 && LB <= 2 && 64 % CPR == 0 && CJ % RB == 0, "tile shape");
 };
 
 // Dt(l, k) = D(k, l), zero outside K x L.
@@ -85,6 +90,32 @@ mttkrp_transpose_kernel(const T *__restrict__ D, T *__restrict__ Dt, int64_t K, 
     }
 }
 
+// A(i, l) = sum of the per_i partial rows of i, in row order.  One workgroup per i:
+// thread (r, l) adds rows r, r+8, ..., then the eight strands are added in order.
+template <typename T>
+__global__ void __launch_bounds__(256)
+mttkrp_reduce_kernel(const T *__restrict__ partial, T *__restrict__ A, int64_t I, int64_t L, int per_i) {
+    __shared__ T strand[8][32];
+    const int r = threadIdx.x >> 5, lx = threadIdx.x & 31;
+    for (int64_t i = blockIdx.x; i < I; i += gridDim.x) {
+        for (int64_t l0 = 0; l0 < L; l0 += 32) {
+            const int64_t l = l0 + lx;
+            T s = T(0);
+            if (l < L)
+                for (int t = r; t < per_i; t += 8) s += partial[(i * per_i + t) * L + l];
+            __syncthreads();
+            strand[r][lx] = s;
+            __syncthreads();
+            if (r == 0 && l < L) {
+                T tot = strand[0][lx];
+#pragma unroll
+                for (int q = 1; q < 8; ++q) tot += strand[q][lx];
+                A[i * L + l] = tot;
+            }
+        }
+    }
+}
+
 // l (0..31 within the column tile) of accumulator element v of l-block lb.  binary64
 // interleaves its two l-blocks (block lb owns l = 2*r + lb for MFMA row r), so that a
 // lane's two blocks own neighbouring l.
@@ -95,7 +126,7 @@ __device__ __forceinline__ int mttkrp_l_of(int v, int lb, int lane) {
 }
 
 // GUARD = false: every row block and k-slice of B is full and 16-byte aligned
-// (J % 32 == 0, K % (4*SL) == 0, L % 32 == 0, aligned bases) - vector loads only.
+// (J % 32 == 0, K % SL == 0, L % 32 == 0, aligned bases) - vector loads only.
 // GUARD = true: any shape and alignment, element loads with bounds checks, zero fill.
 template <typename T, bool GUARD>
 __global__ void __launch_bounds__(256, GUARD ? 1 : (sizeof(T) == 4 ? 3 : 2))
@@ -104,7 +135,7 @@ mttkrp_kernel(const MttkrpArgs<T> args) {
     typedef Mfma<T> MF;
     typedef typename VecOf<T, Cfg::VEC>::type vec_t;
     constexpr int VEC = Cfg::VEC, KV = Cfg::KV, KG = Cfg::KG, NKG = Cfg::NKG, MI = Cfg::MI, LB = Cfg::LB;
-    constexpr int SL = Cfg::SL, BN = Cfg::BN, RB = Cfg::RB;
+    constexpr int SL = Cfg::SL, BN = Cfg::BN, RB = Cfg::RB, CJ = Cfg::CJ;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     T *lds = reinterpret_cast<T *>(lds_raw);
@@ -113,17 +144,38 @@ mttkrp_kernel(const MttkrpArgs<T> args) {
     const int lane = tid & 63, wave = tid >> 6;
     const int li = lane % MF::MB, ls = lane / MF::MB;
     T *patch = lds + wave * Cfg::PATCH;
+    T *cfac = lds + Cfg::NW * Cfg::PATCH;          // C(chunk rows, tile columns), row stride LDC
 
     int bid = blockIdx.x;
-    const int tn = bid % args.tiles_n;   bid /= args.tiles_n;
-    const int kgp = bid % args.kgroups;  bid /= args.kgroups;
-    const int group = bid;                                     // first item of this workgroup
-    const int nitems = (int)(args.I * args.nchunks);           // the host keeps this below 2^31
+    const int tn = bid % args.tiles_n;    bid /= args.tiles_n;
+    const int kgp = bid % args.kgroups;   bid /= args.kgroups;
+    const int chunk = bid % args.nchunks; bid /= args.nchunks;
+    const int ig = bid;                                         // first i of this workgroup
     const int64_t n0 = (int64_t)tn * BN;
-    const int64_t J = args.J, K = args.K, L = args.L;
+    const int64_t I = args.I, J = args.J, K = args.K, L = args.L;
+    const int64_t jb = (int64_t)chunk * CJ;
+    const int64_t je = (jb + CJ < J) ? jb + CJ : J;
+    const int nrb = (int)((je - jb + RB - 1) / RB);
+
+    // set-up: factor rows of this chunk and tile -> LDS, zero outside J x L
+    for (int v = tid; v < CJ * (BN / VEC); v += Cfg::NT) {
+        const int r = v / (BN / VEC), cv = (v % (BN / VEC)) * VEC;
+        vec_t x;
+        if (!GUARD) {
+            x = vec_t(T(0));
+            if (jb + r < J) x = *reinterpret_cast<const vec_t *>(args.C + (jb + r) * L + n0 + cv);
+        } else {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e)
+                x[e] = (jb + r < J && n0 + cv + e < L) ? args.C[(jb + r) * L + n0 + cv + e] : T(0);
+        }
+        *reinterpret_cast<vec_t *>(cfac + r * Cfg::LDC + cv) = x;
+    }
+    __syncthreads();                       // the only barrier of this kernel
+
     const int slice = kgp * Cfg::NW + wave;
     const int64_t k0 = (int64_t)slice * SL;                    // this wavefront's k-slice
-    if (k0 >= K) return;                  // wavefront-uniform; no barrier anywhere below
+    if (k0 >= K || ig >= I) return;       // wavefront-uniform
 
     // Dt operand of this slice, kept in registers: d[lb][g] holds k = k0 + g*KG + ls*KV + (0..KV-1)
     vec_t d[LB][NKG];
@@ -148,79 +200,43 @@ mttkrp_kernel(const MttkrpArgs<T> args) {
 #pragma unroll
     for (int p = 0; p < Cfg::PER_T; ++p)
         boff[p] = (uint32_t)(((int64_t)(prow + p * Cfg::RPI) * K + pcol) * (int64_t)sizeof(T));
-    uint32_t coff[MI];
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-        coff[mi] = (uint32_t)(((int64_t)(mi * MF::NB + li) * L + (sizeof(T) == 4 ? 4 * ls : 2 * ls)) *
-                              (int64_t)sizeof(T));
 
-    // An item is (i, chunk): rows [jb, je) of slice i.  Its first-row pointers are uniform.
-    struct Item { const char *b; const char *c; int64_t jb; int nrb; };
-    auto open_item = [&](int it) {
-        Item x;
-        const int i = it / args.nchunks, ch = it - i * args.nchunks;
-        x.jb = (int64_t)ch * args.jc;
-        const int64_t je = (x.jb + args.jc < J) ? x.jb + args.jc : J;
-        x.nrb = (int)((je - x.jb + RB - 1) / RB);
-        x.b = reinterpret_cast<const char *>(args.B + ((int64_t)i * J + x.jb) * K + k0);
-        x.c = reinterpret_cast<const char *>(args.C + x.jb * L + n0);
-        return x;
-    };
-    auto load_rows = [&](const Item &x, int rb) {
+    // rows [jb + rb*RB, +RB) of slice i, k in [k0, k0 + SL) -> rs
+    auto load_rows = [&](int64_t i, int rb) {
+        const T *base = args.B + (i * J + jb + (int64_t)rb * RB) * K + k0;      // wavefront-uniform
         if constexpr (!GUARD) {
-            const char *base = x.b + (int64_t)rb * RB * K * (int64_t)sizeof(T);
 #pragma unroll
             for (int p = 0; p < Cfg::PER_T; ++p)
-                rs[p] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(base + boff[p]));
+                rs[p] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(
+                    reinterpret_cast<const char *>(base) + boff[p]));
         } else {
-            const T *base = reinterpret_cast<const T *>(x.b) - k0;
 #pragma unroll
             for (int p = 0; p < Cfg::PER_T; ++p) {
-                const int64_t jr = (int64_t)rb * RB + prow + p * Cfg::RPI;      // row within the item
+                const int64_t jr = prow + p * Cfg::RPI;                          // row within the block
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) {
-                    const int64_t k = k0 + pcol + e;
-                    rs[p][e] = (x.jb + jr < J && k < K) ? base[jr * K + k] : T(0);
-                }
+                for (int e = 0; e < VEC; ++e)
+                    rs[p][e] = (jb + (int64_t)rb * RB + jr < J && k0 + pcol + e < K)
+                                   ? base[jr * K + pcol + e] : T(0);
             }
         }
     };
 
-    int item = group;
-    if (item >= nitems) return;
-    Item cur = open_item(item);
+    int64_t i = ig;
     int rb = 0;
-    load_rows(cur, 0);
+    load_rows(i, 0);
     while (true) {
-        // what comes after this block: the item's next block, or the first block of the next item
-        const bool last_rb = (rb + 1 == cur.nrb);
-        const int next_item = last_rb ? item + args.groups : item;
-        const bool more = next_item < nitems;
-        Item nxt = cur;
-        int next_rb = rb + 1;
-        if (last_rb) {
-            next_rb = 0;
-            if (more) nxt = open_item(next_item);
-        }
+        // what comes after this block: the next block of this i, or the first block of the next i
+        const bool last_rb = (rb + 1 == nrb);
+        const int64_t next_i = last_rb ? i + args.igroups : i;
+        const int next_rb = last_rb ? 0 : rb + 1;
+        const bool more = next_i < I;
 
         // registers -> private patch (row-major, k contiguous)
 #pragma unroll
         for (int p = 0; p < Cfg::PER_T; ++p)
             *reinterpret_cast<vec_t *>(patch + (prow + p * Cfg::RPI) * Cfg::LDW + pcol) = rs[p];
-
-        // factor values for this block, requested before the next block's B loads so
-        // that waiting for them does not wait for those loads
-        vec_t c[MI][4];
-        if constexpr (!GUARD) {
-            const char *cb = cur.c + (int64_t)rb * RB * L * (int64_t)sizeof(T);
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    c[mi][q] = *reinterpret_cast<const vec_t *>(cb + coff[mi] + q * 8 * (int)sizeof(T));
-        }
         // past the end: a redundant reload of the current block, never out of bounds
-        if (more) load_rows(nxt, next_rb); else load_rows(cur, rb);
+        load_rows(more ? next_i : i, more ? next_rb : rb);
 
         // the patch is written and read by this wavefront only
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -254,37 +270,29 @@ mttkrp_kernel(const MttkrpArgs<T> args) {
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        // scale Tt(l, j) by C(j, l) and add into the lane's running sums
+        // scale Tt(l, j) by C(j, l) from the LDS copy and add into the lane's running sums
+        // binary32: l = 8q + 4*ls + r, v = 4q + r;  binary64: l = 2*(4v + ls) + lb
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
-            if constexpr (!GUARD) {
+            const T *crow = cfac + (rb * RB + mi * MF::NB + li) * Cfg::LDC + (sizeof(T) == 4 ? 4 * ls : 2 * ls);
+            vec_t c[4];
 #pragma unroll
-                for (int v = 0; v < MF::NACC; ++v)
+            for (int q = 0; q < 4; ++q) c[q] = *reinterpret_cast<const vec_t *>(crow + 8 * q);
 #pragma unroll
-                    for (int lb = 0; lb < LB; ++lb) {
-                        // binary32: l = 8q + 4*ls + r, v = 4q + r;  binary64: l = 2*(4v + ls) + lb
-                        T f;
-                        if constexpr (sizeof(T) == 4) f = c[mi][v >> 2][v & 3];
-                        else f = c[mi][v][lb];
-                        lsum[lb][v] = fma_t(acc[lb][mi][v], f, lsum[lb][v]);
-                    }
-            } else {
-                const int64_t j = cur.jb + (int64_t)rb * RB + mi * MF::NB + li;
+            for (int v = 0; v < MF::NACC; ++v)
 #pragma unroll
-                for (int lb = 0; lb < LB; ++lb)
-#pragma unroll
-                    for (int v = 0; v < MF::NACC; ++v) {
-                        const int64_t l = n0 + mttkrp_l_of<T>(v, lb, lane);
-                        const T f = (j < J && l < L) ? args.C[j * L + l] : T(0);
-                        lsum[lb][v] = fma_t(acc[lb][mi][v], f, lsum[lb][v]);
-                    }
-            }
+                for (int lb = 0; lb < LB; ++lb) {
+                    T f;
+                    if constexpr (sizeof(T) == 4) f = c[v >> 2][v & 3];
+                    else f = c[v][lb];
+                    lsum[lb][v] = fma_t(acc[lb][mi][v], f, lsum[lb][v]);
+                }
         }
 
         if (last_rb) {
-            // Item done: add the lanes that own the same l (same k-slot ls, all li) in a fixed
-            // order and write this wavefront's partial row.
-            T *prow_out = args.partial + ((int64_t)item * args.nslices + slice) * L + n0;
+            // (i, chunk) done: add the lanes that own the same l (same k-slot ls, all li) in a
+            // fixed order and write this wavefront's partial row.
+            T *prow_out = args.partial + ((i * args.nchunks + chunk) * args.nslices + slice) * L + n0;
 #pragma unroll
             for (int lb = 0; lb < LB; ++lb)
 #pragma unroll
@@ -308,8 +316,7 @@ mttkrp_kernel(const MttkrpArgs<T> args) {
                 for (int v = 0; v < MF::NACC; ++v) lsum[lb][v] = T(0);
             if (!more) break;
         }
-        item = next_item;
-        cur = nxt;
+        i = next_i;
         rb = next_rb;
     }
 }

@@ -211,17 +211,4 @@ fill_kernel(T *__restrict__ out, int64_t rows, int64_t cols, int64_t ld, T value
         out[(m / cols) * ld + (m % cols)] = value;
 }
 
-// Pass 2 of MTTKRP: A(i,l) = sum over the j-tiles' partial column sums, in tile order.
-template <typename T>
-__global__ void __launch_bounds__(256)
-mttkrp_reduce_kernel(const T *__restrict__ partial, T *__restrict__ A, int64_t I, int64_t L, int jtiles) {
-    const int64_t n = I * L;
-    for (int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x; m < n; m += (int64_t)gridDim.x * 256) {
-        const int64_t i = m / L, l = m % L;
-        T s = T(0);
-        for (int t = 0; t < jtiles; ++t) s += partial[(i * jtiles + t) * L + l];
-        A[m] = s;
-    }
-}
-
 }  // namespace distal
