@@ -51,9 +51,22 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+SETTLE_MS = 40.0   # the part's power management needs a few tens of ms of load to settle
+
+
 def time_launches(fn, steps, warmup, torch):
-    """K timed launches between synchronisations; also per-launch HIP-event durations."""
-    for _ in range(warmup):
+    """W warm-up launches, then K timed launches between synchronisations, with per-launch
+    HIP-event durations.  For launches much shorter than the settling time of the clocks
+    the warm-up is extended (never shortened) until it has covered SETTLE_MS of GPU time."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    fn()
+    torch.cuda.synchronize()
+    e0.record()
+    fn()
+    e1.record()
+    torch.cuda.synchronize()
+    est = max(e0.elapsed_time(e1), 1e-3)
+    for _ in range(max(warmup - 2, 0, int(SETTLE_MS / est) + 1 - 2)):
         fn()
     torch.cuda.synchronize()
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
@@ -76,6 +89,9 @@ def main():
     ap.add_argument("--rows", default="all",
                     help="comma list of gemm_f64,gemm_f32,ttm,mttkrp,ttv,innerprod (gemm_f64 always runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB read + 1 GiB write elementwise kernel (torch.add), the known-size "
+                         "reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU; every figure is a single-MI355X figure. "
@@ -102,6 +118,13 @@ def main():
         oracle.build()
         cores = oracle.max_threads()
     rows = []
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     def tdt(np_dt):
         return torch.float64 if np.dtype(np_dt) == np.float64 else torch.float32

@@ -1,0 +1,166 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+The oracle cannot redo a 2^30-element contraction in seconds, so each case checks
+outputs the oracle CAN compute one by one - sampled rows, fibres, slices or index
+ranges, regenerated on the host from the same pure input function - plus a
+property that holds for the whole output."""
+import numpy as np
+import pytest
+
+from paper_2203_08069_amd import inputs
+
+import _util as U
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2203_08069_amd import binding
+    binding.load_library()
+    return binding
+
+
+def devgen(seed, ordinal, shape, dtype):
+    from paper_2203_08069_amd.device_inputs import device_tensor
+    return device_tensor(seed, ordinal, shape, dtype, device="cuda:0")
+
+
+def host_rows(seed, ordinal, row_len, rows, dtype):
+    """Rows of a 2-D (or flattened) tensor regenerated on the host: element n = row*row_len + col."""
+    return np.stack([inputs.values(seed, ordinal, int(r) * row_len, row_len, dtype) for r in rows])
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_gemm_8192(lib, oracle, dtype):
+    """configs[1]: M = N = K = 8192, uniform[-1,1) from seed 1, C zero-initialised."""
+    import torch
+    n = 8192
+    A, B = devgen(1, 0, (n, n), dtype), devgen(1, 1, (n, n), dtype)
+    C = torch.zeros((n, n), dtype=A.dtype, device="cuda:0")
+    lib.distal_gemm(A, B, C)
+    rng = np.random.default_rng(7)
+    rows = np.sort(rng.choice(n, 48, replace=False))
+    cols = np.sort(rng.choice(n, 64, replace=False))
+    hA = host_rows(1, 0, n, rows, dtype)                                   # 48 x K
+    hB = inputs.tensor(1, 1, (n, n), dtype, threads=8)
+    ref = oracle.gemm(hA, np.ascontiguousarray(hB[:, cols]))               # 48 x 64 sampled outputs
+    got = C[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy()
+    scale = np.sqrt(n / 3.0)                                               # typical |C| entry
+    err = np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), scale)
+    assert err <= U.tol(dtype, n), err
+    # whole output: Freivalds' check C x = A (B x) with x = +-1, evaluated in binary64 on the host
+    x = rng.integers(0, 2, n).astype(np.float64) * 2 - 1
+    hC = C.cpu().numpy().astype(np.float64)
+    bx = hB.astype(np.float64) @ x
+    del hB
+    hAfull = inputs.tensor(1, 0, (n, n), dtype, threads=8).astype(np.float64)
+    want = hAfull @ bx
+    gotv = hC @ x
+    denom = np.max(np.abs(want))
+    assert np.max(np.abs(gotv - want)) / denom <= (1e-11 if dtype == np.float64 else 1e-4)
+    # accumulate on top: C += A B doubles every entry exactly (power-of-two scaling)
+    lib.distal_gemm(A, B, C, accumulate=True)
+    assert np.array_equal(C[:64].cpu().numpy(), (2 * hC[:64]).astype(dtype))
+
+
+@pytest.fixture(scope="module")
+def cfg3_B():
+    return devgen(2, 0, (1024, 1024, 1024), np.float32)
+
+
+def test_ttv_1024(lib, oracle, cfg3_B):
+    """configs[2]: A(i,j) = sum_k B(i,j,k) c(k), B 1024^3 fp32, seed 2."""
+    import torch
+    I = J = K = 1024
+    c = devgen(2, 1, (K,), np.float32)
+    A = torch.full((I, J), float("nan"), dtype=torch.float32, device="cuda:0")
+    lib.distal_ttv(cfg3_B, c, A)
+    rng = np.random.default_rng(8)
+    rows = np.sort(rng.choice(I * J, 2048, replace=False))
+    hB = host_rows(2, 0, K, rows, np.float32).reshape(1, -1, K)
+    hc = inputs.values(2, 1, 0, K, np.float32)
+    ref = oracle.ttv(hB, hc)[0]
+    got = A.view(-1)[torch.from_numpy(rows).cuda()].cpu().numpy()
+    U.assert_close(got, ref, np.float32, K)
+    assert bool(torch.isfinite(A).all())
+    # all-ones vector: every output is the plain k-sum; compare with the sampled rows
+    lib.distal_ttv(cfg3_B, torch.ones(K, dtype=torch.float32, device="cuda:0"), A)
+    got1 = A.view(-1)[torch.from_numpy(rows).cuda()].cpu().numpy()
+    U.assert_close(got1, hB[0].astype(np.float64).sum(axis=1), np.float32, K)
+
+
+def test_innerprod_1024(lib, oracle, cfg3_B):
+    """configs[2]: a = sum B .* C over 2^30 elements; binary64 accumulation on both sides."""
+    import torch
+    n = 1 << 30
+    C = devgen(2, 2, (1024, 1024, 1024), np.float32)
+    a = torch.empty(1, dtype=torch.float32, device="cuda:0")
+    lib.distal_innerprod(cfg3_B, C, a)
+    full = float(a.item())
+    # the sum splits over contiguous index ranges: GPU pieces add up to the GPU total ...
+    pieces, piece_len = [], n // 16
+    fb, fc = cfg3_B.view(-1), C.view(-1)
+    for p in range(16):
+        sl = slice(p * piece_len, (p + 1) * piece_len)
+        lib.distal_innerprod(fb[sl].view(1, 1, -1), fc[sl].view(1, 1, -1), a)
+        pieces.append(float(a.item()))
+    assert abs(sum(pieces) - full) <= 16 * np.finfo(np.float32).eps * sum(abs(p) for p in pieces)
+    # ... and two of the pieces are recomputed by the oracle from regenerated inputs
+    for p in (3, 12):
+        hb = inputs.tensor(2, 0, (1, 1, piece_len), np.float32, threads=8)
+        hc = inputs.tensor(2, 2, (1, 1, piece_len), np.float32, threads=8)
+        inputs.fill(hb.reshape(-1), 2, 0, p * piece_len, threads=8)
+        inputs.fill(hc.reshape(-1), 2, 2, p * piece_len, threads=8)
+        ref = oracle.innerprod(hb, hc)
+        assert abs(pieces[p] - ref) <= 2 * np.finfo(np.float32).eps * abs(ref) + 1e-3
+    # symmetry, bit for bit, at full size
+    lib.distal_innerprod(C, cfg3_B, a)
+    assert float(a.item()) == full
+
+
+def test_ttm_1024(lib, oracle):
+    """configs[3]: A(i,j,l) = sum_k B(i,j,k) C(k,l), B 1024^3, C 1024 x 256, fp32, seed 3."""
+    import torch
+    I = J = K = 1024
+    L = 256
+    B, C = devgen(3, 0, (I, J, K), np.float32), devgen(3, 1, (K, L), np.float32)
+    A = torch.full((I, J, L), float("nan"), dtype=torch.float32, device="cuda:0")
+    lib.distal_ttm(B, C, A)
+    rng = np.random.default_rng(9)
+    fibres = np.sort(rng.choice(I * J, 512, replace=False))
+    hB = host_rows(3, 0, K, fibres, np.float32).reshape(1, -1, K)
+    hC = inputs.tensor(3, 1, (K, L), np.float32)
+    ref = oracle.ttm(hB, hC)[0]
+    got = A.view(I * J, L)[torch.from_numpy(fibres).cuda()].cpu().numpy()
+    U.assert_close(got, ref, np.float32, K)
+    assert bool(torch.isfinite(A).all())
+    # linear in C: the contraction with 2C is exactly twice the result
+    A2 = torch.empty_like(A[:8])
+    lib.distal_ttm(B[:8], C * 2, A2)
+    assert torch.equal(A2, A[:8] * 2)
+
+
+def test_mttkrp_1024(lib, oracle):
+    """configs[4]: A(i,l) = sum_jk B(i,j,k) C(j,l) D(k,l), B 1024^3, rank 32, fp32, seed 4."""
+    import torch
+    I = J = K = 1024
+    L = 32
+    B = devgen(4, 0, (I, J, K), np.float32)
+    C, D = devgen(4, 1, (J, L), np.float32), devgen(4, 2, (K, L), np.float32)
+    A = torch.full((I, L), float("nan"), dtype=torch.float32, device="cuda:0")
+    lib.distal_mttkrp(B, C, D, A)
+    slices = [0, 357, 1023]
+    hC, hD = inputs.tensor(4, 1, (J, L), np.float32), inputs.tensor(4, 2, (K, L), np.float32)
+    for i in slices:
+        hB = inputs.values(4, 0, i * J * K, J * K, np.float32).reshape(1, J, K)
+        ref = oracle.mttkrp(hB, hC, hD)[0]
+        got = A[i].cpu().numpy()
+        U.assert_close(got, ref, np.float32, J * K)
+    assert bool(torch.isfinite(A).all())
+    # second call gives the same bits (fixed summation order, no atomics)
+    A2 = torch.empty_like(A)
+    lib.distal_mttkrp(B, C, D, A2)
+    assert torch.equal(A, A2)
