@@ -58,14 +58,22 @@ bool allow_lds(Kern kern, int bytes, std::atomic<bool> (&done)[kMaxDevices]) {
     return true;
 }
 
-template <typename T, int BM, int BN, int BK, int WM, int WN, int PF = 1>
-int launch_contract(const ContractArgs<T> &a, hipStream_t stream) {
+template <typename T, int BM, int BN, int BK, int WM, int WN, bool FAST>
+int launch_contract(ContractArgs<T> a, hipStream_t stream) {
     typedef ContractCfg<T, BM, BN, BK, WM, WN> Cfg;
-    auto kern = contract_kernel<T, BM, BN, BK, WM, WN, PF>;
-    static std::atomic<bool> done[kMaxDevices];
-    if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
+    a.tiles_m = (int)((a.M + BM - 1) / BM);
+    a.tiles_n = (int)((a.N + BN - 1) / BN);
     const int64_t nblocks = (int64_t)a.tiles_m * a.tiles_n;
-    hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
+    static std::atomic<bool> done[kMaxDevices];
+    if constexpr (FAST) {
+        auto kern = contract_fast_kernel<T, BM, BN, BK, WM, WN>;
+        if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
+        hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
+    } else {
+        auto kern = contract_kernel<T, BM, BN, BK, WM, WN, 1>;
+        if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
+        hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
+    }
     return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
 }
 
@@ -80,14 +88,19 @@ int launch_fill(T *out, int64_t rows, int64_t cols, int64_t ld, hipStream_t stre
 }
 
 // ---- matrix multiply ------------------------------------------------------
+// Tile choice depends on the shape only.  Shapes made of whole, aligned tiles take the
+// straight-line kernel; a large binary32 problem takes 256 x 256 tiles (16 wavefronts), a
+// large binary64 problem 256 x 128 (8 wavefronts); everything else takes the guarded
+// 128 x 128 kernel.
+constexpr int64_t kBigTileMinTiles = 256;   // below this a grid of big tiles cannot fill 256 CUs
+
 template <typename T>
 int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B, int64_t ldb,
            T *C, int64_t ldc, int accumulate, hipStream_t stream) {
-    constexpr int BM = 128, BN = 128, BK = 16;
     constexpr int VEC = 16 / (int)sizeof(T);
     if (M == 0 || N == 0) return DISTAL_OK;
     if (K == 0) return accumulate ? DISTAL_OK : launch_fill<T>(C, M, N, ldc, stream);
-    const int64_t tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
+    const int64_t tm = (M + 127) / 128, tn = (N + 127) / 128;
     int64_t nblocks;
     if (!mul_ok(tm, tn, &nblocks) || nblocks > std::numeric_limits<int>::max()) return DISTAL_ERR_SHAPE;
     ContractArgs<T> a{};
@@ -95,11 +108,19 @@ int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
     a.M = M; a.N = N; a.K = K;
     a.lda = lda; a.ldb = ldb; a.ldc = ldc;
     a.accumulate = accumulate ? 1 : 0;
-    a.tiles_m = (int)tm; a.tiles_n = (int)tn;
     a.a_vec_ok = aligned16(A) && lda % VEC == 0;
     a.b_vec_ok = aligned16(B) && ldb % VEC == 0;
     a.c_vec_ok = aligned16(C) && ldc % VEC == 0;
-    return launch_contract<T, BM, BN, BK, 2, 2>(a, stream);
+    const bool whole = a.a_vec_ok && a.b_vec_ok && a.c_vec_ok && K % 16 == 0;
+    if constexpr (sizeof(T) == 4) {
+        if (whole && M % 256 == 0 && N % 256 == 0 && (M / 256) * (N / 256) >= kBigTileMinTiles)
+            return launch_contract<T, 256, 256, 16, 4, 4, true>(a, stream);
+    } else {
+        if (whole && M % 256 == 0 && N % 128 == 0 && (M / 256) * (N / 128) >= kBigTileMinTiles)
+            return launch_contract<T, 256, 128, 16, 4, 2, true>(a, stream);
+    }
+    if (whole && M % 128 == 0 && N % 128 == 0) return launch_contract<T, 128, 128, 16, 2, 2, true>(a, stream);
+    return launch_contract<T, 128, 128, 16, 2, 2, false>(a, stream);
 }
 
 int check_dtype(int dt) { return (dt == DISTAL_F32 || dt == DISTAL_F64) ? DISTAL_OK : DISTAL_ERR_DTYPE; }

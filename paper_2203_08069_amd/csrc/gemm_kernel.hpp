@@ -323,4 +323,151 @@ contract_kernel(const ContractArgs<T> args) {
             }
 }
 
+// ---------------------------------------------------------------------------
+// The same contraction for the case every tile and slab is full and every operand
+// 16-byte aligned (M % BM == 0, N % BN == 0, K % BK == 0, aligned bases and leading
+// dimensions).  No bounds checks and no branches inside the k-loop: its body is one
+// straight-line block, so the LDS writes of the next slab and the global loads of the
+// slab after it are issued between the MFMAs of the current slab, in the issue slots
+// the 64-cycle MFMAs leave free, instead of in a burst of their own.
+// ---------------------------------------------------------------------------
+template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N>
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 16) ? 4 : 2)
+contract_fast_kernel(const ContractArgs<T> args) {
+    typedef ContractCfg<T, BM, BN, BK, WAVES_M, WAVES_N> Cfg;
+    typedef Mfma<T> MF;
+    typedef typename VecOf<T, Cfg::VEC>::type vec_t;
+    typedef typename VecOf<T, Cfg::CV>::type cvec_t;
+    constexpr int VEC = Cfg::VEC, KV = Cfg::KV, KG = Cfg::KG, MI = Cfg::MI, NI = Cfg::NI;
+    constexpr int CV = Cfg::CV, NG = Cfg::NG, NT = Cfg::NT, NKG = BK / KG;
+    static_assert(Cfg::A_VECS % NT == 0 && Cfg::B_VECS % NT == 0, "slab vectors must divide over threads");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    T *lds = reinterpret_cast<T *>(lds_raw);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int li = lane % MF::MB, ls = lane / MF::MB;
+
+    int tm, tn;
+    tile_of_block(blockIdx.x, gridDim.x, args.tiles_m, args.tiles_n, tm, tn);
+    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+    const int64_t nk = args.K / BK;
+
+    // per-thread element offsets of its 16-byte pieces inside a slab, and where they go in LDS
+    int64_t a_off[Cfg::A_PER_T], b_off[Cfg::B_PER_T];
+    int a_lds[Cfg::A_PER_T], b_lds[Cfg::B_PER_T];
+#pragma unroll
+    for (int p = 0; p < Cfg::A_PER_T; ++p) {
+        const int v = tid + p * NT, r = v / (BK / VEC), kv = v % (BK / VEC);
+        a_off[p] = (m0 + r) * args.lda + kv * VEC;
+        a_lds[p] = r * Cfg::LDA_S + kv * VEC;
+    }
+#pragma unroll
+    for (int p = 0; p < Cfg::B_PER_T; ++p) {
+        const int v = tid + p * NT, r = v / (BN / VEC), cv = v % (BN / VEC);
+        b_off[p] = (int64_t)r * args.ldb + n0 + cv * VEC;
+        b_lds[p] = Cfg::A_ELEMS + r * Cfg::LDB_S + cv * VEC;
+    }
+
+    vec_t ra[Cfg::A_PER_T], rb[Cfg::B_PER_T];
+    // slab index past the end is clamped to the last slab: a redundant, in-bounds reload
+    auto load_global = [&](int64_t t) {
+        const int64_t k0 = (t < nk ? t : nk - 1) * BK;
+        const T *ap = args.A + k0;
+        const T *bp = args.B + k0 * args.ldb;
+#pragma unroll
+        for (int p = 0; p < Cfg::A_PER_T; ++p) ra[p] = *reinterpret_cast<const vec_t *>(ap + a_off[p]);
+#pragma unroll
+        for (int p = 0; p < Cfg::B_PER_T; ++p) rb[p] = *reinterpret_cast<const vec_t *>(bp + b_off[p]);
+    };
+    auto store_lds = [&](int stage) {
+        T *st = lds + stage * Cfg::STAGE_ELEMS;
+#pragma unroll
+        for (int p = 0; p < Cfg::A_PER_T; ++p) *reinterpret_cast<vec_t *>(st + a_lds[p]) = ra[p];
+#pragma unroll
+        for (int p = 0; p < Cfg::B_PER_T; ++p) *reinterpret_cast<vec_t *>(st + b_lds[p]) = rb[p];
+    };
+
+    typename MF::acc_t acc[MI][NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int v = 0; v < MF::NACC; ++v) acc[mi][ni][v] = T(0);
+
+    const int a_rd = (wm * Cfg::WTM + li) * Cfg::LDA_S + ls * KV;
+    const int b_rd = Cfg::A_ELEMS + (ls * KV) * Cfg::LDB_S + wn * Cfg::WTN + li * CV;
+    auto compute = [&](int stage, int kg_lo, int kg_hi) {
+        const T *as = lds + stage * Cfg::STAGE_ELEMS + a_rd;
+        const T *bs = lds + stage * Cfg::STAGE_ELEMS + b_rd;
+#pragma unroll
+        for (int kg = kg_lo; kg < kg_hi; ++kg) {
+            vec_t a[MI];
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+                a[mi] = *reinterpret_cast<const vec_t *>(as + mi * MF::MB * Cfg::LDA_S + kg * KG);
+            cvec_t b[KV][NG];
+#pragma unroll
+            for (int t = 0; t < KV; ++t)
+#pragma unroll
+                for (int g = 0; g < NG; ++g)
+                    b[t][g] = *reinterpret_cast<const cvec_t *>(bs + (kg * KG + t) * Cfg::LDB_S
+                                                                + g * MF::NB * CV);
+#pragma unroll
+            for (int t = 0; t < KV; ++t)
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni) {
+                        T bv;
+                        if constexpr (CV == 1) bv = b[t][ni];
+                        else bv = b[t][ni / CV][ni % CV];
+                        acc[mi][ni] = MF::run(a[mi][t], bv, acc[mi][ni]);
+                    }
+        }
+    };
+
+    // slab t is in LDS buffer t & 1; slab t+1 is in registers; slab t+2 is requested
+    // during the multiply of slab t
+    load_global(0);
+    store_lds(0);
+    load_global(1);
+    __syncthreads();
+    for (int64_t t = 0; t < nk; ++t) {
+        const int stage = (int)(t & 1);
+        compute(stage, 0, (NKG + 1) / 2);
+        store_lds(stage ^ 1);        // slab t+1 (on the last pass: a copy nobody reads)
+        load_global(t + 2);
+        compute(stage, (NKG + 1) / 2, NKG);
+        __syncthreads();
+    }
+
+    // epilogue: accumulators -> C, CV neighbouring columns per store
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int g = 0; g < NG; ++g)
+#pragma unroll
+            for (int v = 0; v < MF::NACC; ++v) {
+                const int64_t row = m0 + wm * Cfg::WTM + mi * MF::MB + MF::out_row(v, lane);
+                const int64_t col = n0 + wn * Cfg::WTN + g * (MF::NB * CV) + li * CV;
+                T *cp = args.C + row * args.ldc + col;
+                cvec_t o;
+                if constexpr (CV == 1) {
+                    o = acc[mi][g][v];
+                    if (args.accumulate) o += *cp;
+                    *cp = o;
+                } else {
+#pragma unroll
+                    for (int q = 0; q < CV; ++q) o[q] = acc[mi][g * CV + q][v];
+                    if (args.accumulate) o += *reinterpret_cast<const cvec_t *>(cp);
+                    *reinterpret_cast<cvec_t *>(cp) = o;
+                }
+            }
+}
+
 }  // namespace distal

@@ -141,7 +141,10 @@ mttkrp_kernel(const MttkrpArgs<T> args) {
     T *lds = reinterpret_cast<T *>(lds_raw);
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    // the wavefront index is the same in all lanes: say so, and every address that depends on it
+    // stays in scalar registers
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane % MF::MB, ls = lane / MF::MB;
     T *patch = lds + wave * Cfg::PATCH;
     T *cfac = lds + Cfg::NW * Cfg::PATCH;          // C(chunk rows, tile columns), row stride LDC

@@ -37,7 +37,10 @@ def compare(got, ref, dtype, kind, klen):
 # ------------------------------------------------------------------ gemm
 
 GEMM_SHAPES = [(1, 1, 1), (256, 256, 256), (127, 129, 17), (130, 260, 33), (300, 200, 100),
-               (128, 128, 16), (64, 384, 1000), (513, 31, 8)]
+               (128, 128, 16), (64, 384, 1000), (513, 31, 8),
+               (384, 256, 48),          # whole 128 x 128 tiles: straight-line kernel
+               (4096, 4096, 32),        # 256 big tiles (fp32 256 x 256 ...)
+               (4096, 2048, 32)]        # ... and fp64 256 x 128
 
 
 @pytest.mark.parametrize("dtype", DT)
