@@ -87,7 +87,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--rows", default="all",
-                    help="comma list of gemm_f64,gemm_f32,ttm,mttkrp,ttv,innerprod (gemm_f64 always runs)")
+                    help="comma list of gemm_f64,gemm_f32,ttm,mttkrp,ttv,innerprod (gemm_f64 always runs); "
+                         "extra rows, not part of 'all': summa (k-chunk leaf shapes), "
+                         "ttv_f64,innerprod_f64,ttm_f64,mttkrp_f64")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB read + 1 GiB write elementwise kernel (torch.add), the known-size "
@@ -182,6 +184,54 @@ def main():
             r["sample_normwise_err"] = sample_err(got, ref)
             del hB
         del A, B, C
+
+    # ---------------------------------------------------------------- SUMMA k-chunk leaf shapes (extra)
+    if "summa" in want:
+        n = 8192
+        A = device_tensor(1, 0, (n, n), np.float64, device=dev)
+        B = device_tensor(1, 1, (n, n), np.float64, device=dev)
+        C = torch.zeros((n, n), dtype=torch.float64, device=dev)
+        for chunk in (256, 512, 1024, 2048):
+            finish(f"gemm_f64_summa_chunk{chunk}",
+                   f"C += A(:, kc:kc+{chunk}) B(kc:kc+{chunk}, :), M=N={n}: the leaf one processor issues per SUMMA k-step",
+                   "f64", lambda: binding.distal_gemm(A[:, 0:chunk], B[0:chunk, :], C, accumulate=True),
+                   2.0 * n * n * chunk, 8.0 * (2 * n * chunk + 2 * n * n), "mfma")
+        del A, B, C
+
+    # ---------------------------------------------------------------- fp64 higher-order kernels (extra)
+    if want & {"ttv_f64", "innerprod_f64", "ttm_f64", "mttkrp_f64"}:
+        I = J = K = 1024
+        B = device_tensor(2, 0, (I, J, K), np.float64, device=dev)
+        if "ttv_f64" in want:
+            c = device_tensor(2, 1, (K,), np.float64, device=dev)
+            A = torch.empty((I, J), dtype=torch.float64, device=dev)
+            finish("ttv_f64", f"TTV B {I}x{J}x{K} f64, seed 2", "f64", lambda: binding.distal_ttv(B, c, A),
+                   2.0 * I * J * K, 8.0 * (I * J * K + K + I * J), "hbm")
+            del A
+        if "innerprod_f64" in want:
+            C = device_tensor(2, 2, (I, J, K), np.float64, device=dev)
+            a = torch.empty(1, dtype=torch.float64, device=dev)
+            finish("innerprod_f64", f"innerprod B,C {I}x{J}x{K} f64, seed 2", "f64",
+                   lambda: binding.distal_innerprod(B, C, a), 2.0 * I * J * K, 16.0 * I * J * K, "hbm")
+            del C, a
+        if "ttm_f64" in want:
+            L = 256
+            C = device_tensor(3, 1, (K, L), np.float64, device=dev)
+            A = torch.empty((I, J, L), dtype=torch.float64, device=dev)
+            finish("ttm_f64", f"TTM B {I}x{J}x{K}, C {K}x{L} f64", "f64", lambda: binding.distal_ttm(B, C, A),
+                   2.0 * I * J * K * L, 8.0 * (I * J * K + K * L + I * J * L), "mfma")
+            del C, A
+        if "mttkrp_f64" in want:
+            L = 32
+            C = device_tensor(4, 1, (J, L), np.float64, device=dev)
+            D = device_tensor(4, 2, (K, L), np.float64, device=dev)
+            A = torch.empty((I, L), dtype=torch.float64, device=dev)
+            r = finish("mttkrp_f64", f"MTTKRP B {I}x{J}x{K}, rank {L} f64", "f64",
+                       lambda: binding.distal_mttkrp(B, C, D, A), 2.0 * I * J * K * L + 2.0 * I * J * L,
+                       8.0 * (I * J * K + J * L + K * L + I * L), "hbm")
+            r["mfma_frac"] = (2.0 * I * J * K * L + 2.0 * I * J * L) / r["ms_kernel_avg"] / 1e9 / PEAK_TFLOPS["f64"]
+            del C, D, A
+        del B
 
     # ---------------------------------------------------------------- TTV + innerprod (configs[2])
     if "ttv" in want or "innerprod" in want:

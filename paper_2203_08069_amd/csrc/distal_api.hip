@@ -90,8 +90,9 @@ int launch_fill(T *out, int64_t rows, int64_t cols, int64_t ld, hipStream_t stre
 // ---- matrix multiply ------------------------------------------------------
 // Tile choice depends on the shape only.  Shapes made of whole, aligned tiles take the
 // straight-line kernel; a large binary32 problem takes 256 x 256 tiles (16 wavefronts), a
-// large binary64 problem 256 x 128 (8 wavefronts); everything else takes the guarded
-// 128 x 128 kernel.
+// large, deep binary64 problem 256 x 128 (8 wavefronts, half the operand traffic; with one
+// workgroup per CU its epilogue is not hidden, so shallow k-chunks keep 128 x 128);
+// everything else takes the guarded 128 x 128 kernel.
 constexpr int64_t kBigTileMinTiles = 256;   // below this a grid of big tiles cannot fill 256 CUs
 
 template <typename T>
@@ -116,7 +117,7 @@ int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
         if (whole && M % 256 == 0 && N % 256 == 0 && (M / 256) * (N / 256) >= kBigTileMinTiles)
             return launch_contract<T, 256, 256, 16, 4, 4, true>(a, stream);
     } else {
-        if (whole && M % 256 == 0 && N % 128 == 0 && (M / 256) * (N / 128) >= kBigTileMinTiles)
+        if (whole && M % 256 == 0 && N % 128 == 0 && K >= 4096 && (M / 256) * (N / 128) >= kBigTileMinTiles)
             return launch_contract<T, 256, 128, 16, 4, 2, true>(a, stream);
     }
     if (whole && M % 128 == 0 && N % 128 == 0) return launch_contract<T, 128, 128, 16, 2, 2, true>(a, stream);
@@ -128,6 +129,7 @@ int check_dtype(int dt) { return (dt == DISTAL_F32 || dt == DISTAL_F64) ? DISTAL
 size_t elem_size(int dt) { return dt == DISTAL_F64 ? 8 : 4; }
 
 // ---- MTTKRP ---------------------------------------------------------------
+constexpr int kMttkrpCJ = MttkrpCfg<float>::CJ;   // rows of j per chunk (work item and factor copy)
 // Work decomposition and workspace layout, a function of the shape only (never of the
 // device), so the summation order is reproducible.
 // Workspace: [Dt: 32*tiles_n rows x Kpad][partial rows: I*nchunks*nslices x L, unless that is I]
@@ -139,7 +141,7 @@ struct MttkrpPlan {
 MttkrpPlan mttkrp_plan(int dt, int64_t I, int64_t J, int64_t K, int64_t L) {
     MttkrpPlan p{};
     const int64_t sl = 256 / (int64_t)(dt == DISTAL_F64 ? 8 : 4);       // k values per wavefront slice
-    const int64_t cj = MttkrpCfg<float>::CJ;                              // rows of j per chunk
+    const int64_t cj = kMttkrpCJ;                                         // rows of j per chunk
     p.nslices = (K + sl - 1) / sl;
     if (p.nslices < 1) p.nslices = 1;
     p.kgroups = (p.nslices + 3) / 4;

@@ -81,10 +81,13 @@ struct ContractArgs {
 // Block id -> output tile.  Hardware hands consecutive workgroup ids to the 8
 // XCDs in turn; give each XCD one contiguous range of logical ids, and walk
 // that range in bands of GROUP_M tile rows so that tiles resident together
-// share A row-panels and B column-panels in that XCD's L2.
+// share A row-panels and B column-panels in that XCD's L2.  GROUP_M is chosen
+// per tile shape so that the tiles resident on one XCD (32 CUs) cover a roughly
+// square patch of C, which minimises the operand bytes per flop that miss L2.
+template <int GROUP_M>
 __device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m, int tiles_n,
                                               int &tm, int &tn) {
-    constexpr int NXCD = 8, GROUP_M = 8;
+    constexpr int NXCD = 8;
     const int per = nblocks / NXCD, rem = nblocks % NXCD;
     const int x = bid % NXCD, q = bid / NXCD;
     const int p = x * per + (x < rem ? x : rem) + q;
@@ -114,6 +117,7 @@ struct ContractCfg {
     static constexpr int LDS_BYTES = 2 * STAGE_ELEMS * (int)sizeof(T);
     static constexpr int A_VECS = BM * (BK / VEC), B_VECS = BK * (BN / VEC);
     static constexpr int A_PER_T = (A_VECS + NT - 1) / NT, B_PER_T = (B_VECS + NT - 1) / NT;
+    static constexpr int GROUP_M = (BM > BN) ? 4 : 8;     // tile rows per band (see tile_of_block)
     static_assert(BM % (WAVES_M * MF::MB) == 0 && BN % (WAVES_N * MF::NB) == 0, "tile shape");
     static_assert(BK % KG == 0, "BK must hold whole MFMA k-groups");
 };
@@ -138,7 +142,7 @@ contract_kernel(const ContractArgs<T> args) {
     const int ls = lane / MF::MB;          // k-slot
 
     int tm, tn;
-    tile_of_block(blockIdx.x, gridDim.x, args.tiles_m, args.tiles_n, tm, tn);
+    tile_of_block<Cfg::GROUP_M>(blockIdx.x, gridDim.x, args.tiles_m, args.tiles_n, tm, tn);
 
     const int64_t m0 = (int64_t)tm * BM, mlimit = args.M;
     const int64_t n0 = (int64_t)tn * BN;
@@ -352,7 +356,7 @@ contract_fast_kernel(const ContractArgs<T> args) {
     const int li = lane % MF::MB, ls = lane / MF::MB;
 
     int tm, tn;
-    tile_of_block(blockIdx.x, gridDim.x, args.tiles_m, args.tiles_n, tm, tn);
+    tile_of_block<Cfg::GROUP_M>(blockIdx.x, gridDim.x, args.tiles_m, args.tiles_n, tm, tn);
     const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
     const int64_t nk = args.K / BK;
 

@@ -224,10 +224,8 @@ mttkrp_kernel(const MttkrpArgs<T> args) {
         }
     };
 
-    int64_t i = ig;
-    int rb = 0;
-    load_rows(i, 0);
-    while (true) {
+    // One 32-row block: patch -> MFMA -> fold.  `c` are the lane's factor pieces for this block.
+    auto block = [&](int64_t i, int rb, const vec_t (&c)[MI][4]) {
         // what comes after this block: the next block of this i, or the first block of the next i
         const bool last_rb = (rb + 1 == nrb);
         const int64_t next_i = last_rb ? i + args.igroups : i;
@@ -273,54 +271,63 @@ mttkrp_kernel(const MttkrpArgs<T> args) {
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        // scale Tt(l, j) by C(j, l) from the LDS copy and add into the lane's running sums
-        // binary32: l = 8q + 4*ls + r, v = 4q + r;  binary64: l = 2*(4v + ls) + lb
+        // scale Tt(l, j) by C(j, l) and add into the lane's running sums
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi) {
-            const T *crow = cfac + (rb * RB + mi * MF::NB + li) * Cfg::LDC + (sizeof(T) == 4 ? 4 * ls : 2 * ls);
-            vec_t c[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) c[q] = *reinterpret_cast<const vec_t *>(crow + 8 * q);
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
             for (int v = 0; v < MF::NACC; ++v)
 #pragma unroll
                 for (int lb = 0; lb < LB; ++lb) {
                     T f;
-                    if constexpr (sizeof(T) == 4) f = c[v >> 2][v & 3];
-                    else f = c[v][lb];
+                    if constexpr (sizeof(T) == 4) f = c[mi][v >> 2][v & 3];
+                    else f = c[mi][v][lb];
                     lsum[lb][v] = fma_t(acc[lb][mi][v], f, lsum[lb][v]);
                 }
-        }
+    };
 
-        if (last_rb) {
-            // (i, chunk) done: add the lanes that own the same l (same k-slot ls, all li) in a
-            // fixed order and write this wavefront's partial row.
-            T *prow_out = args.partial + ((i * args.nchunks + chunk) * args.nslices + slice) * L + n0;
+    // (i, chunk) done: add the lanes that own the same l (same k-slot ls, all li) in a fixed
+    // order and write this wavefront's partial row
+    auto flush = [&](int64_t i) {
+        T *prow_out = args.partial + ((i * args.nchunks + chunk) * args.nslices + slice) * L + n0;
+#pragma unroll
+        for (int lb = 0; lb < LB; ++lb)
+#pragma unroll
+            for (int v = 0; v < MF::NACC; ++v) {
+                T s = sum16(lsum[lb][v]);
+                if (MF::MB == 32) s += __shfl_xor(s, 16);
+                lsum[lb][v] = s;
+            }
+        if (li == 0) {
 #pragma unroll
             for (int lb = 0; lb < LB; ++lb)
 #pragma unroll
                 for (int v = 0; v < MF::NACC; ++v) {
-                    T s = sum16(lsum[lb][v]);
-                    if (MF::MB == 32) s += __shfl_xor(s, 16);
-                    lsum[lb][v] = s;
+                    const int l = mttkrp_l_of<T>(v, lb, lane);
+                    if (!GUARD || n0 + l < L) prow_out[l] = lsum[lb][v];
                 }
-            if (li == 0) {
-#pragma unroll
-                for (int lb = 0; lb < LB; ++lb)
-#pragma unroll
-                    for (int v = 0; v < MF::NACC; ++v) {
-                        const int l = mttkrp_l_of<T>(v, lb, lane);
-                        if (!GUARD || n0 + l < L) prow_out[l] = lsum[lb][v];
-                    }
-            }
-#pragma unroll
-            for (int lb = 0; lb < LB; ++lb)
-#pragma unroll
-                for (int v = 0; v < MF::NACC; ++v) lsum[lb][v] = T(0);
-            if (!more) break;
         }
-        i = next_i;
-        rb = next_rb;
+#pragma unroll
+        for (int lb = 0; lb < LB; ++lb)
+#pragma unroll
+            for (int v = 0; v < MF::NACC; ++v) lsum[lb][v] = T(0);
+    };
+
+    load_rows(ig, 0);
+    for (int64_t i = ig; i < I; i += args.igroups) {
+        for (int rb = 0; rb < nrb; ++rb) {
+            // the lane's factor pieces for this block, from the LDS copy:
+            // binary32: l = 8q + 4*ls + r (v = 4q + r); binary64: l = 2*(4q + ls) + lb (v = q)
+            vec_t c[MI][4];
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const T *crow = cfac + (rb * RB + mi * MF::NB + li) * Cfg::LDC
+                                + (sizeof(T) == 4 ? 4 * ls : 2 * ls);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) c[mi][q] = *reinterpret_cast<const vec_t *>(crow + 8 * q);
+            }
+            block(i, rb, c);
+        }
+        flush(i);
     }
 }
 

@@ -40,7 +40,7 @@ GEMM_SHAPES = [(1, 1, 1), (256, 256, 256), (127, 129, 17), (130, 260, 33), (300,
                (128, 128, 16), (64, 384, 1000), (513, 31, 8),
                (384, 256, 48),          # whole 128 x 128 tiles: straight-line kernel
                (4096, 4096, 32),        # 256 big tiles (fp32 256 x 256 ...)
-               (4096, 2048, 32)]        # ... and fp64 256 x 128
+               (4096, 2048, 32)]
 
 
 @pytest.mark.parametrize("dtype", DT)
@@ -340,3 +340,23 @@ def test_runs_on_a_side_stream(lib, oracle):
         lib.distal_gemm(dA, dB, C)
     s.synchronize()
     U.assert_close(U.host(C), oracle.gemm(A, B), np.float32, 64)
+
+
+# ------------------------------------------------------------------ schedule driver
+
+@pytest.mark.parametrize("dtype", DT)
+def test_schedule_driver(lib, oracle, dtype):
+    """SUMMA / Cannon / Johnson call sequences from schedules.py give the one-shot product,
+    bit for bit on integer inputs."""
+    import torch
+    from paper_2203_08069_amd import schedules
+    n = 768
+    A, B = U.gen(50, 0, (n, n), dtype, inputs.SMALLINT), U.gen(50, 1, (n, n), dtype, inputs.SMALLINT)
+    ref = oracle.gemm(A, B)
+    dA, dB = U.dev(A), U.dev(B)
+    z = lambda: torch.zeros((n, n), dtype=dA.dtype, device="cuda:0")
+    U.assert_exact(U.host(schedules.summa(dA, dB, z(), 2, 3, 128)), ref)
+    U.assert_exact(U.host(schedules.summa(dA, dB, z(), 1, 1, 100)), ref)       # ragged last chunk
+    U.assert_exact(U.host(schedules.cannon(dA, dB, z(), 3)), ref)
+    parts = schedules.johnson(dA, dB, z(), 2, [empty((n, n), dtype) for _ in range(2)])
+    U.assert_exact(sum(U.host(p).astype(np.float64) for p in parts), ref)
