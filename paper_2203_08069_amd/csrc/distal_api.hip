@@ -70,7 +70,7 @@ int launch_contract(ContractArgs<T> a, hipStream_t stream) {
         if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
         hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
     } else {
-        auto kern = contract_kernel<T, BM, BN, BK, WM, WN, 1>;
+        auto kern = contract_kernel<T, BM, BN, BK, WM, WN>;
         if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
         hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
     }

@@ -9,6 +9,9 @@
 //   k-loop : BK-deep slabs of both operands, global -> registers -> LDS, two LDS
 //            buffers, one barrier per slab; the next slab's global loads are in
 //            flight while the current one is multiplied
+//   two kernels: contract_kernel checks bounds and alignment per tile and serves any
+//            shape; contract_fast_kernel assumes whole aligned tiles and has a
+//            straight-line k-loop
 //
 // Operand-to-lane assignment.  An MFMA contracts KS "k-slots" held by different
 // lane groups.  Which k a slot carries is free as long as both operands agree,
@@ -122,7 +125,7 @@ struct ContractCfg {
     static_assert(BK % KG == 0, "BK must hold whole MFMA k-groups");
 };
 
-template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int PF = 1>
+template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N, 2)
 contract_kernel(const ContractArgs<T> args) {
     typedef ContractCfg<T, BM, BN, BK, WAVES_M, WAVES_N> Cfg;
@@ -151,8 +154,8 @@ contract_kernel(const ContractArgs<T> args) {
     const bool a_fast = args.a_vec_ok && (m0 + BM <= mlimit);
     const bool b_fast = args.b_vec_ok && (n0 + BN <= args.N);
 
-    // PF register sets hold the next PF slabs while they are in flight from HBM/L2.
-    vec_t ra_all[PF][Cfg::A_PER_T], rb_all[PF][Cfg::B_PER_T];
+    // the next slab waits in these registers while it is in flight from HBM/L2
+    vec_t ra_next[Cfg::A_PER_T], rb_next[Cfg::B_PER_T];
 
     auto load_global = [&](vec_t (&ra)[Cfg::A_PER_T], vec_t (&rb)[Cfg::B_PER_T], int64_t k0) {
         const bool kfull = (k0 + BK <= K);
@@ -264,31 +267,24 @@ contract_kernel(const ContractArgs<T> args) {
         }
     };
 
-    // Slab t+1 sits in register set (t+1) % PF while slab t is multiplied; once it has
-    // been written to the idle LDS buffer, that register set is refilled with slab
-    // t+1+PF.  Slab indices past the end are clamped to the last slab: those loads are
-    // redundant cache hits, never out of bounds, and keep the loop free of divergence.
+    // Slab t+1 sits in registers while slab t is multiplied; once it has been written to
+    // the idle LDS buffer the registers are refilled with slab t+2.  Slab indices past the
+    // end are clamped to the last slab: those loads are redundant cache hits, never out of
+    // bounds, and keep the loop free of divergence.
     const int64_t nk = (K + BK - 1) / BK;
     auto k_of = [&](int64_t t) { return (t < nk ? t : nk - 1) * BK; };
     if (nk > 0) {
-#pragma unroll
-        for (int u = 0; u < PF; ++u) load_global(ra_all[u], rb_all[u], k_of(u));
-        store_lds(ra_all[0], rb_all[0], 0);
-        load_global(ra_all[0], rb_all[0], k_of(PF));
+        load_global(ra_next, rb_next, k_of(0));
+        store_lds(ra_next, rb_next, 0);
+        load_global(ra_next, rb_next, k_of(1));
     }
     __syncthreads();
-    for (int64_t t0 = 0; t0 < nk; t0 += PF) {
-#pragma unroll
-        for (int u = 0; u < PF; ++u) {
-            const int64_t t = t0 + u;
-            if (t < nk) {
-                const int stage = (int)(t & 1);
-                compute(stage);
-                if (t + 1 < nk) store_lds(ra_all[(u + 1) % PF], rb_all[(u + 1) % PF], stage ^ 1);
-                load_global(ra_all[(u + 1) % PF], rb_all[(u + 1) % PF], k_of(t + 1 + PF));
-                __syncthreads();
-            }
-        }
+    for (int64_t t = 0; t < nk; ++t) {
+        const int stage = (int)(t & 1);
+        compute(stage);
+        if (t + 1 < nk) store_lds(ra_next, rb_next, stage ^ 1);
+        load_global(ra_next, rb_next, k_of(t + 2));
+        __syncthreads();
     }
 
     // epilogue: accumulators -> C, CV neighbouring columns per store
