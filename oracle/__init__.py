@@ -36,25 +36,54 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def _bind(path: str):
+    """ctypes prototypes for an oracle shared object."""
+    lib = ctypes.CDLL(path)
+    i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+    lib.oracle_gemm.argtypes = [ci, i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, vp]
+    lib.oracle_ttv.argtypes = [ci, i64, i64, i64, vp, vp, vp]
+    lib.oracle_innerprod.argtypes = [ci, i64, i64, i64, vp, vp, vp]
+    lib.oracle_ttm.argtypes = [ci, i64, i64, i64, i64, vp, vp, vp]
+    lib.oracle_mttkrp.argtypes = [ci, i64, i64, i64, i64, vp, vp, vp, vp]
+    for f in (lib.oracle_gemm, lib.oracle_ttv, lib.oracle_innerprod, lib.oracle_ttm,
+              lib.oracle_mttkrp, lib.oracle_version, lib.oracle_long_double_digits,
+              lib.oracle_max_threads):
+        f.restype = ci
+    if lib.oracle_long_double_digits() < 64:
+        raise RuntimeError("oracle needs a long double with a 64-bit significand")
+    return lib
+
+
 def _load():
     global _lib
     with _lock:
         if _lib is None:
-            lib = ctypes.CDLL(build())
-            i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
-            lib.oracle_gemm.argtypes = [ci, i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, vp]
-            lib.oracle_ttv.argtypes = [ci, i64, i64, i64, vp, vp, vp]
-            lib.oracle_innerprod.argtypes = [ci, i64, i64, i64, vp, vp, vp]
-            lib.oracle_ttm.argtypes = [ci, i64, i64, i64, i64, vp, vp, vp]
-            lib.oracle_mttkrp.argtypes = [ci, i64, i64, i64, i64, vp, vp, vp, vp]
-            for f in (lib.oracle_gemm, lib.oracle_ttv, lib.oracle_innerprod, lib.oracle_ttm,
-                      lib.oracle_mttkrp, lib.oracle_version, lib.oracle_long_double_digits,
-                      lib.oracle_max_threads):
-                f.restype = ci
-            if lib.oracle_long_double_digits() < 64:
-                raise RuntimeError("oracle needs a long double with a 64-bit significand")
-            _lib = lib
+            _lib = _bind(build())
     return _lib
+
+
+class Variant:
+    """The same Python front end over another build of the C source.  Tests use it to plant a
+    mistake in a COPY of the oracle and check that the pins notice; nothing else may."""
+
+    def __init__(self, lib_path: str):
+        self._lib = _bind(lib_path)
+
+    def _call(self, name, *a, **k):
+        global _lib
+        with _lock:
+            saved, _lib = _lib, self._lib
+        try:
+            return globals()[name](*a, **k)
+        finally:
+            with _lock:
+                _lib = saved
+
+    def gemm(self, *a, **k): return self._call("gemm", *a, **k)
+    def ttv(self, *a, **k): return self._call("ttv", *a, **k)
+    def innerprod(self, *a, **k): return self._call("innerprod", *a, **k)
+    def ttm(self, *a, **k): return self._call("ttm", *a, **k)
+    def mttkrp(self, *a, **k): return self._call("mttkrp", *a, **k)
 
 
 def max_threads() -> int:
