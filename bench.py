@@ -44,7 +44,10 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the
 # same counters on a plain copy kernel of known size; see profiles/.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    "gemm_f64": 9.129e9, "gemm_f32": 3.741e9, "ttm": 5.511e9,
+    "mttkrp": 4.332e9, "ttv": 4.299e9, "innerprod": 8.590e9,
+}
 
 
 def log(*a):

@@ -132,9 +132,9 @@ size_t elem_size(int dt) { return dt == DISTAL_F64 ? 8 : 4; }
 constexpr int kMttkrpCJ = MttkrpCfg<float>::CJ;   // rows of j per chunk (work item and factor copy)
 // Work decomposition and workspace layout, a function of the shape only (never of the
 // device), so the summation order is reproducible.
-// Workspace: [Dt: 32*tiles_n rows x Kpad][partial rows: I*nchunks*nslices x L, unless that is I]
+// Workspace: partial rows, I*nchunks*nslices x L, unless there is one per i (then none).
 struct MttkrpPlan {
-    int64_t nchunks, nslices, kgroups, tiles_n, kpad, dt_elems, partial_rows, partial_elems;
+    int64_t nchunks, nslices, kgroups, tiles_n, partial_rows, partial_elems;
     bool ok;
 };
 
@@ -145,13 +145,11 @@ MttkrpPlan mttkrp_plan(int dt, int64_t I, int64_t J, int64_t K, int64_t L) {
     p.nslices = (K + sl - 1) / sl;
     if (p.nslices < 1) p.nslices = 1;
     p.kgroups = (p.nslices + 3) / 4;
-    p.kpad = p.kgroups * 4 * sl;
     p.tiles_n = (L + 31) / 32;
     p.nchunks = J > 0 ? (J + cj - 1) / cj : 1;
     int64_t t;
-    p.ok = mul_ok(p.tiles_n * 32, p.kpad, &p.dt_elems) && mul_ok(I, p.nchunks, &t) &&
-           mul_ok(t, p.nslices, &p.partial_rows) && mul_ok(p.partial_rows, L, &p.partial_elems) &&
-           p.dt_elems <= INT64_MAX / 16 && p.partial_elems <= INT64_MAX / 16;
+    p.ok = mul_ok(I, p.nchunks, &t) && mul_ok(t, p.nslices, &p.partial_rows) &&
+           mul_ok(p.partial_rows, L, &p.partial_elems) && p.partial_elems <= INT64_MAX / 16;
     if (p.nchunks * p.nslices <= 1) p.partial_elems = 0;
     return p;
 }
@@ -205,20 +203,11 @@ int mttkrp_t(int64_t I, int64_t J, int64_t K, int64_t L, const T *B, const T *C,
     if (!plan.ok || plan.kgroups > imax / 8 || plan.tiles_n > imax / 8 || plan.nchunks > imax / 8 ||
         plan.nchunks * plan.nslices > imax)
         return DISTAL_ERR_SHAPE;
-    T *dt_buf = static_cast<T *>(workspace);
-    T *partial = dt_buf + plan.dt_elems;
-    {
-        int64_t blocks = (plan.dt_elems + 255) / 256;
-        if (blocks > 1024) blocks = 1024;
-        hipLaunchKernelGGL(mttkrp_transpose_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream, D, dt_buf,
-                           K, L, plan.kpad, plan.tiles_n * 32);
-        if (hipGetLastError() != hipSuccess) return DISTAL_ERR_LAUNCH;
-    }
+    T *partial = static_cast<T *>(workspace);
     const int64_t per_i = plan.nchunks * plan.nslices;
     MttkrpArgs<T> a{};
-    a.B = B; a.C = C; a.Dt = dt_buf;
+    a.B = B; a.C = C; a.D = D;
     a.I = I; a.J = J; a.K = K; a.L = L;
-    a.Kpad = plan.kpad;
     a.nchunks = (int)plan.nchunks;
     a.nslices = (int)plan.nslices;
     a.kgroups = (int)plan.kgroups;
@@ -364,7 +353,7 @@ size_t distal_mttkrp_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, int6
     if (I == 0 || J == 0 || K == 0 || L == 0) return 0;
     const MttkrpPlan p = mttkrp_plan(dt, I, J, K, L);
     if (!p.ok) return 0;
-    return (size_t)(p.dt_elems + p.partial_elems) * elem_size(dt);
+    return (size_t)p.partial_elems * elem_size(dt);
 }
 
 int distal_mttkrp(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L, const void *B,

@@ -8,21 +8,19 @@
 // 16-byte loads of B (the address unit, not HBM or the matrix pipe, is the first
 // thing lane-scattered loads exhaust here).
 //
-//   * A small pre-kernel writes D transposed and zero-padded (Dt: 32*tiles_n rows
-//     of Kpad values), so that k is the contiguous index of BOTH MFMA operands.
 //   * The grid is persistent.  A workgroup is pinned to one chunk of j (CJ rows),
 //     one group of four k-slices and one column tile, and walks a strided list of
 //     i.  The factor rows C(chunk, tile) are copied to LDS once, at set-up.
-//   * A wavefront owns ONE k-slice of SL = 256 bytes for its whole life.  The Dt
-//     values of its slice (32 l x SL k) are loaded into registers once, so D costs
-//     no further traffic.  The four wavefronts of a workgroup take neighbouring
+//   * A wavefront owns ONE k-slice of SL = 256 bytes for its whole life.  The D
+//     values of its slice (SL k x 32 l) are loaded into registers once, already in
+//     the transposed MFMA operand layout, so D costs no further traffic.  The four wavefronts of a workgroup take neighbouring
 //     slices of the same rows (1 KiB contiguous per row).
 //   * The wavefront walks (i, block of RB = 32 rows).  A block's RB x SL piece of B
 //     goes global -> registers (the next block's loads are in flight during the
 //     multiply) -> a wavefront-private LDS patch -> back in MFMA operand layout.
 //     Only the wavefront that wrote the patch reads it, so ordering inside the
 //     wavefront suffices.
-//   * MFMA forms the TRANSPOSED partial product Tt(l,j) = sum_{k in slice} Dt(l,k)
+//   * MFMA forms the TRANSPOSED partial product Tt(l,j) = sum_{k in slice} D(k,l)
 //     B(j,k): a lane owns one j and several l, so the factor values C(j, l..) it
 //     needs are neighbours in the LDS copy.  The sums over j and over k-slices are
 //     both linear: after every block the lane scales its accumulators by C(j,l) and
@@ -45,11 +43,10 @@ template <typename T>
 struct MttkrpArgs {
     const T *B;        // I x J x K
     const T *C;        // J x L
-    const T *Dt;       // (32 * tiles_n) x Kpad, transposed zero-padded D
+    const T *D;        // K x L
     T *partial;        // (I * nchunks * nslices) x L: row ((i * nchunks + chunk) * nslices + slice);
                        // the output itself when nchunks * nslices == 1
     int64_t I, J, K, L;
-    int64_t Kpad;      // K rounded up to a multiple of 4 * SL
     int nchunks;       // ceil(J / CJ)
     int nslices;       // ceil(K / SL)
     int kgroups;       // ceil(nslices / 4): k-slices are handed out four per workgroup
@@ -77,18 +74,6 @@ struct MttkrpCfg {
     static constexpr int LDS_BYTES = (NW * PATCH + C_ELEMS) * (int)sizeof(T);
     static_assert(SL % KG == 0 && RB % MF::NB == 0 && LB <= 2 && 64 % CPR == 0 && CJ % RB == 0, "tile shape");
 };
-
-// Dt(l, k) = D(k, l), zero outside K x L.
-template <typename T>
-__global__ void __launch_bounds__(256)
-mttkrp_transpose_kernel(const T *__restrict__ D, T *__restrict__ Dt, int64_t K, int64_t L,
-                        int64_t Kpad, int64_t Lpad) {
-    const int64_t n = Kpad * Lpad;
-    for (int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x; m < n; m += (int64_t)gridDim.x * 256) {
-        const int64_t l = m / Kpad, k = m % Kpad;
-        Dt[m] = (l < L && k < K) ? D[k * L + l] : T(0);
-    }
-}
 
 // A(i, l) = sum of the per_i partial rows of i, in row order.  One workgroup per i:
 // thread (r, l) adds rows r, r+8, ..., then the eight strands are added in order.
@@ -180,14 +165,21 @@ mttkrp_kernel(const MttkrpArgs<T> args) {
     const int64_t k0 = (int64_t)slice * SL;                    // this wavefront's k-slice
     if (k0 >= K || ig >= I) return;       // wavefront-uniform
 
-    // Dt operand of this slice, kept in registers: d[lb][g] holds k = k0 + g*KG + ls*KV + (0..KV-1)
+    // The D operand of this slice, transposed into registers once: d[lb][g][t] = D(k, l) for
+    // k = k0 + g*KG + ls*KV + t and l = n0 + li (binary32) or n0 + 2*li + lb (binary64); zero
+    // outside K x L.  Lanes with neighbouring li read neighbouring l.
     vec_t d[LB][NKG];
 #pragma unroll
-    for (int lb = 0; lb < LB; ++lb)
+    for (int lb = 0; lb < LB; ++lb) {
+        const int64_t l = n0 + (LB == 1 ? li : 2 * li + lb);
 #pragma unroll
         for (int g = 0; g < NKG; ++g)
-            d[lb][g] = *reinterpret_cast<const vec_t *>(
-                args.Dt + (n0 + (LB == 1 ? li : 2 * li + lb)) * args.Kpad + k0 + g * KG + ls * KV);
+#pragma unroll
+            for (int t = 0; t < KV; ++t) {
+                const int64_t k = k0 + g * KG + ls * KV + t;
+                d[lb][g][t] = (!GUARD || (k < K && l < L)) ? args.D[k * L + l] : T(0);
+            }
+    }
 
     T lsum[LB][MF::NACC];                 // running sum for l = mttkrp_l_of(v, lb, lane)
 #pragma unroll
