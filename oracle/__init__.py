@@ -45,7 +45,9 @@ def _bind(path: str):
     lib.oracle_innerprod.argtypes = [ci, i64, i64, i64, vp, vp, vp]
     lib.oracle_ttm.argtypes = [ci, i64, i64, i64, i64, vp, vp, vp]
     lib.oracle_mttkrp.argtypes = [ci, i64, i64, i64, i64, vp, vp, vp, vp]
-    for f in (lib.oracle_gemm, lib.oracle_ttv, lib.oracle_innerprod, lib.oracle_ttm,
+    lib.oracle_ttm_mode.argtypes = [ci, ci, i64, i64, i64, i64, vp, vp, vp]
+    lib.oracle_mttkrp_mode.argtypes = [ci, ci, i64, i64, i64, i64, vp, vp, vp, vp]
+    for f in (lib.oracle_ttm_mode, lib.oracle_mttkrp_mode, lib.oracle_gemm, lib.oracle_ttv, lib.oracle_innerprod, lib.oracle_ttm,
               lib.oracle_mttkrp, lib.oracle_version, lib.oracle_long_double_digits,
               lib.oracle_max_threads):
         f.restype = ci
@@ -84,6 +86,8 @@ class Variant:
     def innerprod(self, *a, **k): return self._call("innerprod", *a, **k)
     def ttm(self, *a, **k): return self._call("ttm", *a, **k)
     def mttkrp(self, *a, **k): return self._call("mttkrp", *a, **k)
+    def ttm_mode(self, *a, **k): return self._call("ttm_mode", *a, **k)
+    def mttkrp_mode(self, *a, **k): return self._call("mttkrp_mode", *a, **k)
 
 
 def max_threads() -> int:
@@ -187,4 +191,33 @@ def mttkrp(B: np.ndarray, C: np.ndarray, D: np.ndarray) -> np.ndarray:
     B, C, D = (np.ascontiguousarray(x) for x in (B, C, D))
     out = np.empty((I, L), dtype=np.float64)
     _check(_load().oracle_mttkrp(_dt(B, C, D), I, J, K, L, _p(B), _p(C), _p(D), _p(out)))
+    return out
+
+
+def ttm_mode(mode: int, B: np.ndarray, C: np.ndarray) -> np.ndarray:
+    """Tensor times matrix along `mode` of B: that mode's extent is replaced by C's columns."""
+    if B.ndim != 3 or C.ndim != 2 or mode not in (0, 1, 2) or C.shape[0] != B.shape[mode]:
+        raise ValueError("C must have one row per index of the contracted mode")
+    I, J, K = B.shape
+    R = C.shape[1]
+    B, C = np.ascontiguousarray(B), np.ascontiguousarray(C)
+    shape = [I, J, K]
+    shape[mode] = R
+    out = np.empty(shape, dtype=np.float64)
+    _check(_load().oracle_ttm_mode(_dt(B, C), mode, I, J, K, R, _p(B), _p(C), _p(out)))
+    return out
+
+
+def mttkrp_mode(mode: int, B: np.ndarray, C: np.ndarray, D: np.ndarray) -> np.ndarray:
+    """MTTKRP along `mode` of B; C and D are the factors of the other two modes, in mode order."""
+    if B.ndim != 3 or C.ndim != 2 or D.ndim != 2 or mode not in (0, 1, 2):
+        raise ValueError("bad operands")
+    others = [m for m in (0, 1, 2) if m != mode]
+    if C.shape[0] != B.shape[others[0]] or D.shape[0] != B.shape[others[1]] or C.shape[1] != D.shape[1]:
+        raise ValueError("factor shapes do not match B")
+    I, J, K = B.shape
+    L = C.shape[1]
+    B, C, D = (np.ascontiguousarray(x) for x in (B, C, D))
+    out = np.empty((B.shape[mode], L), dtype=np.float64)
+    _check(_load().oracle_mttkrp_mode(_dt(B, C, D), mode, I, J, K, L, _p(B), _p(C), _p(D), _p(out)))
     return out

@@ -21,6 +21,17 @@
  *   ttm        A(i,j,l) = sum_k   B(i,j,k) * C(k,l)          (evaluation list)
  *   mttkrp     A(i,l)   = sum_jk  B(i,j,k) * C(j,l) * D(k,l) (evaluation list)
  *
+ * and the same two higher-order contractions taken along the other modes of B
+ * (the evaluation section names TTM and MTTKRP as the building blocks of Tucker
+ * and canonical polyadic decompositions, which apply them along every mode):
+ *
+ *   ttm_mode     0: A(r,j,k) = sum_i B(i,j,k) * C(i,r)
+ *                1: A(i,r,k) = sum_j B(i,j,k) * C(j,r)
+ *                2: A(i,j,r) = sum_k B(i,j,k) * C(k,r)            (= ttm)
+ *   mttkrp_mode  0: A(i,l)   = sum_jk B(i,j,k) * C(j,l) * D(k,l)  (= mttkrp)
+ *                1: A(j,l)   = sum_ik B(i,j,k) * C(i,l) * D(k,l)
+ *                2: A(k,l)   = sum_ij B(i,j,k) * C(i,l) * D(j,l)
+ *
  * "Variables used only on the right-hand side are sum reductions over their
  * domain" (background section): every sum runs over the full extent.
  *
@@ -199,6 +210,103 @@ int oracle_mttkrp(int dt, int64_t I, int64_t J, int64_t K, int64_t L,
                          * ld_elem(D, dt, k * L + l);
             out[i * L + l] = (double)s;
         }
+    }
+    return ORACLE_OK;
+}
+
+/*
+ * Tensor times matrix along mode `mode` of B (IxJxK).  C has one row per index
+ * of the contracted mode and R columns; the output has that mode replaced by R:
+ *   mode 0: out(r,j,k) = sum_i B(i,j,k) * C(i,r)     C is IxR, out is RxJxK
+ *   mode 1: out(i,r,k) = sum_j B(i,j,k) * C(j,r)     C is JxR, out is IxRxK
+ *   mode 2: out(i,j,r) = sum_k B(i,j,k) * C(k,r)     C is KxR, out is IxJxR
+ * Each case is its own loop nest, written out.
+ */
+int oracle_ttm_mode(int dt, int mode, int64_t I, int64_t J, int64_t K, int64_t R,
+                    const void *B, const void *C, double *out)
+{
+    if (dt != ORACLE_F32 && dt != ORACLE_F64) return ORACLE_BAD_ARG;
+    if (I < 0 || J < 0 || K < 0 || R < 0 || mode < 0 || mode > 2) return ORACLE_BAD_ARG;
+    if (mode == 0) {
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int64_t r = 0; r < R; ++r)
+            for (int64_t j = 0; j < J; ++j)
+                for (int64_t k = 0; k < K; ++k) {
+                    acc_t s = 0;
+                    for (int64_t i = 0; i < I; ++i)
+                        s += ld_elem(B, dt, (i * J + j) * K + k) * ld_elem(C, dt, i * R + r);
+                    out[(r * J + j) * K + k] = (double)s;
+                }
+    } else if (mode == 1) {
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int64_t i = 0; i < I; ++i)
+            for (int64_t r = 0; r < R; ++r)
+                for (int64_t k = 0; k < K; ++k) {
+                    acc_t s = 0;
+                    for (int64_t j = 0; j < J; ++j)
+                        s += ld_elem(B, dt, (i * J + j) * K + k) * ld_elem(C, dt, j * R + r);
+                    out[(i * R + r) * K + k] = (double)s;
+                }
+    } else {
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int64_t i = 0; i < I; ++i)
+            for (int64_t j = 0; j < J; ++j)
+                for (int64_t r = 0; r < R; ++r) {
+                    acc_t s = 0;
+                    for (int64_t k = 0; k < K; ++k)
+                        s += ld_elem(B, dt, (i * J + j) * K + k) * ld_elem(C, dt, k * R + r);
+                    out[(i * J + j) * R + r] = (double)s;
+                }
+    }
+    return ORACLE_OK;
+}
+
+/*
+ * MTTKRP along mode `mode` of B (IxJxK): the output has one row per index of that
+ * mode; C and D are the factor matrices of the two other modes, in mode order:
+ *   mode 0: out(i,l) = sum_j sum_k B(i,j,k) * C(j,l) * D(k,l)    C JxL, D KxL
+ *   mode 1: out(j,l) = sum_i sum_k B(i,j,k) * C(i,l) * D(k,l)    C IxL, D KxL
+ *   mode 2: out(k,l) = sum_i sum_j B(i,j,k) * C(i,l) * D(j,l)    C IxL, D JxL
+ * The literal triple product is summed, earlier mode outermost.
+ */
+int oracle_mttkrp_mode(int dt, int mode, int64_t I, int64_t J, int64_t K, int64_t L,
+                       const void *B, const void *C, const void *D, double *out)
+{
+    if (dt != ORACLE_F32 && dt != ORACLE_F64) return ORACLE_BAD_ARG;
+    if (I < 0 || J < 0 || K < 0 || L < 0 || mode < 0 || mode > 2) return ORACLE_BAD_ARG;
+    if (mode == 0) {
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int64_t i = 0; i < I; ++i)
+            for (int64_t l = 0; l < L; ++l) {
+                acc_t s = 0;
+                for (int64_t j = 0; j < J; ++j)
+                    for (int64_t k = 0; k < K; ++k)
+                        s += ld_elem(B, dt, (i * J + j) * K + k) * ld_elem(C, dt, j * L + l)
+                             * ld_elem(D, dt, k * L + l);
+                out[i * L + l] = (double)s;
+            }
+    } else if (mode == 1) {
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int64_t j = 0; j < J; ++j)
+            for (int64_t l = 0; l < L; ++l) {
+                acc_t s = 0;
+                for (int64_t i = 0; i < I; ++i)
+                    for (int64_t k = 0; k < K; ++k)
+                        s += ld_elem(B, dt, (i * J + j) * K + k) * ld_elem(C, dt, i * L + l)
+                             * ld_elem(D, dt, k * L + l);
+                out[j * L + l] = (double)s;
+            }
+    } else {
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int64_t k = 0; k < K; ++k)
+            for (int64_t l = 0; l < L; ++l) {
+                acc_t s = 0;
+                for (int64_t i = 0; i < I; ++i)
+                    for (int64_t j = 0; j < J; ++j)
+                        s += ld_elem(B, dt, (i * J + j) * K + k) * ld_elem(C, dt, i * L + l)
+                             * ld_elem(D, dt, j * L + l);
+                out[k * L + l] = (double)s;
+            }
     }
     return ORACLE_OK;
 }

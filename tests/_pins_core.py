@@ -60,6 +60,31 @@ def run(o):
         for i, l in itertools.product(range(2), range(4)):
             ex = sum(F(T[i, j, k]) * F(Cf[j, l]) * F(Df[k, l]) for j, k in itertools.product(range(3), range(6)))
             assert near(out[i, l], ex, ulps=4)
+        # the same two contractions along every mode of the tensor
+        for mode in (0, 1, 2):
+            shape = T.shape
+            a, b = [m for m in (0, 1, 2) if m != mode]
+            Cn = t(65, 1, (shape[mode], 4))
+            out = o.ttm_mode(mode, T, Cn)
+            oshape = list(shape)
+            oshape[mode] = 4
+            assert out.shape == tuple(oshape)
+            for idx in itertools.product(*(range(n) for n in oshape)):
+                ex = Fraction(0)
+                for x in range(shape[mode]):
+                    src = list(idx)
+                    src[mode] = x
+                    ex += F(T[tuple(src)]) * F(Cn[x, idx[mode]])
+                assert near(out[idx], ex)
+            Ca, Db = t(66, 1, (shape[a], 3)), t(66, 2, (shape[b], 3))
+            out = o.mttkrp_mode(mode, T, Ca, Db)
+            for x, l in itertools.product(range(shape[mode]), range(3)):
+                ex = Fraction(0)
+                for p_, q_ in itertools.product(range(shape[a]), range(shape[b])):
+                    src = [0, 0, 0]
+                    src[mode], src[a], src[b] = x, p_, q_
+                    ex += F(T[tuple(src)]) * F(Ca[p_, l]) * F(Db[q_, l])
+                assert near(out[x, l], ex, ulps=4)
     # binary64 sums must be carried wider than binary64: a cancelling sum only a 64-bit
     # significand gets right (1 + 2^-60 - 1 keeps the small term)
     a = np.array([[1.0, 2.0 ** -60, -1.0]])

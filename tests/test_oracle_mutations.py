@@ -26,7 +26,18 @@ MUTATIONS = [
     ("innerprod_wrong_pairing", "ld_elem(B, dt, m) * ld_elem(C, dt, m);", "ld_elem(B, dt, m) * ld_elem(C, dt, lo + hi - 1 - m);"),
     ("ttm_wrong_column", "ld_elem(C, dt, k * L + l);", "ld_elem(C, dt, k * L + (L - 1 - l));"),
     ("mttkrp_dropped_factor", "\n                         * ld_elem(D, dt, k * L + l);", ";"),
-    ("mttkrp_swapped_factor_rows", "ld_elem(C, dt, j * L + l)", "ld_elem(C, dt, (J - 1 - j) * L + l)"),
+    ("mttkrp_swapped_factor_rows", "ld_elem(C, dt, j * L + l)\n                         *",
+     "ld_elem(C, dt, (J - 1 - j) * L + l)\n                         *"),
+    ("ttm_mode0_transposed_factor", "ld_elem(C, dt, i * R + r);", "ld_elem(C, dt, r * I + i);"),
+    ("ttm_mode1_output_misplaced", "out[(i * R + r) * K + k] = (double)s;", "out[(i * K + k) * R + r] = (double)s;"),
+    ("ttm_mode1_dropped_term", "for (int64_t j = 0; j < J; ++j)\n                        s += ld_elem(B, dt, (i * J + j) * K + k) * ld_elem(C, dt, j * R + r);",
+     "for (int64_t j = 1; j < J; ++j)\n                        s += ld_elem(B, dt, (i * J + j) * K + k) * ld_elem(C, dt, j * R + r);"),
+    ("mttkrp_mode1_dropped_term", "for (int64_t i = 0; i < I; ++i)\n                    for (int64_t k = 0; k < K; ++k)",
+     "for (int64_t i = 0; i < I - 1; ++i)\n                    for (int64_t k = 0; k < K; ++k)"),
+    ("mttkrp_mode1_dropped_factor", "ld_elem(C, dt, i * L + l)\n                             * ld_elem(D, dt, k * L + l);",
+     "ld_elem(C, dt, i * L + l);"),
+    ("mttkrp_mode2_swapped_factor_rows", "ld_elem(D, dt, j * L + l);", "ld_elem(D, dt, (J - 1 - j) * L + l);"),
+    ("mttkrp_mode2_output_transposed", "out[k * L + l] = (double)s;", "out[l * K + k] = (double)s;"),
     ("narrow_accumulator", "typedef long double acc_t;", "typedef double acc_t;"),
 ]
 
