@@ -51,7 +51,8 @@ typedef enum {
     DISTAL_ERR_STRIDE = 4,    /* a leading dimension is smaller than its row     */
     DISTAL_ERR_ALIAS = 5,     /* output pointer equals an input pointer          */
     DISTAL_ERR_WORKSPACE = 6, /* workspace missing, misaligned or too small      */
-    DISTAL_ERR_LAUNCH = 7     /* the HIP runtime refused a kernel launch         */
+    DISTAL_ERR_LAUNCH = 7,    /* the HIP runtime refused a kernel launch         */
+    DISTAL_ERR_MODE = 8       /* mode is not 0, 1 or 2                           */
 } distal_status;
 
 /*
@@ -77,6 +78,19 @@ int distal_gemm(distal_dtype dt, int64_t M, int64_t N, int64_t K,
  */
 int distal_ttm(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L,
                const void *B, const void *C, void *A, void *stream);
+
+/*
+ * Tensor times matrix along any mode of B (I x J x K).  C has one row per index
+ * of the contracted mode and R columns; A is B with that mode's extent replaced
+ * by R.  The evaluation section names TTM as a building block of the Tucker
+ * decomposition, which applies it along every mode; its list states mode 2.
+ *   mode 0: A(r,j,k) = sum_i B(i,j,k) * C(i,r)     C: I x R, A: R x J x K
+ *   mode 1: A(i,r,k) = sum_j B(i,j,k) * C(j,r)     C: J x R, A: I x R x K
+ *   mode 2: A(i,j,r) = sum_k B(i,j,k) * C(k,r)     C: K x R, A: I x J x R  (= distal_ttm)
+ * All dense; A is overwritten.  B is read in place (no transposed copy is made).
+ */
+int distal_ttm_mode(distal_dtype dt, int mode, int64_t I, int64_t J, int64_t K, int64_t R,
+                    const void *B, const void *C, void *A, void *stream);
 
 /*
  * Matricized tensor times Khatri-Rao product:

@@ -19,11 +19,13 @@ OK = 0
 STATUS_NAMES = {
     0: "DISTAL_OK", 1: "DISTAL_ERR_NULL", 2: "DISTAL_ERR_SHAPE", 3: "DISTAL_ERR_DTYPE",
     4: "DISTAL_ERR_STRIDE", 5: "DISTAL_ERR_ALIAS", 6: "DISTAL_ERR_WORKSPACE", 7: "DISTAL_ERR_LAUNCH",
+    8: "DISTAL_ERR_MODE",
 }
 
 # every symbol include/distal.h declares
 EXPORTS = (
     "distal_gemm", "distal_ttm", "distal_mttkrp", "distal_ttv", "distal_innerprod",
+    "distal_ttm_mode",
     "distal_mttkrp_workspace_bytes", "distal_innerprod_workspace_bytes",
     "distal_status_string", "distal_version",
 )
@@ -52,6 +54,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     i64, vp, ci, sz = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     lib.distal_gemm.argtypes = [ci, i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, vp]
     lib.distal_ttm.argtypes = [ci, i64, i64, i64, i64, vp, vp, vp, vp]
+    lib.distal_ttm_mode.argtypes = [ci, ci, i64, i64, i64, i64, vp, vp, vp, vp]
     lib.distal_mttkrp.argtypes = [ci, i64, i64, i64, i64, vp, vp, vp, vp, vp, sz, vp]
     lib.distal_ttv.argtypes = [ci, i64, i64, i64, vp, vp, vp, vp]
     lib.distal_innerprod.argtypes = [ci, i64, i64, i64, vp, vp, vp, vp, sz, vp]
@@ -60,7 +63,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.distal_status_string.argtypes = [ci]
     lib.distal_version.argtypes = []
     for name in ("distal_gemm", "distal_ttm", "distal_mttkrp", "distal_ttv", "distal_innerprod",
-                 "distal_version"):
+                 "distal_ttm_mode", "distal_version"):
         getattr(lib, name).restype = ci
     lib.distal_mttkrp_workspace_bytes.restype = sz
     lib.distal_innerprod_workspace_bytes.restype = sz
@@ -180,6 +183,24 @@ def distal_ttm(B, C, A):
     with _torch().cuda.device(B.device):
         rc = load_library().distal_ttm(dt, I, J, K, L, _ptr(B), _ptr(C), _ptr(A), _stream(B))
     _raise(rc, "distal_ttm")
+    return A
+
+
+def distal_ttm_mode(mode, B, C, A):
+    """Tensor times matrix along `mode` of B: A is B with that mode's extent replaced by C's columns."""
+    dt = _same(B, C, A)
+    _dense(B, "B", 3), _dense(C, "C", 2), _dense(A, "A", 3)
+    I, J, K = B.shape
+    if mode not in (0, 1, 2):
+        raise ValueError("mode must be 0, 1 or 2")
+    R = C.shape[1]
+    want = [I, J, K]
+    want[mode] = R
+    if C.shape[0] != B.shape[mode] or list(A.shape) != want:
+        raise ValueError("shapes do not match a mode-%d tensor-times-matrix product" % mode)
+    with _torch().cuda.device(B.device):
+        rc = load_library().distal_ttm_mode(dt, mode, I, J, K, R, _ptr(B), _ptr(C), _ptr(A), _stream(B))
+    _raise(rc, "distal_ttm_mode")
     return A
 
 

@@ -58,23 +58,34 @@ bool allow_lds(Kern kern, int bytes, std::atomic<bool> (&done)[kMaxDevices]) {
     return true;
 }
 
-template <typename T, int BM, int BN, int BK, int WM, int WN, bool FAST>
-int launch_contract(ContractArgs<T> a, hipStream_t stream) {
-    typedef ContractCfg<T, BM, BN, BK, WM, WN> Cfg;
+constexpr int64_t kMaxGridY = 65535;
+
+// One launch per run of at most kMaxGridY problems of the batch (blockIdx.y picks the problem).
+template <typename T, int BM, int BN, int BK, int WM, int WN, bool FAST, bool TA>
+int launch_contract(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
+    typedef ContractCfg<T, BM, BN, BK, WM, WN, TA> Cfg;
     a.tiles_m = (int)((a.M + BM - 1) / BM);
     a.tiles_n = (int)((a.N + BN - 1) / BN);
     const int64_t nblocks = (int64_t)a.tiles_m * a.tiles_n;
     static std::atomic<bool> done[kMaxDevices];
-    if constexpr (FAST) {
-        auto kern = contract_fast_kernel<T, BM, BN, BK, WM, WN>;
-        if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
-        hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
-    } else {
-        auto kern = contract_kernel<T, BM, BN, BK, WM, WN>;
-        if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
-        hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
+    for (int64_t first = 0; first < batch; first += kMaxGridY) {
+        const int64_t count = batch - first < kMaxGridY ? batch - first : kMaxGridY;
+        const dim3 grid((unsigned)nblocks, (unsigned)count);
+        if constexpr (FAST) {
+            auto kern = contract_fast_kernel<T, BM, BN, BK, WM, WN, TA>;
+            if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
+            hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
+        } else {
+            auto kern = contract_kernel<T, BM, BN, BK, WM, WN, TA>;
+            if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
+            hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
+        }
+        if (hipGetLastError() != hipSuccess) return DISTAL_ERR_LAUNCH;
+        a.A += count * a.batch_a;
+        a.B += count * a.batch_b;
+        a.C += count * a.batch_c;
     }
-    return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
+    return DISTAL_OK;
 }
 
 template <typename T>
@@ -95,12 +106,23 @@ int launch_fill(T *out, int64_t rows, int64_t cols, int64_t ld, hipStream_t stre
 // everything else takes the guarded 128 x 128 kernel.
 constexpr int64_t kBigTileMinTiles = 256;   // below this a grid of big tiles cannot fill 256 CUs
 
-template <typename T>
+// TA = false: C = [C +] A * B with A stored M x K.  TA = true: the left operand is stored
+// K x M (C = [C +] At^T * B), the form a contraction over a non-last tensor mode takes.
+// `batch` independent problems, operand p of problem n at p + n * stride_p (elements).
+template <typename T, bool TA = false>
 int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B, int64_t ldb,
-           T *C, int64_t ldc, int accumulate, hipStream_t stream) {
+           T *C, int64_t ldc, int accumulate, hipStream_t stream, int64_t batch = 1,
+           int64_t stride_a = 0, int64_t stride_b = 0, int64_t stride_c = 0) {
     constexpr int VEC = 16 / (int)sizeof(T);
-    if (M == 0 || N == 0) return DISTAL_OK;
-    if (K == 0) return accumulate ? DISTAL_OK : launch_fill<T>(C, M, N, ldc, stream);
+    if (M == 0 || N == 0 || batch == 0) return DISTAL_OK;
+    if (K == 0) {
+        if (accumulate) return DISTAL_OK;
+        for (int64_t n = 0; n < batch; ++n) {
+            const int rc = launch_fill<T>(C + n * stride_c, M, N, ldc, stream);
+            if (rc != DISTAL_OK) return rc;
+        }
+        return DISTAL_OK;
+    }
     const int64_t tm = (M + 127) / 128, tn = (N + 127) / 128;
     int64_t nblocks;
     if (!mul_ok(tm, tn, &nblocks) || nblocks > std::numeric_limits<int>::max()) return DISTAL_ERR_SHAPE;
@@ -108,20 +130,23 @@ int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
     a.A = A; a.B = B; a.C = C;
     a.M = M; a.N = N; a.K = K;
     a.lda = lda; a.ldb = ldb; a.ldc = ldc;
+    a.batch_a = stride_a; a.batch_b = stride_b; a.batch_c = stride_c;
     a.accumulate = accumulate ? 1 : 0;
-    a.a_vec_ok = aligned16(A) && lda % VEC == 0;
-    a.b_vec_ok = aligned16(B) && ldb % VEC == 0;
-    a.c_vec_ok = aligned16(C) && ldc % VEC == 0;
+    a.a_vec_ok = aligned16(A) && lda % VEC == 0 && stride_a % VEC == 0;
+    a.b_vec_ok = aligned16(B) && ldb % VEC == 0 && stride_b % VEC == 0;
+    a.c_vec_ok = aligned16(C) && ldc % VEC == 0 && stride_c % VEC == 0;
     const bool whole = a.a_vec_ok && a.b_vec_ok && a.c_vec_ok && K % 16 == 0;
     if constexpr (sizeof(T) == 4) {
-        if (whole && M % 256 == 0 && N % 256 == 0 && (M / 256) * (N / 256) >= kBigTileMinTiles)
-            return launch_contract<T, 256, 256, 16, 4, 4, true>(a, stream);
+        if (whole && M % 256 == 0 && N % 256 == 0 && (M / 256) * (N / 256) * batch >= kBigTileMinTiles)
+            return launch_contract<T, 256, 256, 16, 4, 4, true, TA>(a, batch, stream);
     } else {
-        if (whole && M % 256 == 0 && N % 128 == 0 && K >= 4096 && (M / 256) * (N / 128) >= kBigTileMinTiles)
-            return launch_contract<T, 256, 128, 16, 4, 2, true>(a, stream);
+        if (whole && M % 256 == 0 && N % 128 == 0 && K >= 4096 &&
+            (M / 256) * (N / 128) * batch >= kBigTileMinTiles)
+            return launch_contract<T, 256, 128, 16, 4, 2, true, TA>(a, batch, stream);
     }
-    if (whole && M % 128 == 0 && N % 128 == 0) return launch_contract<T, 128, 128, 16, 2, 2, true>(a, stream);
-    return launch_contract<T, 128, 128, 16, 2, 2, false>(a, stream);
+    if (whole && M % 128 == 0 && N % 128 == 0)
+        return launch_contract<T, 128, 128, 16, 2, 2, true, TA>(a, batch, stream);
+    return launch_contract<T, 128, 128, 16, 2, 2, false, TA>(a, batch, stream);
 }
 
 int check_dtype(int dt) { return (dt == DISTAL_F32 || dt == DISTAL_F64) ? DISTAL_OK : DISTAL_ERR_DTYPE; }
@@ -305,6 +330,7 @@ const char *distal_status_string(int status) {
         case DISTAL_ERR_ALIAS: return "output aliases an input";
         case DISTAL_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case DISTAL_ERR_LAUNCH: return "kernel launch failed";
+        case DISTAL_ERR_MODE: return "mode is not 0, 1 or 2";
         default: return "unknown status";
     }
 }
@@ -346,6 +372,41 @@ int distal_ttm(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L, cons
     if (dt == DISTAL_F64)
         return gemm_t<double>(ij, L, K, (const double *)B, ldk, (const double *)C, ldl, (double *)A, ldl, 0, s);
     return gemm_t<float>(ij, L, K, (const float *)B, ldk, (const float *)C, ldl, (float *)A, ldl, 0, s);
+}
+
+int distal_ttm_mode(distal_dtype dt, int mode, int64_t I, int64_t J, int64_t K, int64_t R, const void *B,
+                    const void *C, void *A, void *stream) {
+    if (check_dtype(dt) != DISTAL_OK) return DISTAL_ERR_DTYPE;
+    if (mode < 0 || mode > 2) return DISTAL_ERR_MODE;
+    if (mode == 2) return distal_ttm(dt, I, J, K, R, B, C, A, stream);
+    if (I < 0 || J < 0 || K < 0 || R < 0) return DISTAL_ERR_SHAPE;
+    const int64_t X = mode == 0 ? I : J;                    // the contracted extent
+    int64_t nb, na, nc, jk;
+    if (!tensor_elems(I, J, K, &nb) || !mul_ok(J, K, &jk) || !mul_ok(X, R, &nc) ||
+        !tensor_elems(mode == 0 ? R : I, mode == 0 ? J : R, K, &na))
+        return DISTAL_ERR_SHAPE;
+    if ((nb > 0 && R > 0 && !B) || (nc > 0 && na > 0 && !C) || (na > 0 && !A)) return DISTAL_ERR_NULL;
+    if (na > 0 && (A == B || A == C)) return DISTAL_ERR_ALIAS;
+    if (na == 0) return DISTAL_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool f64 = dt == DISTAL_F64;
+    if (X == 0)   // empty sum: the whole (contiguous) output is zero
+        return f64 ? launch_fill<double>((double *)A, 1, na, na, s) : launch_fill<float>((float *)A, 1, na, na, s);
+    const int64_t ldr = R > 0 ? R : 1;
+    if (mode == 0) {
+        // A(r, jk) = sum_i C(i, r) * B(i, jk): one product with the left operand stored I x R
+        if (f64)
+            return gemm_t<double, true>(R, jk, I, (const double *)C, ldr, (const double *)B, jk, (double *)A, jk, 0, s);
+        return gemm_t<float, true>(R, jk, I, (const float *)C, ldr, (const float *)B, jk, (float *)A, jk, 0, s);
+    }
+    // mode 1: for every i, A_i(r, k) = sum_j C(j, r) * B_i(j, k): a batch of I products sharing C
+    int64_t rk;
+    if (!mul_ok(R, K, &rk)) return DISTAL_ERR_SHAPE;
+    if (f64)
+        return gemm_t<double, true>(R, K, J, (const double *)C, ldr, (const double *)B, K, (double *)A, K, 0, s,
+                                    I, 0, jk, rk);
+    return gemm_t<float, true>(R, K, J, (const float *)C, ldr, (const float *)B, K, (float *)A, K, 0, s,
+                               I, 0, jk, rk);
 }
 
 size_t distal_mttkrp_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L) {

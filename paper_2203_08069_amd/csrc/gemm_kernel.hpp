@@ -21,6 +21,12 @@
 // blocks that share an LDS read take interleaved columns (lane jj of block q
 // owns column jj*CV + q), so a lane reads CV neighbouring B values at once and
 // finally owns CV neighbouring outputs, which it stores as one vector.
+//
+// TA = true contracts over the ROWS of the left operand (C = At^T * B with At stored
+// K x M, row-major): the contractions over a non-last mode of a tensor have this
+// form.  The left slab is then staged like the right one (k rows, m contiguous) and
+// read the same way: RV row blocks that share an LDS read own interleaved rows.
+// blockIdx.y selects one problem of a batch (operands advance by fixed strides).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -71,7 +77,7 @@ template <> struct Mfma<float> {           // v_mfma_f32_32x32x2_f32
 
 template <typename T>
 struct ContractArgs {
-    const T *A;          // left operand rows (M x K view), row stride lda
+    const T *A;          // left operand: M x K (TA = false) or K x M (TA = true), row stride lda
     const T *B;          // right operand (K x N), row stride ldb
     T *C;                // output (M x N), row stride ldc
     int64_t M, N, K;
@@ -79,6 +85,7 @@ struct ContractArgs {
     int accumulate;
     int tiles_m, tiles_n;
     int a_vec_ok, b_vec_ok, c_vec_ok;   // 16-byte vector access is legal on that operand
+    int64_t batch_a, batch_b, batch_c;  // element strides between the problems of a batch (blockIdx.y)
 };
 
 // Block id -> output tile.  Hardware hands consecutive workgroup ids to the 8
@@ -102,7 +109,7 @@ __device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m,
     tn = r / gs;
 }
 
-template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N>
+template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TA = false>
 struct ContractCfg {
     typedef Mfma<T> MF;
     static constexpr int NT = 64 * WAVES_M * WAVES_N;
@@ -113,27 +120,119 @@ struct ContractCfg {
     static constexpr int MI = WTM / MF::MB, NI = WTN / MF::NB;
     static constexpr int CV = (NI % 2 == 0) ? 2 : 1;      // column blocks sharing one B read
     static constexpr int NG = NI / CV;
-    static constexpr int LDA_S = BK + VEC;                // LDS row strides (elements): +16 B
+    static constexpr int RV = (TA && MI % 2 == 0) ? 2 : 1; // row blocks sharing one A read (TA only)
+    static constexpr int MG = MI / RV;
+    static constexpr int LDA_S = (TA ? BM : BK) + VEC;    // LDS row strides (elements): +16 B
     static constexpr int LDB_S = BN + VEC;
-    static constexpr int A_ELEMS = BM * LDA_S, B_ELEMS = BK * LDB_S;
+    static constexpr int A_ROWLEN = TA ? BM : BK;         // contiguous elements per staged A row
+    static constexpr int A_ELEMS = (TA ? BK : BM) * LDA_S, B_ELEMS = BK * LDB_S;
     static constexpr int STAGE_ELEMS = A_ELEMS + B_ELEMS;
     static constexpr int LDS_BYTES = 2 * STAGE_ELEMS * (int)sizeof(T);
     static constexpr int A_VECS = BM * (BK / VEC), B_VECS = BK * (BN / VEC);
     static constexpr int A_PER_T = (A_VECS + NT - 1) / NT, B_PER_T = (B_VECS + NT - 1) / NT;
     static constexpr int GROUP_M = (BM > BN) ? 4 : 8;     // tile rows per band (see tile_of_block)
+    static constexpr bool TRANS_A = TA;
     static_assert(BM % (WAVES_M * MF::MB) == 0 && BN % (WAVES_N * MF::NB) == 0, "tile shape");
     static_assert(BK % KG == 0, "BK must hold whole MFMA k-groups");
 };
 
-template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N>
-__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N, 2)
-contract_kernel(const ContractArgs<T> args) {
-    typedef ContractCfg<T, BM, BN, BK, WAVES_M, WAVES_N> Cfg;
+
+// Lane offsets (elements) of the operand reads inside a staged slab pair.
+template <typename Cfg>
+__device__ __forceinline__ int a_read_offset(int wm, int li, int ls) {
+    if constexpr (Cfg::TRANS_A) return (ls * Cfg::KV) * Cfg::LDA_S + wm * Cfg::WTM + li * Cfg::RV;
+    else return (wm * Cfg::WTM + li) * Cfg::LDA_S + ls * Cfg::KV;
+}
+template <typename Cfg>
+__device__ __forceinline__ int b_read_offset(int wn, int li, int ls) {
+    return Cfg::A_ELEMS + (ls * Cfg::KV) * Cfg::LDB_S + wn * Cfg::WTN + li * Cfg::CV;
+}
+
+// Output row (within the wavefront's sub-tile) of accumulator register v of row block mi.
+template <typename Cfg>
+__device__ __forceinline__ int sub_tile_row(int mi, int v, int lane) {
+    typedef typename Cfg::MF MF;
+    if constexpr (Cfg::TRANS_A)
+        return (mi / Cfg::RV) * (MF::MB * Cfg::RV) + MF::out_row(v, lane) * Cfg::RV + mi % Cfg::RV;
+    else
+        return mi * MF::MB + MF::out_row(v, lane);
+}
+
+// MFMA k-groups [KG_LO, KG_HI) of one staged slab pair; `as` and `bs` point at the lane's
+// read positions (a_read_offset / b_read_offset) of that stage.
+template <typename T, typename Cfg, int KG_LO, int KG_HI>
+__device__ __forceinline__ void mfma_groups(const T *as, const T *bs,
+                                            typename Mfma<T>::acc_t (&acc)[Cfg::MI][Cfg::NI]) {
     typedef Mfma<T> MF;
     typedef typename VecOf<T, Cfg::VEC>::type vec_t;
     typedef typename VecOf<T, Cfg::CV>::type cvec_t;
+    typedef typename VecOf<T, Cfg::RV>::type rvec_t;
+    constexpr int KV = Cfg::KV, KG = Cfg::KG, MI = Cfg::MI, NI = Cfg::NI, CV = Cfg::CV, NG = Cfg::NG;
+    constexpr int RV = Cfg::RV, MG = Cfg::MG;
+#pragma unroll
+    for (int kg = KG_LO; kg < KG_HI; ++kg) {
+        T av[KV][MI];
+        if constexpr (!Cfg::TRANS_A) {
+            vec_t a[MI];
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+                a[mi] = *reinterpret_cast<const vec_t *>(as + mi * MF::MB * Cfg::LDA_S + kg * KG);
+#pragma unroll
+            for (int t = 0; t < KV; ++t)
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi) av[t][mi] = a[mi][t];
+        } else {
+            rvec_t a[KV][MG];
+#pragma unroll
+            for (int t = 0; t < KV; ++t)
+#pragma unroll
+                for (int h = 0; h < MG; ++h)
+                    a[t][h] = *reinterpret_cast<const rvec_t *>(as + (kg * KG + t) * Cfg::LDA_S
+                                                                + h * MF::MB * RV);
+#pragma unroll
+            for (int t = 0; t < KV; ++t)
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi) {
+                    if constexpr (RV == 1) av[t][mi] = a[t][mi];
+                    else av[t][mi] = a[t][mi / RV][mi % RV];
+                }
+        }
+        cvec_t b[KV][NG];
+#pragma unroll
+        for (int t = 0; t < KV; ++t)
+#pragma unroll
+            for (int g = 0; g < NG; ++g)
+                b[t][g] = *reinterpret_cast<const cvec_t *>(bs + (kg * KG + t) * Cfg::LDB_S
+                                                            + g * MF::NB * CV);
+#pragma unroll
+        for (int t = 0; t < KV; ++t)
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) {
+                    T bv;
+                    if constexpr (CV == 1) bv = b[t][ni];
+                    else bv = b[t][ni / CV][ni % CV];
+                    acc[mi][ni] = MF::run(av[t][mi], bv, acc[mi][ni]);
+                }
+    }
+}
+
+template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TA = false>
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N, 2)
+contract_kernel(ContractArgs<T> args) {
+    typedef ContractCfg<T, BM, BN, BK, WAVES_M, WAVES_N, TA> Cfg;
+    typedef Mfma<T> MF;
+    typedef typename VecOf<T, Cfg::VEC>::type vec_t;
+    typedef typename VecOf<T, Cfg::CV>::type cvec_t;
+    typedef typename VecOf<T, Cfg::RV>::type rvec_t;
     constexpr int VEC = Cfg::VEC, KV = Cfg::KV, KG = Cfg::KG, MI = Cfg::MI, NI = Cfg::NI;
-    constexpr int CV = Cfg::CV, NG = Cfg::NG, NT = Cfg::NT;
+    constexpr int CV = Cfg::CV, NG = Cfg::NG, NT = Cfg::NT, RV = Cfg::RV, MG = Cfg::MG;
+    constexpr int ARL = Cfg::A_ROWLEN / VEC;          // 16-byte pieces per staged A row
+
+    args.A += (int64_t)blockIdx.y * args.batch_a;
+    args.B += (int64_t)blockIdx.y * args.batch_b;
+    args.C += (int64_t)blockIdx.y * args.batch_c;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     T *lds = reinterpret_cast<T *>(lds_raw);
@@ -164,20 +263,28 @@ contract_kernel(const ContractArgs<T> args) {
             for (int p = 0; p < Cfg::A_PER_T; ++p) {
                 const int v = tid + p * NT;
                 if (Cfg::A_VECS % NT != 0 && v >= Cfg::A_VECS) break;
-                const int r = v / (BK / VEC), kv = v % (BK / VEC);
-                ra[p] = *reinterpret_cast<const vec_t *>(args.A + (m0 + r) * args.lda + k0 + kv * VEC);
+                const int r = v / ARL, kv = v % ARL;
+                if constexpr (TA)
+                    ra[p] = *reinterpret_cast<const vec_t *>(args.A + (k0 + r) * args.lda + m0 + kv * VEC);
+                else
+                    ra[p] = *reinterpret_cast<const vec_t *>(args.A + (m0 + r) * args.lda + k0 + kv * VEC);
             }
         } else {
 #pragma unroll
             for (int p = 0; p < Cfg::A_PER_T; ++p) {
                 const int v = tid + p * NT;
                 if (Cfg::A_VECS % NT != 0 && v >= Cfg::A_VECS) break;
-                const int r = v / (BK / VEC), kv = v % (BK / VEC);
+                const int r = v / ARL, kv = v % ARL;
                 T tmp[VEC];
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) {
-                    const int64_t row = m0 + r, k = k0 + kv * VEC + e;
-                    tmp[e] = (row < mlimit && k < K) ? args.A[row * args.lda + k] : T(0);
+                    if constexpr (TA) {
+                        const int64_t k = k0 + r, row = m0 + kv * VEC + e;
+                        tmp[e] = (row < mlimit && k < K) ? args.A[k * args.lda + row] : T(0);
+                    } else {
+                        const int64_t row = m0 + r, k = k0 + kv * VEC + e;
+                        tmp[e] = (row < mlimit && k < K) ? args.A[row * args.lda + k] : T(0);
+                    }
                 }
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) ra[p][e] = tmp[e];
@@ -216,7 +323,7 @@ contract_kernel(const ContractArgs<T> args) {
         for (int p = 0; p < Cfg::A_PER_T; ++p) {
             const int v = tid + p * NT;
             if (Cfg::A_VECS % NT != 0 && v >= Cfg::A_VECS) break;
-            const int r = v / (BK / VEC), kv = v % (BK / VEC);
+            const int r = v / ARL, kv = v % ARL;
             *reinterpret_cast<vec_t *>(as + r * Cfg::LDA_S + kv * VEC) = ra[p];
         }
 #pragma unroll
@@ -236,35 +343,10 @@ contract_kernel(const ContractArgs<T> args) {
 #pragma unroll
             for (int v = 0; v < MF::NACC; ++v) acc[mi][ni][v] = T(0);
 
+    const int a_rd = a_read_offset<Cfg>(wm, li, ls), b_rd = b_read_offset<Cfg>(wn, li, ls);
     auto compute = [&](int stage) {
-        const T *as = lds + stage * Cfg::STAGE_ELEMS + (wm * Cfg::WTM + li) * Cfg::LDA_S + ls * KV;
-        const T *bs = lds + stage * Cfg::STAGE_ELEMS + Cfg::A_ELEMS + (ls * KV) * Cfg::LDB_S
-                      + wn * Cfg::WTN + li * CV;
-#pragma unroll
-        for (int kg = 0; kg < BK / KG; ++kg) {
-            vec_t a[MI];
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-                a[mi] = *reinterpret_cast<const vec_t *>(as + mi * MF::MB * Cfg::LDA_S + kg * KG);
-            cvec_t b[KV][NG];
-#pragma unroll
-            for (int t = 0; t < KV; ++t)
-#pragma unroll
-                for (int g = 0; g < NG; ++g)
-                    b[t][g] = *reinterpret_cast<const cvec_t *>(bs + (kg * KG + t) * Cfg::LDB_S
-                                                                + g * MF::NB * CV);
-#pragma unroll
-            for (int t = 0; t < KV; ++t)
-#pragma unroll
-                for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                    for (int ni = 0; ni < NI; ++ni) {
-                        T bv;
-                        if constexpr (CV == 1) bv = b[t][ni];
-                        else bv = b[t][ni / CV][ni % CV];
-                        acc[mi][ni] = MF::run(a[mi][t], bv, acc[mi][ni]);
-                    }
-        }
+        const T *st = lds + stage * Cfg::STAGE_ELEMS;
+        mfma_groups<T, Cfg, 0, BK / KG>(st + a_rd, st + b_rd, acc);
     };
 
     // Slab t+1 sits in registers while slab t is multiplied; once it has been written to
@@ -295,7 +377,7 @@ contract_kernel(const ContractArgs<T> args) {
         for (int g = 0; g < NG; ++g)
 #pragma unroll
             for (int v = 0; v < MF::NACC; ++v) {
-                const int64_t row = m0 + wm * Cfg::WTM + mi * MF::MB + MF::out_row(v, lane);
+                const int64_t row = m0 + wm * Cfg::WTM + sub_tile_row<Cfg>(mi, v, lane);
                 const int64_t col = n0 + wn * Cfg::WTN + g * (MF::NB * CV) + li * CV;
                 T *cp = args.C + row * args.ldc + col;
                 if (c_fast) {
@@ -331,16 +413,21 @@ contract_kernel(const ContractArgs<T> args) {
 // slab after it are issued between the MFMAs of the current slab, in the issue slots
 // the 64-cycle MFMAs leave free, instead of in a burst of their own.
 // ---------------------------------------------------------------------------
-template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N>
+template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TA = false>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 16) ? 4 : 2)
-contract_fast_kernel(const ContractArgs<T> args) {
-    typedef ContractCfg<T, BM, BN, BK, WAVES_M, WAVES_N> Cfg;
+contract_fast_kernel(ContractArgs<T> args) {
+    typedef ContractCfg<T, BM, BN, BK, WAVES_M, WAVES_N, TA> Cfg;
     typedef Mfma<T> MF;
     typedef typename VecOf<T, Cfg::VEC>::type vec_t;
     typedef typename VecOf<T, Cfg::CV>::type cvec_t;
-    constexpr int VEC = Cfg::VEC, KV = Cfg::KV, KG = Cfg::KG, MI = Cfg::MI, NI = Cfg::NI;
+    constexpr int VEC = Cfg::VEC, KG = Cfg::KG, MI = Cfg::MI, NI = Cfg::NI;
     constexpr int CV = Cfg::CV, NG = Cfg::NG, NT = Cfg::NT, NKG = BK / KG;
+    constexpr int ARL = Cfg::A_ROWLEN / VEC;          // 16-byte pieces per staged A row
     static_assert(Cfg::A_VECS % NT == 0 && Cfg::B_VECS % NT == 0, "slab vectors must divide over threads");
+
+    args.A += (int64_t)blockIdx.y * args.batch_a;
+    args.B += (int64_t)blockIdx.y * args.batch_b;
+    args.C += (int64_t)blockIdx.y * args.batch_c;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     T *lds = reinterpret_cast<T *>(lds_raw);
@@ -361,8 +448,8 @@ contract_fast_kernel(const ContractArgs<T> args) {
     int a_lds[Cfg::A_PER_T], b_lds[Cfg::B_PER_T];
 #pragma unroll
     for (int p = 0; p < Cfg::A_PER_T; ++p) {
-        const int v = tid + p * NT, r = v / (BK / VEC), kv = v % (BK / VEC);
-        a_off[p] = (m0 + r) * args.lda + kv * VEC;
+        const int v = tid + p * NT, r = v / ARL, kv = v % ARL;
+        a_off[p] = TA ? (int64_t)r * args.lda + m0 + kv * VEC : (m0 + r) * args.lda + kv * VEC;
         a_lds[p] = r * Cfg::LDA_S + kv * VEC;
     }
 #pragma unroll
@@ -376,7 +463,7 @@ contract_fast_kernel(const ContractArgs<T> args) {
     // slab index past the end is clamped to the last slab: a redundant, in-bounds reload
     auto load_global = [&](int64_t t) {
         const int64_t k0 = (t < nk ? t : nk - 1) * BK;
-        const T *ap = args.A + k0;
+        const T *ap = args.A + (TA ? k0 * args.lda : k0);
         const T *bp = args.B + k0 * args.ldb;
 #pragma unroll
         for (int p = 0; p < Cfg::A_PER_T; ++p) ra[p] = *reinterpret_cast<const vec_t *>(ap + a_off[p]);
@@ -399,37 +486,7 @@ contract_fast_kernel(const ContractArgs<T> args) {
 #pragma unroll
             for (int v = 0; v < MF::NACC; ++v) acc[mi][ni][v] = T(0);
 
-    const int a_rd = (wm * Cfg::WTM + li) * Cfg::LDA_S + ls * KV;
-    const int b_rd = Cfg::A_ELEMS + (ls * KV) * Cfg::LDB_S + wn * Cfg::WTN + li * CV;
-    auto compute = [&](int stage, int kg_lo, int kg_hi) {
-        const T *as = lds + stage * Cfg::STAGE_ELEMS + a_rd;
-        const T *bs = lds + stage * Cfg::STAGE_ELEMS + b_rd;
-#pragma unroll
-        for (int kg = kg_lo; kg < kg_hi; ++kg) {
-            vec_t a[MI];
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-                a[mi] = *reinterpret_cast<const vec_t *>(as + mi * MF::MB * Cfg::LDA_S + kg * KG);
-            cvec_t b[KV][NG];
-#pragma unroll
-            for (int t = 0; t < KV; ++t)
-#pragma unroll
-                for (int g = 0; g < NG; ++g)
-                    b[t][g] = *reinterpret_cast<const cvec_t *>(bs + (kg * KG + t) * Cfg::LDB_S
-                                                                + g * MF::NB * CV);
-#pragma unroll
-            for (int t = 0; t < KV; ++t)
-#pragma unroll
-                for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                    for (int ni = 0; ni < NI; ++ni) {
-                        T bv;
-                        if constexpr (CV == 1) bv = b[t][ni];
-                        else bv = b[t][ni / CV][ni % CV];
-                        acc[mi][ni] = MF::run(a[mi][t], bv, acc[mi][ni]);
-                    }
-        }
-    };
+    const int a_rd = a_read_offset<Cfg>(wm, li, ls), b_rd = b_read_offset<Cfg>(wn, li, ls);
 
     // slab t is in LDS buffer t & 1; slab t+1 is in registers; slab t+2 is requested
     // during the multiply of slab t
@@ -439,10 +496,11 @@ contract_fast_kernel(const ContractArgs<T> args) {
     __syncthreads();
     for (int64_t t = 0; t < nk; ++t) {
         const int stage = (int)(t & 1);
-        compute(stage, 0, (NKG + 1) / 2);
+        const T *st = lds + stage * Cfg::STAGE_ELEMS;
+        mfma_groups<T, Cfg, 0, (NKG + 1) / 2>(st + a_rd, st + b_rd, acc);
         store_lds(stage ^ 1);        // slab t+1 (on the last pass: a copy nobody reads)
         load_global(t + 2);
-        compute(stage, (NKG + 1) / 2, NKG);
+        mfma_groups<T, Cfg, (NKG + 1) / 2, NKG>(st + a_rd, st + b_rd, acc);
         __syncthreads();
     }
 
@@ -453,7 +511,7 @@ contract_fast_kernel(const ContractArgs<T> args) {
         for (int g = 0; g < NG; ++g)
 #pragma unroll
             for (int v = 0; v < MF::NACC; ++v) {
-                const int64_t row = m0 + wm * Cfg::WTM + mi * MF::MB + MF::out_row(v, lane);
+                const int64_t row = m0 + wm * Cfg::WTM + sub_tile_row<Cfg>(mi, v, lane);
                 const int64_t col = n0 + wn * Cfg::WTN + g * (MF::NB * CV) + li * CV;
                 T *cp = args.C + row * args.ldc + col;
                 cvec_t o;

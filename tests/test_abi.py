@@ -37,7 +37,7 @@ def test_exports_every_declared_symbol(lib):
 def test_version_and_status_strings(lib):
     assert lib.distal_version() >= 100
     seen = set()
-    for code in range(0, 8):
+    for code in range(0, 9):
         s = lib.distal_status_string(code).decode()
         assert s and s not in seen
         seen.add(s)
@@ -131,3 +131,19 @@ def test_product_does_not_import_the_oracle():
     otext = open(os.path.join(ROOT, "oracle", "__init__.py")).read() + \
         open(os.path.join(ROOT, "oracle", "distal_oracle.c")).read()
     assert "paper_2203_08069_amd" not in otext and "distal.h" not in otext
+
+
+def test_mode_call_argument_errors(lib):
+    a, b, c = (P(FAKE + 256 * i) for i in range(3))
+    t = lib.distal_ttm_mode
+    assert t(0, 3, 2, 2, 2, 2, a, b, c, None) == 8
+    assert t(0, -1, 2, 2, 2, 2, a, b, c, None) == 8
+    assert t(5, 1, 2, 2, 2, 2, a, b, c, None) == 3
+    for mode in (0, 1, 2):
+        assert t(0, mode, 2, -2, 2, 2, a, b, c, None) == 2
+        assert t(0, mode, 1 << 31, 1 << 31, 1 << 31, 2, a, b, c, None) == 2
+        assert t(0, mode, 2, 2, 2, 2, None, b, c, None) == 1
+        assert t(0, mode, 2, 2, 2, 2, a, None, c, None) == 1
+        assert t(0, mode, 2, 2, 2, 2, a, b, None, None) == 1
+        assert t(0, mode, 2, 2, 2, 2, a, b, a, None) == 5
+        assert t(1, mode, 2, 2, 2, 0, None, None, None, None) == 0      # empty output

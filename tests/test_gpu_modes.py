@@ -1,0 +1,136 @@
+"""GPU parity for the contractions along the other modes of the tensor (TTM and MTTKRP
+along mode 0, 1 and 2), against the CPU oracle on the same seeded inputs.  Small and
+ragged shapes are compared element by element; shapes large enough to reach the
+big-tile launch configurations are compared on slices of the output that depend on a
+slice of the input only, which the oracle recomputes from that slice."""
+import numpy as np
+import pytest
+
+from paper_2203_08069_amd import inputs
+
+import _util as U
+
+pytestmark = pytest.mark.gpu
+
+DT = [np.float32, np.float64]
+KINDS = [inputs.UNIFORM, inputs.SMALLINT]
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2203_08069_amd import binding
+    binding.load_library()          # raises if the HIP library was not built
+    return binding
+
+
+def empty(shape, dtype):
+    import torch
+    return torch.full(tuple(shape), float("nan"), dtype=getattr(torch, np.dtype(dtype).name), device="cuda:0")
+
+
+def compare(got, ref, dtype, kind, klen):
+    if kind == inputs.SMALLINT:
+        U.assert_exact(got, ref)
+    else:
+        U.assert_close(got, ref, dtype, klen)
+
+
+def out_shape(shape, mode, R):
+    s = list(shape)
+    s[mode] = R
+    return tuple(s)
+
+
+# ------------------------------------------------------------------ ttm along a mode
+
+# (I, J, K, R): ragged, extent-1 modes, and shapes made of whole 128 x 128 tiles in each mode's
+# matrix form (mode 0: R x JK over I; mode 1: per i, R x K over J)
+TTM_MODE_SHAPES = [(3, 5, 7, 4), (17, 9, 33, 130), (32, 8, 32, 128), (130, 3, 44, 5), (1, 1, 1, 1),
+                   (5, 40, 3, 1), (16, 128, 128, 128), (48, 2, 64, 256), (2, 19, 520, 36)]
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("I,J,K,R", TTM_MODE_SHAPES)
+def test_ttm_mode(lib, oracle, dtype, kind, mode, I, J, K, R):
+    shape = (I, J, K)
+    B, C = U.gen(40 + mode, 0, shape, dtype, kind), U.gen(40 + mode, 1, (shape[mode], R), dtype, kind)
+    A = empty(out_shape(shape, mode, R), dtype)
+    lib.distal_ttm_mode(mode, U.dev(B), U.dev(C), A)
+    compare(U.host(A), oracle.ttm_mode(mode, B, C), dtype, kind, shape[mode])
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_ttm_mode_identity_and_permutation(lib, dtype, mode):
+    shape = (24, 40, 56)
+    B = U.gen(43, 0, shape, dtype)
+    n = shape[mode]
+    A = empty(shape, dtype)
+    lib.distal_ttm_mode(mode, U.dev(B), U.dev(np.eye(n, dtype=dtype)), A)
+    assert np.array_equal(U.host(A), B)
+    perm = np.roll(np.arange(n), 3)
+    lib.distal_ttm_mode(mode, U.dev(B), U.dev(np.ascontiguousarray(np.eye(n, dtype=dtype)[:, perm])), A)
+    assert np.array_equal(U.host(A), np.take(B, perm, axis=mode))
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("kind", KINDS)
+def test_ttm_mode1_many_batches_big_tiles(lib, oracle, dtype, kind):
+    """mode 1 as a batch of I products R x K over J: 256 problems of one 256 x 256 tile each
+    (the binary32 big-tile configuration); a few i are checked in full."""
+    I, J, K, R = 256, 48, 256, 256
+    B, C = U.gen(44, 0, (I, J, K), dtype, kind), U.gen(44, 1, (J, R), dtype, kind)
+    A = empty((I, R, K), dtype)
+    lib.distal_ttm_mode(1, U.dev(B), U.dev(C), A)
+    got = U.host(A)
+    assert np.all(np.isfinite(got))
+    for i in (0, 1, 100, 255):
+        compare(got[i:i + 1], oracle.ttm_mode(1, B[i:i + 1], C), dtype, kind, J)
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("kind", KINDS)
+def test_ttm_mode0_wide_big_tiles(lib, oracle, dtype, kind):
+    """mode 0 as one product R x JK over I with JK = 65536 (256 tiles of 256 x 256 in binary32);
+    some j-slices are checked in full (A(:, j, :) depends on B(:, j, :) only)."""
+    I, J, K, R = 32, 256, 256, 256
+    B, C = U.gen(45, 0, (I, J, K), dtype, kind), U.gen(45, 1, (I, R), dtype, kind)
+    A = empty((R, J, K), dtype)
+    lib.distal_ttm_mode(0, U.dev(B), U.dev(C), A)
+    got = U.host(A)
+    assert np.all(np.isfinite(got))
+    for j in (0, 77, 255):
+        compare(got[:, j:j + 1, :], oracle.ttm_mode(0, np.ascontiguousarray(B[:, j:j + 1, :]), C), dtype, kind, I)
+
+
+def test_ttm_mode0_deep_binary64_big_tiles(lib, oracle):
+    """binary64, contracted extent 4096 and 256 tiles of 256 x 128: the deep big-tile configuration."""
+    dtype = np.float64
+    I, J, K, R = 4096, 64, 512, 256
+    B, C = U.gen(46, 0, (I, J, K), dtype), U.gen(46, 1, (I, R), dtype)
+    A = empty((R, J, K), dtype)
+    lib.distal_ttm_mode(0, U.dev(B), U.dev(C), A)
+    got = U.host(A)
+    assert np.all(np.isfinite(got))
+    for j, k0 in ((0, 0), (31, 200), (63, 504)):
+        ref = oracle.ttm_mode(0, np.ascontiguousarray(B[:, j:j + 1, k0:k0 + 8]), C)
+        U.assert_close(got[:, j:j + 1, k0:k0 + 8], ref, dtype, I)
+
+
+@pytest.mark.parametrize("dtype", DT)
+def test_ttm_mode_zero_extents(lib, dtype):
+    import torch
+    tdt = getattr(torch, np.dtype(dtype).name)
+    z = lambda *s: torch.zeros(s, dtype=tdt, device="cuda:0")
+    A = empty((4, 3, 5), dtype)
+    lib.distal_ttm_mode(0, z(0, 3, 5), z(0, 4), A)          # empty sum -> zeros
+    assert np.array_equal(U.host(A), np.zeros((4, 3, 5)))
+    A = empty((2, 4, 5), dtype)
+    lib.distal_ttm_mode(1, z(2, 0, 5), z(0, 4), A)
+    assert np.array_equal(U.host(A), np.zeros((2, 4, 5)))
+    lib.distal_ttm_mode(1, z(2, 3, 0), z(3, 4), z(2, 4, 0))  # empty output: a no-op
+    lib.distal_ttm_mode(0, z(2, 3, 5), z(2, 0), z(0, 3, 5))
