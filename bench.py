@@ -92,7 +92,8 @@ def main():
     ap.add_argument("--rows", default="all",
                     help="comma list of gemm_f64,gemm_f32,ttm,mttkrp,ttv,innerprod (gemm_f64 always runs); "
                          "extra rows, not part of 'all': summa (k-chunk leaf shapes), "
-                         "ttv_f64,innerprod_f64,ttm_f64,mttkrp_f64")
+                         "ttv_f64,innerprod_f64,ttm_f64,mttkrp_f64, ttm_mode0,ttm_mode1 (TTM along the "
+                         "other modes of the configs[3] tensor)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB read + 1 GiB write elementwise kernel (torch.add), the known-size "
@@ -302,6 +303,41 @@ def main():
                                  "kind": "oracle", "seconds": sec, "sample": f"first {i_s} of {I} i-slices"}
             r["sample_normwise_err"] = sample_err(A[:i_s].cpu().numpy(), ref)
         del B, C, A
+
+    # ---------------------------------------------------------------- TTM along modes 0 and 1 (extra)
+    if want & {"ttm_mode0", "ttm_mode1"}:
+        I = J = K = 1024
+        R = 256
+        B = device_tensor(3, 0, (I, J, K), np.float32, device=dev)
+        C = device_tensor(3, 1, (K, R), np.float32, device=dev)      # I = J = K: one factor serves every mode
+        for mode in (0, 1):
+            if f"ttm_mode{mode}" not in want:
+                continue
+            shape = [I, J, K]
+            shape[mode] = R
+            A = torch.empty(shape, dtype=torch.float32, device=dev)
+            r = finish(f"ttm_mode{mode}", f"TTM along mode {mode}, B {I}x{J}x{K}, C {K}x{R} f32, seed 3", "f32",
+                       lambda: binding.distal_ttm_mode(mode, B, C, A), 2.0 * I * J * K * R,
+                       4.0 * (I * J * K + K * R + I * J * R), "mfma")
+            if cpu:
+                # outputs that depend on one slice of B only: mode 0 -> A(:, j, :), mode 1 -> A(i, :, :)
+                n_s = 8
+                hC = inputs.tensor(3, 1, (K, R), np.float32)
+                if mode == 0:
+                    hB = np.ascontiguousarray(B[:, :n_s, :].cpu().numpy())
+                    got = A[:, :n_s, :].cpu().numpy()
+                else:
+                    hB = np.ascontiguousarray(B[:n_s].cpu().numpy())
+                    got = A[:n_s].cpu().numpy()
+                t0 = time.perf_counter()
+                ref = oracle.ttm_mode(mode, hB, hC)
+                sec = time.perf_counter() - t0
+                r["cpu_baseline"] = {"value": 2.0 * n_s * J * K * R / sec / 1e9, "unit": "GFLOP/s", "cores": cores,
+                                     "kind": "oracle", "seconds": sec,
+                                     "sample": f"{n_s} of 1024 slices of the output along mode {1 - mode}"}
+                r["sample_normwise_err"] = sample_err(got, ref)
+            del A
+        del B, C
 
     # ---------------------------------------------------------------- MTTKRP (configs[4])
     if "mttkrp" in want:
