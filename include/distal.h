@@ -106,6 +106,23 @@ int distal_mttkrp(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L,
                   void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * MTTKRP along any mode of B (I x J x K): A has one row per index of that mode,
+ * C and D are the factor matrices of the two other modes, in mode order.  The
+ * evaluation section names MTTKRP as a building block of the canonical polyadic
+ * decomposition, whose alternating sweep needs it along every mode; its list
+ * states mode 0.
+ *   mode 0: A(i,l) = sum_j sum_k B(i,j,k) * C(j,l) * D(k,l)   C: J x L, D: K x L  (= distal_mttkrp)
+ *   mode 1: A(j,l) = sum_i sum_k B(i,j,k) * C(i,l) * D(k,l)   C: I x L, D: K x L
+ *   mode 2: A(k,l) = sum_i sum_j B(i,j,k) * C(i,l) * D(j,l)   C: I x L, D: J x L
+ * All dense; A is overwritten; B is read once, in place (no transposed copy).
+ *   workspace: device scratch of at least distal_mttkrp_mode_workspace_bytes(...)
+ *   bytes, 256-byte aligned; may be NULL when that size is 0.
+ */
+int distal_mttkrp_mode(distal_dtype dt, int mode, int64_t I, int64_t J, int64_t K, int64_t L,
+                       const void *B, const void *C, const void *D, void *A,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Tensor times vector:  A(i,j) = sum_k B(i,j,k) * c(k)
  * (background section on tensor index notation; evaluation list).
  *   B: I x J x K, c: K, A: I x J, all dense.  A is overwritten.
@@ -126,8 +143,10 @@ int distal_innerprod(distal_dtype dt, int64_t I, int64_t J, int64_t K,
                      const void *B, const void *C, void *a,
                      void *workspace, size_t workspace_bytes, void *stream);
 
-/* Scratch sizes for the two calls above (0 for invalid arguments). */
+/* Scratch sizes for the calls that take a workspace (0 for invalid arguments). */
 size_t distal_mttkrp_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L);
+size_t distal_mttkrp_mode_workspace_bytes(distal_dtype dt, int mode, int64_t I, int64_t J, int64_t K,
+                                          int64_t L);
 size_t distal_innerprod_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, int64_t K);
 
 /* Static, human-readable text for a distal_status value. */

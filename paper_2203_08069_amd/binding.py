@@ -25,7 +25,7 @@ STATUS_NAMES = {
 # every symbol include/distal.h declares
 EXPORTS = (
     "distal_gemm", "distal_ttm", "distal_mttkrp", "distal_ttv", "distal_innerprod",
-    "distal_ttm_mode",
+    "distal_ttm_mode", "distal_mttkrp_mode", "distal_mttkrp_mode_workspace_bytes",
     "distal_mttkrp_workspace_bytes", "distal_innerprod_workspace_bytes",
     "distal_status_string", "distal_version",
 )
@@ -55,6 +55,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.distal_gemm.argtypes = [ci, i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, vp]
     lib.distal_ttm.argtypes = [ci, i64, i64, i64, i64, vp, vp, vp, vp]
     lib.distal_ttm_mode.argtypes = [ci, ci, i64, i64, i64, i64, vp, vp, vp, vp]
+    lib.distal_mttkrp_mode.argtypes = [ci, ci, i64, i64, i64, i64, vp, vp, vp, vp, vp, sz, vp]
+    lib.distal_mttkrp_mode_workspace_bytes.argtypes = [ci, ci, i64, i64, i64, i64]
+    lib.distal_mttkrp_mode_workspace_bytes.restype = sz
     lib.distal_mttkrp.argtypes = [ci, i64, i64, i64, i64, vp, vp, vp, vp, vp, sz, vp]
     lib.distal_ttv.argtypes = [ci, i64, i64, i64, vp, vp, vp, vp]
     lib.distal_innerprod.argtypes = [ci, i64, i64, i64, vp, vp, vp, vp, sz, vp]
@@ -63,7 +66,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.distal_status_string.argtypes = [ci]
     lib.distal_version.argtypes = []
     for name in ("distal_gemm", "distal_ttm", "distal_mttkrp", "distal_ttv", "distal_innerprod",
-                 "distal_ttm_mode", "distal_version"):
+                 "distal_ttm_mode", "distal_mttkrp_mode", "distal_version"):
         getattr(lib, name).restype = ci
     lib.distal_mttkrp_workspace_bytes.restype = sz
     lib.distal_innerprod_workspace_bytes.restype = sz
@@ -222,6 +225,31 @@ def distal_mttkrp(B, C, D, A, workspace=None):
         rc = load_library().distal_mttkrp(dt, I, J, K, L, _ptr(B), _ptr(C), _ptr(D), _ptr(A),
                                           _ptr(ws), ws.numel() * ws.element_size(), _stream(B))
     _raise(rc, "distal_mttkrp")
+    return A
+
+
+def mttkrp_mode_workspace_bytes(dtype_code: int, mode: int, I: int, J: int, K: int, L: int) -> int:
+    return int(load_library().distal_mttkrp_mode_workspace_bytes(dtype_code, mode, I, J, K, L))
+
+
+def distal_mttkrp_mode(mode, B, C, D, A, workspace=None):
+    """MTTKRP along `mode` of B; C and D are the factors of the two other modes, in mode order."""
+    dt = _same(B, C, D, A)
+    _dense(B, "B", 3), _dense(C, "C", 2), _dense(D, "D", 2), _dense(A, "A", 2)
+    if mode not in (0, 1, 2):
+        raise ValueError("mode must be 0, 1 or 2")
+    I, J, K = B.shape
+    L = C.shape[1]
+    a, b = [m for m in (0, 1, 2) if m != mode]
+    if (tuple(C.shape) != (B.shape[a], L) or tuple(D.shape) != (B.shape[b], L)
+            or tuple(A.shape) != (B.shape[mode], L)):
+        raise ValueError("shapes do not match a mode-%d MTTKRP" % mode)
+    need = mttkrp_mode_workspace_bytes(dt, mode, I, J, K, L)
+    ws = workspace if workspace is not None else _workspace(B.device, need)
+    with _torch().cuda.device(B.device):
+        rc = load_library().distal_mttkrp_mode(dt, mode, I, J, K, L, _ptr(B), _ptr(C), _ptr(D), _ptr(A),
+                                               _ptr(ws), ws.numel() * ws.element_size(), _stream(B))
+    _raise(rc, "distal_mttkrp_mode")
     return A
 
 

@@ -249,6 +249,109 @@ int mttkrp_t(int64_t I, int64_t J, int64_t K, int64_t L, const T *B, const T *C,
     return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
 }
 
+// ---- MTTKRP along modes 1 and 2 --------------------------------------------
+// Both kernels give every workgroup a fixed piece of the two kept indices and a contiguous
+// range of i; the number of ranges is a function of the shape only (enough workgroups for
+// three per CU of a 256-CU part), never of the device, so the summation order is reproducible.
+constexpr int64_t kModeTargetBlocks = 768;
+
+struct MttkrpModePlan {
+    int64_t tasks;          // workgroups per range of i
+    int64_t isplit, nsplit; // i per range; ranges (none empty)
+    int64_t nparts;         // partial rows per output row
+    int64_t partial_elems;  // workspace elements (0 when nparts == 1)
+    int64_t nslices, kgroups, jblocks, jgroups, kblocks, tiles_n;
+    bool ok;
+};
+
+MttkrpModePlan mttkrp_mode_plan(int dt, int mode, int64_t I, int64_t J, int64_t K, int64_t L) {
+    MttkrpModePlan p{};
+    const int64_t esz = dt == DISTAL_F64 ? 8 : 4;
+    p.tiles_n = (L + 31) / 32;
+    int64_t out_rows, per_split;
+    if (mode == 1) {
+        const int64_t sl = 256 / esz;
+        p.nslices = (K + sl - 1) / sl;
+        p.kgroups = (p.nslices + 3) / 4;
+        p.jblocks = (J + 31) / 32;
+        p.ok = mul_ok(p.kgroups * p.tiles_n, p.jblocks, &p.tasks);
+        per_split = p.nslices;
+        out_rows = J;
+    } else {
+        const int64_t kw = 512 / esz;
+        p.kblocks = (K + kw - 1) / kw;
+        p.jgroups = (J + 63) / 64;
+        p.ok = mul_ok(p.kblocks * p.tiles_n, p.jgroups, &p.tasks);
+        per_split = p.jgroups;
+        out_rows = K;
+    }
+    if (!p.ok || p.tasks < 1) { p.ok = false; return p; }
+    int64_t want = (kModeTargetBlocks + p.tasks - 1) / p.tasks;
+    if (want > I) want = I;
+    if (want < 1) want = 1;
+    p.isplit = (I + want - 1) / want;
+    p.nsplit = (I + p.isplit - 1) / p.isplit;
+    int64_t rows;
+    p.ok = mul_ok(p.nsplit, per_split, &p.nparts) && mul_ok(out_rows, p.nparts, &rows) &&
+           mul_ok(rows, L, &p.partial_elems) && p.partial_elems <= INT64_MAX / 16 &&
+           p.nparts <= std::numeric_limits<int>::max();
+    int64_t nblocks;
+    p.ok = p.ok && mul_ok(p.tasks, p.nsplit, &nblocks) && nblocks <= std::numeric_limits<int>::max();
+    if (p.nparts <= 1) p.partial_elems = 0;
+    return p;
+}
+
+template <typename T>
+int mttkrp_mode_t(int mode, int64_t I, int64_t J, int64_t K, int64_t L, const T *B, const T *C, const T *D,
+                  T *A, void *workspace, hipStream_t stream) {
+    const int64_t out_rows = mode == 1 ? J : K;
+    if (out_rows == 0 || L == 0) return DISTAL_OK;
+    if (I == 0 || (mode == 1 ? K : J) == 0) return launch_fill<T>(A, out_rows, L, L, stream);
+    const MttkrpModePlan plan = mttkrp_mode_plan(sizeof(T) == 8 ? DISTAL_F64 : DISTAL_F32, mode, I, J, K, L);
+    if (!plan.ok) return DISTAL_ERR_SHAPE;
+    T *partial = plan.nparts == 1 ? A : static_cast<T *>(workspace);
+    const unsigned nblocks = (unsigned)(plan.tasks * plan.nsplit);
+    // the unguarded kernels address a row block with 32-bit byte offsets
+    const bool aligned = aligned16(B) && L % 32 == 0 && K <= (1 << 22);
+    if (mode == 1) {
+        typedef MttkrpCfg<T> Cfg;
+        MttkrpMode1Args<T> a{};
+        a.B = B; a.C = C; a.D = D; a.partial = partial;
+        a.I = I; a.J = J; a.K = K; a.L = L;
+        a.isplit = plan.isplit; a.nsplit = (int)plan.nsplit;
+        a.nslices = (int)plan.nslices; a.kgroups = (int)plan.kgroups;
+        a.tiles_n = (int)plan.tiles_n; a.jblocks = (int)plan.jblocks;
+        constexpr int lds = Cfg::NW * Cfg::PATCH * (int)sizeof(T);
+        static std::atomic<bool> done_full[kMaxDevices], done_guard[kMaxDevices];
+        if (aligned && J % Cfg::RB == 0 && K % Cfg::SL == 0) {
+            auto kern = mttkrp_mode1_kernel<T, false>;
+            if (!allow_lds(kern, lds, done_full)) return DISTAL_ERR_LAUNCH;
+            hipLaunchKernelGGL(kern, dim3(nblocks), dim3(Cfg::NT), lds, stream, a);
+        } else {
+            auto kern = mttkrp_mode1_kernel<T, true>;
+            if (!allow_lds(kern, lds, done_guard)) return DISTAL_ERR_LAUNCH;
+            hipLaunchKernelGGL(kern, dim3(nblocks), dim3(Cfg::NT), lds, stream, a);
+        }
+    } else {
+        typedef MttkrpMode2Cfg<T> Cfg;
+        MttkrpMode2Args<T> a{};
+        a.B = B; a.C = C; a.D = D; a.partial = partial;
+        a.I = I; a.J = J; a.K = K; a.L = L;
+        a.isplit = plan.isplit; a.nsplit = (int)plan.nsplit;
+        a.jgroups = (int)plan.jgroups; a.kblocks = (int)plan.kblocks; a.tiles_n = (int)plan.tiles_n;
+        if (aligned && J % Cfg::JB == 0 && K % Cfg::KW == 0)
+            hipLaunchKernelGGL((mttkrp_mode2_kernel<T, false>), dim3(nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
+        else
+            hipLaunchKernelGGL((mttkrp_mode2_kernel<T, true>), dim3(nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
+    }
+    if (hipGetLastError() != hipSuccess) return DISTAL_ERR_LAUNCH;
+    if (plan.nparts == 1) return DISTAL_OK;
+    const int64_t blocks = out_rows < 4096 ? out_rows : 4096;
+    hipLaunchKernelGGL(mttkrp_reduce_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                       static_cast<const T *>(partial), A, out_rows, L, (int)plan.nparts);
+    return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
+}
+
 // ---- TTV ------------------------------------------------------------------
 template <typename T>
 int ttv_t(int64_t rows, int64_t K, const T *B, const T *c, T *A, hipStream_t stream) {
@@ -415,6 +518,46 @@ size_t distal_mttkrp_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, int6
     const MttkrpPlan p = mttkrp_plan(dt, I, J, K, L);
     if (!p.ok) return 0;
     return (size_t)p.partial_elems * elem_size(dt);
+}
+
+size_t distal_mttkrp_mode_workspace_bytes(distal_dtype dt, int mode, int64_t I, int64_t J, int64_t K,
+                                          int64_t L) {
+    if (mode == 0) return distal_mttkrp_workspace_bytes(dt, I, J, K, L);
+    if (check_dtype(dt) != DISTAL_OK || mode < 0 || mode > 2 || I < 0 || J < 0 || K < 0 || L < 0) return 0;
+    if (I == 0 || J == 0 || K == 0 || L == 0) return 0;
+    const MttkrpModePlan p = mttkrp_mode_plan(dt, mode, I, J, K, L);
+    if (!p.ok) return 0;
+    return (size_t)p.partial_elems * elem_size(dt);
+}
+
+int distal_mttkrp_mode(distal_dtype dt, int mode, int64_t I, int64_t J, int64_t K, int64_t L,
+                       const void *B, const void *C, const void *D, void *A, void *workspace,
+                       size_t workspace_bytes, void *stream) {
+    if (check_dtype(dt) != DISTAL_OK) return DISTAL_ERR_DTYPE;
+    if (mode < 0 || mode > 2) return DISTAL_ERR_MODE;
+    if (mode == 0) return distal_mttkrp(dt, I, J, K, L, B, C, D, A, workspace, workspace_bytes, stream);
+    if (I < 0 || J < 0 || K < 0 || L < 0) return DISTAL_ERR_SHAPE;
+    // factor extents: C belongs to mode i, D to k (mode 1) or j (mode 2); the output to the mode itself
+    const int64_t drows = mode == 1 ? K : J, arows = mode == 1 ? J : K;
+    int64_t nb, nc, nd, na;
+    if (!tensor_elems(I, J, K, &nb) || !mul_ok(I, L, &nc) || !mul_ok(drows, L, &nd) || !mul_ok(arows, L, &na))
+        return DISTAL_ERR_SHAPE;
+    const bool work = nb > 0 && L > 0;
+    if (work && !mttkrp_mode_plan(dt, mode, I, J, K, L).ok) return DISTAL_ERR_SHAPE;
+    if ((work && (!B || !C || !D)) || (na > 0 && !A)) return DISTAL_ERR_NULL;
+    if (na > 0 && (A == B || A == C || A == D)) return DISTAL_ERR_ALIAS;
+    const size_t need = work ? distal_mttkrp_mode_workspace_bytes(dt, mode, I, J, K, L) : 0;
+    if (need > 0 && (!workspace || workspace_bytes < need ||
+                     (reinterpret_cast<uintptr_t>(workspace) % kWorkspaceAlign) != 0))
+        return DISTAL_ERR_WORKSPACE;
+    if (need > 0 && (workspace == A || workspace == B || workspace == C || workspace == D))
+        return DISTAL_ERR_ALIAS;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dt == DISTAL_F64)
+        return mttkrp_mode_t<double>(mode, I, J, K, L, (const double *)B, (const double *)C, (const double *)D,
+                                     (double *)A, workspace, s);
+    return mttkrp_mode_t<float>(mode, I, J, K, L, (const float *)B, (const float *)C, (const float *)D,
+                                (float *)A, workspace, s);
 }
 
 int distal_mttkrp(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L, const void *B,

@@ -75,6 +75,114 @@ struct MttkrpCfg {
     static_assert(SL % KG == 0 && RB % MF::NB == 0 && LB <= 2 && 64 % CPR == 0 && CJ % RB == 0, "tile shape");
 };
 
+// ---- pieces shared by the kernels of this file --------------------------------------------
+
+// Orders this wavefront's own LDS writes and reads (a patch has one owner).
+__device__ __forceinline__ void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Where a lane's 16-byte pieces of a row block sit: piece p is row prow + p*RPI, elements
+// pcol .. pcol+VEC-1 of the k-slice; boff[p] is its byte offset from the block's first element
+// for a tensor whose rows are `row_stride` elements apart.
+template <typename T>
+struct MttkrpPieces {
+    typedef MttkrpCfg<T> Cfg;
+    int prow, pcol;
+    uint32_t boff[Cfg::PER_T];
+    __device__ __forceinline__ MttkrpPieces(int lane, int64_t row_stride) {
+        prow = lane / Cfg::CPR;
+        pcol = (lane % Cfg::CPR) * Cfg::VEC;
+#pragma unroll
+        for (int p = 0; p < Cfg::PER_T; ++p)
+            boff[p] = (uint32_t)(((int64_t)(prow + p * Cfg::RPI) * row_stride + pcol) * (int64_t)sizeof(T));
+    }
+};
+
+// RB rows x SL k-values starting at `base` (rows `row_stride` elements apart) -> rs.
+// GUARD: rows >= rows_valid and k >= k_valid read as zero, element loads (any alignment).
+template <typename T, bool GUARD>
+__device__ __forceinline__ void mttkrp_load_block(
+    const T *base, int64_t row_stride, int64_t rows_valid, int64_t k_valid, const MttkrpPieces<T> &pc,
+    typename VecOf<T, MttkrpCfg<T>::VEC>::type (&rs)[MttkrpCfg<T>::PER_T]) {
+    typedef MttkrpCfg<T> Cfg;
+    typedef typename VecOf<T, Cfg::VEC>::type vec_t;
+    if constexpr (!GUARD) {
+#pragma unroll
+        for (int p = 0; p < Cfg::PER_T; ++p)
+            rs[p] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(
+                reinterpret_cast<const char *>(base) + pc.boff[p]));
+    } else {
+#pragma unroll
+        for (int p = 0; p < Cfg::PER_T; ++p) {
+            const int64_t jr = pc.prow + p * Cfg::RPI;                          // row within the block
+#pragma unroll
+            for (int e = 0; e < Cfg::VEC; ++e)
+                rs[p][e] = (jr < rows_valid && pc.pcol + e < k_valid) ? base[jr * row_stride + pc.pcol + e] : T(0);
+        }
+    }
+}
+
+// registers -> the wavefront's private patch (row-major, k contiguous)
+template <typename T>
+__device__ __forceinline__ void mttkrp_patch_store(
+    T *patch, const MttkrpPieces<T> &pc, const typename VecOf<T, MttkrpCfg<T>::VEC>::type (&rs)[MttkrpCfg<T>::PER_T]) {
+    typedef MttkrpCfg<T> Cfg;
+    typedef typename VecOf<T, Cfg::VEC>::type vec_t;
+#pragma unroll
+    for (int p = 0; p < Cfg::PER_T; ++p)
+        *reinterpret_cast<vec_t *>(patch + (pc.prow + p * Cfg::RPI) * Cfg::LDW + pc.pcol) = rs[p];
+}
+
+// acc(l, j) += sum over the slice of d(l, k) * patch(j, k): the transposed product of one block
+template <typename T>
+__device__ __forceinline__ void mttkrp_patch_mfma(
+    const T *patch, int li, int ls,
+    const typename VecOf<T, MttkrpCfg<T>::VEC>::type (&d)[MttkrpCfg<T>::LB][MttkrpCfg<T>::NKG],
+    typename Mfma<T>::acc_t (&acc)[MttkrpCfg<T>::LB][MttkrpCfg<T>::MI]) {
+    typedef MttkrpCfg<T> Cfg;
+    typedef Mfma<T> MF;
+    typedef typename VecOf<T, Cfg::VEC>::type vec_t;
+#pragma unroll
+    for (int g = 0; g < Cfg::NKG; ++g) {
+        vec_t b[Cfg::MI];
+#pragma unroll
+        for (int mi = 0; mi < Cfg::MI; ++mi)
+            b[mi] = *reinterpret_cast<const vec_t *>(patch + (mi * MF::NB + li) * Cfg::LDW
+                                                     + g * Cfg::KG + ls * Cfg::KV);
+#pragma unroll
+        for (int t = 0; t < Cfg::KV; ++t)
+#pragma unroll
+            for (int lb = 0; lb < Cfg::LB; ++lb)
+#pragma unroll
+                for (int mi = 0; mi < Cfg::MI; ++mi)
+                    acc[lb][mi] = MF::run(d[lb][g][t], b[mi][t], acc[lb][mi]);
+    }
+}
+
+// The D operand of one k-slice, transposed into registers: d[lb][g][t] = D(k, l) for
+// k = k0 + g*KG + ls*KV + t and l = n0 + li (binary32) or n0 + 2*li + lb (binary64); zero
+// outside K x L when GUARD.  Lanes with neighbouring li read neighbouring l.
+template <typename T, bool GUARD>
+__device__ __forceinline__ void mttkrp_load_d(
+    const T *D, int64_t K, int64_t L, int64_t k0, int64_t n0, int li, int ls,
+    typename VecOf<T, MttkrpCfg<T>::VEC>::type (&d)[MttkrpCfg<T>::LB][MttkrpCfg<T>::NKG]) {
+    typedef MttkrpCfg<T> Cfg;
+#pragma unroll
+    for (int lb = 0; lb < Cfg::LB; ++lb) {
+        const int64_t l = n0 + (Cfg::LB == 1 ? li : 2 * li + lb);
+#pragma unroll
+        for (int g = 0; g < Cfg::NKG; ++g)
+#pragma unroll
+            for (int t = 0; t < Cfg::KV; ++t) {
+                const int64_t k = k0 + g * Cfg::KG + ls * Cfg::KV + t;
+                d[lb][g][t] = (!GUARD || (k < K && l < L)) ? D[k * L + l] : T(0);
+            }
+    }
+}
+
 // A(i, l) = sum of the per_i partial rows of i, in row order.  One workgroup per i:
 // thread (r, l) adds rows r, r+8, ..., then the eight strands are added in order.
 template <typename T>
@@ -119,7 +227,7 @@ mttkrp_kernel(const MttkrpArgs<T> args) {
     typedef MttkrpCfg<T> Cfg;
     typedef Mfma<T> MF;
     typedef typename VecOf<T, Cfg::VEC>::type vec_t;
-    constexpr int VEC = Cfg::VEC, KV = Cfg::KV, KG = Cfg::KG, NKG = Cfg::NKG, MI = Cfg::MI, LB = Cfg::LB;
+    constexpr int VEC = Cfg::VEC, NKG = Cfg::NKG, MI = Cfg::MI, LB = Cfg::LB;
     constexpr int SL = Cfg::SL, BN = Cfg::BN, RB = Cfg::RB, CJ = Cfg::CJ;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
@@ -165,21 +273,8 @@ mttkrp_kernel(const MttkrpArgs<T> args) {
     const int64_t k0 = (int64_t)slice * SL;                    // this wavefront's k-slice
     if (k0 >= K || ig >= I) return;       // wavefront-uniform
 
-    // The D operand of this slice, transposed into registers once: d[lb][g][t] = D(k, l) for
-    // k = k0 + g*KG + ls*KV + t and l = n0 + li (binary32) or n0 + 2*li + lb (binary64); zero
-    // outside K x L.  Lanes with neighbouring li read neighbouring l.
-    vec_t d[LB][NKG];
-#pragma unroll
-    for (int lb = 0; lb < LB; ++lb) {
-        const int64_t l = n0 + (LB == 1 ? li : 2 * li + lb);
-#pragma unroll
-        for (int g = 0; g < NKG; ++g)
-#pragma unroll
-            for (int t = 0; t < KV; ++t) {
-                const int64_t k = k0 + g * KG + ls * KV + t;
-                d[lb][g][t] = (!GUARD || (k < K && l < L)) ? args.D[k * L + l] : T(0);
-            }
-    }
+    vec_t d[LB][NKG];                     // the D operand of this slice, for the wavefront's whole life
+    mttkrp_load_d<T, GUARD>(args.D, K, L, k0, n0, li, ls, d);
 
     T lsum[LB][MF::NACC];                 // running sum for l = mttkrp_l_of(v, lb, lane)
 #pragma unroll
@@ -188,32 +283,13 @@ mttkrp_kernel(const MttkrpArgs<T> args) {
         for (int v = 0; v < MF::NACC; ++v) lsum[lb][v] = T(0);
 
     vec_t rs[Cfg::PER_T];
-    const int prow = lane / Cfg::CPR, pcol = (lane % Cfg::CPR) * VEC;
-    // Per-lane byte offsets inside a row block; the block base is wavefront-uniform.  The host
-    // sends shapes whose block spans exceed 32-bit offsets to the guarded kernel.
-    uint32_t boff[Cfg::PER_T];
-#pragma unroll
-    for (int p = 0; p < Cfg::PER_T; ++p)
-        boff[p] = (uint32_t)(((int64_t)(prow + p * Cfg::RPI) * K + pcol) * (int64_t)sizeof(T));
+    // The host sends shapes whose block spans exceed 32-bit byte offsets to the guarded kernel.
+    const MttkrpPieces<T> pc(lane, K);
 
     // rows [jb + rb*RB, +RB) of slice i, k in [k0, k0 + SL) -> rs
     auto load_rows = [&](int64_t i, int rb) {
-        const T *base = args.B + (i * J + jb + (int64_t)rb * RB) * K + k0;      // wavefront-uniform
-        if constexpr (!GUARD) {
-#pragma unroll
-            for (int p = 0; p < Cfg::PER_T; ++p)
-                rs[p] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(
-                    reinterpret_cast<const char *>(base) + boff[p]));
-        } else {
-#pragma unroll
-            for (int p = 0; p < Cfg::PER_T; ++p) {
-                const int64_t jr = prow + p * Cfg::RPI;                          // row within the block
-#pragma unroll
-                for (int e = 0; e < VEC; ++e)
-                    rs[p][e] = (jb + (int64_t)rb * RB + jr < J && k0 + pcol + e < K)
-                                   ? base[jr * K + pcol + e] : T(0);
-            }
-        }
+        const int64_t j0 = jb + (int64_t)rb * RB;
+        mttkrp_load_block<T, GUARD>(args.B + (i * J + j0) * K + k0, K, J - j0, K - k0, pc, rs);   // uniform base
     };
 
     // One 32-row block: patch -> MFMA -> fold.  `c` are the lane's factor pieces for this block.
@@ -224,17 +300,10 @@ mttkrp_kernel(const MttkrpArgs<T> args) {
         const int next_rb = last_rb ? 0 : rb + 1;
         const bool more = next_i < I;
 
-        // registers -> private patch (row-major, k contiguous)
-#pragma unroll
-        for (int p = 0; p < Cfg::PER_T; ++p)
-            *reinterpret_cast<vec_t *>(patch + (prow + p * Cfg::RPI) * Cfg::LDW + pcol) = rs[p];
+        mttkrp_patch_store<T>(patch, pc, rs);
         // past the end: a redundant reload of the current block, never out of bounds
         load_rows(more ? next_i : i, more ? next_rb : rb);
-
-        // the patch is written and read by this wavefront only
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        wave_lds_fence();                  // the patch is written and read by this wavefront only
 
         typename MF::acc_t acc[LB][MI];
 #pragma unroll
@@ -243,25 +312,8 @@ mttkrp_kernel(const MttkrpArgs<T> args) {
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                 for (int v = 0; v < MF::NACC; ++v) acc[lb][mi][v] = T(0);
-#pragma unroll
-        for (int g = 0; g < NKG; ++g) {
-            vec_t b[MI];
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-                b[mi] = *reinterpret_cast<const vec_t *>(patch + (mi * MF::NB + li) * Cfg::LDW
-                                                         + g * KG + ls * KV);
-#pragma unroll
-            for (int t = 0; t < KV; ++t)
-#pragma unroll
-                for (int lb = 0; lb < LB; ++lb)
-#pragma unroll
-                    for (int mi = 0; mi < MI; ++mi)
-                        acc[lb][mi] = MF::run(d[lb][g][t], b[mi][t], acc[lb][mi]);
-        }
-        // all reads of the patch are done before the next block overwrites it
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        mttkrp_patch_mfma<T>(patch, li, ls, d, acc);
+        wave_lds_fence();                  // all reads of the patch are done before it is overwritten
 
         // scale Tt(l, j) by C(j, l) and add into the lane's running sums
 #pragma unroll
@@ -320,6 +372,312 @@ mttkrp_kernel(const MttkrpArgs<T> args) {
             block(i, rb, c);
         }
         flush(i);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// MTTKRP along mode 1:  A(j,l) = sum_i C(i,l) * ( sum_k B(i,j,k) * D(k,l) ).
+//
+// The contracted index k is still the contiguous one, so a block of B takes the same way
+// as above (coalesced loads -> private patch -> MFMA operand layout) and the same
+// transposed product Tt(l,j) is formed.  What changes is the sum that follows: it runs
+// over i, not over j, so a wavefront keeps ONE 32-row block of j and one k-slice for its
+// whole life and walks a range of i.  For each i it scales its D slice by C(i,l) (32
+// multiplies) and lets the MFMAs add straight into one accumulator that lives as long as
+// the wavefront: no fold, no lane reduction, no barrier anywhere.  At the end it writes
+// its 32 x 32 partial block; the row-sum kernel adds the partial rows of each j in order.
+// ---------------------------------------------------------------------------
+template <typename T>
+struct MttkrpMode1Args {
+    const T *B;        // I x J x K
+    const T *C;        // I x L
+    const T *D;        // K x L
+    T *partial;        // (J * nparts) x L: row j * nparts + (split * nslices + slice);
+                       // the output itself when nparts == 1
+    int64_t I, J, K, L;
+    int64_t isplit;    // i per range
+    int nsplit;        // ranges of i: ceil(I / isplit), none empty
+    int nslices;       // ceil(K / SL)
+    int kgroups;       // ceil(nslices / 4)
+    int tiles_n;       // ceil(L / 32)
+    int jblocks;       // ceil(J / 32)
+};
+
+template <typename T, bool GUARD>
+__global__ void __launch_bounds__(256, GUARD ? 1 : (sizeof(T) == 4 ? 3 : 2))
+mttkrp_mode1_kernel(const MttkrpMode1Args<T> args) {
+    typedef MttkrpCfg<T> Cfg;
+    typedef Mfma<T> MF;
+    typedef typename VecOf<T, Cfg::VEC>::type vec_t;
+    constexpr int NKG = Cfg::NKG, MI = Cfg::MI, LB = Cfg::LB, KV = Cfg::KV;
+    constexpr int SL = Cfg::SL, BN = Cfg::BN, RB = Cfg::RB;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane % MF::MB, ls = lane / MF::MB;
+    T *patch = reinterpret_cast<T *>(lds_raw) + wave * Cfg::PATCH;
+
+    int bid = blockIdx.x;
+    const int tn = bid % args.tiles_n;     bid /= args.tiles_n;
+    const int kgp = bid % args.kgroups;    bid /= args.kgroups;
+    const int jblk = bid % args.jblocks;   bid /= args.jblocks;
+    const int split = bid;
+    const int64_t I = args.I, J = args.J, K = args.K, L = args.L;
+    const int64_t n0 = (int64_t)tn * BN, j0 = (int64_t)jblk * RB;
+    const int slice = kgp * Cfg::NW + wave;
+    const int64_t k0 = (int64_t)slice * SL;
+    if (k0 >= K) return;                   // wavefront-uniform; this kernel has no barrier
+    const int64_t i_lo = (int64_t)split * args.isplit;
+    const int64_t i_hi = (i_lo + args.isplit < I) ? i_lo + args.isplit : I;      // i_lo < i_hi by the plan
+
+    vec_t d[LB][NKG];
+    mttkrp_load_d<T, GUARD>(args.D, K, L, k0, n0, li, ls, d);
+
+    typename MF::acc_t acc[LB][MI];
+#pragma unroll
+    for (int lb = 0; lb < LB; ++lb)
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int v = 0; v < MF::NACC; ++v) acc[lb][mi][v] = T(0);
+
+    vec_t rs[Cfg::PER_T];
+    T cnext[LB];                           // C(i, l) of the block in flight, l as in d
+    const MttkrpPieces<T> pc(lane, K);
+    auto fetch = [&](int64_t i) {
+        mttkrp_load_block<T, GUARD>(args.B + (i * J + j0) * K + k0, K, J - j0, K - k0, pc, rs);
+#pragma unroll
+        for (int lb = 0; lb < LB; ++lb) {
+            const int64_t l = n0 + (LB == 1 ? li : 2 * li + lb);
+            cnext[lb] = (!GUARD || l < L) ? args.C[i * L + l] : T(0);
+        }
+    };
+
+    fetch(i_lo);
+    for (int64_t i = i_lo; i < i_hi; ++i) {
+        T c[LB];
+#pragma unroll
+        for (int lb = 0; lb < LB; ++lb) c[lb] = cnext[lb];
+        mttkrp_patch_store<T>(patch, pc, rs);
+        fetch(i + 1 < i_hi ? i + 1 : i);   // past the end: a redundant, in-bounds reload
+        wave_lds_fence();
+        vec_t ds[LB][NKG];                 // the slice of D scaled by C(i, l)
+#pragma unroll
+        for (int lb = 0; lb < LB; ++lb)
+#pragma unroll
+            for (int g = 0; g < NKG; ++g)
+#pragma unroll
+                for (int t = 0; t < KV; ++t) ds[lb][g][t] = d[lb][g][t] * c[lb];
+        mttkrp_patch_mfma<T>(patch, li, ls, ds, acc);
+        wave_lds_fence();
+    }
+
+    const int nparts = args.nsplit * args.nslices;
+    const int part = split * args.nslices + slice;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+        const int64_t j = j0 + mi * MF::NB + li;
+        if (GUARD && j >= J) continue;
+        T *row = args.partial + (j * nparts + part) * L + n0;
+#pragma unroll
+        for (int lb = 0; lb < LB; ++lb)
+#pragma unroll
+            for (int v = 0; v < MF::NACC; ++v) {
+                const int l = mttkrp_l_of<T>(v, lb, lane);
+                if (!GUARD || n0 + l < L) row[l] = acc[lb][mi][v];
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// MTTKRP along mode 2:  A(k,l) = sum_i sum_j B(i,j,k) * C(i,l) * D(j,l).
+//
+// The output rows are indexed by the CONTIGUOUS index of B, so B's rows are already in
+// MFMA operand layout: the lane that owns output row k reads B(i,j,k) itself, with
+// coalesced 16-byte loads and no LDS.  A lane's VEC neighbouring values belong to VEC
+// interleaved row blocks (block e owns k = ... + li*VEC + e).  The other operand is the
+// Khatri-Rao row W((i,j), l) = C(i,l) * D(j,l), formed in registers: a wavefront keeps 16
+// rows of j (their D values stay in registers), walks a range of i, and for each i
+// multiplies by C(i,l).  The accumulators (KW output rows x 32 columns per wavefront)
+// live as long as the wavefront.  The four wavefronts of a workgroup take neighbouring
+// j-blocks of the same k-range; at the end they are added through LDS in wavefront order
+// and the workgroup writes one partial block; the row-sum kernel finishes.
+// ---------------------------------------------------------------------------
+template <typename T>
+struct MttkrpMode2Cfg {
+    typedef Mfma<T> MF;
+    static constexpr int NT = 256, NW = 4, BN = 32;
+    static constexpr int VEC = 16 / (int)sizeof(T);
+    static constexpr int KW = 512 / (int)sizeof(T);        // output rows (k) per workgroup
+    static constexpr int NP = KW / (MF::MB * VEC);         // 16-byte loads per lane per r-group
+    static constexpr int RBK = NP * VEC;                   // row blocks per wavefront
+    static constexpr int LB = BN / MF::NB;                 // column blocks
+    static constexpr int JB = 16;                          // rows of j per wavefront
+    static constexpr int NG = JB / MF::KS;                 // MFMA steps (groups of KS rows) per block
+    static constexpr int PER_T = NG * NP;                  // loads per lane per block
+    static constexpr int NACC = RBK * LB * MF::NACC;       // accumulator values per lane
+    static constexpr int LDS_BYTES = NACC * 64 * (int)sizeof(T);
+    static_assert(KW % (MF::MB * VEC) == 0 && JB % MF::KS == 0, "tile shape");
+};
+
+template <typename T>
+struct MttkrpMode2Args {
+    const T *B;        // I x J x K
+    const T *C;        // I x L
+    const T *D;        // J x L
+    T *partial;        // (K * nparts) x L: row k * nparts + (split * jgroups + jgroup);
+                       // the output itself when nparts == 1
+    int64_t I, J, K, L;
+    int64_t isplit;    // i per range
+    int nsplit;        // ranges of i, none empty
+    int jgroups;       // ceil(J / (4 * JB))
+    int kblocks;       // ceil(K / KW)
+    int tiles_n;       // ceil(L / 32)
+};
+
+template <typename T, bool GUARD>
+__global__ void __launch_bounds__(256, GUARD ? 1 : 2)
+mttkrp_mode2_kernel(const MttkrpMode2Args<T> args) {
+    typedef MttkrpMode2Cfg<T> Cfg;
+    typedef Mfma<T> MF;
+    typedef typename VecOf<T, Cfg::VEC>::type vec_t;
+    constexpr int VEC = Cfg::VEC, NP = Cfg::NP, RBK = Cfg::RBK, LB = Cfg::LB, NG = Cfg::NG;
+    constexpr int PER_T = Cfg::PER_T, JB = Cfg::JB;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    T *red = reinterpret_cast<T *>(lds_raw);          // [NACC][64]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane % MF::MB, ls = lane / MF::MB;
+
+    int bid = blockIdx.x;
+    const int tn = bid % args.tiles_n;     bid /= args.tiles_n;
+    const int kblk = bid % args.kblocks;   bid /= args.kblocks;
+    const int jgroup = bid % args.jgroups; bid /= args.jgroups;
+    const int split = bid;
+    const int64_t I = args.I, J = args.J, K = args.K, L = args.L;
+    const int64_t n0 = (int64_t)tn * Cfg::BN, k0 = (int64_t)kblk * Cfg::KW;
+    const int64_t j0 = ((int64_t)jgroup * Cfg::NW + wave) * JB;
+    const bool active = j0 < J;                       // wavefront-uniform
+    const int64_t i_lo = (int64_t)split * args.isplit;
+    const int64_t i_hi = (i_lo + args.isplit < I) ? i_lo + args.isplit : I;
+
+    typename MF::acc_t acc[RBK][LB];
+#pragma unroll
+    for (int rb = 0; rb < RBK; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < LB; ++cb)
+#pragma unroll
+            for (int v = 0; v < MF::NACC; ++v) acc[rb][cb][v] = T(0);
+
+    if (active) {
+        // D(j, l) of this wavefront's rows: dj[g][cb] for j = j0 + g*KS + ls, l = n0 + cb*NB + li
+        T dj[NG][LB];
+#pragma unroll
+        for (int g = 0; g < NG; ++g)
+#pragma unroll
+            for (int cb = 0; cb < LB; ++cb) {
+                const int64_t j = j0 + g * MF::KS + ls, l = n0 + cb * MF::NB + li;
+                dj[g][cb] = (!GUARD || (j < J && l < L)) ? args.D[j * L + l] : T(0);
+            }
+        // byte offsets of the lane's pieces inside a block (rows j0.., columns k0..)
+        uint32_t boff[PER_T];
+#pragma unroll
+        for (int g = 0; g < NG; ++g)
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+                boff[g * NP + p] = (uint32_t)(((int64_t)(g * MF::KS + ls) * K + p * MF::MB * VEC + li * VEC)
+                                              * (int64_t)sizeof(T));
+
+        auto fetch = [&](int64_t i, vec_t (&rs)[PER_T], T (&c)[LB]) {
+            const T *base = args.B + (i * J + j0) * K + k0;                     // wavefront-uniform
+            if constexpr (!GUARD) {
+#pragma unroll
+                for (int q = 0; q < PER_T; ++q)
+                    rs[q] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(
+                        reinterpret_cast<const char *>(base) + boff[q]));
+            } else {
+#pragma unroll
+                for (int g = 0; g < NG; ++g)
+#pragma unroll
+                    for (int p = 0; p < NP; ++p)
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) {
+                            const int64_t jr = g * MF::KS + ls, kc = p * MF::MB * VEC + li * VEC + e;
+                            rs[g * NP + p][e] = (j0 + jr < J && k0 + kc < K) ? base[jr * K + kc] : T(0);
+                        }
+            }
+#pragma unroll
+            for (int cb = 0; cb < LB; ++cb) {
+                const int64_t l = n0 + cb * MF::NB + li;
+                c[cb] = (!GUARD || l < L) ? args.C[i * L + l] : T(0);
+            }
+        };
+        auto multiply = [&](const vec_t (&rs)[PER_T], const T (&c)[LB]) {
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                T w[LB];
+#pragma unroll
+                for (int cb = 0; cb < LB; ++cb) w[cb] = c[cb] * dj[g][cb];
+#pragma unroll
+                for (int p = 0; p < NP; ++p)
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e)
+#pragma unroll
+                        for (int cb = 0; cb < LB; ++cb)
+                            acc[p * VEC + e][cb] = MF::run(rs[g * NP + p][e], w[cb], acc[p * VEC + e][cb]);
+            }
+        };
+
+        // two register sets: the block of i+1 is in flight while the block of i is multiplied
+        vec_t rs0[PER_T], rs1[PER_T];
+        T c0[LB], c1[LB];
+        fetch(i_lo, rs0, c0);
+        for (int64_t i = i_lo; i < i_hi; i += 2) {
+            fetch(i + 1 < i_hi ? i + 1 : i, rs1, c1);      // past the end: a redundant, in-bounds reload
+            multiply(rs0, c0);
+            if (i + 1 >= i_hi) break;
+            fetch(i + 2 < i_hi ? i + 2 : i + 1, rs0, c0);
+            multiply(rs1, c1);
+        }
+    }
+
+    // add the four wavefronts in wavefront order (inactive ones hold zeros)
+#pragma unroll 1
+    for (int w = 0; w < Cfg::NW; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int rb = 0; rb < RBK; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < LB; ++cb)
+#pragma unroll
+                    for (int v = 0; v < MF::NACC; ++v) {
+                        T *slot = red + ((rb * LB + cb) * MF::NACC + v) * 64 + lane;
+                        *slot = (w == 0) ? acc[rb][cb][v] : *slot + acc[rb][cb][v];
+                    }
+        }
+        __syncthreads();
+    }
+    // the workgroup's partial block: row block rb is written by wavefront rb % NW
+    const int nparts = args.nsplit * args.jgroups;
+    const int part = split * args.jgroups + jgroup;
+#pragma unroll
+    for (int rb = 0; rb < RBK; ++rb) {
+        if (rb % Cfg::NW != wave) continue;
+        const int p = rb / VEC, e = rb % VEC;
+#pragma unroll
+        for (int cb = 0; cb < LB; ++cb)
+#pragma unroll
+            for (int v = 0; v < MF::NACC; ++v) {
+                const int64_t k = k0 + p * MF::MB * VEC + MF::out_row(v, lane) * VEC + e;
+                const int64_t l = n0 + cb * MF::NB + li;
+                if (!GUARD || (k < K && l < L))
+                    args.partial[(k * nparts + part) * L + l] = red[((rb * LB + cb) * MF::NACC + v) * 64 + lane];
+            }
     }
 }
 

@@ -147,3 +147,27 @@ def test_mode_call_argument_errors(lib):
         assert t(0, mode, 2, 2, 2, 2, a, b, None, None) == 1
         assert t(0, mode, 2, 2, 2, 2, a, b, a, None) == 5
         assert t(1, mode, 2, 2, 2, 0, None, None, None, None) == 0      # empty output
+
+
+def test_mttkrp_mode_argument_errors(lib):
+    a, b, c, d, w = (P(FAKE + 256 * i) for i in range(5))
+    m = lib.distal_mttkrp_mode
+    assert m(0, 3, 2, 2, 2, 2, a, b, c, d, w, 1 << 20, None) == 8
+    assert m(4, 1, 2, 2, 2, 2, a, b, c, d, w, 1 << 20, None) == 3
+    for mode in (0, 1, 2):
+        assert m(0, mode, 2, 2, -2, 2, a, b, c, d, w, 1 << 20, None) == 2
+        assert m(0, mode, 2, 2, 2, 2, a, b, c, None, w, 1 << 20, None) == 1
+        assert m(0, mode, 2, 2, 2, 2, None, b, c, d, w, 1 << 20, None) == 1
+        assert m(0, mode, 2, 2, 2, 2, a, b, c, a, w, 1 << 20, None) == 5
+        assert m(0, mode, 0, 0, 0, 4, None, None, None, None, None, 0, None) == 0
+    # several ranges of i: one partial row per (range, k-slice) resp. (range, group of 64 j)
+    lib.distal_mttkrp_mode_workspace_bytes.restype = ctypes.c_size_t
+    need1 = lib.distal_mttkrp_mode_workspace_bytes(0, 1, 10, 32, 64, 32)
+    assert need1 == 32 * 10 * 32 * 4          # J rows x 10 ranges x 1 slice x L floats
+    need2 = lib.distal_mttkrp_mode_workspace_bytes(0, 2, 10, 32, 128, 32)
+    assert need2 == 128 * 10 * 32 * 4         # K rows x 10 ranges x 1 group x L floats
+    assert lib.distal_mttkrp_mode_workspace_bytes(0, 1, 1, 32, 64, 32) == 0
+    assert lib.distal_mttkrp_mode_workspace_bytes(0, 0, 4, 1000, 8, 32) == lib.distal_mttkrp_workspace_bytes(0, 4, 1000, 8, 32)
+    assert m(0, 1, 10, 32, 64, 32, a, b, c, d, None, 0, None) == 6
+    assert m(0, 1, 10, 32, 64, 32, a, b, c, d, w, need1 - 1, None) == 6
+    assert m(0, 2, 10, 32, 128, 32, a, b, c, d, P(FAKE + 8), need2, None) == 6

@@ -134,3 +134,81 @@ def test_ttm_mode_zero_extents(lib, dtype):
     assert np.array_equal(U.host(A), np.zeros((2, 4, 5)))
     lib.distal_ttm_mode(1, z(2, 3, 0), z(3, 4), z(2, 4, 0))  # empty output: a no-op
     lib.distal_ttm_mode(0, z(2, 3, 5), z(2, 0), z(0, 3, 5))
+
+
+# ------------------------------------------------------------------ mttkrp along a mode
+
+def factor_shapes(shape, mode, L):
+    a, b = [m for m in (0, 1, 2) if m != mode]
+    return (shape[a], L), (shape[b], L)
+
+
+# (I, J, K, L): ragged and tiny shapes (guarded kernels), shapes of whole blocks (vector kernels),
+# several column tiles, one-i-per-range and several-i-per-range splits (odd and even counts)
+MTTKRP_MODE_SHAPES = [(3, 5, 7, 4), (9, 33, 129, 5), (2, 70, 256, 32), (1, 1, 1, 1), (4, 16, 128, 32),
+                      (6, 64, 128, 32), (40, 32, 256, 64), (50, 32, 64, 32), (7, 48, 200, 40),
+                      (100, 256, 512, 32)]
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("I,J,K,L", MTTKRP_MODE_SHAPES)
+def test_mttkrp_mode(lib, oracle, dtype, kind, mode, I, J, K, L):
+    shape = (I, J, K)
+    cs, ds = factor_shapes(shape, mode, L)
+    B = U.gen(50 + mode, 0, shape, dtype, kind, 2)
+    C, D = U.gen(50 + mode, 1, cs, dtype, kind, 2), U.gen(50 + mode, 2, ds, dtype, kind, 2)
+    A = empty((shape[mode], L), dtype)
+    lib.distal_mttkrp_mode(mode, U.dev(B), U.dev(C), U.dev(D), A)
+    compare(U.host(A), oracle.mttkrp_mode(mode, B, C, D), dtype, kind, cs[0] * ds[0])
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("mode", [1, 2])
+def test_mttkrp_mode_selection_and_rank1(lib, dtype, mode):
+    shape = (12, 32, 128)
+    a, b = [m for m in (0, 1, 2) if m != mode]
+    B = U.gen(53, 0, shape, dtype)
+    L = 32
+    C, D = np.zeros((shape[a], L), dtype=dtype), np.zeros((shape[b], L), dtype=dtype)
+    for l in range(L):
+        C[(3 * l + 1) % shape[a], l] = 1
+        D[(5 * l + 2) % shape[b], l] = 1
+    A = empty((shape[mode], L), dtype)
+    lib.distal_mttkrp_mode(mode, U.dev(B), U.dev(C), U.dev(D), A)
+    got = U.host(A)
+    for l in range(L):
+        idx = [slice(None)] * 3
+        idx[a], idx[b] = (3 * l + 1) % shape[a], (5 * l + 2) % shape[b]
+        assert np.array_equal(got[:, l], B[tuple(idx)])
+    # all-ones rank-1 factors: sums over the two other modes
+    A1 = empty((shape[mode], 1), dtype)
+    lib.distal_mttkrp_mode(mode, U.dev(B), U.dev(np.ones((shape[a], 1), dtype)), U.dev(np.ones((shape[b], 1), dtype)), A1)
+    ref = B.astype(np.float64).sum(axis=(a, b))
+    U.assert_close(U.host(A1)[:, 0], ref, dtype, shape[a] * shape[b])
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("mode", [1, 2])
+def test_mttkrp_mode_reproducible_and_zero_extents(lib, dtype, mode):
+    import torch
+    shape = (20, 64, 256)
+    cs, ds = factor_shapes(shape, mode, 32)
+    B, C, D = (U.dev(U.gen(54, o, s, dtype)) for o, s in ((0, shape), (1, cs), (2, ds)))
+    outs = []
+    for _ in range(2):
+        A = empty((shape[mode], 32), dtype)
+        lib.distal_mttkrp_mode(mode, B, C, D, A)
+        outs.append(U.host(A).tobytes())
+    assert outs[0] == outs[1]
+    tdt = getattr(torch, np.dtype(dtype).name)
+    z = lambda *s: torch.zeros(s, dtype=tdt, device="cuda:0")
+    # an empty summed mode gives zeros; an empty output mode is a no-op
+    A = empty((3 if mode == 1 else 4, 5), dtype)
+    lib.distal_mttkrp_mode(mode, z(0, 3, 4), z(0, 5), z(4 if mode == 1 else 3, 5), A)
+    assert np.array_equal(U.host(A), np.zeros(tuple(A.shape)))
+    if mode == 1:
+        lib.distal_mttkrp_mode(1, z(2, 0, 4), z(2, 5), z(4, 5), z(0, 5))
+    else:
+        lib.distal_mttkrp_mode(2, z(2, 3, 0), z(2, 5), z(3, 5), z(0, 5))
