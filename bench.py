@@ -93,7 +93,8 @@ def main():
                     help="comma list of gemm_f64,gemm_f32,ttm,mttkrp,ttv,innerprod (gemm_f64 always runs); "
                          "extra rows, not part of 'all': summa (k-chunk leaf shapes), "
                          "ttv_f64,innerprod_f64,ttm_f64,mttkrp_f64, ttm_mode0,ttm_mode1 (TTM along the "
-                         "other modes of the configs[3] tensor)")
+                         "other modes of the configs[3] tensor), mttkrp_mode1,mttkrp_mode2 (MTTKRP along the "
+                         "other modes of the configs[4] tensor)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB read + 1 GiB write elementwise kernel (torch.add), the known-size "
@@ -364,6 +365,37 @@ def main():
                                  "unit": "GFLOP/s", "cores": cores, "kind": "oracle", "seconds": sec,
                                  "sample": f"first {i_s} of {I} i-slices"}
             r["sample_normwise_err"] = sample_err(A[:i_s].cpu().numpy(), ref)
+        del B, C, D, A
+
+    # ---------------------------------------------------------------- MTTKRP along modes 1 and 2 (extra)
+    if want & {"mttkrp_mode1", "mttkrp_mode2"}:
+        I = J = K = 1024
+        L = 32
+        B = device_tensor(4, 0, (I, J, K), np.float32, device=dev)
+        C = device_tensor(4, 1, (J, L), np.float32, device=dev)       # I = J = K: the factors fit every mode
+        D = device_tensor(4, 2, (K, L), np.float32, device=dev)
+        A = torch.empty((I, L), dtype=torch.float32, device=dev)
+        flops = 2.0 * I * J * K * L + 2.0 * I * J * L
+        bytes_ = 4.0 * (I * J * K + J * L + K * L + I * L)
+        for mode in (1, 2):
+            if f"mttkrp_mode{mode}" not in want:
+                continue
+            r = finish(f"mttkrp_mode{mode}", f"MTTKRP along mode {mode}, B {I}x{J}x{K}, rank {L} f32, seed 4", "f32",
+                       lambda: binding.distal_mttkrp_mode(mode, B, C, D, A), flops, bytes_, "hbm")
+            r["mfma_frac"] = flops / r["ms_kernel_avg"] / 1e9 / PEAK_TFLOPS["f32"]
+            if cpu:
+                # output row x depends only on the slice of B with that mode fixed at x
+                n_s = 8
+                hB = np.ascontiguousarray((B[:, :n_s, :] if mode == 1 else B[:, :, :n_s]).cpu().numpy())
+                hC, hD = C.cpu().numpy(), D.cpu().numpy()
+                t0 = time.perf_counter()
+                ref = oracle.mttkrp_mode(mode, hB, hC, hD)
+                sec = time.perf_counter() - t0
+                r["cpu_baseline"] = {"value": 2.0 * n_s * I * J * L * 1.5 / sec / 1e9, "unit": "GFLOP/s",
+                                     "cores": cores, "kind": "oracle", "seconds": sec,
+                                     "sample": f"first {n_s} of 1024 output rows (3 flop per term, as the oracle "
+                                               "sums the literal triple product)"}
+                r["sample_normwise_err"] = sample_err(A[:n_s].cpu().numpy(), ref)
         del B, C, D, A
 
     head = rows[0]

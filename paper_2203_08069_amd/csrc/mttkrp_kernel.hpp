@@ -501,7 +501,8 @@ mttkrp_mode1_kernel(const MttkrpMode1Args<T> args) {
 // Khatri-Rao row W((i,j), l) = C(i,l) * D(j,l), formed in registers: a wavefront keeps 16
 // rows of j (their D values stay in registers), walks a range of i, and for each i
 // multiplies by C(i,l).  The accumulators (KW output rows x 32 columns per wavefront)
-// live as long as the wavefront.  The four wavefronts of a workgroup take neighbouring
+// live as long as the wavefront, and so does the single register set that holds a block
+// of B: each piece is reloaded with the next slice's values right after its MFMAs issue.  The four wavefronts of a workgroup take neighbouring
 // j-blocks of the same k-range; at the end they are added through LDS in wavefront order
 // and the workgroup writes one partial block; the row-sum kernel finishes.
 // ---------------------------------------------------------------------------
@@ -538,7 +539,7 @@ struct MttkrpMode2Args {
 };
 
 template <typename T, bool GUARD>
-__global__ void __launch_bounds__(256, GUARD ? 1 : 2)
+__global__ void __launch_bounds__(256, GUARD ? 1 : 3)
 mttkrp_mode2_kernel(const MttkrpMode2Args<T> args) {
     typedef MttkrpMode2Cfg<T> Cfg;
     typedef Mfma<T> MF;
@@ -584,40 +585,44 @@ mttkrp_mode2_kernel(const MttkrpMode2Args<T> args) {
                 const int64_t j = j0 + g * MF::KS + ls, l = n0 + cb * MF::NB + li;
                 dj[g][cb] = (!GUARD || (j < J && l < L)) ? args.D[j * L + l] : T(0);
             }
-        // byte offsets of the lane's pieces inside a block (rows j0.., columns k0..)
-        uint32_t boff[PER_T];
-#pragma unroll
-        for (int g = 0; g < NG; ++g)
-#pragma unroll
-            for (int p = 0; p < NP; ++p)
-                boff[g * NP + p] = (uint32_t)(((int64_t)(g * MF::KS + ls) * K + p * MF::MB * VEC + li * VEC)
-                                              * (int64_t)sizeof(T));
-
-        auto fetch = [&](int64_t i, vec_t (&rs)[PER_T], T (&c)[LB]) {
-            const T *base = args.B + (i * J + j0) * K + k0;                     // wavefront-uniform
+        // The lane's piece (g, p) of the block of slice i: row j0 + g*KS + ls, elements
+        // k0 + p*MB*VEC + li*VEC ...  The row-group part of the address is wavefront-uniform.
+        const int64_t lane_off = (int64_t)ls * K + li * VEC;
+        auto piece = [&](int64_t i, int g, int p) -> vec_t {
+            const T *base = args.B + ((i * J + j0 + g * MF::KS) * K + k0 + p * MF::MB * VEC);   // uniform
             if constexpr (!GUARD) {
-#pragma unroll
-                for (int q = 0; q < PER_T; ++q)
-                    rs[q] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(
-                        reinterpret_cast<const char *>(base) + boff[q]));
+                return __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(base + lane_off));
             } else {
+                vec_t x;
 #pragma unroll
-                for (int g = 0; g < NG; ++g)
-#pragma unroll
-                    for (int p = 0; p < NP; ++p)
-#pragma unroll
-                        for (int e = 0; e < VEC; ++e) {
-                            const int64_t jr = g * MF::KS + ls, kc = p * MF::MB * VEC + li * VEC + e;
-                            rs[g * NP + p][e] = (j0 + jr < J && k0 + kc < K) ? base[jr * K + kc] : T(0);
-                        }
+                for (int e = 0; e < VEC; ++e) {
+                    const int64_t jr = g * MF::KS + ls, kc = p * MF::MB * VEC + li * VEC + e;
+                    x[e] = (j0 + jr < J && k0 + kc < K) ? base[lane_off + e] : T(0);
+                }
+                return x;
             }
+        };
+        auto factor = [&](int64_t i, T (&c)[LB]) {
 #pragma unroll
             for (int cb = 0; cb < LB; ++cb) {
                 const int64_t l = n0 + cb * MF::NB + li;
                 c[cb] = (!GUARD || l < L) ? args.C[i * L + l] : T(0);
             }
         };
-        auto multiply = [&](const vec_t (&rs)[PER_T], const T (&c)[LB]) {
+
+        // One register set, refilled piece by piece: as soon as the MFMAs of a row group have
+        // been issued its registers are reloaded with the same group of the next slice, so
+        // every piece has a whole block's multiply time to arrive.
+        vec_t rs[PER_T];
+        T c[LB], cn[LB];
+#pragma unroll
+        for (int g = 0; g < NG; ++g)
+#pragma unroll
+            for (int p = 0; p < NP; ++p) rs[g * NP + p] = piece(i_lo, g, p);
+        factor(i_lo, c);
+        for (int64_t i = i_lo; i < i_hi; ++i) {
+            const int64_t inext = i + 1 < i_hi ? i + 1 : i;      // past the end: a redundant, in-bounds reload
+            factor(inext, cn);
 #pragma unroll
             for (int g = 0; g < NG; ++g) {
                 T w[LB];
@@ -630,19 +635,12 @@ mttkrp_mode2_kernel(const MttkrpMode2Args<T> args) {
 #pragma unroll
                         for (int cb = 0; cb < LB; ++cb)
                             acc[p * VEC + e][cb] = MF::run(rs[g * NP + p][e], w[cb], acc[p * VEC + e][cb]);
+#pragma unroll
+                for (int p = 0; p < NP; ++p) rs[g * NP + p] = piece(inext, g, p);
+                __builtin_amdgcn_sched_barrier(0);     // keep each refill next to the MFMAs that freed it
             }
-        };
-
-        // two register sets: the block of i+1 is in flight while the block of i is multiplied
-        vec_t rs0[PER_T], rs1[PER_T];
-        T c0[LB], c1[LB];
-        fetch(i_lo, rs0, c0);
-        for (int64_t i = i_lo; i < i_hi; i += 2) {
-            fetch(i + 1 < i_hi ? i + 1 : i, rs1, c1);      // past the end: a redundant, in-bounds reload
-            multiply(rs0, c0);
-            if (i + 1 >= i_hi) break;
-            fetch(i + 2 < i_hi ? i + 2 : i + 1, rs0, c0);
-            multiply(rs1, c1);
+#pragma unroll
+            for (int cb = 0; cb < LB; ++cb) c[cb] = cn[cb];
         }
     }
 
