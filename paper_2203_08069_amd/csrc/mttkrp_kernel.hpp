@@ -85,19 +85,18 @@ __device__ __forceinline__ void wave_lds_fence() {
 }
 
 // Where a lane's 16-byte pieces of a row block sit: piece p is row prow + p*RPI, elements
-// pcol .. pcol+VEC-1 of the k-slice; boff[p] is its byte offset from the block's first element
-// for a tensor whose rows are `row_stride` elements apart.
+// pcol .. pcol+VEC-1 of the k-slice.  lane_off is the element offset of piece 0 from the
+// block's first element for a tensor whose rows are `row_stride` elements apart; the step
+// from piece to piece (RPI rows) is the same for every lane.
 template <typename T>
 struct MttkrpPieces {
     typedef MttkrpCfg<T> Cfg;
     int prow, pcol;
-    uint32_t boff[Cfg::PER_T];
+    uint32_t lane_off;
     __device__ __forceinline__ MttkrpPieces(int lane, int64_t row_stride) {
         prow = lane / Cfg::CPR;
         pcol = (lane % Cfg::CPR) * Cfg::VEC;
-#pragma unroll
-        for (int p = 0; p < Cfg::PER_T; ++p)
-            boff[p] = (uint32_t)(((int64_t)(prow + p * Cfg::RPI) * row_stride + pcol) * (int64_t)sizeof(T));
+        lane_off = (uint32_t)((int64_t)prow * row_stride + pcol);
     }
 };
 
@@ -111,9 +110,9 @@ __device__ __forceinline__ void mttkrp_load_block(
     typedef typename VecOf<T, Cfg::VEC>::type vec_t;
     if constexpr (!GUARD) {
 #pragma unroll
-        for (int p = 0; p < Cfg::PER_T; ++p)
+        for (int p = 0; p < Cfg::PER_T; ++p)      // base + p*RPI rows is wavefront-uniform
             rs[p] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(
-                reinterpret_cast<const char *>(base) + pc.boff[p]));
+                base + (int64_t)(p * Cfg::RPI) * row_stride + pc.lane_off));
     } else {
 #pragma unroll
         for (int p = 0; p < Cfg::PER_T; ++p) {
