@@ -368,7 +368,7 @@ def main():
         del B, C, D, A
 
     # ---------------------------------------------------------------- MTTKRP along modes 1 and 2 (extra)
-    if want & {"mttkrp_mode1", "mttkrp_mode2"}:
+    if want & {"mttkrp_mode0", "mttkrp_mode1", "mttkrp_mode2"}:
         I = J = K = 1024
         L = 32
         B = device_tensor(4, 0, (I, J, K), np.float32, device=dev)
@@ -377,7 +377,7 @@ def main():
         A = torch.empty((I, L), dtype=torch.float32, device=dev)
         flops = 2.0 * I * J * K * L + 2.0 * I * J * L
         bytes_ = 4.0 * (I * J * K + J * L + K * L + I * L)
-        for mode in (1, 2):
+        for mode in (0, 1, 2):
             if f"mttkrp_mode{mode}" not in want:
                 continue
             r = finish(f"mttkrp_mode{mode}", f"MTTKRP along mode {mode}, B {I}x{J}x{K}, rank {L} f32, seed 4", "f32",
@@ -386,7 +386,7 @@ def main():
             if cpu:
                 # output row x depends only on the slice of B with that mode fixed at x
                 n_s = 8
-                hB = np.ascontiguousarray((B[:, :n_s, :] if mode == 1 else B[:, :, :n_s]).cpu().numpy())
+                hB = np.ascontiguousarray((B[:n_s], B[:, :n_s, :], B[:, :, :n_s])[mode].cpu().numpy())
                 hC, hD = C.cpu().numpy(), D.cpu().numpy()
                 t0 = time.perf_counter()
                 ref = oracle.mttkrp_mode(mode, hB, hC, hD)

@@ -29,20 +29,6 @@ int current_device() {
     return d;
 }
 
-int compute_units() {
-    static std::atomic<int> cached[kMaxDevices];
-    const int d = current_device();
-    int cu = cached[d].load(std::memory_order_relaxed);
-    if (cu == 0) {
-        int v = 0;
-        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, d) != hipSuccess || v <= 0)
-            v = 256;
-        cached[d].store(v, std::memory_order_relaxed);
-        cu = v;
-    }
-    return cu;
-}
-
 // Opt in, once per device and kernel, to dynamic LDS beyond the default limit.
 template <typename Kern>
 bool allow_lds(Kern kern, int bytes, std::atomic<bool> (&done)[kMaxDevices]) {
@@ -154,113 +140,20 @@ int check_dtype(int dt) { return (dt == DISTAL_F32 || dt == DISTAL_F64) ? DISTAL
 size_t elem_size(int dt) { return dt == DISTAL_F64 ? 8 : 4; }
 
 // ---- MTTKRP ---------------------------------------------------------------
-constexpr int kMttkrpCJ = MttkrpCfg<float>::CJ;   // rows of j per chunk (work item and factor copy)
-// Work decomposition and workspace layout, a function of the shape only (never of the
-// device), so the summation order is reproducible.
-// Workspace: partial rows, I*nchunks*nslices x L, unless there is one per i (then none).
-struct MttkrpPlan {
-    int64_t nchunks, nslices, kgroups, tiles_n, partial_rows, partial_elems;
-    bool ok;
-};
-
-MttkrpPlan mttkrp_plan(int dt, int64_t I, int64_t J, int64_t K, int64_t L) {
-    MttkrpPlan p{};
-    const int64_t sl = 256 / (int64_t)(dt == DISTAL_F64 ? 8 : 4);       // k values per wavefront slice
-    const int64_t cj = kMttkrpCJ;                                         // rows of j per chunk
-    p.nslices = (K + sl - 1) / sl;
-    if (p.nslices < 1) p.nslices = 1;
-    p.kgroups = (p.nslices + 3) / 4;
-    p.tiles_n = (L + 31) / 32;
-    p.nchunks = J > 0 ? (J + cj - 1) / cj : 1;
-    int64_t t;
-    p.ok = mul_ok(I, p.nchunks, &t) && mul_ok(t, p.nslices, &p.partial_rows) &&
-           mul_ok(p.partial_rows, L, &p.partial_elems) && p.partial_elems <= INT64_MAX / 16;
-    if (p.nchunks * p.nslices <= 1) p.partial_elems = 0;
-    return p;
-}
-
-template <typename Kern>
-int resident_blocks_per_cu(Kern kern, int lds_bytes, std::atomic<int> (&cache)[kMaxDevices]) {
-    const int d = current_device();
-    int v = cache[d].load(std::memory_order_relaxed);
-    if (v == 0) {
-        int nb = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, reinterpret_cast<const void *>(kern), 256,
-                                                         (size_t)lds_bytes) != hipSuccess || nb < 1) {
-            (void)hipGetLastError();
-            nb = 1;
-        }
-        cache[d].store(nb, std::memory_order_relaxed);
-        v = nb;
-    }
-    return v;
-}
-
-template <typename T, bool GUARD>
-int launch_mttkrp(MttkrpArgs<T> &a, hipStream_t stream) {
-    typedef MttkrpCfg<T> Cfg;
-    auto kern = mttkrp_kernel<T, GUARD>;
-    static std::atomic<bool> done[kMaxDevices];
-    static std::atomic<int> occ[kMaxDevices];
-    if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
-    // persistent grid: as many workgroups as stay resident, shared out over (chunk, k-group, tile)
-    const int64_t resident = (int64_t)resident_blocks_per_cu(kern, Cfg::LDS_BYTES, occ) * compute_units();
-    int64_t lanes;
-    if (!mul_ok((int64_t)a.kgroups * a.tiles_n, (int64_t)a.nchunks, &lanes)) return DISTAL_ERR_SHAPE;
-    int64_t igroups = resident / lanes;
-    if (igroups < 1) igroups = 1;
-    if (igroups > a.I) igroups = a.I;
-    int64_t nblocks;
-    if (!mul_ok(igroups, lanes, &nblocks) || nblocks > std::numeric_limits<int>::max()) return DISTAL_ERR_SHAPE;
-    a.igroups = (int)igroups;
-    hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
-    return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
-}
-
-template <typename T>
-int mttkrp_t(int64_t I, int64_t J, int64_t K, int64_t L, const T *B, const T *C, const T *D, T *A,
-             void *workspace, hipStream_t stream) {
-    typedef MttkrpCfg<T> Cfg;
-    if (I == 0 || L == 0) return DISTAL_OK;
-    if (J == 0 || K == 0) return launch_fill<T>(A, I, L, L, stream);
-    const MttkrpPlan plan = mttkrp_plan(sizeof(T) == 8 ? DISTAL_F64 : DISTAL_F32, I, J, K, L);
-    const int64_t imax = std::numeric_limits<int>::max();
-    if (!plan.ok || plan.kgroups > imax / 8 || plan.tiles_n > imax / 8 || plan.nchunks > imax / 8 ||
-        plan.nchunks * plan.nslices > imax)
-        return DISTAL_ERR_SHAPE;
-    T *partial = static_cast<T *>(workspace);
-    const int64_t per_i = plan.nchunks * plan.nslices;
-    MttkrpArgs<T> a{};
-    a.B = B; a.C = C; a.D = D;
-    a.I = I; a.J = J; a.K = K; a.L = L;
-    a.nchunks = (int)plan.nchunks;
-    a.nslices = (int)plan.nslices;
-    a.kgroups = (int)plan.kgroups;
-    a.tiles_n = (int)plan.tiles_n;
-    a.partial = per_i == 1 ? A : partial;
-    // the unguarded kernel addresses a 32-row block with 32-bit byte offsets
-    const bool full = aligned16(B) && aligned16(C) && J % Cfg::RB == 0 && K % Cfg::SL == 0 &&
-                      L % Cfg::BN == 0 && K <= (1 << 22);
-    const int rc = full ? launch_mttkrp<T, false>(a, stream) : launch_mttkrp<T, true>(a, stream);
-    if (rc != DISTAL_OK || per_i == 1) return rc;
-    const int64_t blocks = I < 4096 ? I : 4096;
-    hipLaunchKernelGGL(mttkrp_reduce_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream,
-                       static_cast<const T *>(partial), A, I, L, (int)per_i);
-    return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
-}
-
-// ---- MTTKRP along modes 1 and 2 --------------------------------------------
-// Both kernels give every workgroup a fixed piece of the two kept indices and a contiguous
-// range of i; the number of ranges is a function of the shape only (enough workgroups for
-// three per CU of a 256-CU part), never of the device, so the summation order is reproducible.
+// Every workgroup gets a fixed piece of the output rows and of one summed index, and a
+// contiguous range of the other summed index (j for mode 0, i for modes 1 and 2).  The number
+// of ranges is a function of the shape only (enough workgroups for three per CU of a 256-CU
+// part), never of the device, so the summation order is reproducible across devices.
+// Workspace: one partial row of L values per (output row, range, piece), none when that is
+// one row per output row.
 constexpr int64_t kModeTargetBlocks = 768;
 
 struct MttkrpModePlan {
     int64_t tasks;          // workgroups per range of i
-    int64_t isplit, nsplit; // i per range; ranges (none empty)
+    int64_t isplit, nsplit; // walked indices per range; ranges (none empty)
     int64_t nparts;         // partial rows per output row
     int64_t partial_elems;  // workspace elements (0 when nparts == 1)
-    int64_t nslices, kgroups, jblocks, jgroups, kblocks, tiles_n;
+    int64_t nslices, kgroups, jblocks /* blocks of 32 kept indices */, jgroups, kblocks, tiles_n;
     bool ok;
 };
 
@@ -269,14 +162,14 @@ MttkrpModePlan mttkrp_mode_plan(int dt, int mode, int64_t I, int64_t J, int64_t 
     const int64_t esz = dt == DISTAL_F64 ? 8 : 4;
     p.tiles_n = (L + 31) / 32;
     int64_t out_rows, per_split;
-    if (mode == 1) {
+    if (mode != 2) {                       // kept index r = i (mode 0) or j (mode 1), the other one is walked
         const int64_t sl = 256 / esz;
+        out_rows = mode == 0 ? I : J;
         p.nslices = (K + sl - 1) / sl;
         p.kgroups = (p.nslices + 3) / 4;
-        p.jblocks = (J + 31) / 32;
+        p.jblocks = (out_rows + 31) / 32;
         p.ok = mul_ok(p.kgroups * p.tiles_n, p.jblocks, &p.tasks);
         per_split = p.nslices;
-        out_rows = J;
     } else {
         const int64_t kw = 512 / esz;
         p.kblocks = (K + kw - 1) / kw;
@@ -286,11 +179,12 @@ MttkrpModePlan mttkrp_mode_plan(int dt, int mode, int64_t I, int64_t J, int64_t 
         out_rows = K;
     }
     if (!p.ok || p.tasks < 1) { p.ok = false; return p; }
+    const int64_t walked = mode == 0 ? J : I;                 // the index each workgroup walks a range of
     int64_t want = (kModeTargetBlocks + p.tasks - 1) / p.tasks;
-    if (want > I) want = I;
+    if (want > walked) want = walked;
     if (want < 1) want = 1;
-    p.isplit = (I + want - 1) / want;
-    p.nsplit = (I + p.isplit - 1) / p.isplit;
+    p.isplit = (walked + want - 1) / want;
+    p.nsplit = (walked + p.isplit - 1) / p.isplit;
     int64_t rows;
     p.ok = mul_ok(p.nsplit, per_split, &p.nparts) && mul_ok(out_rows, p.nparts, &rows) &&
            mul_ok(rows, L, &p.partial_elems) && p.partial_elems <= INT64_MAX / 16 &&
@@ -304,31 +198,34 @@ MttkrpModePlan mttkrp_mode_plan(int dt, int mode, int64_t I, int64_t J, int64_t 
 template <typename T>
 int mttkrp_mode_t(int mode, int64_t I, int64_t J, int64_t K, int64_t L, const T *B, const T *C, const T *D,
                   T *A, void *workspace, hipStream_t stream) {
-    const int64_t out_rows = mode == 1 ? J : K;
+    const int64_t out_rows = mode == 0 ? I : (mode == 1 ? J : K);
     if (out_rows == 0 || L == 0) return DISTAL_OK;
-    if (I == 0 || (mode == 1 ? K : J) == 0) return launch_fill<T>(A, out_rows, L, L, stream);
+    if (I == 0 || J == 0 || K == 0) return launch_fill<T>(A, out_rows, L, L, stream);
     const MttkrpModePlan plan = mttkrp_mode_plan(sizeof(T) == 8 ? DISTAL_F64 : DISTAL_F32, mode, I, J, K, L);
     if (!plan.ok) return DISTAL_ERR_SHAPE;
     T *partial = plan.nparts == 1 ? A : static_cast<T *>(workspace);
     const unsigned nblocks = (unsigned)(plan.tasks * plan.nsplit);
-    // the unguarded kernels address a row block with 32-bit byte offsets
-    const bool aligned = aligned16(B) && L % 32 == 0 && K <= (1 << 22);
-    if (mode == 1) {
+    const bool aligned = aligned16(B) && L % 32 == 0;
+    if (mode != 2) {
         typedef MttkrpCfg<T> Cfg;
-        MttkrpMode1Args<T> a{};
-        a.B = B; a.C = C; a.D = D; a.partial = partial;
-        a.I = I; a.J = J; a.K = K; a.L = L;
-        a.isplit = plan.isplit; a.nsplit = (int)plan.nsplit;
+        MttkrpWalkArgs<T> a{};
+        a.B = B; a.F = C; a.D = D; a.partial = partial;
+        a.K = K; a.L = L;
+        int64_t jk;
+        if (!mul_ok(J, K, &jk)) return DISTAL_ERR_SHAPE;
+        if (mode == 0) { a.R = I; a.W = J; a.row_stride = jk; a.walk_stride = K; }
+        else           { a.R = J; a.W = I; a.row_stride = K;  a.walk_stride = jk; }
+        a.wsplit = plan.isplit; a.nsplit = (int)plan.nsplit;
         a.nslices = (int)plan.nslices; a.kgroups = (int)plan.kgroups;
-        a.tiles_n = (int)plan.tiles_n; a.jblocks = (int)plan.jblocks;
-        constexpr int lds = Cfg::NW * Cfg::PATCH * (int)sizeof(T);
+        a.tiles_n = (int)plan.tiles_n; a.rblocks = (int)plan.jblocks;
+        constexpr int lds = Cfg::LDS_BYTES;
         static std::atomic<bool> done_full[kMaxDevices], done_guard[kMaxDevices];
-        if (aligned && J % Cfg::RB == 0 && K % Cfg::SL == 0) {
-            auto kern = mttkrp_mode1_kernel<T, false>;
+        if (aligned && a.R % Cfg::RB == 0 && K % Cfg::SL == 0) {
+            auto kern = mttkrp_walk_kernel<T, false>;
             if (!allow_lds(kern, lds, done_full)) return DISTAL_ERR_LAUNCH;
             hipLaunchKernelGGL(kern, dim3(nblocks), dim3(Cfg::NT), lds, stream, a);
         } else {
-            auto kern = mttkrp_mode1_kernel<T, true>;
+            auto kern = mttkrp_walk_kernel<T, true>;
             if (!allow_lds(kern, lds, done_guard)) return DISTAL_ERR_LAUNCH;
             hipLaunchKernelGGL(kern, dim3(nblocks), dim3(Cfg::NT), lds, stream, a);
         }
@@ -512,17 +409,8 @@ int distal_ttm_mode(distal_dtype dt, int mode, int64_t I, int64_t J, int64_t K, 
                                I, 0, jk, rk);
 }
 
-size_t distal_mttkrp_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L) {
-    if (check_dtype(dt) != DISTAL_OK || I < 0 || J < 0 || K < 0 || L < 0) return 0;
-    if (I == 0 || J == 0 || K == 0 || L == 0) return 0;
-    const MttkrpPlan p = mttkrp_plan(dt, I, J, K, L);
-    if (!p.ok) return 0;
-    return (size_t)p.partial_elems * elem_size(dt);
-}
-
 size_t distal_mttkrp_mode_workspace_bytes(distal_dtype dt, int mode, int64_t I, int64_t J, int64_t K,
                                           int64_t L) {
-    if (mode == 0) return distal_mttkrp_workspace_bytes(dt, I, J, K, L);
     if (check_dtype(dt) != DISTAL_OK || mode < 0 || mode > 2 || I < 0 || J < 0 || K < 0 || L < 0) return 0;
     if (I == 0 || J == 0 || K == 0 || L == 0) return 0;
     const MttkrpModePlan p = mttkrp_mode_plan(dt, mode, I, J, K, L);
@@ -535,12 +423,12 @@ int distal_mttkrp_mode(distal_dtype dt, int mode, int64_t I, int64_t J, int64_t 
                        size_t workspace_bytes, void *stream) {
     if (check_dtype(dt) != DISTAL_OK) return DISTAL_ERR_DTYPE;
     if (mode < 0 || mode > 2) return DISTAL_ERR_MODE;
-    if (mode == 0) return distal_mttkrp(dt, I, J, K, L, B, C, D, A, workspace, workspace_bytes, stream);
     if (I < 0 || J < 0 || K < 0 || L < 0) return DISTAL_ERR_SHAPE;
     // factor extents: C belongs to mode i, D to k (mode 1) or j (mode 2); the output to the mode itself
-    const int64_t drows = mode == 1 ? K : J, arows = mode == 1 ? J : K;
+    const int64_t crows = mode == 0 ? J : I, drows = mode == 2 ? J : K;
+    const int64_t arows = mode == 0 ? I : (mode == 1 ? J : K);
     int64_t nb, nc, nd, na;
-    if (!tensor_elems(I, J, K, &nb) || !mul_ok(I, L, &nc) || !mul_ok(drows, L, &nd) || !mul_ok(arows, L, &na))
+    if (!tensor_elems(I, J, K, &nb) || !mul_ok(crows, L, &nc) || !mul_ok(drows, L, &nd) || !mul_ok(arows, L, &na))
         return DISTAL_ERR_SHAPE;
     const bool work = nb > 0 && L > 0;
     if (work && !mttkrp_mode_plan(dt, mode, I, J, K, L).ok) return DISTAL_ERR_SHAPE;
@@ -560,30 +448,14 @@ int distal_mttkrp_mode(distal_dtype dt, int mode, int64_t I, int64_t J, int64_t 
                                 (float *)A, workspace, s);
 }
 
+size_t distal_mttkrp_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L) {
+    return distal_mttkrp_mode_workspace_bytes(dt, 0, I, J, K, L);
+}
+
 int distal_mttkrp(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L, const void *B,
                   const void *C, const void *D, void *A, void *workspace, size_t workspace_bytes,
                   void *stream) {
-    if (check_dtype(dt) != DISTAL_OK) return DISTAL_ERR_DTYPE;
-    if (I < 0 || J < 0 || K < 0 || L < 0) return DISTAL_ERR_SHAPE;
-    int64_t nb, nc, nd, na;
-    if (!tensor_elems(I, J, K, &nb) || !mul_ok(J, L, &nc) || !mul_ok(K, L, &nd) || !mul_ok(I, L, &na) ||
-        !mttkrp_plan(dt, I, J, K, L).ok)
-        return DISTAL_ERR_SHAPE;
-    const bool work = nb > 0 && L > 0;
-    if ((work && (!B || !C || !D)) || (na > 0 && !A)) return DISTAL_ERR_NULL;
-    if (na > 0 && (A == B || A == C || A == D)) return DISTAL_ERR_ALIAS;
-    const size_t need = work ? distal_mttkrp_workspace_bytes(dt, I, J, K, L) : 0;
-    if (need > 0 && (!workspace || workspace_bytes < need ||
-                     (reinterpret_cast<uintptr_t>(workspace) % kWorkspaceAlign) != 0))
-        return DISTAL_ERR_WORKSPACE;
-    if (need > 0 && (workspace == A || workspace == B || workspace == C || workspace == D))
-        return DISTAL_ERR_ALIAS;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (dt == DISTAL_F64)
-        return mttkrp_t<double>(I, J, K, L, (const double *)B, (const double *)C, (const double *)D,
-                                (double *)A, workspace, s);
-    return mttkrp_t<float>(I, J, K, L, (const float *)B, (const float *)C, (const float *)D, (float *)A,
-                           workspace, s);
+    return distal_mttkrp_mode(dt, 0, I, J, K, L, B, C, D, A, workspace, workspace_bytes, stream);
 }
 
 int distal_ttv(distal_dtype dt, int64_t I, int64_t J, int64_t K, const void *B, const void *c,

@@ -225,7 +225,7 @@ contract_kernel(ContractArgs<T> args) {
     typedef Mfma<T> MF;
     typedef typename VecOf<T, Cfg::VEC>::type vec_t;
     typedef typename VecOf<T, Cfg::CV>::type cvec_t;
-    constexpr int VEC = Cfg::VEC, KV = Cfg::KV, KG = Cfg::KG, MI = Cfg::MI, NI = Cfg::NI;
+    constexpr int VEC = Cfg::VEC, KG = Cfg::KG, MI = Cfg::MI, NI = Cfg::NI;
     constexpr int CV = Cfg::CV, NG = Cfg::NG, NT = Cfg::NT;
     constexpr int ARL = Cfg::A_ROWLEN / VEC;          // 16-byte pieces per staged A row
 

@@ -1,64 +1,35 @@
-// Fused MTTKRP for gfx950:  A(i,l) = sum_j C(j,l) * ( sum_k B(i,j,k) * D(k,l) ).
+// MTTKRP for gfx950 along every mode of the tensor, in one pass over B:
+//   mode 0: A(i,l) = sum_j sum_k B(i,j,k) * C(j,l) * D(k,l)
+//   mode 1: A(j,l) = sum_i sum_k B(i,j,k) * C(i,l) * D(k,l)
+//   mode 2: A(k,l) = sum_i sum_j B(i,j,k) * C(i,l) * D(j,l)
 //
 // The paper's leaf casts MTTKRP to matrix multiplications followed by an
-// element-wise reduction (evaluation section, leaf kernels).  Here both happen
-// in one pass over B, which is read from HBM exactly once.  After a one-time
-// set-up every wavefront is an independent stream: there is no workgroup barrier
-// in the streaming loop, and the only global loads in it are fully coalesced
-// 16-byte loads of B (the address unit, not HBM or the matrix pipe, is the first
-// thing lane-scattered loads exhaust here).
+// element-wise reduction (evaluation section, leaf kernels).  Here the second
+// factor matrix is folded INTO one operand of the matrix products (each k-slice of
+// D, or each row of D, is scaled by the other factor's entry before it is fed to
+// the MFMAs), so the products of all values of the summed non-contiguous index
+// accumulate in place in the matrix pipe and no separate reduction pass over an
+// intermediate exists.  B is read from HBM exactly once, by fully coalesced
+// 16-byte loads (the address unit, not HBM or the matrix pipe, is the first thing
+// lane-scattered loads exhaust here).  Every wavefront is an independent stream;
+// nothing is atomic and the work split depends on the shape only, so results are
+// bitwise reproducible, also across devices.
 //
-//   * The grid is persistent.  A workgroup is pinned to one chunk of j (CJ rows),
-//     one group of four k-slices and one column tile, and walks a strided list of
-//     i.  The factor rows C(chunk, tile) are copied to LDS once, at set-up.
-//   * A wavefront owns ONE k-slice of SL = 256 bytes for its whole life.  The D
-//     values of its slice (SL k x 32 l) are loaded into registers once, already in
-//     the transposed MFMA operand layout, so D costs no further traffic.  The four wavefronts of a workgroup take neighbouring
-//     slices of the same rows (1 KiB contiguous per row).
-//   * The wavefront walks (i, block of RB = 32 rows).  A block's RB x SL piece of B
-//     goes global -> registers (the next block's loads are in flight during the
-//     multiply) -> a wavefront-private LDS patch -> back in MFMA operand layout.
-//     Only the wavefront that wrote the patch reads it, so ordering inside the
-//     wavefront suffices.
-//   * MFMA forms the TRANSPOSED partial product Tt(l,j) = sum_{k in slice} D(k,l)
-//     B(j,k): a lane owns one j and several l, so the factor values C(j, l..) it
-//     needs are neighbours in the LDS copy.  The sums over j and over k-slices are
-//     both linear: after every block the lane scales its accumulators by C(j,l) and
-//     adds them to running sums, one per owned l.
-//   * At the end of an (i, chunk) the lanes that own the same l are added with DPP
-//     rotations in a fixed order and the wavefront writes its own partial row of 32
-//     values to the workspace; a last small kernel adds the partial rows of each i
-//     in order.  Nothing is atomic and no sum depends on the grid size: results are
-//     bitwise reproducible.
+//   mttkrp_walk_kernel   modes 0 and 1 (the MFMA contracts the contiguous index k)
+//   mttkrp_mode2_kernel  mode 2 (the output rows are the contiguous index)
+//   mttkrp_reduce_kernel adds the partial rows of each output row in a fixed order
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include "gemm_kernel.hpp"
-#include "stream_kernels.hpp"   // sum16 (DPP row rotations)
 
 namespace distal {
-
-template <typename T>
-struct MttkrpArgs {
-    const T *B;        // I x J x K
-    const T *C;        // J x L
-    const T *D;        // K x L
-    T *partial;        // (I * nchunks * nslices) x L: row ((i * nchunks + chunk) * nslices + slice);
-                       // the output itself when nchunks * nslices == 1
-    int64_t I, J, K, L;
-    int nchunks;       // ceil(J / CJ)
-    int nslices;       // ceil(K / SL)
-    int kgroups;       // ceil(nslices / 4): k-slices are handed out four per workgroup
-    int tiles_n;       // ceil(L / 32)
-    int igroups;       // gridDim.x / (tiles_n * kgroups * nchunks): workgroups sharing the list of i
-};
 
 template <typename T>
 struct MttkrpCfg {
     typedef Mfma<T> MF;
     static constexpr int NT = 256, NW = 4, BN = 32, RB = 32;
-    static constexpr int CJ = 128;                        // rows of j per chunk
     static constexpr int VEC = 16 / (int)sizeof(T);
     static constexpr int SL = 256 / (int)sizeof(T);       // k values per slice
     static constexpr int KV = VEC, KG = MF::KS * KV, NKG = SL / KG;
@@ -69,10 +40,8 @@ struct MttkrpCfg {
     static constexpr int PER_T = RB / RPI;                // loads per lane per block (8)
     static constexpr int LDW = SL + VEC;                  // patch row stride (elements): +16 B
     static constexpr int PATCH = RB * LDW;                // elements per wavefront patch
-    static constexpr int LDC = BN + VEC;                  // factor-copy row stride (elements): +16 B
-    static constexpr int C_ELEMS = CJ * LDC;
-    static constexpr int LDS_BYTES = (NW * PATCH + C_ELEMS) * (int)sizeof(T);
-    static_assert(SL % KG == 0 && RB % MF::NB == 0 && LB <= 2 && 64 % CPR == 0 && CJ % RB == 0, "tile shape");
+    static constexpr int LDS_BYTES = NW * PATCH * (int)sizeof(T);
+    static_assert(SL % KG == 0 && RB % MF::NB == 0 && LB <= 2 && 64 % CPR == 0, "tile shape");
 };
 
 // ---- pieces shared by the kernels of this file --------------------------------------------
@@ -92,11 +61,11 @@ template <typename T>
 struct MttkrpPieces {
     typedef MttkrpCfg<T> Cfg;
     int prow, pcol;
-    uint32_t lane_off;
+    int64_t lane_off;
     __device__ __forceinline__ MttkrpPieces(int lane, int64_t row_stride) {
         prow = lane / Cfg::CPR;
         pcol = (lane % Cfg::CPR) * Cfg::VEC;
-        lane_off = (uint32_t)((int64_t)prow * row_stride + pcol);
+        lane_off = (int64_t)prow * row_stride + pcol;
     }
 };
 
@@ -217,194 +186,50 @@ __device__ __forceinline__ int mttkrp_l_of(int v, int lb, int lane) {
     return 2 * Mfma<T>::out_row(v, lane) + lb;
 }
 
+// ---------------------------------------------------------------------------
+// MTTKRP along mode 0 or 1, as one sum over a WALKED index w of scaled matrix products:
+//   A(r,l) = sum_w F(w,l) * ( sum_k B[r, w, k] * D(k,l) )
+// where r is the kept index (the output row), w the other index that is not contracted by
+// the MFMA, and B[r, w, k] = B + r*row_stride + w*walk_stride + k:
+//   mode 0: r = i, w = j, F = C (J x L)      mode 1: r = j, w = i, F = C (I x L).
+//
+// The contracted index k is the contiguous one, while the MFMA wants the lanes of an operand
+// spread over rows.  A block of B (RB = 32 values of r, one k-slice of SL = 256 bytes) therefore
+// goes global -> registers by coalesced loads (a wavefront load covers 4 rows x 256 B; the next
+// block's loads are in flight during the multiply) -> a wavefront-private LDS patch -> back in
+// MFMA operand layout.  Only the wavefront that wrote a patch reads it, so ordering inside the
+// wavefront suffices.  The MFMAs form the TRANSPOSED product Tt(l,r) = sum_k D(k,l) B[r,w,k].
+// A wavefront keeps ONE block of r and one k-slice for its whole life (the D values of the
+// slice stay in registers, already transposed) and walks a range of w.  For each w it scales
+// its D slice by F(w,l) (32 multiplies) and lets the MFMAs add straight into one accumulator
+// that lives as long as the wavefront: no per-block reduction, no lane reduction, no barrier
+// anywhere.  The four wavefronts of a workgroup take neighbouring slices of the same rows
+// (1 KiB contiguous per row).  At the end a wavefront writes its 32 x 32 partial block; the
+// row-sum kernel adds the partial rows of each r in order.
+// ---------------------------------------------------------------------------
+template <typename T>
+struct MttkrpWalkArgs {
+    const T *B;        // I x J x K
+    const T *F;        // W x L: the factor of the walked index
+    const T *D;        // K x L
+    T *partial;        // (R * nparts) x L: row r * nparts + (split * nslices + slice);
+                       // the output itself when nparts == 1
+    int64_t R, W, K, L;
+    int64_t row_stride, walk_stride;   // elements between consecutive r resp. w in B
+    int64_t wsplit;    // w per range
+    int nsplit;        // ranges of w: ceil(W / wsplit), none empty
+    int nslices;       // ceil(K / SL)
+    int kgroups;       // ceil(nslices / 4): k-slices are handed out four per workgroup
+    int tiles_n;       // ceil(L / 32)
+    int rblocks;       // ceil(R / 32)
+};
+
 // GUARD = false: every row block and k-slice of B is full and 16-byte aligned
-// (J % 32 == 0, K % SL == 0, L % 32 == 0, aligned bases) - vector loads only.
+// (R % 32 == 0, K % SL == 0, L % 32 == 0, aligned base) - vector loads only.
 // GUARD = true: any shape and alignment, element loads with bounds checks, zero fill.
 template <typename T, bool GUARD>
 __global__ void __launch_bounds__(256, GUARD ? 1 : (sizeof(T) == 4 ? 3 : 2))
-mttkrp_kernel(const MttkrpArgs<T> args) {
-    typedef MttkrpCfg<T> Cfg;
-    typedef Mfma<T> MF;
-    typedef typename VecOf<T, Cfg::VEC>::type vec_t;
-    constexpr int VEC = Cfg::VEC, NKG = Cfg::NKG, MI = Cfg::MI, LB = Cfg::LB;
-    constexpr int SL = Cfg::SL, BN = Cfg::BN, RB = Cfg::RB, CJ = Cfg::CJ;
-
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    T *lds = reinterpret_cast<T *>(lds_raw);
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    // the wavefront index is the same in all lanes: say so, and every address that depends on it
-    // stays in scalar registers
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int li = lane % MF::MB, ls = lane / MF::MB;
-    T *patch = lds + wave * Cfg::PATCH;
-    T *cfac = lds + Cfg::NW * Cfg::PATCH;          // C(chunk rows, tile columns), row stride LDC
-
-    int bid = blockIdx.x;
-    const int tn = bid % args.tiles_n;    bid /= args.tiles_n;
-    const int kgp = bid % args.kgroups;   bid /= args.kgroups;
-    const int chunk = bid % args.nchunks; bid /= args.nchunks;
-    const int ig = bid;                                         // first i of this workgroup
-    const int64_t n0 = (int64_t)tn * BN;
-    const int64_t I = args.I, J = args.J, K = args.K, L = args.L;
-    const int64_t jb = (int64_t)chunk * CJ;
-    const int64_t je = (jb + CJ < J) ? jb + CJ : J;
-    const int nrb = (int)((je - jb + RB - 1) / RB);
-
-    // set-up: factor rows of this chunk and tile -> LDS, zero outside J x L
-    for (int v = tid; v < CJ * (BN / VEC); v += Cfg::NT) {
-        const int r = v / (BN / VEC), cv = (v % (BN / VEC)) * VEC;
-        vec_t x;
-        if (!GUARD) {
-            x = vec_t(T(0));
-            if (jb + r < J) x = *reinterpret_cast<const vec_t *>(args.C + (jb + r) * L + n0 + cv);
-        } else {
-#pragma unroll
-            for (int e = 0; e < VEC; ++e)
-                x[e] = (jb + r < J && n0 + cv + e < L) ? args.C[(jb + r) * L + n0 + cv + e] : T(0);
-        }
-        *reinterpret_cast<vec_t *>(cfac + r * Cfg::LDC + cv) = x;
-    }
-    __syncthreads();                       // the only barrier of this kernel
-
-    const int slice = kgp * Cfg::NW + wave;
-    const int64_t k0 = (int64_t)slice * SL;                    // this wavefront's k-slice
-    if (k0 >= K || ig >= I) return;       // wavefront-uniform
-
-    vec_t d[LB][NKG];                     // the D operand of this slice, for the wavefront's whole life
-    mttkrp_load_d<T, GUARD>(args.D, K, L, k0, n0, li, ls, d);
-
-    T lsum[LB][MF::NACC];                 // running sum for l = mttkrp_l_of(v, lb, lane)
-#pragma unroll
-    for (int lb = 0; lb < LB; ++lb)
-#pragma unroll
-        for (int v = 0; v < MF::NACC; ++v) lsum[lb][v] = T(0);
-
-    vec_t rs[Cfg::PER_T];
-    // The host sends shapes whose block spans exceed 32-bit byte offsets to the guarded kernel.
-    const MttkrpPieces<T> pc(lane, K);
-
-    // rows [jb + rb*RB, +RB) of slice i, k in [k0, k0 + SL) -> rs
-    auto load_rows = [&](int64_t i, int rb) {
-        const int64_t j0 = jb + (int64_t)rb * RB;
-        mttkrp_load_block<T, GUARD>(args.B + (i * J + j0) * K + k0, K, J - j0, K - k0, pc, rs);   // uniform base
-    };
-
-    // One 32-row block: patch -> MFMA -> fold.  `c` are the lane's factor pieces for this block.
-    auto block = [&](int64_t i, int rb, const vec_t (&c)[MI][4]) {
-        // what comes after this block: the next block of this i, or the first block of the next i
-        const bool last_rb = (rb + 1 == nrb);
-        const int64_t next_i = last_rb ? i + args.igroups : i;
-        const int next_rb = last_rb ? 0 : rb + 1;
-        const bool more = next_i < I;
-
-        mttkrp_patch_store<T>(patch, pc, rs);
-        // past the end: a redundant reload of the current block, never out of bounds
-        load_rows(more ? next_i : i, more ? next_rb : rb);
-        wave_lds_fence();                  // the patch is written and read by this wavefront only
-
-        typename MF::acc_t acc[LB][MI];
-#pragma unroll
-        for (int lb = 0; lb < LB; ++lb)
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int v = 0; v < MF::NACC; ++v) acc[lb][mi][v] = T(0);
-        mttkrp_patch_mfma<T>(patch, li, ls, d, acc);
-        wave_lds_fence();                  // all reads of the patch are done before it is overwritten
-
-        // scale Tt(l, j) by C(j, l) and add into the lane's running sums
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int v = 0; v < MF::NACC; ++v)
-#pragma unroll
-                for (int lb = 0; lb < LB; ++lb) {
-                    T f;
-                    if constexpr (sizeof(T) == 4) f = c[mi][v >> 2][v & 3];
-                    else f = c[mi][v][lb];
-                    lsum[lb][v] = fma_t(acc[lb][mi][v], f, lsum[lb][v]);
-                }
-    };
-
-    // (i, chunk) done: add the lanes that own the same l (same k-slot ls, all li) in a fixed
-    // order and write this wavefront's partial row
-    auto flush = [&](int64_t i) {
-        T *prow_out = args.partial + ((i * args.nchunks + chunk) * args.nslices + slice) * L + n0;
-#pragma unroll
-        for (int lb = 0; lb < LB; ++lb)
-#pragma unroll
-            for (int v = 0; v < MF::NACC; ++v) {
-                T s = sum16(lsum[lb][v]);
-                if (MF::MB == 32) s += __shfl_xor(s, 16);
-                lsum[lb][v] = s;
-            }
-        if (li == 0) {
-#pragma unroll
-            for (int lb = 0; lb < LB; ++lb)
-#pragma unroll
-                for (int v = 0; v < MF::NACC; ++v) {
-                    const int l = mttkrp_l_of<T>(v, lb, lane);
-                    if (!GUARD || n0 + l < L) prow_out[l] = lsum[lb][v];
-                }
-        }
-#pragma unroll
-        for (int lb = 0; lb < LB; ++lb)
-#pragma unroll
-            for (int v = 0; v < MF::NACC; ++v) lsum[lb][v] = T(0);
-    };
-
-    load_rows(ig, 0);
-    for (int64_t i = ig; i < I; i += args.igroups) {
-        for (int rb = 0; rb < nrb; ++rb) {
-            // the lane's factor pieces for this block, from the LDS copy:
-            // binary32: l = 8q + 4*ls + r (v = 4q + r); binary64: l = 2*(4q + ls) + lb (v = q)
-            vec_t c[MI][4];
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi) {
-                const T *crow = cfac + (rb * RB + mi * MF::NB + li) * Cfg::LDC
-                                + (sizeof(T) == 4 ? 4 * ls : 2 * ls);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) c[mi][q] = *reinterpret_cast<const vec_t *>(crow + 8 * q);
-            }
-            block(i, rb, c);
-        }
-        flush(i);
-    }
-}
-
-// ---------------------------------------------------------------------------
-// MTTKRP along mode 1:  A(j,l) = sum_i C(i,l) * ( sum_k B(i,j,k) * D(k,l) ).
-//
-// The contracted index k is still the contiguous one, so a block of B takes the same way
-// as above (coalesced loads -> private patch -> MFMA operand layout) and the same
-// transposed product Tt(l,j) is formed.  What changes is the sum that follows: it runs
-// over i, not over j, so a wavefront keeps ONE 32-row block of j and one k-slice for its
-// whole life and walks a range of i.  For each i it scales its D slice by C(i,l) (32
-// multiplies) and lets the MFMAs add straight into one accumulator that lives as long as
-// the wavefront: no fold, no lane reduction, no barrier anywhere.  At the end it writes
-// its 32 x 32 partial block; the row-sum kernel adds the partial rows of each j in order.
-// ---------------------------------------------------------------------------
-template <typename T>
-struct MttkrpMode1Args {
-    const T *B;        // I x J x K
-    const T *C;        // I x L
-    const T *D;        // K x L
-    T *partial;        // (J * nparts) x L: row j * nparts + (split * nslices + slice);
-                       // the output itself when nparts == 1
-    int64_t I, J, K, L;
-    int64_t isplit;    // i per range
-    int nsplit;        // ranges of i: ceil(I / isplit), none empty
-    int nslices;       // ceil(K / SL)
-    int kgroups;       // ceil(nslices / 4)
-    int tiles_n;       // ceil(L / 32)
-    int jblocks;       // ceil(J / 32)
-};
-
-template <typename T, bool GUARD>
-__global__ void __launch_bounds__(256, GUARD ? 1 : (sizeof(T) == 4 ? 3 : 2))
-mttkrp_mode1_kernel(const MttkrpMode1Args<T> args) {
+mttkrp_walk_kernel(const MttkrpWalkArgs<T> args) {
     typedef MttkrpCfg<T> Cfg;
     typedef Mfma<T> MF;
     typedef typename VecOf<T, Cfg::VEC>::type vec_t;
@@ -421,15 +246,15 @@ mttkrp_mode1_kernel(const MttkrpMode1Args<T> args) {
     int bid = blockIdx.x;
     const int tn = bid % args.tiles_n;     bid /= args.tiles_n;
     const int kgp = bid % args.kgroups;    bid /= args.kgroups;
-    const int jblk = bid % args.jblocks;   bid /= args.jblocks;
+    const int rblk = bid % args.rblocks;   bid /= args.rblocks;
     const int split = bid;
-    const int64_t I = args.I, J = args.J, K = args.K, L = args.L;
-    const int64_t n0 = (int64_t)tn * BN, j0 = (int64_t)jblk * RB;
+    const int64_t R = args.R, W = args.W, K = args.K, L = args.L;
+    const int64_t n0 = (int64_t)tn * BN, r0 = (int64_t)rblk * RB;
     const int slice = kgp * Cfg::NW + wave;
     const int64_t k0 = (int64_t)slice * SL;
     if (k0 >= K) return;                   // wavefront-uniform; this kernel has no barrier
-    const int64_t i_lo = (int64_t)split * args.isplit;
-    const int64_t i_hi = (i_lo + args.isplit < I) ? i_lo + args.isplit : I;      // i_lo < i_hi by the plan
+    const int64_t w_lo = (int64_t)split * args.wsplit;
+    const int64_t w_hi = (w_lo + args.wsplit < W) ? w_lo + args.wsplit : W;      // w_lo < w_hi by the plan
 
     vec_t d[LB][NKG];
     mttkrp_load_d<T, GUARD>(args.D, K, L, k0, n0, li, ls, d);
@@ -443,32 +268,33 @@ mttkrp_mode1_kernel(const MttkrpMode1Args<T> args) {
             for (int v = 0; v < MF::NACC; ++v) acc[lb][mi][v] = T(0);
 
     vec_t rs[Cfg::PER_T];
-    T cnext[LB];                           // C(i, l) of the block in flight, l as in d
-    const MttkrpPieces<T> pc(lane, K);
-    auto fetch = [&](int64_t i) {
-        mttkrp_load_block<T, GUARD>(args.B + (i * J + j0) * K + k0, K, J - j0, K - k0, pc, rs);
+    T fnext[LB];                           // F(w, l) of the block in flight, l as in d
+    const MttkrpPieces<T> pc(lane, args.row_stride);
+    const T *block0 = args.B + r0 * args.row_stride + k0;                        // wavefront-uniform
+    auto fetch = [&](int64_t w) {
+        mttkrp_load_block<T, GUARD>(block0 + w * args.walk_stride, args.row_stride, R - r0, K - k0, pc, rs);
 #pragma unroll
         for (int lb = 0; lb < LB; ++lb) {
             const int64_t l = n0 + (LB == 1 ? li : 2 * li + lb);
-            cnext[lb] = (!GUARD || l < L) ? args.C[i * L + l] : T(0);
+            fnext[lb] = (!GUARD || l < L) ? args.F[w * L + l] : T(0);
         }
     };
 
-    fetch(i_lo);
-    for (int64_t i = i_lo; i < i_hi; ++i) {
-        T c[LB];
+    fetch(w_lo);
+    for (int64_t w = w_lo; w < w_hi; ++w) {
+        T f[LB];
 #pragma unroll
-        for (int lb = 0; lb < LB; ++lb) c[lb] = cnext[lb];
+        for (int lb = 0; lb < LB; ++lb) f[lb] = fnext[lb];
         mttkrp_patch_store<T>(patch, pc, rs);
-        fetch(i + 1 < i_hi ? i + 1 : i);   // past the end: a redundant, in-bounds reload
+        fetch(w + 1 < w_hi ? w + 1 : w);   // past the end: a redundant, in-bounds reload
         wave_lds_fence();
-        vec_t ds[LB][NKG];                 // the slice of D scaled by C(i, l)
+        vec_t ds[LB][NKG];                 // the slice of D scaled by F(w, l)
 #pragma unroll
         for (int lb = 0; lb < LB; ++lb)
 #pragma unroll
             for (int g = 0; g < NKG; ++g)
 #pragma unroll
-                for (int t = 0; t < KV; ++t) ds[lb][g][t] = d[lb][g][t] * c[lb];
+                for (int t = 0; t < KV; ++t) ds[lb][g][t] = d[lb][g][t] * f[lb];
         mttkrp_patch_mfma<T>(patch, li, ls, ds, acc);
         wave_lds_fence();
     }
@@ -477,9 +303,9 @@ mttkrp_mode1_kernel(const MttkrpMode1Args<T> args) {
     const int part = split * args.nslices + slice;
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
-        const int64_t j = j0 + mi * MF::NB + li;
-        if (GUARD && j >= J) continue;
-        T *row = args.partial + (j * nparts + part) * L + n0;
+        const int64_t r = r0 + mi * MF::NB + li;
+        if (GUARD && r >= R) continue;
+        T *row = args.partial + (r * nparts + part) * L + n0;
 #pragma unroll
         for (int lb = 0; lb < LB; ++lb)
 #pragma unroll

@@ -80,12 +80,12 @@ def test_tensor_call_argument_errors(lib):
     assert lib.distal_mttkrp(0, 2, 2, 2, 2, a, b, c, a, w, 1 << 20, None) == 5
     assert lib.distal_mttkrp(0, 2, 2, 2, -2, a, b, c, d, w, 1 << 20, None) == 2
     assert lib.distal_mttkrp(9, 2, 2, 2, 2, a, b, c, d, w, 1 << 20, None) == 3
-    # J large enough to need j-tiles: workspace is then mandatory, big enough and aligned
+    # the sum over j is split into ranges: workspace is then mandatory, big enough and aligned
     need = lib.distal_mttkrp_workspace_bytes(0, 4, 1000, 8, 32)
-    # I x ceil(J / 128) chunks x 1 k-slice x L partial sums, in floats
-    assert need == (4 * 8 * 32) * 4
-    # one chunk and one k-slice: the only partial row of an i is the output row, no workspace
-    assert lib.distal_mttkrp_workspace_bytes(0, 4, 100, 8, 32) == 0
+    # I rows x 500 ranges of two j x 1 k-slice x L partial sums, in floats
+    assert need == (4 * 500 * 32) * 4
+    # one j and one k-slice: the only partial row of an i is the output row, no workspace
+    assert lib.distal_mttkrp_workspace_bytes(0, 4, 1, 8, 32) == 0
     assert lib.distal_mttkrp(0, 4, 1000, 8, 32, a, b, c, d, None, 0, None) == 6
     assert lib.distal_mttkrp(0, 4, 1000, 8, 32, a, b, c, d, w, need - 1, None) == 6
     assert lib.distal_mttkrp(0, 4, 1000, 8, 32, a, b, c, d, P(FAKE + 8), need, None) == 6
