@@ -45,8 +45,8 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the
 # same counters on a plain copy kernel of known size; see profiles/.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "gemm_f64": 9.129e9, "gemm_f32": 3.741e9, "ttm": 5.511e9,
-    "mttkrp": 4.332e9, "ttv": 4.299e9, "innerprod": 8.590e9,
+    "gemm_f64": 9.128e9, "gemm_f32": 3.754e9, "ttm": 5.511e9, "ttm_mode0": 5.505e9, "ttm_mode1": 5.505e9,
+    "mttkrp": 4.331e9, "mttkrp_mode2": 4.329e9, "ttv": 4.299e9, "innerprod": 8.590e9,
 }
 
 
@@ -90,7 +90,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--rows", default="all",
-                    help="comma list of gemm_f64,gemm_f32,ttm,mttkrp,ttv,innerprod (gemm_f64 always runs); "
+                    help="comma list of gemm_f64,gemm_f32,ttm,mttkrp,ttv,innerprod, or all for these six "
+                         "(gemm_f64 always runs); "
                          "extra rows, not part of 'all': summa (k-chunk leaf shapes), "
                          "ttv_f64,innerprod_f64,ttm_f64,mttkrp_f64, ttm_mode0,ttm_mode1 (TTM along the "
                          "other modes of the configs[3] tensor), mttkrp_mode1,mttkrp_mode2 (MTTKRP along the "
@@ -117,8 +118,9 @@ def main():
     binding.load_library()
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    want = {"gemm_f64", "gemm_f32", "ttm", "mttkrp", "ttv", "innerprod"} if args.rows == "all" \
-        else set(args.rows.split(",")) | {"gemm_f64"}
+    want = set(args.rows.split(",")) | {"gemm_f64"}
+    if "all" in want:
+        want |= {"gemm_f32", "ttm", "mttkrp", "ttv", "innerprod"}
     cpu = not args.no_cpu_baseline
     if cpu:
         import oracle
