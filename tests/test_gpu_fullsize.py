@@ -164,3 +164,65 @@ def test_mttkrp_1024(lib, oracle):
     A2 = torch.empty_like(A)
     lib.distal_mttkrp(B, C, D, A2)
     assert torch.equal(A, A2)
+
+
+def test_device_inputs_are_the_generators_bytes():
+    """The device copy that the full-size cases read slices back from is the generator's output."""
+    import torch
+    t = devgen(3, 0, (64, 1024, 1024), np.float32)
+    for start in (0, 12345 * 1024, 64 * 1024 * 1024 - 4096):
+        want = inputs.values(3, 0, start, 4096, np.float32)
+        assert np.array_equal(t.view(-1)[start:start + 4096].cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_ttm_mode_1024(lib, oracle, mode):
+    """TTM along modes 0 and 1 of the configs[3] tensor, in the launch configuration bench.py times
+    (256 x 256 tiles, transposed left operand; mode 1 as a batch of 1024 products)."""
+    import torch
+    I = J = K = 1024
+    R = 256
+    B, C = devgen(3, 0, (I, J, K), np.float32), devgen(3, 1, (K, R), np.float32)
+    shape = [I, J, K]
+    shape[mode] = R
+    A = torch.full(shape, float("nan"), dtype=torch.float32, device="cuda:0")
+    lib.distal_ttm_mode(mode, B, C, A)
+    assert bool(torch.isfinite(A).all())
+    hC = inputs.tensor(3, 1, (K, R), np.float32)
+    # outputs that depend on one slice of B only, recomputed by the oracle from that slice
+    for x in (0, 511, 1023):
+        if mode == 0:       # A(:, j, k0:k0+16) <- B(:, j, k0:k0+16)
+            k0 = (x * 7) % (K - 16)
+            hB = np.ascontiguousarray(B[:, x:x + 1, k0:k0 + 16].cpu().numpy())
+            got = A[:, x:x + 1, k0:k0 + 16].cpu().numpy()
+        else:               # A(i, :, k0:k0+16) <- B(i, :, k0:k0+16)
+            k0 = (x * 5) % (K - 16)
+            hB = np.ascontiguousarray(B[x:x + 1, :, k0:k0 + 16].cpu().numpy())
+            got = A[x:x + 1, :, k0:k0 + 16].cpu().numpy()
+        U.assert_close(got, oracle.ttm_mode(mode, hB, hC), np.float32, 1024)
+    # linear in C, exactly, for a power of two
+    A2 = torch.empty_like(A)
+    lib.distal_ttm_mode(mode, B, C * 2, A2)
+    assert torch.equal(A2, A * 2)
+
+
+@pytest.mark.parametrize("mode", [1, 2])
+def test_mttkrp_mode_1024(lib, oracle, mode):
+    """MTTKRP along modes 1 and 2 of the configs[4] tensor, rank 32, as bench.py launches it."""
+    import torch
+    I = J = K = 1024
+    L = 32
+    B = devgen(4, 0, (I, J, K), np.float32)
+    C, D = devgen(4, 1, (J, L), np.float32), devgen(4, 2, (K, L), np.float32)   # I = J = K: they fit every mode
+    A = torch.full((1024, L), float("nan"), dtype=torch.float32, device="cuda:0")
+    lib.distal_mttkrp_mode(mode, B, C, D, A)
+    assert bool(torch.isfinite(A).all())
+    hC, hD = inputs.tensor(4, 1, (J, L), np.float32), inputs.tensor(4, 2, (K, L), np.float32)
+    # output row x depends on the slice of B with that mode fixed at x
+    for x in (0, 357, 1023):
+        hB = np.ascontiguousarray((B[:, x:x + 1, :] if mode == 1 else B[:, :, x:x + 1]).cpu().numpy())
+        ref = oracle.mttkrp_mode(mode, hB, hC, hD)[0]
+        U.assert_close(A[x].cpu().numpy(), ref, np.float32, 1 << 20)
+    A2 = torch.empty_like(A)
+    lib.distal_mttkrp_mode(mode, B, C, D, A2)
+    assert torch.equal(A, A2)
