@@ -360,3 +360,49 @@ def test_schedule_driver(lib, oracle, dtype):
     U.assert_exact(U.host(schedules.cannon(dA, dB, z(), 3)), ref)
     parts = schedules.johnson(dA, dB, z(), 2, [empty((n, n), dtype) for _ in range(2)])
     U.assert_exact(sum(U.host(p).astype(np.float64) for p in parts), ref)
+
+
+# ------------------------------------------------------------------ graph capture
+
+def test_calls_can_be_captured_in_a_graph(lib, oracle):
+    """Nothing in the library allocates, synchronises or records a memset, so a caller may capture
+    a launch-bound sequence (here the k-steps of a SUMMA schedule plus one call of every other
+    entry point) in a HIP graph.  Every replay is compared with the eager result, bit for bit,
+    with eager work and synchronisations between the replays."""
+    import torch
+    from paper_2203_08069_amd import schedules
+    dt = np.float32
+    n = 384
+    A, Bm = U.dev(U.gen(60, 0, (n, n), dt)), U.dev(U.gen(60, 1, (n, n), dt))
+    T = U.dev(U.gen(61, 0, (12, 64, 128), dt))
+    Cf, Df, cv = U.dev(U.gen(61, 1, (64, 32), dt)), U.dev(U.gen(61, 2, (128, 32), dt)), U.dev(U.gen(61, 1, (128,), dt))
+    Cg = torch.zeros((n, n), dtype=torch.float32, device="cuda:0")
+    o_ttv, o_ttm = empty((12, 64), dt), empty((12, 64, 32), dt)
+    o_mk, o_mk2, o_ip = empty((12, 32), dt), empty((128, 32), dt), empty((1,), dt)
+    Ci = U.dev(U.gen(61, 3, (12, 32), dt))
+
+    def work():
+        Cg.zero_()                                        # a fill kernel, not a memset node
+        schedules.summa(A, Bm, Cg, 1, 1, 64)              # six accumulate k-steps
+        lib.distal_ttv(T, cv, o_ttv)
+        lib.distal_ttm(T, Df, o_ttm)
+        lib.distal_mttkrp(T, Cf, Df, o_mk)
+        lib.distal_mttkrp_mode(2, T, Ci, Cf, o_mk2)
+        lib.distal_innerprod(T, T, o_ip)
+
+    outs = (Cg, o_ttv, o_ttm, o_mk, o_mk2, o_ip)
+    work()                                                # eager: also sizes the cached workspaces
+    torch.cuda.synchronize()
+    eager = [U.host(o).copy() for o in outs]
+    U.assert_close(eager[0], oracle.gemm(U.host(A), U.host(Bm)), dt, n)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        work()
+    for replay in range(3):
+        for o in outs:
+            o.fill_(float("nan"))                         # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for o, e in zip(outs, eager):
+            assert np.array_equal(U.host(o), e), f"replay {replay} differs from the eager result"
