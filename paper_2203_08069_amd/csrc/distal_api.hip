@@ -88,8 +88,9 @@ int launch_fill(T *out, int64_t rows, int64_t cols, int64_t ld, hipStream_t stre
 // Tile choice depends on the shape only.  Shapes made of whole, aligned tiles take the
 // straight-line kernel; a large binary32 problem takes 256 x 256 tiles (16 wavefronts), a
 // large, deep binary64 problem 256 x 128 (8 wavefronts, half the operand traffic; with one
-// workgroup per CU its epilogue is not hidden, so shallow k-chunks keep 128 x 128);
-// everything else takes the guarded 128 x 128 kernel.
+// workgroup per CU its epilogue is not hidden, so shallow k-chunks keep 128 x 128); a problem
+// with fewer than 256 tiles of 128 x 128 takes 64 x 64 tiles; everything else takes the guarded
+// 128 x 128 kernel.
 constexpr int64_t kBigTileMinTiles = 256;   // below this a grid of big tiles cannot fill 256 CUs
 
 // TA = false: C = [C +] A * B with A stored M x K.  TA = true: the left operand is stored
@@ -130,6 +131,9 @@ int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
             (M / 256) * (N / 128) * batch >= kBigTileMinTiles)
             return launch_contract<T, 256, 128, 16, 4, 2, true, TA>(a, batch, stream);
     }
+    // too few 128 x 128 tiles to give every CU one: quarter-size tiles, four times the workgroups
+    if (whole && M % 64 == 0 && N % 64 == 0 && tm * tn * batch < kBigTileMinTiles)
+        return launch_contract<T, 64, 64, 16, 2, 2, true, TA>(a, batch, stream);
     if (whole && M % 128 == 0 && N % 128 == 0)
         return launch_contract<T, 128, 128, 16, 2, 2, true, TA>(a, batch, stream);
     return launch_contract<T, 128, 128, 16, 2, 2, false, TA>(a, batch, stream);
