@@ -131,8 +131,9 @@ int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
             (M / 256) * (N / 128) * batch >= kBigTileMinTiles)
             return launch_contract<T, 256, 128, 16, 4, 2, true, TA>(a, batch, stream);
     }
-    // too few 128 x 128 tiles to give every CU one: quarter-size tiles, four times the workgroups
-    if (whole && M % 64 == 0 && N % 64 == 0 && tm * tn * batch < kBigTileMinTiles)
+    // too few 128 x 128 tiles to give every CU one (binary64: two): quarter-size tiles, four times
+    // the workgroups
+    if (whole && M % 64 == 0 && N % 64 == 0 && tm * tn * batch < (sizeof(T) == 8 ? 2 : 1) * kBigTileMinTiles)
         return launch_contract<T, 64, 64, 16, 2, 2, true, TA>(a, batch, stream);
     if (whole && M % 128 == 0 && N % 128 == 0)
         return launch_contract<T, 128, 128, 16, 2, 2, true, TA>(a, batch, stream);
