@@ -86,11 +86,13 @@ int launch_fill(T *out, int64_t rows, int64_t cols, int64_t ld, hipStream_t stre
 
 // ---- matrix multiply ------------------------------------------------------
 // Tile choice depends on the shape only.  Shapes made of whole, aligned tiles take the
-// straight-line kernel; a large binary32 problem takes 256 x 256 tiles (16 wavefronts), a
-// large, deep binary64 problem 256 x 128 (8 wavefronts, half the operand traffic; with one
-// workgroup per CU its epilogue is not hidden, so shallow k-chunks keep 128 x 128); a problem
-// with fewer than 256 tiles of 128 x 128 takes 64 x 64 tiles; everything else takes the guarded
-// 128 x 128 kernel.
+// straight-line kernel.  What matters most is four wavefronts per SIMD: binary64 wavefronts own
+// 32 x 64 sub-tiles (64 accumulator registers), eight of them on a 128 x 128 tile or, for deep
+// products, sixteen on 256 x 128; binary32 wavefronts own 64 x 64 sub-tiles, sixteen on a
+// 256 x 256 tile with 32-deep slabs for deep products, eight on 256 x 128 for k-chunks (with one
+// workgroup per CU the epilogue is not hidden, so shallow products want smaller tiles), four on
+// 128 x 128 below that.  A problem with fewer than 256 tiles of 128 x 128 takes 64 x 64 tiles;
+// everything else takes the guarded 128 x 128 kernel.
 constexpr int64_t kBigTileMinTiles = 256;   // below this a grid of big tiles cannot fill 256 CUs
 
 // TA = false: C = [C +] A * B with A stored M x K.  TA = true: the left operand is stored
@@ -123,20 +125,25 @@ int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
     a.b_vec_ok = aligned16(B) && ldb % VEC == 0 && stride_b % VEC == 0;
     a.c_vec_ok = aligned16(C) && ldc % VEC == 0 && stride_c % VEC == 0;
     const bool whole = a.a_vec_ok && a.b_vec_ok && a.c_vec_ok && K % 16 == 0;
+    const bool m256 = M % 256 == 0, n128 = N % 128 == 0;
+    const bool fills128 = tm * tn * batch >= kBigTileMinTiles;          // one 128 x 128 tile per CU at least
     if constexpr (sizeof(T) == 4) {
-        if (whole && M % 256 == 0 && N % 256 == 0 && (M / 256) * (N / 256) * batch >= kBigTileMinTiles)
-            return launch_contract<T, 256, 256, 16, 4, 4, true, TA>(a, batch, stream);
-    } else {
-        if (whole && M % 256 == 0 && N % 128 == 0 && K >= 4096 &&
-            (M / 256) * (N / 128) * batch >= kBigTileMinTiles)
+        if (whole && m256 && N % 256 == 0 && K % 32 == 0 && K >= 1024 &&
+            (M / 256) * (N / 256) * batch >= kBigTileMinTiles)
+            return launch_contract<T, 256, 256, 32, 4, 4, true, TA>(a, batch, stream);
+        if (whole && m256 && n128 && K >= 512 && (M / 256) * (N / 128) * batch >= kBigTileMinTiles)
             return launch_contract<T, 256, 128, 16, 4, 2, true, TA>(a, batch, stream);
+        if (whole && M % 128 == 0 && n128 && fills128)
+            return launch_contract<T, 128, 128, 16, 2, 2, true, TA>(a, batch, stream);
+    } else {
+        if (whole && m256 && n128 && K >= 4096 && (M / 256) * (N / 128) * batch >= kBigTileMinTiles)
+            return launch_contract<T, 256, 128, 16, 8, 2, true, TA>(a, batch, stream);
+        if (whole && M % 128 == 0 && n128 && fills128)
+            return launch_contract<T, 128, 128, 16, 4, 2, true, TA>(a, batch, stream);
     }
-    // too few 128 x 128 tiles to give every CU one (binary64: two): quarter-size tiles, four times
-    // the workgroups
-    if (whole && M % 64 == 0 && N % 64 == 0 && tm * tn * batch < (sizeof(T) == 8 ? 2 : 1) * kBigTileMinTiles)
+    // too few 128 x 128 tiles to give every CU one: quarter-size tiles, four times the workgroups
+    if (whole && M % 64 == 0 && N % 64 == 0)
         return launch_contract<T, 64, 64, 16, 2, 2, true, TA>(a, batch, stream);
-    if (whole && M % 128 == 0 && N % 128 == 0)
-        return launch_contract<T, 128, 128, 16, 2, 2, true, TA>(a, batch, stream);
     return launch_contract<T, 128, 128, 16, 2, 2, false, TA>(a, batch, stream);
 }
 

@@ -413,7 +413,7 @@ contract_kernel(ContractArgs<T> args) {
 // the 64-cycle MFMAs leave free, instead of in a burst of their own.
 // ---------------------------------------------------------------------------
 template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TA = false>
-__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 16) ? 4 : 2)
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 4 : 2)
 contract_fast_kernel(ContractArgs<T> args) {
     typedef ContractCfg<T, BM, BN, BK, WAVES_M, WAVES_N, TA> Cfg;
     typedef Mfma<T> MF;

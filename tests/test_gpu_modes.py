@@ -107,6 +107,20 @@ def test_ttm_mode0_wide_big_tiles(lib, oracle, dtype, kind):
         compare(got[:, j:j + 1, :], oracle.ttm_mode(0, np.ascontiguousarray(B[:, j:j + 1, :]), C), dtype, kind, I)
 
 
+@pytest.mark.parametrize("dtype", DT)
+def test_ttm_mode0_k_chunk_tiles(lib, oracle, dtype):
+    """mode 0 with a contracted extent of 512 and 256 tiles of 256 x 128 (the binary32 k-chunk
+    configuration with a transposed left operand)."""
+    I, J, K, R = 512, 128, 256, 256
+    B, C = U.gen(47, 0, (I, J, K), dtype), U.gen(47, 1, (I, R), dtype)
+    A = empty((R, J, K), dtype)
+    lib.distal_ttm_mode(0, U.dev(B), U.dev(C), A)
+    got = U.host(A)
+    assert np.all(np.isfinite(got))
+    for j in (0, 64, 127):
+        U.assert_close(got[:, j:j + 1, :], oracle.ttm_mode(0, np.ascontiguousarray(B[:, j:j + 1, :]), C), dtype, I)
+
+
 def test_ttm_mode0_deep_binary64_big_tiles(lib, oracle):
     """binary64, contracted extent 4096 and 256 tiles of 256 x 128: the deep big-tile configuration."""
     dtype = np.float64

@@ -54,6 +54,30 @@ def test_gemm(lib, oracle, dtype, kind, M, N, K):
     compare(U.host(C), oracle.gemm(A, B), dtype, kind, K)
 
 
+# shapes that reach the large-tile launch configurations (binary32: 256 x 256 tiles with 32-deep
+# slabs, 256 x 128 for k-chunks; binary64: 256 x 128 with sixteen wavefronts, 128 x 128 with eight)
+BIG_TILE_SHAPES = [(np.float32, 4096, 4096, 1024), (np.float32, 4096, 2048, 512),
+                   (np.float64, 4096, 2048, 4096), (np.float64, 2048, 2048, 64)]
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("dtype,M,N,K", BIG_TILE_SHAPES)
+def test_gemm_big_tile_configs(lib, oracle, kind, dtype, M, N, K):
+    """The oracle recomputes sampled rows of the product (all columns) from the same inputs."""
+    import torch
+    A, B = U.gen(200 + K, 0, (M, K), dtype, kind), U.gen(200 + K, 1, (K, N), dtype, kind)
+    C = empty((M, N), dtype)
+    lib.distal_gemm(U.dev(A), U.dev(B), C)
+    got = U.host(C)
+    assert np.all(np.isfinite(got))
+    rows = np.sort(np.random.default_rng(K).choice(M, 24, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    compare(got[rows], oracle.gemm(np.ascontiguousarray(A[rows]), B), dtype, kind, K)
+    # accumulate on top of the product: exactly twice it
+    lib.distal_gemm(U.dev(A), U.dev(B), C, accumulate=True)
+    assert np.array_equal(U.host(C), got * 2)
+
+
 @pytest.mark.parametrize("dtype", DT)
 @pytest.mark.parametrize("kind", KINDS)
 @pytest.mark.parametrize("off", [0, 1, 2, 3])
