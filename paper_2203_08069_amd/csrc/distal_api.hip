@@ -129,8 +129,11 @@ int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
     const bool fills128 = tm * tn * batch >= kBigTileMinTiles;          // one 128 x 128 tile per CU at least
     if constexpr (sizeof(T) == 4) {
         if (whole && m256 && N % 256 == 0 && K % 32 == 0 && K >= 1024 &&
-            (M / 256) * (N / 256) * batch >= kBigTileMinTiles)
-            return launch_contract<T, 256, 256, 32, 4, 4, true, TA>(a, batch, stream);
+            (M / 256) * (N / 256) * batch >= kBigTileMinTiles) {
+            // a transposed left operand is staged in rows of 256 either way: 16-deep slabs measure 1 % faster
+            if constexpr (TA) return launch_contract<T, 256, 256, 16, 4, 4, true, TA>(a, batch, stream);
+            else return launch_contract<T, 256, 256, 32, 4, 4, true, TA>(a, batch, stream);
+        }
         if (whole && m256 && n128 && K >= 512 && (M / 256) * (N / 128) * batch >= kBigTileMinTiles)
             return launch_contract<T, 256, 128, 16, 4, 2, true, TA>(a, batch, stream);
         if (whole && M % 128 == 0 && n128 && fills128)
