@@ -164,11 +164,11 @@ size_t elem_size(int dt) { return dt == DISTAL_F64 ? 8 : 4; }
 constexpr int64_t kModeTargetBlocks = 768;
 
 struct MttkrpModePlan {
-    int64_t tasks;          // workgroups per range of i
+    int64_t tasks;          // workgroups per range of the walked index
     int64_t isplit, nsplit; // walked indices per range; ranges (none empty)
     int64_t nparts;         // partial rows per output row
     int64_t partial_elems;  // workspace elements (0 when nparts == 1)
-    int64_t nslices, kgroups, jblocks /* blocks of 32 kept indices */, jgroups, kblocks, tiles_n;
+    int64_t nslices, kgroups, rblocks /* blocks of 32 output rows */, jgroups, kblocks, tiles_n;
     bool ok;
 };
 
@@ -182,8 +182,8 @@ MttkrpModePlan mttkrp_mode_plan(int dt, int mode, int64_t I, int64_t J, int64_t 
         out_rows = mode == 0 ? I : J;
         p.nslices = (K + sl - 1) / sl;
         p.kgroups = (p.nslices + 3) / 4;
-        p.jblocks = (out_rows + 31) / 32;
-        p.ok = mul_ok(p.kgroups * p.tiles_n, p.jblocks, &p.tasks);
+        p.rblocks = (out_rows + 31) / 32;
+        p.ok = mul_ok(p.kgroups * p.tiles_n, p.rblocks, &p.tasks);
         per_split = p.nslices;
     } else {
         const int64_t kw = 512 / esz;
@@ -232,7 +232,7 @@ int mttkrp_mode_t(int mode, int64_t I, int64_t J, int64_t K, int64_t L, const T 
         else           { a.R = J; a.W = I; a.row_stride = K;  a.walk_stride = jk; }
         a.wsplit = plan.isplit; a.nsplit = (int)plan.nsplit;
         a.nslices = (int)plan.nslices; a.kgroups = (int)plan.kgroups;
-        a.tiles_n = (int)plan.tiles_n; a.rblocks = (int)plan.jblocks;
+        a.tiles_n = (int)plan.tiles_n; a.rblocks = (int)plan.rblocks;
         constexpr int lds = Cfg::LDS_BYTES;
         static std::atomic<bool> done_full[kMaxDevices], done_guard[kMaxDevices];
         if (aligned && a.R % Cfg::RB == 0 && K % Cfg::SL == 0) {
@@ -333,7 +333,7 @@ bool tensor_elems(int64_t I, int64_t J, int64_t K, int64_t *n) {
 
 extern "C" {
 
-int distal_version(void) { return 100; }
+int distal_version(void) { return 200; }   // 0.2.0: mode-n entry points
 
 const char *distal_status_string(int status) {
     switch (status) {
