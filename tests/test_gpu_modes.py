@@ -226,3 +226,66 @@ def test_mttkrp_mode_reproducible_and_zero_extents(lib, dtype, mode):
         lib.distal_mttkrp_mode(1, z(2, 0, 4), z(2, 5), z(4, 5), z(0, 5))
     else:
         lib.distal_mttkrp_mode(2, z(2, 3, 0), z(2, 5), z(3, 5), z(0, 5))
+
+
+# ------------------------------------------------------------------ nothing is written out of bounds
+
+SENTINEL = 12345.0
+
+
+def banded(shape, dtype, offset):
+    """A contiguous tensor of `shape` inside a larger buffer of sentinels, `offset` elements in."""
+    import torch
+    n = int(np.prod(shape))
+    buf = torch.full((n + 2 * 512,), SENTINEL, dtype=getattr(torch, np.dtype(dtype).name), device="cuda:0")
+    return buf, buf[offset:offset + n].view(*shape), (offset, n)
+
+
+def bands_untouched(buf, span):
+    off, n = span
+    h = U.host(buf)
+    return bool(np.all(h[:off] == SENTINEL) and np.all(h[off + n:] == SENTINEL))
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("offset", [256, 259])          # 16-byte aligned and misaligned outputs
+def test_outputs_and_workspaces_stay_inside_their_buffers(lib, oracle, dtype, offset):
+    import torch
+    I, J, K, L = 5, 37, 70, 33                               # ragged in every mode
+    B = U.gen(80, 0, (I, J, K), dtype)
+    dB = U.dev(B)
+    code = 1 if dtype == np.float64 else 0
+    esz = np.dtype(dtype).itemsize
+    # ttv, ttm and ttm along every mode
+    c = U.gen(80, 1, (K,), dtype)
+    buf, A, span = banded((I, J), dtype, offset)
+    lib.distal_ttv(dB, U.dev(c), A)
+    U.assert_close(U.host(A), oracle.ttv(B, c), dtype, K)
+    assert bands_untouched(buf, span)
+    for mode in (0, 1, 2):
+        Cm = U.gen(80, 2, (B.shape[mode], L), dtype)
+        shape = list(B.shape)
+        shape[mode] = L
+        buf, A, span = banded(shape, dtype, offset)
+        lib.distal_ttm_mode(mode, dB, U.dev(Cm), A)
+        U.assert_close(U.host(A), oracle.ttm_mode(mode, B, Cm), dtype, B.shape[mode])
+        assert bands_untouched(buf, span)
+    # mttkrp along every mode, with a workspace of exactly the advertised size inside sentinels
+    for mode in (0, 1, 2):
+        a, b = [m for m in (0, 1, 2) if m != mode]
+        Cf, Df = U.gen(81, 1, (B.shape[a], L), dtype), U.gen(81, 2, (B.shape[b], L), dtype)
+        need = lib.mttkrp_mode_workspace_bytes(code, mode, I, J, K, L)
+        assert need > 0 and need % esz == 0
+        wbuf, ws, wspan = banded((need // esz,), dtype, 256)            # workspaces must be 256-byte aligned
+        buf, A, span = banded((B.shape[mode], L), dtype, offset)
+        lib.distal_mttkrp_mode(mode, dB, U.dev(Cf), U.dev(Df), A, workspace=ws)
+        U.assert_close(U.host(A), oracle.mttkrp_mode(mode, B, Cf, Df), dtype, B.shape[a] * B.shape[b])
+        assert bands_untouched(buf, span) and bands_untouched(wbuf, wspan)
+    # innerprod: scalar output and its workspace
+    need = lib.innerprod_workspace_bytes(code, I, J, K)
+    wbuf, ws, wspan = banded((need // 8,), np.float64, 256)
+    buf, a_out, span = banded((1,), dtype, offset)
+    lib.distal_innerprod(dB, dB, a_out, workspace=ws)
+    ref = oracle.innerprod(B, B)
+    assert abs(float(U.host(a_out)[0]) - ref) <= 4 * np.finfo(dtype).eps * abs(ref)
+    assert bands_untouched(buf, span) and bands_untouched(wbuf, wspan)
