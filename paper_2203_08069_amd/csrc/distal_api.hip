@@ -220,7 +220,8 @@ int mttkrp_mode_t(int mode, int64_t I, int64_t J, int64_t K, int64_t L, const T 
     if (!plan.ok) return DISTAL_ERR_SHAPE;
     T *partial = plan.nparts == 1 ? A : static_cast<T *>(workspace);
     const unsigned nblocks = (unsigned)(plan.tasks * plan.nsplit);
-    const bool aligned = aligned16(B) && L % 32 == 0;
+    // the vector kernels need whole, 16-byte aligned k-slices of B; everything else may be ragged
+    const bool aligned = aligned16(B);
     if (mode != 2) {
         typedef MttkrpCfg<T> Cfg;
         MttkrpWalkArgs<T> a{};
@@ -234,14 +235,18 @@ int mttkrp_mode_t(int mode, int64_t I, int64_t J, int64_t K, int64_t L, const T 
         a.nslices = (int)plan.nslices; a.kgroups = (int)plan.kgroups;
         a.tiles_n = (int)plan.tiles_n; a.rblocks = (int)plan.rblocks;
         constexpr int lds = Cfg::LDS_BYTES;
-        static std::atomic<bool> done_full[kMaxDevices], done_guard[kMaxDevices];
-        if (aligned && a.R % Cfg::RB == 0 && K % Cfg::SL == 0) {
-            auto kern = mttkrp_walk_kernel<T, false>;
-            if (!allow_lds(kern, lds, done_full)) return DISTAL_ERR_LAUNCH;
+        static std::atomic<bool> done[3][kMaxDevices];
+        if (aligned && K % Cfg::SL == 0 && a.R % Cfg::RB == 0 && L % Cfg::BN == 0) {
+            auto kern = mttkrp_walk_kernel<T, false, false>;
+            if (!allow_lds(kern, lds, done[0])) return DISTAL_ERR_LAUNCH;
+            hipLaunchKernelGGL(kern, dim3(nblocks), dim3(Cfg::NT), lds, stream, a);
+        } else if (aligned && K % Cfg::SL == 0) {
+            auto kern = mttkrp_walk_kernel<T, false, true>;
+            if (!allow_lds(kern, lds, done[1])) return DISTAL_ERR_LAUNCH;
             hipLaunchKernelGGL(kern, dim3(nblocks), dim3(Cfg::NT), lds, stream, a);
         } else {
-            auto kern = mttkrp_walk_kernel<T, true>;
-            if (!allow_lds(kern, lds, done_guard)) return DISTAL_ERR_LAUNCH;
+            auto kern = mttkrp_walk_kernel<T, true, true>;
+            if (!allow_lds(kern, lds, done[2])) return DISTAL_ERR_LAUNCH;
             hipLaunchKernelGGL(kern, dim3(nblocks), dim3(Cfg::NT), lds, stream, a);
         }
     } else {
@@ -251,10 +256,13 @@ int mttkrp_mode_t(int mode, int64_t I, int64_t J, int64_t K, int64_t L, const T 
         a.I = I; a.J = J; a.K = K; a.L = L;
         a.isplit = plan.isplit; a.nsplit = (int)plan.nsplit;
         a.jgroups = (int)plan.jgroups; a.kblocks = (int)plan.kblocks; a.tiles_n = (int)plan.tiles_n;
-        if (aligned && J % Cfg::JB == 0 && K % Cfg::KW == 0)
-            hipLaunchKernelGGL((mttkrp_mode2_kernel<T, false>), dim3(nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
+        const dim3 grid(nblocks), block(Cfg::NT);
+        if (aligned && K % Cfg::KW == 0 && J % Cfg::JB == 0 && L % Cfg::BN == 0)
+            hipLaunchKernelGGL((mttkrp_mode2_kernel<T, false, false>), grid, block, Cfg::LDS_BYTES, stream, a);
+        else if (aligned && K % Cfg::KW == 0)
+            hipLaunchKernelGGL((mttkrp_mode2_kernel<T, false, true>), grid, block, Cfg::LDS_BYTES, stream, a);
         else
-            hipLaunchKernelGGL((mttkrp_mode2_kernel<T, true>), dim3(nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
+            hipLaunchKernelGGL((mttkrp_mode2_kernel<T, true, true>), grid, block, Cfg::LDS_BYTES, stream, a);
     }
     if (hipGetLastError() != hipSuccess) return DISTAL_ERR_LAUNCH;
     if (plan.nparts == 1) return DISTAL_OK;

@@ -70,18 +70,31 @@ struct MttkrpPieces {
 };
 
 // RB rows x SL k-values starting at `base` (rows `row_stride` elements apart) -> rs.
+// Unguarded: 16-byte vector loads; needs a whole, aligned k-slice (k_valid >= SL); with RAGGED,
+// rows past rows_valid re-read the last valid row (without it every block must be full).
 // GUARD: rows >= rows_valid and k >= k_valid read as zero, element loads (any alignment).
-template <typename T, bool GUARD>
+template <typename T, bool GUARD, bool RAGGED>
 __device__ __forceinline__ void mttkrp_load_block(
     const T *base, int64_t row_stride, int64_t rows_valid, int64_t k_valid, const MttkrpPieces<T> &pc,
     typename VecOf<T, MttkrpCfg<T>::VEC>::type (&rs)[MttkrpCfg<T>::PER_T]) {
     typedef MttkrpCfg<T> Cfg;
     typedef typename VecOf<T, Cfg::VEC>::type vec_t;
     if constexpr (!GUARD) {
+        if (!RAGGED || rows_valid >= Cfg::RB) {    // wavefront-uniform: a full block
 #pragma unroll
-        for (int p = 0; p < Cfg::PER_T; ++p)      // base + p*RPI rows is wavefront-uniform
-            rs[p] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(
-                base + (int64_t)(p * Cfg::RPI) * row_stride + pc.lane_off));
+            for (int p = 0; p < Cfg::PER_T; ++p)  // base + p*RPI rows is wavefront-uniform
+                rs[p] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(
+                    base + (int64_t)(p * Cfg::RPI) * row_stride + pc.lane_off));
+        } else {
+            // the last, ragged block: rows past the end re-read the last valid row; what they
+            // produce lands in accumulator columns that are never stored
+#pragma unroll
+            for (int p = 0; p < Cfg::PER_T; ++p) {
+                int64_t jr = pc.prow + p * Cfg::RPI;
+                if (jr >= rows_valid) jr = rows_valid - 1;
+                rs[p] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(base + jr * row_stride + pc.pcol));
+            }
+        }
     } else {
 #pragma unroll
         for (int p = 0; p < Cfg::PER_T; ++p) {
@@ -132,8 +145,8 @@ __device__ __forceinline__ void mttkrp_patch_mfma(
 
 // The D operand of one k-slice, transposed into registers: d[lb][g][t] = D(k, l) for
 // k = k0 + g*KG + ls*KV + t and l = n0 + li (binary32) or n0 + 2*li + lb (binary64); zero
-// outside K x L when GUARD.  Lanes with neighbouring li read neighbouring l.
-template <typename T, bool GUARD>
+// for l >= L (RAGGED), and for k >= K (GUARD).  Lanes with neighbouring li read neighbouring l.
+template <typename T, bool GUARD, bool RAGGED>
 __device__ __forceinline__ void mttkrp_load_d(
     const T *D, int64_t K, int64_t L, int64_t k0, int64_t n0, int li, int ls,
     typename VecOf<T, MttkrpCfg<T>::VEC>::type (&d)[MttkrpCfg<T>::LB][MttkrpCfg<T>::NKG]) {
@@ -146,7 +159,7 @@ __device__ __forceinline__ void mttkrp_load_d(
 #pragma unroll
             for (int t = 0; t < Cfg::KV; ++t) {
                 const int64_t k = k0 + g * Cfg::KG + ls * Cfg::KV + t;
-                d[lb][g][t] = (!GUARD || (k < K && l < L)) ? D[k * L + l] : T(0);
+                d[lb][g][t] = ((!RAGGED || l < L) && (!GUARD || k < K)) ? D[k * L + l] : T(0);
             }
     }
 }
@@ -224,10 +237,12 @@ struct MttkrpWalkArgs {
     int rblocks;       // ceil(R / 32)
 };
 
-// GUARD = false: every row block and k-slice of B is full and 16-byte aligned
-// (R % 32 == 0, K % SL == 0, L % 32 == 0, aligned base) - vector loads only.
-// GUARD = true: any shape and alignment, element loads with bounds checks, zero fill.
-template <typename T, bool GUARD>
+// GUARD = false: every k-slice of B is full and 16-byte aligned (K % SL == 0, aligned base):
+// vector loads only.  RAGGED = true then allows any R and L (the last block of r re-reads its
+// last row, columns l >= L carry zero factors, neither is stored); RAGGED = false needs
+// R % 32 == 0 and L % 32 == 0 and keeps the register count at four wavefronts per SIMD.
+// GUARD = true (with RAGGED): any shape and alignment, element loads with bounds checks.
+template <typename T, bool GUARD, bool RAGGED>
 __global__ void __launch_bounds__(256, GUARD ? 1 : (sizeof(T) == 4 ? 3 : 2))
 mttkrp_walk_kernel(const MttkrpWalkArgs<T> args) {
     typedef MttkrpCfg<T> Cfg;
@@ -257,7 +272,7 @@ mttkrp_walk_kernel(const MttkrpWalkArgs<T> args) {
     const int64_t w_hi = (w_lo + args.wsplit < W) ? w_lo + args.wsplit : W;      // w_lo < w_hi by the plan
 
     vec_t d[LB][NKG];
-    mttkrp_load_d<T, GUARD>(args.D, K, L, k0, n0, li, ls, d);
+    mttkrp_load_d<T, GUARD, RAGGED>(args.D, K, L, k0, n0, li, ls, d);
 
     typename MF::acc_t acc[LB][MI];
 #pragma unroll
@@ -272,11 +287,11 @@ mttkrp_walk_kernel(const MttkrpWalkArgs<T> args) {
     const MttkrpPieces<T> pc(lane, args.row_stride);
     const T *block0 = args.B + r0 * args.row_stride + k0;                        // wavefront-uniform
     auto fetch = [&](int64_t w) {
-        mttkrp_load_block<T, GUARD>(block0 + w * args.walk_stride, args.row_stride, R - r0, K - k0, pc, rs);
+        mttkrp_load_block<T, GUARD, RAGGED>(block0 + w * args.walk_stride, args.row_stride, R - r0, K - k0, pc, rs);
 #pragma unroll
         for (int lb = 0; lb < LB; ++lb) {
             const int64_t l = n0 + (LB == 1 ? li : 2 * li + lb);
-            fnext[lb] = (!GUARD || l < L) ? args.F[w * L + l] : T(0);
+            fnext[lb] = (!RAGGED || l < L) ? args.F[w * L + l] : T(0);
         }
     };
 
@@ -304,14 +319,14 @@ mttkrp_walk_kernel(const MttkrpWalkArgs<T> args) {
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
         const int64_t r = r0 + mi * MF::NB + li;
-        if (GUARD && r >= R) continue;
+        if (RAGGED && r >= R) continue;
         T *row = args.partial + (r * nparts + part) * L + n0;
 #pragma unroll
         for (int lb = 0; lb < LB; ++lb)
 #pragma unroll
             for (int v = 0; v < MF::NACC; ++v) {
                 const int l = mttkrp_l_of<T>(v, lb, lane);
-                if (!GUARD || n0 + l < L) row[l] = acc[lb][mi][v];
+                if (!RAGGED || n0 + l < L) row[l] = acc[lb][mi][v];
             }
     }
 }
@@ -363,7 +378,9 @@ struct MttkrpMode2Args {
     int tiles_n;       // ceil(L / 32)
 };
 
-template <typename T, bool GUARD>
+// GUARD / RAGGED as for the kernel above: without GUARD K % KW == 0 and an aligned base are
+// needed; RAGGED = true allows any J and L, RAGGED = false needs J % 16 == 0 and L % 32 == 0.
+template <typename T, bool GUARD, bool RAGGED>
 __global__ void __launch_bounds__(256, GUARD ? 1 : 3)
 mttkrp_mode2_kernel(const MttkrpMode2Args<T> args) {
     typedef MttkrpMode2Cfg<T> Cfg;
@@ -408,15 +425,21 @@ mttkrp_mode2_kernel(const MttkrpMode2Args<T> args) {
 #pragma unroll
             for (int cb = 0; cb < LB; ++cb) {
                 const int64_t j = j0 + g * MF::KS + ls, l = n0 + cb * MF::NB + li;
-                dj[g][cb] = (!GUARD || (j < J && l < L)) ? args.D[j * L + l] : T(0);
+                dj[g][cb] = (!RAGGED || (j < J && l < L)) ? args.D[j * L + l] : T(0);
             }
         // The lane's piece (g, p) of the block of slice i: row j0 + g*KS + ls, elements
         // k0 + p*MB*VEC + li*VEC ...  The row-group part of the address is wavefront-uniform.
         const int64_t lane_off = (int64_t)ls * K + li * VEC;
+        const bool full_rows = j0 + JB <= J;             // wavefront-uniform
         auto piece = [&](int64_t i, int g, int p) -> vec_t {
             const T *base = args.B + ((i * J + j0 + g * MF::KS) * K + k0 + p * MF::MB * VEC);   // uniform
             if constexpr (!GUARD) {
-                return __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(base + lane_off));
+                if (!RAGGED || full_rows) return __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(base + lane_off));
+                // ragged last block of j: rows past the end re-read row J-1; their D factor is zero
+                int64_t j = j0 + g * MF::KS + ls;
+                if (j >= J) j = J - 1;
+                return __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(
+                    args.B + (i * J + j) * K + k0 + p * MF::MB * VEC + li * VEC));
             } else {
                 vec_t x;
 #pragma unroll
@@ -431,7 +454,7 @@ mttkrp_mode2_kernel(const MttkrpMode2Args<T> args) {
 #pragma unroll
             for (int cb = 0; cb < LB; ++cb) {
                 const int64_t l = n0 + cb * MF::NB + li;
-                c[cb] = (!GUARD || l < L) ? args.C[i * L + l] : T(0);
+                c[cb] = (!RAGGED || l < L) ? args.C[i * L + l] : T(0);
             }
         };
 
@@ -498,7 +521,7 @@ mttkrp_mode2_kernel(const MttkrpMode2Args<T> args) {
             for (int v = 0; v < MF::NACC; ++v) {
                 const int64_t k = k0 + p * MF::MB * VEC + MF::out_row(v, lane) * VEC + e;
                 const int64_t l = n0 + cb * MF::NB + li;
-                if (!GUARD || (k < K && l < L))
+                if ((!RAGGED || l < L) && (!GUARD || k < K))
                     args.partial[(k * nparts + part) * L + l] = red[((rb * LB + cb) * MF::NACC + v) * 64 + lane];
             }
     }

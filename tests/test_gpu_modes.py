@@ -161,7 +161,9 @@ def factor_shapes(shape, mode, L):
 # several column tiles, one-i-per-range and several-i-per-range splits (odd and even counts)
 MTTKRP_MODE_SHAPES = [(3, 5, 7, 4), (9, 33, 129, 5), (2, 70, 256, 32), (1, 1, 1, 1), (4, 16, 128, 32),
                       (6, 64, 128, 32), (40, 32, 256, 64), (50, 32, 64, 32), (7, 48, 200, 40),
-                      (100, 256, 512, 32)]
+                      (100, 256, 512, 32),
+                      # whole aligned k-slices, ragged everything else: the vector kernels' ragged variants
+                      (5, 37, 128, 33), (33, 50, 256, 16), (100, 17, 128, 48)]
 
 
 @pytest.mark.parametrize("dtype", DT)
@@ -249,9 +251,10 @@ def bands_untouched(buf, span):
 
 @pytest.mark.parametrize("dtype", DT)
 @pytest.mark.parametrize("offset", [256, 259])          # 16-byte aligned and misaligned outputs
-def test_outputs_and_workspaces_stay_inside_their_buffers(lib, oracle, dtype, offset):
+@pytest.mark.parametrize("K", [70, 128])                # element-load kernels / vector kernels, ragged variants
+def test_outputs_and_workspaces_stay_inside_their_buffers(lib, oracle, dtype, offset, K):
     import torch
-    I, J, K, L = 5, 37, 70, 33                               # ragged in every mode
+    I, J, L = 5, 37, 33                                      # ragged in every other mode
     B = U.gen(80, 0, (I, J, K), dtype)
     dB = U.dev(B)
     code = 1 if dtype == np.float64 else 0
