@@ -33,6 +33,14 @@ def compute_cases():
         cases[f"ttm_{name}"] = oracle.ttm(T, C).ravel()
         Cf, Df = inputs.tensor(4, 1, (3, 2), dt), inputs.tensor(4, 2, (5, 2), dt)
         cases[f"mttkrp_{name}"] = oracle.mttkrp(T, Cf, Df).ravel()
+        # the same two contractions along the other modes of the 2 x 3 x 5 tensor
+        for mode in (0, 1):
+            Cn = inputs.tensor(3, 1, (T.shape[mode], 2), dt)
+            cases[f"ttm_mode{mode}_{name}"] = oracle.ttm_mode(mode, T, Cn).ravel()
+        for mode in (1, 2):
+            a, b = [m for m in (0, 1, 2) if m != mode]
+            Ca, Db = inputs.tensor(4, 1, (T.shape[a], 2), dt), inputs.tensor(4, 2, (T.shape[b], 2), dt)
+            cases[f"mttkrp_mode{mode}_{name}"] = oracle.mttkrp_mode(mode, T, Ca, Db).ravel()
     return cases
 
 
