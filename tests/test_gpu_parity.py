@@ -370,8 +370,8 @@ def test_runs_on_a_side_stream(lib, oracle):
 
 @pytest.mark.parametrize("dtype", DT)
 def test_schedule_driver(lib, oracle, dtype):
-    """SUMMA / Cannon / Johnson call sequences from schedules.py give the one-shot product,
-    bit for bit on integer inputs."""
+    """The call sequences of schedules.py (SUMMA, Cannon, Johnson, PUMMA, Solomonik's 2.5D, COSMA)
+    give the one-shot product, bit for bit on integer inputs."""
     import torch
     from paper_2203_08069_amd import schedules
     n = 768
@@ -383,6 +383,11 @@ def test_schedule_driver(lib, oracle, dtype):
     U.assert_exact(U.host(schedules.summa(dA, dB, z(), 1, 1, 100)), ref)       # ragged last chunk
     U.assert_exact(U.host(schedules.cannon(dA, dB, z(), 3)), ref)
     parts = schedules.johnson(dA, dB, z(), 2, [empty((n, n), dtype) for _ in range(2)])
+    U.assert_exact(sum(U.host(p).astype(np.float64) for p in parts), ref)
+    U.assert_exact(U.host(schedules.pumma(dA, dB, z(), 3, 2)), ref)
+    parts = schedules.solomonik(dA, dB, z(), 4, 2, [z() for _ in range(2)])          # 4 x 4 x 2, two steps per layer
+    U.assert_exact(sum(U.host(p).astype(np.float64) for p in parts), ref)
+    parts = schedules.cosma(dA, dB, z(), 2, 4, 3, 2, [z() for _ in range(3)])        # 2 x 4 x 3 grid, two sequential steps
     U.assert_exact(sum(U.host(p).astype(np.float64) for p in parts), ref)
 
 
