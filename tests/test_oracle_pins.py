@@ -324,6 +324,43 @@ def test_johnson_partials_then_reduce(oracle, dtype):
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
+def test_pumma_and_solomonik_orders(oracle, dtype):
+    """Algorithm table: PUMMA rotates the k-loop by io only (kos = (ko + io) mod gx); Solomonik's
+    2.5D algorithm distributes k over c layers and runs Cannon's rotation (kio + io + jo) mod steps
+    inside each layer, the layers being summed afterwards.  Both visit every k-tile exactly once per
+    output tile, so integer inputs reproduce the one-shot product exactly."""
+    g, t = 3, 4
+    n = g * t
+    A, B = rnd(24, 0, (n, n), dtype, inputs.SMALLINT), rnd(24, 1, (n, n), dtype, inputs.SMALLINT)
+    ref = oracle.gemm(A, B)
+    C = np.zeros((n, n), dtype=dtype)
+    for io in range(g):
+        for jo in range(g):
+            seen = set()
+            for ko in range(g):
+                kos = (ko + io) % g
+                seen.add(kos)
+                C[io * t:(io + 1) * t, jo * t:(jo + 1) * t] = oracle.gemm(
+                    A[io * t:(io + 1) * t, kos * t:(kos + 1) * t], B[kos * t:(kos + 1) * t, jo * t:(jo + 1) * t],
+                    init=C[io * t:(io + 1) * t, jo * t:(jo + 1) * t]).astype(dtype)
+            assert seen == set(range(g))
+    assert np.array_equal(C.astype(np.float64), ref)
+    # 2.5D: 2 x 2 x 2 grid over a 12 x 12 product, three rotated steps per layer
+    g2, c, steps = 2, 2, 3
+    tm, tk = n // g2, n // (c * steps)
+    layers = [np.zeros((n, n), dtype=dtype) for _ in range(c)]
+    for ko in range(c):
+        for io in range(g2):
+            for jo in range(g2):
+                for kio in range(steps):
+                    k0 = (ko * steps + (kio + io + jo) % steps) * tk
+                    blk = (slice(io * tm, (io + 1) * tm), slice(jo * tm, (jo + 1) * tm))
+                    layers[ko][blk] = oracle.gemm(A[blk[0], k0:k0 + tk], B[k0:k0 + tk, blk[1]],
+                                                  init=layers[ko][blk]).astype(dtype)
+    assert np.array_equal(sum(l.astype(np.float64) for l in layers), ref)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
 def test_chunked_float_matches_one_shot(oracle, dtype):
     M, N, K = 5, 4, 64
     A, B = rnd(43, 0, (M, K), dtype), rnd(43, 1, (K, N), dtype)
