@@ -48,7 +48,8 @@ def out_shape(shape, mode, R):
 # (I, J, K, R): ragged, extent-1 modes, and shapes made of whole 128 x 128 tiles in each mode's
 # matrix form (mode 0: R x JK over I; mode 1: per i, R x K over J)
 TTM_MODE_SHAPES = [(3, 5, 7, 4), (17, 9, 33, 130), (32, 8, 32, 128), (130, 3, 44, 5), (1, 1, 1, 1),
-                   (5, 40, 3, 1), (16, 128, 128, 128), (48, 2, 64, 256), (2, 19, 520, 36)]
+                   (5, 40, 3, 1), (16, 128, 128, 128), (48, 2, 64, 256), (2, 19, 520, 36),
+                   (70000, 2, 4, 3)]           # mode 1: more problems in the batch than one grid dimension holds
 
 
 @pytest.mark.parametrize("dtype", DT)
