@@ -226,3 +226,19 @@ def test_mttkrp_mode_1024(lib, oracle, mode):
     A2 = torch.empty_like(A)
     lib.distal_mttkrp_mode(mode, B, C, D, A2)
     assert torch.equal(A, A2)
+
+
+def test_ttv_more_row_groups_than_the_grid_cap(lib, oracle):
+    """2^26 + 5 rows of four values: more 16-row groups than the launch caps its grid at, so the
+    kernel's grid-stride loop runs; sampled rows and the ragged tail against the oracle."""
+    import torch
+    rows, K = (1 << 26) + 5, 4
+    B = devgen(5, 0, (1, rows, K), np.float32)
+    c = devgen(5, 1, (K,), np.float32)
+    A = torch.full((1, rows), float("nan"), dtype=torch.float32, device="cuda:0")
+    lib.distal_ttv(B, c, A)
+    assert bool(torch.isfinite(A).all())
+    hc = inputs.values(5, 1, 0, K, np.float32)
+    for start in (0, (1 << 22) * 16 - 60, (1 << 25) + 12345, rows - 64):
+        hB = inputs.values(5, 0, start * K, 64 * K, np.float32).reshape(1, 64, K)
+        U.assert_close(A[0, start:start + 64].cpu().numpy(), oracle.ttv(hB, hc)[0], np.float32, K)
