@@ -95,7 +95,7 @@ def main():
                          "extra rows, not part of 'all': summa (k-chunk leaf shapes), "
                          "ttv_f64,innerprod_f64,ttm_f64,mttkrp_f64, ttm_mode0,ttm_mode1 (TTM along the "
                          "other modes of the configs[3] tensor), mttkrp_mode1,mttkrp_mode2 (MTTKRP along the "
-                         "other modes of the configs[4] tensor)")
+                         "other modes of the configs[4] tensor), mttkrp_rank64")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB read + 1 GiB write elementwise kernel (torch.add), the known-size "
@@ -366,6 +366,29 @@ def main():
             r["cpu_baseline"] = {"value": (2.0 * i_s * J * K * L + 2.0 * i_s * J * L) / sec / 1e9,
                                  "unit": "GFLOP/s", "cores": cores, "kind": "oracle", "seconds": sec,
                                  "sample": f"first {i_s} of {I} i-slices"}
+            r["sample_normwise_err"] = sample_err(A[:i_s].cpu().numpy(), ref)
+        del B, C, D, A
+
+    # ---------------------------------------------------------------- MTTKRP at rank 64 (extra): MFMA-bound
+    if "mttkrp_rank64" in want:
+        I = J = K = 1024
+        L = 64
+        B = device_tensor(4, 0, (I, J, K), np.float32, device=dev)
+        C = device_tensor(4, 1, (J, L), np.float32, device=dev)
+        D = device_tensor(4, 2, (K, L), np.float32, device=dev)
+        A = torch.empty((I, L), dtype=torch.float32, device=dev)
+        flops = 2.0 * I * J * K * L + 2.0 * I * J * L
+        r = finish("mttkrp_rank64", f"MTTKRP B {I}x{J}x{K}, rank {L} f32 (arithmetic intensity 32 flop/B: MFMA-bound)",
+                   "f32", lambda: binding.distal_mttkrp(B, C, D, A), flops,
+                   4.0 * (I * J * K + J * L + K * L + I * L), "mfma")
+        if cpu:
+            i_s = 16
+            hB = np.ascontiguousarray(B[:i_s].cpu().numpy())
+            t0 = time.perf_counter()
+            ref = oracle.mttkrp(hB, C.cpu().numpy(), D.cpu().numpy())
+            sec = time.perf_counter() - t0
+            r["cpu_baseline"] = {"value": 3.0 * i_s * J * K * L / sec / 1e9, "unit": "GFLOP/s", "cores": cores,
+                                 "kind": "oracle", "seconds": sec, "sample": f"first {i_s} of {I} output rows"}
             r["sample_normwise_err"] = sample_err(A[:i_s].cpu().numpy(), ref)
         del B, C, D, A
 

@@ -175,7 +175,8 @@ struct MttkrpModePlan {
 MttkrpModePlan mttkrp_mode_plan(int dt, int mode, int64_t I, int64_t J, int64_t K, int64_t L) {
     MttkrpModePlan p{};
     const int64_t esz = dt == DISTAL_F64 ? 8 : 4;
-    p.tiles_n = (L + 31) / 32;
+    // a wavefront takes two column tiles of 32 once the rank exceeds 32
+    p.tiles_n = L > 32 ? (L + 63) / 64 : (L + 31) / 32;
     int64_t out_rows, per_split;
     if (mode != 2) {                       // kept index r = i (mode 0) or j (mode 1), the other one is walked
         const int64_t sl = 256 / esz;
@@ -210,6 +211,41 @@ MttkrpModePlan mttkrp_mode_plan(int dt, int mode, int64_t I, int64_t J, int64_t 
     return p;
 }
 
+// vec: whole aligned k-slices (vector loads); full: every block of output rows and columns is whole
+template <typename T, int LT>
+int launch_walk(const MttkrpWalkArgs<T> &a, unsigned nblocks, bool vec, bool full, hipStream_t stream) {
+    typedef MttkrpCfg<T> Cfg;
+    constexpr int lds = Cfg::LDS_BYTES;
+    static std::atomic<bool> done[3][kMaxDevices];
+    if (full) {
+        auto kern = mttkrp_walk_kernel<T, false, false, LT>;
+        if (!allow_lds(kern, lds, done[0])) return DISTAL_ERR_LAUNCH;
+        hipLaunchKernelGGL(kern, dim3(nblocks), dim3(Cfg::NT), lds, stream, a);
+    } else if (vec) {
+        auto kern = mttkrp_walk_kernel<T, false, true, LT>;
+        if (!allow_lds(kern, lds, done[1])) return DISTAL_ERR_LAUNCH;
+        hipLaunchKernelGGL(kern, dim3(nblocks), dim3(Cfg::NT), lds, stream, a);
+    } else {
+        auto kern = mttkrp_walk_kernel<T, true, true, LT>;
+        if (!allow_lds(kern, lds, done[2])) return DISTAL_ERR_LAUNCH;
+        hipLaunchKernelGGL(kern, dim3(nblocks), dim3(Cfg::NT), lds, stream, a);
+    }
+    return DISTAL_OK;
+}
+
+template <typename T, int LT>
+void launch_mode2(const MttkrpMode2Args<T> &a, unsigned nblocks, bool aligned, hipStream_t stream) {
+    typedef MttkrpMode2Cfg<T, LT> Cfg;
+    const dim3 grid(nblocks), block(Cfg::NT);
+    const bool vec = aligned && a.K % Cfg::KW == 0;
+    if (vec && a.J % Cfg::JB == 0 && a.L % Cfg::BN == 0)
+        hipLaunchKernelGGL((mttkrp_mode2_kernel<T, false, false, LT>), grid, block, Cfg::LDS_BYTES, stream, a);
+    else if (vec)
+        hipLaunchKernelGGL((mttkrp_mode2_kernel<T, false, true, LT>), grid, block, Cfg::LDS_BYTES, stream, a);
+    else
+        hipLaunchKernelGGL((mttkrp_mode2_kernel<T, true, true, LT>), grid, block, Cfg::LDS_BYTES, stream, a);
+}
+
 template <typename T>
 int mttkrp_mode_t(int mode, int64_t I, int64_t J, int64_t K, int64_t L, const T *B, const T *C, const T *D,
                   T *A, void *workspace, hipStream_t stream) {
@@ -234,35 +270,19 @@ int mttkrp_mode_t(int mode, int64_t I, int64_t J, int64_t K, int64_t L, const T 
         a.wsplit = plan.isplit; a.nsplit = (int)plan.nsplit;
         a.nslices = (int)plan.nslices; a.kgroups = (int)plan.kgroups;
         a.tiles_n = (int)plan.tiles_n; a.rblocks = (int)plan.rblocks;
-        constexpr int lds = Cfg::LDS_BYTES;
-        static std::atomic<bool> done[3][kMaxDevices];
-        if (aligned && K % Cfg::SL == 0 && a.R % Cfg::RB == 0 && L % Cfg::BN == 0) {
-            auto kern = mttkrp_walk_kernel<T, false, false>;
-            if (!allow_lds(kern, lds, done[0])) return DISTAL_ERR_LAUNCH;
-            hipLaunchKernelGGL(kern, dim3(nblocks), dim3(Cfg::NT), lds, stream, a);
-        } else if (aligned && K % Cfg::SL == 0) {
-            auto kern = mttkrp_walk_kernel<T, false, true>;
-            if (!allow_lds(kern, lds, done[1])) return DISTAL_ERR_LAUNCH;
-            hipLaunchKernelGGL(kern, dim3(nblocks), dim3(Cfg::NT), lds, stream, a);
-        } else {
-            auto kern = mttkrp_walk_kernel<T, true, true>;
-            if (!allow_lds(kern, lds, done[2])) return DISTAL_ERR_LAUNCH;
-            hipLaunchKernelGGL(kern, dim3(nblocks), dim3(Cfg::NT), lds, stream, a);
-        }
+        const bool vec = aligned && K % Cfg::SL == 0;
+        const int rc = L > 32
+            ? launch_walk<T, 2>(a, nblocks, vec, vec && a.R % Cfg::RB == 0 && L % (2 * Cfg::BN) == 0, stream)
+            : launch_walk<T, 1>(a, nblocks, vec, vec && a.R % Cfg::RB == 0 && L % Cfg::BN == 0, stream);
+        if (rc != DISTAL_OK) return rc;
     } else {
-        typedef MttkrpMode2Cfg<T> Cfg;
         MttkrpMode2Args<T> a{};
         a.B = B; a.C = C; a.D = D; a.partial = partial;
         a.I = I; a.J = J; a.K = K; a.L = L;
         a.isplit = plan.isplit; a.nsplit = (int)plan.nsplit;
         a.jgroups = (int)plan.jgroups; a.kblocks = (int)plan.kblocks; a.tiles_n = (int)plan.tiles_n;
-        const dim3 grid(nblocks), block(Cfg::NT);
-        if (aligned && K % Cfg::KW == 0 && J % Cfg::JB == 0 && L % Cfg::BN == 0)
-            hipLaunchKernelGGL((mttkrp_mode2_kernel<T, false, false>), grid, block, Cfg::LDS_BYTES, stream, a);
-        else if (aligned && K % Cfg::KW == 0)
-            hipLaunchKernelGGL((mttkrp_mode2_kernel<T, false, true>), grid, block, Cfg::LDS_BYTES, stream, a);
-        else
-            hipLaunchKernelGGL((mttkrp_mode2_kernel<T, true, true>), grid, block, Cfg::LDS_BYTES, stream, a);
+        if (L > 32) launch_mode2<T, 2>(a, nblocks, aligned, stream);
+        else launch_mode2<T, 1>(a, nblocks, aligned, stream);
     }
     if (hipGetLastError() != hipSuccess) return DISTAL_ERR_LAUNCH;
     if (plan.nparts == 1) return DISTAL_OK;

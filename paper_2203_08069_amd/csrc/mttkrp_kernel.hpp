@@ -117,12 +117,15 @@ __device__ __forceinline__ void mttkrp_patch_store(
         *reinterpret_cast<vec_t *>(patch + (pc.prow + p * Cfg::RPI) * Cfg::LDW + pc.pcol) = rs[p];
 }
 
-// acc(l, j) += sum over the slice of d(l, k) * patch(j, k): the transposed product of one block
-template <typename T>
+// acc[lt](l, j) += sum over the slice of f[lt](l) * d[lt](l, k) * patch(j, k): the transposed
+// product of one block with LT column tiles of 32, the D slice scaled by the walked index's
+// factor on the way into the matrix pipe (KV multiplies per MFMA group; no scaled copy is kept).
+template <typename T, int LT>
 __device__ __forceinline__ void mttkrp_patch_mfma(
     const T *patch, int li, int ls,
-    const typename VecOf<T, MttkrpCfg<T>::VEC>::type (&d)[MttkrpCfg<T>::LB][MttkrpCfg<T>::NKG],
-    typename Mfma<T>::acc_t (&acc)[MttkrpCfg<T>::LB][MttkrpCfg<T>::MI]) {
+    const typename VecOf<T, MttkrpCfg<T>::VEC>::type (&d)[LT][MttkrpCfg<T>::LB][MttkrpCfg<T>::NKG],
+    const T (&f)[LT][MttkrpCfg<T>::LB],
+    typename Mfma<T>::acc_t (&acc)[LT][MttkrpCfg<T>::LB][MttkrpCfg<T>::MI]) {
     typedef MttkrpCfg<T> Cfg;
     typedef Mfma<T> MF;
     typedef typename VecOf<T, Cfg::VEC>::type vec_t;
@@ -134,12 +137,16 @@ __device__ __forceinline__ void mttkrp_patch_mfma(
             b[mi] = *reinterpret_cast<const vec_t *>(patch + (mi * MF::NB + li) * Cfg::LDW
                                                      + g * Cfg::KG + ls * Cfg::KV);
 #pragma unroll
-        for (int t = 0; t < Cfg::KV; ++t)
+        for (int lt = 0; lt < LT; ++lt)
 #pragma unroll
-            for (int lb = 0; lb < Cfg::LB; ++lb)
+            for (int lb = 0; lb < Cfg::LB; ++lb) {
+                const vec_t ds = d[lt][lb][g] * f[lt][lb];
 #pragma unroll
-                for (int mi = 0; mi < Cfg::MI; ++mi)
-                    acc[lb][mi] = MF::run(d[lb][g][t], b[mi][t], acc[lb][mi]);
+                for (int t = 0; t < Cfg::KV; ++t)
+#pragma unroll
+                    for (int mi = 0; mi < Cfg::MI; ++mi)
+                        acc[lt][lb][mi] = MF::run(ds[t], b[mi][t], acc[lt][lb][mi]);
+            }
     }
 }
 
@@ -233,7 +240,7 @@ struct MttkrpWalkArgs {
     int nsplit;        // ranges of w: ceil(W / wsplit), none empty
     int nslices;       // ceil(K / SL)
     int kgroups;       // ceil(nslices / 4): k-slices are handed out four per workgroup
-    int tiles_n;       // ceil(L / 32)
+    int tiles_n;       // ceil(L / (32 * LT))
     int rblocks;       // ceil(R / 32)
 };
 
@@ -242,14 +249,16 @@ struct MttkrpWalkArgs {
 // last row, columns l >= L carry zero factors, neither is stored); RAGGED = false needs
 // R % 32 == 0 and L % 32 == 0 and keeps the register count at four wavefronts per SIMD.
 // GUARD = true (with RAGGED): any shape and alignment, element loads with bounds checks.
-template <typename T, bool GUARD, bool RAGGED>
-__global__ void __launch_bounds__(256, GUARD ? 1 : (sizeof(T) == 4 ? 3 : 2))
+// LT = column tiles of 32 per wavefront (1 or 2): with two, a rank above 32 reads B once per 64
+// columns instead of once per 32.
+template <typename T, bool GUARD, bool RAGGED, int LT>
+__global__ void __launch_bounds__(256, GUARD ? 1 : ((sizeof(T) == 4 && LT == 1) ? 3 : 2))
 mttkrp_walk_kernel(const MttkrpWalkArgs<T> args) {
     typedef MttkrpCfg<T> Cfg;
     typedef Mfma<T> MF;
     typedef typename VecOf<T, Cfg::VEC>::type vec_t;
-    constexpr int NKG = Cfg::NKG, MI = Cfg::MI, LB = Cfg::LB, KV = Cfg::KV;
-    constexpr int SL = Cfg::SL, BN = Cfg::BN, RB = Cfg::RB;
+    constexpr int NKG = Cfg::NKG, MI = Cfg::MI, LB = Cfg::LB;
+    constexpr int SL = Cfg::SL, BN = Cfg::BN * LT, RB = Cfg::RB;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     const int tid = threadIdx.x;
@@ -271,46 +280,46 @@ mttkrp_walk_kernel(const MttkrpWalkArgs<T> args) {
     const int64_t w_lo = (int64_t)split * args.wsplit;
     const int64_t w_hi = (w_lo + args.wsplit < W) ? w_lo + args.wsplit : W;      // w_lo < w_hi by the plan
 
-    vec_t d[LB][NKG];
-    mttkrp_load_d<T, GUARD, RAGGED>(args.D, K, L, k0, n0, li, ls, d);
+    vec_t d[LT][LB][NKG];
+#pragma unroll
+    for (int lt = 0; lt < LT; ++lt) mttkrp_load_d<T, GUARD, RAGGED>(args.D, K, L, k0, n0 + lt * Cfg::BN, li, ls, d[lt]);
 
-    typename MF::acc_t acc[LB][MI];
+    typename MF::acc_t acc[LT][LB][MI];
 #pragma unroll
-    for (int lb = 0; lb < LB; ++lb)
+    for (int lt = 0; lt < LT; ++lt)
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
+        for (int lb = 0; lb < LB; ++lb)
 #pragma unroll
-            for (int v = 0; v < MF::NACC; ++v) acc[lb][mi][v] = T(0);
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int v = 0; v < MF::NACC; ++v) acc[lt][lb][mi][v] = T(0);
 
     vec_t rs[Cfg::PER_T];
-    T fnext[LB];                           // F(w, l) of the block in flight, l as in d
+    T fnext[LT][LB];                       // F(w, l) of the block in flight, l as in d
     const MttkrpPieces<T> pc(lane, args.row_stride);
     const T *block0 = args.B + r0 * args.row_stride + k0;                        // wavefront-uniform
     auto fetch = [&](int64_t w) {
         mttkrp_load_block<T, GUARD, RAGGED>(block0 + w * args.walk_stride, args.row_stride, R - r0, K - k0, pc, rs);
 #pragma unroll
-        for (int lb = 0; lb < LB; ++lb) {
-            const int64_t l = n0 + (LB == 1 ? li : 2 * li + lb);
-            fnext[lb] = (!RAGGED || l < L) ? args.F[w * L + l] : T(0);
-        }
+        for (int lt = 0; lt < LT; ++lt)
+#pragma unroll
+            for (int lb = 0; lb < LB; ++lb) {
+                const int64_t l = n0 + lt * Cfg::BN + (LB == 1 ? li : 2 * li + lb);
+                fnext[lt][lb] = (!RAGGED || l < L) ? args.F[w * L + l] : T(0);
+            }
     };
 
     fetch(w_lo);
     for (int64_t w = w_lo; w < w_hi; ++w) {
-        T f[LB];
+        T f[LT][LB];
 #pragma unroll
-        for (int lb = 0; lb < LB; ++lb) f[lb] = fnext[lb];
+        for (int lt = 0; lt < LT; ++lt)
+#pragma unroll
+            for (int lb = 0; lb < LB; ++lb) f[lt][lb] = fnext[lt][lb];
         mttkrp_patch_store<T>(patch, pc, rs);
         fetch(w + 1 < w_hi ? w + 1 : w);   // past the end: a redundant, in-bounds reload
         wave_lds_fence();
-        vec_t ds[LB][NKG];                 // the slice of D scaled by F(w, l)
-#pragma unroll
-        for (int lb = 0; lb < LB; ++lb)
-#pragma unroll
-            for (int g = 0; g < NKG; ++g)
-#pragma unroll
-                for (int t = 0; t < KV; ++t) ds[lb][g][t] = d[lb][g][t] * f[lb];
-        mttkrp_patch_mfma<T>(patch, li, ls, ds, acc);
+        mttkrp_patch_mfma<T, LT>(patch, li, ls, d, f, acc);
         wave_lds_fence();
     }
 
@@ -322,12 +331,14 @@ mttkrp_walk_kernel(const MttkrpWalkArgs<T> args) {
         if (RAGGED && r >= R) continue;
         T *row = args.partial + (r * nparts + part) * L + n0;
 #pragma unroll
-        for (int lb = 0; lb < LB; ++lb)
+        for (int lt = 0; lt < LT; ++lt)
 #pragma unroll
-            for (int v = 0; v < MF::NACC; ++v) {
-                const int l = mttkrp_l_of<T>(v, lb, lane);
-                if (!RAGGED || n0 + l < L) row[l] = acc[lb][mi][v];
-            }
+            for (int lb = 0; lb < LB; ++lb)
+#pragma unroll
+                for (int v = 0; v < MF::NACC; ++v) {
+                    const int l = lt * Cfg::BN + mttkrp_l_of<T>(v, lb, lane);
+                    if (!RAGGED || n0 + l < L) row[l] = acc[lt][lb][mi][v];
+                }
     }
 }
 
@@ -346,10 +357,10 @@ mttkrp_walk_kernel(const MttkrpWalkArgs<T> args) {
 // j-blocks of the same k-range; at the end they are added through LDS in wavefront order
 // and the workgroup writes one partial block; the row-sum kernel finishes.
 // ---------------------------------------------------------------------------
-template <typename T>
+template <typename T, int LT>
 struct MttkrpMode2Cfg {
     typedef Mfma<T> MF;
-    static constexpr int NT = 256, NW = 4, BN = 32;
+    static constexpr int NT = 256, NW = 4, BN = 32 * LT;    // LT column tiles of 32 per wavefront
     static constexpr int VEC = 16 / (int)sizeof(T);
     static constexpr int KW = 512 / (int)sizeof(T);        // output rows (k) per workgroup
     static constexpr int NP = KW / (MF::MB * VEC);         // 16-byte loads per lane per r-group
@@ -375,15 +386,15 @@ struct MttkrpMode2Args {
     int nsplit;        // ranges of i, none empty
     int jgroups;       // ceil(J / (4 * JB))
     int kblocks;       // ceil(K / KW)
-    int tiles_n;       // ceil(L / 32)
+    int tiles_n;       // ceil(L / (32 * LT))
 };
 
-// GUARD / RAGGED as for the kernel above: without GUARD K % KW == 0 and an aligned base are
-// needed; RAGGED = true allows any J and L, RAGGED = false needs J % 16 == 0 and L % 32 == 0.
-template <typename T, bool GUARD, bool RAGGED>
-__global__ void __launch_bounds__(256, GUARD ? 1 : 3)
+// GUARD / RAGGED / LT as for the kernel above: without GUARD K % KW == 0 and an aligned base are
+// needed; RAGGED = true allows any J and L, RAGGED = false needs J % 16 == 0 and L % (32 * LT) == 0.
+template <typename T, bool GUARD, bool RAGGED, int LT>
+__global__ void __launch_bounds__(256, GUARD ? 1 : (LT == 1 ? 3 : 2))
 mttkrp_mode2_kernel(const MttkrpMode2Args<T> args) {
-    typedef MttkrpMode2Cfg<T> Cfg;
+    typedef MttkrpMode2Cfg<T, LT> Cfg;
     typedef Mfma<T> MF;
     typedef typename VecOf<T, Cfg::VEC>::type vec_t;
     constexpr int VEC = Cfg::VEC, NP = Cfg::NP, RBK = Cfg::RBK, LB = Cfg::LB, NG = Cfg::NG;

@@ -164,7 +164,9 @@ MTTKRP_MODE_SHAPES = [(3, 5, 7, 4), (9, 33, 129, 5), (2, 70, 256, 32), (1, 1, 1,
                       (6, 64, 128, 32), (40, 32, 256, 64), (50, 32, 64, 32), (7, 48, 200, 40),
                       (100, 256, 512, 32),
                       # whole aligned k-slices, ragged everything else: the vector kernels' ragged variants
-                      (5, 37, 128, 33), (33, 50, 256, 16), (100, 17, 128, 48)]
+                      (5, 37, 128, 33), (33, 50, 256, 16), (100, 17, 128, 48),
+                      # ranks above 32: two column tiles per wavefront, whole (128) and ragged (96)
+                      (6, 64, 128, 128), (5, 37, 128, 96)]
 
 
 @pytest.mark.parametrize("dtype", DT)
