@@ -304,6 +304,14 @@ int ttv_t(int64_t rows, int64_t K, const T *B, const T *c, T *A, hipStream_t str
     const bool vec = aligned16(B) && aligned16(c) && K % VEC == 0;
     if (!vec) {
         hipLaunchKernelGGL(ttv_generic_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream, B, c, A, rows, K);
+    } else if (K / VEC <= 16) {
+        // short rows: eight rows per 16-lane group and trip, so a workgroup streams 128 rows
+        int64_t b8 = (rows + 127) / 128;
+        if (b8 > (1 << 22)) b8 = 1 << 22;
+        hipLaunchKernelGGL((ttv_short_kernel<T, 8>), dim3((unsigned)b8), dim3(256), 0, stream, B, c, A, rows, K);
+    } else if (rows < 8192 && K * (int64_t)sizeof(T) >= 64 * 1024) {
+        // too few rows to fill the chip with 16 per workgroup: one workgroup per row
+        hipLaunchKernelGGL((ttv_wide_kernel<T, 8>), dim3((unsigned)rows), dim3(256), 0, stream, B, c, A, rows, K);
     } else if (K * (int64_t)sizeof(T) <= 32 * 1024) {
         hipLaunchKernelGGL((ttv_vec_kernel<T, 16, true>), dim3((unsigned)blocks), dim3(256),
                            (size_t)K * sizeof(T), stream, B, c, A, rows, K);

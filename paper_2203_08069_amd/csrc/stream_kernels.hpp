@@ -100,6 +100,84 @@ ttv_vec_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict__
 }
 
 // Any K, any alignment: same 16-lanes-per-row shape with element loads.
+// Short rows (at most 16 pieces of 16 bytes: one piece per lane of a group).  A row then gives a
+// lane a single load, so RU rows are taken at once to keep RU loads per lane in flight; the
+// lane's piece of c stays in a register.
+template <typename T, int RU>
+__global__ void __launch_bounds__(256)
+ttv_short_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict__ A,
+                 int64_t rows, int64_t K) {
+    constexpr int VEC = 16 / (int)sizeof(T);
+    typedef typename VecOf<T, VEC>::type vec_t;
+    const int kvecs = (int)(K / VEC);                 // <= 16
+    const int q = threadIdx.x & 15;
+    const bool mine = q < kvecs;
+    const vec_t cc = mine ? reinterpret_cast<const vec_t *>(c)[q] : vec_t(T(0));
+    const int64_t group = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int64_t stride = (int64_t)gridDim.x * 16;
+    for (int64_t r0 = group; r0 < rows; r0 += stride * RU) {
+        vec_t b[RU];
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+            const int64_t r = r0 + u * stride;
+            b[u] = (mine && r < rows) ? __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(B + r * K) + q)
+                                      : vec_t(T(0));
+        }
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+            T acc = T(0);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc = fma_t(b[u][e], cc[e], acc);
+            acc = sum16(acc);
+            const int64_t r = r0 + u * stride;
+            if (q == 0 && r < rows) A[r] = acc;
+        }
+    }
+}
+
+// Few, long rows: one workgroup per row (256 lanes stride the row), so that a tensor with too few
+// rows for the 16-lane kernel still fills the chip.  Lanes, then wavefronts, are added in a fixed
+// order.  c is read from global memory (it is as long as a row and stays in L2).
+template <typename T, int UNROLL>
+__global__ void __launch_bounds__(256)
+ttv_wide_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict__ A,
+                int64_t rows, int64_t K) {
+    constexpr int VEC = 16 / (int)sizeof(T);
+    typedef typename VecOf<T, VEC>::type vec_t;
+    __shared__ T wsum[4];
+    const int64_t kvecs = K / VEC;
+    const vec_t *cv = reinterpret_cast<const vec_t *>(c);
+    for (int64_t r = blockIdx.x; r < rows; r += gridDim.x) {
+        const vec_t *row = reinterpret_cast<const vec_t *>(B + r * K);
+        T acc = T(0);
+        int64_t v = threadIdx.x;
+        for (; v + 256 * (UNROLL - 1) < kvecs; v += 256 * UNROLL) {
+            vec_t b[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) b[u] = __builtin_nontemporal_load(row + v + 256 * u);
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const vec_t cc = cv[v + 256 * u];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc = fma_t(b[u][e], cc[e], acc);
+            }
+        }
+        for (; v < kvecs; v += 256) {
+            const vec_t b = __builtin_nontemporal_load(row + v);
+            const vec_t cc = cv[v];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc = fma_t(b[e], cc[e], acc);
+        }
+        acc = sum16(acc);
+        acc += __shfl_xor(acc, 16);
+        acc += __shfl_xor(acc, 32);
+        __syncthreads();                       // the previous row's sums have been read
+        if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = acc;
+        __syncthreads();
+        if (threadIdx.x == 0) A[r] = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
+    }
+}
+
 template <typename T>
 __global__ void __launch_bounds__(256)
 ttv_generic_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict__ A,
