@@ -45,6 +45,8 @@ def _bind(path: str):
     lib.oracle_innerprod.argtypes = [ci, i64, i64, i64, vp, vp, vp]
     lib.oracle_ttm.argtypes = [ci, i64, i64, i64, i64, vp, vp, vp]
     lib.oracle_mttkrp.argtypes = [ci, i64, i64, i64, i64, vp, vp, vp, vp]
+    lib.oracle_ttv_mode.argtypes = [ci, ci, i64, i64, i64, vp, vp, vp]
+    lib.oracle_ttv_mode.restype = ci
     lib.oracle_ttm_mode.argtypes = [ci, ci, i64, i64, i64, i64, vp, vp, vp]
     lib.oracle_mttkrp_mode.argtypes = [ci, ci, i64, i64, i64, i64, vp, vp, vp, vp]
     for f in (lib.oracle_ttm_mode, lib.oracle_mttkrp_mode, lib.oracle_gemm, lib.oracle_ttv, lib.oracle_innerprod, lib.oracle_ttm,
@@ -86,6 +88,7 @@ class Variant:
     def innerprod(self, *a, **k): return self._call("innerprod", *a, **k)
     def ttm(self, *a, **k): return self._call("ttm", *a, **k)
     def mttkrp(self, *a, **k): return self._call("mttkrp", *a, **k)
+    def ttv_mode(self, *a, **k): return self._call("ttv_mode", *a, **k)
     def ttm_mode(self, *a, **k): return self._call("ttm_mode", *a, **k)
     def mttkrp_mode(self, *a, **k): return self._call("mttkrp_mode", *a, **k)
 
@@ -220,4 +223,15 @@ def mttkrp_mode(mode: int, B: np.ndarray, C: np.ndarray, D: np.ndarray) -> np.nd
     B, C, D = (np.ascontiguousarray(x) for x in (B, C, D))
     out = np.empty((B.shape[mode], L), dtype=np.float64)
     _check(_load().oracle_mttkrp_mode(_dt(B, C, D), mode, I, J, K, L, _p(B), _p(C), _p(D), _p(out)))
+    return out
+
+
+def ttv_mode(mode: int, B: np.ndarray, c: np.ndarray) -> np.ndarray:
+    """Tensor times vector along `mode` of B: that mode disappears from the output."""
+    if B.ndim != 3 or c.ndim != 1 or mode not in (0, 1, 2) or c.shape[0] != B.shape[mode]:
+        raise ValueError("c must have one entry per index of the contracted mode")
+    I, J, K = B.shape
+    B, c = np.ascontiguousarray(B), np.ascontiguousarray(c)
+    out = np.empty([n for m, n in enumerate(B.shape) if m != mode], dtype=np.float64)
+    _check(_load().oracle_ttv_mode(_dt(B, c), mode, I, J, K, _p(B), _p(c), _p(out)))
     return out

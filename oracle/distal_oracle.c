@@ -21,10 +21,13 @@
  *   ttm        A(i,j,l) = sum_k   B(i,j,k) * C(k,l)          (evaluation list)
  *   mttkrp     A(i,l)   = sum_jk  B(i,j,k) * C(j,l) * D(k,l) (evaluation list)
  *
- * and the same two higher-order contractions taken along the other modes of B
+ * and the higher-order contractions with a vector or a matrix taken along the other modes of B
  * (the evaluation section names TTM and MTTKRP as the building blocks of Tucker
  * and canonical polyadic decompositions, which apply them along every mode):
  *
+ *   ttv_mode     0: A(j,k)   = sum_i B(i,j,k) * c(i)
+ *                1: A(i,k)   = sum_j B(i,j,k) * c(j)
+ *                2: A(i,j)   = sum_k B(i,j,k) * c(k)              (= ttv)
  *   ttm_mode     0: A(r,j,k) = sum_i B(i,j,k) * C(i,r)
  *                1: A(i,r,k) = sum_j B(i,j,k) * C(j,r)
  *                2: A(i,j,r) = sum_k B(i,j,k) * C(k,r)            (= ttm)
@@ -306,6 +309,49 @@ int oracle_mttkrp_mode(int dt, int mode, int64_t I, int64_t J, int64_t K, int64_
                         s += ld_elem(B, dt, (i * J + j) * K + k) * ld_elem(C, dt, i * L + l)
                              * ld_elem(D, dt, j * L + l);
                 out[k * L + l] = (double)s;
+            }
+    }
+    return ORACLE_OK;
+}
+
+/*
+ * Tensor times vector along mode `mode` of B (IxJxK): c has one entry per index of
+ * the contracted mode, the output keeps the two other modes in order:
+ *   mode 0: out(j,k) = sum_i B(i,j,k) * c(i)     out is JxK
+ *   mode 1: out(i,k) = sum_j B(i,j,k) * c(j)     out is IxK
+ *   mode 2: out(i,j) = sum_k B(i,j,k) * c(k)     out is IxJ
+ */
+int oracle_ttv_mode(int dt, int mode, int64_t I, int64_t J, int64_t K,
+                    const void *B, const void *c, double *out)
+{
+    if (dt != ORACLE_F32 && dt != ORACLE_F64) return ORACLE_BAD_ARG;
+    if (I < 0 || J < 0 || K < 0 || mode < 0 || mode > 2) return ORACLE_BAD_ARG;
+    if (mode == 0) {
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int64_t j = 0; j < J; ++j)
+            for (int64_t k = 0; k < K; ++k) {
+                acc_t s = 0;
+                for (int64_t i = 0; i < I; ++i)
+                    s += ld_elem(B, dt, (i * J + j) * K + k) * ld_elem(c, dt, i);
+                out[j * K + k] = (double)s;
+            }
+    } else if (mode == 1) {
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int64_t i = 0; i < I; ++i)
+            for (int64_t k = 0; k < K; ++k) {
+                acc_t s = 0;
+                for (int64_t j = 0; j < J; ++j)
+                    s += ld_elem(B, dt, (i * J + j) * K + k) * ld_elem(c, dt, j);
+                out[i * K + k] = (double)s;
+            }
+    } else {
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int64_t i = 0; i < I; ++i)
+            for (int64_t j = 0; j < J; ++j) {
+                acc_t s = 0;
+                for (int64_t k = 0; k < K; ++k)
+                    s += ld_elem(B, dt, (i * J + j) * K + k) * ld_elem(c, dt, k);
+                out[i * J + j] = (double)s;
             }
     }
     return ORACLE_OK;

@@ -76,6 +76,15 @@ def run(o):
                     src[mode] = x
                     ex += F(T[tuple(src)]) * F(Cn[x, idx[mode]])
                 assert near(out[idx], ex)
+            cn = t(65, 2, (shape[mode],))
+            out = o.ttv_mode(mode, T, cn)
+            for p_, q_ in itertools.product(range(shape[a]), range(shape[b])):
+                ex = Fraction(0)
+                for x in range(shape[mode]):
+                    src = [0, 0, 0]
+                    src[mode], src[a], src[b] = x, p_, q_
+                    ex += F(T[tuple(src)]) * F(cn[x])
+                assert near(out[p_, q_], ex)
             Ca, Db = t(66, 1, (shape[a], 3)), t(66, 2, (shape[b], 3))
             out = o.mttkrp_mode(mode, T, Ca, Db)
             for x, l in itertools.product(range(shape[mode]), range(3)):

@@ -21,7 +21,8 @@ MUTATIONS = [
     ("gemm_wrong_column", "ld_elem(B, dt, k * ldb + j);", "ld_elem(B, dt, k * ldb + (N - 1 - j));"),
     ("gemm_ignores_lda", "ld_elem(A, dt, i * lda + k)", "ld_elem(A, dt, i * K + k)"),
     ("gemm_ignores_ldb", "ld_elem(B, dt, k * ldb + j);", "ld_elem(B, dt, k * N + j);"),
-    ("ttv_wrong_index", "ld_elem(c, dt, k);", "ld_elem(c, dt, K - 1 - k);"),
+    ("ttv_wrong_index", "\n                s += ld_elem(B, dt, (i * J + j) * K + k) * ld_elem(c, dt, k);",
+     "\n                s += ld_elem(B, dt, (i * J + j) * K + k) * ld_elem(c, dt, K - 1 - k);"),
     ("innerprod_dropped_tail", "for (int64_t m = lo; m < hi; ++m)", "for (int64_t m = lo; m < hi - 1; ++m)"),
     ("innerprod_wrong_pairing", "ld_elem(B, dt, m) * ld_elem(C, dt, m);", "ld_elem(B, dt, m) * ld_elem(C, dt, lo + hi - 1 - m);"),
     ("ttm_wrong_column", "ld_elem(C, dt, k * L + l);", "ld_elem(C, dt, k * L + (L - 1 - l));"),
@@ -38,6 +39,8 @@ MUTATIONS = [
      "ld_elem(C, dt, i * L + l);"),
     ("mttkrp_mode2_swapped_factor_rows", "ld_elem(D, dt, j * L + l);", "ld_elem(D, dt, (J - 1 - j) * L + l);"),
     ("mttkrp_mode2_output_transposed", "out[k * L + l] = (double)s;", "out[l * K + k] = (double)s;"),
+    ("ttv_mode0_wrong_weight", "ld_elem(c, dt, i);", "ld_elem(c, dt, I - 1 - i);"),
+    ("ttv_mode1_output_transposed", "out[i * K + k] = (double)s;", "out[k * I + i] = (double)s;"),
     ("narrow_accumulator", "typedef long double acc_t;", "typedef double acc_t;"),
 ]
 

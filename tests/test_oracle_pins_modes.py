@@ -15,6 +15,7 @@ from paper_2203_08069_amd import inputs
 
 DTYPES = [np.float32, np.float64]
 SHAPES = [(2, 3, 4), (4, 1, 3), (1, 5, 2), (3, 2, 1)]
+EINSUM_TTV = {0: "ijk,i->jk", 1: "ijk,j->ik", 2: "ijk,k->ij"}
 EINSUM_TTM = {0: "ijk,ir->rjk", 1: "ijk,jr->irk", 2: "ijk,kr->ijr"}
 EINSUM_MTTKRP = {0: "ijk,jl,kl->il", 1: "ijk,il,kl->jl", 2: "ijk,il,jl->kl"}
 
@@ -168,3 +169,48 @@ def test_modes_zero_extents_and_bad_arguments(oracle, dtype):
     with pytest.raises(ValueError):
         oracle.mttkrp_mode(1, np.zeros((2, 3, 4), dtype=dtype), np.zeros((3, 2), dtype=dtype),
                            np.zeros((4, 2), dtype=dtype))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_ttv_mode_brute_force(oracle, dtype, shape, mode):
+    B, c = rnd(76, 0, shape, dtype), rnd(76, 1, (shape[mode],), dtype)
+    out = oracle.ttv_mode(mode, B, c)
+    keep = others(mode)
+    assert out.shape == (shape[keep[0]], shape[keep[1]])
+    for p, q in itertools.product(range(shape[keep[0]]), range(shape[keep[1]])):
+        ex = Fraction(0)
+        for x in range(shape[mode]):
+            src = [0, 0, 0]
+            src[mode], src[keep[0]], src[keep[1]] = x, p, q
+            ex += F(B[tuple(src)]) * F(c[x])
+        assert near(out[p, q], ex), (mode, p, q)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_ttv_mode_closed_forms(oracle, dtype, mode):
+    shape = (5, 6, 7)
+    B = rnd(77, 0, shape, dtype, inputs.SMALLINT)
+    n = shape[mode]
+    c = rnd(77, 1, (n,), dtype, inputs.SMALLINT)
+    ref = np.einsum(EINSUM_TTV[mode], B.astype(np.int64), c.astype(np.int64))
+    assert np.array_equal(oracle.ttv_mode(mode, B, c), ref.astype(np.float64))
+    # all ones: the plain sum over the mode; a unit vector: the slice at that index
+    assert np.array_equal(oracle.ttv_mode(mode, B, np.ones(n, dtype=dtype)), B.astype(np.float64).sum(axis=mode))
+    e = np.zeros(n, dtype=dtype)
+    e[n - 2] = 1
+    assert np.array_equal(oracle.ttv_mode(mode, B, e), np.take(B, n - 2, axis=mode).astype(np.float64))
+    # the last mode is the paper's statement; the others are it on a transposed copy, bit for bit
+    Bf = rnd(77, 2, shape, dtype)
+    cf = rnd(77, 3, (n,), dtype)
+    if mode == 2:
+        assert np.array_equal(oracle.ttv_mode(2, Bf, cf), oracle.ttv(Bf, cf))
+    else:
+        keep = others(mode)
+        moved = np.ascontiguousarray(Bf.transpose(keep[0], keep[1], mode))
+        assert np.array_equal(oracle.ttv_mode(mode, Bf, cf), oracle.ttv(moved, cf))
+    # tensor times vector is tensor times a one-column matrix
+    assert np.array_equal(oracle.ttv_mode(mode, Bf, cf),
+                          np.squeeze(oracle.ttm_mode(mode, Bf, np.ascontiguousarray(cf[:, None])), axis=mode))
