@@ -95,7 +95,7 @@ def main():
                          "extra rows, not part of 'all': summa (k-chunk leaf shapes), "
                          "ttv_f64,innerprod_f64,ttm_f64,mttkrp_f64, ttm_mode0,ttm_mode1 (TTM along the "
                          "other modes of the configs[3] tensor), mttkrp_mode1,mttkrp_mode2 (MTTKRP along the "
-                         "other modes of the configs[4] tensor), mttkrp_rank64")
+                         "other modes of the configs[4] tensor), mttkrp_rank64, ttv_mode0,ttv_mode1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB read + 1 GiB write elementwise kernel (torch.add), the known-size "
@@ -283,6 +283,28 @@ def main():
                 del hB, hC
             del C, a
         del B
+
+    # ---------------------------------------------------------------- TTV along modes 0 and 1 (extra)
+    if want & {"ttv_mode0", "ttv_mode1"}:
+        I = J = K = 1024
+        B = device_tensor(2, 0, (I, J, K), np.float32, device=dev)
+        c = device_tensor(2, 1, (K,), np.float32, device=dev)             # I = J = K: the vector fits every mode
+        A = torch.empty((I, J), dtype=torch.float32, device=dev)
+        for mode in (0, 1):
+            if f"ttv_mode{mode}" not in want:
+                continue
+            r = finish(f"ttv_mode{mode}", f"TTV along mode {mode}, B {I}x{J}x{K} f32, seed 2", "f32",
+                       lambda: binding.distal_ttv_mode(mode, B, c, A), 2.0 * I * J * K, 4.0 * (I * J * K + K + I * J), "hbm")
+            if cpu:
+                # a block of outputs depends on the matching block of B only
+                hB = np.ascontiguousarray((B[:, :4, :] if mode == 0 else B[:4]).cpu().numpy())
+                t0 = time.perf_counter()
+                ref = oracle.ttv_mode(mode, hB, c.cpu().numpy())
+                sec = time.perf_counter() - t0
+                r["cpu_baseline"] = {"value": hB.nbytes / sec / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+                                     "seconds": sec, "sample": "4 of 1024 slices of B along mode %d" % (1 - mode)}
+                r["sample_normwise_err"] = sample_err(A[:4].cpu().numpy(), ref)
+        del B, c, A
 
     # ---------------------------------------------------------------- TTM (configs[3])
     if "ttm" in want:

@@ -131,6 +131,19 @@ int distal_ttv(distal_dtype dt, int64_t I, int64_t J, int64_t K,
                const void *B, const void *c, void *A, void *stream);
 
 /*
+ * Tensor times vector along any mode of B (I x J x K).  c has one entry per index
+ * of the contracted mode; A keeps the two other modes, in order.  (The background
+ * section's statement contracts the last mode; the decompositions the evaluation
+ * section names apply such products along every mode.)
+ *   mode 0: A(j,k) = sum_i B(i,j,k) * c(i)     A: J x K
+ *   mode 1: A(i,k) = sum_j B(i,j,k) * c(j)     A: I x K
+ *   mode 2: A(i,j) = sum_k B(i,j,k) * c(k)     A: I x J   (= distal_ttv)
+ * All dense; A is overwritten; B is read once, in place.
+ */
+int distal_ttv_mode(distal_dtype dt, int mode, int64_t I, int64_t J, int64_t K,
+                    const void *B, const void *c, void *A, void *stream);
+
+/*
  * Tensor inner product:  a = sum_i sum_j sum_k B(i,j,k) * C(i,j,k)
  * (evaluation list).  B, C: I x J x K dense.  `a` is a DEVICE pointer to one
  * element of type dt, overwritten.  Products are summed in binary64 for both

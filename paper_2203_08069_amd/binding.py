@@ -25,7 +25,7 @@ STATUS_NAMES = {
 # every symbol include/distal.h declares
 EXPORTS = (
     "distal_gemm", "distal_ttm", "distal_mttkrp", "distal_ttv", "distal_innerprod",
-    "distal_ttm_mode", "distal_mttkrp_mode", "distal_mttkrp_mode_workspace_bytes",
+    "distal_ttv_mode", "distal_ttm_mode", "distal_mttkrp_mode", "distal_mttkrp_mode_workspace_bytes",
     "distal_mttkrp_workspace_bytes", "distal_innerprod_workspace_bytes",
     "distal_status_string", "distal_version",
 )
@@ -54,6 +54,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     i64, vp, ci, sz = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     lib.distal_gemm.argtypes = [ci, i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, vp]
     lib.distal_ttm.argtypes = [ci, i64, i64, i64, i64, vp, vp, vp, vp]
+    lib.distal_ttv_mode.argtypes = [ci, ci, i64, i64, i64, vp, vp, vp, vp]
+    lib.distal_ttv_mode.restype = ci
     lib.distal_ttm_mode.argtypes = [ci, ci, i64, i64, i64, i64, vp, vp, vp, vp]
     lib.distal_mttkrp_mode.argtypes = [ci, ci, i64, i64, i64, i64, vp, vp, vp, vp, vp, sz, vp]
     lib.distal_mttkrp_mode_workspace_bytes.argtypes = [ci, ci, i64, i64, i64, i64]
@@ -263,6 +265,22 @@ def distal_ttv(B, c, A):
     with _torch().cuda.device(B.device):
         rc = load_library().distal_ttv(dt, I, J, K, _ptr(B), _ptr(c), _ptr(A), _stream(B))
     _raise(rc, "distal_ttv")
+    return A
+
+
+def distal_ttv_mode(mode, B, c, A):
+    """Tensor times vector along `mode` of B: A keeps the two other modes, in order."""
+    dt = _same(B, c, A)
+    _dense(B, "B", 3), _dense(c, "c", 1), _dense(A, "A", 2)
+    if mode not in (0, 1, 2):
+        raise ValueError("mode must be 0, 1 or 2")
+    I, J, K = B.shape
+    keep = [n for m, n in enumerate(B.shape) if m != mode]
+    if c.shape[0] != B.shape[mode] or list(A.shape) != keep:
+        raise ValueError("shapes do not match a mode-%d tensor-times-vector product" % mode)
+    with _torch().cuda.device(B.device):
+        rc = load_library().distal_ttv_mode(dt, mode, I, J, K, _ptr(B), _ptr(c), _ptr(A), _stream(B))
+    _raise(rc, "distal_ttv_mode")
     return A
 
 

@@ -322,6 +322,33 @@ int ttv_t(int64_t rows, int64_t K, const T *B, const T *c, T *A, hipStream_t str
     return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
 }
 
+// out(b, n) = sum_r c(r) * B(b, r, n): TTV along mode 0 (batch 1, r = i, n = (j,k)) or 1 (b = i, r = j, n = k)
+template <typename T>
+int ttv_left_t(int64_t batch, int64_t R, int64_t N, const T *B, const T *c, T *A, hipStream_t stream) {
+    constexpr int VEC = 16 / (int)sizeof(T);
+    int64_t total;
+    if (!mul_ok(batch, N, &total)) return DISTAL_ERR_SHAPE;
+    if (total == 0) return DISTAL_OK;
+    if (R == 0) return launch_fill<T>(A, 1, total, total, stream);
+    const bool vec = aligned16(B) && aligned16(A) && N % VEC == 0;
+    const int64_t work = vec ? total / VEC : total;
+    int64_t blocks = (work + 255) / 256;
+    if (blocks > (1 << 22)) blocks = 1 << 22;
+    // Rows far apart (a whole slice per step of r) stream best when a workgroup reads 16 KiB
+    // of each row in one go; needs that many whole spans to give every compute unit one.
+    constexpr int64_t kWideSpan = 4 * 256 * VEC;
+    const int64_t wide_groups = (vec && N % kWideSpan == 0) ? total / kWideSpan : 0;
+    if (wide_groups >= 256)
+        hipLaunchKernelGGL((ttv_left_wide_kernel<T, 4, 4>),
+                           dim3((unsigned)(wide_groups < (1 << 22) ? wide_groups : (1 << 22))), dim3(256), 0,
+                           stream, B, c, A, batch, R, N);
+    else if (vec)
+        hipLaunchKernelGGL((ttv_left_vec_kernel<T, 8>), dim3((unsigned)blocks), dim3(256), 0, stream, B, c, A, batch, R, N);
+    else
+        hipLaunchKernelGGL(ttv_left_generic_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream, B, c, A, batch, R, N);
+    return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
+}
+
 // ---- innerprod ------------------------------------------------------------
 template <typename T>
 int innerprod_t(int64_t n, const T *B, const T *C, T *out, double *partial, hipStream_t stream) {
@@ -526,6 +553,24 @@ size_t distal_innerprod_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, i
     int64_t n;
     if (check_dtype(dt) != DISTAL_OK || I < 0 || J < 0 || K < 0 || !tensor_elems(I, J, K, &n)) return 0;
     return (size_t)kInnerprodMaxBlocks * sizeof(double);
+}
+
+int distal_ttv_mode(distal_dtype dt, int mode, int64_t I, int64_t J, int64_t K, const void *B, const void *c,
+                    void *A, void *stream) {
+    if (check_dtype(dt) != DISTAL_OK) return DISTAL_ERR_DTYPE;
+    if (mode < 0 || mode > 2) return DISTAL_ERR_MODE;
+    if (mode == 2) return distal_ttv(dt, I, J, K, B, c, A, stream);
+    if (I < 0 || J < 0 || K < 0) return DISTAL_ERR_SHAPE;
+    int64_t nb, na, jk;
+    if (!tensor_elems(I, J, K, &nb) || !mul_ok(J, K, &jk) || !mul_ok(mode == 0 ? J : I, K, &na)) return DISTAL_ERR_SHAPE;
+    const int64_t X = mode == 0 ? I : J;                    // the contracted extent
+    if ((nb > 0 && !B) || (X > 0 && na > 0 && !c) || (na > 0 && !A)) return DISTAL_ERR_NULL;
+    if (na > 0 && (A == B || A == c)) return DISTAL_ERR_ALIAS;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t batch = mode == 0 ? 1 : I, N = mode == 0 ? jk : K;
+    if (dt == DISTAL_F64)
+        return ttv_left_t<double>(batch, X, N, (const double *)B, (const double *)c, (double *)A, s);
+    return ttv_left_t<float>(batch, X, N, (const float *)B, (const float *)c, (float *)A, s);
 }
 
 int distal_innerprod(distal_dtype dt, int64_t I, int64_t J, int64_t K, const void *B, const void *C,

@@ -178,6 +178,109 @@ ttv_wide_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict_
     }
 }
 
+// TTV along a mode that is not the contiguous one, as a weighted sum of rows:
+//   out(b, n) = sum_r c(r) * B(b, r, n),  n contiguous  (mode 0: b = 1, r = i, n = (j,k);
+//   mode 1: b = i, r = j, n = k).
+// A lane owns VEC neighbouring n of one b and walks r, UNROLL 16-byte loads in flight; what the
+// lanes of a wavefront read for one r is contiguous, so the stream is fully coalesced.  Each output
+// is summed by one lane in increasing r: no reduction across lanes, nothing to make deterministic.
+template <typename T, int UNROLL>
+__global__ void __launch_bounds__(256)
+ttv_left_vec_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict__ A,
+                    int64_t batch, int64_t R, int64_t N) {
+    constexpr int VEC = 16 / (int)sizeof(T);
+    typedef typename VecOf<T, VEC>::type vec_t;
+    const int64_t nv = N / VEC, total = batch * nv;
+    for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < total; v += (int64_t)gridDim.x * 256) {
+        const int64_t b = v / nv, n = (v % nv) * VEC;
+        const T *col = B + b * R * N + n;
+        vec_t acc = vec_t(T(0));
+        int64_t r = 0;
+        for (; r + UNROLL <= R; r += UNROLL) {
+            vec_t x[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u)
+                x[u] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(col + (r + u) * N));
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const T w = c[r + u];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[e] = fma_t(x[u][e], w, acc[e]);
+            }
+        }
+        for (; r < R; ++r) {
+            const vec_t x = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(col + r * N));
+            const T w = c[r];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] = fma_t(x[e], w, acc[e]);
+        }
+        *reinterpret_cast<vec_t *>(A + b * N + n) = acc;
+    }
+}
+
+// The same sum with NV pieces per lane, 4 KiB apart: a workgroup then reads NV * 4 KiB contiguous
+// bytes of every row, which suits rows that are far apart (mode 0: consecutive r are a whole
+// J x K slice apart).  Needs N to be a multiple of NV * 256 pieces.
+template <typename T, int NV, int UNROLL>
+__global__ void __launch_bounds__(256)
+ttv_left_wide_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict__ A,
+                     int64_t batch, int64_t R, int64_t N) {
+    constexpr int VEC = 16 / (int)sizeof(T);
+    typedef typename VecOf<T, VEC>::type vec_t;
+    const int64_t span = (int64_t)NV * 256 * VEC;             // elements of n per workgroup
+    const int64_t per_b = N / span, total = batch * per_b;
+    for (int64_t g = blockIdx.x; g < total; g += gridDim.x) {
+        const int64_t b = g / per_b, n = (g % per_b) * span + (int64_t)threadIdx.x * VEC;
+        const T *col = B + b * R * N + n;
+        vec_t acc[NV];
+#pragma unroll
+        for (int q = 0; q < NV; ++q) acc[q] = vec_t(T(0));
+        int64_t r = 0;
+        for (; r + UNROLL <= R; r += UNROLL) {
+            vec_t x[UNROLL][NV];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+                for (int q = 0; q < NV; ++q)
+                    x[u][q] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(col + (r + u) * N + q * 256 * VEC));
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const T w = c[r + u];
+#pragma unroll
+                for (int q = 0; q < NV; ++q)
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) acc[q][e] = fma_t(x[u][q][e], w, acc[q][e]);
+            }
+        }
+        for (; r < R; ++r) {
+            const T w = c[r];
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                const vec_t x = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(col + r * N + q * 256 * VEC));
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[q][e] = fma_t(x[e], w, acc[q][e]);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < NV; ++q) *reinterpret_cast<vec_t *>(A + b * N + n + q * 256 * VEC) = acc[q];
+    }
+}
+
+// Same sum, one element per lane: any alignment and any N.
+template <typename T>
+__global__ void __launch_bounds__(256)
+ttv_left_generic_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict__ A,
+                        int64_t batch, int64_t R, int64_t N) {
+    const int64_t total = batch * N;
+    for (int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x; m < total; m += (int64_t)gridDim.x * 256) {
+        const int64_t b = m / N, n = m % N;
+        const T *col = B + b * R * N + n;
+        T acc = T(0);
+        for (int64_t r = 0; r < R; ++r) acc = fma_t(col[r * N], c[r], acc);
+        A[m] = acc;
+    }
+}
+
 template <typename T>
 __global__ void __launch_bounds__(256)
 ttv_generic_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict__ A,

@@ -149,6 +149,22 @@ def test_mode_call_argument_errors(lib):
         assert t(1, mode, 2, 2, 2, 0, None, None, None, None) == 0      # empty output
 
 
+def test_ttv_mode_argument_errors(lib):
+    a, b, c = (P(FAKE + 256 * i) for i in range(3))
+    t = lib.distal_ttv_mode
+    assert t(0, 3, 2, 2, 2, a, b, c, None) == 8
+    assert t(6, 0, 2, 2, 2, a, b, c, None) == 3
+    for mode in (0, 1, 2):
+        assert t(0, mode, 2, 2, -1, a, b, c, None) == 2
+        assert t(0, mode, 1 << 31, 1 << 31, 1 << 31, a, b, c, None) == 2
+        assert t(0, mode, 2, 2, 2, None, b, c, None) == 1
+        assert t(0, mode, 2, 2, 2, a, None, c, None) == 1
+        assert t(0, mode, 2, 2, 2, a, b, None, None) == 1
+        assert t(0, mode, 2, 2, 2, a, b, a, None) == 5
+    assert t(1, 0, 3, 0, 2, None, None, None, None) == 0          # empty output
+    assert t(1, 1, 0, 3, 2, None, None, None, None) == 0
+
+
 def test_mttkrp_mode_argument_errors(lib):
     a, b, c, d, w = (P(FAKE + 256 * i) for i in range(5))
     m = lib.distal_mttkrp_mode

@@ -151,6 +151,56 @@ def test_ttm_mode_zero_extents(lib, dtype):
     lib.distal_ttm_mode(0, z(2, 3, 5), z(2, 0), z(0, 3, 5))
 
 
+# ------------------------------------------------------------------ ttv along a mode
+
+TTV_MODE_SHAPES = [(3, 5, 7), (17, 9, 36), (64, 33, 128), (1, 1, 1), (300, 4, 8), (5, 700, 3), (40, 50, 1024),
+                   (1000, 16, 64), (2, 1000, 260),
+                   # >= 256 spans of 16 KiB per row: the one-span-per-workgroup kernel, with a leftover row
+                   # (mode 0: N = J*K = 2^20; mode 1: N = K, batch I)
+                   (5, 1024, 1024), (9, 5, 262144)]
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("I,J,K", TTV_MODE_SHAPES)
+def test_ttv_mode(lib, oracle, dtype, kind, mode, I, J, K):
+    shape = (I, J, K)
+    B, c = U.gen(48 + mode, 0, shape, dtype, kind), U.gen(48 + mode, 1, (shape[mode],), dtype, kind)
+    A = empty([n for m, n in enumerate(shape) if m != mode], dtype)
+    lib.distal_ttv_mode(mode, U.dev(B), U.dev(c), A)
+    compare(U.host(A), oracle.ttv_mode(mode, B, c), dtype, kind, shape[mode])
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("mode", [0, 1])
+def test_ttv_mode_closed_forms_and_zero_extents(lib, dtype, mode):
+    import torch
+    shape = (12, 20, 48)
+    B = U.gen(49, 0, shape, dtype)
+    n = shape[mode]
+    keep = [x for m, x in enumerate(shape) if m != mode]
+    A = empty(keep, dtype)
+    e = np.zeros(n, dtype=dtype)
+    e[n - 3] = 1
+    lib.distal_ttv_mode(mode, U.dev(B), U.dev(e), A)
+    assert np.array_equal(U.host(A), np.take(B, n - 3, axis=mode))
+    lib.distal_ttv_mode(mode, U.dev(B), U.dev(np.ones(n, dtype=dtype)), A)
+    U.assert_close(U.host(A), B.astype(np.float64).sum(axis=mode), dtype, n)
+    tdt = getattr(torch, np.dtype(dtype).name)
+    z = lambda *s: torch.zeros(s, dtype=tdt, device="cuda:0")
+    if mode == 0:
+        A = empty((3, 4), dtype)
+        lib.distal_ttv_mode(0, z(0, 3, 4), z(0), A)
+        assert np.array_equal(U.host(A), np.zeros((3, 4)))
+        lib.distal_ttv_mode(0, z(2, 0, 4), z(2), z(0, 4))
+    else:
+        A = empty((2, 4), dtype)
+        lib.distal_ttv_mode(1, z(2, 0, 4), z(0), A)
+        assert np.array_equal(U.host(A), np.zeros((2, 4)))
+        lib.distal_ttv_mode(1, z(2, 3, 0), z(3), z(2, 0))
+
+
 # ------------------------------------------------------------------ mttkrp along a mode
 
 def factor_shapes(shape, mode, L):
@@ -268,6 +318,12 @@ def test_outputs_and_workspaces_stay_inside_their_buffers(lib, oracle, dtype, of
     lib.distal_ttv(dB, U.dev(c), A)
     U.assert_close(U.host(A), oracle.ttv(B, c), dtype, K)
     assert bands_untouched(buf, span)
+    for mode in (0, 1):
+        cm = U.gen(80, 3, (B.shape[mode],), dtype)
+        buf, A, span = banded([n for m, n in enumerate(B.shape) if m != mode], dtype, offset)
+        lib.distal_ttv_mode(mode, dB, U.dev(cm), A)
+        U.assert_close(U.host(A), oracle.ttv_mode(mode, B, cm), dtype, B.shape[mode])
+        assert bands_untouched(buf, span)
     for mode in (0, 1, 2):
         Cm = U.gen(80, 2, (B.shape[mode], L), dtype)
         shape = list(B.shape)
