@@ -46,7 +46,7 @@ PEAK_HBM_GBS = 8000.0
 # same counters on a plain copy kernel of known size; see profiles/.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
     "gemm_f64": 9.133e9, "gemm_f32": 3.535e9, "ttm": 5.518e9, "ttm_mode0": 5.504e9, "ttm_mode1": 5.505e9,
-    "mttkrp": 4.331e9, "mttkrp_mode2": 4.328e9, "ttv": 4.299e9, "innerprod": 8.590e9,
+    "mttkrp": 4.331e9, "mttkrp_mode2": 4.328e9, "ttv": 4.299e9, "ttv_mode0": 4.299e9, "innerprod": 8.590e9,
 }
 
 

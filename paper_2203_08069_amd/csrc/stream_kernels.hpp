@@ -77,7 +77,8 @@ ttv_vec_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict__
         const vec_t *row = reinterpret_cast<const vec_t *>(B + r * K);
         T acc = T(0);
         int64_t v = q;
-        for (; v + 16 * (UNROLL - 1) < kvecs; v += 16 * UNROLL) {
+        // whole trips of UNROLL pieces per lane (the same count for every lane of the group) ...
+        for (; v - q + 16 * UNROLL <= kvecs; v += 16 * UNROLL) {
             vec_t b[UNROLL];
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) b[u] = __builtin_nontemporal_load(row + v + 16 * u);
@@ -88,11 +89,18 @@ ttv_vec_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict__
                 for (int e = 0; e < VEC; ++e) acc = fma_t(b[u][e], cc[e], acc);
             }
         }
-        for (; v < kvecs; v += 16) {
-            const vec_t b = __builtin_nontemporal_load(row + v);
-            const vec_t cc = cv[v];
+        // ... then the rest of the row in predicated trips of four
+        for (; v - q < kvecs; v += 16 * 4) {
+            vec_t b[4];
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc = fma_t(b[e], cc[e], acc);
+            for (int u = 0; u < 4; ++u)
+                b[u] = v + 16 * u < kvecs ? __builtin_nontemporal_load(row + v + 16 * u) : vec_t(T(0));
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const vec_t cc = v + 16 * u < kvecs ? cv[v + 16 * u] : vec_t(T(0));
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc = fma_t(b[u][e], cc[e], acc);
+            }
         }
         acc = sum16(acc);
         if (q == 0) A[r] = acc;
@@ -132,6 +140,95 @@ ttv_short_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict
             const int64_t r = r0 + u * stride;
             if (q == 0 && r < rows) A[r] = acc;
         }
+    }
+}
+
+// One step of ttv_row_kernel: PU pieces (v, v+64, ...) of each of the RW rows r .. r+RW-1, rows
+// at or past `hi` replaced by row hi-1.
+template <typename T, int RW, int PU>
+__device__ __forceinline__ void ttv_row_load(typename VecOf<T, 16 / (int)sizeof(T)>::type (&b)[RW][PU],
+                                             const T *__restrict__ B, int64_t K, int64_t r, int64_t hi, int64_t v) {
+    typedef typename VecOf<T, 16 / (int)sizeof(T)>::type vec_t;
+#pragma unroll
+    for (int t = 0; t < RW; ++t) {
+        const vec_t *row = reinterpret_cast<const vec_t *>(B + (r + t < hi ? r + t : hi - 1) * K) + v;
+#pragma unroll
+        for (int u = 0; u < PU; ++u) b[t][u] = __builtin_nontemporal_load(row + 64 * u);
+    }
+}
+
+// One step of ttv_row_kernel on the pieces in `cur` (rows r .., pieces v0 + lane + 64u): issues
+// the next step's loads into `nxt` first, then multiplies, and when the rows are complete adds
+// across the wavefront and stores.  Advances (r, v0); false when there is no next step.
+template <typename T, int RW, int PU>
+__device__ __forceinline__ bool ttv_row_step(typename VecOf<T, 16 / (int)sizeof(T)>::type (&cur)[RW][PU],
+                                             typename VecOf<T, 16 / (int)sizeof(T)>::type (&nxt)[RW][PU],
+                                             T (&acc)[RW], const T *__restrict__ B,
+                                             const typename VecOf<T, 16 / (int)sizeof(T)>::type *__restrict__ cv,
+                                             T *__restrict__ A, int64_t K, int64_t kvecs, int64_t hi, int lane,
+                                             int64_t &r, int64_t &v0) {
+    constexpr int VEC = 16 / (int)sizeof(T);
+    typedef typename VecOf<T, VEC>::type vec_t;
+    int64_t v1 = v0 + 64 * PU, r1 = r;
+    if (v1 >= kvecs) { v1 = 0; r1 = r + 4 * RW; }
+    const bool more = r1 < hi;
+    if (more) ttv_row_load<T, RW, PU>(nxt, B, K, r1, hi, v1 + lane);
+#pragma unroll
+    for (int u = 0; u < PU; ++u) {
+        const vec_t cc = cv[v0 + lane + 64 * u];
+#pragma unroll
+        for (int t = 0; t < RW; ++t)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[t] = fma_t(cur[t][u][e], cc[e], acc[t]);
+    }
+    if (v1 == 0) {                              // the rows are complete
+        T out = T(0);
+#pragma unroll
+        for (int t = 0; t < RW; ++t) {
+            T s = sum16(acc[t]);
+            s += __shfl_xor(s, 16);
+            s += __shfl_xor(s, 32);
+            if (lane == t) out = s;
+            acc[t] = T(0);
+        }
+        if (lane < RW && r + lane < hi) A[r + lane] = out;
+    }
+    r = r1;
+    v0 = v1;
+    return more;
+}
+
+// Rows of at least 64 pieces, many of them: a wavefront takes RW whole rows per trip (lane l
+// reads pieces l, l+64, ... of each, PU of them per row in flight, RW * PU = 8), and a workgroup
+// owns a contiguous range of `per` rows (a multiple of 4 * RW), so with one workgroup per compute
+// unit the chip reads 256 sequential streams - the pattern HBM serves fastest here.  c comes
+// through the caches (staging it in LDS gains nothing).  K / VEC must be a multiple of 64 * PU.
+// Rows past the range's end are clamped to its last row and not stored.  The loads of the next
+// step are issued before the arithmetic and the reduction of the current one, so the stream
+// never pauses for a row's sum.  Each row's sum is formed in an order fixed by K alone.
+template <typename T, int RW, int PU>
+__global__ void __launch_bounds__(256)
+ttv_row_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict__ A,
+               int64_t rows, int64_t K, int64_t per) {
+    constexpr int VEC = 16 / (int)sizeof(T);
+    typedef typename VecOf<T, VEC>::type vec_t;
+    const int64_t kvecs = K / VEC;
+    const vec_t *cv = reinterpret_cast<const vec_t *>(c);
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t lo = (int64_t)blockIdx.x * per;
+    const int64_t hi = lo + per < rows ? lo + per : rows;
+    int64_t r = lo + w * RW;
+    if (r >= hi) return;
+
+    vec_t even[RW][PU], odd[RW][PU];           // steps alternate between the two register sets
+    T acc[RW];
+#pragma unroll
+    for (int t = 0; t < RW; ++t) acc[t] = T(0);
+    int64_t v0 = 0;
+    ttv_row_load<T, RW, PU>(even, B, K, r, hi, v0 + lane);
+    for (;;) {
+        if (!ttv_row_step<T, RW, PU>(even, odd, acc, B, cv, A, K, kvecs, hi, lane, r, v0)) break;
+        if (!ttv_row_step<T, RW, PU>(odd, even, acc, B, cv, A, K, kvecs, hi, lane, r, v0)) break;
     }
 }
 
