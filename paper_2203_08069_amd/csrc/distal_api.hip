@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <algorithm>
 #include <cstdint>
 #include <limits>
 
@@ -20,6 +21,7 @@ constexpr int kInnerprodMaxBlocks = 2048;   // fixed: the summation order must n
 // Workgroups of a streaming launch that gives each a contiguous range: one per compute unit of
 // the part (256), which is what HBM serves fastest; a constant, so results do not depend on the device.
 constexpr int kStreamBlocks = 256;
+constexpr int64_t kComputeUnits = 256;
 constexpr size_t kWorkspaceAlign = 256;
 
 bool mul_ok(int64_t a, int64_t b, int64_t *out) { return !__builtin_mul_overflow(a, b, out); }
@@ -50,7 +52,9 @@ bool allow_lds(Kern kern, int bytes, std::atomic<bool> (&done)[kMaxDevices]) {
 constexpr int64_t kMaxGridY = 65535;
 
 // One launch per run of at most kMaxGridY problems of the batch (blockIdx.y picks the problem).
-template <typename T, int BM, int BN, int BK, int WM, int WN, bool FAST, bool TA>
+// KIND: the guarded kernel, the straight-line kernel on whole tiles, or its edge-clamping form.
+enum { kGuarded = 0, kWhole = 1, kEdge = 2 };
+template <typename T, int BM, int BN, int BK, int WM, int WN, int KIND, bool TA>
 int launch_contract(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
     typedef ContractCfg<T, BM, BN, BK, WM, WN, TA> Cfg;
     a.tiles_m = (int)((a.M + BM - 1) / BM);
@@ -60,12 +64,12 @@ int launch_contract(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
     for (int64_t first = 0; first < batch; first += kMaxGridY) {
         const int64_t count = batch - first < kMaxGridY ? batch - first : kMaxGridY;
         const dim3 grid((unsigned)nblocks, (unsigned)count);
-        if constexpr (FAST) {
-            auto kern = contract_fast_kernel<T, BM, BN, BK, WM, WN, TA>;
+        if constexpr (KIND == kGuarded) {
+            auto kern = contract_kernel<T, BM, BN, BK, WM, WN, TA>;
             if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
             hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
         } else {
-            auto kern = contract_kernel<T, BM, BN, BK, WM, WN, TA>;
+            auto kern = contract_fast_kernel<T, BM, BN, BK, WM, WN, TA, KIND == kEdge>;
             if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
             hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
         }
@@ -75,6 +79,26 @@ int launch_contract(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
         a.C += count * a.batch_c;
     }
     return DISTAL_OK;
+}
+
+// The straight-line kernel with BM x BN x BK tiles on operands whose 16-byte pieces never
+// straddle an edge: whole tiles as they are, ragged M or N through the edge-clamping form, and
+// the K % BK trailing terms added by a second, guarded pass over C (K >= BK).
+template <typename T, int BM, int BN, int BK, int WM, int WN, bool TA>
+int launch_tiles(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
+    const int64_t k_main = a.K / BK * BK, k_tail = a.K - k_main;
+    ContractArgs<T> m = a;
+    m.K = k_main;
+    const int rc = (a.M % BM == 0 && a.N % BN == 0)
+                       ? launch_contract<T, BM, BN, BK, WM, WN, kWhole, TA>(m, batch, stream)
+                       : launch_contract<T, BM, BN, BK, WM, WN, kEdge, TA>(m, batch, stream);
+    if (rc != DISTAL_OK || k_tail == 0) return rc;
+    ContractArgs<T> t = a;                       // k_main is a multiple of 16: alignment is unchanged
+    t.A += TA ? k_main * a.lda : k_main;
+    t.B += k_main * a.ldb;
+    t.K = k_tail;
+    t.accumulate = 1;
+    return launch_contract<T, 128, 128, 16, 2, 2, kGuarded, TA>(t, batch, stream);
 }
 
 template <typename T>
@@ -88,15 +112,20 @@ int launch_fill(T *out, int64_t rows, int64_t cols, int64_t ld, hipStream_t stre
 }
 
 // ---- matrix multiply ------------------------------------------------------
-// Tile choice depends on the shape only.  Shapes made of whole, aligned tiles take the
-// straight-line kernel.  What matters most is four wavefronts per SIMD: binary64 wavefronts own
-// 32 x 64 sub-tiles (64 accumulator registers), eight of them on a 128 x 128 tile or, for deep
-// products, sixteen on 256 x 128; binary32 wavefronts own 64 x 64 sub-tiles, sixteen on a
-// 256 x 256 tile with 32-deep slabs for deep products, eight on 256 x 128 for k-chunks (with one
-// workgroup per CU the epilogue is not hidden, so shallow products want smaller tiles), four on
-// 128 x 128 below that.  A problem with fewer than 256 tiles of 128 x 128 takes 64 x 64 tiles;
-// everything else takes the guarded 128 x 128 kernel.
-constexpr int64_t kBigTileMinTiles = 256;   // below this a grid of big tiles cannot fill 256 CUs
+// Tile choice depends on the shape only.  What matters most is four wavefronts per SIMD:
+// binary64 wavefronts own 32 x 64 sub-tiles (64 accumulator registers), eight of them on a
+// 128 x 128 tile or, for deep products, sixteen on 256 x 128; binary32 wavefronts own 64 x 64
+// sub-tiles, sixteen on a 256 x 256 tile with 32-deep slabs for deep products, eight on 256 x 128
+// for k-chunks (with one workgroup per CU the epilogue is not hidden, so shallow products want
+// smaller tiles), four on 128 x 128; 64 x 64 tiles for problems too small to fill the part with
+// those.  Among the shapes a product is deep enough for, the one with the least estimated time
+// wins: tiles per compute unit, a partly filled last round counted in full, x tile area / the
+// kernel's speed relative to the best one (measured at 8192^3: binary64 1, 0.985, 0.915 for
+// 256 x 128, 128 x 128, 64 x 64; binary32 1, 0.973, 0.95, 0.81 from 256 x 256 down).  Whole
+// aligned tiles take the straight-line kernels as they are, ragged M and N their edge-clamping
+// form (the padding is paid for through the tile count), K % 16 trailing terms a second pass;
+// only operands whose 16-byte pieces would straddle an edge (misaligned bases or leading
+// dimensions, N not a multiple of the vector) take the guarded 128 x 128 kernel.
 
 // TA = false: C = [C +] A * B with A stored M x K.  TA = true: the left operand is stored
 // K x M (C = [C +] At^T * B), the form a contraction over a non-last tensor mode takes.
@@ -127,30 +156,37 @@ int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
     a.a_vec_ok = aligned16(A) && lda % VEC == 0 && stride_a % VEC == 0;
     a.b_vec_ok = aligned16(B) && ldb % VEC == 0 && stride_b % VEC == 0;
     a.c_vec_ok = aligned16(C) && ldc % VEC == 0 && stride_c % VEC == 0;
-    const bool whole = a.a_vec_ok && a.b_vec_ok && a.c_vec_ok && K % 16 == 0;
-    const bool m256 = M % 256 == 0, n128 = N % 128 == 0;
-    const bool fills128 = tm * tn * batch >= kBigTileMinTiles;          // one 128 x 128 tile per CU at least
+    // the straight-line kernels need 16-byte pieces that never straddle an edge of an operand
+    const bool pieces = a.a_vec_ok && a.b_vec_ok && a.c_vec_ok && N % VEC == 0 && (!TA || M % VEC == 0);
+    if (!pieces || K < 16) return launch_contract<T, 128, 128, 16, 2, 2, kGuarded, TA>(a, batch, stream);
+    // Estimated time of a tile shape: tiles per compute unit (256 of them, the last round of a
+    // grid counts in full) x tile area / measured relative speed of that kernel.  Ragged shapes
+    // pay for their padding and for a partly filled last round through the same count.
+    auto cost = [&](int64_t bm, int64_t bn, double speed) {
+        const int64_t t = ((M + bm - 1) / bm) * ((N + bn - 1) / bn) * batch;
+        return (double)((t + kComputeUnits - 1) / kComputeUnits) * (double)(bm * bn) / speed;
+    };
     if constexpr (sizeof(T) == 4) {
-        if (whole && m256 && N % 256 == 0 && K % 32 == 0 && K >= 1024 &&
-            (M / 256) * (N / 256) * batch >= kBigTileMinTiles) {
+        const double c64 = cost(64, 64, 0.81), c128 = cost(128, 128, 0.95);
+        const double c256x128 = K >= 512 ? cost(256, 128, 0.973) : 1e300;
+        // 32-deep slabs unless they alone would leave trailing terms to a second pass
+        const double c256 = (K >= 1024 && (K % 32 == 0 || K % 16 != 0)) ? cost(256, 256, 1.0) : 1e300;
+        const double best = std::min(std::min(c64, c128), std::min(c256x128, c256));
+        if (c256 == best) {
             // a transposed left operand is staged in rows of 256 either way: 16-deep slabs measure 1 % faster
-            if constexpr (TA) return launch_contract<T, 256, 256, 16, 4, 4, true, TA>(a, batch, stream);
-            else return launch_contract<T, 256, 256, 32, 4, 4, true, TA>(a, batch, stream);
+            if constexpr (TA) return launch_tiles<T, 256, 256, 16, 4, 4, TA>(a, batch, stream);
+            else return launch_tiles<T, 256, 256, 32, 4, 4, TA>(a, batch, stream);
         }
-        if (whole && m256 && n128 && K >= 512 && (M / 256) * (N / 128) * batch >= kBigTileMinTiles)
-            return launch_contract<T, 256, 128, 16, 4, 2, true, TA>(a, batch, stream);
-        if (whole && M % 128 == 0 && n128 && fills128)
-            return launch_contract<T, 128, 128, 16, 2, 2, true, TA>(a, batch, stream);
+        if (c256x128 == best) return launch_tiles<T, 256, 128, 16, 4, 2, TA>(a, batch, stream);
+        if (c128 == best) return launch_tiles<T, 128, 128, 16, 2, 2, TA>(a, batch, stream);
     } else {
-        if (whole && m256 && n128 && K >= 4096 && (M / 256) * (N / 128) * batch >= kBigTileMinTiles)
-            return launch_contract<T, 256, 128, 16, 8, 2, true, TA>(a, batch, stream);
-        if (whole && M % 128 == 0 && n128 && fills128)
-            return launch_contract<T, 128, 128, 16, 4, 2, true, TA>(a, batch, stream);
+        const double c64 = cost(64, 64, 0.915), c128 = cost(128, 128, 0.985);
+        const double c256x128 = K >= 4096 ? cost(256, 128, 1.0) : 1e300;
+        const double best = std::min(std::min(c64, c128), c256x128);
+        if (c256x128 == best) return launch_tiles<T, 256, 128, 16, 8, 2, TA>(a, batch, stream);
+        if (c128 == best) return launch_tiles<T, 128, 128, 16, 4, 2, TA>(a, batch, stream);
     }
-    // too few 128 x 128 tiles to give every CU one: quarter-size tiles, four times the workgroups
-    if (whole && M % 64 == 0 && N % 64 == 0)
-        return launch_contract<T, 64, 64, 16, 2, 2, true, TA>(a, batch, stream);
-    return launch_contract<T, 128, 128, 16, 2, 2, false, TA>(a, batch, stream);
+    return launch_tiles<T, 64, 64, 16, 2, 2, TA>(a, batch, stream);
 }
 
 int check_dtype(int dt) { return (dt == DISTAL_F32 || dt == DISTAL_F64) ? DISTAL_OK : DISTAL_ERR_DTYPE; }

@@ -411,8 +411,15 @@ contract_kernel(ContractArgs<T> args) {
 // straight-line block, so the LDS writes of the next slab and the global loads of the
 // slab after it are issued between the MFMAs of the current slab, in the issue slots
 // the 64-cycle MFMAs leave free, instead of in a burst of their own.
+//
+// EDGE = true serves M and N that are not whole tiles at no cost in the k-loop: a 16-byte
+// piece that lies past the edge is fetched from the last valid row (or last valid piece of a
+// row) instead, so every load stays in bounds and the rows and columns it feeds hold values
+// that no valid output depends on; the epilogue stores only what lies inside M x N.
+// Pieces must not straddle an edge: N (and M, when TA) a multiple of the 16-byte vector.
+// K is a multiple of BK in both forms.
 // ---------------------------------------------------------------------------
-template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TA = false>
+template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TA = false, bool EDGE = false>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 4 : 2)
 contract_fast_kernel(ContractArgs<T> args) {
     typedef ContractCfg<T, BM, BN, BK, WAVES_M, WAVES_N, TA> Cfg;
@@ -448,13 +455,23 @@ contract_fast_kernel(ContractArgs<T> args) {
 #pragma unroll
     for (int p = 0; p < Cfg::A_PER_T; ++p) {
         const int v = tid + p * NT, r = v / ARL, kv = v % ARL;
-        a_off[p] = TA ? (int64_t)r * args.lda + m0 + kv * VEC : (m0 + r) * args.lda + kv * VEC;
+        if constexpr (TA) {
+            int64_t m = m0 + kv * VEC;
+            if (EDGE && m > args.M - VEC) m = args.M - VEC;
+            a_off[p] = (int64_t)r * args.lda + m;
+        } else {
+            int64_t m = m0 + r;
+            if (EDGE && m > args.M - 1) m = args.M - 1;
+            a_off[p] = m * args.lda + kv * VEC;
+        }
         a_lds[p] = r * Cfg::LDA_S + kv * VEC;
     }
 #pragma unroll
     for (int p = 0; p < Cfg::B_PER_T; ++p) {
         const int v = tid + p * NT, r = v / (BN / VEC), cv = v % (BN / VEC);
-        b_off[p] = (int64_t)r * args.ldb + n0 + cv * VEC;
+        int64_t n = n0 + cv * VEC;
+        if (EDGE && n > args.N - VEC) n = args.N - VEC;
+        b_off[p] = (int64_t)r * args.ldb + n;
         b_lds[p] = Cfg::A_ELEMS + r * Cfg::LDB_S + cv * VEC;
     }
 
@@ -512,6 +529,7 @@ contract_fast_kernel(ContractArgs<T> args) {
             for (int v = 0; v < MF::NACC; ++v) {
                 const int64_t row = m0 + wm * Cfg::WTM + sub_tile_row<Cfg>(mi, v, lane);
                 const int64_t col = n0 + wn * Cfg::WTN + g * (MF::NB * CV) + li * CV;
+                if (EDGE && (row >= args.M || col >= args.N)) continue;
                 T *cp = args.C + row * args.ldc + col;
                 cvec_t o;
                 if constexpr (CV == 1) {

@@ -109,6 +109,22 @@ def test_ttm_mode0_wide_big_tiles(lib, oracle, dtype, kind):
 
 
 @pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("I,J,K,R", [(520, 50, 40, 2040), (1028, 60, 68, 4000), (4100, 30, 68, 4000)])
+def test_ttm_mode0_ragged_edge_tiles(lib, oracle, dtype, kind, I, J, K, R):
+    """mode 0 with R and J*K that are not whole tiles and a contracted extent with trailing terms:
+    the transposed-left-operand kernels in their edge-clamping form (128 x 128 tiles; 256 x 256
+    binary32 tiles; 256 x 128 tiles in both types).  Some j-slices are checked in full."""
+    B, C = U.gen(46, 0, (I, J, K), dtype, kind), U.gen(46, 1, (I, R), dtype, kind)
+    A = empty((R, J, K), dtype)
+    lib.distal_ttm_mode(0, U.dev(B), U.dev(C), A)
+    got = U.host(A)
+    assert np.all(np.isfinite(got))
+    for j in (0, J // 2, J - 1):
+        compare(got[:, j:j + 1, :], oracle.ttm_mode(0, np.ascontiguousarray(B[:, j:j + 1, :]), C), dtype, kind, I)
+
+
+@pytest.mark.parametrize("dtype", DT)
 def test_ttm_mode0_k_chunk_tiles(lib, oracle, dtype):
     """mode 0 with a contracted extent of 512 and 256 tiles of 256 x 128 (the binary32 k-chunk
     configuration with a transposed left operand)."""

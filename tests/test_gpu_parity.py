@@ -78,6 +78,48 @@ def test_gemm_big_tile_configs(lib, oracle, kind, dtype, M, N, K):
     assert np.array_equal(U.host(C), got * 2)
 
 
+# ragged shapes that reach the same launch configurations in their edge-clamping form (M and N
+# not whole tiles, K with trailing terms for the second pass), in the order of BIG_TILE_SHAPES,
+# then 128 x 128 binary32 and a shape whose K is made of whole slabs
+RAGGED_TILE_SHAPES = [(np.float32, 4000, 4000, 1028), (np.float32, 4000, 2040, 520),
+                      (np.float64, 4000, 2040, 4100), (np.float64, 2000, 2040, 72),
+                      (np.float32, 2000, 2040, 100), (np.float32, 3900, 4072, 1056)]
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("dtype,M,N,K", RAGGED_TILE_SHAPES)
+def test_gemm_ragged_edge_tiles(lib, oracle, kind, dtype, M, N, K):
+    """C is a block inside a larger matrix filled with a sentinel: rows past M and columns past N
+    of the edge tiles must not be stored.  The oracle recomputes sampled rows (first, last, some
+    of the last tile row) over all columns."""
+    vec = 16 // np.dtype(dtype).itemsize
+    A, B = U.gen(300 + K, 0, (M, K), dtype, kind), U.gen(300 + K, 1, (K, N), dtype, kind)
+    big = np.full((M + 3, N + 2 * vec), 77.0, dtype=dtype)
+    dC = U.dev(big)
+    view = dC[2:2 + M, vec:vec + N]
+    lib.distal_gemm(U.dev(A), U.dev(B), view)
+    out = U.host(dC)
+    got = out[2:2 + M, vec:vec + N]
+    assert np.all(np.isfinite(got))
+    mask = np.ones_like(big, dtype=bool)
+    mask[2:2 + M, vec:vec + N] = False
+    assert np.all(out[mask] == 77.0)
+    rows = np.sort(np.random.default_rng(K).choice(M, 24, replace=False))
+    rows[0], rows[-1], rows[-2], rows[-3] = 0, M - 1, M - 2, M - 70
+    rows = np.unique(rows)
+    compare(got[rows], oracle.gemm(np.ascontiguousarray(A[rows]), B), dtype, kind, K)
+    # accumulate on top of the product: twice it (exactly so when one pass forms the product: the
+    # trailing terms of K are a second pass, and (P + p) + P + p rounds differently from 2 (P + p)),
+    # and still nothing outside
+    lib.distal_gemm(U.dev(A), U.dev(B), view, accumulate=True)
+    out2 = U.host(dC)
+    if kind == inputs.SMALLINT or K % 32 == 0:
+        assert np.array_equal(out2[2:2 + M, vec:vec + N], got * 2)
+    else:
+        U.assert_close(out2[2:2 + M, vec:vec + N], got.astype(np.float64) * 2, dtype, K)
+    assert np.all(out2[mask] == 77.0)
+
+
 @pytest.mark.parametrize("dtype", DT)
 @pytest.mark.parametrize("kind", KINDS)
 @pytest.mark.parametrize("off", [0, 1, 2, 3])
