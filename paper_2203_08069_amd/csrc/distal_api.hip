@@ -276,8 +276,8 @@ template <typename T, int LT>
 void launch_mode2(const MttkrpMode2Args<T> &a, unsigned nblocks, bool aligned, hipStream_t stream) {
     typedef MttkrpMode2Cfg<T, LT> Cfg;
     const dim3 grid(nblocks), block(Cfg::NT);
-    const bool vec = aligned && a.K % Cfg::KW == 0;
-    if (vec && a.J % Cfg::JB == 0 && a.L % Cfg::BN == 0)
+    const bool vec = aligned && a.K % Cfg::VEC == 0;
+    if (vec && a.K % Cfg::KW == 0 && a.J % Cfg::JB == 0 && a.L % Cfg::BN == 0)
         hipLaunchKernelGGL((mttkrp_mode2_kernel<T, false, false, LT>), grid, block, Cfg::LDS_BYTES, stream, a);
     else if (vec)
         hipLaunchKernelGGL((mttkrp_mode2_kernel<T, false, true, LT>), grid, block, Cfg::LDS_BYTES, stream, a);
@@ -295,7 +295,8 @@ int mttkrp_mode_t(int mode, int64_t I, int64_t J, int64_t K, int64_t L, const T 
     if (!plan.ok) return DISTAL_ERR_SHAPE;
     T *partial = plan.nparts == 1 ? A : static_cast<T *>(workspace);
     const unsigned nblocks = (unsigned)(plan.tasks * plan.nsplit);
-    // the vector kernels need whole, 16-byte aligned k-slices of B; everything else may be ragged
+    // the vector kernels need 16-byte aligned rows of B (an aligned base, K a multiple of the vector);
+    // everything else may be ragged
     const bool aligned = aligned16(B);
     if (mode != 2) {
         typedef MttkrpCfg<T> Cfg;
@@ -309,10 +310,9 @@ int mttkrp_mode_t(int mode, int64_t I, int64_t J, int64_t K, int64_t L, const T 
         a.wsplit = plan.isplit; a.nsplit = (int)plan.nsplit;
         a.nslices = (int)plan.nslices; a.kgroups = (int)plan.kgroups;
         a.tiles_n = (int)plan.tiles_n; a.rblocks = (int)plan.rblocks;
-        const bool vec = aligned && K % Cfg::SL == 0;
-        const int rc = L > 32
-            ? launch_walk<T, 2>(a, nblocks, vec, vec && a.R % Cfg::RB == 0 && L % (2 * Cfg::BN) == 0, stream)
-            : launch_walk<T, 1>(a, nblocks, vec, vec && a.R % Cfg::RB == 0 && L % Cfg::BN == 0, stream);
+        const bool vec = aligned && K % Cfg::VEC == 0, whole = vec && K % Cfg::SL == 0 && a.R % Cfg::RB == 0;
+        const int rc = L > 32 ? launch_walk<T, 2>(a, nblocks, vec, whole && L % (2 * Cfg::BN) == 0, stream)
+                              : launch_walk<T, 1>(a, nblocks, vec, whole && L % Cfg::BN == 0, stream);
         if (rc != DISTAL_OK) return rc;
     } else {
         MttkrpMode2Args<T> a{};

@@ -70,8 +70,9 @@ struct MttkrpPieces {
 };
 
 // RB rows x SL k-values starting at `base` (rows `row_stride` elements apart) -> rs.
-// Unguarded: 16-byte vector loads; needs a whole, aligned k-slice (k_valid >= SL); with RAGGED,
-// rows past rows_valid re-read the last valid row (without it every block must be full).
+// Unguarded: 16-byte vector loads from an aligned base; without RAGGED every block must be full
+// (k_valid >= SL, rows_valid >= RB); with it rows past rows_valid re-read the last valid row and
+// a last k-slice may be short by whole 16-byte pieces.
 // GUARD: rows >= rows_valid and k >= k_valid read as zero, element loads (any alignment).
 template <typename T, bool GUARD, bool RAGGED>
 __device__ __forceinline__ void mttkrp_load_block(
@@ -80,19 +81,22 @@ __device__ __forceinline__ void mttkrp_load_block(
     typedef MttkrpCfg<T> Cfg;
     typedef typename VecOf<T, Cfg::VEC>::type vec_t;
     if constexpr (!GUARD) {
-        if (!RAGGED || rows_valid >= Cfg::RB) {    // wavefront-uniform: a full block
+        if (!RAGGED || (rows_valid >= Cfg::RB && k_valid >= Cfg::SL)) {    // wavefront-uniform: a full block
 #pragma unroll
             for (int p = 0; p < Cfg::PER_T; ++p)  // base + p*RPI rows is wavefront-uniform
                 rs[p] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(
                     base + (int64_t)(p * Cfg::RPI) * row_stride + pc.lane_off));
         } else {
-            // the last, ragged block: rows past the end re-read the last valid row; what they
-            // produce lands in accumulator columns that are never stored
+            // a ragged block: rows past the end re-read the last valid row (what they produce
+            // lands in accumulator columns that are never stored); pieces past the end of a
+            // short last k-slice (k_valid is a multiple of VEC) are zero
 #pragma unroll
             for (int p = 0; p < Cfg::PER_T; ++p) {
                 int64_t jr = pc.prow + p * Cfg::RPI;
                 if (jr >= rows_valid) jr = rows_valid - 1;
-                rs[p] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(base + jr * row_stride + pc.pcol));
+                rs[p] = pc.pcol < k_valid
+                            ? __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(base + jr * row_stride + pc.pcol))
+                            : vec_t(T(0));
             }
         }
     } else {
@@ -166,7 +170,7 @@ __device__ __forceinline__ void mttkrp_load_d(
 #pragma unroll
             for (int t = 0; t < Cfg::KV; ++t) {
                 const int64_t k = k0 + g * Cfg::KG + ls * Cfg::KV + t;
-                d[lb][g][t] = ((!RAGGED || l < L) && (!GUARD || k < K)) ? D[k * L + l] : T(0);
+                d[lb][g][t] = ((!RAGGED || l < L) && ((!GUARD && !RAGGED) || k < K)) ? D[k * L + l] : T(0);
             }
     }
 }
@@ -244,15 +248,16 @@ struct MttkrpWalkArgs {
     int rblocks;       // ceil(R / 32)
 };
 
-// GUARD = false: every k-slice of B is full and 16-byte aligned (K % SL == 0, aligned base):
-// vector loads only.  RAGGED = true then allows any R and L (the last block of r re-reads its
-// last row, columns l >= L carry zero factors, neither is stored); RAGGED = false needs
-// R % 32 == 0 and L % 32 == 0 and keeps the register count at four wavefronts per SIMD.
+// GUARD = false: rows of B are 16-byte aligned (aligned base, K a multiple of the vector):
+// vector loads only.  RAGGED = true then allows any R and L and a short last k-slice (the last
+// block of r re-reads its last row, columns l >= L carry zero factors, neither is stored; pieces
+// and D rows past K are zero); RAGGED = false needs K % SL == 0, R % 32 == 0 and L % 32 == 0
+// and keeps the register count at four wavefronts per SIMD.
 // GUARD = true (with RAGGED): any shape and alignment, element loads with bounds checks.
 // LT = column tiles of 32 per wavefront (1 or 2): with two, a rank above 32 reads B once per 64
 // columns instead of once per 32.
 template <typename T, bool GUARD, bool RAGGED, int LT>
-__global__ void __launch_bounds__(256, GUARD ? 1 : ((sizeof(T) == 4 && LT == 1) ? 3 : 2))
+__global__ void __launch_bounds__(256, GUARD ? 1 : (sizeof(T) == 4 ? 3 : 2))
 mttkrp_walk_kernel(const MttkrpWalkArgs<T> args) {
     typedef MttkrpCfg<T> Cfg;
     typedef Mfma<T> MF;
@@ -389,8 +394,9 @@ struct MttkrpMode2Args {
     int tiles_n;       // ceil(L / (32 * LT))
 };
 
-// GUARD / RAGGED / LT as for the kernel above: without GUARD K % KW == 0 and an aligned base are
-// needed; RAGGED = true allows any J and L, RAGGED = false needs J % 16 == 0 and L % (32 * LT) == 0.
+// GUARD / RAGGED / LT as for the kernel above: without GUARD an aligned base and K % VEC == 0 are
+// needed; RAGGED = true allows any J and L and such K, RAGGED = false needs K % KW == 0,
+// J % 16 == 0 and L % (32 * LT) == 0.
 template <typename T, bool GUARD, bool RAGGED, int LT>
 __global__ void __launch_bounds__(256, GUARD ? 1 : (LT == 1 ? 3 : 2))
 mttkrp_mode2_kernel(const MttkrpMode2Args<T> args) {
@@ -441,16 +447,18 @@ mttkrp_mode2_kernel(const MttkrpMode2Args<T> args) {
         // The lane's piece (g, p) of the block of slice i: row j0 + g*KS + ls, elements
         // k0 + p*MB*VEC + li*VEC ...  The row-group part of the address is wavefront-uniform.
         const int64_t lane_off = (int64_t)ls * K + li * VEC;
-        const bool full_rows = j0 + JB <= J;             // wavefront-uniform
+        const bool full_rows = j0 + JB <= J && k0 + Cfg::KW <= K;   // wavefront-uniform: a full block
         auto piece = [&](int64_t i, int g, int p) -> vec_t {
             const T *base = args.B + ((i * J + j0 + g * MF::KS) * K + k0 + p * MF::MB * VEC);   // uniform
             if constexpr (!GUARD) {
                 if (!RAGGED || full_rows) return __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(base + lane_off));
-                // ragged last block of j: rows past the end re-read row J-1; their D factor is zero
-                int64_t j = j0 + g * MF::KS + ls;
+                // a ragged block: rows of j past the end re-read row J-1 (their D factor is zero);
+                // pieces past the end of a row re-read its last piece (K is a multiple of VEC) and
+                // feed output rows k >= K, which are not stored
+                int64_t j = j0 + g * MF::KS + ls, k = k0 + p * MF::MB * VEC + li * VEC;
                 if (j >= J) j = J - 1;
-                return __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(
-                    args.B + (i * J + j) * K + k0 + p * MF::MB * VEC + li * VEC));
+                if (k > K - VEC) k = K - VEC;
+                return __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(args.B + (i * J + j) * K + k));
             } else {
                 vec_t x;
 #pragma unroll
@@ -532,7 +540,7 @@ mttkrp_mode2_kernel(const MttkrpMode2Args<T> args) {
             for (int v = 0; v < MF::NACC; ++v) {
                 const int64_t k = k0 + p * MF::MB * VEC + MF::out_row(v, lane) * VEC + e;
                 const int64_t l = n0 + cb * MF::NB + li;
-                if ((!RAGGED || l < L) && (!GUARD || k < K))
+                if ((!RAGGED || l < L) && ((!GUARD && !RAGGED) || k < K))
                     args.partial[(k * nparts + part) * L + l] = red[((rb * LB + cb) * MF::NACC + v) * 64 + lane];
             }
     }

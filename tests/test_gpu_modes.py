@@ -232,7 +232,10 @@ MTTKRP_MODE_SHAPES = [(3, 5, 7, 4), (9, 33, 129, 5), (2, 70, 256, 32), (1, 1, 1,
                       # whole aligned k-slices, ragged everything else: the vector kernels' ragged variants
                       (5, 37, 128, 33), (33, 50, 256, 16), (100, 17, 128, 48),
                       # ranks above 32: two column tiles per wavefront, whole (128) and ragged (96)
-                      (6, 64, 128, 128), (5, 37, 128, 96)]
+                      (6, 64, 128, 128), (5, 37, 128, 96),
+                      # K a multiple of the 16-byte vector but not of a k-slice: vector kernels with a short
+                      # last slice (one slice only; several; with two column tiles; binary64 only for 130)
+                      (33, 50, 72, 16), (20, 40, 1000, 32), (12, 20, 132, 40), (6, 10, 1028, 64), (9, 21, 130, 8)]
 
 
 @pytest.mark.parametrize("dtype", DT)
