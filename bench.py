@@ -95,7 +95,8 @@ def main():
                          "extra rows, not part of 'all': summa (k-chunk leaf shapes), "
                          "ttv_f64,innerprod_f64,ttm_f64,mttkrp_f64, ttm_mode0,ttm_mode1 (TTM along the "
                          "other modes of the configs[3] tensor), mttkrp_mode1,mttkrp_mode2 (MTTKRP along the "
-                         "other modes of the configs[4] tensor), mttkrp_rank64, ttv_mode0,ttv_mode1")
+                         "other modes of the configs[4] tensor), mttkrp_rank64, ttv_mode0,ttv_mode1, "
+                         "ttm_rank32 (all three modes at rank 32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB read + 1 GiB write elementwise kernel (torch.add), the known-size "
@@ -360,6 +361,36 @@ def main():
                 r["cpu_baseline"] = {"value": 2.0 * n_s * J * K * R / sec / 1e9, "unit": "GFLOP/s", "cores": cores,
                                      "kind": "oracle", "seconds": sec,
                                      "sample": f"{n_s} of 1024 slices of the output along mode {1 - mode}"}
+                r["sample_normwise_err"] = sample_err(got, ref)
+            del A
+        del B, C
+
+    # ---------------------------------------------------------------- TTM at rank 32 (extra): HBM-bound
+    if "ttm_rank32" in want:
+        I = J = K = 1024
+        R = 32
+        B = device_tensor(3, 0, (I, J, K), np.float32, device=dev)
+        C = device_tensor(3, 1, (K, R), np.float32, device=dev)
+        for mode in (2, 0, 1):
+            shape = [I, J, K]
+            shape[mode] = R
+            A = torch.empty(shape, dtype=torch.float32, device=dev)
+            r = finish(f"ttm_rank32_mode{mode}",
+                       f"TTM along mode {mode}, B {I}x{J}x{K}, C {K}x{R} f32, seed 3 (16 flop/B: HBM-bound)", "f32",
+                       lambda: binding.distal_ttm_mode(mode, B, C, A), 2.0 * I * J * K * R,
+                       4.0 * (I * J * K + K * R + I * J * R), "hbm")
+            if cpu:
+                n_s = 16
+                hC = C.cpu().numpy()
+                if mode == 0:
+                    hB, got = np.ascontiguousarray(B[:, :n_s, :].cpu().numpy()), A[:, :n_s, :].cpu().numpy()
+                else:
+                    hB, got = np.ascontiguousarray(B[:n_s].cpu().numpy()), A[:n_s].cpu().numpy()
+                t0 = time.perf_counter()
+                ref = oracle.ttm_mode(mode, hB, hC)
+                sec = time.perf_counter() - t0
+                r["cpu_baseline"] = {"value": 2.0 * n_s * J * K * R / sec / 1e9, "unit": "GFLOP/s", "cores": cores,
+                                     "kind": "oracle", "seconds": sec, "sample": f"{n_s} of 1024 slices of the output"}
                 r["sample_normwise_err"] = sample_err(got, ref)
             del A
         del B, C

@@ -121,7 +121,10 @@ int launch_fill(T *out, int64_t rows, int64_t cols, int64_t ld, hipStream_t stre
 // those.  Among the shapes a product is deep enough for, the one with the least estimated time
 // wins: tiles per compute unit, a partly filled last round counted in full, x tile area / the
 // kernel's speed relative to the best one (measured at 8192^3: binary64 1, 0.985, 0.915 for
-// 256 x 128, 128 x 128, 64 x 64; binary32 1, 0.973, 0.95, 0.81 from 256 x 256 down).  Whole
+// 256 x 128, 128 x 128, 64 x 64; binary32 1, 0.973, 0.95, 0.81 from 256 x 256 down).  A
+// rank-sized output side (N <= 64, or M <= 64 as the transposed forms of a tensor-times-matrix
+// have it) adds tiles with a 64- or 32-wide short side, which read the large operand once
+// instead of padding the narrow one to 64 (speeds measured on such products at 1024^3).  Whole
 // aligned tiles take the straight-line kernels as they are, ragged M and N their edge-clamping
 // form (the padding is paid for through the tile count), K % 16 trailing terms a second pass;
 // only operands whose 16-byte pieces would straddle an edge (misaligned bases or leading
@@ -166,26 +169,57 @@ int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
         const int64_t t = ((M + bm - 1) / bm) * ((N + bn - 1) / bn) * batch;
         return (double)((t + kComputeUnits - 1) / kComputeUnits) * (double)(bm * bn) / speed;
     };
+    double best = 1e300;
+    int pick = 0;
+    auto consider = [&](int id, bool eligible, int64_t bm, int64_t bn, double speed) {
+        if (!eligible) return;
+        const double c = cost(bm, bn, speed);
+        if (c < best) { best = c; pick = id; }       // earlier candidates win ties
+    };
+    // tiles with a short side only for an output that is that narrow (rank-sized N, or M under TA)
+    const bool n32 = N <= 32, n64 = N <= 64, m32 = M <= 32, m64 = M <= 64;
     if constexpr (sizeof(T) == 4) {
-        const double c64 = cost(64, 64, 0.81), c128 = cost(128, 128, 0.95);
-        const double c256x128 = K >= 512 ? cost(256, 128, 0.973) : 1e300;
         // 32-deep slabs unless they alone would leave trailing terms to a second pass
-        const double c256 = (K >= 1024 && (K % 32 == 0 || K % 16 != 0)) ? cost(256, 256, 1.0) : 1e300;
-        const double best = std::min(std::min(c64, c128), std::min(c256x128, c256));
-        if (c256 == best) {
+        consider(1, K >= 1024 && (K % 32 == 0 || K % 16 != 0), 256, 256, 1.0);
+        consider(2, K >= 512, 256, 128, 0.973);
+        consider(3, true, 128, 128, 0.95);
+        consider(4, true, 64, 64, 0.81);
+        consider(5, n64, 256, 64, 0.885);
+        consider(6, n32 && K >= 32, 256, 32, 0.587);
+        consider(7, m64, 64, 256, 0.889);
+        consider(8, m32 && K >= 32, 32, 256, 0.637);
+        switch (pick) {
+        case 1:
             // a transposed left operand is staged in rows of 256 either way: 16-deep slabs measure 1 % faster
             if constexpr (TA) return launch_tiles<T, 256, 256, 16, 4, 4, TA>(a, batch, stream);
             else return launch_tiles<T, 256, 256, 32, 4, 4, TA>(a, batch, stream);
+        case 2: return launch_tiles<T, 256, 128, 16, 4, 2, TA>(a, batch, stream);
+        case 3: return launch_tiles<T, 128, 128, 16, 2, 2, TA>(a, batch, stream);
+        case 5: return launch_tiles<T, 256, 64, 16, 4, 1, TA>(a, batch, stream);
+        case 6: return launch_tiles<T, 256, 32, 32, 4, 1, TA>(a, batch, stream);
+        case 7: return launch_tiles<T, 64, 256, 16, 1, 4, TA>(a, batch, stream);
+        case 8: return launch_tiles<T, 32, 256, 32, 1, 4, TA>(a, batch, stream);
+        default: break;
         }
-        if (c256x128 == best) return launch_tiles<T, 256, 128, 16, 4, 2, TA>(a, batch, stream);
-        if (c128 == best) return launch_tiles<T, 128, 128, 16, 2, 2, TA>(a, batch, stream);
     } else {
-        const double c64 = cost(64, 64, 0.915), c128 = cost(128, 128, 0.985);
-        const double c256x128 = K >= 4096 ? cost(256, 128, 1.0) : 1e300;
-        const double best = std::min(std::min(c64, c128), c256x128);
-        if (c256x128 == best) return launch_tiles<T, 256, 128, 16, 8, 2, TA>(a, batch, stream);
-        if (c128 == best) return launch_tiles<T, 128, 128, 16, 4, 2, TA>(a, batch, stream);
+        consider(2, K >= 4096, 256, 128, 1.0);
+        consider(3, true, 128, 128, 0.985);
+        consider(4, true, 64, 64, 0.915);
+        consider(5, n64, 128, 64, 0.94);
+        consider(6, n32, 128, 32, 0.697);
+        consider(7, m64, 64, 128, 0.95);
+        consider(8, m32, 32, 256, 0.617);
+        switch (pick) {
+        case 2: return launch_tiles<T, 256, 128, 16, 8, 2, TA>(a, batch, stream);
+        case 3: return launch_tiles<T, 128, 128, 16, 4, 2, TA>(a, batch, stream);
+        case 5: return launch_tiles<T, 128, 64, 16, 4, 1, TA>(a, batch, stream);
+        case 6: return launch_tiles<T, 128, 32, 16, 4, 1, TA>(a, batch, stream);
+        case 7: return launch_tiles<T, 64, 128, 16, 2, 2, TA>(a, batch, stream);
+        case 8: return launch_tiles<T, 32, 256, 16, 1, 4, TA>(a, batch, stream);
+        default: break;
+        }
     }
+    // too few larger tiles to give every CU one: quarter-size tiles, four times the workgroups
     return launch_tiles<T, 64, 64, 16, 2, 2, TA>(a, batch, stream);
 }
 

@@ -124,6 +124,25 @@ def test_ttm_mode0_ragged_edge_tiles(lib, oracle, dtype, kind, I, J, K, R):
         compare(got[:, j:j + 1, :], oracle.ttm_mode(0, np.ascontiguousarray(B[:, j:j + 1, :]), C), dtype, kind, I)
 
 
+# (mode, I, J, K, R) with a rank-sized R and enough of the other side to fill the part: the tiles with a
+# 32- or 64-wide short side (N side for mode 2, M side under a transposed left operand for modes 0
+# and 1, there also as a batch), whole and in their edge-clamping form, with trailing K terms
+NARROW_TTM = [(2, 256, 256, 64, 32), (2, 256, 255, 72, 24), (2, 256, 256, 64, 64),
+              (0, 64, 256, 256, 32), (0, 60, 250, 260, 24), (0, 64, 256, 256, 64),
+              (1, 128, 64, 512, 32), (1, 256, 72, 256, 64)]
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("mode,I,J,K,R", NARROW_TTM)
+def test_ttm_mode_narrow_rank_tiles(lib, oracle, dtype, kind, mode, I, J, K, R):
+    shape = (I, J, K)
+    B, C = U.gen(48, 0, shape, dtype, kind), U.gen(48, 1, (shape[mode], R), dtype, kind)
+    A = empty(out_shape(shape, mode, R), dtype)
+    lib.distal_ttm_mode(mode, U.dev(B), U.dev(C), A)
+    compare(U.host(A), oracle.ttm_mode(mode, B, C), dtype, kind, shape[mode])
+
+
 @pytest.mark.parametrize("dtype", DT)
 def test_ttm_mode0_k_chunk_tiles(lib, oracle, dtype):
     """mode 0 with a contracted extent of 512 and 256 tiles of 256 x 128 (the binary32 k-chunk
