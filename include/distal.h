@@ -156,6 +156,17 @@ int distal_innerprod(distal_dtype dt, int64_t I, int64_t J, int64_t K,
                      const void *B, const void *C, void *a,
                      void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Host-only query (no device work): the tile BM x BN and slab depth BK the library uses for
+ * C = A * B with these extents when the operands are 16-byte aligned (K >= 16, N and the
+ * leading dimensions multiples of 16 bytes; other operands take the bounds-checked 128 x 128
+ * kernel whatever this returns).  TTM is such a product: mode 2 is M = I*J, N = L; mode 0 is
+ * transposed_left with M = R, N = J*K, K = I; mode 1 the same with batch = I, N = K, K = J.
+ * The choice is a function of the arguments only, never of the device.  Returns a status.
+ */
+int distal_gemm_tile(distal_dtype dt, int transposed_left, int64_t M, int64_t N, int64_t K, int64_t batch,
+                     int *bm, int *bn, int *bk);
+
 /* Scratch sizes for the calls that take a workspace (0 for invalid arguments). */
 size_t distal_mttkrp_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L);
 size_t distal_mttkrp_mode_workspace_bytes(distal_dtype dt, int mode, int64_t I, int64_t J, int64_t K,

@@ -26,7 +26,7 @@ STATUS_NAMES = {
 EXPORTS = (
     "distal_gemm", "distal_ttm", "distal_mttkrp", "distal_ttv", "distal_innerprod",
     "distal_ttv_mode", "distal_ttm_mode", "distal_mttkrp_mode", "distal_mttkrp_mode_workspace_bytes",
-    "distal_mttkrp_workspace_bytes", "distal_innerprod_workspace_bytes",
+    "distal_mttkrp_workspace_bytes", "distal_innerprod_workspace_bytes", "distal_gemm_tile",
     "distal_status_string", "distal_version",
 )
 
@@ -67,6 +67,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.distal_innerprod_workspace_bytes.argtypes = [ci, i64, i64, i64]
     lib.distal_status_string.argtypes = [ci]
     lib.distal_version.argtypes = []
+    ip = ctypes.POINTER(ctypes.c_int)
+    lib.distal_gemm_tile.argtypes = [ci, ci, i64, i64, i64, i64, ip, ip, ip]
+    lib.distal_gemm_tile.restype = ci
     for name in ("distal_gemm", "distal_ttm", "distal_mttkrp", "distal_ttv", "distal_innerprod",
                  "distal_ttm_mode", "distal_mttkrp_mode", "distal_version"):
         getattr(lib, name).restype = ci
@@ -282,6 +285,15 @@ def distal_ttv_mode(mode, B, c, A):
         rc = load_library().distal_ttv_mode(dt, mode, I, J, K, _ptr(B), _ptr(c), _ptr(A), _stream(B))
     _raise(rc, "distal_ttv_mode")
     return A
+
+
+def gemm_tile(dtype_code: int, transposed_left: bool, M: int, N: int, K: int, batch: int = 1):
+    """(BM, BN, BK) the library uses for an aligned M x N x K product (host-only query)."""
+    bm, bn, bk = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    rc = load_library().distal_gemm_tile(dtype_code, int(bool(transposed_left)), M, N, K, batch,
+                                         ctypes.byref(bm), ctypes.byref(bn), ctypes.byref(bk))
+    _raise(rc, "distal_gemm_tile")
+    return bm.value, bn.value, bk.value
 
 
 def innerprod_workspace_bytes(dtype_code: int, I: int, J: int, K: int) -> int:

@@ -130,6 +130,45 @@ int launch_fill(T *out, int64_t rows, int64_t cols, int64_t ld, hipStream_t stre
 // only operands whose 16-byte pieces would straddle an edge (misaligned bases or leading
 // dimensions, N not a multiple of the vector) take the guarded 128 x 128 kernel.
 
+struct TilePick { int id, bm, bn, bk; };
+
+// The tile the straight-line kernels use for a product whose operands allow them (see above).
+// Estimated time of a tile shape: tiles per compute unit (256 of them, the last round of a grid
+// counts in full) x tile area / measured relative speed of that kernel; ragged shapes pay for
+// their padding and for a partly filled last round through the same count.
+TilePick pick_tile(bool f64, bool ta, int64_t M, int64_t N, int64_t K, int64_t batch) {
+    double best = 1e300;
+    TilePick pick{4, 64, 64, 16};
+    auto consider = [&](int id, bool eligible, int bm, int bn, int bk, double speed) {
+        if (!eligible) return;
+        const int64_t t = ((M + bm - 1) / bm) * ((N + bn - 1) / bn) * batch;
+        const double c = (double)((t + kComputeUnits - 1) / kComputeUnits) * (double)(bm * bn) / speed;
+        if (c < best) { best = c; pick = TilePick{id, bm, bn, bk}; }     // earlier candidates win ties
+    };
+    // tiles with a short side only for an output that is that narrow (rank-sized N, or M under TA)
+    const bool n32 = N <= 32, n64 = N <= 64, m32 = M <= 32, m64 = M <= 64;
+    if (!f64) {
+        // 32-deep slabs unless they alone would leave trailing terms to a second pass
+        consider(1, K >= 1024 && (K % 32 == 0 || K % 16 != 0), 256, 256, ta ? 16 : 32, 1.0);
+        consider(2, K >= 512, 256, 128, 16, 0.973);
+        consider(3, true, 128, 128, 16, 0.95);
+        consider(4, true, 64, 64, 16, 0.81);
+        consider(5, n64, 256, 64, 16, 0.885);
+        consider(6, n32 && K >= 32, 256, 32, 32, 0.587);
+        consider(7, m64, 64, 256, 16, 0.889);
+        consider(8, m32 && K >= 32, 32, 256, 32, 0.637);
+    } else {
+        consider(2, K >= 4096, 256, 128, 16, 1.0);
+        consider(3, true, 128, 128, 16, 0.985);
+        consider(4, true, 64, 64, 16, 0.915);
+        consider(5, n64, 128, 64, 16, 0.94);
+        consider(6, n32, 128, 32, 16, 0.697);
+        consider(7, m64, 64, 128, 16, 0.95);
+        consider(8, m32, 32, 256, 16, 0.617);
+    }
+    return pick;
+}
+
 // TA = false: C = [C +] A * B with A stored M x K.  TA = true: the left operand is stored
 // K x M (C = [C +] At^T * B), the form a contraction over a non-last tensor mode takes.
 // `batch` independent problems, operand p of problem n at p + n * stride_p (elements).
@@ -162,62 +201,33 @@ int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
     // the straight-line kernels need 16-byte pieces that never straddle an edge of an operand
     const bool pieces = a.a_vec_ok && a.b_vec_ok && a.c_vec_ok && N % VEC == 0 && (!TA || M % VEC == 0);
     if (!pieces || K < 16) return launch_contract<T, 128, 128, 16, 2, 2, kGuarded, TA>(a, batch, stream);
-    // Estimated time of a tile shape: tiles per compute unit (256 of them, the last round of a
-    // grid counts in full) x tile area / measured relative speed of that kernel.  Ragged shapes
-    // pay for their padding and for a partly filled last round through the same count.
-    auto cost = [&](int64_t bm, int64_t bn, double speed) {
-        const int64_t t = ((M + bm - 1) / bm) * ((N + bn - 1) / bn) * batch;
-        return (double)((t + kComputeUnits - 1) / kComputeUnits) * (double)(bm * bn) / speed;
-    };
-    double best = 1e300;
-    int pick = 0;
-    auto consider = [&](int id, bool eligible, int64_t bm, int64_t bn, double speed) {
-        if (!eligible) return;
-        const double c = cost(bm, bn, speed);
-        if (c < best) { best = c; pick = id; }       // earlier candidates win ties
-    };
-    // tiles with a short side only for an output that is that narrow (rank-sized N, or M under TA)
-    const bool n32 = N <= 32, n64 = N <= 64, m32 = M <= 32, m64 = M <= 64;
-    if constexpr (sizeof(T) == 4) {
-        // 32-deep slabs unless they alone would leave trailing terms to a second pass
-        consider(1, K >= 1024 && (K % 32 == 0 || K % 16 != 0), 256, 256, 1.0);
-        consider(2, K >= 512, 256, 128, 0.973);
-        consider(3, true, 128, 128, 0.95);
-        consider(4, true, 64, 64, 0.81);
-        consider(5, n64, 256, 64, 0.885);
-        consider(6, n32 && K >= 32, 256, 32, 0.587);
-        consider(7, m64, 64, 256, 0.889);
-        consider(8, m32 && K >= 32, 32, 256, 0.637);
-        switch (pick) {
-        case 1:
-            // a transposed left operand is staged in rows of 256 either way: 16-deep slabs measure 1 % faster
+    switch (pick_tile(sizeof(T) == 8, TA, M, N, K, batch).id) {
+    case 1:
+        // a transposed left operand is staged in rows of 256 either way: 16-deep slabs measure 1 % faster
+        if constexpr (sizeof(T) == 4) {
             if constexpr (TA) return launch_tiles<T, 256, 256, 16, 4, 4, TA>(a, batch, stream);
             else return launch_tiles<T, 256, 256, 32, 4, 4, TA>(a, batch, stream);
-        case 2: return launch_tiles<T, 256, 128, 16, 4, 2, TA>(a, batch, stream);
-        case 3: return launch_tiles<T, 128, 128, 16, 2, 2, TA>(a, batch, stream);
-        case 5: return launch_tiles<T, 256, 64, 16, 4, 1, TA>(a, batch, stream);
-        case 6: return launch_tiles<T, 256, 32, 32, 4, 1, TA>(a, batch, stream);
-        case 7: return launch_tiles<T, 64, 256, 16, 1, 4, TA>(a, batch, stream);
-        case 8: return launch_tiles<T, 32, 256, 32, 1, 4, TA>(a, batch, stream);
-        default: break;
         }
-    } else {
-        consider(2, K >= 4096, 256, 128, 1.0);
-        consider(3, true, 128, 128, 0.985);
-        consider(4, true, 64, 64, 0.915);
-        consider(5, n64, 128, 64, 0.94);
-        consider(6, n32, 128, 32, 0.697);
-        consider(7, m64, 64, 128, 0.95);
-        consider(8, m32, 32, 256, 0.617);
-        switch (pick) {
-        case 2: return launch_tiles<T, 256, 128, 16, 8, 2, TA>(a, batch, stream);
-        case 3: return launch_tiles<T, 128, 128, 16, 4, 2, TA>(a, batch, stream);
-        case 5: return launch_tiles<T, 128, 64, 16, 4, 1, TA>(a, batch, stream);
-        case 6: return launch_tiles<T, 128, 32, 16, 4, 1, TA>(a, batch, stream);
-        case 7: return launch_tiles<T, 64, 128, 16, 2, 2, TA>(a, batch, stream);
-        case 8: return launch_tiles<T, 32, 256, 16, 1, 4, TA>(a, batch, stream);
-        default: break;
-        }
+        break;
+    case 2:
+        if constexpr (sizeof(T) == 4) return launch_tiles<T, 256, 128, 16, 4, 2, TA>(a, batch, stream);
+        else return launch_tiles<T, 256, 128, 16, 8, 2, TA>(a, batch, stream);
+    case 3:
+        if constexpr (sizeof(T) == 4) return launch_tiles<T, 128, 128, 16, 2, 2, TA>(a, batch, stream);
+        else return launch_tiles<T, 128, 128, 16, 4, 2, TA>(a, batch, stream);
+    case 5:
+        if constexpr (sizeof(T) == 4) return launch_tiles<T, 256, 64, 16, 4, 1, TA>(a, batch, stream);
+        else return launch_tiles<T, 128, 64, 16, 4, 1, TA>(a, batch, stream);
+    case 6:
+        if constexpr (sizeof(T) == 4) return launch_tiles<T, 256, 32, 32, 4, 1, TA>(a, batch, stream);
+        else return launch_tiles<T, 128, 32, 16, 4, 1, TA>(a, batch, stream);
+    case 7:
+        if constexpr (sizeof(T) == 4) return launch_tiles<T, 64, 256, 16, 1, 4, TA>(a, batch, stream);
+        else return launch_tiles<T, 64, 128, 16, 2, 2, TA>(a, batch, stream);
+    case 8:
+        if constexpr (sizeof(T) == 4) return launch_tiles<T, 32, 256, 32, 1, 4, TA>(a, batch, stream);
+        else return launch_tiles<T, 32, 256, 16, 1, 4, TA>(a, batch, stream);
+    default: break;
     }
     // too few larger tiles to give every CU one: quarter-size tiles, four times the workgroups
     return launch_tiles<T, 64, 64, 16, 2, 2, TA>(a, batch, stream);
@@ -642,6 +652,19 @@ int distal_ttv(distal_dtype dt, int64_t I, int64_t J, int64_t K, const void *B, 
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (dt == DISTAL_F64) return ttv_t<double>(rows, K, (const double *)B, (const double *)c, (double *)A, s);
     return ttv_t<float>(rows, K, (const float *)B, (const float *)c, (float *)A, s);
+}
+
+int distal_gemm_tile(distal_dtype dt, int transposed_left, int64_t M, int64_t N, int64_t K, int64_t batch,
+                     int *bm, int *bn, int *bk) {
+    if (check_dtype(dt) != DISTAL_OK) return DISTAL_ERR_DTYPE;
+    if (M <= 0 || N <= 0 || K <= 0 || batch <= 0) return DISTAL_ERR_SHAPE;
+    if (!bm || !bn || !bk) return DISTAL_ERR_NULL;
+    int64_t tiles;
+    if (!mul_ok((M + 127) / 128, (N + 127) / 128, &tiles) || tiles > std::numeric_limits<int>::max())
+        return DISTAL_ERR_SHAPE;
+    const TilePick t = pick_tile(dt == DISTAL_F64, transposed_left != 0, M, N, K, batch);
+    *bm = t.bm; *bn = t.bn; *bk = t.bk;
+    return DISTAL_OK;
 }
 
 size_t distal_innerprod_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, int64_t K) {

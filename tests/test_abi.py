@@ -187,3 +187,44 @@ def test_mttkrp_mode_argument_errors(lib):
     assert m(0, 1, 10, 32, 64, 32, a, b, c, d, None, 0, None) == 6
     assert m(0, 1, 10, 32, 64, 32, a, b, c, d, w, need1 - 1, None) == 6
     assert m(0, 2, 10, 32, 128, 32, a, b, c, d, P(FAKE + 8), need2, None) == 6
+
+
+def test_gemm_tile_choice(lib):
+    """The host-side tile choice for the shapes the benchmark rows and the schedules issue, for
+    narrow rank-sized outputs, ragged shapes (padding and the last round of tiles count) and
+    small problems; and its argument checks."""
+    from paper_2203_08069_amd import binding
+    F32, F64 = 0, 1
+    tile = binding.gemm_tile
+    # headline and fp32 GEMM (BASELINE configs[1]), TTM (configs[3]) along modes 2, 0, 1
+    assert tile(F64, False, 8192, 8192, 8192) == (256, 128, 16)
+    assert tile(F32, False, 8192, 8192, 8192) == (256, 256, 32)
+    assert tile(F32, False, 1 << 20, 256, 1024) == (256, 256, 32)
+    assert tile(F32, True, 256, 1 << 20, 1024) == (256, 256, 16)
+    assert tile(F32, True, 256, 1024, 1024, batch=1024) == (256, 256, 16)
+    assert tile(F64, False, 1 << 20, 256, 1024) == (128, 128, 16)
+    # SUMMA k-chunks: shallow products take the smaller tiles
+    for K in (256, 512, 1024, 2048):
+        assert tile(F64, False, 8192, 8192, K) == (128, 128, 16)
+    assert tile(F32, False, 8192, 8192, 512) == (256, 128, 16)
+    assert tile(F32, False, 8192, 8192, 256) == (128, 128, 16)
+    assert tile(F32, False, 8192, 8192, 1040) == (256, 128, 16)     # K % 32 == 16: no second pass with 16-deep slabs
+    # rank-sized outputs: a 32- or 64-wide short side on the narrow operand's side
+    assert tile(F32, False, 1 << 20, 32, 1024) == (256, 32, 32)
+    assert tile(F32, False, 1 << 20, 64, 1024) == (256, 64, 16)
+    assert tile(F32, True, 32, 1 << 20, 1024) == (32, 256, 32)
+    assert tile(F64, False, 1 << 19, 16, 1024) == (128, 32, 16)
+    assert tile(F64, True, 64, 1 << 19, 1024) == (64, 128, 16)
+    # ragged: 8200 rows are 8.25 rounds of 256 x 128 tiles but 16.25 of 128 x 128
+    assert tile(F64, False, 8200, 8192, 8192) == (128, 128, 16)
+    assert tile(F64, False, 8000, 8000, 8000) == (256, 128, 16)
+    assert tile(F64, False, 3000, 3000, 3000) == (64, 64, 16)
+    # small problems: quarter-size tiles
+    assert tile(F32, False, 1024, 1024, 1024) == (64, 64, 16)
+    assert tile(F64, False, 300, 200, 100) == (64, 64, 16)
+    bm, bn, bk = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    refs = (ctypes.byref(bm), ctypes.byref(bn), ctypes.byref(bk))
+    assert lib.distal_gemm_tile(7, 0, 8, 8, 8, 1, *refs) == 3
+    assert lib.distal_gemm_tile(0, 0, 0, 8, 8, 1, *refs) == 2
+    assert lib.distal_gemm_tile(0, 0, 8, 8, 8, 0, *refs) == 2
+    assert lib.distal_gemm_tile(0, 0, 8, 8, 8, 1, None, None, None) == 1
