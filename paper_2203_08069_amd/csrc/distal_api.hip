@@ -53,7 +53,7 @@ constexpr int64_t kMaxGridY = 65535;
 
 // One launch per run of at most kMaxGridY problems of the batch (blockIdx.y picks the problem).
 // KIND: the guarded kernel, the straight-line kernel on whole tiles, or its edge-clamping form.
-enum { kGuarded = 0, kWhole = 1, kEdge = 2 };
+enum { kGuarded = 0, kWhole = 1, kEdge = 2, kEdgeK = 3 };
 template <typename T, int BM, int BN, int BK, int WM, int WN, int KIND, bool TA>
 int launch_contract(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
     typedef ContractCfg<T, BM, BN, BK, WM, WN, TA> Cfg;
@@ -69,7 +69,7 @@ int launch_contract(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
             if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
             hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
         } else {
-            auto kern = contract_fast_kernel<T, BM, BN, BK, WM, WN, TA, KIND == kEdge>;
+            auto kern = contract_fast_kernel<T, BM, BN, BK, WM, WN, TA, KIND == kEdgeK ? 2 : (KIND == kEdge ? 1 : 0)>;
             if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
             hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
         }
@@ -82,19 +82,23 @@ int launch_contract(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
 }
 
 // The straight-line kernel with BM x BN x BK tiles on operands whose 16-byte pieces never
-// straddle an edge: whole tiles as they are, ragged M or N through the edge-clamping form, and
-// the K % BK trailing terms added by a second, guarded pass over C (K >= BK).
+// straddle an edge (K >= BK): whole tiles as they are, ragged M or N through the edge-clamping
+// form, K % BK trailing terms as that form's extra slab - or, where pieces of A would straddle
+// the end of K (no TA, K not a multiple of the vector), by a second, guarded pass over C.
 template <typename T, int BM, int BN, int BK, int WM, int WN, bool TA>
 int launch_tiles(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
+    constexpr int VEC = 16 / (int)sizeof(T);
     const int64_t k_main = a.K / BK * BK, k_tail = a.K - k_main;
+    if (k_tail == 0)
+        return (a.M % BM == 0 && a.N % BN == 0) ? launch_contract<T, BM, BN, BK, WM, WN, kWhole, TA>(a, batch, stream)
+                                                : launch_contract<T, BM, BN, BK, WM, WN, kEdge, TA>(a, batch, stream);
+    if (TA || a.K % VEC == 0) return launch_contract<T, BM, BN, BK, WM, WN, kEdgeK, TA>(a, batch, stream);
     ContractArgs<T> m = a;
     m.K = k_main;
-    const int rc = (a.M % BM == 0 && a.N % BN == 0)
-                       ? launch_contract<T, BM, BN, BK, WM, WN, kWhole, TA>(m, batch, stream)
-                       : launch_contract<T, BM, BN, BK, WM, WN, kEdge, TA>(m, batch, stream);
-    if (rc != DISTAL_OK || k_tail == 0) return rc;
+    const int rc = launch_contract<T, BM, BN, BK, WM, WN, kEdge, TA>(m, batch, stream);
+    if (rc != DISTAL_OK) return rc;
     ContractArgs<T> t = a;                       // k_main is a multiple of 16: alignment is unchanged
-    t.A += TA ? k_main * a.lda : k_main;
+    t.A += k_main;
     t.B += k_main * a.ldb;
     t.K = k_tail;
     t.accumulate = 1;
@@ -126,7 +130,8 @@ int launch_fill(T *out, int64_t rows, int64_t cols, int64_t ld, hipStream_t stre
 // have it) adds tiles with a 64- or 32-wide short side, which read the large operand once
 // instead of padding the narrow one to 64 (speeds measured on such products at 1024^3).  Whole
 // aligned tiles take the straight-line kernels as they are, ragged M and N their edge-clamping
-// form (the padding is paid for through the tile count), K % 16 trailing terms a second pass;
+// form (the padding is paid for through the tile count), with one more zero-filled slab for
+// K % BK trailing terms;
 // only operands whose 16-byte pieces would straddle an edge (misaligned bases or leading
 // dimensions, N not a multiple of the vector) take the guarded 128 x 128 kernel.
 
@@ -148,8 +153,7 @@ TilePick pick_tile(bool f64, bool ta, int64_t M, int64_t N, int64_t K, int64_t b
     // tiles with a short side only for an output that is that narrow (rank-sized N, or M under TA)
     const bool n32 = N <= 32, n64 = N <= 64, m32 = M <= 32, m64 = M <= 64;
     if (!f64) {
-        // 32-deep slabs unless they alone would leave trailing terms to a second pass
-        consider(1, K >= 1024 && (K % 32 == 0 || K % 16 != 0), 256, 256, ta ? 16 : 32, 1.0);
+        consider(1, K >= 1024, 256, 256, ta ? 16 : 32, 1.0);
         consider(2, K >= 512, 256, 128, 16, 0.973);
         consider(3, true, 128, 128, 16, 0.95);
         consider(4, true, 64, 64, 16, 0.81);

@@ -417,9 +417,11 @@ contract_kernel(ContractArgs<T> args) {
 // row) instead, so every load stays in bounds and the rows and columns it feeds hold values
 // that no valid output depends on; the epilogue stores only what lies inside M x N.
 // Pieces must not straddle an edge: N (and M, when TA) a multiple of the 16-byte vector.
-// K is a multiple of BK in both forms.
+// EDGE = 2 also takes K >= BK that is not a multiple of BK (without TA: a multiple of the
+// vector, pieces of A run along k): the trailing terms are one zero-filled slab after the loop.
+// In the other forms K is a multiple of BK.
 // ---------------------------------------------------------------------------
-template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TA = false, bool EDGE = false>
+template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TA = false, int EDGE = 0>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 4 : 2)
 contract_fast_kernel(ContractArgs<T> args) {
     typedef ContractCfg<T, BM, BN, BK, WAVES_M, WAVES_N, TA> Cfg;
@@ -518,6 +520,30 @@ contract_fast_kernel(ContractArgs<T> args) {
         load_global(t + 2);
         mfma_groups<T, Cfg, (NKG + 1) / 2, NKG>(st + a_rd, st + b_rd, acc);
         __syncthreads();
+    }
+
+    if constexpr (EDGE == 2) {
+        // the K % BK trailing terms: one more slab whose pieces past K are zero, staged after
+        // the loop's last barrier (both buffers are free then) and multiplied in full
+        const int tail = (int)(args.K - nk * BK);            // block-uniform
+        if (tail > 0) {
+            const T *ap = args.A + (TA ? nk * BK * args.lda : nk * BK);
+            const T *bp = args.B + nk * BK * args.ldb;
+#pragma unroll
+            for (int p = 0; p < Cfg::A_PER_T; ++p) {
+                const int v = tid + p * NT, r = v / ARL, kv = v % ARL;
+                const bool valid = TA ? r < tail : kv * VEC < tail;
+                ra[p] = valid ? *reinterpret_cast<const vec_t *>(ap + a_off[p]) : vec_t(T(0));
+            }
+#pragma unroll
+            for (int p = 0; p < Cfg::B_PER_T; ++p) {
+                const int r = (tid + p * NT) / (BN / VEC);
+                rb[p] = r < tail ? *reinterpret_cast<const vec_t *>(bp + b_off[p]) : vec_t(T(0));
+            }
+            store_lds(0);
+            __syncthreads();
+            mfma_groups<T, Cfg, 0, NKG>(lds + a_rd, lds + b_rd, acc);
+        }
     }
 
     // epilogue: accumulators -> C, CV neighbouring columns per store
