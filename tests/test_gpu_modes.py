@@ -49,7 +49,10 @@ def out_shape(shape, mode, R):
 # matrix form (mode 0: R x JK over I; mode 1: per i, R x K over J)
 TTM_MODE_SHAPES = [(3, 5, 7, 4), (17, 9, 33, 130), (32, 8, 32, 128), (130, 3, 44, 5), (1, 1, 1, 1),
                    (5, 40, 3, 1), (16, 128, 128, 128), (48, 2, 64, 256), (2, 19, 520, 36),
-                   (70000, 2, 4, 3)]           # mode 1: more problems in the batch than one grid dimension holds
+                   (70000, 2, 4, 3),           # mode 1: more problems in the batch than one grid dimension holds
+                   # aligned pieces with a contracted extent that leaves trailing terms (37 is no multiple
+                   # of the vector either: fine under a transposed left operand, a second pass along mode 2)
+                   (37, 12, 20, 8), (21, 16, 24, 12), (8, 6, 37, 8)]
 
 
 @pytest.mark.parametrize("dtype", DT)

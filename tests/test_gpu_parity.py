@@ -142,6 +142,19 @@ def test_gemm_strided_views_accumulate(lib, oracle, dtype, kind, off):
 
 
 @pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("M,N,K", [(300, 200, 101), (520, 264, 1029), (64, 64, 17)])
+def test_gemm_k_not_a_multiple_of_the_vector(lib, oracle, dtype, kind, M, N, K):
+    """A is the leading K columns of a wider, aligned matrix: its 16-byte pieces would straddle the
+    end of K, so the trailing terms are a second pass that accumulates into C; with accumulate."""
+    wide = U.gen(9, 0, (M, K + 7 - (K + 7) % 4 + 4), dtype, kind)
+    B, C0 = U.gen(9, 1, (K, N), dtype, kind), U.gen(9, 2, (M, N), dtype, kind)
+    dC = U.dev(C0)
+    lib.distal_gemm(U.dev(wide)[:, :K], U.dev(B), dC, accumulate=True)
+    compare(U.host(dC), oracle.gemm(np.ascontiguousarray(wide[:, :K]), B, init=C0), dtype, kind, K + 1)
+
+
+@pytest.mark.parametrize("dtype", DT)
 def test_gemm_identity_returns_input(lib, dtype):
     A = U.gen(8, 0, (200, 136), dtype)
     C = empty((200, 136), dtype)
