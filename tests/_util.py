@@ -34,6 +34,20 @@ def assert_close(got, ref, dtype, reduction_length):
     assert e <= tol(dtype, reduction_length), f"normwise error {e:.3e} > {tol(dtype, reduction_length):.3e}"
 
 
+def assert_componentwise(got, ref, absref, dtype, nterms):
+    """Every element within the worst-case bound of floating-point summation in ANY order:
+    |got - ref| <= (n + 8) u * sum|terms|, u the unit roundoff of dtype, n the number of terms
+    (gamma_n of the standard analysis; the 8 covers the extra roundings of three-factor terms and
+    of partial results).  absref = the same expression evaluated by the oracle on |inputs|."""
+    got, ref = np.asarray(got, dtype=np.float64), np.asarray(ref, dtype=np.float64)
+    absref = np.asarray(absref, dtype=np.float64)
+    assert got.shape == ref.shape == absref.shape
+    u = 2.0 ** -53 if np.dtype(dtype) == np.float64 else 2.0 ** -24
+    bound = (int(nterms) + 8) * u * absref
+    bad = np.abs(got - ref) > bound
+    assert not bad.any(), f"{int(bad.sum())} of {got.size} elements exceed the componentwise bound"
+
+
 def assert_exact(got, ref):
     """Integer-valued inputs: every partial sum is exact, so the match is bit for bit
     (+0 and -0 compare equal: the sign of an exact zero depends on summation order)."""
