@@ -157,15 +157,21 @@ int distal_innerprod(distal_dtype dt, int64_t I, int64_t J, int64_t K,
                      void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Host-only query (no device work): the tile BM x BN and slab depth BK the library uses for
- * C = A * B with these extents when the operands are 16-byte aligned (K >= 16, N and the
- * leading dimensions multiples of 16 bytes; other operands take the bounds-checked 128 x 128
- * kernel whatever this returns).  TTM is such a product: mode 2 is M = I*J, N = L; mode 0 is
- * transposed_left with M = R, N = J*K, K = I; mode 1 the same with batch = I, N = K, K = J.
- * The choice is a function of the arguments only, never of the device.  Returns a status.
+ * Host-only query (no device work): how the library runs C = A * B with these extents when the
+ * operands are 16-byte aligned (K >= 16, N and the leading dimensions multiples of 16 bytes;
+ * other operands take the bounds-checked 128 x 128 kernel whatever this returns).  TTM is such a
+ * product: mode 2 is M = I*J, N = L; mode 0 is transposed_left with M = R, N = J*K, K = I;
+ * mode 1 the same with batch = I, N = K, K = J.
+ *   tile      = {BM, BN, BK}: tile and slab depth of the (first) launch
+ *   split     = 0: one launch.  1: rows [0, cut) of C with `tile`, rows [cut, M) in a second
+ *               launch with rest_tile.  2: the same along columns, [0, cut) and [cut, N).
+ *               A product whose tiles would end in a thin last round of the compute units is
+ *               split so that the first launch is whole rounds and the rest runs on small tiles.
+ *   rest_tile = {BM, BN, BK} of the second launch, zeros when split == 0.
+ * The plan is a function of the arguments only, never of the device.  Returns a status.
  */
-int distal_gemm_tile(distal_dtype dt, int transposed_left, int64_t M, int64_t N, int64_t K, int64_t batch,
-                     int *bm, int *bn, int *bk);
+int distal_gemm_plan(distal_dtype dt, int transposed_left, int64_t M, int64_t N, int64_t K, int64_t batch,
+                     int tile[3], int *split, int64_t *cut, int rest_tile[3]);
 
 /* Scratch sizes for the calls that take a workspace (0 for invalid arguments). */
 size_t distal_mttkrp_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L);

@@ -26,7 +26,7 @@ STATUS_NAMES = {
 EXPORTS = (
     "distal_gemm", "distal_ttm", "distal_mttkrp", "distal_ttv", "distal_innerprod",
     "distal_ttv_mode", "distal_ttm_mode", "distal_mttkrp_mode", "distal_mttkrp_mode_workspace_bytes",
-    "distal_mttkrp_workspace_bytes", "distal_innerprod_workspace_bytes", "distal_gemm_tile",
+    "distal_mttkrp_workspace_bytes", "distal_innerprod_workspace_bytes", "distal_gemm_plan",
     "distal_status_string", "distal_version",
 )
 
@@ -68,8 +68,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.distal_status_string.argtypes = [ci]
     lib.distal_version.argtypes = []
     ip = ctypes.POINTER(ctypes.c_int)
-    lib.distal_gemm_tile.argtypes = [ci, ci, i64, i64, i64, i64, ip, ip, ip]
-    lib.distal_gemm_tile.restype = ci
+    lib.distal_gemm_plan.argtypes = [ci, ci, i64, i64, i64, i64, ip, ip, ctypes.POINTER(ctypes.c_int64), ip]
+    lib.distal_gemm_plan.restype = ci
     for name in ("distal_gemm", "distal_ttm", "distal_mttkrp", "distal_ttv", "distal_innerprod",
                  "distal_ttm_mode", "distal_mttkrp_mode", "distal_version"):
         getattr(lib, name).restype = ci
@@ -287,13 +287,21 @@ def distal_ttv_mode(mode, B, c, A):
     return A
 
 
+def gemm_plan(dtype_code: int, transposed_left: bool, M: int, N: int, K: int, batch: int = 1):
+    """How the library runs an aligned M x N x K product (host-only query):
+    ((BM, BN, BK), split, cut, (BM, BN, BK) of the second launch); split 0 = one launch,
+    1 = rows [0, cut) then [cut, M), 2 = columns [0, cut) then [cut, N)."""
+    tile, rest = (ctypes.c_int * 3)(), (ctypes.c_int * 3)()
+    split, cut = ctypes.c_int(), ctypes.c_int64()
+    rc = load_library().distal_gemm_plan(dtype_code, int(bool(transposed_left)), M, N, K, batch,
+                                         tile, ctypes.byref(split), ctypes.byref(cut), rest)
+    _raise(rc, "distal_gemm_plan")
+    return tuple(tile), split.value, cut.value, tuple(rest)
+
+
 def gemm_tile(dtype_code: int, transposed_left: bool, M: int, N: int, K: int, batch: int = 1):
-    """(BM, BN, BK) the library uses for an aligned M x N x K product (host-only query)."""
-    bm, bn, bk = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
-    rc = load_library().distal_gemm_tile(dtype_code, int(bool(transposed_left)), M, N, K, batch,
-                                         ctypes.byref(bm), ctypes.byref(bn), ctypes.byref(bk))
-    _raise(rc, "distal_gemm_tile")
-    return bm.value, bn.value, bk.value
+    """(BM, BN, BK) of the first launch of gemm_plan()."""
+    return gemm_plan(dtype_code, transposed_left, M, N, K, batch)[0]
 
 
 def innerprod_workspace_bytes(dtype_code: int, I: int, J: int, K: int) -> int:

@@ -135,42 +135,123 @@ int launch_fill(T *out, int64_t rows, int64_t cols, int64_t ld, hipStream_t stre
 // only operands whose 16-byte pieces would straddle an edge (misaligned bases or leading
 // dimensions, N not a multiple of the vector) take the guarded 128 x 128 kernel.
 
-struct TilePick { int id, bm, bn, bk; };
+struct TilePick { int id, bm, bn, bk; double cost; };
 
 // The tile the straight-line kernels use for a product whose operands allow them (see above).
 // Estimated time of a tile shape: tiles per compute unit (256 of them, the last round of a grid
 // counts in full) x tile area / measured relative speed of that kernel; ragged shapes pay for
 // their padding and for a partly filled last round through the same count.
-TilePick pick_tile(bool f64, bool ta, int64_t M, int64_t N, int64_t K, int64_t batch) {
-    double best = 1e300;
-    TilePick pick{4, 64, 64, 16};
-    auto consider = [&](int id, bool eligible, int bm, int bn, int bk, double speed) {
-        if (!eligible) return;
-        const int64_t t = ((M + bm - 1) / bm) * ((N + bn - 1) / bn) * batch;
-        const double c = (double)((t + kComputeUnits - 1) / kComputeUnits) * (double)(bm * bn) / speed;
-        if (c < best) { best = c; pick = TilePick{id, bm, bn, bk}; }     // earlier candidates win ties
-    };
+struct TileCandidate { int id; bool eligible; int bm, bn, bk; double speed; };
+
+int tile_candidates(bool f64, bool ta, int64_t M, int64_t N, int64_t K, TileCandidate (&c)[8]) {
     // tiles with a short side only for an output that is that narrow (rank-sized N, or M under TA)
     const bool n32 = N <= 32, n64 = N <= 64, m32 = M <= 32, m64 = M <= 64;
     if (!f64) {
-        consider(1, K >= 1024, 256, 256, ta ? 16 : 32, 1.0);
-        consider(2, K >= 512, 256, 128, 16, 0.973);
-        consider(3, true, 128, 128, 16, 0.95);
-        consider(4, true, 64, 64, 16, 0.81);
-        consider(5, n64, 256, 64, 16, 0.885);
-        consider(6, n32 && K >= 32, 256, 32, 32, 0.587);
-        consider(7, m64, 64, 256, 16, 0.889);
-        consider(8, m32 && K >= 32, 32, 256, 32, 0.637);
-    } else {
-        consider(2, K >= 4096, 256, 128, 16, 1.0);
-        consider(3, true, 128, 128, 16, 0.985);
-        consider(4, true, 64, 64, 16, 0.915);
-        consider(5, n64, 128, 64, 16, 0.94);
-        consider(6, n32, 128, 32, 16, 0.697);
-        consider(7, m64, 64, 128, 16, 0.95);
-        consider(8, m32, 32, 256, 16, 0.617);
+        c[0] = {1, K >= 1024, 256, 256, ta ? 16 : 32, 1.0};
+        c[1] = {2, K >= 512, 256, 128, 16, 0.973};
+        c[2] = {3, true, 128, 128, 16, 0.95};
+        c[3] = {4, true, 64, 64, 16, 0.81};
+        c[4] = {5, n64, 256, 64, 16, 0.885};
+        c[5] = {6, n32 && K >= 32, 256, 32, 32, 0.587};
+        c[6] = {7, m64, 64, 256, 16, 0.889};
+        c[7] = {8, m32 && K >= 32, 32, 256, 32, 0.637};
+        return 8;
+    }
+    c[0] = {2, K >= 4096, 256, 128, 16, 1.0};
+    c[1] = {3, true, 128, 128, 16, 0.985};
+    c[2] = {4, true, 64, 64, 16, 0.915};
+    c[3] = {5, n64, 128, 64, 16, 0.94};
+    c[4] = {6, n32, 128, 32, 16, 0.697};
+    c[5] = {7, m64, 64, 128, 16, 0.95};
+    c[6] = {8, m32, 32, 256, 16, 0.617};
+    return 7;
+}
+
+double rounds_cost(int64_t tiles, const TileCandidate &c) {
+    return (double)((tiles + kComputeUnits - 1) / kComputeUnits) * (double)(c.bm * c.bn) / c.speed;
+}
+
+TilePick pick_tile(bool f64, bool ta, int64_t M, int64_t N, int64_t K, int64_t batch) {
+    TileCandidate cand[8];
+    const int n = tile_candidates(f64, ta, M, N, K, cand);
+    TilePick pick{4, 64, 64, 16, 1e300};
+    for (int i = 0; i < n; ++i) {
+        if (!cand[i].eligible) continue;
+        const int64_t t = ((M + cand[i].bm - 1) / cand[i].bm) * ((N + cand[i].bn - 1) / cand[i].bn) * batch;
+        const double c = rounds_cost(t, cand[i]);
+        if (c < pick.cost) pick = TilePick{cand[i].id, cand[i].bm, cand[i].bn, cand[i].bk, c};   // earlier candidates win ties
     }
     return pick;
+}
+
+// A product as at most two launches: the leading rows (or columns) of the output - a whole
+// number of tile rows (columns) whose tiles fill whole rounds of the compute units - with
+// `main`, and what remains, if anything, with the tile that suits it alone; so the part of a
+// grid that would be a thin last round of large tiles runs as a round of small ones.
+// split = 0: one launch; 1: rows [0, cut) and [cut, M); 2: columns [0, cut) and [cut, N).
+struct ProductPlan { TilePick main; int split; int64_t cut; TilePick rest; };
+
+ProductPlan plan_product(bool f64, bool ta, int64_t M, int64_t N, int64_t K, int64_t batch) {
+    ProductPlan plan{pick_tile(f64, ta, M, N, K, batch), 0, 0, TilePick{0, 0, 0, 0, 0.0}};
+    // a second launch costs about 3 us of an otherwise busy part: in units of tile area
+    const double launch_cost = 3e-6 * (f64 ? 78.6e12 : 157.3e12) / (double)kComputeUnits / (2.0 * (double)K);
+    TileCandidate cand[8];
+    const int n = tile_candidates(f64, ta, M, N, K, cand);
+    double best = plan.main.cost;
+    for (int i = 0; i < n; ++i) {
+        if (!cand[i].eligible) continue;
+        const TileCandidate &c = cand[i];
+        const int64_t tm = (M + c.bm - 1) / c.bm, tn = (N + c.bn - 1) / c.bn;
+        const int64_t whole = tm * tn * batch / kComputeUnits * kComputeUnits;     // tiles inside whole rounds
+        for (int split = 1; split <= 2; ++split) {
+            const int64_t per_line = (split == 1 ? tn : tm) * batch;               // tiles per row (column) of tiles
+            const int64_t lines = whole / per_line, cut = lines * (split == 1 ? c.bm : c.bn);
+            if (lines < 1 || cut >= (split == 1 ? M : N)) continue;
+            const TilePick rest = split == 1 ? pick_tile(f64, ta, M - cut, N, K, batch)
+                                             : pick_tile(f64, ta, M, N - cut, K, batch);
+            const double total = rounds_cost(lines * per_line, c) + rest.cost + launch_cost;
+            if (total < 0.97 * best) {                                             // worth a second launch
+                best = total / 0.97;
+                plan = ProductPlan{TilePick{c.id, c.bm, c.bn, c.bk, total}, split, cut, rest};
+            }
+        }
+    }
+    return plan;
+}
+
+// The launch for a tile id of tile_candidates().
+template <typename T, bool TA>
+int launch_by_id(int id, const ContractArgs<T> &a, int64_t batch, hipStream_t stream) {
+    switch (id) {
+    case 1:
+        // a transposed left operand is staged in rows of 256 either way: 16-deep slabs measure 1 % faster
+        if constexpr (sizeof(T) == 4) {
+            if constexpr (TA) return launch_tiles<T, 256, 256, 16, 4, 4, TA>(a, batch, stream);
+            else return launch_tiles<T, 256, 256, 32, 4, 4, TA>(a, batch, stream);
+        }
+        break;
+    case 2:
+        if constexpr (sizeof(T) == 4) return launch_tiles<T, 256, 128, 16, 4, 2, TA>(a, batch, stream);
+        else return launch_tiles<T, 256, 128, 16, 8, 2, TA>(a, batch, stream);
+    case 3:
+        if constexpr (sizeof(T) == 4) return launch_tiles<T, 128, 128, 16, 2, 2, TA>(a, batch, stream);
+        else return launch_tiles<T, 128, 128, 16, 4, 2, TA>(a, batch, stream);
+    case 5:
+        if constexpr (sizeof(T) == 4) return launch_tiles<T, 256, 64, 16, 4, 1, TA>(a, batch, stream);
+        else return launch_tiles<T, 128, 64, 16, 4, 1, TA>(a, batch, stream);
+    case 6:
+        if constexpr (sizeof(T) == 4) return launch_tiles<T, 256, 32, 32, 4, 1, TA>(a, batch, stream);
+        else return launch_tiles<T, 128, 32, 16, 4, 1, TA>(a, batch, stream);
+    case 7:
+        if constexpr (sizeof(T) == 4) return launch_tiles<T, 64, 256, 16, 1, 4, TA>(a, batch, stream);
+        else return launch_tiles<T, 64, 128, 16, 2, 2, TA>(a, batch, stream);
+    case 8:
+        if constexpr (sizeof(T) == 4) return launch_tiles<T, 32, 256, 32, 1, 4, TA>(a, batch, stream);
+        else return launch_tiles<T, 32, 256, 16, 1, 4, TA>(a, batch, stream);
+    default: break;
+    }
+    // too few larger tiles to give every CU one: quarter-size tiles, four times the workgroups
+    return launch_tiles<T, 64, 64, 16, 2, 2, TA>(a, batch, stream);
 }
 
 // TA = false: C = [C +] A * B with A stored M x K.  TA = true: the left operand is stored
@@ -205,36 +286,22 @@ int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
     // the straight-line kernels need 16-byte pieces that never straddle an edge of an operand
     const bool pieces = a.a_vec_ok && a.b_vec_ok && a.c_vec_ok && N % VEC == 0 && (!TA || M % VEC == 0);
     if (!pieces || K < 16) return launch_contract<T, 128, 128, 16, 2, 2, kGuarded, TA>(a, batch, stream);
-    switch (pick_tile(sizeof(T) == 8, TA, M, N, K, batch).id) {
-    case 1:
-        // a transposed left operand is staged in rows of 256 either way: 16-deep slabs measure 1 % faster
-        if constexpr (sizeof(T) == 4) {
-            if constexpr (TA) return launch_tiles<T, 256, 256, 16, 4, 4, TA>(a, batch, stream);
-            else return launch_tiles<T, 256, 256, 32, 4, 4, TA>(a, batch, stream);
-        }
-        break;
-    case 2:
-        if constexpr (sizeof(T) == 4) return launch_tiles<T, 256, 128, 16, 4, 2, TA>(a, batch, stream);
-        else return launch_tiles<T, 256, 128, 16, 8, 2, TA>(a, batch, stream);
-    case 3:
-        if constexpr (sizeof(T) == 4) return launch_tiles<T, 128, 128, 16, 2, 2, TA>(a, batch, stream);
-        else return launch_tiles<T, 128, 128, 16, 4, 2, TA>(a, batch, stream);
-    case 5:
-        if constexpr (sizeof(T) == 4) return launch_tiles<T, 256, 64, 16, 4, 1, TA>(a, batch, stream);
-        else return launch_tiles<T, 128, 64, 16, 4, 1, TA>(a, batch, stream);
-    case 6:
-        if constexpr (sizeof(T) == 4) return launch_tiles<T, 256, 32, 32, 4, 1, TA>(a, batch, stream);
-        else return launch_tiles<T, 128, 32, 16, 4, 1, TA>(a, batch, stream);
-    case 7:
-        if constexpr (sizeof(T) == 4) return launch_tiles<T, 64, 256, 16, 1, 4, TA>(a, batch, stream);
-        else return launch_tiles<T, 64, 128, 16, 2, 2, TA>(a, batch, stream);
-    case 8:
-        if constexpr (sizeof(T) == 4) return launch_tiles<T, 32, 256, 32, 1, 4, TA>(a, batch, stream);
-        else return launch_tiles<T, 32, 256, 16, 1, 4, TA>(a, batch, stream);
-    default: break;
+    const ProductPlan plan = plan_product(sizeof(T) == 8, TA, M, N, K, batch);
+    if (plan.split == 0) return launch_by_id<T, TA>(plan.main.id, a, batch, stream);
+    ContractArgs<T> first = a, second = a;       // the cut is a multiple of 32: alignment is unchanged
+    if (plan.split == 1) {
+        first.M = plan.cut;
+        second.M = M - plan.cut;
+        second.A += TA ? plan.cut : plan.cut * lda;
+        second.C += plan.cut * ldc;
+    } else {
+        first.N = plan.cut;
+        second.N = N - plan.cut;
+        second.B += plan.cut;
+        second.C += plan.cut;
     }
-    // too few larger tiles to give every CU one: quarter-size tiles, four times the workgroups
-    return launch_tiles<T, 64, 64, 16, 2, 2, TA>(a, batch, stream);
+    const int rc = launch_by_id<T, TA>(plan.main.id, first, batch, stream);
+    return rc != DISTAL_OK ? rc : launch_by_id<T, TA>(plan.rest.id, second, batch, stream);
 }
 
 int check_dtype(int dt) { return (dt == DISTAL_F32 || dt == DISTAL_F64) ? DISTAL_OK : DISTAL_ERR_DTYPE; }
@@ -658,16 +725,19 @@ int distal_ttv(distal_dtype dt, int64_t I, int64_t J, int64_t K, const void *B, 
     return ttv_t<float>(rows, K, (const float *)B, (const float *)c, (float *)A, s);
 }
 
-int distal_gemm_tile(distal_dtype dt, int transposed_left, int64_t M, int64_t N, int64_t K, int64_t batch,
-                     int *bm, int *bn, int *bk) {
+int distal_gemm_plan(distal_dtype dt, int transposed_left, int64_t M, int64_t N, int64_t K, int64_t batch,
+                     int tile[3], int *split, int64_t *cut, int rest_tile[3]) {
     if (check_dtype(dt) != DISTAL_OK) return DISTAL_ERR_DTYPE;
     if (M <= 0 || N <= 0 || K <= 0 || batch <= 0) return DISTAL_ERR_SHAPE;
-    if (!bm || !bn || !bk) return DISTAL_ERR_NULL;
+    if (!tile || !split || !cut || !rest_tile) return DISTAL_ERR_NULL;
     int64_t tiles;
     if (!mul_ok((M + 127) / 128, (N + 127) / 128, &tiles) || tiles > std::numeric_limits<int>::max())
         return DISTAL_ERR_SHAPE;
-    const TilePick t = pick_tile(dt == DISTAL_F64, transposed_left != 0, M, N, K, batch);
-    *bm = t.bm; *bn = t.bn; *bk = t.bk;
+    const ProductPlan p = plan_product(dt == DISTAL_F64, transposed_left != 0, M, N, K, batch);
+    tile[0] = p.main.bm; tile[1] = p.main.bn; tile[2] = p.main.bk;
+    *split = p.split;
+    *cut = p.cut;
+    rest_tile[0] = p.rest.bm; rest_tile[1] = p.rest.bn; rest_tile[2] = p.rest.bk;
     return DISTAL_OK;
 }
 

@@ -189,7 +189,7 @@ def test_mttkrp_mode_argument_errors(lib):
     assert m(0, 2, 10, 32, 128, 32, a, b, c, d, P(FAKE + 8), need2, None) == 6
 
 
-def test_gemm_tile_choice(lib):
+def test_gemm_plan_choice(lib):
     """The host-side tile choice for the shapes the benchmark rows and the schedules issue, for
     narrow rank-sized outputs, ragged shapes (padding and the last round of tiles count) and
     small problems; and its argument checks."""
@@ -215,16 +215,27 @@ def test_gemm_tile_choice(lib):
     assert tile(F32, True, 32, 1 << 20, 1024) == (32, 256, 32)
     assert tile(F64, False, 1 << 19, 16, 1024) == (128, 32, 16)
     assert tile(F64, True, 64, 1 << 19, 1024) == (64, 128, 16)
-    # ragged: 8200 rows are 8.25 rounds of 256 x 128 tiles but 16.25 of 128 x 128
-    assert tile(F64, False, 8200, 8192, 8192) == (128, 128, 16)
+    # ragged: 8200 rows are 8.25 rounds of 256 x 128 tiles: the first 8192 rows are eight whole rounds
+    # of them (the tile reported), the other 8 rows a second launch of small tiles
+    assert tile(F64, False, 8200, 8192, 8192) == (256, 128, 16)
     assert tile(F64, False, 8000, 8000, 8000) == (256, 128, 16)
-    assert tile(F64, False, 3000, 3000, 3000) == (64, 64, 16)
+    # 3000^3: 576 tiles of 128 x 128 are 2.25 rounds; 21 rows of them are two whole rounds, the rest small tiles
+    assert tile(F64, False, 3000, 3000, 3000) == (128, 128, 16)
     # small problems: quarter-size tiles
     assert tile(F32, False, 1024, 1024, 1024) == (64, 64, 16)
     assert tile(F64, False, 300, 200, 100) == (64, 64, 16)
-    bm, bn, bk = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
-    refs = (ctypes.byref(bm), ctypes.byref(bn), ctypes.byref(bk))
-    assert lib.distal_gemm_tile(7, 0, 8, 8, 8, 1, *refs) == 3
-    assert lib.distal_gemm_tile(0, 0, 0, 8, 8, 1, *refs) == 2
-    assert lib.distal_gemm_tile(0, 0, 8, 8, 8, 0, *refs) == 2
-    assert lib.distal_gemm_tile(0, 0, 8, 8, 8, 1, None, None, None) == 1
+    # the two-launch plans: whole rounds of large tiles first, the rest on small tiles
+    plan = binding.gemm_plan
+    assert plan(F64, False, 8192, 8192, 8192) == ((256, 128, 16), 0, 0, (0, 0, 0))
+    assert plan(F64, False, 8200, 8192, 8192) == ((256, 128, 16), 1, 8192, (64, 64, 16))
+    assert plan(F64, False, 8192, 8200, 8192) == ((256, 128, 16), 2, 8192, (64, 64, 16))
+    assert plan(F64, False, 5000, 5000, 5000) == ((256, 128, 16), 1, 4864, (64, 64, 16))
+    assert plan(F32, False, 4200, 4096, 1024) == ((256, 256, 32), 1, 4096, (64, 64, 16))
+    assert plan(F64, False, 4096, 4104, 4096) == ((256, 128, 16), 2, 4096, (64, 64, 16))
+    tile3, rest3 = (ctypes.c_int * 3)(), (ctypes.c_int * 3)()
+    split, cut = ctypes.c_int(), ctypes.c_int64()
+    refs = (tile3, ctypes.byref(split), ctypes.byref(cut), rest3)
+    assert lib.distal_gemm_plan(7, 0, 8, 8, 8, 1, *refs) == 3
+    assert lib.distal_gemm_plan(0, 0, 0, 8, 8, 1, *refs) == 2
+    assert lib.distal_gemm_plan(0, 0, 8, 8, 8, 0, *refs) == 2
+    assert lib.distal_gemm_plan(0, 0, 8, 8, 8, 1, None, None, None, None) == 1

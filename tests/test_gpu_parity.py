@@ -87,7 +87,10 @@ def test_gemm_big_tile_configs(lib, oracle, kind, dtype, M, N, K):
 # then 128 x 128 binary32 and a shape whose K is made of whole slabs
 RAGGED_TILE_SHAPES = [(np.float32, 4000, 4000, 1028), (np.float32, 4000, 2040, 520),
                       (np.float64, 4000, 2040, 4100), (np.float64, 2000, 2040, 72),
-                      (np.float32, 2000, 2040, 100), (np.float32, 3900, 4072, 1056)]
+                      (np.float32, 2000, 2040, 100), (np.float32, 3900, 4072, 1056),
+                      # two launches: whole rounds of large tiles, the rest on small tiles - cut along the
+                      # rows (binary32 256 x 256; binary64 128 x 128) and along the columns (binary64 256 x 128)
+                      (np.float32, 4200, 4096, 1024), (np.float64, 4200, 4096, 512), (np.float64, 4096, 4104, 4096)]
 
 
 @pytest.mark.parametrize("kind", KINDS)
@@ -97,6 +100,8 @@ def test_gemm_ragged_edge_tiles(lib, oracle, kind, dtype, M, N, K):
     of the edge tiles must not be stored.  The oracle recomputes sampled rows (first, last, some
     of the last tile row) over all columns."""
     vec = 16 // np.dtype(dtype).itemsize
+    split = {(4200, 4096, 1024): 1, (4200, 4096, 512): 1, (4096, 4104, 4096): 2}.get((M, N, K), 0)
+    assert lib.gemm_plan(int(dtype == np.float64), False, M, N, K)[1] == split
     A, B = U.gen(300 + K, 0, (M, K), dtype, kind), U.gen(300 + K, 1, (K, N), dtype, kind)
     big = np.full((M + 3, N + 2 * vec), 77.0, dtype=dtype)
     dC = U.dev(big)
@@ -110,7 +115,7 @@ def test_gemm_ragged_edge_tiles(lib, oracle, kind, dtype, M, N, K):
     assert np.all(out[mask] == 77.0)
     rows = np.sort(np.random.default_rng(K).choice(M, 24, replace=False))
     rows[0], rows[-1], rows[-2], rows[-3] = 0, M - 1, M - 2, M - 70
-    rows = np.unique(rows)
+    rows = np.unique(np.concatenate([rows, [min(M - 1, 4095), min(M - 1, 4096), min(M - 1, 2047), min(M - 1, 2048)]]))
     compare(got[rows], oracle.gemm(np.ascontiguousarray(A[rows]), B), dtype, kind, K)
     # accumulate on top of the product: twice it (exactly so when one pass forms the product: the
     # trailing terms of K are a second pass, and (P + p) + P + p rounds differently from 2 (P + p)),
