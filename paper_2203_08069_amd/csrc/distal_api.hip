@@ -141,34 +141,45 @@ struct TilePick { int id, bm, bn, bk; double cost; };
 // Estimated time of a tile shape: tiles per compute unit (256 of them, the last round of a grid
 // counts in full) x tile area / measured relative speed of that kernel; ragged shapes pay for
 // their padding and for a partly filled last round through the same count.
-struct TileCandidate { int id; bool eligible; int bm, bn, bk; double speed; };
+// wps: wavefronts per SIMD one workgroup brings; occ: workgroups of that kernel a compute unit holds.
+struct TileCandidate { int id; bool eligible; int bm, bn, bk; double speed; int wps, occ; };
 
 int tile_candidates(bool f64, bool ta, int64_t M, int64_t N, int64_t K, TileCandidate (&c)[8]) {
     // tiles with a short side only for an output that is that narrow (rank-sized N, or M under TA)
     const bool n32 = N <= 32, n64 = N <= 64, m32 = M <= 32, m64 = M <= 64;
     if (!f64) {
-        c[0] = {1, K >= 1024, 256, 256, ta ? 16 : 32, 1.0};
-        c[1] = {2, K >= 512, 256, 128, 16, 0.973};
-        c[2] = {3, true, 128, 128, 16, 0.95};
-        c[3] = {4, true, 64, 64, 16, 0.81};
-        c[4] = {5, n64, 256, 64, 16, 0.885};
-        c[5] = {6, n32 && K >= 32, 256, 32, 32, 0.587};
-        c[6] = {7, m64, 64, 256, 16, 0.889};
-        c[7] = {8, m32 && K >= 32, 32, 256, 32, 0.637};
+        c[0] = {1, K >= 1024, 256, 256, ta ? 16 : 32, 1.0, 4, 1};
+        c[1] = {2, K >= 512, 256, 128, 16, 0.973, 2, 2};
+        c[2] = {3, true, 128, 128, 16, 0.95, 1, 4};
+        c[3] = {4, true, 64, 64, 16, 0.81, 1, 8};
+        c[4] = {5, n64, 256, 64, 16, 0.885, 1, 3};
+        c[5] = {6, n32 && K >= 32, 256, 32, 32, 0.587, 1, 1};
+        c[6] = {7, m64, 64, 256, 16, 0.889, 1, 3};
+        c[7] = {8, m32 && K >= 32, 32, 256, 32, 0.637, 1, 2};
         return 8;
     }
-    c[0] = {2, K >= 4096, 256, 128, 16, 1.0};
-    c[1] = {3, true, 128, 128, 16, 0.985};
-    c[2] = {4, true, 64, 64, 16, 0.915};
-    c[3] = {5, n64, 128, 64, 16, 0.94};
-    c[4] = {6, n32, 128, 32, 16, 0.697};
-    c[5] = {7, m64, 64, 128, 16, 0.95};
-    c[6] = {8, m32, 32, 256, 16, 0.617};
+    c[0] = {2, K >= 4096, 256, 128, 16, 1.0, 4, 1};
+    c[1] = {3, true, 128, 128, 16, 0.985, 2, 2};
+    c[2] = {4, true, 64, 64, 16, 0.915, 1, 4};
+    c[3] = {5, n64, 128, 64, 16, 0.94, 1, 3};
+    c[4] = {6, n32, 128, 32, 16, 0.697, 1, 3};
+    c[5] = {7, m64, 64, 128, 16, 0.95, 1, 3};
+    c[6] = {8, m32, 32, 256, 16, 0.617, 1, 2};
     return 7;
 }
 
+// Estimated time of a grid: tiles per compute unit (a partly filled last round counts in full) x
+// tile area / speed; a grid too small to bring a compute unit its four wavefronts per SIMD runs
+// below that speed (measured with one 128 x 128 tile per compute unit: binary64, two wavefronts
+// per SIMD, 0.87; binary32, one, 0.80).
 double rounds_cost(int64_t tiles, const TileCandidate &c) {
-    return (double)((tiles + kComputeUnits - 1) / kComputeUnits) * (double)(c.bm * c.bn) / c.speed;
+    const int64_t n = (tiles + kComputeUnits - 1) / kComputeUnits;
+    auto fill = [](int64_t wavefronts_per_simd) {
+        return wavefronts_per_simd >= 4 ? 1.0 : (wavefronts_per_simd == 3 ? 0.94 : (wavefronts_per_simd == 2 ? 0.87 : 0.80));
+    };
+    // c.speed was measured on a large grid, i.e. with c.occ workgroups resident
+    const double rel = fill((n < c.occ ? n : c.occ) * c.wps) / fill((int64_t)c.occ * c.wps);
+    return (double)n * (double)(c.bm * c.bn) / (c.speed * rel);
 }
 
 TilePick pick_tile(bool f64, bool ta, int64_t M, int64_t N, int64_t K, int64_t batch) {

@@ -60,15 +60,15 @@ def test_gemm(lib, oracle, dtype, kind, M, N, K):
 
 # shapes that reach the large-tile launch configurations (binary32: 256 x 256 tiles with 32-deep
 # slabs, 256 x 128 for k-chunks; binary64: 256 x 128 with sixteen wavefronts, 128 x 128 with eight)
-BIG_TILE_SHAPES = [(np.float32, 4096, 4096, 1024), (np.float32, 4096, 2048, 512),
-                   (np.float64, 4096, 2048, 4096), (np.float64, 2048, 2048, 64)]
+BIG_TILE_SHAPES = [(np.float32, 4096, 4096, 1024, (256, 256, 32)), (np.float32, 4096, 2048, 512, (256, 128, 16)),
+                   (np.float64, 4096, 2048, 4096, (256, 128, 16)), (np.float64, 4096, 2048, 64, (128, 128, 16))]
 
 
 @pytest.mark.parametrize("kind", KINDS)
-@pytest.mark.parametrize("dtype,M,N,K", BIG_TILE_SHAPES)
-def test_gemm_big_tile_configs(lib, oracle, kind, dtype, M, N, K):
+@pytest.mark.parametrize("dtype,M,N,K,tile", BIG_TILE_SHAPES)
+def test_gemm_big_tile_configs(lib, oracle, kind, dtype, M, N, K, tile):
     """The oracle recomputes sampled rows of the product (all columns) from the same inputs."""
-    import torch
+    assert lib.gemm_plan(int(dtype == np.float64), False, M, N, K) == (tile, 0, 0, (0, 0, 0))
     A, B = U.gen(200 + K, 0, (M, K), dtype, kind), U.gen(200 + K, 1, (K, N), dtype, kind)
     C = empty((M, N), dtype)
     lib.distal_gemm(U.dev(A), U.dev(B), C)
@@ -85,23 +85,23 @@ def test_gemm_big_tile_configs(lib, oracle, kind, dtype, M, N, K):
 # ragged shapes that reach the same launch configurations in their edge-clamping form (M and N
 # not whole tiles, K with trailing terms for the second pass), in the order of BIG_TILE_SHAPES,
 # then 128 x 128 binary32 and a shape whose K is made of whole slabs
-RAGGED_TILE_SHAPES = [(np.float32, 4000, 4000, 1028), (np.float32, 4000, 2040, 520),
-                      (np.float64, 4000, 2040, 4100), (np.float64, 2000, 2040, 72),
-                      (np.float32, 2000, 2040, 100), (np.float32, 3900, 4072, 1056),
+RAGGED_TILE_SHAPES = [(np.float32, 4000, 4000, 1028, (256, 256, 32), 0), (np.float32, 4000, 2040, 520, (256, 128, 16), 0),
+                      (np.float64, 4000, 2040, 4100, (256, 128, 16), 0), (np.float64, 4000, 2040, 72, (128, 128, 16), 0),
+                      (np.float32, 4000, 2040, 100, (128, 128, 16), 0), (np.float32, 3900, 4072, 1056, (256, 256, 32), 0),
                       # two launches: whole rounds of large tiles, the rest on small tiles - cut along the
                       # rows (binary32 256 x 256; binary64 128 x 128) and along the columns (binary64 256 x 128)
-                      (np.float32, 4200, 4096, 1024), (np.float64, 4200, 4096, 512), (np.float64, 4096, 4104, 4096)]
+                      (np.float32, 4200, 4096, 1024, (256, 256, 32), 1), (np.float64, 4200, 4096, 512, (128, 128, 16), 1),
+                      (np.float64, 4096, 4104, 4096, (256, 128, 16), 2)]
 
 
 @pytest.mark.parametrize("kind", KINDS)
-@pytest.mark.parametrize("dtype,M,N,K", RAGGED_TILE_SHAPES)
-def test_gemm_ragged_edge_tiles(lib, oracle, kind, dtype, M, N, K):
+@pytest.mark.parametrize("dtype,M,N,K,tile,split", RAGGED_TILE_SHAPES)
+def test_gemm_ragged_edge_tiles(lib, oracle, kind, dtype, M, N, K, tile, split):
     """C is a block inside a larger matrix filled with a sentinel: rows past M and columns past N
     of the edge tiles must not be stored.  The oracle recomputes sampled rows (first, last, some
     of the last tile row) over all columns."""
     vec = 16 // np.dtype(dtype).itemsize
-    split = {(4200, 4096, 1024): 1, (4200, 4096, 512): 1, (4096, 4104, 4096): 2}.get((M, N, K), 0)
-    assert lib.gemm_plan(int(dtype == np.float64), False, M, N, K)[1] == split
+    assert lib.gemm_plan(int(dtype == np.float64), False, M, N, K)[:2] == (tile, split)
     A, B = U.gen(300 + K, 0, (M, K), dtype, kind), U.gen(300 + K, 1, (K, N), dtype, kind)
     big = np.full((M + 3, N + 2 * vec), 77.0, dtype=dtype)
     dC = U.dev(big)
