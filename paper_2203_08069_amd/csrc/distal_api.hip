@@ -153,7 +153,7 @@ int tile_candidates(bool f64, bool ta, int64_t M, int64_t N, int64_t K, TileCand
         c[2] = {3, true, 128, 128, 16, 0.95, 1, 4};
         c[3] = {4, true, 64, 64, 16, 0.81, 1, 8};
         c[4] = {5, n64, 256, 64, 16, 0.885, 1, 3};
-        c[5] = {6, n32 && K >= 32, 256, 32, 32, 0.587, 1, 1};
+        c[5] = {6, n32 && K >= 32, 128, 32, 32, 0.626, 1, 3};
         c[6] = {7, m64, 64, 256, 16, 0.889, 1, 3};
         c[7] = {8, m32 && K >= 32, 32, 256, 32, 0.637, 1, 2};
         return 8;
@@ -251,7 +251,7 @@ int launch_by_id(int id, const ContractArgs<T> &a, int64_t batch, hipStream_t st
         if constexpr (sizeof(T) == 4) return launch_tiles<T, 256, 64, 16, 4, 1, TA>(a, batch, stream);
         else return launch_tiles<T, 128, 64, 16, 4, 1, TA>(a, batch, stream);
     case 6:
-        if constexpr (sizeof(T) == 4) return launch_tiles<T, 256, 32, 32, 4, 1, TA>(a, batch, stream);
+        if constexpr (sizeof(T) == 4) return launch_tiles<T, 128, 32, 32, 4, 1, TA>(a, batch, stream);
         else return launch_tiles<T, 128, 32, 16, 4, 1, TA>(a, batch, stream);
     case 7:
         if constexpr (sizeof(T) == 4) return launch_tiles<T, 64, 256, 16, 1, 4, TA>(a, batch, stream);

@@ -210,7 +210,7 @@ def test_gemm_plan_choice(lib):
     assert tile(F32, False, 8192, 8192, 256) == (128, 128, 16)
     assert tile(F32, False, 8192, 8192, 1040) == (256, 256, 32)     # K % 32 == 16: one more, half-filled slab
     # rank-sized outputs: a 32- or 64-wide short side on the narrow operand's side
-    assert tile(F32, False, 1 << 20, 32, 1024) == (256, 32, 32)
+    assert tile(F32, False, 1 << 20, 32, 1024) == (128, 32, 32)
     assert tile(F32, False, 1 << 20, 64, 1024) == (256, 64, 16)
     assert tile(F32, True, 32, 1 << 20, 1024) == (32, 256, 32)
     assert tile(F64, False, 1 << 19, 16, 1024) == (128, 32, 16)
