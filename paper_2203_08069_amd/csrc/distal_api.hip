@@ -131,17 +131,15 @@ int launch_fill(T *out, int64_t rows, int64_t cols, int64_t ld, hipStream_t stre
 // instead of padding the narrow one to 64 (speeds measured on such products at 1024^3).  Whole
 // aligned tiles take the straight-line kernels as they are, ragged M and N their edge-clamping
 // form (the padding is paid for through the tile count), with one more zero-filled slab for
-// K % BK trailing terms;
-// only operands whose 16-byte pieces would straddle an edge (misaligned bases or leading
-// dimensions, N not a multiple of the vector) take the guarded 128 x 128 kernel.
+// K % BK trailing terms; only operands whose 16-byte pieces would straddle an edge (misaligned
+// bases or leading dimensions, N not a multiple of the vector) take the guarded 128 x 128
+// kernel.  A grid that would end in a thin last round is cut into two launches (plan_product).
 
 struct TilePick { int id, bm, bn, bk; double cost; };
 
-// The tile the straight-line kernels use for a product whose operands allow them (see above).
-// Estimated time of a tile shape: tiles per compute unit (256 of them, the last round of a grid
-// counts in full) x tile area / measured relative speed of that kernel; ragged shapes pay for
-// their padding and for a partly filled last round through the same count.
-// wps: wavefronts per SIMD one workgroup brings; occ: workgroups of that kernel a compute unit holds.
+// A tile shape the straight-line kernels exist for: its measured relative speed, the
+// wavefronts per SIMD one workgroup brings (wps) and the workgroups of that kernel a compute
+// unit holds (occ).
 struct TileCandidate { int id; bool eligible; int bm, bn, bk; double speed; int wps, occ; };
 
 int tile_candidates(bool f64, bool ta, int64_t M, int64_t N, int64_t K, TileCandidate (&c)[8]) {
@@ -182,6 +180,7 @@ double rounds_cost(int64_t tiles, const TileCandidate &c) {
     return (double)n * (double)(c.bm * c.bn) / (c.speed * rel);
 }
 
+// The tile with the least estimated time for a product run as one launch.
 TilePick pick_tile(bool f64, bool ta, int64_t M, int64_t N, int64_t K, int64_t batch) {
     TileCandidate cand[8];
     const int n = tile_candidates(f64, ta, M, N, K, cand);
