@@ -69,9 +69,17 @@ int launch_contract(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
             if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
             hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
         } else {
-            auto kern = contract_fast_kernel<T, BM, BN, BK, WM, WN, TA, KIND == kEdgeK ? 2 : (KIND == kEdge ? 1 : 0)>;
-            if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
-            hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
+            constexpr int EDGE = KIND == kEdgeK ? 2 : (KIND == kEdge ? 1 : 0);
+            if (sizeof(T) == 4 && a.accumulate) {          // binary32: old C into the accumulators up front
+                static std::atomic<bool> done_acc[kMaxDevices];
+                auto kern = contract_fast_kernel<T, BM, BN, BK, WM, WN, TA, EDGE, sizeof(T) == 4>;
+                if (!allow_lds(kern, Cfg::LDS_BYTES, done_acc)) return DISTAL_ERR_LAUNCH;
+                hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
+            } else {
+                auto kern = contract_fast_kernel<T, BM, BN, BK, WM, WN, TA, EDGE, false>;
+                if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
+                hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
+            }
         }
         if (hipGetLastError() != hipSuccess) return DISTAL_ERR_LAUNCH;
         a.A += count * a.batch_a;

@@ -61,9 +61,14 @@ def test_gemm_8192(lib, oracle, dtype):
     gotv = hC @ x
     denom = np.max(np.abs(want))
     assert np.max(np.abs(gotv - want)) / denom <= (1e-11 if dtype == np.float64 else 1e-4)
-    # accumulate on top: C += A B doubles every entry exactly (power-of-two scaling)
+    # accumulate on top: C += A B doubles every entry - exactly in binary64, where the product is
+    # formed first and added to C in the epilogue (power-of-two scaling); in binary32 the terms are
+    # added to the old C one by one, so each entry is twice the product to within the tolerance
     lib.distal_gemm(A, B, C, accumulate=True)
-    assert np.array_equal(C[:64].cpu().numpy(), (2 * hC[:64]).astype(dtype))
+    if dtype == np.float64:
+        assert np.array_equal(C[:64].cpu().numpy(), (2 * hC[:64]).astype(dtype))
+    else:
+        U.assert_close(C[:64].cpu().numpy(), 2 * hC[:64], dtype, n)
 
 
 @pytest.fixture(scope="module")
