@@ -96,6 +96,7 @@ int launch_contract(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
 template <typename T, int BM, int BN, int BK, int WM, int WN, bool TA>
 int launch_tiles(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
     constexpr int VEC = 16 / (int)sizeof(T);
+    if (a.K < BK) return launch_contract<T, 128, 128, 16, 2, 2, kGuarded, TA>(a, batch, stream);   // no whole slab
     const int64_t k_main = a.K / BK * BK, k_tail = a.K - k_main;
     if (k_tail == 0)
         return (a.M % BM == 0 && a.N % BN == 0) ? launch_contract<T, BM, BN, BK, WM, WN, kWhole, TA>(a, batch, stream)
@@ -469,6 +470,8 @@ int mttkrp_mode_t(int mode, int64_t I, int64_t J, int64_t K, int64_t L, const T 
 // workgroup; K / VEC must be a multiple of 64 * PU.
 template <typename T, int RW, int PU>
 int launch_ttv_rows(int64_t rows, int64_t K, const T *B, const T *c, T *A, hipStream_t stream) {
+    constexpr int VEC = 16 / (int)sizeof(T);
+    if (K % VEC != 0 || (K / VEC) % (64 * PU) != 0) return DISTAL_ERR_SHAPE;   // the kernel reads whole steps only
     int64_t per = (rows + kStreamBlocks - 1) / kStreamBlocks;
     per = (per + 4 * RW - 1) / (4 * RW) * (4 * RW);
     const unsigned blocks = (unsigned)((rows + per - 1) / per);
