@@ -26,7 +26,7 @@ STATUS_NAMES = {
 EXPORTS = (
     "distal_gemm", "distal_ttm", "distal_mttkrp", "distal_ttv", "distal_innerprod",
     "distal_ttv_mode", "distal_ttm_mode", "distal_mttkrp_mode", "distal_mttkrp_mode_workspace_bytes",
-    "distal_mttkrp_workspace_bytes", "distal_innerprod_workspace_bytes", "distal_gemm_plan",
+    "distal_mttkrp_workspace_bytes", "distal_innerprod_workspace_bytes", "distal_gemm_plan", "distal_gemm_tile_of_block",
     "distal_status_string", "distal_version",
 )
 
@@ -70,6 +70,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     ip = ctypes.POINTER(ctypes.c_int)
     lib.distal_gemm_plan.argtypes = [ci, ci, i64, i64, i64, i64, ip, ip, ctypes.POINTER(ctypes.c_int64), ip]
     lib.distal_gemm_plan.restype = ci
+    lib.distal_gemm_tile_of_block.argtypes = [ci, ci, ci, ci, ip, ip]
+    lib.distal_gemm_tile_of_block.restype = ci
     for name in ("distal_gemm", "distal_ttm", "distal_mttkrp", "distal_ttv", "distal_innerprod",
                  "distal_ttm_mode", "distal_mttkrp_mode", "distal_version"):
         getattr(lib, name).restype = ci

@@ -746,6 +746,17 @@ int distal_ttv(distal_dtype dt, int64_t I, int64_t J, int64_t K, const void *B, 
     return ttv_t<float>(rows, K, (const float *)B, (const float *)c, (float *)A, s);
 }
 
+int distal_gemm_tile_of_block(int band_rows, int block, int tiles_m, int tiles_n, int *tile_m, int *tile_n) {
+    if (tiles_m <= 0 || tiles_n <= 0 || (int64_t)tiles_m * tiles_n > std::numeric_limits<int>::max())
+        return DISTAL_ERR_SHAPE;
+    const int nblocks = tiles_m * tiles_n;
+    if (block < 0 || block >= nblocks || (band_rows != 4 && band_rows != 8)) return DISTAL_ERR_SHAPE;
+    if (!tile_m || !tile_n) return DISTAL_ERR_NULL;
+    if (band_rows == 4) tile_of_block<4>(block, nblocks, tiles_m, tiles_n, *tile_m, *tile_n);
+    else tile_of_block<8>(block, nblocks, tiles_m, tiles_n, *tile_m, *tile_n);
+    return DISTAL_OK;
+}
+
 int distal_gemm_plan(distal_dtype dt, int transposed_left, int64_t M, int64_t N, int64_t K, int64_t batch,
                      int tile[3], int *split, int64_t *cut, int rest_tile[3]) {
     if (check_dtype(dt) != DISTAL_OK) return DISTAL_ERR_DTYPE;

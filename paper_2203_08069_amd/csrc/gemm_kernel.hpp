@@ -95,7 +95,7 @@ struct ContractArgs {
 // per tile shape so that the tiles resident on one XCD (32 CUs) cover a roughly
 // square patch of C, which minimises the operand bytes per flop that miss L2.
 template <int GROUP_M>
-__device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m, int tiles_n,
+__host__ __device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m, int tiles_n,
                                               int &tm, int &tn) {
     constexpr int NXCD = 8;
     const int per = nblocks / NXCD, rem = nblocks % NXCD;
