@@ -341,7 +341,7 @@ struct MttkrpModePlan {
     int64_t isplit, nsplit; // walked indices per range; ranges (none empty)
     int64_t nparts;         // partial rows per output row
     int64_t partial_elems;  // workspace elements (0 when nparts == 1)
-    int64_t nslices, kgroups, rblocks /* blocks of 32 output rows */, jgroups, kblocks, tiles_n;
+    int64_t nslices, spw, kgroups, rblocks /* blocks of 32 output rows */, rgroups, jgroups, kblocks, tiles_n;
     bool ok;
 };
 
@@ -355,9 +355,13 @@ MttkrpModePlan mttkrp_mode_plan(int dt, int mode, int64_t I, int64_t J, int64_t 
         const int64_t sl = 256 / esz;
         out_rows = mode == 0 ? I : J;
         p.nslices = (K + sl - 1) / sl;
-        p.kgroups = (p.nslices + 3) / 4;
+        // four k-slices per workgroup, one per wavefront; a short K gives a workgroup fewer slices
+        // and its other wavefronts further blocks of output rows instead
+        p.spw = p.nslices >= 3 ? 4 : p.nslices;
+        p.kgroups = (p.nslices + p.spw - 1) / p.spw;
         p.rblocks = (out_rows + 31) / 32;
-        p.ok = mul_ok(p.kgroups * p.tiles_n, p.rblocks, &p.tasks);
+        p.rgroups = (p.rblocks + 4 / p.spw - 1) / (4 / p.spw);
+        p.ok = mul_ok(p.kgroups * p.tiles_n, p.rgroups, &p.tasks);
         per_split = p.nslices;
     } else {
         const int64_t kw = 512 / esz;
@@ -442,8 +446,8 @@ int mttkrp_mode_t(int mode, int64_t I, int64_t J, int64_t K, int64_t L, const T 
         if (mode == 0) { a.R = I; a.W = J; a.row_stride = jk; a.walk_stride = K; }
         else           { a.R = J; a.W = I; a.row_stride = K;  a.walk_stride = jk; }
         a.wsplit = plan.isplit; a.nsplit = (int)plan.nsplit;
-        a.nslices = (int)plan.nslices; a.kgroups = (int)plan.kgroups;
-        a.tiles_n = (int)plan.tiles_n; a.rblocks = (int)plan.rblocks;
+        a.nslices = (int)plan.nslices; a.spw = (int)plan.spw; a.kgroups = (int)plan.kgroups;
+        a.tiles_n = (int)plan.tiles_n; a.rblocks = (int)plan.rblocks; a.rgroups = (int)plan.rgroups;
         const bool vec = aligned && K % Cfg::VEC == 0, whole = vec && K % Cfg::SL == 0 && a.R % Cfg::RB == 0;
         const int rc = L > 32 ? launch_walk<T, 2>(a, nblocks, vec, whole && L % (2 * Cfg::BN) == 0, stream)
                               : launch_walk<T, 1>(a, nblocks, vec, whole && L % Cfg::BN == 0, stream);

@@ -243,9 +243,12 @@ struct MttkrpWalkArgs {
     int64_t wsplit;    // w per range
     int nsplit;        // ranges of w: ceil(W / wsplit), none empty
     int nslices;       // ceil(K / SL)
-    int kgroups;       // ceil(nslices / 4): k-slices are handed out four per workgroup
+    int spw;           // k-slices per workgroup: 4, or 2 or 1 when K has no more; the workgroup's
+                       // other wavefronts then take the next blocks of r (4 / spw blocks per workgroup)
+    int kgroups;       // ceil(nslices / spw)
     int tiles_n;       // ceil(L / (32 * LT))
     int rblocks;       // ceil(R / 32)
+    int rgroups;       // ceil(rblocks / (4 / spw))
 };
 
 // GUARD = false: rows of B are 16-byte aligned (aligned base, K a multiple of the vector):
@@ -275,13 +278,15 @@ mttkrp_walk_kernel(const MttkrpWalkArgs<T> args) {
     int bid = blockIdx.x;
     const int tn = bid % args.tiles_n;     bid /= args.tiles_n;
     const int kgp = bid % args.kgroups;    bid /= args.kgroups;
-    const int rblk = bid % args.rblocks;   bid /= args.rblocks;
+    const int rgrp = bid % args.rgroups;   bid /= args.rgroups;
     const int split = bid;
     const int64_t R = args.R, W = args.W, K = args.K, L = args.L;
+    const int spw_log2 = args.spw >> 1;                          // spw is 1, 2 or 4
+    const int slice = (kgp << spw_log2) + (wave & (args.spw - 1));
+    const int rblk = (rgrp << (2 - spw_log2)) + (wave >> spw_log2);
     const int64_t n0 = (int64_t)tn * BN, r0 = (int64_t)rblk * RB;
-    const int slice = kgp * Cfg::NW + wave;
     const int64_t k0 = (int64_t)slice * SL;
-    if (k0 >= K) return;                   // wavefront-uniform; this kernel has no barrier
+    if (k0 >= K || rblk >= args.rblocks) return;   // wavefront-uniform; this kernel has no barrier
     const int64_t w_lo = (int64_t)split * args.wsplit;
     const int64_t w_hi = (w_lo + args.wsplit < W) ? w_lo + args.wsplit : W;      // w_lo < w_hi by the plan
 
