@@ -510,6 +510,9 @@ int ttv_t(int64_t rows, int64_t K, const T *B, const T *c, T *A, hipStream_t str
         // binary32 rows of whole 2 KiB runs: the same with four rows per wavefront (+5 %; binary64
         // rows of 2 KiB lose 5 % and stay with the grid below)
         return launch_ttv_rows<T, 4, 2>(rows, K, B, c, A, stream);
+    } else if (rows >= 1024 && rows < 8192 && (K / VEC) % 512 == 0 && K * (int64_t)sizeof(T) >= 64 * 1024) {
+        // a thousand or more long rows: one whole row per wavefront at a time, four rows per workgroup
+        return launch_ttv_rows<T, 1, 8>(rows, K, B, c, A, stream);
     } else if (rows < 8192 && K * (int64_t)sizeof(T) >= 64 * 1024) {
         // too few rows to fill the chip with 16 per workgroup: one workgroup per row
         hipLaunchKernelGGL((ttv_wide_kernel<T, 8>), dim3((unsigned)rows), dim3(256), 0, stream, B, c, A, rows, K);

@@ -252,7 +252,8 @@ TTV_SHAPES = [(4, 8, 1024), (3, 7, 1000), (5, 5, 7), (2, 9, 1), (1, 1, 64), (6, 
               # (one and several steps per row, ranges with a ragged end, both register sets last)
               (83, 101, 1024), (91, 97, 2048), (64, 129, 3072), (70, 120, 1536), (128, 65, 512), (8192, 1, 4096),
               (90, 93, 2560),   # binary32: rows of five 2 KiB runs (four rows per wavefront, five steps per row)
-              (8200, 1, 8192), (4100, 2, 16384)]   # 32 / 64 KiB rows: two rows per wavefront, many steps per row
+              (8200, 1, 8192), (4100, 2, 16384),   # 32 / 64 KiB rows: two rows per wavefront, many steps per row
+              (1030, 1, 16384), (3, 400, 32768)]   # 1024 to 8191 long rows: one row per wavefront, four per workgroup
 
 
 @pytest.mark.parametrize("dtype", DT)
