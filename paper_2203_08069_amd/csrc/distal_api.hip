@@ -499,9 +499,9 @@ int ttv_t(int64_t rows, int64_t K, const T *B, const T *c, T *A, hipStream_t str
         int64_t b8 = (rows + 127) / 128;
         if (b8 > (1 << 22)) b8 = 1 << 22;
         hipLaunchKernelGGL((ttv_short_kernel<T, 8>), dim3((unsigned)b8), dim3(256), 0, stream, B, c, A, rows, K);
-    } else if (rows >= 8192 && (K / VEC) % 256 == 0 && K * (int64_t)sizeof(T) <= 128 * 1024) {
-        // many rows of whole 4 KiB runs, up to 128 KiB: whole rows per wavefront, a contiguous range of
-        // rows per workgroup and one workgroup per compute unit (2 to 10 % faster than the grid below)
+    } else if (rows >= 8192 && (K / VEC) % 256 == 0) {
+        // many rows of whole 4 KiB runs: whole rows per wavefront, a contiguous range of rows per
+        // workgroup and one workgroup per compute unit (1 to 16 % faster than the grid below)
         // 8 KiB rows: one row per wavefront and step; others (4 KiB; 12 KiB and longer): two rows of
         // four pieces (16 KiB rows: 6.98 TB/s against 6.37 with one row of eight)
         if (K / VEC == 512) return launch_ttv_rows<T, 1, 8>(rows, K, B, c, A, stream);
