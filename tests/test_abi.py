@@ -259,3 +259,41 @@ def test_block_to_tile_map_is_a_bijection(lib):
     assert lib.distal_gemm_tile_of_block(8, 6, 2, 3, ctypes.byref(tm), ctypes.byref(tn)) == 2
     assert lib.distal_gemm_tile_of_block(5, 0, 2, 3, ctypes.byref(tm), ctypes.byref(tn)) == 2
     assert lib.distal_gemm_tile_of_block(8, 0, 2, 3, None, None) == 1
+
+
+def test_gemm_plan_invariants_on_random_extents(lib):
+    """Whatever the extents: tiles come from the dtype's set, narrow tiles only serve narrow outputs,
+    slabs are no deeper than K allows the kernels to start (K >= BK or the guarded kernel is used),
+    a cut is a positive multiple of the first tile inside the extent it cuts."""
+    import random
+    from paper_2203_08069_amd import binding
+    rng = random.Random(5)
+    tiles = {0: {(256, 256), (256, 128), (128, 128), (64, 64), (256, 64), (128, 32), (64, 256), (32, 256)},
+             1: {(256, 128), (128, 128), (64, 64), (128, 64), (128, 32), (64, 128), (32, 256)}}
+    pick = lambda: rng.choice([1, 4, 8, 16, 24, 32, 48, 64, 100, 128, 250, 256, 512, 1000, 1024, 3000, 4096, 5000, 8192, 8200,
+                               65536, 1 << 20]) + rng.choice([0, 0, 0, 4, -4 if rng.random() < .5 else 8])
+    for _ in range(3000):
+        dt, ta = rng.randrange(2), rng.randrange(2)
+        M, N, K = max(1, pick()), max(1, pick()), max(16, pick())
+        batch = rng.choice([1, 1, 1, 7, 1024])
+        if M * N * batch > 1 << 44:
+            continue
+        tile, split, cut, rest = binding.gemm_plan(dt, bool(ta), M, N, K, batch)
+        assert binding.gemm_plan(dt, bool(ta), M, N, K, batch) == (tile, split, cut, rest)
+
+        def ok(t, m, n):
+            assert (t[0], t[1]) in tiles[dt], (t, dt)
+            assert t[2] in (16, 32) and t[2] <= max(K, 16), (t, K)
+            if t[1] < 64 or (t[1] == 64 and t[0] > 64):
+                assert n <= 64, (t, n)              # a narrow N side only for a narrow N
+            if t[0] < 64 or (t[0] == 64 and t[1] > 64):
+                assert m <= 64, (t, m)
+        if split == 0:
+            ok(tile, M, N)
+            assert cut == 0 and rest == (0, 0, 0)
+        elif split == 1:
+            assert 0 < cut < M and cut % tile[0] == 0
+            ok(tile, M, N), ok(rest, M - cut, N)
+        else:
+            assert split == 2 and 0 < cut < N and cut % tile[1] == 0
+            ok(tile, M, N), ok(rest, M, N - cut)
