@@ -128,14 +128,25 @@ def _same(*ts):
     return _dtype_code(ts[0])
 
 
-def _ld(t, name: str) -> int:
-    """Leading dimension of a 2-D tensor with unit column stride (may be a row-strided view)."""
-    _check(t, name, 2)
+def _row_stride(t, name: str) -> int:
+    """Leading dimension (elements) of a 2-D view with unit column stride.  Rows must not
+    overlap: a row stride smaller than the row length (an expanded or overlapping view) is
+    refused here, since the kernels would read or write past the buffer behind such a view."""
+    if t.dim() != 2:
+        raise ValueError(f"{name} must have 2 dimensions")
     if t.shape[1] > 1 and t.stride(1) != 1:
         raise ValueError(f"{name}: columns must be contiguous")
     if t.shape[0] > 1:
-        return int(t.stride(0))
+        ld = int(t.stride(0))
+        if ld < int(t.shape[1]):
+            raise ValueError(f"{name}: row stride {ld} is smaller than the row length {int(t.shape[1])}")
+        return ld
     return max(int(t.shape[1]), 1)
+
+
+def _ld(t, name: str) -> int:
+    _check(t, name, 2)
+    return _row_stride(t, name)
 
 
 def _stream(t) -> ctypes.c_void_p:
@@ -176,8 +187,8 @@ def distal_gemm(A, B, C, accumulate: bool = False):
     if K != K2 or tuple(C.shape) != (M, N):
         raise ValueError("shapes do not match C(M,N) = A(M,K) B(K,N)")
     with _torch().cuda.device(A.device):
-        rc = load_library().distal_gemm(dt, M, N, K, _ptr(A), max(lda, K), _ptr(B), max(ldb, N),
-                                        _ptr(C), max(ldc, N), int(bool(accumulate)), _stream(A))
+        rc = load_library().distal_gemm(dt, M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc,
+                                        int(bool(accumulate)), _stream(A))
     _raise(rc, "distal_gemm")
     return C
 
@@ -324,3 +335,4 @@ def distal_innerprod(B, C, a, workspace=None):
                                              ws.numel() * ws.element_size(), _stream(B))
     _raise(rc, "distal_innerprod")
     return a
+

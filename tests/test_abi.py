@@ -297,3 +297,21 @@ def test_gemm_plan_invariants_on_random_extents(lib):
         else:
             assert split == 2 and 0 < cut < N and cut % tile[1] == 0
             ok(tile, M, N), ok(rest, M, N - cut)
+
+
+def test_binding_refuses_views_whose_rows_overlap():
+    """A row stride below the row length (expand(), overlapping as_strided) must raise in the
+    binding instead of reaching the kernels with a leading dimension that was silently raised."""
+    import torch
+    from paper_2203_08069_amd import binding
+    row = torch.zeros(1, 8)
+    with pytest.raises(ValueError):
+        binding._row_stride(row.expand(5, 8), "A")                     # stride(0) == 0
+    with pytest.raises(ValueError):
+        binding._row_stride(torch.zeros(64).as_strided((5, 8), (4, 1)), "A")   # rows overlap
+    with pytest.raises(ValueError):
+        binding._row_stride(torch.zeros(8, 8).t(), "A")                # columns not contiguous
+    assert binding._row_stride(torch.zeros(5, 8), "A") == 8
+    assert binding._row_stride(torch.zeros(5, 16)[:, 3:11], "A") == 16     # a column slice keeps its stride
+    assert binding._row_stride(row, "A") == 8                          # one row: the row length
+    assert binding._row_stride(torch.zeros(64).as_strided((5, 8), (8, 1)), "A") == 8
