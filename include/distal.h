@@ -157,6 +157,20 @@ int distal_innerprod(distal_dtype dt, int64_t I, int64_t J, int64_t K,
                      void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * distal_innerprod for callers that cannot allocate or hand over device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same result, bit
+ * for bit, as distal_innerprod; the partial sums live in an array the library's code object
+ * holds on every device (16 KiB, there until the process ends), so no workspace is passed and
+ * nothing is allocated, freed or synchronised.  Every shape distal_innerprod accepts fits; a
+ * shape whose partial sums would not fit returns DISTAL_ERR_WORKSPACE, and a runtime that
+ * cannot give the array's address DISTAL_ERR_LAUNCH.  All calls on one device share the one
+ * array: calls that may overlap in time on one device (different streams, different host
+ * threads) race and must be ordered by the caller; calls on one stream are safe.
+ */
+int distal_innerprod_noalloc(distal_dtype dt, int64_t I, int64_t J, int64_t K,
+                             const void *B, const void *C, void *a, void *stream);
+
+/*
  * Host-only query (no device work): how the library runs C = A * B with these extents when the
  * operands are 16-byte aligned (K >= 16, N and the leading dimensions multiples of 16 bytes;
  * other operands take the bounds-checked 128 x 128 kernel whatever this returns).  TTM is such a

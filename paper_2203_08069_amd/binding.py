@@ -27,7 +27,7 @@ EXPORTS = (
     "distal_gemm", "distal_ttm", "distal_mttkrp", "distal_ttv", "distal_innerprod",
     "distal_ttv_mode", "distal_ttm_mode", "distal_mttkrp_mode", "distal_mttkrp_mode_workspace_bytes",
     "distal_mttkrp_workspace_bytes", "distal_innerprod_workspace_bytes", "distal_gemm_plan", "distal_gemm_tile_of_block",
-    "distal_status_string", "distal_version",
+    "distal_status_string", "distal_version", "distal_innerprod_noalloc",
 )
 
 
@@ -63,6 +63,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.distal_mttkrp.argtypes = [ci, i64, i64, i64, i64, vp, vp, vp, vp, vp, sz, vp]
     lib.distal_ttv.argtypes = [ci, i64, i64, i64, vp, vp, vp, vp]
     lib.distal_innerprod.argtypes = [ci, i64, i64, i64, vp, vp, vp, vp, sz, vp]
+    lib.distal_innerprod_noalloc.argtypes = [ci, i64, i64, i64, vp, vp, vp, vp]
+    lib.distal_innerprod_noalloc.restype = ci
     lib.distal_mttkrp_workspace_bytes.argtypes = [ci, i64, i64, i64, i64]
     lib.distal_innerprod_workspace_bytes.argtypes = [ci, i64, i64, i64]
     lib.distal_status_string.argtypes = [ci]
@@ -336,3 +338,15 @@ def distal_innerprod(B, C, a, workspace=None):
     _raise(rc, "distal_innerprod")
     return a
 
+
+def distal_innerprod_noalloc(B, C, a):
+    """distal_innerprod on the library's own scratch array: no workspace, nothing allocated."""
+    dt = _same(B, C, a)
+    _dense(B, "B", 3), _dense(C, "C", 3)
+    if tuple(B.shape) != tuple(C.shape) or a.numel() != 1 or not a.is_cuda:
+        raise ValueError("B and C must have equal shapes and a must hold one element on the device")
+    I, J, K = B.shape
+    with _torch().cuda.device(B.device):
+        rc = load_library().distal_innerprod_noalloc(dt, I, J, K, _ptr(B), _ptr(C), _ptr(a), _stream(B))
+    _raise(rc, "distal_innerprod_noalloc")
+    return a

@@ -596,6 +596,27 @@ int innerprod_t(int64_t n, const T *B, const T *C, T *out, double *partial, hipS
     return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
 }
 
+// ---- library-owned scratch for the entry point that allocates nothing ------
+// One array per device, inside the code object: the partial sums of distal_innerprod_noalloc.
+// In host code the array's name is only a handle for hipGetSymbolAddress; kernels and every
+// other device-side use take the address that call returns, looked up once per device.
+constexpr size_t kScratchBytes = (size_t)kInnerprodMaxBlocks * sizeof(double);
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+namespace {
+std::atomic<void *> scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device (NULL if the runtime refuses).
+void *scratch_of_current_device() {
+    int d = -1;
+    if (hipGetDevice(&d) != hipSuccess || d < 0 || d >= kMaxDevices) { (void)hipGetLastError(); return nullptr; }
+    void *p = scratch_ptr[d].load(std::memory_order_acquire);
+    if (p) return p;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return nullptr; }
+    scratch_ptr[d].store(p, std::memory_order_release);   // every thread finds the same address
+    return p;
+}
+
 bool tensor_elems(int64_t I, int64_t J, int64_t K, int64_t *n) {
     int64_t ij;
     // keep byte offsets inside int64 as well
@@ -827,6 +848,25 @@ int distal_innerprod(distal_dtype dt, int64_t I, int64_t J, int64_t K, const voi
     if (dt == DISTAL_F64)
         return innerprod_t<double>(n, (const double *)B, (const double *)C, (double *)a, (double *)workspace, s);
     return innerprod_t<float>(n, (const float *)B, (const float *)C, (float *)a, (double *)workspace, s);
+}
+
+int distal_innerprod_noalloc(distal_dtype dt, int64_t I, int64_t J, int64_t K, const void *B, const void *C,
+                             void *a, void *stream) {
+    if (check_dtype(dt) != DISTAL_OK) return DISTAL_ERR_DTYPE;
+    if (I < 0 || J < 0 || K < 0) return DISTAL_ERR_SHAPE;
+    int64_t n;
+    if (!tensor_elems(I, J, K, &n)) return DISTAL_ERR_SHAPE;
+    if (!a || (n > 0 && (!B || !C))) return DISTAL_ERR_NULL;
+    if (a == B || a == C) return DISTAL_ERR_ALIAS;
+    // the partial sums of this shape must fit the library's array
+    if (distal_innerprod_workspace_bytes(dt, I, J, K) > kScratchBytes) return DISTAL_ERR_WORKSPACE;
+    void *ws = scratch_of_current_device();
+    if (!ws) return DISTAL_ERR_LAUNCH;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // pass 1 writes every partial that pass 2 reads, so nothing of an earlier call is seen
+    if (dt == DISTAL_F64)
+        return innerprod_t<double>(n, (const double *)B, (const double *)C, (double *)a, (double *)ws, s);
+    return innerprod_t<float>(n, (const float *)B, (const float *)C, (float *)a, (double *)ws, s);
 }
 
 }  // extern "C"

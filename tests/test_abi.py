@@ -315,3 +315,15 @@ def test_binding_refuses_views_whose_rows_overlap():
     assert binding._row_stride(torch.zeros(5, 16)[:, 3:11], "A") == 16     # a column slice keeps its stride
     assert binding._row_stride(row, "A") == 8                          # one row: the row length
     assert binding._row_stride(torch.zeros(64).as_strided((5, 8), (8, 1)), "A") == 8
+
+
+def test_noalloc_argument_errors(lib):
+    """The allocation-free entry point validates on the host before it touches the device."""
+    a, b, c = (P(FAKE + 256 * i) for i in range(3))
+    f = lib.distal_innerprod_noalloc
+    assert f(9, 2, 2, 2, a, b, c, None) == 3
+    assert f(0, 2, -2, 2, a, b, c, None) == 2
+    assert f(0, 1 << 31, 1 << 31, 1 << 31, a, b, c, None) == 2
+    assert f(0, 2, 2, 2, None, b, c, None) == 1
+    assert f(0, 2, 2, 2, a, b, None, None) == 1
+    assert f(1, 2, 2, 2, a, b, a, None) == 5
