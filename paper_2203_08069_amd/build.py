@@ -17,6 +17,9 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdistal.so")
 SOURCES = ["distal_api.hip"]
 HEADERS = ["gemm_kernel.hpp", "mttkrp_kernel.hpp", "stream_kernels.hpp"]
+# the measurement aid of include/distal_probe.h: a library of its own, never loaded by the binding
+PROBE_LIB = os.path.join(HERE, "libdistal_probe.so")
+PROBE_SOURCES = ["roofline_probe.hip"]
 
 # Packed-FP32 VALU forms are switched off for every kernel of this library.
 HIPCC_FLAGS = [
@@ -43,7 +46,19 @@ def build_library(force: bool = True, extra_flags=()) -> str:
     cmd = [hipcc()] + HIPCC_FLAGS + list(extra_flags) + ["-o", tmp] + srcs
     subprocess.check_call(cmd)
     os.replace(tmp, LIB)
+    build_probe(force=force)
     return LIB
+
+
+def build_probe(force: bool = True) -> str:
+    srcs = [os.path.join(CSRC, s) for s in PROBE_SOURCES]
+    deps = srcs + [os.path.join(os.path.dirname(HERE), "include", "distal_probe.h")]
+    if not force and os.path.exists(PROBE_LIB) and all(os.path.getmtime(PROBE_LIB) >= os.path.getmtime(d) for d in deps):
+        return PROBE_LIB
+    tmp = PROBE_LIB + ".tmp.%d" % os.getpid()
+    subprocess.check_call([hipcc()] + HIPCC_FLAGS + ["-o", tmp] + srcs)
+    os.replace(tmp, PROBE_LIB)
+    return PROBE_LIB
 
 
 if __name__ == "__main__":

@@ -327,3 +327,26 @@ def test_noalloc_argument_errors(lib):
     assert f(0, 2, 2, 2, None, b, c, None) == 1
     assert f(0, 2, 2, 2, a, b, None, None) == 1
     assert f(1, 2, 2, 2, a, b, a, None) == 5
+
+
+def test_probe_library_exports_and_argument_errors():
+    """The measurement aid (include/distal_probe.h) is a library of its own: it loads, exports what
+    its header declares and validates on the host before launching."""
+    from paper_2203_08069_amd import build, probe
+    if not os.path.exists(probe.LIB_PATH):
+        build.build_probe()
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "distal_probe.h")).read(), flags=re.S)
+    declared = sorted(set(re.findall(r"\b(distal_probe_[a-z_]+)\s*\(", text)))
+    assert declared == sorted(probe.EXPORTS)
+    lib = probe.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+    f = lib.distal_probe_stream_mfma
+    a, b, c = (P(FAKE + 256 * i) for i in range(3))
+    assert lib.distal_probe_out_bytes(1024, 1024, 1024) == 768 * 256 * 16 * 4
+    assert lib.distal_probe_out_bytes(1000, 1024, 1024) == 0
+    assert f(1000, 8, 256, a, b, 1, c, 1 << 30, None) == 2          # I not a multiple of 32
+    assert f(32, 8, 100, a, b, 1, c, 1 << 30, None) == 2            # K not a multiple of 256
+    assert f(32, 8, 256, None, b, 1, c, 1 << 30, None) == 1
+    assert f(32, 8, 256, P(FAKE + 4), b, 1, c, 1 << 30, None) == 4
+    assert f(32, 8, 256, a, b, 1, c, 16, None) == 6

@@ -24,8 +24,11 @@ def lib():
 
 
 def devgen(seed, ordinal, shape, dtype):
-    from paper_2203_08069_amd.device_inputs import device_tensor
-    return device_tensor(seed, ordinal, shape, dtype, device="cuda:0")
+    """The seeded tensor, filled in place on the device by the torch-integer form of the generator
+    (test_device_inputs_are_the_generators_bytes pins it to the numpy form on the GPU; every case
+    below recomputes its expected values from inputs regenerated on the host by the numpy form)."""
+    from paper_2203_08069_amd.device_inputs import generate_on_device
+    return generate_on_device(seed, ordinal, shape, dtype, device="cuda:0")
 
 
 def host_rows(seed, ordinal, row_len, rows, dtype):
@@ -42,15 +45,16 @@ def test_gemm_8192(lib, oracle, dtype):
     C = torch.zeros((n, n), dtype=A.dtype, device="cuda:0")
     lib.distal_gemm(A, B, C)
     rng = np.random.default_rng(7)
-    rows = np.sort(rng.choice(n, 48, replace=False))
-    cols = np.sort(rng.choice(n, 64, replace=False))
-    hA = host_rows(1, 0, n, rows, dtype)                                   # 48 x K
+    # one whole row of C inside every band of 128 rows, at a random offset in the band: every row
+    # of tiles of every tiling (256 x 128, 256 x 256) and every column tile is covered
+    rows = np.arange(0, n, 128) + rng.integers(0, 128, n // 128)
+    hA = host_rows(1, 0, n, rows, dtype)                                   # 64 x K
     hB = inputs.tensor(1, 1, (n, n), dtype, threads=8)
-    ref = oracle.gemm(hA, np.ascontiguousarray(hB[:, cols]))               # 48 x 64 sampled outputs
-    got = C[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy()
-    scale = np.sqrt(n / 3.0)                                               # typical |C| entry
-    err = np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), scale)
-    assert err <= U.tol(dtype, n), err
+    ref = oracle.gemm(hA, hB)                                              # 64 full rows of C
+    got = C[torch.from_numpy(rows).cuda()].cpu().numpy()
+    U.assert_close(got, ref, dtype, n)
+    absref = oracle.gemm(np.abs(hA), np.abs(hB))
+    U.assert_componentwise(got, ref, absref, dtype, n)
     # whole output: Freivalds' check C x = A (B x) with x = +-1, evaluated in binary64 on the host
     x = rng.integers(0, 2, n).astype(np.float64) * 2 - 1
     hC = C.cpu().numpy().astype(np.float64)
@@ -83,18 +87,18 @@ def test_ttv_1024(lib, oracle, cfg3_B):
     c = devgen(2, 1, (K,), np.float32)
     A = torch.full((I, J), float("nan"), dtype=torch.float32, device="cuda:0")
     lib.distal_ttv(cfg3_B, c, A)
-    rng = np.random.default_rng(8)
-    rows = np.sort(rng.choice(I * J, 2048, replace=False))
-    hB = host_rows(2, 0, K, rows, np.float32).reshape(1, -1, K)
-    hc = inputs.values(2, 1, 0, K, np.float32)
-    ref = oracle.ttv(hB, hc)[0]
-    got = A.view(-1)[torch.from_numpy(rows).cuda()].cpu().numpy()
-    U.assert_close(got, ref, np.float32, K)
     assert bool(torch.isfinite(A).all())
-    # all-ones vector: every output is the plain k-sum; compare with the sampled rows
-    lib.distal_ttv(cfg3_B, torch.ones(K, dtype=torch.float32, device="cuda:0"), A)
-    got1 = A.view(-1)[torch.from_numpy(rows).cuda()].cpu().numpy()
-    U.assert_close(got1, hB[0].astype(np.float64).sum(axis=1), np.float32, K)
+    A1 = torch.empty_like(A)
+    lib.distal_ttv(cfg3_B, torch.ones(K, dtype=torch.float32, device="cuda:0"), A1)
+    hc = inputs.values(2, 1, 0, K, np.float32)
+    # every one of the 2^20 outputs, the tensor regenerated on the host 64 slices at a time
+    step = 64
+    hB = np.empty((step, J, K), np.float32)
+    for i0 in range(0, I, step):
+        inputs.fill(hB.reshape(-1), 2, 0, i0 * J * K, threads=8)
+        U.assert_close(A[i0:i0 + step].cpu().numpy(), oracle.ttv(hB, hc), np.float32, K)
+        # all-ones vector: every output is the plain k-sum
+        U.assert_close(A1[i0:i0 + step].cpu().numpy(), hB.sum(axis=2, dtype=np.float64), np.float32, K)
 
 
 def test_innerprod_1024(lib, oracle, cfg3_B):
@@ -113,14 +117,17 @@ def test_innerprod_1024(lib, oracle, cfg3_B):
         lib.distal_innerprod(fb[sl].view(1, 1, -1), fc[sl].view(1, 1, -1), a)
         pieces.append(float(a.item()))
     assert abs(sum(pieces) - full) <= 16 * np.finfo(np.float32).eps * sum(abs(p) for p in pieces)
-    # ... and two of the pieces are recomputed by the oracle from regenerated inputs
-    for p in (3, 12):
-        hb = inputs.tensor(2, 0, (1, 1, piece_len), np.float32, threads=8)
-        hc = inputs.tensor(2, 2, (1, 1, piece_len), np.float32, threads=8)
+    # ... and every piece is recomputed by the oracle from regenerated inputs
+    hb = np.empty((1, 1, piece_len), np.float32)
+    hc = np.empty((1, 1, piece_len), np.float32)
+    total = 0.0
+    for p in range(16):
         inputs.fill(hb.reshape(-1), 2, 0, p * piece_len, threads=8)
         inputs.fill(hc.reshape(-1), 2, 2, p * piece_len, threads=8)
         ref = oracle.innerprod(hb, hc)
+        total += ref
         assert abs(pieces[p] - ref) <= 2 * np.finfo(np.float32).eps * abs(ref) + 1e-3
+    assert abs(full - total) <= 2 * np.finfo(np.float32).eps * abs(total) + 1e-2
     # symmetry, bit for bit, at full size
     lib.distal_innerprod(C, cfg3_B, a)
     assert float(a.item()) == full
@@ -135,7 +142,8 @@ def test_ttm_1024(lib, oracle):
     A = torch.full((I, J, L), float("nan"), dtype=torch.float32, device="cuda:0")
     lib.distal_ttm(B, C, A)
     rng = np.random.default_rng(9)
-    fibres = np.sort(rng.choice(I * J, 512, replace=False))
+    # one whole fibre A(i,j,:) inside every band of 256 rows of the (I*J) x L view: every output tile
+    fibres = np.arange(0, I * J, 256) + rng.integers(0, 256, I * J // 256)
     hB = host_rows(3, 0, K, fibres, np.float32).reshape(1, -1, K)
     hC = inputs.tensor(3, 1, (K, L), np.float32)
     ref = oracle.ttm(hB, hC)[0]
@@ -157,14 +165,15 @@ def test_mttkrp_1024(lib, oracle):
     C, D = devgen(4, 1, (J, L), np.float32), devgen(4, 2, (K, L), np.float32)
     A = torch.full((I, L), float("nan"), dtype=torch.float32, device="cuda:0")
     lib.distal_mttkrp(B, C, D, A)
-    slices = [0, 357, 1023]
     hC, hD = inputs.tensor(4, 1, (J, L), np.float32), inputs.tensor(4, 2, (K, L), np.float32)
-    for i in slices:
-        hB = inputs.values(4, 0, i * J * K, J * K, np.float32).reshape(1, J, K)
-        ref = oracle.mttkrp(hB, hC, hD)[0]
-        got = A[i].cpu().numpy()
-        U.assert_close(got, ref, np.float32, J * K)
     assert bool(torch.isfinite(A).all())
+    # every one of the 1024 output rows, the tensor regenerated on the host 64 slices at a time
+    step = 64
+    hB = np.empty((step, J, K), np.float32)
+    got = A.cpu().numpy()
+    for i0 in range(0, I, step):
+        inputs.fill(hB.reshape(-1), 4, 0, i0 * J * K, threads=8)
+        U.assert_close(got[i0:i0 + step], oracle.mttkrp(hB, hC, hD), np.float32, J * K)
     # second call gives the same bits (fixed summation order, no atomics)
     A2 = torch.empty_like(A)
     lib.distal_mttkrp(B, C, D, A2)
@@ -174,10 +183,18 @@ def test_mttkrp_1024(lib, oracle):
 def test_device_inputs_are_the_generators_bytes():
     """The device copy that the full-size cases read slices back from is the generator's output."""
     import torch
-    t = devgen(3, 0, (64, 1024, 1024), np.float32)
-    for start in (0, 12345 * 1024, 64 * 1024 * 1024 - 4096):
-        want = inputs.values(3, 0, start, 4096, np.float32)
-        assert np.array_equal(t.view(-1)[start:start + 4096].cpu().numpy(), want)
+    from paper_2203_08069_amd.device_inputs import device_tensor
+    for dtype in (np.float32, np.float64):
+        t = devgen(3, 0, (64, 1024, 1024), dtype)                         # filled in place by torch integer ops
+        u = device_tensor(3, 0, (8, 1024, 1024), dtype, device="cuda:0")  # generated by numpy, copied
+        assert torch.equal(t[:8], u)
+        for start in (0, 12345 * 1024, 64 * 1024 * 1024 - 4096):
+            want = inputs.values(3, 0, start, 4096, dtype)
+            assert np.array_equal(t.view(-1)[start:start + 4096].cpu().numpy(), want)
+    for kind, r in ((inputs.SMALLINT, 3), (inputs.SMALLINT, 2)):
+        from paper_2203_08069_amd.device_inputs import generate_on_device
+        t = generate_on_device(6, 1, (3, 1000, 1000), np.float32, kind, r, device="cuda:0")
+        assert np.array_equal(t.cpu().numpy(), inputs.tensor(6, 1, (3, 1000, 1000), np.float32, kind, r, threads=8))
 
 
 @pytest.mark.parametrize("mode", [0, 1])
@@ -247,3 +264,103 @@ def test_ttv_more_row_groups_than_the_grid_cap(lib, oracle):
     for start in (0, (1 << 22) * 16 - 60, (1 << 25) + 12345, rows - 64):
         hB = inputs.values(5, 0, start * K, 64 * K, np.float32).reshape(1, 64, K)
         U.assert_close(A[0, start:start + 64].cpu().numpy(), oracle.ttv(hB, hc)[0], np.float32, K)
+
+
+# ---------------------------------------------------------------------------------------------
+# binary64 (the paper's own element type) at the full sizes: the instantiations these shapes
+# select - the row-streaming TTV kernel, 256 x 128 contraction tiles, the two-row-block MTTKRP
+# layout - are reached only here.  Sampled outputs are recomputed by the oracle from inputs
+# regenerated on the host; whole-output properties cover the rest.
+# ---------------------------------------------------------------------------------------------
+
+@pytest.fixture(scope="module")
+def cfg3_B64():
+    return devgen(2, 0, (1024, 1024, 1024), np.float64)
+
+
+def test_ttv_1024_f64(lib, oracle, cfg3_B64):
+    import torch
+    I = J = K = 1024
+    c = devgen(2, 1, (K,), np.float64)
+    A = torch.full((I, J), float("nan"), dtype=torch.float64, device="cuda:0")
+    lib.distal_ttv(cfg3_B64, c, A)
+    assert bool(torch.isfinite(A).all())
+    hc = inputs.values(2, 1, 0, K, np.float64)
+    rng = np.random.default_rng(18)
+    # four whole i-slices (4096 rows each) spread over the tensor: a row range of every workgroup kind
+    for i in (0, int(rng.integers(1, 511)), int(rng.integers(512, 1023)), 1023):
+        hB = inputs.values(2, 0, i * J * K, J * K, np.float64).reshape(1, J, K)
+        U.assert_close(A[i:i + 1].cpu().numpy(), oracle.ttv(hB, hc), np.float64, K)
+    # one sampled row in every run of 256 rows of the (I*J) x K view
+    rows = np.arange(0, I * J, 256) + rng.integers(0, 256, I * J // 256)
+    hB = host_rows(2, 0, K, rows, np.float64).reshape(1, -1, K)
+    got = A.view(-1)[torch.from_numpy(rows).cuda()].cpu().numpy()
+    U.assert_close(got, oracle.ttv(hB, hc)[0], np.float64, K)
+
+
+def test_innerprod_1024_f64(lib, oracle, cfg3_B64):
+    import torch
+    n = 1 << 30
+    C = devgen(2, 2, (1024, 1024, 1024), np.float64)
+    a = torch.empty(1, dtype=torch.float64, device="cuda:0")
+    lib.distal_innerprod(cfg3_B64, C, a)
+    full = float(a.item())
+    pieces, piece_len = [], n // 16
+    fb, fc = cfg3_B64.view(-1), C.view(-1)
+    for p in range(16):
+        sl = slice(p * piece_len, (p + 1) * piece_len)
+        lib.distal_innerprod(fb[sl].view(1, 1, -1), fc[sl].view(1, 1, -1), a)
+        pieces.append(float(a.item()))
+    scale = sum(abs(p) for p in pieces)
+    assert abs(sum(pieces) - full) <= 1e-12 * scale
+    hb = np.empty((1, 1, piece_len), np.float64)
+    hc = np.empty((1, 1, piece_len), np.float64)
+    for p in (0, 5, 10, 15):
+        inputs.fill(hb.reshape(-1), 2, 0, p * piece_len, threads=8)
+        inputs.fill(hc.reshape(-1), 2, 2, p * piece_len, threads=8)
+        ref = oracle.innerprod(hb, hc)
+        # 2^26 terms of magnitude <= 1 summed in binary64 in another order than the oracle's
+        assert abs(pieces[p] - ref) <= 1e-12 * max(abs(ref), np.sqrt(piece_len) / 3)
+    lib.distal_innerprod(C, cfg3_B64, a)
+    assert float(a.item()) == full
+
+
+def test_ttm_1024_f64(lib, oracle):
+    import torch
+    I = J = K = 1024
+    L = 256
+    B, C = devgen(3, 0, (I, J, K), np.float64), devgen(3, 1, (K, L), np.float64)
+    A = torch.full((I, J, L), float("nan"), dtype=torch.float64, device="cuda:0")
+    lib.distal_ttm(B, C, A)
+    assert bool(torch.isfinite(A).all())
+    rng = np.random.default_rng(19)
+    fibres = np.arange(0, I * J, 256) + rng.integers(0, 256, I * J // 256)     # every band of 256 rows: every tile
+    hB = host_rows(3, 0, K, fibres, np.float64).reshape(1, -1, K)
+    hC = inputs.tensor(3, 1, (K, L), np.float64)
+    got = A.view(I * J, L)[torch.from_numpy(fibres).cuda()].cpu().numpy()
+    U.assert_close(got, oracle.ttm(hB, hC)[0], np.float64, K)
+    A2 = torch.empty_like(A[:8])
+    lib.distal_ttm(B[:8], C * 2, A2)
+    assert torch.equal(A2, A[:8] * 2)
+
+
+def test_mttkrp_1024_f64(lib, oracle):
+    import torch
+    I = J = K = 1024
+    L = 32
+    B = devgen(4, 0, (I, J, K), np.float64)
+    C, D = devgen(4, 1, (J, L), np.float64), devgen(4, 2, (K, L), np.float64)
+    A = torch.full((I, L), float("nan"), dtype=torch.float64, device="cuda:0")
+    lib.distal_mttkrp(B, C, D, A)
+    assert bool(torch.isfinite(A).all())
+    hC, hD = inputs.tensor(4, 1, (J, L), np.float64), inputs.tensor(4, 2, (K, L), np.float64)
+    rng = np.random.default_rng(20)
+    got = A.cpu().numpy()
+    # two rows of every block of 32 output rows (every row block of every workgroup)
+    for i in np.sort(np.concatenate([np.arange(0, I, 32) + rng.integers(0, 16, I // 32),
+                                     np.arange(0, I, 32) + rng.integers(16, 32, I // 32)])):
+        hB = inputs.values(4, 0, int(i) * J * K, J * K, np.float64).reshape(1, J, K)
+        U.assert_close(got[i:i + 1], oracle.mttkrp(hB, hC, hD), np.float64, J * K)
+    A2 = torch.empty_like(A)
+    lib.distal_mttkrp(B, C, D, A2)
+    assert torch.equal(A, A2)

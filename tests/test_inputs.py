@@ -65,3 +65,15 @@ def test_bad_arguments():
         inputs.values(0, 0, -1, 4, np.float32)
     with pytest.raises(ValueError):
         inputs.values(0, 0, 0, 4, np.float32, "gauss")
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("kind", [inputs.UNIFORM, inputs.SMALLINT])
+def test_torch_generator_reproduces_the_numpy_one(dtype, kind):
+    """The torch-integer form of the generator (used to fill device tensors in place) must give
+    the same bytes as the numpy one, across chunk boundaries and for large indices."""
+    from paper_2203_08069_amd import device_inputs
+    got = device_inputs.generate_on_device(4, 2, (3, 7, 1001), dtype, kind, device="cpu", chunk_elems=5000).numpy()
+    assert np.array_equal(got, inputs.tensor(4, 2, (3, 7, 1001), dtype, kind))
+    big = device_inputs.generate_on_device(9, 0, (1 << 16,), dtype, kind, r=2, device="cpu").numpy()
+    assert np.array_equal(big, inputs.values(9, 0, 0, 1 << 16, dtype, kind, 2))
