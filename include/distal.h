@@ -148,7 +148,7 @@ int distal_ttv_mode(distal_dtype dt, int mode, int64_t I, int64_t J, int64_t K,
  * (evaluation list).  B, C: I x J x K dense.  `a` is a DEVICE pointer to one
  * element of type dt, overwritten.  Products are summed in binary64 for both
  * dtypes (per-block partial sums, then one fixed-order final pass - the
- * on-device part of the paper's "node-level reduction"), and rounded once to dt.
+ * on-device part of the paper's node-level reduction), and rounded once to dt.
  *   workspace: device scratch of at least distal_innerprod_workspace_bytes(...)
  *   bytes, 256-byte aligned.
  */
@@ -186,14 +186,6 @@ int distal_innerprod_noalloc(distal_dtype dt, int64_t I, int64_t J, int64_t K,
  */
 int distal_gemm_plan(distal_dtype dt, int transposed_left, int64_t M, int64_t N, int64_t K, int64_t batch,
                      int tile[3], int *split, int64_t *cut, int rest_tile[3]);
-
-/*
- * Host-only: the output tile (tile_m, tile_n) that workgroup `block` of a contraction launch
- * over tiles_m x tiles_n tiles works on - the very function the kernels call, exposed so that
- * a host test can check that it is a bijection for any grid (band_rows: 4 for tiles taller than
- * wide, 8 otherwise).  Returns a status.
- */
-int distal_gemm_tile_of_block(int band_rows, int block, int tiles_m, int tiles_n, int *tile_m, int *tile_n);
 
 /* Scratch sizes for the calls that take a workspace (0 for invalid arguments). */
 size_t distal_mttkrp_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L);

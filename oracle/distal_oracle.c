@@ -35,8 +35,9 @@
  *                1: A(j,l)   = sum_ik B(i,j,k) * C(i,l) * D(k,l)
  *                2: A(k,l)   = sum_ij B(i,j,k) * C(i,l) * D(j,l)
  *
- * "Variables used only on the right-hand side are sum reductions over their
- * domain" (background section): every sum runs over the full extent.
+ * An index variable that occurs only on the right-hand side is summed over its
+ * whole domain (background section, tensor index notation): every sum below
+ * runs over the full extent of such an index.
  *
  * Layout: dense row-major, last index fastest (evaluation section: inputs are
  * laid out row-major).  gemm alone takes leading dimensions (in elements), as

@@ -26,7 +26,7 @@ STATUS_NAMES = {
 EXPORTS = (
     "distal_gemm", "distal_ttm", "distal_mttkrp", "distal_ttv", "distal_innerprod",
     "distal_ttv_mode", "distal_ttm_mode", "distal_mttkrp_mode", "distal_mttkrp_mode_workspace_bytes",
-    "distal_mttkrp_workspace_bytes", "distal_innerprod_workspace_bytes", "distal_gemm_plan", "distal_gemm_tile_of_block",
+    "distal_mttkrp_workspace_bytes", "distal_innerprod_workspace_bytes", "distal_gemm_plan",
     "distal_status_string", "distal_version", "distal_innerprod_noalloc",
 )
 
@@ -72,8 +72,6 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     ip = ctypes.POINTER(ctypes.c_int)
     lib.distal_gemm_plan.argtypes = [ci, ci, i64, i64, i64, i64, ip, ip, ctypes.POINTER(ctypes.c_int64), ip]
     lib.distal_gemm_plan.restype = ci
-    lib.distal_gemm_tile_of_block.argtypes = [ci, ci, ci, ci, ip, ip]
-    lib.distal_gemm_tile_of_block.restype = ci
     for name in ("distal_gemm", "distal_ttm", "distal_mttkrp", "distal_ttv", "distal_innerprod",
                  "distal_ttm_mode", "distal_mttkrp_mode", "distal_version"):
         getattr(lib, name).restype = ci
@@ -168,13 +166,22 @@ _workspaces = {}
 
 
 def _workspace(device, nbytes: int):
-    """Per-device scratch tensor, grown on demand (torch memory; the library allocates nothing)."""
+    """Scratch tensor of the current stream of `device`, grown on demand (torch memory; the
+    library allocates nothing).  One per (device, stream): calls issued on different streams
+    never share partial sums, and a tensor that is outgrown is only dropped after it has been
+    marked as in use on its stream, so the caching allocator does not hand its block to another
+    stream while kernels may still read it.  Callers who manage streams themselves can pass
+    their own workspace instead."""
     torch = _torch()
     nbytes = max(int(nbytes), 256)
-    ws = _workspaces.get(device)
+    stream = torch.cuda.current_stream(device)
+    key = (device, stream.cuda_stream)
+    ws = _workspaces.get(key)
     if ws is None or ws.numel() < nbytes:
+        if ws is not None:
+            ws.record_stream(stream)
         ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
-        _workspaces[device] = ws
+        _workspaces[key] = ws
     return ws
 
 

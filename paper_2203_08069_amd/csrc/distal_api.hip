@@ -8,6 +8,7 @@
 #include <limits>
 
 #include "../../include/distal.h"
+#include "host_plan.hpp"
 #include "gemm_kernel.hpp"
 #include "mttkrp_kernel.hpp"
 #include "stream_kernels.hpp"
@@ -17,14 +18,7 @@ using namespace distal;
 namespace {
 
 constexpr int kMaxDevices = 64;
-constexpr int kInnerprodMaxBlocks = 2048;   // fixed: the summation order must not depend on the device
-// Workgroups of a streaming launch that gives each a contiguous range: one per compute unit of
-// the part (256), which is what HBM serves fastest; a constant, so results do not depend on the device.
-constexpr int kStreamBlocks = 256;
-constexpr int64_t kComputeUnits = 256;
 constexpr size_t kWorkspaceAlign = 256;
-
-bool mul_ok(int64_t a, int64_t b, int64_t *out) { return !__builtin_mul_overflow(a, b, out); }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -144,100 +138,6 @@ int launch_fill(T *out, int64_t rows, int64_t cols, int64_t ld, hipStream_t stre
 // bases or leading dimensions, N not a multiple of the vector) take the guarded 128 x 128
 // kernel.  A grid that would end in a thin last round is cut into two launches (plan_product).
 
-struct TilePick { int id, bm, bn, bk; double cost; };
-
-// A tile shape the straight-line kernels exist for: its measured relative speed, the
-// wavefronts per SIMD one workgroup brings (wps) and the workgroups of that kernel a compute
-// unit holds (occ).
-struct TileCandidate { int id; bool eligible; int bm, bn, bk; double speed; int wps, occ; };
-
-int tile_candidates(bool f64, bool ta, int64_t M, int64_t N, int64_t K, TileCandidate (&c)[8]) {
-    // tiles with a short side only for an output that is that narrow (rank-sized N, or M under TA)
-    const bool n32 = N <= 32, n64 = N <= 64, m32 = M <= 32, m64 = M <= 64;
-    if (!f64) {
-        c[0] = {1, K >= 1024, 256, 256, ta ? 16 : 32, 1.0, 4, 1};
-        c[1] = {2, K >= 512, 256, 128, 16, 0.973, 2, 2};
-        c[2] = {3, true, 128, 128, 16, 0.95, 1, 4};
-        c[3] = {4, true, 64, 64, 16, 0.81, 1, 8};
-        c[4] = {5, n64, 256, 64, 16, 0.885, 1, 3};
-        c[5] = {6, n32 && K >= 32, 128, 32, 32, 0.626, 1, 3};
-        c[6] = {7, m64, 64, 256, 16, 0.889, 1, 3};
-        c[7] = {8, m32 && K >= 32, 32, 256, 32, 0.637, 1, 2};
-        return 8;
-    }
-    c[0] = {2, K >= 4096, 256, 128, 16, 1.0, 4, 1};
-    c[1] = {3, true, 128, 128, 16, 0.985, 2, 2};
-    c[2] = {4, true, 64, 64, 16, 0.915, 1, 4};
-    c[3] = {5, n64, 128, 64, 16, 0.94, 1, 3};
-    c[4] = {6, n32, 128, 32, 16, 0.697, 1, 3};
-    c[5] = {7, m64, 64, 128, 16, 0.95, 1, 3};
-    c[6] = {8, m32, 32, 256, 16, 0.617, 1, 2};
-    return 7;
-}
-
-// Estimated time of a grid: tiles per compute unit (a partly filled last round counts in full) x
-// tile area / speed; a grid too small to bring a compute unit its four wavefronts per SIMD runs
-// below that speed (measured with one 128 x 128 tile per compute unit: binary64, two wavefronts
-// per SIMD, 0.87; binary32, one, 0.80).
-double rounds_cost(int64_t tiles, const TileCandidate &c) {
-    const int64_t n = (tiles + kComputeUnits - 1) / kComputeUnits;
-    auto fill = [](int64_t wavefronts_per_simd) {
-        return wavefronts_per_simd >= 4 ? 1.0 : (wavefronts_per_simd == 3 ? 0.94 : (wavefronts_per_simd == 2 ? 0.87 : 0.80));
-    };
-    // c.speed was measured on a large grid, i.e. with c.occ workgroups resident
-    const double rel = fill((n < c.occ ? n : c.occ) * c.wps) / fill((int64_t)c.occ * c.wps);
-    return (double)n * (double)(c.bm * c.bn) / (c.speed * rel);
-}
-
-// The tile with the least estimated time for a product run as one launch.
-TilePick pick_tile(bool f64, bool ta, int64_t M, int64_t N, int64_t K, int64_t batch) {
-    TileCandidate cand[8];
-    const int n = tile_candidates(f64, ta, M, N, K, cand);
-    TilePick pick{4, 64, 64, 16, 1e300};
-    for (int i = 0; i < n; ++i) {
-        if (!cand[i].eligible) continue;
-        const int64_t t = ((M + cand[i].bm - 1) / cand[i].bm) * ((N + cand[i].bn - 1) / cand[i].bn) * batch;
-        const double c = rounds_cost(t, cand[i]);
-        if (c < pick.cost) pick = TilePick{cand[i].id, cand[i].bm, cand[i].bn, cand[i].bk, c};   // earlier candidates win ties
-    }
-    return pick;
-}
-
-// A product as at most two launches: the leading rows (or columns) of the output - a whole
-// number of tile rows (columns) whose tiles fill whole rounds of the compute units - with
-// `main`, and what remains, if anything, with the tile that suits it alone; so the part of a
-// grid that would be a thin last round of large tiles runs as a round of small ones.
-// split = 0: one launch; 1: rows [0, cut) and [cut, M); 2: columns [0, cut) and [cut, N).
-struct ProductPlan { TilePick main; int split; int64_t cut; TilePick rest; };
-
-ProductPlan plan_product(bool f64, bool ta, int64_t M, int64_t N, int64_t K, int64_t batch) {
-    ProductPlan plan{pick_tile(f64, ta, M, N, K, batch), 0, 0, TilePick{0, 0, 0, 0, 0.0}};
-    // a second launch costs about 3 us of an otherwise busy part: in units of tile area
-    const double launch_cost = 3e-6 * (f64 ? 78.6e12 : 157.3e12) / (double)kComputeUnits / (2.0 * (double)K);
-    TileCandidate cand[8];
-    const int n = tile_candidates(f64, ta, M, N, K, cand);
-    double best = plan.main.cost;
-    for (int i = 0; i < n; ++i) {
-        if (!cand[i].eligible) continue;
-        const TileCandidate &c = cand[i];
-        const int64_t tm = (M + c.bm - 1) / c.bm, tn = (N + c.bn - 1) / c.bn;
-        const int64_t whole = tm * tn * batch / kComputeUnits * kComputeUnits;     // tiles inside whole rounds
-        for (int split = 1; split <= 2; ++split) {
-            const int64_t per_line = (split == 1 ? tn : tm) * batch;               // tiles per row (column) of tiles
-            const int64_t lines = whole / per_line, cut = lines * (split == 1 ? c.bm : c.bn);
-            if (lines < 1 || cut >= (split == 1 ? M : N)) continue;
-            const TilePick rest = split == 1 ? pick_tile(f64, ta, M - cut, N, K, batch)
-                                             : pick_tile(f64, ta, M, N - cut, K, batch);
-            const double total = rounds_cost(lines * per_line, c) + rest.cost + launch_cost;
-            if (total < 0.97 * best) {                                             // worth a second launch
-                best = total / 0.97;
-                plan = ProductPlan{TilePick{c.id, c.bm, c.bn, c.bk, total}, split, cut, rest};
-            }
-        }
-    }
-    return plan;
-}
-
 // The launch for a tile id of tile_candidates().
 template <typename T, bool TA>
 int launch_by_id(int id, const ContractArgs<T> &a, int64_t batch, hipStream_t stream) {
@@ -334,60 +234,6 @@ size_t elem_size(int dt) { return dt == DISTAL_F64 ? 8 : 4; }
 // part), never of the device, so the summation order is reproducible across devices.
 // Workspace: one partial row of L values per (output row, range, piece), none when that is
 // one row per output row.
-constexpr int64_t kModeTargetBlocks = 768;
-
-struct MttkrpModePlan {
-    int64_t tasks;          // workgroups per range of the walked index
-    int64_t isplit, nsplit; // walked indices per range; ranges (none empty)
-    int64_t nparts;         // partial rows per output row
-    int64_t partial_elems;  // workspace elements (0 when nparts == 1)
-    int64_t nslices, spw, kgroups, rblocks /* blocks of 32 output rows */, rgroups, jgroups, kblocks, tiles_n;
-    bool ok;
-};
-
-MttkrpModePlan mttkrp_mode_plan(int dt, int mode, int64_t I, int64_t J, int64_t K, int64_t L) {
-    MttkrpModePlan p{};
-    const int64_t esz = dt == DISTAL_F64 ? 8 : 4;
-    // a wavefront takes two column tiles of 32 once the rank exceeds 32
-    p.tiles_n = L > 32 ? (L + 63) / 64 : (L + 31) / 32;
-    int64_t out_rows, per_split;
-    if (mode != 2) {                       // kept index r = i (mode 0) or j (mode 1), the other one is walked
-        const int64_t sl = 256 / esz;
-        out_rows = mode == 0 ? I : J;
-        p.nslices = (K + sl - 1) / sl;
-        // four k-slices per workgroup, one per wavefront; a short K gives a workgroup fewer slices
-        // and its other wavefronts further blocks of output rows instead
-        p.spw = p.nslices >= 3 ? 4 : p.nslices;
-        p.kgroups = (p.nslices + p.spw - 1) / p.spw;
-        p.rblocks = (out_rows + 31) / 32;
-        p.rgroups = (p.rblocks + 4 / p.spw - 1) / (4 / p.spw);
-        p.ok = mul_ok(p.kgroups * p.tiles_n, p.rgroups, &p.tasks);
-        per_split = p.nslices;
-    } else {
-        const int64_t kw = 512 / esz;
-        p.kblocks = (K + kw - 1) / kw;
-        p.jgroups = (J + 63) / 64;
-        p.ok = mul_ok(p.kblocks * p.tiles_n, p.jgroups, &p.tasks);
-        per_split = p.jgroups;
-        out_rows = K;
-    }
-    if (!p.ok || p.tasks < 1) { p.ok = false; return p; }
-    const int64_t walked = mode == 0 ? J : I;                 // the index each workgroup walks a range of
-    int64_t want = (kModeTargetBlocks + p.tasks - 1) / p.tasks;
-    if (want > walked) want = walked;
-    if (want < 1) want = 1;
-    p.isplit = (walked + want - 1) / want;
-    p.nsplit = (walked + p.isplit - 1) / p.isplit;
-    int64_t rows;
-    p.ok = mul_ok(p.nsplit, per_split, &p.nparts) && mul_ok(out_rows, p.nparts, &rows) &&
-           mul_ok(rows, L, &p.partial_elems) && p.partial_elems <= INT64_MAX / 16 &&
-           p.nparts <= std::numeric_limits<int>::max();
-    int64_t nblocks;
-    p.ok = p.ok && mul_ok(p.tasks, p.nsplit, &nblocks) && nblocks <= std::numeric_limits<int>::max();
-    if (p.nparts <= 1) p.partial_elems = 0;
-    return p;
-}
-
 // vec: whole aligned k-slices (vector loads); full: every block of output rows and columns is whole
 template <typename T, int LT>
 int launch_walk(const MttkrpWalkArgs<T> &a, unsigned nblocks, bool vec, bool full, hipStream_t stream) {
@@ -476,10 +322,8 @@ template <typename T, int RW, int PU>
 int launch_ttv_rows(int64_t rows, int64_t K, const T *B, const T *c, T *A, hipStream_t stream) {
     constexpr int VEC = 16 / (int)sizeof(T);
     if (K % VEC != 0 || (K / VEC) % (64 * PU) != 0) return DISTAL_ERR_SHAPE;   // the kernel reads whole steps only
-    int64_t per = (rows + kStreamBlocks - 1) / kStreamBlocks;
-    per = (per + 4 * RW - 1) / (4 * RW) * (4 * RW);
-    const unsigned blocks = (unsigned)((rows + per - 1) / per);
-    hipLaunchKernelGGL((ttv_row_kernel<T, RW, PU>), dim3(blocks), dim3(256), 0, stream, B, c, A, rows, K, per);
+    const RangeSplit r = split_ranges(rows, kStreamBlocks, 1, 4 * RW);   // four wavefronts of RW rows per step
+    hipLaunchKernelGGL((ttv_row_kernel<T, RW, PU>), dim3((unsigned)r.blocks), dim3(256), 0, stream, B, c, A, rows, K, r.per);
     return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
 }
 
@@ -568,27 +412,19 @@ int innerprod_t(int64_t n, const T *B, const T *C, T *out, double *partial, hipS
     if (n > 0 && aligned16(B) && aligned16(C)) {
         const int64_t nvec = n / VEC;
         if (nvec > 0) {
-            int64_t blocks = (nvec + 255) / 256;
-            if (blocks > kStreamBlocks) blocks = kStreamBlocks;
-            int64_t per = (nvec + blocks - 1) / blocks;
-            per = (per + 255) / 256 * 256;
-            blocks = (nvec + per - 1) / per;
-            hipLaunchKernelGGL((innerprod_pass1_kernel<T, 4>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                               B, C, partial, nvec, per);
+            const RangeSplit r = split_ranges(nvec, kStreamBlocks, 256, 256);
+            hipLaunchKernelGGL((innerprod_pass1_kernel<T, 4>), dim3((unsigned)r.blocks), dim3(256), 0, stream,
+                               B, C, partial, nvec, r.per);
             if (hipGetLastError() != hipSuccess) return DISTAL_ERR_LAUNCH;
-            nparts = (int)blocks;
+            nparts = (int)r.blocks;
         }
         tail_lo = nvec * VEC;
     } else if (n > 0) {
-        int64_t blocks = (n + 1023) / 1024;
-        if (blocks > kInnerprodMaxBlocks) blocks = kInnerprodMaxBlocks;
-        int64_t per = (n + blocks - 1) / blocks;
-        per = (per + 255) / 256 * 256;
-        blocks = (n + per - 1) / per;
-        hipLaunchKernelGGL(innerprod_pass1_generic_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream,
-                           B, C, partial, n, per);
+        const RangeSplit r = split_ranges(n, kInnerprodMaxBlocks, 1024, 256);
+        hipLaunchKernelGGL(innerprod_pass1_generic_kernel<T>, dim3((unsigned)r.blocks), dim3(256), 0, stream,
+                           B, C, partial, n, r.per);
         if (hipGetLastError() != hipSuccess) return DISTAL_ERR_LAUNCH;
-        nparts = (int)blocks;
+        nparts = (int)r.blocks;
         tail_lo = n;
     }
     hipLaunchKernelGGL(innerprod_pass2_kernel<T>, dim3(1), dim3(256), 0, stream,
@@ -627,7 +463,7 @@ bool tensor_elems(int64_t I, int64_t J, int64_t K, int64_t *n) {
 
 extern "C" {
 
-int distal_version(void) { return 200; }   // 0.2.0: mode-n entry points
+int distal_version(void) { return 300; }   // 0.3.0
 
 const char *distal_status_string(int status) {
     switch (status) {
@@ -778,17 +614,6 @@ int distal_ttv(distal_dtype dt, int64_t I, int64_t J, int64_t K, const void *B, 
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (dt == DISTAL_F64) return ttv_t<double>(rows, K, (const double *)B, (const double *)c, (double *)A, s);
     return ttv_t<float>(rows, K, (const float *)B, (const float *)c, (float *)A, s);
-}
-
-int distal_gemm_tile_of_block(int band_rows, int block, int tiles_m, int tiles_n, int *tile_m, int *tile_n) {
-    if (tiles_m <= 0 || tiles_n <= 0 || (int64_t)tiles_m * tiles_n > std::numeric_limits<int>::max())
-        return DISTAL_ERR_SHAPE;
-    const int nblocks = tiles_m * tiles_n;
-    if (block < 0 || block >= nblocks || (band_rows != 4 && band_rows != 8)) return DISTAL_ERR_SHAPE;
-    if (!tile_m || !tile_n) return DISTAL_ERR_NULL;
-    if (band_rows == 4) tile_of_block<4>(block, nblocks, tiles_m, tiles_n, *tile_m, *tile_n);
-    else tile_of_block<8>(block, nblocks, tiles_m, tiles_n, *tile_m, *tile_n);
-    return DISTAL_OK;
 }
 
 int distal_gemm_plan(distal_dtype dt, int transposed_left, int64_t M, int64_t N, int64_t K, int64_t batch,

@@ -31,6 +31,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "tile_map.hpp"
+
 namespace distal {
 
 typedef double v2d __attribute__((ext_vector_type(2)));
@@ -87,27 +89,6 @@ struct ContractArgs {
     int a_vec_ok, b_vec_ok, c_vec_ok;   // 16-byte vector access is legal on that operand
     int64_t batch_a, batch_b, batch_c;  // element strides between the problems of a batch (blockIdx.y)
 };
-
-// Block id -> output tile.  Hardware hands consecutive workgroup ids to the 8
-// XCDs in turn; give each XCD one contiguous range of logical ids, and walk
-// that range in bands of GROUP_M tile rows so that tiles resident together
-// share A row-panels and B column-panels in that XCD's L2.  GROUP_M is chosen
-// per tile shape so that the tiles resident on one XCD (32 CUs) cover a roughly
-// square patch of C, which minimises the operand bytes per flop that miss L2.
-template <int GROUP_M>
-__host__ __device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m, int tiles_n,
-                                              int &tm, int &tn) {
-    constexpr int NXCD = 8;
-    const int per = nblocks / NXCD, rem = nblocks % NXCD;
-    const int x = bid % NXCD, q = bid / NXCD;
-    const int p = x * per + (x < rem ? x : rem) + q;
-    const int width = GROUP_M * tiles_n;
-    const int g = p / width, r = p % width;
-    const int first = g * GROUP_M;
-    const int gs = (tiles_m - first) < GROUP_M ? (tiles_m - first) : GROUP_M;
-    tm = first + r % gs;
-    tn = r / gs;
-}
 
 template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TA = false>
 struct ContractCfg {

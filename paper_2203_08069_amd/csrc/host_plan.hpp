@@ -1,0 +1,188 @@
+// Host-side launch planning of the leaf-kernel library: which tiles a product runs on, how a
+// grid is cut into launches, how MTTKRP and the streaming kernels split their index ranges, and
+// how large the workspaces are.  Plain C++ with no HIP in it: the library includes it, and so
+// does a host-only test program that is built with the address and undefined-behaviour
+// sanitizers and fuzzes the extents.  Every plan is a function of the extents only, never of
+// the device, so summation orders and results are reproducible across devices.
+#pragma once
+#include <stdint.h>
+
+#include <limits>
+
+#include "tile_map.hpp"
+
+namespace distal {
+
+constexpr int kInnerprodMaxBlocks = 2048;   // partial sums the inner product's workspace holds
+// Workgroups of a streaming launch that gives each a contiguous range: one per compute unit of
+// the part (256), which is what HBM serves fastest; a constant, so results do not depend on the device.
+constexpr int kStreamBlocks = 256;
+constexpr int64_t kComputeUnits = 256;
+
+inline bool mul_ok(int64_t a, int64_t b, int64_t *out) { return !__builtin_mul_overflow(a, b, out); }
+
+// ---- streaming kernels: contiguous index ranges per workgroup ---------------------------------
+// n items over at most max_blocks workgroups of at least min_per items each: workgroup b owns
+// [b * per, min((b + 1) * per, n)), per a multiple of `granule`; no range is empty.
+struct RangeSplit { int64_t per, blocks; };
+
+inline RangeSplit split_ranges(int64_t n, int64_t max_blocks, int64_t min_per, int64_t granule) {
+    if (n <= 0) return RangeSplit{granule, 0};
+    int64_t blocks = (n - 1) / min_per + 1;
+    if (blocks > max_blocks) blocks = max_blocks;
+    int64_t per = (n - 1) / blocks + 1;
+    per = ((per - 1) / granule + 1) * granule;
+    return RangeSplit{per, (n - 1) / per + 1};
+}
+
+// ---- matrix products: tile choice and the cut into two launches ------------------------------
+struct TilePick { int id, bm, bn, bk; double cost; };
+
+// A tile shape the straight-line kernels exist for: its measured relative speed, the
+// wavefronts per SIMD one workgroup brings (wps) and the workgroups of that kernel a compute
+// unit holds (occ).
+struct TileCandidate { int id; bool eligible; int bm, bn, bk; double speed; int wps, occ; };
+
+inline int tile_candidates(bool f64, bool ta, int64_t M, int64_t N, int64_t K, TileCandidate (&c)[8]) {
+    // tiles with a short side only for an output that is that narrow (rank-sized N, or M under TA)
+    const bool n32 = N <= 32, n64 = N <= 64, m32 = M <= 32, m64 = M <= 64;
+    if (!f64) {
+        c[0] = {1, K >= 1024, 256, 256, ta ? 16 : 32, 1.0, 4, 1};
+        c[1] = {2, K >= 512, 256, 128, 16, 0.973, 2, 2};
+        c[2] = {3, true, 128, 128, 16, 0.95, 1, 4};
+        c[3] = {4, true, 64, 64, 16, 0.81, 1, 8};
+        c[4] = {5, n64, 256, 64, 16, 0.885, 1, 3};
+        c[5] = {6, n32 && K >= 32, 128, 32, 32, 0.626, 1, 3};
+        c[6] = {7, m64, 64, 256, 16, 0.889, 1, 3};
+        c[7] = {8, m32 && K >= 32, 32, 256, 32, 0.637, 1, 2};
+        return 8;
+    }
+    c[0] = {2, K >= 4096, 256, 128, 16, 1.0, 4, 1};
+    c[1] = {3, true, 128, 128, 16, 0.985, 2, 2};
+    c[2] = {4, true, 64, 64, 16, 0.915, 1, 4};
+    c[3] = {5, n64, 128, 64, 16, 0.94, 1, 3};
+    c[4] = {6, n32, 128, 32, 16, 0.697, 1, 3};
+    c[5] = {7, m64, 64, 128, 16, 0.95, 1, 3};
+    c[6] = {8, m32, 32, 256, 16, 0.617, 1, 2};
+    return 7;
+}
+
+// Estimated time of a grid: tiles per compute unit (a partly filled last round counts in full) x
+// tile area / speed; a grid too small to bring a compute unit its four wavefronts per SIMD runs
+// below that speed (measured with one 128 x 128 tile per compute unit: binary64, two wavefronts
+// per SIMD, 0.87; binary32, one, 0.80).
+inline double rounds_cost(int64_t tiles, const TileCandidate &c) {
+    const int64_t n = (tiles + kComputeUnits - 1) / kComputeUnits;
+    auto fill = [](int64_t wavefronts_per_simd) {
+        return wavefronts_per_simd >= 4 ? 1.0 : (wavefronts_per_simd == 3 ? 0.94 : (wavefronts_per_simd == 2 ? 0.87 : 0.80));
+    };
+    // c.speed was measured on a large grid, i.e. with c.occ workgroups resident
+    const double rel = fill((n < c.occ ? n : c.occ) * c.wps) / fill((int64_t)c.occ * c.wps);
+    return (double)n * (double)(c.bm * c.bn) / (c.speed * rel);
+}
+
+// The tile with the least estimated time for a product run as one launch.
+inline TilePick pick_tile(bool f64, bool ta, int64_t M, int64_t N, int64_t K, int64_t batch) {
+    TileCandidate cand[8];
+    const int n = tile_candidates(f64, ta, M, N, K, cand);
+    TilePick pick{4, 64, 64, 16, 1e300};
+    for (int i = 0; i < n; ++i) {
+        if (!cand[i].eligible) continue;
+        const int64_t t = ((M + cand[i].bm - 1) / cand[i].bm) * ((N + cand[i].bn - 1) / cand[i].bn) * batch;
+        const double c = rounds_cost(t, cand[i]);
+        if (c < pick.cost) pick = TilePick{cand[i].id, cand[i].bm, cand[i].bn, cand[i].bk, c};   // earlier candidates win ties
+    }
+    return pick;
+}
+
+// A product as at most two launches: the leading rows (or columns) of the output - a whole
+// number of tile rows (columns) whose tiles fill whole rounds of the compute units - with
+// `main`, and what remains, if anything, with the tile that suits it alone; so the part of a
+// grid that would be a thin last round of large tiles runs as a round of small ones.
+// split = 0: one launch; 1: rows [0, cut) and [cut, M); 2: columns [0, cut) and [cut, N).
+struct ProductPlan { TilePick main; int split; int64_t cut; TilePick rest; };
+
+inline ProductPlan plan_product(bool f64, bool ta, int64_t M, int64_t N, int64_t K, int64_t batch) {
+    ProductPlan plan{pick_tile(f64, ta, M, N, K, batch), 0, 0, TilePick{0, 0, 0, 0, 0.0}};
+    // a second launch costs about 3 us of an otherwise busy part: in units of tile area
+    const double launch_cost = 3e-6 * (f64 ? 78.6e12 : 157.3e12) / (double)kComputeUnits / (2.0 * (double)K);
+    TileCandidate cand[8];
+    const int n = tile_candidates(f64, ta, M, N, K, cand);
+    double best = plan.main.cost;
+    for (int i = 0; i < n; ++i) {
+        if (!cand[i].eligible) continue;
+        const TileCandidate &c = cand[i];
+        const int64_t tm = (M + c.bm - 1) / c.bm, tn = (N + c.bn - 1) / c.bn;
+        const int64_t whole = tm * tn * batch / kComputeUnits * kComputeUnits;     // tiles inside whole rounds
+        for (int split = 1; split <= 2; ++split) {
+            const int64_t per_line = (split == 1 ? tn : tm) * batch;               // tiles per row (column) of tiles
+            const int64_t lines = whole / per_line, cut = lines * (split == 1 ? c.bm : c.bn);
+            if (lines < 1 || cut >= (split == 1 ? M : N)) continue;
+            const TilePick rest = split == 1 ? pick_tile(f64, ta, M - cut, N, K, batch)
+                                             : pick_tile(f64, ta, M, N - cut, K, batch);
+            const double total = rounds_cost(lines * per_line, c) + rest.cost + launch_cost;
+            if (total < 0.97 * best) {                                             // worth a second launch
+                best = total / 0.97;
+                plan = ProductPlan{TilePick{c.id, c.bm, c.bn, c.bk, total}, split, cut, rest};
+            }
+        }
+    }
+    return plan;
+}
+
+// ---- MTTKRP: ranges of the walked index and partial rows --------------------------------------
+constexpr int64_t kModeTargetBlocks = 768;
+
+struct MttkrpModePlan {
+    int64_t tasks;          // workgroups per range of the walked index
+    int64_t isplit, nsplit; // walked indices per range; ranges (none empty)
+    int64_t nparts;         // partial rows per output row
+    int64_t partial_elems;  // workspace elements (0 when nparts == 1)
+    int64_t nslices, spw, kgroups, rblocks /* blocks of 32 output rows */, rgroups, jgroups, kblocks, tiles_n;
+    bool ok;
+};
+
+inline MttkrpModePlan mttkrp_mode_plan(int dt, int mode, int64_t I, int64_t J, int64_t K, int64_t L) {
+    MttkrpModePlan p{};
+    const int64_t esz = dt == 1 /* binary64 */ ? 8 : 4;
+    // a wavefront takes two column tiles of 32 once the rank exceeds 32
+    p.tiles_n = L > 32 ? (L + 63) / 64 : (L + 31) / 32;
+    int64_t out_rows, per_split;
+    if (mode != 2) {                       // kept index r = i (mode 0) or j (mode 1), the other one is walked
+        const int64_t sl = 256 / esz;
+        out_rows = mode == 0 ? I : J;
+        p.nslices = (K + sl - 1) / sl;
+        // four k-slices per workgroup, one per wavefront; a short K gives a workgroup fewer slices
+        // and its other wavefronts further blocks of output rows instead
+        p.spw = p.nslices >= 3 ? 4 : p.nslices;
+        p.kgroups = (p.nslices + p.spw - 1) / p.spw;
+        p.rblocks = (out_rows + 31) / 32;
+        p.rgroups = (p.rblocks + 4 / p.spw - 1) / (4 / p.spw);
+        p.ok = mul_ok(p.kgroups * p.tiles_n, p.rgroups, &p.tasks);
+        per_split = p.nslices;
+    } else {
+        const int64_t kw = 512 / esz;
+        p.kblocks = (K + kw - 1) / kw;
+        p.jgroups = (J + 63) / 64;
+        p.ok = mul_ok(p.kblocks * p.tiles_n, p.jgroups, &p.tasks);
+        per_split = p.jgroups;
+        out_rows = K;
+    }
+    if (!p.ok || p.tasks < 1) { p.ok = false; return p; }
+    const int64_t walked = mode == 0 ? J : I;                 // the index each workgroup walks a range of
+    int64_t want = (kModeTargetBlocks + p.tasks - 1) / p.tasks;
+    if (want > walked) want = walked;
+    if (want < 1) want = 1;
+    p.isplit = (walked + want - 1) / want;
+    p.nsplit = (walked + p.isplit - 1) / p.isplit;
+    int64_t rows;
+    p.ok = mul_ok(p.nsplit, per_split, &p.nparts) && mul_ok(out_rows, p.nparts, &rows) &&
+           mul_ok(rows, L, &p.partial_elems) && p.partial_elems <= INT64_MAX / 16 &&
+           p.nparts <= std::numeric_limits<int>::max();
+    int64_t nblocks;
+    p.ok = p.ok && mul_ok(p.tasks, p.nsplit, &nblocks) && nblocks <= std::numeric_limits<int>::max();
+    if (p.nparts <= 1) p.partial_elems = 0;
+    return p;
+}
+
+}  // namespace distal

@@ -241,26 +241,6 @@ def test_gemm_plan_choice(lib):
     assert lib.distal_gemm_plan(0, 0, 8, 8, 8, 1, None, None, None, None) == 1
 
 
-def test_block_to_tile_map_is_a_bijection(lib):
-    """Every workgroup of a contraction launch gets a tile inside the grid and no two get the same
-    one - for whole and ragged grids, fewer blocks than XCDs, single rows and columns (the kernels
-    call this very function; a tile outside the grid would be an out-of-bounds tile)."""
-    tm, tn = ctypes.c_int(), ctypes.c_int()
-    grids = [(1, 1), (1, 7), (7, 1), (2, 3), (3, 5), (8, 8), (9, 9), (16, 1), (1, 16), (17, 33), (33, 17),
-             (32, 64), (64, 32), (5, 128), (128, 5), (31, 63), (4, 2), (12, 20)]
-    for band in (4, 8):
-        for tiles_m, tiles_n in grids:
-            seen = set()
-            for b in range(tiles_m * tiles_n):
-                assert lib.distal_gemm_tile_of_block(band, b, tiles_m, tiles_n, ctypes.byref(tm), ctypes.byref(tn)) == 0
-                assert 0 <= tm.value < tiles_m and 0 <= tn.value < tiles_n, (band, tiles_m, tiles_n, b)
-                seen.add((tm.value, tn.value))
-            assert len(seen) == tiles_m * tiles_n, (band, tiles_m, tiles_n)
-    assert lib.distal_gemm_tile_of_block(8, 6, 2, 3, ctypes.byref(tm), ctypes.byref(tn)) == 2
-    assert lib.distal_gemm_tile_of_block(5, 0, 2, 3, ctypes.byref(tm), ctypes.byref(tn)) == 2
-    assert lib.distal_gemm_tile_of_block(8, 0, 2, 3, None, None) == 1
-
-
 def test_gemm_plan_invariants_on_random_extents(lib):
     """Whatever the extents: tiles come from the dtype's set, narrow tiles only serve narrow outputs,
     slabs are no deeper than K allows the kernels to start (K >= BK or the guarded kernel is used),
@@ -350,3 +330,9 @@ def test_probe_library_exports_and_argument_errors():
     assert f(32, 8, 256, None, b, 1, c, 1 << 30, None) == 1
     assert f(32, 8, 256, P(FAKE + 4), b, 1, c, 1 << 30, None) == 4
     assert f(32, 8, 256, a, b, 1, c, 16, None) == 6
+
+
+def test_package_and_library_versions_agree(lib):
+    import paper_2203_08069_amd as pkg
+    major, minor, patch = (int(x) for x in pkg.__version__.split()[0].strip('"').split("."))
+    assert lib.distal_version() == major * 10000 + minor * 100 + patch
