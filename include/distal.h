@@ -171,9 +171,12 @@ int distal_innerprod_noalloc(distal_dtype dt, int64_t I, int64_t J, int64_t K,
                              const void *B, const void *C, void *a, void *stream);
 
 /*
- * Host-only query (no device work): how the library runs C = A * B with these extents when the
- * operands are 16-byte aligned (K >= 16, N and the leading dimensions multiples of 16 bytes;
- * other operands take the bounds-checked 128 x 128 kernel whatever this returns).  TTM is such a
+ * Host-only query (no device work): how the library runs C = A * B with these extents (K >= 16).
+ * Bases and leading dimensions need no alignment.  What the plan covers is the part of the
+ * output whose 16-byte pieces do not straddle an edge: all but the last N % (16 / sizeof dt)
+ * columns (those few run as a streaming matrix-vector kernel) and, with a transposed left
+ * operand, all but the last M % (16 / sizeof dt) rows (bounds-checked kernel); pass the
+ * extents of that part.  K < 16 takes the bounds-checked 128 x 128 kernel.  TTM is such a
  * product: mode 2 is M = I*J, N = L; mode 0 is transposed_left with M = R, N = J*K, K = I;
  * mode 1 the same with batch = I, N = K, K = J.
  *   tile      = {BM, BN, BK}: tile and slab depth of the (first) launch

@@ -202,20 +202,47 @@ int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
     a.a_vec_ok = aligned16(A) && lda % VEC == 0 && stride_a % VEC == 0;
     a.b_vec_ok = aligned16(B) && ldb % VEC == 0 && stride_b % VEC == 0;
     a.c_vec_ok = aligned16(C) && ldc % VEC == 0 && stride_c % VEC == 0;
-    // the straight-line kernels need 16-byte pieces that never straddle an edge of an operand
-    const bool pieces = a.a_vec_ok && a.b_vec_ok && a.c_vec_ok && N % VEC == 0 && (!TA || M % VEC == 0);
-    if (!pieces || K < 16) return launch_contract<T, 128, 128, 16, 2, 2, kGuarded, TA>(a, batch, stream);
-    const ProductPlan plan = plan_product(sizeof(T) == 8, TA, M, N, K, batch);
+    if (K < 16) return launch_contract<T, 128, 128, 16, 2, 2, kGuarded, TA>(a, batch, stream);
+    // The straight-line kernels move 16-byte pieces that must not straddle an edge of an operand
+    // (alignment does not matter: their global accesses are only element-aligned).  The trailing
+    // N % VEC columns - and, with a transposed left operand, the trailing M % VEC rows - are
+    // therefore peeled off: the columns go to a streaming kernel, the rows to the guarded one.
+    const int64_t nfr = N % VEC, mfr = TA ? M % VEC : 0;
+    const int64_t Nm = N - nfr, Mm = M - mfr;
+    if (nfr > 0) {
+        int64_t blocks = TA ? (M + 255) / 256 : (M + 15) / 16;
+        if (blocks > (1 << 20)) blocks = 1 << 20;
+        for (int64_t n = 0; n < batch; ++n) {
+            hipLaunchKernelGGL((gemm_fringe_cols_kernel<T, TA>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                               A + n * stride_a, lda, B + n * stride_b + Nm, ldb, C + n * stride_c + Nm, ldc,
+                               M, K, (int)nfr, a.accumulate);
+            if (hipGetLastError() != hipSuccess) return DISTAL_ERR_LAUNCH;
+        }
+        if (Nm == 0) return DISTAL_OK;
+    }
+    if (mfr > 0) {
+        ContractArgs<T> r = a;                   // rows [Mm, M) x columns [0, Nm)
+        r.A += Mm;
+        r.C += Mm * ldc;
+        r.M = mfr;
+        r.N = Nm;
+        r.a_vec_ok = r.c_vec_ok = 0;
+        const int rc = launch_contract<T, 128, 128, 16, 2, 2, kGuarded, TA>(r, batch, stream);
+        if (rc != DISTAL_OK || Mm == 0) return rc;
+    }
+    a.M = Mm;
+    a.N = Nm;
+    const ProductPlan plan = plan_product(sizeof(T) == 8, TA, Mm, Nm, K, batch);
     if (plan.split == 0) return launch_by_id<T, TA>(plan.main.id, a, batch, stream);
-    ContractArgs<T> first = a, second = a;       // the cut is a multiple of 32: alignment is unchanged
+    ContractArgs<T> first = a, second = a;
     if (plan.split == 1) {
         first.M = plan.cut;
-        second.M = M - plan.cut;
+        second.M = Mm - plan.cut;
         second.A += TA ? plan.cut : plan.cut * lda;
         second.C += plan.cut * ldc;
     } else {
         first.N = plan.cut;
-        second.N = N - plan.cut;
+        second.N = Nm - plan.cut;
         second.B += plan.cut;
         second.C += plan.cut;
     }

@@ -48,6 +48,13 @@ template <> struct VecOf<float, 1> { typedef float type; };
 template <> struct VecOf<float, 2> { typedef v2f type; };
 template <> struct VecOf<float, 4> { typedef v4f type; };
 
+// The same vectors as they sit in global memory: only element-aligned.  Operands may be views
+// whose base or leading dimension is not a multiple of 16 bytes; the hardware serves such
+// accesses with the same wide instruction, so the kernels make no alignment promise for them.
+template <typename T, int N> struct GlobalVecOf {
+    typedef typename VecOf<T, N>::type type __attribute__((aligned(sizeof(T))));
+};
+
 // Fused multiply-add in the element type (the unsuffixed builtin is binary64 only).
 __device__ __forceinline__ float fma_t(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
 __device__ __forceinline__ double fma_t(double a, double b, double c) { return __builtin_fma(a, b, c); }
@@ -415,6 +422,8 @@ contract_fast_kernel(ContractArgs<T> args) {
     typedef Mfma<T> MF;
     typedef typename VecOf<T, Cfg::VEC>::type vec_t;
     typedef typename VecOf<T, Cfg::CV>::type cvec_t;
+    typedef typename GlobalVecOf<T, Cfg::VEC>::type gvec_t;
+    typedef typename GlobalVecOf<T, Cfg::CV>::type gcvec_t;
     constexpr int VEC = Cfg::VEC, KG = Cfg::KG, MI = Cfg::MI, NI = Cfg::NI;
     constexpr int CV = Cfg::CV, NG = Cfg::NG, NT = Cfg::NT, NKG = BK / KG;
     constexpr int ARL = Cfg::A_ROWLEN / VEC;          // 16-byte pieces per staged A row
@@ -466,15 +475,16 @@ contract_fast_kernel(ContractArgs<T> args) {
 
     vec_t ra[Cfg::A_PER_T], rb[Cfg::B_PER_T];
     // slab index past the end is clamped to the last slab: a redundant, in-bounds reload
-    auto load_global = [&](int64_t t) {
+    auto load_into = [&](vec_t (&xa)[Cfg::A_PER_T], vec_t (&xb)[Cfg::B_PER_T], int64_t t) {
         const int64_t k0 = (t < nk ? t : nk - 1) * BK;
         const T *ap = args.A + (TA ? k0 * args.lda : k0);
         const T *bp = args.B + k0 * args.ldb;
 #pragma unroll
-        for (int p = 0; p < Cfg::A_PER_T; ++p) ra[p] = *reinterpret_cast<const vec_t *>(ap + a_off[p]);
+        for (int p = 0; p < Cfg::A_PER_T; ++p) xa[p] = *reinterpret_cast<const gvec_t *>(ap + a_off[p]);
 #pragma unroll
-        for (int p = 0; p < Cfg::B_PER_T; ++p) rb[p] = *reinterpret_cast<const vec_t *>(bp + b_off[p]);
+        for (int p = 0; p < Cfg::B_PER_T; ++p) xb[p] = *reinterpret_cast<const gvec_t *>(bp + b_off[p]);
     };
+    auto load_global = [&](int64_t t) { load_into(ra, rb, t); };
     auto store_lds = [&](int stage) {
         T *st = lds + stage * Cfg::STAGE_ELEMS;
 #pragma unroll
@@ -499,7 +509,7 @@ contract_fast_kernel(ContractArgs<T> args) {
                     if constexpr (CV == 1) {
                         acc[mi][g][v] = inside ? *cp : T(0);
                     } else {
-                        const cvec_t o = inside ? *reinterpret_cast<const cvec_t *>(cp) : cvec_t(T(0));
+                        const cvec_t o = inside ? *reinterpret_cast<const gcvec_t *>(cp) : cvec_t(T(0));
 #pragma unroll
                         for (int q = 0; q < CV; ++q) acc[mi][g * CV + q][v] = o[q];
                     }
@@ -542,12 +552,12 @@ contract_fast_kernel(ContractArgs<T> args) {
             for (int p = 0; p < Cfg::A_PER_T; ++p) {
                 const int v = tid + p * NT, r = v / ARL, kv = v % ARL;
                 const bool valid = TA ? r < tail : kv * VEC < tail;
-                ra[p] = valid ? *reinterpret_cast<const vec_t *>(ap + a_off[p]) : vec_t(T(0));
+                ra[p] = valid ? *reinterpret_cast<const gvec_t *>(ap + a_off[p]) : vec_t(T(0));
             }
 #pragma unroll
             for (int p = 0; p < Cfg::B_PER_T; ++p) {
                 const int r = (tid + p * NT) / (BN / VEC);
-                rb[p] = r < tail ? *reinterpret_cast<const vec_t *>(bp + b_off[p]) : vec_t(T(0));
+                rb[p] = r < tail ? *reinterpret_cast<const gvec_t *>(bp + b_off[p]) : vec_t(T(0));
             }
             store_lds(0);
             __syncthreads();
@@ -555,7 +565,10 @@ contract_fast_kernel(ContractArgs<T> args) {
         }
     }
 
-    // epilogue: accumulators -> C, CV neighbouring columns per store
+    // epilogue: accumulators -> C, CV neighbouring columns per store.  (Under `accumulate` each
+    // old vector is fetched right before its add; requesting them in batches ahead of the adds
+    // measured 2-3 % slower on the shallow k-steps it was meant for: the other workgroup on the
+    // compute unit hides the waits, and the burst only adds contention.)
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -574,8 +587,8 @@ contract_fast_kernel(ContractArgs<T> args) {
                 } else {
 #pragma unroll
                     for (int q = 0; q < CV; ++q) o[q] = acc[mi][g * CV + q][v];
-                    if (!ACC_INIT && args.accumulate) o += *reinterpret_cast<const cvec_t *>(cp);
-                    *reinterpret_cast<cvec_t *>(cp) = o;
+                    if (!ACC_INIT && args.accumulate) o += *reinterpret_cast<const gcvec_t *>(cp);
+                    *reinterpret_cast<gcvec_t *>(cp) = o;
                 }
             }
 }

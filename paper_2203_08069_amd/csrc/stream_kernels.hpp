@@ -480,6 +480,55 @@ innerprod_pass2_kernel(const double *__restrict__ partial, int nparts,
     }
 }
 
+// ---------------------------------------------------------------------------
+// The last one to three columns of a matrix product, C(i, j) = [C(i, j) +] sum_k A(i,k) B(k,j)
+// for j < ncols: the columns whose 16-byte piece would straddle the right edge of B and C when N
+// is not a multiple of the vector.  The contraction kernels run the columns before them; these
+// few are a matrix-vector product per column, i.e. one stream over the left operand.
+//   TA = false: A is M x K; 16 lanes share a row and stride over k, then add up.
+//   TA = true : the left operand is stored K x M; a lane owns a row i and walks k
+//               (neighbouring lanes read neighbouring elements).
+// B and C point at the first of the ncols columns.
+// ---------------------------------------------------------------------------
+template <typename T, bool TA>
+__global__ void __launch_bounds__(256)
+gemm_fringe_cols_kernel(const T *__restrict__ A, int64_t lda, const T *__restrict__ B, int64_t ldb,
+                        T *__restrict__ C, int64_t ldc, int64_t M, int64_t K, int ncols, int accumulate) {
+    if constexpr (!TA) {
+        const int q = threadIdx.x & 15;
+        const int64_t stride = (int64_t)gridDim.x * 16;
+        for (int64_t i = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4); i < M; i += stride) {
+            const T *row = A + i * lda;
+            T acc[3] = {T(0), T(0), T(0)};
+            for (int64_t k = q; k < K; k += 16) {
+                const T a = row[k];
+#pragma unroll
+                for (int c = 0; c < 3; ++c)
+                    if (c < ncols) acc[c] = fma_t(a, B[k * ldb + c], acc[c]);
+            }
+#pragma unroll
+            for (int c = 0; c < 3; ++c) {
+                const T s = sum16(acc[c]);
+                if (q == 0 && c < ncols) C[i * ldc + c] = accumulate ? C[i * ldc + c] + s : s;
+            }
+        }
+    } else {
+        const int64_t stride = (int64_t)gridDim.x * 256;
+        for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < M; i += stride) {
+            T acc[3] = {T(0), T(0), T(0)};
+            for (int64_t k = 0; k < K; ++k) {
+                const T a = A[k * lda + i];
+#pragma unroll
+                for (int c = 0; c < 3; ++c)
+                    if (c < ncols) acc[c] = fma_t(a, B[k * ldb + c], acc[c]);
+            }
+#pragma unroll
+            for (int c = 0; c < 3; ++c)
+                if (c < ncols) C[i * ldc + c] = accumulate ? C[i * ldc + c] + acc[c] : acc[c];
+        }
+    }
+}
+
 // Row-strided fill, used where an empty sum must still define its output.
 template <typename T>
 __global__ void __launch_bounds__(256)
