@@ -146,7 +146,10 @@ def test_ttm_mode0_ragged_edge_tiles(lib, oracle, dtype, kind, I, J, K, R):
 # and 1, there also as a batch), whole and in their edge-clamping form, with trailing K terms
 NARROW_TTM = [(2, 256, 256, 64, 32), (2, 256, 255, 72, 24), (2, 256, 256, 64, 64),
               (0, 64, 256, 256, 32), (0, 60, 250, 260, 24), (0, 64, 256, 256, 64),
-              (1, 128, 64, 512, 32), (1, 256, 72, 256, 64)]
+              (1, 128, 64, 512, 32), (1, 256, 72, 256, 64),
+              # a rank or a kept extent that is not a multiple of the 16-byte vector: the trailing rows of
+              # the transposed form go to the bounds-checked kernel, the trailing columns to the streaming one
+              (0, 64, 256, 256, 33), (1, 128, 64, 512, 31), (1, 64, 64, 257, 32), (0, 64, 15, 17, 34), (2, 64, 250, 66, 29)]
 
 
 @pytest.mark.parametrize("dtype", DT)

@@ -156,6 +156,30 @@ def test_gemm_strided_views_accumulate(lib, oracle, dtype, kind, off):
 
 @pytest.mark.parametrize("dtype", DT)
 @pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("accumulate", [False, True])
+@pytest.mark.parametrize("M,N,K,offs", [(300, 259, 96, (1, 3, 2)), (257, 513, 528, (0, 1, 3)), (520, 130, 1040, (3, 0, 1)),
+                                        (129, 3, 64, (1, 1, 1)), (64, 1027, 48, (2, 2, 0))])
+def test_gemm_each_operand_misaligned_differently_and_odd_n(lib, oracle, dtype, kind, accumulate, M, N, K, offs):
+    """Views whose bases sit at different element offsets from a 16-byte boundary, with row
+    strides that are not multiples of the vector and N not a multiple of it: the straight-line
+    kernels take all of it but the last N % vector columns, which a streaming kernel computes.
+    Nothing outside the output block may be written."""
+    oa, ob, oc = offs
+    big_a, big_b = U.gen(17, 0, (M + 2, K + oa + 5), dtype, kind), U.gen(17, 1, (K + 1, N + ob + 3), dtype, kind)
+    big_c = U.gen(17, 2, (M + 2, N + oc + 6), dtype, kind)
+    dA, dB, dC = U.dev(big_a), U.dev(big_b), U.dev(big_c)
+    sa, sb, sc = (slice(1, 1 + M), slice(oa, oa + K)), (slice(1, 1 + K), slice(ob, ob + N)), (slice(2, 2 + M), slice(oc, oc + N))
+    ref = oracle.gemm(big_a[sa], big_b[sb], init=big_c[sc] if accumulate else None)
+    lib.distal_gemm(dA[sa], dB[sb], dC[sc], accumulate=accumulate)
+    out = U.host(dC)
+    compare(out[sc], ref, dtype, kind, K + 1)
+    mask = np.ones_like(big_c, dtype=bool)
+    mask[sc] = False
+    assert np.array_equal(out[mask], big_c[mask])
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("kind", KINDS)
 @pytest.mark.parametrize("M,N,K", [(300, 200, 101), (520, 264, 1029), (64, 64, 17)])
 def test_gemm_k_not_a_multiple_of_the_vector(lib, oracle, dtype, kind, M, N, K):
     """A is the leading K columns of a wider, aligned matrix: its 16-byte pieces would straddle the
