@@ -210,12 +210,17 @@ int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
     const int64_t nfr = N % VEC, mfr = TA ? M % VEC : 0;
     const int64_t Nm = N - nfr, Mm = M - mfr;
     if (nfr > 0) {
-        int64_t blocks = TA ? (M + 255) / 256 : (M + 15) / 16;
+        int64_t blocks = TA ? (M + 255) / 256 : (M + 31) / 32;
         if (blocks > (1 << 20)) blocks = 1 << 20;
         for (int64_t n = 0; n < batch; ++n) {
-            hipLaunchKernelGGL((gemm_fringe_cols_kernel<T, TA>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                               A + n * stride_a, lda, B + n * stride_b + Nm, ldb, C + n * stride_c + Nm, ldc,
-                               M, K, (int)nfr, a.accumulate);
+            if constexpr (TA)
+                hipLaunchKernelGGL(gemm_fringe_cols_ta_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                                   A + n * stride_a, lda, B + n * stride_b + Nm, ldb, C + n * stride_c + Nm, ldc,
+                                   M, K, (int)nfr, a.accumulate);
+            else
+                hipLaunchKernelGGL(gemm_fringe_cols_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                                   A + n * stride_a, lda, B + n * stride_b + Nm, ldb, C + n * stride_c + Nm, ldc,
+                                   M, K, (int)nfr, a.accumulate);
             if (hipGetLastError() != hipSuccess) return DISTAL_ERR_LAUNCH;
         }
         if (Nm == 0) return DISTAL_OK;
@@ -423,8 +428,12 @@ int ttv_left_t(int64_t batch, int64_t R, int64_t N, const T *B, const T *c, T *A
         hipLaunchKernelGGL((ttv_left_wide_kernel<T, 4, 4>),
                            dim3((unsigned)(wide_groups < (1 << 22) ? wide_groups : (1 << 22))), dim3(256), 0,
                            stream, B, c, A, batch, R, N);
-    else if (vec)
+    else if (vec) {
+        // long walks over many output pieces: one workgroup per compute unit, each taking several
+        // 4 KiB column strips in turn (1024^3 along mode 1: +1 % in binary32, +4 % in binary64)
+        if (blocks >= 4 * kStreamBlocks && R >= 256) blocks = kStreamBlocks;
         hipLaunchKernelGGL((ttv_left_vec_kernel<T, 8>), dim3((unsigned)blocks), dim3(256), 0, stream, B, c, A, batch, R, N);
+    }
     else
         hipLaunchKernelGGL(ttv_left_generic_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream, B, c, A, batch, R, N);
     return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;

@@ -485,47 +485,107 @@ innerprod_pass2_kernel(const double *__restrict__ partial, int nparts,
 // for j < ncols: the columns whose 16-byte piece would straddle the right edge of B and C when N
 // is not a multiple of the vector.  The contraction kernels run the columns before them; these
 // few are a matrix-vector product per column, i.e. one stream over the left operand.
-//   TA = false: A is M x K; 16 lanes share a row and stride over k, then add up.
-//   TA = true : the left operand is stored K x M; a lane owns a row i and walks k
-//               (neighbouring lanes read neighbouring elements).
 // B and C point at the first of the ncols columns.
+//
+// gemm_fringe_cols_kernel (A is M x K): a workgroup owns 32 rows, 16 lanes share a row (two rows
+// per lane group, four 16-byte loads of each in flight) and the columns of B are staged in LDS
+// 2048 values of k at a time, so the only HBM stream is A itself.
+// gemm_fringe_cols_ta_kernel (the left operand is stored K x M): a lane owns a row i and walks k;
+// neighbouring lanes read neighbouring elements.
 // ---------------------------------------------------------------------------
-template <typename T, bool TA>
+template <typename T>
 __global__ void __launch_bounds__(256)
 gemm_fringe_cols_kernel(const T *__restrict__ A, int64_t lda, const T *__restrict__ B, int64_t ldb,
                         T *__restrict__ C, int64_t ldc, int64_t M, int64_t K, int ncols, int accumulate) {
-    if constexpr (!TA) {
-        const int q = threadIdx.x & 15;
-        const int64_t stride = (int64_t)gridDim.x * 16;
-        for (int64_t i = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4); i < M; i += stride) {
-            const T *row = A + i * lda;
-            T acc[3] = {T(0), T(0), T(0)};
-            for (int64_t k = q; k < K; k += 16) {
-                const T a = row[k];
+    constexpr int VEC = 16 / (int)sizeof(T), NC = VEC - 1, KC = 2048, RG = 2, ROWS = 16 * RG, U = 4;
+    typedef typename VecOf<T, VEC>::type vec_t;
+    typedef typename GlobalVecOf<T, VEC>::type gvec_t;
+    __shared__ __attribute__((aligned(16))) T bs[NC][KC];
+    const int q = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    for (int64_t row0 = (int64_t)blockIdx.x * ROWS; row0 < M; row0 += (int64_t)gridDim.x * ROWS) {
+        T acc[RG][NC];
 #pragma unroll
-                for (int c = 0; c < 3; ++c)
-                    if (c < ncols) acc[c] = fma_t(a, B[k * ldb + c], acc[c]);
+        for (int g = 0; g < RG; ++g)
+#pragma unroll
+            for (int c = 0; c < NC; ++c) acc[g][c] = T(0);
+        // rows past M re-read row M-1 and are not stored
+        const T *ar[RG];
+#pragma unroll
+        for (int g = 0; g < RG; ++g) {
+            const int64_t r = row0 + grp * RG + g;
+            ar[g] = A + (r < M ? r : M - 1) * lda;
+        }
+        for (int64_t k0 = 0; k0 < K; k0 += KC) {
+            const int kc = (int)(K - k0 < KC ? K - k0 : KC);
+            __syncthreads();                               // the previous chunk has been consumed
+            for (int k = threadIdx.x; k < KC; k += 256)
+#pragma unroll
+                for (int c = 0; c < NC; ++c) bs[c][k] = (k < kc && c < ncols) ? B[(k0 + k) * ldb + c] : T(0);
+            __syncthreads();
+            const int kv = kc / VEC;                       // whole 16-byte pieces of this chunk
+            int v = q;
+            for (; v + 16 * (U - 1) < kv; v += 16 * U) {
+                vec_t a[RG][U];
+#pragma unroll
+                for (int g = 0; g < RG; ++g)
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+                        a[g][u] = __builtin_nontemporal_load(reinterpret_cast<const gvec_t *>(ar[g] + k0 + (int64_t)(v + 16 * u) * VEC));
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) {
+                        const vec_t b = *reinterpret_cast<const vec_t *>(&bs[c][(v + 16 * u) * VEC]);
+#pragma unroll
+                        for (int g = 0; g < RG; ++g)
+#pragma unroll
+                            for (int e = 0; e < VEC; ++e) acc[g][c] = fma_t(a[g][u][e], b[e], acc[g][c]);
+                    }
             }
+            for (; v < kv; v += 16) {
 #pragma unroll
-            for (int c = 0; c < 3; ++c) {
-                const T s = sum16(acc[c]);
-                if (q == 0 && c < ncols) C[i * ldc + c] = accumulate ? C[i * ldc + c] + s : s;
+                for (int g = 0; g < RG; ++g) {
+                    const vec_t a = *reinterpret_cast<const gvec_t *>(ar[g] + k0 + (int64_t)v * VEC);
+#pragma unroll
+                    for (int c = 0; c < NC; ++c)
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) acc[g][c] = fma_t(a[e], bs[c][v * VEC + e], acc[g][c]);
+                }
+            }
+            for (int k = kv * VEC + q; k < kc; k += 16)   // fewer than VEC trailing elements of the last chunk
+#pragma unroll
+                for (int g = 0; g < RG; ++g)
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) acc[g][c] = fma_t(ar[g][k0 + k], bs[c][k], acc[g][c]);
+        }
+#pragma unroll
+        for (int g = 0; g < RG; ++g) {
+            const int64_t r = row0 + grp * RG + g;
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                const T s = sum16(acc[g][c]);
+                if (q == 0 && r < M && c < ncols) C[r * ldc + c] = accumulate ? C[r * ldc + c] + s : s;
             }
         }
-    } else {
-        const int64_t stride = (int64_t)gridDim.x * 256;
-        for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < M; i += stride) {
-            T acc[3] = {T(0), T(0), T(0)};
-            for (int64_t k = 0; k < K; ++k) {
-                const T a = A[k * lda + i];
-#pragma unroll
-                for (int c = 0; c < 3; ++c)
-                    if (c < ncols) acc[c] = fma_t(a, B[k * ldb + c], acc[c]);
-            }
+    }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+gemm_fringe_cols_ta_kernel(const T *__restrict__ A, int64_t lda, const T *__restrict__ B, int64_t ldb,
+                           T *__restrict__ C, int64_t ldc, int64_t M, int64_t K, int ncols, int accumulate) {
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < M; i += stride) {
+        T acc[3] = {T(0), T(0), T(0)};
+        for (int64_t k = 0; k < K; ++k) {
+            const T a = A[k * lda + i];
 #pragma unroll
             for (int c = 0; c < 3; ++c)
-                if (c < ncols) C[i * ldc + c] = accumulate ? C[i * ldc + c] + acc[c] : acc[c];
+                if (c < ncols) acc[c] = fma_t(a, B[k * ldb + c], acc[c]);
         }
+#pragma unroll
+        for (int c = 0; c < 3; ++c)
+            if (c < ncols) C[i * ldc + c] = accumulate ? C[i * ldc + c] + acc[c] : acc[c];
     }
 }
 
