@@ -212,15 +212,17 @@ int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
     if (nfr > 0) {
         int64_t blocks = TA ? (M + 255) / 256 : (M + 31) / 32;
         if (blocks > (1 << 20)) blocks = 1 << 20;
-        for (int64_t n = 0; n < batch; ++n) {
+        for (int64_t first = 0; first < batch; first += kMaxGridY) {
+            const int64_t count = batch - first < kMaxGridY ? batch - first : kMaxGridY;
+            const dim3 grid((unsigned)blocks, (unsigned)count);
+            const T *Af = A + first * stride_a, *Bf = B + first * stride_b + Nm;
+            T *Cf = C + first * stride_c + Nm;
             if constexpr (TA)
-                hipLaunchKernelGGL(gemm_fringe_cols_ta_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream,
-                                   A + n * stride_a, lda, B + n * stride_b + Nm, ldb, C + n * stride_c + Nm, ldc,
-                                   M, K, (int)nfr, a.accumulate);
+                hipLaunchKernelGGL(gemm_fringe_cols_ta_kernel<T>, grid, dim3(256), 0, stream, Af, lda, Bf, ldb, Cf, ldc,
+                                   M, K, (int)nfr, a.accumulate, stride_a, stride_b, stride_c);
             else
-                hipLaunchKernelGGL(gemm_fringe_cols_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream,
-                                   A + n * stride_a, lda, B + n * stride_b + Nm, ldb, C + n * stride_c + Nm, ldc,
-                                   M, K, (int)nfr, a.accumulate);
+                hipLaunchKernelGGL(gemm_fringe_cols_kernel<T>, grid, dim3(256), 0, stream, Af, lda, Bf, ldb, Cf, ldc,
+                                   M, K, (int)nfr, a.accumulate, stride_a, stride_b, stride_c);
             if (hipGetLastError() != hipSuccess) return DISTAL_ERR_LAUNCH;
         }
         if (Nm == 0) return DISTAL_OK;

@@ -485,7 +485,8 @@ innerprod_pass2_kernel(const double *__restrict__ partial, int nparts,
 // for j < ncols: the columns whose 16-byte piece would straddle the right edge of B and C when N
 // is not a multiple of the vector.  The contraction kernels run the columns before them; these
 // few are a matrix-vector product per column, i.e. one stream over the left operand.
-// B and C point at the first of the ncols columns.
+// B and C point at the first of the ncols columns; blockIdx.y selects one problem of a batch
+// (operands advance by fixed strides).
 //
 // gemm_fringe_cols_kernel (A is M x K): a workgroup owns 32 rows, 16 lanes share a row (two rows
 // per lane group, four 16-byte loads of each in flight) and the columns of B are staged in LDS
@@ -496,8 +497,12 @@ innerprod_pass2_kernel(const double *__restrict__ partial, int nparts,
 template <typename T>
 __global__ void __launch_bounds__(256)
 gemm_fringe_cols_kernel(const T *__restrict__ A, int64_t lda, const T *__restrict__ B, int64_t ldb,
-                        T *__restrict__ C, int64_t ldc, int64_t M, int64_t K, int ncols, int accumulate) {
+                        T *__restrict__ C, int64_t ldc, int64_t M, int64_t K, int ncols, int accumulate,
+                        int64_t batch_a, int64_t batch_b, int64_t batch_c) {
     constexpr int VEC = 16 / (int)sizeof(T), NC = VEC - 1, KC = 2048, RG = 2, ROWS = 16 * RG, U = 4;
+    A += (int64_t)blockIdx.y * batch_a;                    // blockIdx.y: one problem of a batch
+    B += (int64_t)blockIdx.y * batch_b;
+    C += (int64_t)blockIdx.y * batch_c;
     typedef typename VecOf<T, VEC>::type vec_t;
     typedef typename GlobalVecOf<T, VEC>::type gvec_t;
     __shared__ __attribute__((aligned(16))) T bs[NC][KC];
@@ -573,7 +578,11 @@ gemm_fringe_cols_kernel(const T *__restrict__ A, int64_t lda, const T *__restric
 template <typename T>
 __global__ void __launch_bounds__(256)
 gemm_fringe_cols_ta_kernel(const T *__restrict__ A, int64_t lda, const T *__restrict__ B, int64_t ldb,
-                           T *__restrict__ C, int64_t ldc, int64_t M, int64_t K, int ncols, int accumulate) {
+                           T *__restrict__ C, int64_t ldc, int64_t M, int64_t K, int ncols, int accumulate,
+                           int64_t batch_a, int64_t batch_b, int64_t batch_c) {
+    A += (int64_t)blockIdx.y * batch_a;
+    B += (int64_t)blockIdx.y * batch_b;
+    C += (int64_t)blockIdx.y * batch_c;
     const int64_t stride = (int64_t)gridDim.x * 256;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < M; i += stride) {
         T acc[3] = {T(0), T(0), T(0)};
