@@ -171,6 +171,25 @@ int distal_innerprod_noalloc(distal_dtype dt, int64_t I, int64_t J, int64_t K,
                              const void *B, const void *C, void *a, void *stream);
 
 /*
+ * distal_gemm with the tile of the output chosen by the caller instead of by distal_gemm_plan:
+ * for schedules that fix their leaf tile themselves, for tuning, and for tests that must reach
+ * one particular kernel.  bm x bn is one of the tile shapes the dtype has kernels for (the BM x
+ * BN pairs distal_gemm_plan can report for it: 256x256 [binary32], 256x128, 128x128, 128x64,
+ * 64x128, 64x64, 128x32, 32x256, and 256x64, 64x256 [binary32]); anything else returns
+ * DISTAL_ERR_SHAPE.  The whole product runs as one launch of that tile (plus the peeled
+ * trailing columns and rows described under distal_gemm_plan); K < 16 takes the bounds-checked
+ * kernel whatever the tile.  transposed_left != 0: the left operand is stored K x M (lda >= M)
+ * and C = [C +] A^T * B (the product a tensor-times-matrix contraction over a non-last mode
+ * consists of).  Other arguments, ownership and errors as distal_gemm.  It is the same
+ * operation as distal_gemm (the local update of the matrix-multiplication schedules, whose
+ * scheduling language lets the schedule divide loops down to a leaf tile of its own choosing);
+ * which tile is fastest for given extents is what distal_gemm_plan estimates.
+ */
+int distal_gemm_tiled(distal_dtype dt, int transposed_left, int bm, int bn, int64_t M, int64_t N, int64_t K,
+                      const void *A, int64_t lda, const void *B, int64_t ldb, void *C, int64_t ldc,
+                      int accumulate, void *stream);
+
+/*
  * Host-only query (no device work): how the library runs C = A * B with these extents (K >= 16).
  * Bases and leading dimensions need no alignment.  What the plan covers is the part of the
  * output whose 16-byte pieces do not straddle an edge: all but the last N % (16 / sizeof dt)

@@ -27,7 +27,7 @@ EXPORTS = (
     "distal_gemm", "distal_ttm", "distal_mttkrp", "distal_ttv", "distal_innerprod",
     "distal_ttv_mode", "distal_ttm_mode", "distal_mttkrp_mode", "distal_mttkrp_mode_workspace_bytes",
     "distal_mttkrp_workspace_bytes", "distal_innerprod_workspace_bytes", "distal_gemm_plan",
-    "distal_status_string", "distal_version", "distal_innerprod_noalloc",
+    "distal_status_string", "distal_version", "distal_innerprod_noalloc", "distal_gemm_tiled",
 )
 
 
@@ -53,6 +53,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib = ctypes.CDLL(p)
     i64, vp, ci, sz = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     lib.distal_gemm.argtypes = [ci, i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, vp]
+    lib.distal_gemm_tiled.argtypes = [ci, ci, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, vp]
+    lib.distal_gemm_tiled.restype = ci
     lib.distal_ttm.argtypes = [ci, i64, i64, i64, i64, vp, vp, vp, vp]
     lib.distal_ttv_mode.argtypes = [ci, ci, i64, i64, i64, vp, vp, vp, vp]
     lib.distal_ttv_mode.restype = ci
@@ -199,6 +201,22 @@ def distal_gemm(A, B, C, accumulate: bool = False):
         rc = load_library().distal_gemm(dt, M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc,
                                         int(bool(accumulate)), _stream(A))
     _raise(rc, "distal_gemm")
+    return C
+
+
+def distal_gemm_tiled(tile, A, B, C, accumulate: bool = False, transposed_left: bool = False):
+    """distal_gemm run on tiles of ``tile = (BM, BN)``; with ``transposed_left`` A is stored K x M."""
+    dt = _same(A, B, C)
+    lda, ldb, ldc = _ld(A, "A"), _ld(B, "B"), _ld(C, "C")
+    (K, M) = A.shape if transposed_left else A.shape[::-1]
+    K2, N = B.shape
+    if K != K2 or tuple(C.shape) != (M, N):
+        raise ValueError("shapes do not match C(M,N) = A(M,K) B(K,N)")
+    with _torch().cuda.device(A.device):
+        rc = load_library().distal_gemm_tiled(dt, int(bool(transposed_left)), int(tile[0]), int(tile[1]), M, N, K,
+                                              _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc,
+                                              int(bool(accumulate)), _stream(A))
+    _raise(rc, "distal_gemm_tiled")
     return C
 
 

@@ -167,6 +167,12 @@ int launch_by_id(int id, const ContractArgs<T> &a, int64_t batch, hipStream_t st
     case 8:
         if constexpr (sizeof(T) == 4) return launch_tiles<T, 32, 256, 32, 1, 4, TA>(a, batch, stream);
         else return launch_tiles<T, 32, 256, 16, 1, 4, TA>(a, batch, stream);
+    case 9:
+        if constexpr (sizeof(T) == 4) return launch_tiles<T, 128, 64, 16, 4, 1, TA>(a, batch, stream);
+        break;
+    case 10:
+        if constexpr (sizeof(T) == 4) return launch_tiles<T, 64, 128, 16, 2, 2, TA>(a, batch, stream);
+        break;
     default: break;
     }
     // too few larger tiles to give every CU one: quarter-size tiles, four times the workgroups
@@ -179,7 +185,7 @@ int launch_by_id(int id, const ContractArgs<T> &a, int64_t batch, hipStream_t st
 template <typename T, bool TA = false>
 int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B, int64_t ldb,
            T *C, int64_t ldc, int accumulate, hipStream_t stream, int64_t batch = 1,
-           int64_t stride_a = 0, int64_t stride_b = 0, int64_t stride_c = 0) {
+           int64_t stride_a = 0, int64_t stride_b = 0, int64_t stride_c = 0, int force_id = 0) {
     constexpr int VEC = 16 / (int)sizeof(T);
     if (M == 0 || N == 0 || batch == 0) return DISTAL_OK;
     if (K == 0) {
@@ -239,6 +245,7 @@ int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
     }
     a.M = Mm;
     a.N = Nm;
+    if (force_id != 0) return launch_by_id<T, TA>(force_id, a, batch, stream);   // the caller's tile
     const ProductPlan plan = plan_product(sizeof(T) == 8, TA, Mm, Nm, K, batch);
     if (plan.split == 0) return launch_by_id<T, TA>(plan.main.id, a, batch, stream);
     ContractArgs<T> first = a, second = a;
@@ -537,6 +544,44 @@ int distal_gemm(distal_dtype dt, int64_t M, int64_t N, int64_t K, const void *A,
                               accumulate, s);
     return gemm_t<float>(M, N, K, (const float *)A, lda, (const float *)B, ldb, (float *)C, ldc,
                          accumulate, s);
+}
+
+int distal_gemm_tiled(distal_dtype dt, int transposed_left, int bm, int bn, int64_t M, int64_t N, int64_t K,
+                      const void *A, int64_t lda, const void *B, int64_t ldb, void *C, int64_t ldc,
+                      int accumulate, void *stream) {
+    if (check_dtype(dt) != DISTAL_OK) return DISTAL_ERR_DTYPE;
+    if (M < 0 || N < 0 || K < 0) return DISTAL_ERR_SHAPE;
+    // the tile must be one the dtype has kernels for, whatever the extents make eligible
+    TileCandidate cand[kMaxTileCandidates];
+    const int n = tile_candidates(dt == DISTAL_F64, transposed_left != 0, 1, 1, K, cand);
+    int id = 0;
+    for (int i = 0; i < n; ++i)
+        if (cand[i].bm == bm && cand[i].bn == bn) id = cand[i].id;
+    if (id == 0) return DISTAL_ERR_SHAPE;
+    int64_t t;
+    if (!mul_ok(M, N, &t) || !mul_ok(M, K, &t) || !mul_ok(K, N, &t)) return DISTAL_ERR_SHAPE;
+    const int64_t a_rows = transposed_left ? K : M, a_cols = transposed_left ? M : K;
+    if (lda < a_cols || ldb < N || ldc < N) return DISTAL_ERR_STRIDE;
+    if ((a_rows > 1 && (!mul_ok(a_rows, lda, &t) || t > INT64_MAX / 8)) ||
+        (M > 1 && (!mul_ok(M, ldc, &t) || t > INT64_MAX / 8)) ||
+        (K > 1 && (!mul_ok(K, ldb, &t) || t > INT64_MAX / 8)))
+        return DISTAL_ERR_SHAPE;
+    const bool need_in = M > 0 && K > 0 && N > 0, need_c = M > 0 && N > 0;
+    if ((need_in && (!A || !B)) || (need_c && !C)) return DISTAL_ERR_NULL;
+    if (need_c && (C == A || C == B)) return DISTAL_ERR_ALIAS;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dt == DISTAL_F64) {
+        if (transposed_left)
+            return gemm_t<double, true>(M, N, K, (const double *)A, lda, (const double *)B, ldb, (double *)C, ldc,
+                                        accumulate, s, 1, 0, 0, 0, id);
+        return gemm_t<double>(M, N, K, (const double *)A, lda, (const double *)B, ldb, (double *)C, ldc,
+                              accumulate, s, 1, 0, 0, 0, id);
+    }
+    if (transposed_left)
+        return gemm_t<float, true>(M, N, K, (const float *)A, lda, (const float *)B, ldb, (float *)C, ldc,
+                                   accumulate, s, 1, 0, 0, 0, id);
+    return gemm_t<float>(M, N, K, (const float *)A, lda, (const float *)B, ldb, (float *)C, ldc,
+                         accumulate, s, 1, 0, 0, 0, id);
 }
 
 int distal_ttm(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L, const void *B,

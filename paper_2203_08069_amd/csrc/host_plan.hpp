@@ -38,52 +38,71 @@ inline RangeSplit split_ranges(int64_t n, int64_t max_blocks, int64_t min_per, i
 // ---- matrix products: tile choice and the cut into two launches ------------------------------
 struct TilePick { int id, bm, bn, bk; double cost; };
 
-// A tile shape the straight-line kernels exist for: its measured relative speed, the
-// wavefronts per SIMD one workgroup brings (wps) and the workgroups of that kernel a compute
-// unit holds (occ).
-struct TileCandidate { int id; bool eligible; int bm, bn, bk; double speed; int wps, occ; };
+// A tile shape the straight-line kernels exist for, with its measured efficiency (fraction of
+// the MFMA peak of the dtype) on grids that give every compute unit exactly J tiles, for
+// J = 1, 2, 3, 4, 8 and 16 or more (aligned products, K = 2048; 4096 for the deep binary64 tile).
+// Few tiles per compute unit mean few wavefronts per SIMD and less overlap of one tile's
+// prologue and epilogue with another's k-loop, and how much that costs differs by tile: a
+// 256 x 256 binary32 tile brings its own four wavefronts per SIMD and loses 1 %, a 64 x 64 one
+// alone on a compute unit runs at 60 % of its large-grid speed.
+struct TileCandidate { int id; bool eligible; int bm, bn, bk; double eff[6]; };
 
-inline int tile_candidates(bool f64, bool ta, int64_t M, int64_t N, int64_t K, TileCandidate (&c)[8]) {
-    // tiles with a short side only for an output that is that narrow (rank-sized N, or M under TA)
+constexpr int kMaxTileCandidates = 12;
+
+// efficiencies of a narrow tile from one large-grid figure (what a rank-sized product of the
+// tensor-times-matrix shapes reaches with it): the small-grid entries follow the 128 x 128
+// tile's curve
+inline void narrow_eff(TileCandidate &c, double large) {
+    const double shape[6] = {0.82, 0.92, 0.96, 0.98, 0.99, 1.0};
+    for (int i = 0; i < 6; ++i) c.eff[i] = large * shape[i];
+}
+
+inline int tile_candidates(bool f64, bool ta, int64_t M, int64_t N, int64_t K, TileCandidate (&c)[kMaxTileCandidates]) {
+    // tiles with a 32-wide (or, in binary32, 64-wide) short side only for an output that is that
+    // narrow (rank-sized N, or M under TA)
     const bool n32 = N <= 32, n64 = N <= 64, m32 = M <= 32, m64 = M <= 64;
+    (void)ta;
     if (!f64) {
-        c[0] = {1, K >= 1024, 256, 256, ta ? 16 : 32, 1.0, 4, 1};
-        c[1] = {2, K >= 512, 256, 128, 16, 0.973, 2, 2};
-        c[2] = {3, true, 128, 128, 16, 0.95, 1, 4};
-        c[3] = {4, true, 64, 64, 16, 0.81, 1, 8};
-        c[4] = {5, n64, 256, 64, 16, 0.885, 1, 3};
-        c[5] = {6, n32 && K >= 32, 128, 32, 32, 0.626, 1, 3};
-        c[6] = {7, m64, 64, 256, 16, 0.889, 1, 3};
-        c[7] = {8, m32 && K >= 32, 32, 256, 32, 0.637, 1, 2};
-        return 8;
+        c[0] = {1, K >= 1024, 256, 256, ta ? 16 : 32, {0.906, 0.909, 0.911, 0.913, 0.915, 0.919}};
+        c[1] = {2, K >= 512, 256, 128, 16, {0.853, 0.886, 0.887, 0.893, 0.899, 0.901}};
+        c[2] = {3, true, 128, 128, 16, {0.720, 0.808, 0.853, 0.865, 0.873, 0.881}};
+        c[3] = {4, true, 64, 64, 16, {0.461, 0.650, 0.716, 0.737, 0.758, 0.765}};
+        c[4] = {9, true, 128, 64, 16, {0.623, 0.762, 0.785, 0.812, 0.822, 0.835}};
+        c[5] = {10, true, 64, 128, 16, {0.625, 0.727, 0.779, 0.808, 0.825, 0.833}};
+        c[6] = {5, n64, 256, 64, 16, {}};
+        c[7] = {6, n32 && K >= 32, 128, 32, 32, {}};
+        c[8] = {7, m64, 64, 256, 16, {}};
+        c[9] = {8, m32 && K >= 32, 32, 256, 32, {}};
+        narrow_eff(c[6], 0.891); narrow_eff(c[7], 0.575); narrow_eff(c[8], 0.883); narrow_eff(c[9], 0.585);
+        return 10;
     }
-    c[0] = {2, K >= 4096, 256, 128, 16, 1.0, 4, 1};
-    c[1] = {3, true, 128, 128, 16, 0.985, 2, 2};
-    c[2] = {4, true, 64, 64, 16, 0.915, 1, 4};
-    c[3] = {5, n64, 128, 64, 16, 0.94, 1, 3};
-    c[4] = {6, n32, 128, 32, 16, 0.697, 1, 3};
-    c[5] = {7, m64, 64, 128, 16, 0.95, 1, 3};
-    c[6] = {8, m32, 32, 256, 16, 0.617, 1, 2};
+    c[0] = {2, K >= 2048, 256, 128, 16, {0.901, 0.903, 0.903, 0.902, 0.907, 0.908}};
+    c[1] = {3, true, 128, 128, 16, {0.790, 0.867, 0.865, 0.875, 0.885, 0.892}};
+    c[2] = {4, true, 64, 64, 16, {0.587, 0.813, 0.813, 0.829, 0.848, 0.849}};
+    c[3] = {5, true, 128, 64, 16, {0.665, 0.809, 0.853, 0.837, 0.871, 0.886}};
+    c[4] = {7, true, 64, 128, 16, {0.660, 0.823, 0.855, 0.840, 0.873, 0.885}};
+    c[5] = {6, n32, 128, 32, 16, {}};
+    c[6] = {8, m32, 32, 256, 16, {}};
+    narrow_eff(c[5], 0.633); narrow_eff(c[6], 0.560);
     return 7;
 }
 
-// Estimated time of a grid: tiles per compute unit (a partly filled last round counts in full) x
-// tile area / speed; a grid too small to bring a compute unit its four wavefronts per SIMD runs
-// below that speed (measured with one 128 x 128 tile per compute unit: binary64, two wavefronts
-// per SIMD, 0.87; binary32, one, 0.80).
+// Estimated time of a grid, in units of tile area: the most loaded compute unit works
+// J = ceil(tiles / 256) tiles at the efficiency measured for J tiles per compute unit
+// (interpolated between the measured J; padding counts through the tile count).
 inline double rounds_cost(int64_t tiles, const TileCandidate &c) {
-    const int64_t n = (tiles + kComputeUnits - 1) / kComputeUnits;
-    auto fill = [](int64_t wavefronts_per_simd) {
-        return wavefronts_per_simd >= 4 ? 1.0 : (wavefronts_per_simd == 3 ? 0.94 : (wavefronts_per_simd == 2 ? 0.87 : 0.80));
-    };
-    // c.speed was measured on a large grid, i.e. with c.occ workgroups resident
-    const double rel = fill((n < c.occ ? n : c.occ) * c.wps) / fill((int64_t)c.occ * c.wps);
-    return (double)n * (double)(c.bm * c.bn) / (c.speed * rel);
+    const int64_t J = (tiles + kComputeUnits - 1) / kComputeUnits;
+    double e;
+    if (J <= 4) e = c.eff[J < 1 ? 0 : J - 1];
+    else if (J < 8) e = c.eff[3] + (c.eff[4] - c.eff[3]) * (double)(J - 4) / 4.0;
+    else if (J < 16) e = c.eff[4] + (c.eff[5] - c.eff[4]) * (double)(J - 8) / 8.0;
+    else e = c.eff[5];
+    return (double)J * (double)(c.bm * c.bn) / e;
 }
 
 // The tile with the least estimated time for a product run as one launch.
 inline TilePick pick_tile(bool f64, bool ta, int64_t M, int64_t N, int64_t K, int64_t batch) {
-    TileCandidate cand[8];
+    TileCandidate cand[kMaxTileCandidates];
     const int n = tile_candidates(f64, ta, M, N, K, cand);
     TilePick pick{4, 64, 64, 16, 1e300};
     for (int i = 0; i < n; ++i) {
@@ -106,7 +125,7 @@ inline ProductPlan plan_product(bool f64, bool ta, int64_t M, int64_t N, int64_t
     ProductPlan plan{pick_tile(f64, ta, M, N, K, batch), 0, 0, TilePick{0, 0, 0, 0, 0.0}};
     // a second launch costs about 3 us of an otherwise busy part: in units of tile area
     const double launch_cost = 3e-6 * (f64 ? 78.6e12 : 157.3e12) / (double)kComputeUnits / (2.0 * (double)K);
-    TileCandidate cand[8];
+    TileCandidate cand[kMaxTileCandidates];
     const int n = tile_candidates(f64, ta, M, N, K, cand);
     double best = plan.main.cost;
     for (int i = 0; i < n; ++i) {
@@ -121,8 +140,8 @@ inline ProductPlan plan_product(bool f64, bool ta, int64_t M, int64_t N, int64_t
             const TilePick rest = split == 1 ? pick_tile(f64, ta, M - cut, N, K, batch)
                                              : pick_tile(f64, ta, M, N - cut, K, batch);
             const double total = rounds_cost(lines * per_line, c) + rest.cost + launch_cost;
-            if (total < 0.97 * best) {                                             // worth a second launch
-                best = total / 0.97;
+            if (total < 0.985 * best) {                                             // worth a second launch
+                best = total / 0.985;
                 plan = ProductPlan{TilePick{c.id, c.bm, c.bn, c.bk, total}, split, cut, rest};
             }
         }

@@ -42,7 +42,7 @@ static void check_tile_map(int tiles_m, int tiles_n) {
 }
 
 static bool known_tile(bool f64, bool ta, int64_t M, int64_t N, int64_t K, const TilePick &t) {
-    TileCandidate c[8];
+    TileCandidate c[kMaxTileCandidates];
     const int n = tile_candidates(f64, ta, M, N, K, c);
     for (int i = 0; i < n; ++i)
         if (c[i].eligible && c[i].id == t.id) return c[i].bm == t.bm && c[i].bn == t.bn && c[i].bk == t.bk;

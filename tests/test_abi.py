@@ -195,7 +195,7 @@ def test_gemm_plan_choice(lib):
     small problems; and its argument checks."""
     from paper_2203_08069_amd import binding
     F32, F64 = 0, 1
-    tile = binding.gemm_tile
+    tile, plan = binding.gemm_tile, binding.gemm_plan
     # headline and fp32 GEMM (BASELINE configs[1]), TTM (configs[3]) along modes 2, 0, 1
     assert tile(F64, False, 8192, 8192, 8192) == (256, 128, 16)
     assert tile(F32, False, 8192, 8192, 8192) == (256, 256, 32)
@@ -204,8 +204,9 @@ def test_gemm_plan_choice(lib):
     assert tile(F32, True, 256, 1024, 1024, batch=1024) == (256, 256, 16)
     assert tile(F64, False, 1 << 20, 256, 1024) == (128, 128, 16)
     # SUMMA k-chunks: shallow products take the smaller tiles
-    for K in (256, 512, 1024, 2048):
+    for K in (256, 512, 1024):
         assert tile(F64, False, 8192, 8192, K) == (128, 128, 16)
+    assert tile(F64, False, 8192, 8192, 2048) == (256, 128, 16)
     assert tile(F32, False, 8192, 8192, 512) == (256, 128, 16)
     assert tile(F32, False, 8192, 8192, 256) == (128, 128, 16)
     assert tile(F32, False, 8192, 8192, 1040) == (256, 256, 32)     # K % 32 == 16: one more, half-filled slab
@@ -218,14 +219,17 @@ def test_gemm_plan_choice(lib):
     # ragged: 8200 rows are 8.25 rounds of 256 x 128 tiles: the first 8192 rows are eight whole rounds
     # of them (the tile reported), the other 8 rows a second launch of small tiles
     assert tile(F64, False, 8200, 8192, 8192) == (256, 128, 16)
-    assert tile(F64, False, 8000, 8000, 8000) == (256, 128, 16)
-    # 3000^3: 576 tiles of 128 x 128 are 2.25 rounds; 21 rows of them are two whole rounds, the rest small tiles
-    assert tile(F64, False, 3000, 3000, 3000) == (128, 128, 16)
+    # 8000^3: 2016 tiles of 256 x 128 pad the output by 3 %, 7875 of 128 x 64 by 0.8 %
+    assert tile(F64, False, 8000, 8000, 8000) == (128, 64, 16)
+    # 3000^3: 576 tiles of 128 x 128 are 2.25 rounds of one or two tiles per compute unit, where that
+    # tile runs at 79 and 87 % of its speed; 2209 tiles of 64 x 64 are nine rounds at full speed
+    assert plan(F64, False, 3000, 3000, 3000) == ((64, 64, 16), 0, 0, (0, 0, 0))
+    # 2000^3 in binary32: two 128 x 64 tiles per compute unit beat eight 64 x 64 ones
+    assert plan(F32, False, 2000, 2000, 2000) == ((128, 64, 16), 0, 0, (0, 0, 0))
     # small problems: quarter-size tiles
     assert tile(F32, False, 1024, 1024, 1024) == (64, 64, 16)
     assert tile(F64, False, 300, 200, 100) == (64, 64, 16)
     # the two-launch plans: whole rounds of large tiles first, the rest on small tiles
-    plan = binding.gemm_plan
     assert plan(F64, False, 8192, 8192, 8192) == ((256, 128, 16), 0, 0, (0, 0, 0))
     assert plan(F64, False, 8200, 8192, 8192) == ((256, 128, 16), 1, 8192, (64, 64, 16))
     assert plan(F64, False, 8192, 8200, 8192) == ((256, 128, 16), 2, 8192, (64, 64, 16))
@@ -248,7 +252,7 @@ def test_gemm_plan_invariants_on_random_extents(lib):
     import random
     from paper_2203_08069_amd import binding
     rng = random.Random(5)
-    tiles = {0: {(256, 256), (256, 128), (128, 128), (64, 64), (256, 64), (128, 32), (64, 256), (32, 256)},
+    tiles = {0: {(256, 256), (256, 128), (128, 128), (64, 64), (128, 64), (64, 128), (256, 64), (128, 32), (64, 256), (32, 256)},
              1: {(256, 128), (128, 128), (64, 64), (128, 64), (128, 32), (64, 128), (32, 256)}}
     pick = lambda: rng.choice([1, 4, 8, 16, 24, 32, 48, 64, 100, 128, 250, 256, 512, 1000, 1024, 3000, 4096, 5000, 8192, 8200,
                                65536, 1 << 20]) + rng.choice([0, 0, 0, 4, -4 if rng.random() < .5 else 8])
@@ -264,9 +268,9 @@ def test_gemm_plan_invariants_on_random_extents(lib):
         def ok(t, m, n):
             assert (t[0], t[1]) in tiles[dt], (t, dt)
             assert t[2] in (16, 32) and t[2] <= max(K, 16), (t, K)
-            if t[1] < 64 or (t[1] == 64 and t[0] > 64):
+            if t[1] < 64 or (t[1] == 64 and t[0] == 256):
                 assert n <= 64, (t, n)              # a narrow N side only for a narrow N
-            if t[0] < 64 or (t[0] == 64 and t[1] > 64):
+            if t[0] < 64 or (t[0] == 64 and t[1] == 256):
                 assert m <= 64, (t, m)
         if split == 0:
             ok(tile, M, N)
@@ -307,6 +311,25 @@ def test_noalloc_argument_errors(lib):
     assert f(0, 2, 2, 2, None, b, c, None) == 1
     assert f(0, 2, 2, 2, a, b, None, None) == 1
     assert f(1, 2, 2, 2, a, b, a, None) == 5
+
+
+def test_gemm_tiled_argument_errors(lib):
+    """The caller-chosen-tile product validates tile, extents, strides and pointers on the host."""
+    a, b, c = (P(FAKE + 256 * i) for i in range(3))
+    f = lib.distal_gemm_tiled
+    ok = (64, 64, 64, a, 64, b, 64, c, 64, 0, None)
+    assert f(9, 0, 64, 64, *ok) == 3
+    for dt, bm, bn in ((1, 256, 256), (1, 256, 64), (1, 64, 256), (0, 48, 48), (0, 0, 0), (0, 64, 32), (1, 256, 32)):
+        assert f(dt, 0, bm, bn, *ok) == 2, (dt, bm, bn)          # no kernel of that tile for the dtype
+    assert f(0, 0, 64, 64, -1, 64, 64, a, 64, b, 64, c, 64, 0, None) == 2
+    assert f(0, 0, 64, 64, 64, 64, 64, a, 63, b, 64, c, 64, 0, None) == 4
+    assert f(0, 1, 64, 64, 128, 64, 64, a, 64, b, 64, c, 64, 0, None) == 4      # stored K x M: lda >= M
+    assert f(0, 0, 64, 64, 64, 64, 64, a, 64, b, 63, c, 64, 0, None) == 4
+    assert f(0, 0, 64, 64, 64, 64, 64, a, 64, b, 64, c, 63, 0, None) == 4
+    assert f(0, 0, 64, 64, 64, 64, 64, None, 64, b, 64, c, 64, 0, None) == 1
+    assert f(0, 0, 64, 64, 64, 64, 64, a, 64, b, 64, None, 64, 0, None) == 1
+    assert f(0, 0, 64, 64, 64, 64, 64, a, 64, b, 64, a, 64, 0, None) == 5
+    assert f(1, 1, 128, 64, 0, 64, 64, None, 64, None, 64, None, 64, 0, None) == 0   # empty output: nothing to do
 
 
 def test_probe_library_exports_and_argument_errors():

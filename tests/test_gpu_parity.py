@@ -58,6 +58,56 @@ def test_gemm(lib, oracle, dtype, kind, M, N, K):
     compare(U.host(C), oracle.gemm(A, B), dtype, kind, K, lambda: oracle.gemm(np.abs(A), np.abs(B)))
 
 
+# every tile shape a dtype has kernels for, reached by name whatever the planner would choose
+TILES = {np.float32: [(256, 256), (256, 128), (128, 128), (128, 64), (64, 128), (64, 64), (256, 64), (128, 32),
+                      (64, 256), (32, 256)],
+         np.float64: [(256, 128), (128, 128), (128, 64), (64, 128), (64, 64), (128, 32), (32, 256)]}
+TILE_CASES = [(dt, t) for dt in DT for t in TILES[dt]]
+# whole tiles and whole slabs (the straight-line form); ragged in M and N with trailing terms in K
+# (edge-clamping form with a second pass); a ragged K made of whole slabs (edge form, one pass)
+TILED_EXTENTS = [(512, 768, 128), (520, 712, 100), (300, 264, 96)]
+
+
+@pytest.mark.parametrize("ta", [False, True])
+@pytest.mark.parametrize("M,N,K", TILED_EXTENTS)
+@pytest.mark.parametrize("dtype,tile", TILE_CASES)
+def test_gemm_every_tile_by_name(lib, oracle, dtype, tile, M, N, K, ta):
+    """distal_gemm_tiled with each tile, left operand stored either way, C a block inside a larger
+    matrix of sentinels; then accumulated on top.  Every element is compared."""
+    kind = inputs.SMALLINT if (M + tile[0]) % 3 == 0 else inputs.UNIFORM
+    vec = 16 // np.dtype(dtype).itemsize
+    A, B = U.gen(700 + M, 0, (M, K), dtype, kind), U.gen(700 + M, 1, (K, N), dtype, kind)
+    left = np.ascontiguousarray(A.T) if ta else A
+    big = np.full((M + 3, N + 2 * vec), 77.0, dtype=dtype)
+    dC = U.dev(big)
+    view = dC[2:2 + M, vec:vec + N]
+    lib.distal_gemm_tiled(tile, U.dev(left), U.dev(B), view, transposed_left=ta)
+    out = U.host(dC)
+    got = out[2:2 + M, vec:vec + N]
+    mask = np.ones_like(big, dtype=bool)
+    mask[2:2 + M, vec:vec + N] = False
+    assert np.all(out[mask] == 77.0)
+    ref = oracle.gemm(A, B)
+    compare(got, ref, dtype, kind, K, lambda: oracle.gemm(np.abs(A), np.abs(B)))
+    lib.distal_gemm_tiled(tile, U.dev(left), U.dev(B), view, accumulate=True, transposed_left=ta)
+    out2 = U.host(dC)
+    if kind == inputs.SMALLINT or dtype == np.float64:
+        assert np.array_equal(out2[2:2 + M, vec:vec + N], got * 2)
+    else:
+        U.assert_close(out2[2:2 + M, vec:vec + N], got.astype(np.float64) * 2, dtype, K)
+    assert np.all(out2[mask] == 77.0)
+
+
+def test_gemm_tiled_rejects_unknown_tiles(lib):
+    import torch
+    A = torch.zeros(64, 64, dtype=torch.float64, device="cuda:0")
+    C = torch.zeros(64, 64, dtype=torch.float64, device="cuda:0")
+    for tile in ((256, 256), (256, 64), (48, 48), (0, 0)):      # binary32-only shapes and no shape at all
+        with pytest.raises(lib.DistalError) as e:
+            lib.distal_gemm_tiled(tile, A, A.clone(), C)
+        assert e.value.status == 2
+
+
 # shapes that reach the large-tile launch configurations (binary32: 256 x 256 tiles with 32-deep
 # slabs, 256 x 128 for k-chunks; binary64: 256 x 128 with sixteen wavefronts, 128 x 128 with eight)
 BIG_TILE_SHAPES = [(np.float32, 4096, 4096, 1024, (256, 256, 32)), (np.float32, 4096, 2048, 512, (256, 128, 16)),
@@ -88,13 +138,13 @@ def test_gemm_big_tile_configs(lib, oracle, kind, dtype, M, N, K, tile):
 
 # ragged shapes that reach the same launch configurations in their edge-clamping form (M and N
 # not whole tiles, K with trailing terms for the second pass), in the order of BIG_TILE_SHAPES,
-# then 128 x 128 binary32 and a shape whose K is made of whole slabs
+# then 128 x 64 binary32 and a shape whose K is made of whole slabs
 RAGGED_TILE_SHAPES = [(np.float32, 4000, 4000, 1028, (256, 256, 32), 0), (np.float32, 4000, 2040, 520, (256, 128, 16), 0),
                       (np.float64, 4000, 2040, 4100, (256, 128, 16), 0), (np.float64, 4000, 2040, 72, (128, 128, 16), 0),
-                      (np.float32, 4000, 2040, 100, (128, 128, 16), 0), (np.float32, 3900, 4072, 1056, (256, 256, 32), 0),
+                      (np.float32, 4000, 2040, 100, (128, 64, 16), 0), (np.float32, 3900, 4072, 1056, (256, 256, 32), 0),
                       # two launches: whole rounds of large tiles, the rest on small tiles - cut along the
-                      # rows (binary32 256 x 256; binary64 128 x 128) and along the columns (binary64 256 x 128)
-                      (np.float32, 4200, 4096, 1024, (256, 256, 32), 1), (np.float64, 4200, 4096, 512, (128, 128, 16), 1),
+                      # rows (binary32 256 x 256; binary64 256 x 128) and along the columns (binary64 256 x 128)
+                      (np.float32, 4200, 4096, 1024, (256, 256, 32), 1), (np.float64, 4200, 4096, 4096, (256, 128, 16), 1),
                       (np.float64, 4096, 4104, 4096, (256, 128, 16), 2)]
 
 
