@@ -124,19 +124,18 @@ int launch_fill(T *out, int64_t rows, int64_t cols, int64_t ld, hipStream_t stre
 // 128 x 128 tile or, for deep products, sixteen on 256 x 128; binary32 wavefronts own 64 x 64
 // sub-tiles, sixteen on a 256 x 256 tile with 32-deep slabs for deep products, eight on 256 x 128
 // for k-chunks (with one workgroup per CU the epilogue is not hidden, so shallow products want
-// smaller tiles), four on 128 x 128; 64 x 64 tiles for problems too small to fill the part with
-// those.  Among the shapes a product is deep enough for, the one with the least estimated time
-// wins: tiles per compute unit, a partly filled last round counted in full, x tile area / the
-// kernel's speed relative to the best one (measured at 8192^3: binary64 1, 0.985, 0.915 for
-// 256 x 128, 128 x 128, 64 x 64; binary32 1, 0.973, 0.95, 0.81 from 256 x 256 down).  A
-// rank-sized output side (N <= 64, or M <= 64 as the transposed forms of a tensor-times-matrix
-// have it) adds tiles with a 64- or 32-wide short side, which read the large operand once
-// instead of padding the narrow one to 64 (speeds measured on such products at 1024^3).  Whole
-// aligned tiles take the straight-line kernels as they are, ragged M and N their edge-clamping
+// smaller tiles), four on 128 x 128; 128 x 64, 64 x 128 and 64 x 64 tiles for problems too small
+// to fill the part with those.  Among the shapes a product is deep enough for, the one with the
+// least estimated time wins: tiles per compute unit, a partly filled last round counted in
+// full, x tile area / the efficiency measured for that tile at that many tiles per compute
+// unit (tile_candidates() holds the table).  A rank-sized output side (N <= 64, or M <= 64 as
+// the transposed forms of a tensor-times-matrix have it) adds tiles with a 64- or 32-wide short
+// side, which read the large operand once instead of padding the narrow one to 64.  Whole
+// tiles take the straight-line kernels as they are, ragged M and N their edge-clamping
 // form (the padding is paid for through the tile count), with one more zero-filled slab for
-// K % BK trailing terms; only operands whose 16-byte pieces would straddle an edge (misaligned
-// bases or leading dimensions, N not a multiple of the vector) take the guarded 128 x 128
-// kernel.  A grid that would end in a thin last round is cut into two launches (plan_product).
+// K % BK trailing terms.  Alignment does not matter; columns (and, transposed, rows) whose
+// 16-byte pieces would straddle an edge are peeled off first (see gemm_t).  A grid that would
+// end in a thin last round is cut into two launches (plan_product).
 
 // The launch for a tile id of tile_candidates().
 template <typename T, bool TA>
@@ -172,6 +171,9 @@ int launch_by_id(int id, const ContractArgs<T> &a, int64_t batch, hipStream_t st
         break;
     case 10:
         if constexpr (sizeof(T) == 4) return launch_tiles<T, 64, 128, 16, 2, 2, TA>(a, batch, stream);
+        break;
+    case 11:
+        if constexpr (sizeof(T) == 4) return launch_tiles<T, 64, 64, 32, 2, 2, TA>(a, batch, stream);
         break;
     default: break;
     }
@@ -555,8 +557,8 @@ int distal_gemm_tiled(distal_dtype dt, int transposed_left, int bm, int bn, int6
     TileCandidate cand[kMaxTileCandidates];
     const int n = tile_candidates(dt == DISTAL_F64, transposed_left != 0, 1, 1, K, cand);
     int id = 0;
-    for (int i = 0; i < n; ++i)
-        if (cand[i].bm == bm && cand[i].bn == bn) id = cand[i].id;
+    for (int i = 0; i < n; ++i)            // of two slab depths of one tile, the one this K is deep enough for
+        if (cand[i].bm == bm && cand[i].bn == bn && (id == 0 || cand[i].eligible)) id = cand[i].id;
     if (id == 0) return DISTAL_ERR_SHAPE;
     int64_t t;
     if (!mul_ok(M, N, &t) || !mul_ok(M, K, &t) || !mul_ok(K, N, &t)) return DISTAL_ERR_SHAPE;

@@ -224,17 +224,21 @@ def test_gemm_plan_choice(lib):
     # 3000^3: 576 tiles of 128 x 128 are 2.25 rounds of one or two tiles per compute unit, where that
     # tile runs at 79 and 87 % of its speed; 2209 tiles of 64 x 64 are nine rounds at full speed
     assert plan(F64, False, 3000, 3000, 3000) == ((64, 64, 16), 0, 0, (0, 0, 0))
-    # 2000^3 in binary32: two 128 x 64 tiles per compute unit beat eight 64 x 64 ones
-    assert plan(F32, False, 2000, 2000, 2000) == ((128, 64, 16), 0, 0, (0, 0, 0))
+    # binary32: 64 x 64 tiles take 32-deep slabs from K = 256 on; a flat 4000 x 2040 x 100 product
+    # runs on 128 x 64 tiles (two per compute unit)
+    assert plan(F32, False, 2000, 2000, 2000) == ((64, 64, 32), 0, 0, (0, 0, 0))
+    assert plan(F32, False, 2000, 2000, 200) == ((128, 64, 16), 0, 0, (0, 0, 0))
+    assert tile(F32, False, 1024, 1024, 128) == (64, 64, 16)
+    assert plan(F32, False, 4000, 2040, 100) == ((128, 64, 16), 0, 0, (0, 0, 0))
     # small problems: quarter-size tiles
-    assert tile(F32, False, 1024, 1024, 1024) == (64, 64, 16)
+    assert tile(F32, False, 1024, 1024, 1024) == (64, 64, 32)
     assert tile(F64, False, 300, 200, 100) == (64, 64, 16)
     # the two-launch plans: whole rounds of large tiles first, the rest on small tiles
     assert plan(F64, False, 8192, 8192, 8192) == ((256, 128, 16), 0, 0, (0, 0, 0))
     assert plan(F64, False, 8200, 8192, 8192) == ((256, 128, 16), 1, 8192, (64, 64, 16))
     assert plan(F64, False, 8192, 8200, 8192) == ((256, 128, 16), 2, 8192, (64, 64, 16))
     assert plan(F64, False, 5000, 5000, 5000) == ((256, 128, 16), 1, 4864, (64, 64, 16))
-    assert plan(F32, False, 4200, 4096, 1024) == ((256, 256, 32), 1, 4096, (64, 64, 16))
+    assert plan(F32, False, 4200, 4096, 1024) == ((256, 256, 32), 1, 4096, (64, 64, 32))
     assert plan(F64, False, 4096, 4104, 4096) == ((256, 128, 16), 2, 4096, (64, 64, 16))
     tile3, rest3 = (ctypes.c_int * 3)(), (ctypes.c_int * 3)()
     split, cut = ctypes.c_int(), ctypes.c_int64()

@@ -65,7 +65,8 @@ TILES = {np.float32: [(256, 256), (256, 128), (128, 128), (128, 64), (64, 128), 
 TILE_CASES = [(dt, t) for dt in DT for t in TILES[dt]]
 # whole tiles and whole slabs (the straight-line form); ragged in M and N with trailing terms in K
 # (edge-clamping form with a second pass); a ragged K made of whole slabs (edge form, one pass)
-TILED_EXTENTS = [(512, 768, 128), (520, 712, 100), (300, 264, 96)]
+TILED_EXTENTS = [(512, 768, 128), (520, 712, 100), (300, 264, 96),
+                 (256, 256, 256), (200, 136, 300)]     # deep enough for the 32-deep slabs of binary32 64 x 64
 
 
 @pytest.mark.parametrize("ta", [False, True])
