@@ -250,14 +250,14 @@ def main():
                      f"{m_s} evenly spaced rows of C (all {n} columns, full K={n})")
             del hA, hB
 
-        if name == "gemm_f64" and "summa" in want:
+        if "summa" in want:
             # the leaf one processor issues per k-step of SUMMA / Cannon: C += A(:, chunk) B(chunk, :)
             for chunk in (128, 256, 512, 1024, 2048):
                 C.zero_()
-                r = finish(f"gemm_f64_summa_chunk{chunk}",
-                           f"C += A(:, 0:{chunk}) B(0:{chunk}, :), M=N={n}, f64: one k-step of a SUMMA schedule", "f64",
+                r = finish(f"{name}_summa_chunk{chunk}",
+                           f"C += A(:, 0:{chunk}) B(0:{chunk}, :), M=N={n}, {dt}: one k-step of a SUMMA schedule", dt,
                            lambda: binding.distal_gemm(A[:, 0:chunk], B[0:chunk, :], C, accumulate=True),
-                           2.0 * n * n * chunk, 8.0 * (2 * n * chunk + 2 * n * n), "mfma")
+                           2.0 * n * n * chunk, np.dtype(npdt).itemsize * (2.0 * n * chunk + 2 * n * n), "mfma")
                 if cpu:
                     # after W + K accumulating launches C holds (launches) x the chunk product: check one launch's worth
                     C.zero_()

@@ -197,7 +197,8 @@ int distal_gemm_tiled(distal_dtype dt, int transposed_left, int bm, int bn, int6
  * operand, all but the last M % (16 / sizeof dt) rows (bounds-checked kernel); pass the
  * extents of that part.  K < 16 takes the bounds-checked 128 x 128 kernel.  TTM is such a
  * product: mode 2 is M = I*J, N = L; mode 0 is transposed_left with M = R, N = J*K, K = I;
- * mode 1 the same with batch = I, N = K, K = J.
+ * mode 1 the same with batch = I, N = K, K = J.  accumulate as in distal_gemm: a product added
+ * onto an old C takes its largest tiles from deeper K on (the tensor calls overwrite: 0).
  *   tile      = {BM, BN, BK}: tile and slab depth of the (first) launch
  *   split     = 0: one launch.  1: rows [0, cut) of C with `tile`, rows [cut, M) in a second
  *               launch with rest_tile.  2: the same along columns, [0, cut) and [cut, N).
@@ -207,7 +208,7 @@ int distal_gemm_tiled(distal_dtype dt, int transposed_left, int bm, int bn, int6
  * The plan is a function of the arguments only, never of the device.  Returns a status.
  */
 int distal_gemm_plan(distal_dtype dt, int transposed_left, int64_t M, int64_t N, int64_t K, int64_t batch,
-                     int tile[3], int *split, int64_t *cut, int rest_tile[3]);
+                     int accumulate, int tile[3], int *split, int64_t *cut, int rest_tile[3]);
 
 /* Scratch sizes for the calls that take a workspace (0 for invalid arguments). */
 size_t distal_mttkrp_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L);

@@ -72,7 +72,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.distal_status_string.argtypes = [ci]
     lib.distal_version.argtypes = []
     ip = ctypes.POINTER(ctypes.c_int)
-    lib.distal_gemm_plan.argtypes = [ci, ci, i64, i64, i64, i64, ip, ip, ctypes.POINTER(ctypes.c_int64), ip]
+    lib.distal_gemm_plan.argtypes = [ci, ci, i64, i64, i64, i64, ci, ip, ip, ctypes.POINTER(ctypes.c_int64), ip]
     lib.distal_gemm_plan.restype = ci
     for name in ("distal_gemm", "distal_ttm", "distal_mttkrp", "distal_ttv", "distal_innerprod",
                  "distal_ttm_mode", "distal_mttkrp_mode", "distal_version"):
@@ -327,21 +327,21 @@ def distal_ttv_mode(mode, B, c, A):
     return A
 
 
-def gemm_plan(dtype_code: int, transposed_left: bool, M: int, N: int, K: int, batch: int = 1):
+def gemm_plan(dtype_code: int, transposed_left: bool, M: int, N: int, K: int, batch: int = 1, accumulate: bool = False):
     """How the library runs an aligned M x N x K product (host-only query):
     ((BM, BN, BK), split, cut, (BM, BN, BK) of the second launch); split 0 = one launch,
     1 = rows [0, cut) then [cut, M), 2 = columns [0, cut) then [cut, N)."""
     tile, rest = (ctypes.c_int * 3)(), (ctypes.c_int * 3)()
     split, cut = ctypes.c_int(), ctypes.c_int64()
-    rc = load_library().distal_gemm_plan(dtype_code, int(bool(transposed_left)), M, N, K, batch,
+    rc = load_library().distal_gemm_plan(dtype_code, int(bool(transposed_left)), M, N, K, batch, int(bool(accumulate)),
                                          tile, ctypes.byref(split), ctypes.byref(cut), rest)
     _raise(rc, "distal_gemm_plan")
     return tuple(tile), split.value, cut.value, tuple(rest)
 
 
-def gemm_tile(dtype_code: int, transposed_left: bool, M: int, N: int, K: int, batch: int = 1):
+def gemm_tile(dtype_code: int, transposed_left: bool, M: int, N: int, K: int, batch: int = 1, accumulate: bool = False):
     """(BM, BN, BK) of the first launch of gemm_plan()."""
-    return gemm_plan(dtype_code, transposed_left, M, N, K, batch)[0]
+    return gemm_plan(dtype_code, transposed_left, M, N, K, batch, accumulate)[0]
 
 
 def innerprod_workspace_bytes(dtype_code: int, I: int, J: int, K: int) -> int:

@@ -57,17 +57,25 @@ inline void narrow_eff(TileCandidate &c, double large) {
     for (int i = 0; i < 6; ++i) c.eff[i] = large * shape[i];
 }
 
-inline int tile_candidates(bool f64, bool ta, int64_t M, int64_t N, int64_t K, TileCandidate (&c)[kMaxTileCandidates]) {
+inline int tile_candidates(bool f64, bool ta, int64_t M, int64_t N, int64_t K, TileCandidate (&c)[kMaxTileCandidates],
+                           bool acc = false) {
     // tiles with a 32-wide (or, in binary32, 64-wide) short side only for an output that is that
     // narrow (rank-sized N, or M under TA)
     const bool n32 = N <= 32, n64 = N <= 64, m32 = M <= 32, m64 = M <= 64;
     (void)ta;
     if (!f64) {
-        c[0] = {1, K >= 1024, 256, 256, ta ? 16 : 32, {0.906, 0.909, 0.911, 0.913, 0.915, 0.919}};
+        // added onto an old C the largest tile pays from deeper products on: its one workgroup per
+        // compute unit has nothing to overlap the read-modify-write of its 256 KiB of C with
+        // (8192 x 8192 x 1024 under accumulate: 82.8 % of peak, 256 x 128 tiles 85.7 %)
+        c[0] = {1, K >= (acc ? 4096 : 1024), 256, 256, ta ? 16 : 32, {0.906, 0.909, 0.911, 0.913, 0.915, 0.919}};
         c[1] = {2, K >= 512, 256, 128, 16, {0.853, 0.886, 0.887, 0.893, 0.899, 0.901}};
-        c[2] = {3, true, 128, 128, 16, {0.720, 0.808, 0.853, 0.865, 0.873, 0.881}};
+        // a product of at most 256 terms added onto an old C is bound by the traffic of C: tiles with
+        // 128 columns and 64 rows (512-byte runs of C, four workgroups per compute unit) then measure
+        // 4..5 points ahead of 128 x 128 and of 128 x 64
+        const bool thin_acc = acc && K <= 256;
+        c[2] = {3, !thin_acc, 128, 128, 16, {0.720, 0.808, 0.853, 0.865, 0.873, 0.881}};
         c[3] = {4, true, 64, 64, 16, {0.461, 0.650, 0.716, 0.737, 0.758, 0.765}};
-        c[4] = {9, true, 128, 64, 16, {0.623, 0.762, 0.785, 0.812, 0.822, 0.835}};
+        c[4] = {9, !thin_acc, 128, 64, 16, {0.623, 0.762, 0.785, 0.812, 0.822, 0.835}};
         c[5] = {10, true, 64, 128, 16, {0.625, 0.727, 0.779, 0.808, 0.825, 0.833}};
         // 64 x 64 with 32-deep slabs: half the barriers per term; pays from K = 256 on (binary32 only:
         // the same in binary64 measured 3..9 % slower)
@@ -104,9 +112,9 @@ inline double rounds_cost(int64_t tiles, const TileCandidate &c) {
 }
 
 // The tile with the least estimated time for a product run as one launch.
-inline TilePick pick_tile(bool f64, bool ta, int64_t M, int64_t N, int64_t K, int64_t batch) {
+inline TilePick pick_tile(bool f64, bool ta, int64_t M, int64_t N, int64_t K, int64_t batch, bool acc = false) {
     TileCandidate cand[kMaxTileCandidates];
-    const int n = tile_candidates(f64, ta, M, N, K, cand);
+    const int n = tile_candidates(f64, ta, M, N, K, cand, acc);
     TilePick pick{4, 64, 64, 16, 1e300};
     for (int i = 0; i < n; ++i) {
         if (!cand[i].eligible) continue;
@@ -124,12 +132,12 @@ inline TilePick pick_tile(bool f64, bool ta, int64_t M, int64_t N, int64_t K, in
 // split = 0: one launch; 1: rows [0, cut) and [cut, M); 2: columns [0, cut) and [cut, N).
 struct ProductPlan { TilePick main; int split; int64_t cut; TilePick rest; };
 
-inline ProductPlan plan_product(bool f64, bool ta, int64_t M, int64_t N, int64_t K, int64_t batch) {
-    ProductPlan plan{pick_tile(f64, ta, M, N, K, batch), 0, 0, TilePick{0, 0, 0, 0, 0.0}};
+inline ProductPlan plan_product(bool f64, bool ta, int64_t M, int64_t N, int64_t K, int64_t batch, bool acc = false) {
+    ProductPlan plan{pick_tile(f64, ta, M, N, K, batch, acc), 0, 0, TilePick{0, 0, 0, 0, 0.0}};
     // a second launch costs about 3 us of an otherwise busy part: in units of tile area
     const double launch_cost = 3e-6 * (f64 ? 78.6e12 : 157.3e12) / (double)kComputeUnits / (2.0 * (double)K);
     TileCandidate cand[kMaxTileCandidates];
-    const int n = tile_candidates(f64, ta, M, N, K, cand);
+    const int n = tile_candidates(f64, ta, M, N, K, cand, acc);
     double best = plan.main.cost;
     for (int i = 0; i < n; ++i) {
         if (!cand[i].eligible) continue;
@@ -140,8 +148,8 @@ inline ProductPlan plan_product(bool f64, bool ta, int64_t M, int64_t N, int64_t
             const int64_t per_line = (split == 1 ? tn : tm) * batch;               // tiles per row (column) of tiles
             const int64_t lines = whole / per_line, cut = lines * (split == 1 ? c.bm : c.bn);
             if (lines < 1 || cut >= (split == 1 ? M : N)) continue;
-            const TilePick rest = split == 1 ? pick_tile(f64, ta, M - cut, N, K, batch)
-                                             : pick_tile(f64, ta, M, N - cut, K, batch);
+            const TilePick rest = split == 1 ? pick_tile(f64, ta, M - cut, N, K, batch, acc)
+                                             : pick_tile(f64, ta, M, N - cut, K, batch, acc);
             const double total = rounds_cost(lines * per_line, c) + rest.cost + launch_cost;
             if (total < 0.985 * best) {                                             // worth a second launch
                 best = total / 0.985;

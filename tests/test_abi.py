@@ -243,10 +243,17 @@ def test_gemm_plan_choice(lib):
     tile3, rest3 = (ctypes.c_int * 3)(), (ctypes.c_int * 3)()
     split, cut = ctypes.c_int(), ctypes.c_int64()
     refs = (tile3, ctypes.byref(split), ctypes.byref(cut), rest3)
-    assert lib.distal_gemm_plan(7, 0, 8, 8, 8, 1, *refs) == 3
-    assert lib.distal_gemm_plan(0, 0, 0, 8, 8, 1, *refs) == 2
-    assert lib.distal_gemm_plan(0, 0, 8, 8, 8, 0, *refs) == 2
-    assert lib.distal_gemm_plan(0, 0, 8, 8, 8, 1, None, None, None, None) == 1
+    assert lib.distal_gemm_plan(7, 0, 8, 8, 8, 1, 0, *refs) == 3
+    assert lib.distal_gemm_plan(0, 0, 0, 8, 8, 1, 0, *refs) == 2
+    assert lib.distal_gemm_plan(0, 0, 8, 8, 8, 0, 0, *refs) == 2
+    assert lib.distal_gemm_plan(0, 0, 8, 8, 8, 1, 0, None, None, None, None) == 1
+    # added onto an old C, binary32 takes 256 x 256 tiles from K = 4096 on; binary64 plans do not change
+    assert tile(F32, False, 8192, 8192, 1024, accumulate=True) == (256, 128, 16)
+    assert tile(F32, False, 8192, 8192, 4096, accumulate=True) == (256, 256, 32)
+    assert tile(F32, False, 8192, 8192, 256, accumulate=True) == (64, 128, 16)      # thin and bound by C's traffic
+    assert tile(F32, False, 8192, 8192, 512, accumulate=True) == (256, 128, 16)
+    for K in (128, 1024, 8192):
+        assert plan(F64, False, 8192, 8192, K, accumulate=True) == plan(F64, False, 8192, 8192, K)
 
 
 def test_gemm_plan_invariants_on_random_extents(lib):
