@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdistal.so")
 SOURCES = ["distal_api.hip"]
-HEADERS = ["gemm_kernel.hpp", "mttkrp_kernel.hpp", "stream_kernels.hpp"]
+HEADERS = ["gemm_kernel.hpp", "mttkrp_kernel.hpp", "stream_kernels.hpp", "host_plan.hpp", "tile_map.hpp"]
 # the measurement aid of include/distal_probe.h: a library of its own, never loaded by the binding
 PROBE_LIB = os.path.join(HERE, "libdistal_probe.so")
 PROBE_SOURCES = ["roofline_probe.hip"]
