@@ -411,9 +411,11 @@ contract_kernel(ContractArgs<T> args) {
 //
 // ACC_INIT = true is the accumulating product (args.accumulate is taken as set) with the old
 // values of C loaded into the accumulators before the first slab instead of added in the
-// epilogue, which then only stores: nothing is waited for at the end of a tile, which pays for
-// the shallow k-steps of a distributed schedule in binary32 (8192 x 8192 x 128: +20 %, x 256:
-// +6 %; no gain in binary64, whose kernels keep the add in the epilogue).
+// epilogue, which then only stores: nothing is waited for at the end of a tile.  That pays
+// where the k-loop is short and the tile small - binary32, tiles up to 128 x 128, at most 256
+// terms (64 x 128 tiles at K = 128: +7 %) - and costs 1..4 % everywhere else (the loads then
+// sit in front of the first multiply with nothing to hide behind), so the host launches this
+// form there only; binary64 shows no gain at any shape and always adds in the epilogue.
 // ---------------------------------------------------------------------------
 template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TA = false, int EDGE = 0, bool ACC_INIT = false>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 4 : 2)
