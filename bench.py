@@ -60,6 +60,9 @@ EXTRA = ["summa", "gemm_shapes", "ttv_f64", "innerprod_f64", "ttm_f64", "mttkrp_
 PROFILE_OF_ROW = {
     "gemm_f64": "contract_fast_kernel_f64_gemm_8192.md",
     "gemm_f32": "contract_fast_kernel_f32_gemm_8192.md",
+    "gemm_f64_summa_chunk128": "contract_fast_kernel_f64_summa_kstep_8192x8192x128.md",
+    "gemm_f64_summa_chunk256": "contract_fast_kernel_f64_summa_kstep_8192x8192x256.md",
+    "gemm_f64_summa_chunk512": "contract_fast_kernel_f64_summa_kstep_8192x8192x512.md",
     "ttm": "contract_fast_kernel_f32_ttm_1024x1024x1024x256.md",
     "ttm_mode0": "contract_fast_kernel_tn_f32_ttm_mode0_1024x1024x1024x256.md",
     "ttm_mode1": "contract_fast_kernel_tn_f32_ttm_mode1_1024x1024x1024x256.md",
@@ -128,6 +131,8 @@ def main():
     ap.add_argument("--rows", default="all",
                     help="'all' (default), 'core' (" + ",".join(CORE) + "), or a comma list of these and of "
                          + ",".join(EXTRA) + "; gemm_f64, the headline, always runs")
+    ap.add_argument("--summa-chunks", default="128,256,512,1024,2048",
+                    help="k-step depths of the summa rows (a profiler run takes one depth at a time)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--host-inputs", action="store_true",
                     help="generate the operands with numpy on the host and copy them (slow); the default fills "
@@ -252,7 +257,7 @@ def main():
 
         if "summa" in want:
             # the leaf one processor issues per k-step of SUMMA / Cannon: C += A(:, chunk) B(chunk, :)
-            for chunk in (128, 256, 512, 1024, 2048):
+            for chunk in [int(c) for c in args.summa_chunks.split(",") if c]:
                 C.zero_()
                 r = finish(f"{name}_summa_chunk{chunk}",
                            f"C += A(:, 0:{chunk}) B(0:{chunk}, :), M=N={n}, {dt}: one k-step of a SUMMA schedule", dt,
