@@ -36,4 +36,5 @@ def test_row_sets_are_consistent():
     import bench
     assert bench.CORE[0] == "gemm_f64"                      # the headline row comes first
     assert not set(bench.CORE) & set(bench.EXTRA)
-    assert set(bench.PROFILE_OF_ROW) <= set(bench.CORE) | set(bench.EXTRA) | {"mttkrp_mode1"}
+    summa = {f"gemm_f64_summa_chunk{k}" for k in (128, 256, 512, 1024, 2048)}       # the rows of the "summa" set
+    assert set(bench.PROFILE_OF_ROW) <= set(bench.CORE) | set(bench.EXTRA) | {"mttkrp_mode1"} | summa
