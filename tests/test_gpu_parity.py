@@ -66,7 +66,8 @@ TILE_CASES = [(dt, t) for dt in DT for t in TILES[dt]]
 # whole tiles and whole slabs (the straight-line form); ragged in M and N with trailing terms in K
 # (edge-clamping form with a second pass); a ragged K made of whole slabs (edge form, one pass)
 TILED_EXTENTS = [(512, 768, 128), (520, 712, 100), (300, 264, 96),
-                 (256, 256, 256), (200, 136, 300)]     # deep enough for the 32-deep slabs of binary32 64 x 64
+                 (256, 256, 256), (200, 136, 300),     # deep enough for the 32-deep slabs of binary32 64 x 64
+                 (70, 72, 8)]                          # fewer than 16 terms: the bounds-checked kernel, whatever the tile
 
 
 @pytest.mark.parametrize("ta", [False, True])
