@@ -445,7 +445,25 @@ int ttv_left_t(int64_t batch, int64_t R, int64_t N, const T *B, const T *c, T *A
     // of each row in one go; needs that many whole spans to give every compute unit one.
     constexpr int64_t kWideSpan = 4 * 256 * VEC;
     const int64_t wide_groups = (vec && N % kWideSpan == 0) ? total / kWideSpan : 0;
-    if (wide_groups >= 256)
+    if (blocks < kComputeUnits && R >= 64) {
+        // fewer outputs than give every compute unit a workgroup, many rows to add: the rows are split
+        // inside a workgroup.  16 lanes per 256-byte run of a row and 16 row groups where that gives
+        // every compute unit a workgroup, else 8 lanes and 32 groups (4 lanes and 64-byte runs
+        // measured slower than leaving compute units idle)
+        const int64_t np = vec ? N / VEC : N;
+        const int64_t g16 = batch * ((np + 15) / 16), g8 = batch * ((np + 7) / 8);
+        const int64_t g32 = batch * ((np + 31) / 32);
+        const int64_t cap = 1 << 20;
+        if (vec && g16 >= kComputeUnits)
+            hipLaunchKernelGGL((ttv_left_split_kernel<T, VEC, 16, 4>), dim3((unsigned)(g16 < cap ? g16 : cap)), dim3(256), 0,
+                               stream, B, c, A, batch, R, N);
+        else if (vec)
+            hipLaunchKernelGGL((ttv_left_split_kernel<T, VEC, 8, 4>), dim3((unsigned)(g8 < cap ? g8 : cap)), dim3(256), 0,
+                               stream, B, c, A, batch, R, N);
+        else
+            hipLaunchKernelGGL((ttv_left_split_kernel<T, 1, 32, 4>), dim3((unsigned)(g32 < cap ? g32 : cap)), dim3(256), 0,
+                               stream, B, c, A, batch, R, N);
+    } else if (wide_groups >= 256)
         hipLaunchKernelGGL((ttv_left_wide_kernel<T, 4, 4>),
                            dim3((unsigned)(wide_groups < (1 << 22) ? wide_groups : (1 << 22))), dim3(256), 0,
                            stream, B, c, A, batch, R, N);

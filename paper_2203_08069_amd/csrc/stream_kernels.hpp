@@ -363,6 +363,66 @@ ttv_left_wide_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__rest
     }
 }
 
+// The same sum for outputs too few to give every compute unit a workgroup of the kernels above
+// (a tall tensor contracted over its long leading mode): W lanes share a run of W pieces of the
+// output row and the 256 / W lane groups of the workgroup split the rows r between them (group
+// s takes r = s, s + S, s + 2 S, ...: what the groups read together is S consecutive rows),
+// UNROLL loads per lane in flight.  The groups' sums meet in LDS and are added in the order of s.
+// PV = elements per piece: the 16-byte vector, or 1 for operands that allow no vector access.
+template <typename T, int PV, int W, int UNROLL>
+__global__ void __launch_bounds__(256)
+ttv_left_split_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict__ A,
+                      int64_t batch, int64_t R, int64_t N) {
+    typedef typename VecOf<T, PV>::type vec_t;
+    constexpr int S = 256 / W;
+    __shared__ vec_t part[S][W];
+    const int64_t np = (N + PV - 1) / PV;                   // pieces per output row (PV > 1: N % PV == 0)
+    const int64_t strips = (np + W - 1) / W, total = batch * strips;
+    const int lw = threadIdx.x % W, s = threadIdx.x / W;
+    for (int64_t g = blockIdx.x; g < total; g += gridDim.x) {
+        const int64_t b = g / strips, piece = (g % strips) * W + lw;
+        const bool valid = piece < np;
+        const T *col = B + b * R * N + (valid ? piece : np - 1) * PV;      // a lane past the end re-reads the last piece
+        vec_t acc = vec_t(T(0));
+        int64_t r = s;
+        for (; r + (int64_t)(UNROLL - 1) * S < R; r += (int64_t)UNROLL * S) {
+            vec_t x[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u)
+                x[u] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(col + (r + (int64_t)u * S) * N));
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const T w = c[r + (int64_t)u * S];
+                if constexpr (PV == 1) {
+                    acc = fma_t(x[u], w, acc);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < PV; ++e) acc[e] = fma_t(x[u][e], w, acc[e]);
+                }
+            }
+        }
+        for (; r < R; r += S) {
+            const vec_t x = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(col + r * N));
+            const T w = c[r];
+            if constexpr (PV == 1) {
+                acc = fma_t(x, w, acc);
+            } else {
+#pragma unroll
+                for (int e = 0; e < PV; ++e) acc[e] = fma_t(x[e], w, acc[e]);
+            }
+        }
+        part[s][lw] = acc;
+        __syncthreads();
+        if (s == 0 && valid) {
+            vec_t sum = part[0][lw];
+#pragma unroll
+            for (int q = 1; q < S; ++q) sum += part[q][lw];
+            *reinterpret_cast<vec_t *>(A + b * N + piece * PV) = sum;
+        }
+        __syncthreads();                       // the sums have been read before the next strip overwrites them
+    }
+}
+
 // Same sum, one element per lane: any alignment and any N.
 template <typename T>
 __global__ void __launch_bounds__(256)

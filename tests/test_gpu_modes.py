@@ -211,6 +211,9 @@ def test_ttm_mode_zero_extents(lib, dtype):
 
 TTV_MODE_SHAPES = [(3, 5, 7), (17, 9, 36), (64, 33, 128), (1, 1, 1), (300, 4, 8), (5, 700, 3), (40, 50, 1024),
                    (1000, 16, 64), (2, 1000, 260),
+                   # few outputs and many rows to add: the kernels that split the rows inside a workgroup
+                   # (16 or 8 lanes per run of a row; ragged runs; a batch of short walks along mode 1)
+                   (200, 40, 300), (1030, 100, 100), (77, 1, 4100),
                    # >= 256 spans of 16 KiB per row: the one-span-per-workgroup kernel, with a leftover row
                    # (mode 0: N = J*K = 2^20; mode 1: N = K, batch I)
                    (5, 1024, 1024), (9, 5, 262144)]
