@@ -390,7 +390,12 @@ int ttv_t(int64_t rows, int64_t K, const T *B, const T *c, T *A, hipStream_t str
     if (blocks > (1 << 22)) blocks = 1 << 22;
     const bool vec = aligned16(B) && aligned16(c) && K % VEC == 0;
     if (!vec) {
-        hipLaunchKernelGGL(ttv_generic_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream, B, c, A, rows, K);
+        // odd K or operands off a 16-byte boundary: rows of at least 16 pieces take the vector kernel
+        // with element-aligned loads, shorter ones the element-wise kernel
+        if (K >= 16 * VEC)
+            hipLaunchKernelGGL((ttv_vec_kernel<T, 8, false, true>), dim3((unsigned)blocks), dim3(256), 0, stream, B, c, A, rows, K);
+        else
+            hipLaunchKernelGGL(ttv_generic_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream, B, c, A, rows, K);
     } else if (K / VEC <= 16) {
         // short rows: eight rows per 16-lane group and trip, so a workgroup streams 128 rows
         int64_t b8 = (rows + 127) / 128;
@@ -437,44 +442,50 @@ int ttv_left_t(int64_t batch, int64_t R, int64_t N, const T *B, const T *c, T *A
     if (!mul_ok(batch, N, &total)) return DISTAL_ERR_SHAPE;
     if (total == 0) return DISTAL_OK;
     if (R == 0) return launch_fill<T>(A, 1, total, total, stream);
-    const bool vec = aligned16(B) && aligned16(A) && N % VEC == 0;
-    const int64_t work = vec ? total / VEC : total;
+    // 16-byte pieces of the output row: aligned ones, or - any N >= VEC, any alignment - the same
+    // accesses typed as element-aligned with a last piece that overlaps its neighbour
+    const bool al = aligned16(B) && aligned16(A) && N % VEC == 0;
+    const bool vec = al || N >= VEC;
+    const int64_t np = vec ? (N + VEC - 1) / VEC : N;
+    int64_t work;
+    if (!mul_ok(batch, np, &work)) return DISTAL_ERR_SHAPE;
     int64_t blocks = (work + 255) / 256;
     if (blocks > (1 << 22)) blocks = 1 << 22;
     // Rows far apart (a whole slice per step of r) stream best when a workgroup reads 16 KiB
     // of each row in one go; needs that many whole spans to give every compute unit one.
     constexpr int64_t kWideSpan = 4 * 256 * VEC;
-    const int64_t wide_groups = (vec && N % kWideSpan == 0) ? total / kWideSpan : 0;
+    const int64_t wide_groups = (al && N % kWideSpan == 0) ? total / kWideSpan : 0;
+    const dim3 wg(256);
     if (blocks < kComputeUnits && R >= 64) {
         // fewer outputs than give every compute unit a workgroup, many rows to add: the rows are split
         // inside a workgroup.  16 lanes per 256-byte run of a row and 16 row groups where that gives
         // every compute unit a workgroup, else 8 lanes and 32 groups (4 lanes and 64-byte runs
         // measured slower than leaving compute units idle)
-        const int64_t np = vec ? N / VEC : N;
-        const int64_t g16 = batch * ((np + 15) / 16), g8 = batch * ((np + 7) / 8);
-        const int64_t g32 = batch * ((np + 31) / 32);
+        const int64_t g16 = batch * ((np + 15) / 16), g8 = batch * ((np + 7) / 8), g32 = batch * ((np + 31) / 32);
         const int64_t cap = 1 << 20;
-        if (vec && g16 >= kComputeUnits)
-            hipLaunchKernelGGL((ttv_left_split_kernel<T, VEC, 16, 4>), dim3((unsigned)(g16 < cap ? g16 : cap)), dim3(256), 0,
-                               stream, B, c, A, batch, R, N);
-        else if (vec)
-            hipLaunchKernelGGL((ttv_left_split_kernel<T, VEC, 8, 4>), dim3((unsigned)(g8 < cap ? g8 : cap)), dim3(256), 0,
-                               stream, B, c, A, batch, R, N);
-        else
-            hipLaunchKernelGGL((ttv_left_split_kernel<T, 1, 32, 4>), dim3((unsigned)(g32 < cap ? g32 : cap)), dim3(256), 0,
-                               stream, B, c, A, batch, R, N);
-    } else if (wide_groups >= 256)
+        const dim3 d16((unsigned)(g16 < cap ? g16 : cap)), d8((unsigned)(g8 < cap ? g8 : cap)), d32((unsigned)(g32 < cap ? g32 : cap));
+        if (vec && g16 >= kComputeUnits) {
+            if (al) hipLaunchKernelGGL((ttv_left_split_kernel<T, VEC, 16, 4>), d16, wg, 0, stream, B, c, A, batch, R, N);
+            else hipLaunchKernelGGL((ttv_left_split_kernel<T, VEC, 16, 4, true>), d16, wg, 0, stream, B, c, A, batch, R, N);
+        } else if (vec) {
+            if (al) hipLaunchKernelGGL((ttv_left_split_kernel<T, VEC, 8, 4>), d8, wg, 0, stream, B, c, A, batch, R, N);
+            else hipLaunchKernelGGL((ttv_left_split_kernel<T, VEC, 8, 4, true>), d8, wg, 0, stream, B, c, A, batch, R, N);
+        } else {
+            hipLaunchKernelGGL((ttv_left_split_kernel<T, 1, 32, 4>), d32, wg, 0, stream, B, c, A, batch, R, N);
+        }
+    } else if (wide_groups >= 256) {
         hipLaunchKernelGGL((ttv_left_wide_kernel<T, 4, 4>),
-                           dim3((unsigned)(wide_groups < (1 << 22) ? wide_groups : (1 << 22))), dim3(256), 0,
+                           dim3((unsigned)(wide_groups < (1 << 22) ? wide_groups : (1 << 22))), wg, 0,
                            stream, B, c, A, batch, R, N);
-    else if (vec) {
+    } else if (vec) {
         // long walks over many output pieces: one workgroup per compute unit, each taking several
         // 4 KiB column strips in turn (1024^3 along mode 1: +1 % in binary32, +4 % in binary64)
         if (blocks >= 4 * kStreamBlocks && R >= 256) blocks = kStreamBlocks;
-        hipLaunchKernelGGL((ttv_left_vec_kernel<T, 8>), dim3((unsigned)blocks), dim3(256), 0, stream, B, c, A, batch, R, N);
+        if (al) hipLaunchKernelGGL((ttv_left_vec_kernel<T, 8>), dim3((unsigned)blocks), wg, 0, stream, B, c, A, batch, R, N);
+        else hipLaunchKernelGGL((ttv_left_vec_kernel<T, 8, true>), dim3((unsigned)blocks), wg, 0, stream, B, c, A, batch, R, N);
+    } else {
+        hipLaunchKernelGGL(ttv_left_generic_kernel<T>, dim3((unsigned)blocks), wg, 0, stream, B, c, A, batch, R, N);
     }
-    else
-        hipLaunchKernelGGL(ttv_left_generic_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream, B, c, A, batch, R, N);
     return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
 }
 
@@ -484,23 +495,22 @@ int innerprod_t(int64_t n, const T *B, const T *C, T *out, double *partial, hipS
     constexpr int VEC = 16 / (int)sizeof(T);
     int nparts = 0;
     int64_t tail_lo = 0;
-    if (n > 0 && aligned16(B) && aligned16(C)) {
+    if (n > 0) {
+        // 16-byte pieces counted from each operand's own start; operands that do not start on a
+        // 16-byte boundary (views) take the same loads typed as element-aligned
         const int64_t nvec = n / VEC;
         if (nvec > 0) {
             const RangeSplit r = split_ranges(nvec, kStreamBlocks, 256, 256);
-            hipLaunchKernelGGL((innerprod_pass1_kernel<T, 4>), dim3((unsigned)r.blocks), dim3(256), 0, stream,
-                               B, C, partial, nvec, r.per);
+            if (aligned16(B) && aligned16(C))
+                hipLaunchKernelGGL((innerprod_pass1_kernel<T, 4>), dim3((unsigned)r.blocks), dim3(256), 0, stream,
+                                   B, C, partial, nvec, r.per);
+            else
+                hipLaunchKernelGGL((innerprod_pass1_kernel<T, 4, true>), dim3((unsigned)r.blocks), dim3(256), 0, stream,
+                                   B, C, partial, nvec, r.per);
             if (hipGetLastError() != hipSuccess) return DISTAL_ERR_LAUNCH;
             nparts = (int)r.blocks;
         }
         tail_lo = nvec * VEC;
-    } else if (n > 0) {
-        const RangeSplit r = split_ranges(n, kInnerprodMaxBlocks, 1024, 256);
-        hipLaunchKernelGGL(innerprod_pass1_generic_kernel<T>, dim3((unsigned)r.blocks), dim3(256), 0, stream,
-                           B, C, partial, n, r.per);
-        if (hipGetLastError() != hipSuccess) return DISTAL_ERR_LAUNCH;
-        nparts = (int)r.blocks;
-        tail_lo = n;
     }
     hipLaunchKernelGGL(innerprod_pass2_kernel<T>, dim3(1), dim3(256), 0, stream,
                        (const double *)partial, nparts, B, C, tail_lo, n, out);

@@ -3,6 +3,7 @@
 // per lane; arithmetic and reductions are arranged so that nothing but the
 // loads sits on the critical path.
 #pragma once
+#include <type_traits>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -51,30 +52,35 @@ __device__ __forceinline__ double sum64(double x) {
 // of the row, so the four groups of a wavefront stream four rows at once and a
 // wavefront load touches four 256-byte runs.  c is staged in LDS once per block.
 // UNROLL row pieces are in flight per lane before the first multiply.
+// UNALIGNED: rows and c may start at any element (K odd, views): the same 16-byte loads, typed as
+// element-aligned (the hardware serves them at any element alignment), pieces counted from the
+// start of each row, and the K % VEC trailing elements of a row taken by the group's first lanes.
 // ---------------------------------------------------------------------------
-template <typename T, int UNROLL, bool C_IN_LDS>
+template <typename T, int UNROLL, bool C_IN_LDS, bool UNALIGNED = false>
 __global__ void __launch_bounds__(256)
 ttv_vec_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict__ A,
                int64_t rows, int64_t K) {
     constexpr int VEC = 16 / (int)sizeof(T);
     typedef typename VecOf<T, VEC>::type vec_t;
+    typedef typename std::conditional<UNALIGNED, typename GlobalVecOf<T, VEC>::type, vec_t>::type gvec_t;
+    static_assert(!(C_IN_LDS && UNALIGNED), "the staged copy of c assumes aligned pieces");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    const vec_t *cv;
+    const gvec_t *cv;
     const int64_t kvecs = K / VEC;
-    if (C_IN_LDS) {
+    if constexpr (C_IN_LDS) {
         vec_t *cl = reinterpret_cast<vec_t *>(lds_raw);
         for (int64_t v = threadIdx.x; v < kvecs; v += 256)
             cl[v] = reinterpret_cast<const vec_t *>(c)[v];
         __syncthreads();
         cv = cl;
     } else {
-        cv = reinterpret_cast<const vec_t *>(c);
+        cv = reinterpret_cast<const gvec_t *>(c);
     }
     const int q = threadIdx.x & 15;
     const int64_t group = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
     const int64_t stride = (int64_t)gridDim.x * 16;
     for (int64_t r = group; r < rows; r += stride) {
-        const vec_t *row = reinterpret_cast<const vec_t *>(B + r * K);
+        const gvec_t *row = reinterpret_cast<const gvec_t *>(B + r * K);
         T acc = T(0);
         int64_t v = q;
         // whole trips of UNROLL pieces per lane (the same count for every lane of the group) ...
@@ -101,6 +107,10 @@ ttv_vec_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict__
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) acc = fma_t(b[u][e], cc[e], acc);
             }
+        }
+        if constexpr (UNALIGNED) {
+            const int64_t kt = kvecs * VEC + q;
+            if (kt < K) acc = fma_t(B[r * K + kt], c[kt], acc);
         }
         acc = sum16(acc);
         if (q == 0) A[r] = acc;
@@ -281,15 +291,20 @@ ttv_wide_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict_
 // A lane owns VEC neighbouring n of one b and walks r, UNROLL 16-byte loads in flight; what the
 // lanes of a wavefront read for one r is contiguous, so the stream is fully coalesced.  Each output
 // is summed by one lane in increasing r: no reduction across lanes, nothing to make deterministic.
-template <typename T, int UNROLL>
+// UNALIGNED: N >= VEC of any parity and operands at any element alignment: the same 16-byte accesses
+// typed as element-aligned, and a last piece that starts at N - VEC, overlapping its neighbour (the
+// outputs they share are summed twice in the same order and stored twice with the same value).
+template <typename T, int UNROLL, bool UNALIGNED = false>
 __global__ void __launch_bounds__(256)
 ttv_left_vec_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict__ A,
                     int64_t batch, int64_t R, int64_t N) {
     constexpr int VEC = 16 / (int)sizeof(T);
-    typedef typename VecOf<T, VEC>::type vec_t;
-    const int64_t nv = N / VEC, total = batch * nv;
+    typedef typename std::conditional<UNALIGNED, typename GlobalVecOf<T, VEC>::type, typename VecOf<T, VEC>::type>::type vec_t;
+    const int64_t nv = UNALIGNED ? (N + VEC - 1) / VEC : N / VEC, total = batch * nv;
     for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < total; v += (int64_t)gridDim.x * 256) {
-        const int64_t b = v / nv, n = (v % nv) * VEC;
+        const int64_t b = v / nv;
+        int64_t n = (v % nv) * VEC;
+        if (UNALIGNED && n > N - VEC) n = N - VEC;
         const T *col = B + b * R * N + n;
         vec_t acc = vec_t(T(0));
         int64_t r = 0;
@@ -368,21 +383,25 @@ ttv_left_wide_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__rest
 // output row and the 256 / W lane groups of the workgroup split the rows r between them (group
 // s takes r = s, s + S, s + 2 S, ...: what the groups read together is S consecutive rows),
 // UNROLL loads per lane in flight.  The groups' sums meet in LDS and are added in the order of s.
-// PV = elements per piece: the 16-byte vector, or 1 for operands that allow no vector access.
-template <typename T, int PV, int W, int UNROLL>
+// PV = elements per piece: the 16-byte vector, or 1 for rows shorter than one.  UNALIGNED as in
+// ttv_left_vec_kernel: element-aligned accesses and an overlapping last piece (N >= PV).
+template <typename T, int PV, int W, int UNROLL, bool UNALIGNED = false>
 __global__ void __launch_bounds__(256)
 ttv_left_split_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__restrict__ A,
                       int64_t batch, int64_t R, int64_t N) {
-    typedef typename VecOf<T, PV>::type vec_t;
+    typedef typename VecOf<T, PV>::type lvec_t;
+    typedef typename std::conditional<UNALIGNED, typename GlobalVecOf<T, PV>::type, lvec_t>::type vec_t;
     constexpr int S = 256 / W;
-    __shared__ vec_t part[S][W];
-    const int64_t np = (N + PV - 1) / PV;                   // pieces per output row (PV > 1: N % PV == 0)
+    __shared__ lvec_t part[S][W];
+    const int64_t np = (N + PV - 1) / PV;                   // pieces per output row (N % PV == 0 unless UNALIGNED)
     const int64_t strips = (np + W - 1) / W, total = batch * strips;
     const int lw = threadIdx.x % W, s = threadIdx.x / W;
     for (int64_t g = blockIdx.x; g < total; g += gridDim.x) {
         const int64_t b = g / strips, piece = (g % strips) * W + lw;
         const bool valid = piece < np;
-        const T *col = B + b * R * N + (valid ? piece : np - 1) * PV;      // a lane past the end re-reads the last piece
+        int64_t n = (valid ? piece : np - 1) * PV;          // a lane past the end re-reads the last piece
+        if (UNALIGNED && n > N - PV) n = N - PV;
+        const T *col = B + b * R * N + n;
         vec_t acc = vec_t(T(0));
         int64_t r = s;
         for (; r + (int64_t)(UNROLL - 1) * S < R; r += (int64_t)UNROLL * S) {
@@ -417,7 +436,7 @@ ttv_left_split_kernel(const T *__restrict__ B, const T *__restrict__ c, T *__res
             vec_t sum = part[0][lw];
 #pragma unroll
             for (int q = 1; q < S; ++q) sum += part[q][lw];
-            *reinterpret_cast<vec_t *>(A + b * N + piece * PV) = sum;
+            *reinterpret_cast<vec_t *>(A + b * N + n) = sum;
         }
         __syncthreads();                       // the sums have been read before the next strip overwrites them
     }
@@ -475,14 +494,17 @@ __device__ __forceinline__ double piece_dot(const v2d b, const v2d c) {
     return __builtin_fma(b[1], c[1], b[0] * c[0]);
 }
 
-template <typename T, int UNROLL>
+// UNALIGNED: the operands may start at any element (views): the same 16-byte loads, typed as
+// element-aligned, pieces counted from each operand's own start.
+template <typename T, int UNROLL, bool UNALIGNED = false>
 __global__ void __launch_bounds__(256)
 innerprod_pass1_kernel(const T *__restrict__ B, const T *__restrict__ C, double *__restrict__ partial,
                        int64_t nvec, int64_t per_block) {
     constexpr int VEC = 16 / (int)sizeof(T);
     typedef typename VecOf<T, VEC>::type vec_t;
-    const vec_t *bv = reinterpret_cast<const vec_t *>(B);
-    const vec_t *cv = reinterpret_cast<const vec_t *>(C);
+    typedef typename std::conditional<UNALIGNED, typename GlobalVecOf<T, VEC>::type, vec_t>::type gvec_t;
+    const gvec_t *bv = reinterpret_cast<const gvec_t *>(B);
+    const gvec_t *cv = reinterpret_cast<const gvec_t *>(C);
     const int64_t lo = (int64_t)blockIdx.x * per_block;
     const int64_t hi = lo + per_block < nvec ? lo + per_block : nvec;
     double acc = 0.0;
@@ -499,22 +521,6 @@ innerprod_pass1_kernel(const T *__restrict__ B, const T *__restrict__ C, double 
     }
     for (; v < hi; v += 256) acc += piece_dot(bv[v], cv[v]);
 
-    __shared__ double wsum[4];
-    acc = sum64(acc);
-    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = acc;
-    __syncthreads();
-    if (threadIdx.x == 0) partial[blockIdx.x] = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
-}
-
-// Element-wise pass 1 for operands that are not 16-byte aligned.
-template <typename T>
-__global__ void __launch_bounds__(256)
-innerprod_pass1_generic_kernel(const T *__restrict__ B, const T *__restrict__ C,
-                               double *__restrict__ partial, int64_t n, int64_t per_block) {
-    const int64_t lo = (int64_t)blockIdx.x * per_block;
-    const int64_t hi = lo + per_block < n ? lo + per_block : n;
-    double acc = 0.0;
-    for (int64_t m = lo + threadIdx.x; m < hi; m += 256) acc = __builtin_fma((double)B[m], (double)C[m], acc);
     __shared__ double wsum[4];
     acc = sum64(acc);
     if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = acc;

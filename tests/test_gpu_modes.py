@@ -214,6 +214,8 @@ TTV_MODE_SHAPES = [(3, 5, 7), (17, 9, 36), (64, 33, 128), (1, 1, 1), (300, 4, 8)
                    # few outputs and many rows to add: the kernels that split the rows inside a workgroup
                    # (16 or 8 lanes per run of a row; ragged runs; a batch of short walks along mode 1)
                    (200, 40, 300), (1030, 100, 100), (77, 1, 4100),
+                   # odd output rows: element-aligned 16-byte accesses with an overlapping last piece
+                   (300, 33, 101), (1000, 3, 4097), (50, 20, 33333), (70, 5, 5), (2, 66, 9),
                    # >= 256 spans of 16 KiB per row: the one-span-per-workgroup kernel, with a leftover row
                    # (mode 0: N = J*K = 2^20; mode 1: N = K, batch I)
                    (5, 1024, 1024), (9, 5, 262144)]

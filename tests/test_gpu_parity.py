@@ -322,6 +322,7 @@ def test_ttm_equals_gemm_on_view_and_identity(lib, dtype):
 
 TTV_SHAPES = [(4, 8, 1024), (3, 7, 1000), (5, 5, 7), (2, 9, 1), (1, 1, 64), (6, 11, 520), (2, 3, 8200),
               (33, 17, 128), (2, 2, 16388),
+              (6, 11, 521), (2, 3, 8201), (40, 50, 1001), (9, 9, 67), (300, 7, 131),   # odd K: element-aligned 16-byte loads and a tail
               (40, 500, 64), (3, 1000, 32), (7, 77, 8),      # short rows: several rows per lane group
               (2, 3, 1 << 17), (1, 5, 70000),               # few long rows: one workgroup per row
               # >= 8192 rows of whole 4 KiB runs: whole rows per wavefront, a row range per workgroup
@@ -358,16 +359,16 @@ def test_ttv_closed_forms(lib, dtype):
 
 
 @pytest.mark.parametrize("dtype", DT)
-def test_ttv_misaligned_operands(lib, oracle, dtype):
-    import torch
-    I, J, K = 3, 5, 64
-    flat = U.gen(22, 0, (I * J * K + 1,), dtype)
-    cc = U.gen(22, 1, (K + 1,), dtype)
-    dB = U.dev(flat)[1:].view(I, J, K)
-    dc = U.dev(cc)[1:]
+@pytest.mark.parametrize("I,J,K,ob,oc", [(3, 5, 64, 1, 1), (7, 9, 1001, 1, 3), (2, 3, 8200, 3, 0), (5, 4, 40, 1, 2), (64, 70, 256, 0, 1)])
+def test_ttv_misaligned_operands(lib, oracle, dtype, I, J, K, ob, oc):
+    """The tensor and the vector start ob and oc elements past a 16-byte boundary."""
+    flat = U.gen(22, 0, (I * J * K + ob,), dtype)
+    cc = U.gen(22, 1, (K + oc,), dtype)
+    dB = U.dev(flat)[ob:].view(I, J, K)
+    dc = U.dev(cc)[oc:]
     A = empty((I, J), dtype)
     lib.distal_ttv(dB, dc, A)
-    U.assert_close(U.host(A), oracle.ttv(flat[1:].reshape(I, J, K), cc[1:]), dtype, K)
+    U.assert_close(U.host(A), oracle.ttv(flat[ob:].reshape(I, J, K), cc[oc:]), dtype, K)
 
 
 # ------------------------------------------------------------------ innerprod
@@ -412,12 +413,15 @@ def test_innerprod_closed_forms(lib, dtype):
 
 
 @pytest.mark.parametrize("dtype", DT)
-def test_innerprod_misaligned(lib, oracle, dtype):
-    n = 70001
-    fb, fc = U.gen(24, 0, (n + 1,), dtype, inputs.SMALLINT), U.gen(24, 2, (n + 1,), dtype, inputs.SMALLINT)
+@pytest.mark.parametrize("n,ob,oc", [(70001, 1, 1), (70001, 1, 2), (3, 1, 0), (1 << 21, 3, 1), (262147, 0, 1)])
+def test_innerprod_misaligned(lib, oracle, dtype, n, ob, oc):
+    """The operands start ob and oc elements past a 16-byte boundary; small integers: exact."""
+    fb, fc = U.gen(24, 0, (n + ob,), dtype, inputs.SMALLINT), U.gen(24, 2, (n + oc,), dtype, inputs.SMALLINT)
     a = empty((1,), dtype)
-    lib.distal_innerprod(U.dev(fb)[1:].view(1, 1, n), U.dev(fc)[1:].view(1, 1, n), a)
-    assert float(U.host(a)[0]) == oracle.innerprod(fb[1:].reshape(1, 1, n), fc[1:].reshape(1, 1, n))
+    lib.distal_innerprod(U.dev(fb)[ob:].view(1, 1, n), U.dev(fc)[oc:].view(1, 1, n), a)
+    assert float(U.host(a)[0]) == oracle.innerprod(fb[ob:].reshape(1, 1, n), fc[oc:].reshape(1, 1, n))
+    lib.distal_innerprod_noalloc(U.dev(fb)[ob:].view(1, 1, n), U.dev(fc)[oc:].view(1, 1, n), a)
+    assert float(U.host(a)[0]) == oracle.innerprod(fb[ob:].reshape(1, 1, n), fc[oc:].reshape(1, 1, n))
 
 
 # ------------------------------------------------------------------ mttkrp
