@@ -17,8 +17,10 @@ that bounds it and the CPU oracle timed on a bounded sample of the same inputs:
     all    core + the k-chunk leaf shapes of the schedules (summa), mid-size and
            misaligned products (gemm_shapes), the binary64 forms of the higher-order
            calls (*_f64), every other mode (ttm_mode*, ttv_mode*, mttkrp_mode*),
-           rank-sized factors (ttm_rank32, mttkrp_rank64) and the synthetic
-           stream + MFMA kernel timed next to MTTKRP (mttkrp_floor)
+           rank-sized factors (ttm_rank32, mttkrp_rank64), the synthetic
+           stream + MFMA kernel timed next to MTTKRP (mttkrp_floor) and the
+           register-only matrix-instruction loop that checks the peak denominators
+           on the device (mfma_peak)
 
 Per-launch durations come from HIP events recorded on the stream the kernels run on
 (torch's current stream, which is the stream handed to the library).  ``roofline.traffic``
@@ -54,7 +56,7 @@ PEAK_HBM_GBS = 8000.0
 
 CORE = ["gemm_f64", "gemm_f32", "ttm", "mttkrp", "ttv", "innerprod"]
 EXTRA = ["summa", "gemm_shapes", "ttv_f64", "innerprod_f64", "ttm_f64", "mttkrp_f64", "ttv_mode0", "ttv_mode1",
-         "ttm_mode0", "ttm_mode1", "ttm_rank32", "mttkrp_floor", "mttkrp_rank64", "mttkrp_mode1", "mttkrp_mode2"]
+         "ttm_mode0", "ttm_mode1", "ttm_rank32", "mttkrp_floor", "mttkrp_rank64", "mttkrp_mode1", "mttkrp_mode2", "mfma_peak"]
 
 # rocprofv3 summary that covers a row's dominant kernel (HBM traffic per launch is read from it)
 PROFILE_OF_ROW = {
@@ -449,6 +451,23 @@ def main():
                 del T
             del F, out
         del B, C64, D64
+
+    if "mfma_peak" in want:
+        # Not a row of the method: matrix instructions on registers alone, the on-device check of the
+        # peak denominators (clock under that load x pipe width)
+        from paper_2203_08069_amd import probe
+        for f64 in (True, False):
+            dt = "f64" if f64 else "f32"
+            out = torch.empty(probe.mfma_peak_out_bytes(f64) // (8 if f64 else 4),
+                              dtype=torch.float64 if f64 else torch.float32, device=dev)
+            iters = 3000
+            r = finish(f"mfma_peak_{dt}",
+                       f"synthetic: 2048 workgroups x 4 wavefronts x {iters} rounds of 8 independent "
+                       + ("v_mfma_f64_16x16x4_f64" if f64 else "v_mfma_f32_32x32x2_f32") + " on registers, no memory traffic",
+                       dt, lambda: probe.mfma_peak(f64, iters, out), probe.mfma_peak_flops(f64, iters), float(out.numel() * out.element_size()),
+                       "mfma")
+            r["synthetic"] = True
+            del out
 
     head = rows[0]
     out = {

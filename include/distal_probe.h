@@ -40,6 +40,20 @@ int distal_probe_stream_mfma(int64_t I, int64_t J, int64_t K, const void *B, con
 /* Bytes of `out` the call above needs (0 for extents it does not accept). */
 size_t distal_probe_out_bytes(int64_t I, int64_t J, int64_t K);
 
+/*
+ * The rate of the matrix pipe on registers alone: 2048 workgroups of four wavefronts, each
+ * wavefront issuing `iters` rounds of eight independent v_mfma_f64_16x16x4_f64 (f64 != 0) or
+ * v_mfma_f32_32x32x2_f32 (f64 == 0) on operands that never change; no memory traffic but one
+ * store per lane at the end.  distal_probe_mfma_peak_flops(f64, iters) / duration is what the
+ * benchmark's peak denominators (78.6 and 157.3 TFLOP/s) are checked against on the device.
+ *   out: DEVICE scratch of at least distal_probe_mfma_peak_out_bytes(f64) bytes.
+ *   iters in [1, 2^24].  Asynchronous; nothing is allocated.
+ * Returns 0, or 1 (NULL pointer), 2 (iters), 6 (out too small), 7 (launch).
+ */
+int distal_probe_mfma_peak(int f64, int64_t iters, void *out, size_t out_bytes, void *stream);
+size_t distal_probe_mfma_peak_out_bytes(int f64);
+double distal_probe_mfma_peak_flops(int f64, int64_t iters);
+
 #ifdef __cplusplus
 }
 #endif

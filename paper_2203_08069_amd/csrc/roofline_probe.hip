@@ -20,6 +20,7 @@ namespace {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef double v4d __attribute__((ext_vector_type(4)));
 
 constexpr int kPatchStride = 68;             // floats per patch row: 256 B + 16 B
 constexpr int64_t kTargetBlocks = 768;       // as the library's MTTKRP plan: three workgroups per CU
@@ -103,6 +104,57 @@ __global__ void __launch_bounds__(256, 3) probe_stream_mfma_kernel(const ProbeAr
     for (int v = 0; v < 16; ++v) o[v] = acc[v];
 }
 
+// Nothing but matrix instructions on registers: eight independent accumulator chains per
+// wavefront, four wavefronts per SIMD, operands that never change.  What this reaches is the rate
+// of the matrix pipe at the clock the part holds under that load.  (Four wavefronts per SIMD are
+// asked for so that the accumulators stay in one register file: with the default bound the compiler
+// moved all of them between the two files in every round, and the loop measured those moves.)
+constexpr int kPeakBlocks = 2048, kPeakChains = 8;
+
+__global__ void __launch_bounds__(256, 4)
+probe_mfma_peak_f64_kernel(double *out, int64_t iters, double x) {
+    v4d acc[kPeakChains];
+#pragma unroll
+    for (int q = 0; q < kPeakChains; ++q) acc[q] = v4d{0.0, 0.0, 0.0, 0.0};
+    const double a = x + (double)(threadIdx.x & 63) * 0.0078125, b = x - (double)(threadIdx.x & 15) * 0.015625;
+    for (int64_t i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int q = 0; q < kPeakChains; ++q) acc[q] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[q], 0, 0, 0);
+    }
+    v4d s = acc[0];
+#pragma unroll
+    for (int q = 1; q < kPeakChains; ++q) s += acc[q];
+    out[(int64_t)blockIdx.x * 256 + threadIdx.x] = (s[0] + s[1]) + (s[2] + s[3]);
+}
+
+__global__ void __launch_bounds__(256, 4)
+probe_mfma_peak_f32_kernel(float *out, int64_t iters, float x) {
+    v16f acc[kPeakChains / 2];                       // 16 registers each: four chains keep the pipe full
+#pragma unroll
+    for (int q = 0; q < kPeakChains / 2; ++q)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[q][v] = 0.0f;
+    const float a = x + (float)(threadIdx.x & 63) * 0.0078125f, b = x - (float)(threadIdx.x & 31) * 0.015625f;
+    // An operand constraint on the accumulation register file makes the compiler keep the
+    // accumulators there (the a[...] form of the instruction): with the accumulators in ordinary
+    // vector registers this loop - same instruction, same operands - issued 12 % slower (137.7
+    // against 155 TFLOP/s, same clock), which is a property of the loop's fixed registers, not of
+    // the pipe; the contraction kernels measured no faster in that form and do not use it.
+    asm volatile("" : : "a"(x));
+    for (int64_t i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int q = 0; q < kPeakChains / 2; ++q) acc[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[q], 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int q = 0; q < kPeakChains / 2; ++q)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s += acc[q][v];
+    out[(int64_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 struct ProbePlan { int64_t kgroups, rgroups, wsplit, nsplit, blocks; };
 
 bool probe_plan(int64_t I, int64_t J, int64_t K, ProbePlan *p) {
@@ -145,6 +197,23 @@ int distal_probe_stream_mfma(int64_t I, int64_t J, int64_t K, const void *B, con
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (lds) hipLaunchKernelGGL(probe_stream_mfma_kernel<true>, dim3((unsigned)p.blocks), dim3(256), 0, s, a);
     else hipLaunchKernelGGL(probe_stream_mfma_kernel<false>, dim3((unsigned)p.blocks), dim3(256), 0, s, a);
+    return hipGetLastError() == hipSuccess ? 0 : 7;
+}
+
+size_t distal_probe_mfma_peak_out_bytes(int f64) { return (size_t)kPeakBlocks * 256 * (f64 ? sizeof(double) : sizeof(float)); }
+
+double distal_probe_mfma_peak_flops(int f64, int64_t iters) {
+    // wavefronts x iterations x instructions per iteration x flop per instruction (16x16x4 resp. 32x32x2, two per term)
+    return (double)kPeakBlocks * 4.0 * (double)iters * (double)kPeakChains * (f64 ? 2048.0 : 4096.0);
+}
+
+int distal_probe_mfma_peak(int f64, int64_t iters, void *out, size_t out_bytes, void *stream) {
+    if (iters < 1 || iters > ((int64_t)1 << 24)) return 2;
+    if (!out) return 1;
+    if (out_bytes < distal_probe_mfma_peak_out_bytes(f64)) return 6;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (f64) hipLaunchKernelGGL(probe_mfma_peak_f64_kernel, dim3(kPeakBlocks), dim3(256), 0, s, static_cast<double *>(out), iters, 0.5);
+    else hipLaunchKernelGGL(probe_mfma_peak_f32_kernel, dim3(kPeakBlocks), dim3(256), 0, s, static_cast<float *>(out), iters, 0.5f);
     return hipGetLastError() == hipSuccess ? 0 : 7;
 }
 

@@ -10,7 +10,8 @@ import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdistal_probe.so")
-EXPORTS = ("distal_probe_stream_mfma", "distal_probe_out_bytes")
+EXPORTS = ("distal_probe_stream_mfma", "distal_probe_out_bytes", "distal_probe_mfma_peak",
+           "distal_probe_mfma_peak_out_bytes", "distal_probe_mfma_peak_flops")
 
 _lib = None
 
@@ -26,6 +27,12 @@ def load_library() -> ctypes.CDLL:
         lib.distal_probe_stream_mfma.restype = ctypes.c_int
         lib.distal_probe_out_bytes.argtypes = [i64, i64, i64]
         lib.distal_probe_out_bytes.restype = ctypes.c_size_t
+        lib.distal_probe_mfma_peak.argtypes = [ctypes.c_int, i64, vp, ctypes.c_size_t, vp]
+        lib.distal_probe_mfma_peak.restype = ctypes.c_int
+        lib.distal_probe_mfma_peak_out_bytes.argtypes = [ctypes.c_int]
+        lib.distal_probe_mfma_peak_out_bytes.restype = ctypes.c_size_t
+        lib.distal_probe_mfma_peak_flops.argtypes = [ctypes.c_int, i64]
+        lib.distal_probe_mfma_peak_flops.restype = ctypes.c_double
         _lib = lib
     return _lib
 
@@ -47,3 +54,22 @@ def stream_mfma(B, F, out, lds: bool):
         ctypes.c_void_p(torch.cuda.current_stream(B.device).cuda_stream))
     if rc != 0:
         raise RuntimeError(f"distal_probe_stream_mfma failed with status {rc}")
+
+
+def mfma_peak_out_bytes(f64: bool) -> int:
+    return int(load_library().distal_probe_mfma_peak_out_bytes(int(bool(f64))))
+
+
+def mfma_peak_flops(f64: bool, iters: int) -> float:
+    return float(load_library().distal_probe_mfma_peak_flops(int(bool(f64)), int(iters)))
+
+
+def mfma_peak(f64: bool, iters: int, out):
+    """One launch of the register-only matrix-instruction loop on torch's current stream."""
+    import torch
+    assert out.is_cuda and out.is_contiguous()
+    rc = load_library().distal_probe_mfma_peak(
+        int(bool(f64)), int(iters), ctypes.c_void_p(out.data_ptr()), out.numel() * out.element_size(),
+        ctypes.c_void_p(torch.cuda.current_stream(out.device).cuda_stream))
+    if rc != 0:
+        raise RuntimeError(f"distal_probe_mfma_peak failed with status {rc}")

@@ -364,6 +364,13 @@ def test_probe_library_exports_and_argument_errors():
     assert f(32, 8, 256, None, b, 1, c, 1 << 30, None) == 1
     assert f(32, 8, 256, P(FAKE + 4), b, 1, c, 1 << 30, None) == 4
     assert f(32, 8, 256, a, b, 1, c, 16, None) == 6
+    g = lib.distal_probe_mfma_peak
+    assert lib.distal_probe_mfma_peak_out_bytes(1) == 2048 * 256 * 8 and lib.distal_probe_mfma_peak_out_bytes(0) == 2048 * 256 * 4
+    assert lib.distal_probe_mfma_peak_flops(1, 10) == 2048 * 4 * 10 * 8 * 2048.0      # 16x16x4: 2048 flop per instruction
+    assert lib.distal_probe_mfma_peak_flops(0, 10) == 2048 * 4 * 10 * 8 * 4096.0      # 32x32x2: 4096
+    assert g(1, 0, c, 1 << 30, None) == 2
+    assert g(1, 10, None, 1 << 30, None) == 1
+    assert g(0, 10, c, 16, None) == 6
 
 
 def test_package_and_library_versions_agree(lib):
