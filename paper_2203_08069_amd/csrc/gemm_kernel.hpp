@@ -435,6 +435,7 @@ contract_fast_kernel(ContractArgs<T> args) {
     constexpr int VEC = Cfg::VEC, KG = Cfg::KG, MI = Cfg::MI, NI = Cfg::NI;
     constexpr int CV = Cfg::CV, NG = Cfg::NG, NT = Cfg::NT, NKG = BK / KG;
     constexpr int ARL = Cfg::A_ROWLEN / VEC;          // 16-byte pieces per staged A row
+    constexpr bool DEEP = BM == 32 || BN == 32;       // rank-sized tiles: two slabs of loads in flight
     static_assert(Cfg::A_VECS % NT == 0 && Cfg::B_VECS % NT == 0, "slab vectors must divide over threads");
 
     args.A += (int64_t)blockIdx.y * args.batch_a;
@@ -533,6 +534,43 @@ contract_fast_kernel(ContractArgs<T> args) {
 
     const int a_rd = a_read_offset<Cfg>(wm, li, ls), b_rd = b_read_offset<Cfg>(wn, li, ls);
 
+    if constexpr (DEEP) {
+        // Narrow tiles do 16 flop per byte of the large operand: the product is bound by HBM, and one
+        // slab in flight per workgroup is too little to cover its latency.  Two register sets: slab
+        // t is in LDS buffer t & 1, slab t+1 in one set, slab t+2 in flight into the other, and
+        // slab t+3 is requested into the first as soon as it has been copied to LDS.
+        vec_t ra2[Cfg::A_PER_T], rb2[Cfg::B_PER_T];
+        auto store_from = [&](const vec_t (&xa)[Cfg::A_PER_T], const vec_t (&xb)[Cfg::B_PER_T], int stage) {
+            T *st = lds + stage * Cfg::STAGE_ELEMS;
+#pragma unroll
+            for (int p = 0; p < Cfg::A_PER_T; ++p) *reinterpret_cast<vec_t *>(st + a_lds[p]) = xa[p];
+#pragma unroll
+            for (int p = 0; p < Cfg::B_PER_T; ++p) *reinterpret_cast<vec_t *>(st + b_lds[p]) = xb[p];
+        };
+        const T *st0 = lds, *st1 = lds + Cfg::STAGE_ELEMS;
+        load_into(ra, rb, 0);
+        store_from(ra, rb, 0);
+        load_into(ra, rb, 1);
+        load_into(ra2, rb2, 2);
+        __syncthreads();
+        int64_t t = 0;
+        for (; t + 2 <= nk; t += 2) {
+            mfma_groups<T, Cfg, 0, (NKG + 1) / 2>(st0 + a_rd, st0 + b_rd, acc);
+            store_from(ra, rb, 1);           // slab t+1
+            load_into(ra, rb, t + 3);
+            mfma_groups<T, Cfg, (NKG + 1) / 2, NKG>(st0 + a_rd, st0 + b_rd, acc);
+            __syncthreads();
+            mfma_groups<T, Cfg, 0, (NKG + 1) / 2>(st1 + a_rd, st1 + b_rd, acc);
+            store_from(ra2, rb2, 0);         // slab t+2 (on the last pass: a copy nobody reads)
+            load_into(ra2, rb2, t + 4);
+            mfma_groups<T, Cfg, (NKG + 1) / 2, NKG>(st1 + a_rd, st1 + b_rd, acc);
+            __syncthreads();
+        }
+        if (t < nk) {                        // an odd number of slabs: the last one sits in buffer 0
+            mfma_groups<T, Cfg, 0, NKG>(st0 + a_rd, st0 + b_rd, acc);
+            __syncthreads();                 // both buffers are free again (the trailing-terms slab reuses one)
+        }
+    } else {
     // slab t is in LDS buffer t & 1; slab t+1 is in registers; slab t+2 is requested
     // during the multiply of slab t
     load_global(0);
@@ -547,6 +585,7 @@ contract_fast_kernel(ContractArgs<T> args) {
         load_global(t + 2);
         mfma_groups<T, Cfg, (NKG + 1) / 2, NKG>(st + a_rd, st + b_rd, acc);
         __syncthreads();
+    }
     }
 
     if constexpr (EDGE == 2) {
