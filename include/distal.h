@@ -17,7 +17,11 @@
  *     allocates, frees or synchronises inside these calls.  Inputs are only read.
  *   - `stream` is a hipStream_t passed as void*; NULL is the default stream.
  *     Calls are asynchronous: outputs are valid once the stream reaches the
- *     point of the call.
+ *     point of the call.  A call enqueues kernels only (no memset or copy
+ *     nodes), so sequences of calls can be recorded under HIP stream capture
+ *     and replayed as a graph, provided the same call (same dtype and
+ *     extents) has run once outside the capture on that device: the first
+ *     launch of a kernel raises its LDS limit, which is not a stream operation.
  *   - Return value: DISTAL_OK (0) or a distal_status error code.  All argument
  *     checks happen on the host before anything is launched, so a call that
  *     returns an argument error has touched no device memory.
