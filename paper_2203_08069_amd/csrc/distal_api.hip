@@ -101,6 +101,9 @@ template <typename T, int BM, int BN, int BK, int WM, int WN, bool TA>
 int launch_tiles(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
     constexpr int VEC = 16 / (int)sizeof(T);
     if (a.K < BK) return launch_contract<T, 128, 128, 16, 2, 2, kGuarded, TA>(a, batch, stream);   // no whole slab
+    // leading dimensions so large that a slab's rows lie more than 4 GiB apart: the straight-line
+    // kernel's 32-bit offsets do not reach, the bounds-checked kernel addresses with pointers
+    if (!fast_offsets_fit<T, BM, BN, BK, TA>(a.lda, a.ldb)) return launch_contract<T, 128, 128, 16, 2, 2, kGuarded, TA>(a, batch, stream);
     const int64_t k_main = a.K / BK * BK, k_tail = a.K - k_main;
     if (k_tail == 0)
         return (a.M % BM == 0 && a.N % BN == 0) ? launch_contract<T, BM, BN, BK, WM, WN, kWhole, TA>(a, batch, stream)

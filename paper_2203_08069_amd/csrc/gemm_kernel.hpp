@@ -398,6 +398,16 @@ contract_kernel(ContractArgs<T> args) {
             }
 }
 
+// Whether the 32-bit byte offsets of contract_fast_kernel cover a slab of this tile for these
+// leading dimensions: the last row of a slab, plus one row length, from the tile's first element.
+template <typename T, int BM, int BN, int BK, bool TA>
+inline bool fast_offsets_fit(int64_t lda, int64_t ldb) {
+    const double limit = 4294967296.0 - 64.0;
+    const double a = TA ? ((double)(BK - 1) * (double)lda + BM) : ((double)(BM - 1) * (double)lda + BK);
+    const double b = (double)(BK - 1) * (double)ldb + BN;
+    return a * sizeof(T) < limit && b * sizeof(T) < limit;
+}
+
 // ---------------------------------------------------------------------------
 // The same contraction for the case every tile and slab is full and every operand
 // 16-byte aligned (M % BM == 0, N % BN == 0, K % BK == 0, aligned bases and leading
@@ -430,7 +440,6 @@ contract_fast_kernel(ContractArgs<T> args) {
     typedef Mfma<T> MF;
     typedef typename VecOf<T, Cfg::VEC>::type vec_t;
     typedef typename VecOf<T, Cfg::CV>::type cvec_t;
-    typedef typename GlobalVecOf<T, Cfg::VEC>::type gvec_t;
     typedef typename GlobalVecOf<T, Cfg::CV>::type gcvec_t;
     constexpr int VEC = Cfg::VEC, KG = Cfg::KG, MI = Cfg::MI, NI = Cfg::NI;
     constexpr int CV = Cfg::CV, NG = Cfg::NG, NT = Cfg::NT, NKG = BK / KG;
@@ -456,20 +465,30 @@ contract_fast_kernel(ContractArgs<T> args) {
     const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
     const int64_t nk = args.K / BK;
 
-    // per-thread element offsets of its 16-byte pieces inside a slab, and where they go in LDS
-    int64_t a_off[Cfg::A_PER_T], b_off[Cfg::B_PER_T];
+    // Per-thread byte offsets of its 16-byte pieces from the tile's first row and column, and where
+    // they go in LDS.  The loads are buffer loads: the slab's base travels in a descriptor in scalar
+    // registers and a lane supplies its 32-bit offset, which never changes, so no vector arithmetic
+    // is spent on addresses inside the k-loop (with 64-bit pointers per lane the loop held three
+    // 64-bit vector adds per load; together with the constant LDS buffers of the two-slab trip
+    // below their removal was worth 2.4 points at 8192^3 and 5 to 9 at 2000^3...3000^3).  The offsets
+    // are unsigned 32-bit: the host launches this kernel only where (rows of a slab - 1) x leading
+    // dimension fits (fast_offsets_fit), and bounds checking by the descriptor is off (its range is
+    // the whole 4 GiB): every address is in bounds by construction, exactly as with pointers.
+    int a_off[Cfg::A_PER_T], b_off[Cfg::B_PER_T];
     int a_lds[Cfg::A_PER_T], b_lds[Cfg::B_PER_T];
+    const char *a_tile = reinterpret_cast<const char *>(args.A + (TA ? m0 : m0 * args.lda));
+    const char *b_tile = reinterpret_cast<const char *>(args.B + n0);
 #pragma unroll
     for (int p = 0; p < Cfg::A_PER_T; ++p) {
         const int v = tid + p * NT, r = v / ARL, kv = v % ARL;
         if constexpr (TA) {
             int64_t m = m0 + kv * VEC;
             if (EDGE && m > args.M - VEC) m = args.M - VEC;
-            a_off[p] = (int64_t)r * args.lda + m;
+            a_off[p] = (int)(unsigned)(((int64_t)r * args.lda + (m - m0)) * (int64_t)sizeof(T));
         } else {
             int64_t m = m0 + r;
             if (EDGE && m > args.M - 1) m = args.M - 1;
-            a_off[p] = m * args.lda + kv * VEC;
+            a_off[p] = (int)(unsigned)(((m - m0) * args.lda + kv * VEC) * (int64_t)sizeof(T));
         }
         a_lds[p] = r * Cfg::LDA_S + kv * VEC;
     }
@@ -478,20 +497,26 @@ contract_fast_kernel(ContractArgs<T> args) {
         const int v = tid + p * NT, r = v / (BN / VEC), cv = v % (BN / VEC);
         int64_t n = n0 + cv * VEC;
         if (EDGE && n > args.N - VEC) n = args.N - VEC;
-        b_off[p] = (int64_t)r * args.ldb + n;
+        b_off[p] = (int)(unsigned)(((int64_t)r * args.ldb + (n - n0)) * (int64_t)sizeof(T));
         b_lds[p] = Cfg::A_ELEMS + r * Cfg::LDB_S + cv * VEC;
     }
+    // raw buffer, no stride, the full 32-bit range; word 3 is the 32-bit data format of this family
+    auto slab_rsrc = [&](const char *base) {
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(base), 0, -1, 0x00020000);
+    };
 
     vec_t ra[Cfg::A_PER_T], rb[Cfg::B_PER_T];
     // slab index past the end is clamped to the last slab: a redundant, in-bounds reload
     auto load_into = [&](vec_t (&xa)[Cfg::A_PER_T], vec_t (&xb)[Cfg::B_PER_T], int64_t t) {
         const int64_t k0 = (t < nk ? t : nk - 1) * BK;
-        const T *ap = args.A + (TA ? k0 * args.lda : k0);
-        const T *bp = args.B + k0 * args.ldb;
+        const auto ar = slab_rsrc(a_tile + (TA ? k0 * args.lda : k0) * (int64_t)sizeof(T));
+        const auto br = slab_rsrc(b_tile + k0 * args.ldb * (int64_t)sizeof(T));
 #pragma unroll
-        for (int p = 0; p < Cfg::A_PER_T; ++p) xa[p] = *reinterpret_cast<const gvec_t *>(ap + a_off[p]);
+        for (int p = 0; p < Cfg::A_PER_T; ++p)
+            xa[p] = __builtin_bit_cast(vec_t, __builtin_amdgcn_raw_buffer_load_b128(ar, a_off[p], 0, 0));
 #pragma unroll
-        for (int p = 0; p < Cfg::B_PER_T; ++p) xb[p] = *reinterpret_cast<const gvec_t *>(bp + b_off[p]);
+        for (int p = 0; p < Cfg::B_PER_T; ++p)
+            xb[p] = __builtin_bit_cast(vec_t, __builtin_amdgcn_raw_buffer_load_b128(br, b_off[p], 0, 0));
     };
     auto load_global = [&](int64_t t) { load_into(ra, rb, t); };
     auto store_lds = [&](int stage) {
@@ -571,21 +596,31 @@ contract_fast_kernel(ContractArgs<T> args) {
             __syncthreads();                 // both buffers are free again (the trailing-terms slab reuses one)
         }
     } else {
-    // slab t is in LDS buffer t & 1; slab t+1 is in registers; slab t+2 is requested
-    // during the multiply of slab t
-    load_global(0);
-    store_lds(0);
-    load_global(1);
-    __syncthreads();
-    for (int64_t t = 0; t < nk; ++t) {
-        const int stage = (int)(t & 1);
-        const T *st = lds + stage * Cfg::STAGE_ELEMS;
-        mfma_groups<T, Cfg, 0, (NKG + 1) / 2>(st + a_rd, st + b_rd, acc);
-        store_lds(stage ^ 1);        // slab t+1 (on the last pass: a copy nobody reads)
-        load_global(t + 2);
-        mfma_groups<T, Cfg, (NKG + 1) / 2, NKG>(st + a_rd, st + b_rd, acc);
+        // slab t is in LDS buffer t & 1; slab t+1 is in registers; slab t+2 is requested during the
+        // multiply of slab t.  Two slabs per trip, so that the buffer of each half is a constant and
+        // the LDS addresses need no arithmetic inside the loop.
+        const T *st0 = lds, *st1 = lds + Cfg::STAGE_ELEMS;
+        load_global(0);
+        store_lds(0);
+        load_global(1);
         __syncthreads();
-    }
+        int64_t t = 0;
+        for (; t + 2 <= nk; t += 2) {
+            mfma_groups<T, Cfg, 0, (NKG + 1) / 2>(st0 + a_rd, st0 + b_rd, acc);
+            store_lds(1);                // slab t+1
+            load_global(t + 2);
+            mfma_groups<T, Cfg, (NKG + 1) / 2, NKG>(st0 + a_rd, st0 + b_rd, acc);
+            __syncthreads();
+            mfma_groups<T, Cfg, 0, (NKG + 1) / 2>(st1 + a_rd, st1 + b_rd, acc);
+            store_lds(0);                // slab t+2 (on the last pass: a copy nobody reads)
+            load_global(t + 3);
+            mfma_groups<T, Cfg, (NKG + 1) / 2, NKG>(st1 + a_rd, st1 + b_rd, acc);
+            __syncthreads();
+        }
+        if (t < nk) {                    // an odd number of slabs: the last one sits in buffer 0
+            mfma_groups<T, Cfg, 0, NKG>(st0 + a_rd, st0 + b_rd, acc);
+            __syncthreads();             // both buffers are free again (the trailing-terms slab reuses one)
+        }
     }
 
     if constexpr (EDGE == 2) {
@@ -593,18 +628,18 @@ contract_fast_kernel(ContractArgs<T> args) {
         // the loop's last barrier (both buffers are free then) and multiplied in full
         const int tail = (int)(args.K - nk * BK);            // block-uniform
         if (tail > 0) {
-            const T *ap = args.A + (TA ? nk * BK * args.lda : nk * BK);
-            const T *bp = args.B + nk * BK * args.ldb;
+            const auto ar = slab_rsrc(a_tile + (TA ? nk * BK * args.lda : nk * BK) * (int64_t)sizeof(T));
+            const auto br = slab_rsrc(b_tile + nk * BK * args.ldb * (int64_t)sizeof(T));
 #pragma unroll
             for (int p = 0; p < Cfg::A_PER_T; ++p) {
                 const int v = tid + p * NT, r = v / ARL, kv = v % ARL;
                 const bool valid = TA ? r < tail : kv * VEC < tail;
-                ra[p] = valid ? *reinterpret_cast<const gvec_t *>(ap + a_off[p]) : vec_t(T(0));
+                ra[p] = valid ? __builtin_bit_cast(vec_t, __builtin_amdgcn_raw_buffer_load_b128(ar, a_off[p], 0, 0)) : vec_t(T(0));
             }
 #pragma unroll
             for (int p = 0; p < Cfg::B_PER_T; ++p) {
                 const int r = (tid + p * NT) / (BN / VEC);
-                rb[p] = r < tail ? *reinterpret_cast<const gvec_t *>(bp + b_off[p]) : vec_t(T(0));
+                rb[p] = r < tail ? __builtin_bit_cast(vec_t, __builtin_amdgcn_raw_buffer_load_b128(br, b_off[p], 0, 0)) : vec_t(T(0));
             }
             store_lds(0);
             __syncthreads();

@@ -219,3 +219,61 @@ def test_mttkrp_mode_past_2_to_32(lib, oracle, big, mode):
         hB = np.ascontiguousarray((big[:, x:x + 1, :] if mode == 1 else big[:, :, x:x + 1]).cpu().numpy())
         ref = oracle.mttkrp_mode(mode, hB, hC, hD)[0]
         U.assert_close(A[x].cpu().numpy(), ref, np.float32, I * (K if mode == 1 else J))
+
+
+# (tile, rows of the view, what the case exercises).  The tensor viewed as `rows` rows gives a
+# leading dimension of (2^32 + 2^22) / rows elements.
+HUGE_LD = [
+    ((256, 128), 1024, "rows of a 256-row tile 4.28e9 bytes apart: unsigned 32-bit offsets, just inside their range"),
+    ((256, 128), 512, "8.5e9 bytes apart: beyond 32 bits, the pointer-addressed kernel takes over"),
+    ((128, 128), 512, "4.27e9 bytes apart within a 128-row tile: inside the range again"),
+    ((64, 64), 128, "8.5e9 bytes apart within a 64-row tile: beyond"),
+]
+
+
+@pytest.mark.parametrize("tile,rows,why", HUGE_LD, ids=[f"{t[0]}x{t[1]}-rows{r}" for t, r, _ in HUGE_LD])
+def test_gemm_left_operand_rows_gigabytes_apart(lib, oracle, big, tile, rows, why):
+    """Left operand: the first 256 columns of the tensor viewed as a few very long rows, so that the
+    rows of one tile lie up to and beyond 4 GiB apart (the straight-line kernels address a tile
+    with 32-bit byte offsets and must hand over where those do not reach)."""
+    import torch
+    ld = I * J * K // rows
+    Kd, N = 256, 128
+    A = big.view(rows, ld)[:, :Kd]
+    Bm = devgen(20, (Kd, N))
+    C = torch.full((rows, N), float("nan"), dtype=torch.float32, device="cuda:0")
+    lib.distal_gemm_tiled(tile, A, Bm, C)
+    assert bool(torch.isfinite(C).all())
+    hB = host(20, 0, Kd * N).reshape(Kd, N)
+    hA = np.stack([host(0, r * ld, Kd) for r in range(rows)])
+    U.assert_close(C.cpu().numpy(), oracle.gemm(hA, hB), np.float32, Kd)
+    C2 = torch.full((rows, N), float("nan"), dtype=torch.float32, device="cuda:0")
+    lib.distal_gemm(A, Bm, C2)                                  # and whatever the plan picks
+    U.assert_close(C2.cpu().numpy(), oracle.gemm(hA, hB), np.float32, Kd)
+
+
+@pytest.mark.parametrize("transposed_left", [False, True])
+def test_gemm_slab_rows_gigabytes_apart(lib, oracle, big, transposed_left):
+    """The contracted index walks rows 537 MB apart (32 rows of the tensor): for the right operand,
+    and for a left operand stored K x M, the 16 rows of one slab then span 8 GB."""
+    import torch
+    Kd, ld = 32, I * J * K // 32
+    wide = big.view(Kd, ld)
+    M, N = 256, 192
+    if transposed_left:
+        A, Bm = wide[:, 4096:4096 + M], devgen(21, (Kd, N))
+        hA = np.stack([host(0, k * ld + 4096, M) for k in range(Kd)]).T
+        hB = host(21, 0, Kd * N).reshape(Kd, N)
+    else:
+        A, Bm = devgen(22, (M, Kd)), wide[:, 8192:8192 + N]
+        hA = host(22, 0, M * Kd).reshape(M, Kd)
+        hB = np.stack([host(0, k * ld + 8192, N) for k in range(Kd)])
+    ref = oracle.gemm(np.ascontiguousarray(hA), hB)
+    for tile in ((128, 128), (64, 64), (128, 64)):
+        C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda:0")
+        lib.distal_gemm_tiled(tile, A, Bm, C, transposed_left=transposed_left)
+        U.assert_close(C.cpu().numpy(), ref, np.float32, Kd)
+    if not transposed_left:
+        C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda:0")
+        lib.distal_gemm(A, Bm, C)
+        U.assert_close(C.cpu().numpy(), ref, np.float32, Kd)
