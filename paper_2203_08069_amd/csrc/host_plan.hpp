@@ -67,19 +67,21 @@ inline int tile_candidates(bool f64, bool ta, int64_t M, int64_t N, int64_t K, T
         // added onto an old C the largest tile pays from deeper products on: its one workgroup per
         // compute unit has nothing to overlap the read-modify-write of its 256 KiB of C with
         // (8192 x 8192 x 1024 under accumulate: 82.8 % of peak, 256 x 128 tiles 85.7 %)
-        c[0] = {1, K >= (acc ? 4096 : 1024), 256, 256, ta ? 16 : 32, {0.906, 0.909, 0.911, 0.913, 0.915, 0.919}};
-        c[1] = {2, K >= 512, 256, 128, 16, {0.853, 0.886, 0.887, 0.893, 0.899, 0.901}};
+        // (the two largest tiles measure within half a point of each other on large grids, 95.1 and
+        // 95.0 % at 8192^3: they carry the same last entry, and the larger one, listed first, wins the tie)
+        c[0] = {1, K >= (acc ? 4096 : 1024), 256, 256, ta ? 16 : 32, {0.927, 0.931, 0.933, 0.934, 0.940, 0.945}};
+        c[1] = {2, K >= (acc ? 512 : 256), 256, 128, 16, {0.882, 0.923, 0.932, 0.938, 0.943, 0.945}};
         // a product of at most 256 terms added onto an old C is bound by the traffic of C: tiles with
         // 128 columns and 64 rows (512-byte runs of C, four workgroups per compute unit) then measure
         // 4..5 points ahead of 128 x 128 and of 128 x 64
         const bool thin_acc = acc && K <= 256;
-        c[2] = {3, !thin_acc, 128, 128, 16, {0.720, 0.808, 0.853, 0.865, 0.873, 0.881}};
-        c[3] = {4, true, 64, 64, 16, {0.461, 0.650, 0.716, 0.737, 0.758, 0.765}};
-        c[4] = {9, !thin_acc, 128, 64, 16, {0.623, 0.762, 0.785, 0.812, 0.822, 0.835}};
-        c[5] = {10, true, 64, 128, 16, {0.625, 0.727, 0.779, 0.808, 0.825, 0.833}};
+        c[2] = {3, !thin_acc, 128, 128, 16, {0.775, 0.884, 0.905, 0.923, 0.933, 0.939}};
+        c[3] = {4, K < 256, 64, 64, 16, {0.628, 0.759, 0.806, 0.829, 0.835, 0.852}};
+        c[4] = {9, !thin_acc, 128, 64, 16, {0.666, 0.830, 0.877, 0.835, 0.880, 0.900}};
+        c[5] = {10, true, 64, 128, 16, {0.666, 0.832, 0.876, 0.877, 0.885, 0.902}};
         // 64 x 64 with 32-deep slabs: half the barriers per term; pays from K = 256 on (binary32 only:
         // the same in binary64 measured 3..9 % slower)
-        c[6] = {11, K >= 256, 64, 64, 32, {0.50, 0.67, 0.74, 0.776, 0.80, 0.817}};
+        c[6] = {11, K >= 256, 64, 64, 32, {0.614, 0.763, 0.812, 0.828, 0.830, 0.836}};
         c[7] = {5, n64, 256, 64, 16, {}};
         c[8] = {6, n32 && K >= 32, 128, 32, 32, {}};
         c[9] = {7, m64, 64, 256, 16, {}};
@@ -87,11 +89,11 @@ inline int tile_candidates(bool f64, bool ta, int64_t M, int64_t N, int64_t K, T
         narrow_eff(c[7], 0.891); narrow_eff(c[8], 0.575); narrow_eff(c[9], 0.883); narrow_eff(c[10], 0.585);
         return 11;
     }
-    c[0] = {2, K >= 2048, 256, 128, 16, {0.901, 0.903, 0.903, 0.902, 0.907, 0.908}};
-    c[1] = {3, true, 128, 128, 16, {0.790, 0.867, 0.865, 0.875, 0.885, 0.892}};
-    c[2] = {4, true, 64, 64, 16, {0.587, 0.813, 0.813, 0.829, 0.848, 0.849}};
-    c[3] = {5, true, 128, 64, 16, {0.665, 0.809, 0.853, 0.837, 0.871, 0.886}};
-    c[4] = {7, true, 64, 128, 16, {0.660, 0.823, 0.855, 0.840, 0.873, 0.885}};
+    c[0] = {2, K >= 2048, 256, 128, 16, {0.863, 0.941, 0.943, 0.941, 0.946, 0.945}};
+    c[1] = {3, true, 128, 128, 16, {0.883, 0.935, 0.937, 0.941, 0.949, 0.954}};
+    c[2] = {4, true, 64, 64, 16, {0.668, 0.832, 0.889, 0.883, 0.917, 0.909}};
+    c[3] = {5, true, 128, 64, 16, {0.774, 0.851, 0.855, 0.871, 0.880, 0.890}};
+    c[4] = {7, true, 64, 128, 16, {0.773, 0.855, 0.903, 0.900, 0.921, 0.929}};
     c[5] = {6, n32, 128, 32, 16, {}};
     c[6] = {8, m32, 32, 256, 16, {}};
     narrow_eff(c[5], 0.633); narrow_eff(c[6], 0.560);
@@ -111,6 +113,12 @@ inline double rounds_cost(int64_t tiles, const TileCandidate &c) {
     return (double)J * (double)(c.bm * c.bn) / e;
 }
 
+// A tile as wide as the output (or as tall) lets each slab of the long operand be read by exactly
+// one workgroup instead of by two or four that must meet in L2: the tensor-times-matrix shapes
+// (2^20 x 256 x 1024) measure 1.2 to 2 points more on 256 x 256 binary32 tiles than on 256 x 128
+// ones, which are the faster tile on square grids of the same depth.
+inline double span_factor(int64_t tm, int64_t tn) { return (tm == 1 || tn == 1) ? 0.975 : 1.0; }
+
 // The tile with the least estimated time for a product run as one launch.
 inline TilePick pick_tile(bool f64, bool ta, int64_t M, int64_t N, int64_t K, int64_t batch, bool acc = false) {
     TileCandidate cand[kMaxTileCandidates];
@@ -118,8 +126,8 @@ inline TilePick pick_tile(bool f64, bool ta, int64_t M, int64_t N, int64_t K, in
     TilePick pick{4, 64, 64, 16, 1e300};
     for (int i = 0; i < n; ++i) {
         if (!cand[i].eligible) continue;
-        const int64_t t = ((M + cand[i].bm - 1) / cand[i].bm) * ((N + cand[i].bn - 1) / cand[i].bn) * batch;
-        const double c = rounds_cost(t, cand[i]);
+        const int64_t tm = (M + cand[i].bm - 1) / cand[i].bm, tn = (N + cand[i].bn - 1) / cand[i].bn;
+        const double c = rounds_cost(tm * tn * batch, cand[i]) * span_factor(tm, tn);
         if (c < pick.cost) pick = TilePick{cand[i].id, cand[i].bm, cand[i].bn, cand[i].bk, c};   // earlier candidates win ties
     }
     return pick;
@@ -150,7 +158,8 @@ inline ProductPlan plan_product(bool f64, bool ta, int64_t M, int64_t N, int64_t
             if (lines < 1 || cut >= (split == 1 ? M : N)) continue;
             const TilePick rest = split == 1 ? pick_tile(f64, ta, M - cut, N, K, batch, acc)
                                              : pick_tile(f64, ta, M, N - cut, K, batch, acc);
-            const double total = rounds_cost(lines * per_line, c) + rest.cost + launch_cost;
+            const double total = rounds_cost(lines * per_line, c) * span_factor(split == 1 ? lines : tm, split == 1 ? tn : lines)
+                                 + rest.cost + launch_cost;
             if (total < 0.985 * best) {                                             // worth a second launch
                 best = total / 0.985;
                 plan = ProductPlan{TilePick{c.id, c.bm, c.bn, c.bk, total}, split, cut, rest};

@@ -197,49 +197,50 @@ def test_gemm_plan_choice(lib):
     F32, F64 = 0, 1
     tile, plan = binding.gemm_tile, binding.gemm_plan
     # headline and fp32 GEMM (BASELINE configs[1]), TTM (configs[3]) along modes 2, 0, 1
-    assert tile(F64, False, 8192, 8192, 8192) == (256, 128, 16)
-    assert tile(F32, False, 8192, 8192, 8192) == (256, 256, 32)
-    assert tile(F32, False, 1 << 20, 256, 1024) == (256, 256, 32)
+    assert tile(F64, False, 8192, 8192, 8192) == (128, 128, 16)
+    assert tile(F32, False, 8192, 8192, 8192) == (256, 128, 16)
+    assert tile(F32, False, 1 << 20, 256, 1024) == (256, 256, 32)      # as wide as the output: the tensor is read once
     assert tile(F32, True, 256, 1 << 20, 1024) == (256, 256, 16)
     assert tile(F32, True, 256, 1024, 1024, batch=1024) == (256, 256, 16)
     assert tile(F64, False, 1 << 20, 256, 1024) == (128, 128, 16)
-    # SUMMA k-chunks: shallow products take the smaller tiles
-    for K in (256, 512, 1024):
+    # SUMMA k-chunks
+    for K in (256, 512, 1024, 2048):
         assert tile(F64, False, 8192, 8192, K) == (128, 128, 16)
-    assert tile(F64, False, 8192, 8192, 2048) == (256, 128, 16)
     assert tile(F32, False, 8192, 8192, 512) == (256, 128, 16)
-    assert tile(F32, False, 8192, 8192, 256) == (128, 128, 16)
-    assert tile(F32, False, 8192, 8192, 1040) == (256, 256, 32)     # K % 32 == 16: one more, half-filled slab
+    assert tile(F32, False, 8192, 8192, 256) == (256, 128, 16)
+    assert tile(F32, False, 8192, 8192, 128) == (128, 128, 16)
+    assert tile(F32, False, 8192, 8192, 1040) == (256, 128, 16)
+    assert tile(F32, False, 4096, 4096, 4096) == (256, 256, 32)     # one tile per compute unit
     # rank-sized outputs: a 32- or 64-wide short side on the narrow operand's side
     assert tile(F32, False, 1 << 20, 32, 1024) == (128, 32, 32)
-    assert tile(F32, False, 1 << 20, 64, 1024) == (256, 64, 16)
+    assert tile(F32, False, 1 << 20, 64, 1024) == (128, 64, 16)
     assert tile(F32, True, 32, 1 << 20, 1024) == (32, 256, 32)
     assert tile(F64, False, 1 << 19, 16, 1024) == (128, 32, 16)
     assert tile(F64, True, 64, 1 << 19, 1024) == (64, 128, 16)
-    # ragged: 8200 rows are 8.25 rounds of 256 x 128 tiles: the first 8192 rows are eight whole rounds
+    # ragged: 8200 rows are 16.25 rounds of 128 x 128 tiles: the first 8192 rows are sixteen whole rounds
     # of them (the tile reported), the other 8 rows a second launch of small tiles
-    assert tile(F64, False, 8200, 8192, 8192) == (256, 128, 16)
-    # 8000^3: 2016 tiles of 256 x 128 pad the output by 3 %, 7875 of 128 x 64 by 0.8 %
-    assert tile(F64, False, 8000, 8000, 8000) == (128, 64, 16)
+    assert tile(F64, False, 8200, 8192, 8192) == (128, 128, 16)
+    # 8000^3: 3969 tiles of 128 x 128 pad the output by 1.6 %, 7875 of 64 x 128 by 0.8 %
+    assert tile(F64, False, 8000, 8000, 8000) == (64, 128, 16)
     # 3000^3: 576 tiles of 128 x 128 are 2.25 rounds of one or two tiles per compute unit, where that
-    # tile runs at 79 and 87 % of its speed; 2209 tiles of 64 x 64 are nine rounds at full speed
+    # tile runs below its speed; 2209 tiles of 64 x 64 are nine rounds at full speed
     assert plan(F64, False, 3000, 3000, 3000) == ((64, 64, 16), 0, 0, (0, 0, 0))
-    # binary32: 64 x 64 tiles take 32-deep slabs from K = 256 on; a flat 4000 x 2040 x 100 product
-    # runs on 128 x 64 tiles (two per compute unit)
-    assert plan(F32, False, 2000, 2000, 2000) == ((64, 64, 32), 0, 0, (0, 0, 0))
-    assert plan(F32, False, 2000, 2000, 200) == ((128, 64, 16), 0, 0, (0, 0, 0))
+    # binary32: 64 x 64 tiles take 32-deep slabs from K = 256 on
+    assert plan(F32, False, 3000, 3000, 3000) == ((64, 64, 32), 0, 0, (0, 0, 0))
+    assert plan(F32, False, 2000, 2000, 2000) == ((64, 128, 16), 0, 0, (0, 0, 0))
+    assert plan(F32, False, 2000, 2000, 200) == ((64, 128, 16), 0, 0, (0, 0, 0))
     assert tile(F32, False, 1024, 1024, 128) == (64, 64, 16)
-    assert plan(F32, False, 4000, 2040, 100) == ((128, 64, 16), 0, 0, (0, 0, 0))
+    assert plan(F32, False, 4000, 2040, 100) == ((128, 128, 16), 0, 0, (0, 0, 0))
     # small problems: quarter-size tiles
     assert tile(F32, False, 1024, 1024, 1024) == (64, 64, 32)
     assert tile(F64, False, 300, 200, 100) == (64, 64, 16)
     # the two-launch plans: whole rounds of large tiles first, the rest on small tiles
-    assert plan(F64, False, 8192, 8192, 8192) == ((256, 128, 16), 0, 0, (0, 0, 0))
-    assert plan(F64, False, 8200, 8192, 8192) == ((256, 128, 16), 1, 8192, (64, 64, 16))
-    assert plan(F64, False, 8192, 8200, 8192) == ((256, 128, 16), 2, 8192, (64, 64, 16))
-    assert plan(F64, False, 5000, 5000, 5000) == ((256, 128, 16), 1, 4864, (64, 64, 16))
+    assert plan(F64, False, 8192, 8192, 8192) == ((128, 128, 16), 0, 0, (0, 0, 0))
+    assert plan(F64, False, 8200, 8192, 8192) == ((128, 128, 16), 1, 8192, (64, 64, 16))
+    assert plan(F64, False, 8192, 8200, 8192) == ((128, 128, 16), 2, 8192, (64, 64, 16))
+    assert plan(F64, False, 5000, 5000, 5000) == ((128, 128, 16), 1, 4864, (64, 64, 16))
     assert plan(F32, False, 4200, 4096, 1024) == ((256, 256, 32), 1, 4096, (64, 64, 32))
-    assert plan(F64, False, 4096, 4104, 4096) == ((256, 128, 16), 2, 4096, (64, 64, 16))
+    assert plan(F32, False, 8200, 8192, 8192) == ((256, 128, 16), 1, 8192, (64, 64, 32))
     tile3, rest3 = (ctypes.c_int * 3)(), (ctypes.c_int * 3)()
     split, cut = ctypes.c_int(), ctypes.c_int64()
     refs = (tile3, ctypes.byref(split), ctypes.byref(cut), rest3)
@@ -247,9 +248,11 @@ def test_gemm_plan_choice(lib):
     assert lib.distal_gemm_plan(0, 0, 0, 8, 8, 1, 0, *refs) == 2
     assert lib.distal_gemm_plan(0, 0, 8, 8, 8, 0, 0, *refs) == 2
     assert lib.distal_gemm_plan(0, 0, 8, 8, 8, 1, 0, None, None, None, None) == 1
-    # added onto an old C, binary32 takes 256 x 256 tiles from K = 4096 on; binary64 plans do not change
+    # added onto an old C, binary32 keeps the 256 x 256 tile for K >= 4096 and the 256 x 128 one for
+    # K >= 512; binary64 plans do not change
     assert tile(F32, False, 8192, 8192, 1024, accumulate=True) == (256, 128, 16)
-    assert tile(F32, False, 8192, 8192, 4096, accumulate=True) == (256, 256, 32)
+    assert tile(F32, False, 16384, 16384, 4096, accumulate=True) == (256, 256, 32)
+    assert tile(F32, False, 16384, 16384, 2048, accumulate=True) == (256, 128, 16)
     assert tile(F32, False, 8192, 8192, 256, accumulate=True) == (64, 128, 16)      # thin and bound by C's traffic
     assert tile(F32, False, 8192, 8192, 512, accumulate=True) == (256, 128, 16)
     for K in (128, 1024, 8192):

@@ -112,8 +112,8 @@ def test_gemm_tiled_rejects_unknown_tiles(lib):
 
 # shapes that reach the large-tile launch configurations (binary32: 256 x 256 tiles with 32-deep
 # slabs, 256 x 128 for k-chunks; binary64: 256 x 128 with sixteen wavefronts, 128 x 128 with eight)
-BIG_TILE_SHAPES = [(np.float32, 4096, 4096, 1024, (256, 256, 32)), (np.float32, 4096, 2048, 512, (256, 128, 16)),
-                   (np.float64, 4096, 2048, 4096, (256, 128, 16)), (np.float64, 4096, 2048, 64, (128, 128, 16))]
+BIG_TILE_SHAPES = [(np.float32, 4096, 4096, 1024, (256, 256, 32)), (np.float32, 4096, 4096, 512, (256, 128, 16)),
+                   (np.float64, 4096, 4096, 4096, (256, 128, 16)), (np.float64, 4096, 2048, 64, (128, 128, 16))]
 
 
 @pytest.mark.parametrize("kind", KINDS)
@@ -140,14 +140,14 @@ def test_gemm_big_tile_configs(lib, oracle, kind, dtype, M, N, K, tile):
 
 # ragged shapes that reach the same launch configurations in their edge-clamping form (M and N
 # not whole tiles, K with trailing terms for the second pass), in the order of BIG_TILE_SHAPES,
-# then 128 x 64 binary32 and a shape whose K is made of whole slabs
-RAGGED_TILE_SHAPES = [(np.float32, 4000, 4000, 1028, (256, 256, 32), 0), (np.float32, 4000, 2040, 520, (256, 128, 16), 0),
-                      (np.float64, 4000, 2040, 4100, (256, 128, 16), 0), (np.float64, 4000, 2040, 72, (128, 128, 16), 0),
-                      (np.float32, 4000, 2040, 100, (128, 64, 16), 0), (np.float32, 3900, 4072, 1056, (256, 256, 32), 0),
+# then 64 x 128 binary32 and a shape whose K is made of whole slabs
+RAGGED_TILE_SHAPES = [(np.float32, 4000, 4000, 1028, (256, 256, 32), 0), (np.float32, 4000, 4090, 520, (256, 128, 16), 0),
+                      (np.float64, 4000, 4090, 4100, (256, 128, 16), 0), (np.float64, 4000, 2040, 72, (128, 128, 16), 0),
+                      (np.float32, 2000, 2040, 100, (64, 128, 16), 0), (np.float32, 3900, 4072, 1056, (256, 256, 32), 0),
                       # two launches: whole rounds of large tiles, the rest on small tiles - cut along the
-                      # rows (binary32 256 x 256; binary64 256 x 128) and along the columns (binary64 256 x 128)
-                      (np.float32, 4200, 4096, 1024, (256, 256, 32), 1), (np.float64, 4200, 4096, 4096, (256, 128, 16), 1),
-                      (np.float64, 4096, 4104, 4096, (256, 128, 16), 2)]
+                      # rows (binary32 256 x 256; binary64 128 x 128) and along the columns (binary64 128 x 128)
+                      (np.float32, 4200, 4096, 1024, (256, 256, 32), 1), (np.float64, 8200, 8192, 272, (128, 128, 16), 1),
+                      (np.float64, 8192, 8200, 272, (128, 128, 16), 2)]
 
 
 @pytest.mark.parametrize("kind", KINDS)
