@@ -103,7 +103,7 @@ int launch_tiles(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
     if (a.K < BK) return launch_contract<T, 128, 128, 16, 2, 2, kGuarded, TA>(a, batch, stream);   // no whole slab
     // leading dimensions so large that a slab's rows lie more than 4 GiB apart: the straight-line
     // kernel's 32-bit offsets do not reach, the bounds-checked kernel addresses with pointers
-    if (!fast_offsets_fit<T, BM, BN, BK, TA>(a.lda, a.ldb)) return launch_contract<T, 128, 128, 16, 2, 2, kGuarded, TA>(a, batch, stream);
+    if (!slab_offsets_fit((int64_t)sizeof(T), TA, BM, BN, BK, a.lda, a.ldb)) return launch_contract<T, 128, 128, 16, 2, 2, kGuarded, TA>(a, batch, stream);
     const int64_t k_main = a.K / BK * BK, k_tail = a.K - k_main;
     if (k_tail == 0)
         return (a.M % BM == 0 && a.N % BN == 0) ? launch_contract<T, BM, BN, BK, WM, WN, kWhole, TA>(a, batch, stream)

@@ -398,16 +398,6 @@ contract_kernel(ContractArgs<T> args) {
             }
 }
 
-// Whether the 32-bit byte offsets of contract_fast_kernel cover a slab of this tile for these
-// leading dimensions: the last row of a slab, plus one row length, from the tile's first element.
-template <typename T, int BM, int BN, int BK, bool TA>
-inline bool fast_offsets_fit(int64_t lda, int64_t ldb) {
-    const double limit = 4294967296.0 - 64.0;
-    const double a = TA ? ((double)(BK - 1) * (double)lda + BM) : ((double)(BM - 1) * (double)lda + BK);
-    const double b = (double)(BK - 1) * (double)ldb + BN;
-    return a * sizeof(T) < limit && b * sizeof(T) < limit;
-}
-
 // ---------------------------------------------------------------------------
 // The same contraction for the case every tile and slab is full and every operand
 // 16-byte aligned (M % BM == 0, N % BN == 0, K % BK == 0, aligned bases and leading
@@ -472,7 +462,7 @@ contract_fast_kernel(ContractArgs<T> args) {
     // 64-bit vector adds per load; together with the constant LDS buffers of the two-slab trip
     // below their removal was worth 2.4 points at 8192^3 and 5 to 9 at 2000^3...3000^3).  The offsets
     // are unsigned 32-bit: the host launches this kernel only where (rows of a slab - 1) x leading
-    // dimension fits (fast_offsets_fit), and bounds checking by the descriptor is off (its range is
+    // dimension fits (slab_offsets_fit of the host-side planning), and bounds checking by the descriptor is off (its range is
     // the whole 4 GiB): every address is in bounds by construction, exactly as with pointers.
     int a_off[Cfg::A_PER_T], b_off[Cfg::B_PER_T];
     int a_lds[Cfg::A_PER_T], b_lds[Cfg::B_PER_T];

@@ -169,6 +169,21 @@ inline ProductPlan plan_product(bool f64, bool ta, int64_t M, int64_t N, int64_t
     return plan;
 }
 
+// Whether unsigned 32-bit byte offsets from a tile's first element reach every 16-byte piece of
+// one slab of it: the straight-line contraction kernels address a slab that way (the slab's base
+// is a 64-bit scalar).  The farthest piece starts at (rows of the slab - 1) x leading dimension +
+// row length - one vector; the bound leaves the whole last row below 2^32 - 64.  Operands whose
+// rows lie farther apart run the pointer-addressed kernel.
+inline bool slab_offsets_fit(int64_t esz, bool ta, int bm, int bn, int bk, int64_t lda, int64_t ldb) {
+    const int64_t limit = ((int64_t)1 << 32) - 64;
+    const int64_t a_rows = ta ? bk : bm, a_len = ta ? bm : bk;
+    int64_t a, b;
+    if (lda < 0 || ldb < 0) return false;
+    if (!mul_ok(a_rows - 1, lda, &a) || !mul_ok(bk - 1, ldb, &b)) return false;
+    if (a > limit || b > limit) return false;                    // before the next products can overflow
+    return (a + a_len) * esz < limit && (b + bn) * esz < limit;
+}
+
 // ---- MTTKRP: ranges of the walked index and partial rows --------------------------------------
 constexpr int64_t kModeTargetBlocks = 768;
 

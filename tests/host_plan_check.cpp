@@ -133,6 +133,27 @@ int main() {
     for (auto &s : shapes)
         for (int f = 0; f < 4; ++f) check_product(f & 1, f & 2, s[0], s[1], s[2], 1);
 
+    // 32-bit slab offsets: whenever the predicate accepts leading dimensions, the farthest byte a
+    // lane of the straight-line kernel can touch (computed in 128 bits) lies below 2^32; and it
+    // does accept every operand whose tile spans less than 2 GiB
+    for (int it = 0; it < 400000; ++it) {
+        const int64_t esz = (rnd() & 1) ? 8 : 4;
+        const bool ta = rnd() & 1;
+        const int bms[] = {32, 64, 128, 256}, bks[] = {16, 32};
+        const int bm = bms[rnd() % 4], bn = bms[rnd() % 4], bk = bks[rnd() % 2];
+        const int64_t lda = (rnd() % 8 == 0) ? (int64_t)(rnd() >> 1) : extent((int64_t)1 << 36);
+        const int64_t ldb = (rnd() % 8 == 0) ? (int64_t)(rnd() >> 1) : extent((int64_t)1 << 36);
+        const bool fit = slab_offsets_fit(esz, ta, bm, bn, bk, lda, ldb);
+        const unsigned __int128 a_end = ((unsigned __int128)((ta ? bk : bm) - 1) * (unsigned __int128)lda + (ta ? bm : bk)) * esz;
+        const unsigned __int128 b_end = ((unsigned __int128)(bk - 1) * (unsigned __int128)ldb + bn) * esz;
+        const unsigned __int128 top = (unsigned __int128)1 << 32;
+        if (fit) CHECK(a_end < top && b_end < top, "offsets past 2^32 accepted: lda %" PRId64 " ldb %" PRId64, lda, ldb);
+        if (a_end < top / 2 && b_end < top / 2) CHECK(fit, "small operand rejected: lda %" PRId64 " ldb %" PRId64, lda, ldb);
+    }
+    CHECK(slab_offsets_fit(4, false, 256, 128, 16, 4198400, 128), "rows 4.28e9 bytes apart fit");
+    CHECK(!slab_offsets_fit(4, false, 256, 128, 16, 8396800, 128), "rows 8.5e9 bytes apart do not");
+    CHECK(!slab_offsets_fit(8, true, 128, 128, 16, INT64_MAX, 128), "overflowing product");
+
     // MTTKRP plans: extents whose product stays below 2^60, as the entry point demands
     for (int it = 0; it < 300000; ++it) {
         const int dt = (int)(rnd() & 1), mode = (int)(rnd() % 3);
