@@ -14,7 +14,8 @@ configuration the same way and reports them under ``rows``, each with the roofli
 that bounds it and the CPU oracle timed on a bounded sample of the same inputs:
 
     core   gemm_f64 gemm_f32 ttm mttkrp ttv innerprod           (the five expressions)
-    all    core + the k-chunk leaf shapes of the schedules (summa), mid-size and
+    all    core + the k-step leaf shapes of the schedules and one whole SUMMA
+           schedule issued by the schedule driver (summa), mid-size and
            misaligned products (gemm_shapes), the binary64 forms of the higher-order
            calls (*_f64), every other mode (ttm_mode*, ttv_mode*, mttkrp_mode*),
            rank-sized factors (ttm_rank32, mttkrp_rank64), the synthetic
@@ -273,6 +274,26 @@ def main():
                     hA, hB = h(A[idx][:, 0:chunk]), h(B[0:chunk, :])
                     baseline(r, lambda: oracle.gemm(hA, hB), lambda: h(C[idx]), 2.0 * 16 * n * chunk, "GFLOP/s",
                              f"16 evenly spaced rows of one k-step's product")
+        if "summa" in want:
+            # the whole schedule of one processor's share: K / 512 accumulating k-steps through the
+            # schedule driver (one "launch" of this row is the sequence of all of them)
+            from paper_2203_08069_amd import schedules
+            chunk = 512
+            C.zero_()
+            r = finish(f"{name}_summa_schedule_chunk{chunk}",
+                       f"SUMMA on a 1 x 1 grid, M=N=K={n}, {dt}: {n // chunk} accumulating k-steps of {chunk} "
+                       f"issued by the schedule driver, timed as one unit", dt,
+                       lambda: schedules.summa(A, B, C, 1, 1, chunk), 2.0 * n ** 3,
+                       np.dtype(npdt).itemsize * (2.0 * n * n + (n // chunk) * 2.0 * n * n), "mfma")
+            r["launches_per_step"] = n // chunk
+            if cpu:
+                C.zero_()
+                schedules.summa(A, B, C, 1, 1, chunk)
+                idx = torch.from_numpy(np.linspace(0, n - 1, 8).astype(np.int64)).to(dev)
+                hA, hB = h(A[idx]), h(B)
+                baseline(r, lambda: oracle.gemm(hA, hB), lambda: h(C[idx]), 2.0 * 8 * n * n, "GFLOP/s",
+                         f"8 evenly spaced rows of C after one run of the schedule from C = 0")
+                del hA, hB
         if "gemm_shapes" in want:
             # shapes off the benchmark's grid: two or three rounds of tiles, an odd extent, a misaligned view
             cases = [("3000", 3000, 3000, 3000, 0), ("2000", 2000, 2000, 2000, 0), ("n8191", 8192, 8191, 8192, 0),
