@@ -75,6 +75,10 @@ PROFILE_OF_ROW = {
     "ttv": "ttv_row_kernel_f32_1024.md",
     "ttv_mode0": "ttv_left_wide_kernel_f32_mode0_1024.md",
     "innerprod": "innerprod_pass1_kernel_f32_1024.md",
+    "ttv_f64": "ttv_row_kernel_f64_1024.md",
+    "innerprod_f64": "innerprod_pass1_kernel_f64_1024.md",
+    "ttm_f64": "contract_fast_kernel_f64_ttm_1024x1024x1024x256.md",
+    "mttkrp_f64": "mttkrp_walk_kernel_f64_1024_rank32.md",
 }
 
 
