@@ -196,7 +196,7 @@ def test_gemm_plan_choice(lib):
     from paper_2203_08069_amd import binding
     F32, F64 = 0, 1
     tile, plan = binding.gemm_tile, binding.gemm_plan
-    # headline and fp32 GEMM (BASELINE configs[1]), TTM (configs[3]) along modes 2, 0, 1
+    # the headline product in both types, and the benchmark's tensor-times-matrix shape along modes 2, 0, 1
     assert tile(F64, False, 8192, 8192, 8192) == (128, 128, 16)
     assert tile(F32, False, 8192, 8192, 8192) == (256, 128, 16)
     assert tile(F32, False, 1 << 20, 256, 1024) == (256, 256, 32)      # as wide as the output: the tensor is read once
