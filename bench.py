@@ -20,8 +20,8 @@ that bounds it and the CPU oracle timed on a bounded sample of the same inputs:
            calls (*_f64), every other mode (ttm_mode*, ttv_mode*, mttkrp_mode*),
            rank-sized factors (ttm_rank32, mttkrp_rank64), the synthetic
            stream + MFMA kernel timed next to MTTKRP (mttkrp_floor) and the
-           register-only matrix-instruction loop that checks the peak denominators
-           on the device (mfma_peak)
+           register-only matrix-instruction loop and the read-only stream that check
+           the peak denominators on the device (mfma_peak, hbm_peak)
 
 Per-launch durations come from HIP events recorded on the stream the kernels run on
 (torch's current stream, which is the stream handed to the library).  ``roofline.traffic``
@@ -57,7 +57,7 @@ PEAK_HBM_GBS = 8000.0
 
 CORE = ["gemm_f64", "gemm_f32", "ttm", "mttkrp", "ttv", "innerprod"]
 EXTRA = ["summa", "gemm_shapes", "ttv_f64", "innerprod_f64", "ttm_f64", "mttkrp_f64", "ttv_mode0", "ttv_mode1",
-         "ttm_mode0", "ttm_mode1", "ttm_rank32", "mttkrp_floor", "mttkrp_rank64", "mttkrp_mode1", "mttkrp_mode2", "mfma_peak"]
+         "ttm_mode0", "ttm_mode1", "ttm_rank32", "mttkrp_floor", "mttkrp_rank64", "mttkrp_mode1", "mttkrp_mode2", "mfma_peak", "hbm_peak"]
 
 # rocprofv3 summary that covers a row's dominant kernel (HBM traffic per launch is read from it)
 PROFILE_OF_ROW = {
@@ -493,6 +493,21 @@ def main():
                        "mfma")
             r["synthetic"] = True
             del out
+
+    if "hbm_peak" in want:
+        # Not a row of the method: a kernel that only reads 4 GiB, the on-device check of what HBM
+        # delivers (the ceiling of the TTV and inner-product rows) for three launch shapes
+        from paper_2203_08069_amd import probe
+        src = operand(2, 0, (1 << 30,), np.float32)
+        for blocks, in_flight in ((256, 8), (1024, 8), (2048, 16)):
+            out = torch.empty(probe.hbm_read_out_bytes(blocks) // 4, dtype=torch.float32, device=dev)
+            r = finish(f"hbm_read_{blocks}x{in_flight}",
+                       f"synthetic: one read of a 4 GiB f32 array, {blocks} workgroups each on its own contiguous range, "
+                       f"{in_flight} 16-byte non-temporal loads per lane in flight, nothing else",
+                       "f32", lambda: probe.hbm_read(src, blocks, in_flight, out), 2.0 ** 30, 4.0 * 2 ** 30, "hbm")
+            r["synthetic"] = True
+            del out
+        del src
 
     head = rows[0]
     out = {

@@ -54,6 +54,22 @@ int distal_probe_mfma_peak(int f64, int64_t iters, void *out, size_t out_bytes, 
 size_t distal_probe_mfma_peak_out_bytes(int f64);
 double distal_probe_mfma_peak_flops(int f64, int64_t iters);
 
+/*
+ * What HBM delivers to a kernel that only reads: `bytes` bytes (a multiple of 16, DEVICE pointer,
+ * 16-byte aligned) are read once with 16-byte non-temporal loads, `blocks` workgroups of 256
+ * lanes each owning one contiguous range (rounded up to whole 4 KiB runs, so fewer workgroups
+ * may be launched), `in_flight` (4, 8 or 16) loads per lane requested before the first is used.
+ * bytes / duration is the ceiling the streaming rows of the benchmark (TTV, inner product) are
+ * read against, next to the published 8 TB/s.
+ *   out: DEVICE scratch of at least distal_probe_hbm_read_out_bytes(blocks) bytes (receives one
+ *   partial sum per lane; meaningless values).  Asynchronous; nothing is allocated.
+ * Returns 0, or 1 (NULL pointer), 2 (bytes, blocks or in_flight), 4 (src misaligned),
+ * 6 (out too small), 7 (launch).
+ */
+int distal_probe_hbm_read(const void *src, int64_t bytes, int blocks, int in_flight, void *out, size_t out_bytes,
+                          void *stream);
+size_t distal_probe_hbm_read_out_bytes(int blocks);
+
 #ifdef __cplusplus
 }
 #endif

@@ -173,7 +173,46 @@ bool probe_plan(int64_t I, int64_t J, int64_t K, ProbePlan *p) {
 
 }  // namespace
 
+// A read of `nvec` 16-byte pieces and nothing else: each workgroup owns one contiguous range and
+// keeps U loads per lane in flight; the sums only keep the loads alive (one store per workgroup
+// whose condition never holds for finite data would let the compiler drop nothing either way:
+// the store below is unconditional).
+typedef float v4f_probe __attribute__((ext_vector_type(4)));
+template <int U>
+__global__ void __launch_bounds__(256) probe_hbm_read_kernel(const v4f_probe *__restrict__ src, float *out, int64_t nvec, int64_t per) {
+    const int64_t lo = (int64_t)blockIdx.x * per, hi = lo + per < nvec ? lo + per : nvec;
+    float s = 0.f;
+    for (int64_t v = lo + threadIdx.x; v < hi; v += 256 * U) {
+        v4f_probe x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = (v + 256 * u < hi) ? __builtin_nontemporal_load(src + v + 256 * u) : v4f_probe(0.f);
+#pragma unroll
+        for (int u = 0; u < U; ++u) s += (x[u][0] + x[u][1]) + (x[u][2] + x[u][3]);
+    }
+    out[(int64_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 extern "C" {
+
+size_t distal_probe_hbm_read_out_bytes(int blocks) { return blocks > 0 ? (size_t)blocks * 256 * sizeof(float) : 0; }
+
+int distal_probe_hbm_read(const void *src, int64_t bytes, int blocks, int in_flight, void *out, size_t out_bytes, void *stream) {
+    if (!src || !out) return 1;
+    if (bytes < 16 || bytes % 16 != 0 || blocks < 1 || blocks > 65536 || (in_flight != 4 && in_flight != 8 && in_flight != 16)) return 2;
+    if ((reinterpret_cast<uintptr_t>(src) & 15u) != 0) return 4;
+    if (out_bytes < distal_probe_hbm_read_out_bytes(blocks)) return 6;
+    const int64_t nvec = bytes / 16;
+    int64_t per = (nvec + blocks - 1) / blocks;
+    per = (per + 255) / 256 * 256;                     // whole 4 KiB runs per workgroup
+    const unsigned nb = (unsigned)((nvec + per - 1) / per);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const v4f_probe *p = static_cast<const v4f_probe *>(src);
+    float *o = static_cast<float *>(out);
+    if (in_flight == 4) hipLaunchKernelGGL(probe_hbm_read_kernel<4>, dim3(nb), dim3(256), 0, s, p, o, nvec, per);
+    else if (in_flight == 8) hipLaunchKernelGGL(probe_hbm_read_kernel<8>, dim3(nb), dim3(256), 0, s, p, o, nvec, per);
+    else hipLaunchKernelGGL(probe_hbm_read_kernel<16>, dim3(nb), dim3(256), 0, s, p, o, nvec, per);
+    return hipGetLastError() == hipSuccess ? 0 : 7;
+}
 
 size_t distal_probe_out_bytes(int64_t I, int64_t J, int64_t K) {
     ProbePlan p;

@@ -11,7 +11,8 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdistal_probe.so")
 EXPORTS = ("distal_probe_stream_mfma", "distal_probe_out_bytes", "distal_probe_mfma_peak",
-           "distal_probe_mfma_peak_out_bytes", "distal_probe_mfma_peak_flops")
+           "distal_probe_mfma_peak_out_bytes", "distal_probe_mfma_peak_flops", "distal_probe_hbm_read",
+           "distal_probe_hbm_read_out_bytes")
 
 _lib = None
 
@@ -33,6 +34,10 @@ def load_library() -> ctypes.CDLL:
         lib.distal_probe_mfma_peak_out_bytes.restype = ctypes.c_size_t
         lib.distal_probe_mfma_peak_flops.argtypes = [ctypes.c_int, i64]
         lib.distal_probe_mfma_peak_flops.restype = ctypes.c_double
+        lib.distal_probe_hbm_read.argtypes = [vp, i64, ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t, vp]
+        lib.distal_probe_hbm_read.restype = ctypes.c_int
+        lib.distal_probe_hbm_read_out_bytes.argtypes = [ctypes.c_int]
+        lib.distal_probe_hbm_read_out_bytes.restype = ctypes.c_size_t
         _lib = lib
     return _lib
 
@@ -73,3 +78,19 @@ def mfma_peak(f64: bool, iters: int, out):
         ctypes.c_void_p(torch.cuda.current_stream(out.device).cuda_stream))
     if rc != 0:
         raise RuntimeError(f"distal_probe_mfma_peak failed with status {rc}")
+
+
+def hbm_read_out_bytes(blocks: int) -> int:
+    return int(load_library().distal_probe_hbm_read_out_bytes(int(blocks)))
+
+
+def hbm_read(src, blocks: int, in_flight: int, out):
+    """One launch of the read-only stream over the whole device tensor `src` on torch's current stream."""
+    import torch
+    assert src.is_cuda and src.is_contiguous() and out.is_cuda and out.is_contiguous()
+    rc = load_library().distal_probe_hbm_read(
+        ctypes.c_void_p(src.data_ptr()), src.numel() * src.element_size(), int(blocks), int(in_flight),
+        ctypes.c_void_p(out.data_ptr()), out.numel() * out.element_size(),
+        ctypes.c_void_p(torch.cuda.current_stream(src.device).cuda_stream))
+    if rc != 0:
+        raise RuntimeError(f"distal_probe_hbm_read failed with status {rc}")

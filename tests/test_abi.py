@@ -374,6 +374,14 @@ def test_probe_library_exports_and_argument_errors():
     assert g(1, 0, c, 1 << 30, None) == 2
     assert g(1, 10, None, 1 << 30, None) == 1
     assert g(0, 10, c, 16, None) == 6
+    r = lib.distal_probe_hbm_read
+    assert lib.distal_probe_hbm_read_out_bytes(256) == 256 * 256 * 4 and lib.distal_probe_hbm_read_out_bytes(0) == 0
+    big = 1 << 30
+    assert r(None, 1 << 20, 256, 8, c, big, None) == 1 and r(c, 1 << 20, 256, 8, None, big, None) == 1
+    assert r(c, 24, 256, 8, c, big, None) == 2 and r(c, 0, 256, 8, c, big, None) == 2      # not whole 16-byte pieces
+    assert r(c, 1 << 20, 0, 8, c, big, None) == 2 and r(c, 1 << 20, 256, 5, c, big, None) == 2
+    assert r(ctypes.c_void_p(FAKE + 4), 1 << 20, 256, 8, c, big, None) == 4
+    assert r(c, 1 << 20, 256, 8, c, 1024, None) == 6
 
 
 def test_package_and_library_versions_agree(lib):
