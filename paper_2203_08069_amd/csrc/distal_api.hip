@@ -150,9 +150,20 @@ int launch_fill(T *out, int64_t rows, int64_t cols, int64_t ld, hipStream_t stre
 // 16-byte pieces would straddle an edge are peeled off first (see gemm_t).  A grid that would
 // end in a thin last round is cut into two launches (plan_product).
 
-// The launch for a tile id of tile_candidates().
+// The launch for a tile id of tile_candidates().  How many wavefronts share a tile is chosen here,
+// not by the caller: the result does not depend on it (every output sums its terms in the same
+// order whichever wavefront owns it), only the speed does.  A grid that gives a compute unit one
+// tile or two leaves its SIMDs with one wavefront each unless the tile is cut into more of them:
+// binary32 128 x 128 on eight wavefronts of 32 x 64 instead of four of 64 x 64 measures 86.7 against
+// 79.0 % of peak at 2048^3 (256 tiles) and 91.1 against 92.1 at 4096^2 x 2048 (1024 tiles); binary64
+// 128 x 128 on sixteen instead of eight 90.8 against 88.8 at 256 tiles, 91.2 against 93.6 at 512;
+// binary64 64 x 64 on eight instead of four 74.2 against 64.1 at 1024^3 (256 tiles), level from
+// 600 tiles on.  The binary64 128 x 64 and 64 x 128 tiles run on eight wavefronts of 32 x 32 at
+// every grid size (4096^2 x 2048: 93.5 against 88.8 and 94.9 against 92.4 on four); in binary32
+// the same cut loses 1 to 5 points everywhere and is not used.
 template <typename T, bool TA>
 int launch_by_id(int id, const ContractArgs<T> &a, int64_t batch, hipStream_t stream) {
+    auto tiles = [&](int bm, int bn) { return ((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn) * batch; };
     switch (id) {
     case 1:
         // a transposed left operand is staged in rows of 256 either way: 16-deep slabs measure 1 % faster
@@ -165,17 +176,22 @@ int launch_by_id(int id, const ContractArgs<T> &a, int64_t batch, hipStream_t st
         if constexpr (sizeof(T) == 4) return launch_tiles<T, 256, 128, 16, 4, 2, TA>(a, batch, stream);
         else return launch_tiles<T, 256, 128, 16, 8, 2, TA>(a, batch, stream);
     case 3:
-        if constexpr (sizeof(T) == 4) return launch_tiles<T, 128, 128, 16, 2, 2, TA>(a, batch, stream);
-        else return launch_tiles<T, 128, 128, 16, 4, 2, TA>(a, batch, stream);
+        if constexpr (sizeof(T) == 4) {
+            if (tiles(128, 128) <= 384) return launch_tiles<T, 128, 128, 16, 4, 2, TA>(a, batch, stream);
+            return launch_tiles<T, 128, 128, 16, 2, 2, TA>(a, batch, stream);
+        } else {
+            if (tiles(128, 128) <= 256) return launch_tiles<T, 128, 128, 16, 8, 2, TA>(a, batch, stream);
+            return launch_tiles<T, 128, 128, 16, 4, 2, TA>(a, batch, stream);
+        }
     case 5:
         if constexpr (sizeof(T) == 4) return launch_tiles<T, 256, 64, 16, 4, 1, TA>(a, batch, stream);
-        else return launch_tiles<T, 128, 64, 16, 4, 1, TA>(a, batch, stream);
+        else return launch_tiles<T, 128, 64, 16, 4, 2, TA>(a, batch, stream);
     case 6:
         if constexpr (sizeof(T) == 4) return launch_tiles<T, 128, 32, 32, 4, 1, TA>(a, batch, stream);
         else return launch_tiles<T, 128, 32, 16, 4, 1, TA>(a, batch, stream);
     case 7:
         if constexpr (sizeof(T) == 4) return launch_tiles<T, 64, 256, 16, 1, 4, TA>(a, batch, stream);
-        else return launch_tiles<T, 64, 128, 16, 2, 2, TA>(a, batch, stream);
+        else return launch_tiles<T, 64, 128, 16, 4, 2, TA>(a, batch, stream);
     case 8:
         if constexpr (sizeof(T) == 4) return launch_tiles<T, 32, 256, 32, 1, 4, TA>(a, batch, stream);
         else return launch_tiles<T, 32, 256, 16, 1, 4, TA>(a, batch, stream);
@@ -191,6 +207,8 @@ int launch_by_id(int id, const ContractArgs<T> &a, int64_t batch, hipStream_t st
     default: break;
     }
     // too few larger tiles to give every CU one: quarter-size tiles, four times the workgroups
+    if constexpr (sizeof(T) == 8)
+        if (tiles(64, 64) <= 512) return launch_tiles<T, 64, 64, 16, 4, 2, TA>(a, batch, stream);
     return launch_tiles<T, 64, 64, 16, 2, 2, TA>(a, batch, stream);
 }
 

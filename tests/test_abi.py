@@ -227,8 +227,11 @@ def test_gemm_plan_choice(lib):
     assert plan(F64, False, 3000, 3000, 3000) == ((64, 64, 16), 0, 0, (0, 0, 0))
     # binary32: 64 x 64 tiles take 32-deep slabs from K = 256 on
     assert plan(F32, False, 3000, 3000, 3000) == ((64, 64, 32), 0, 0, (0, 0, 0))
-    assert plan(F32, False, 2000, 2000, 2000) == ((64, 128, 16), 0, 0, (0, 0, 0))
-    assert plan(F32, False, 2000, 2000, 200) == ((64, 128, 16), 0, 0, (0, 0, 0))
+    # 2000^3: one 128 x 128 tile per compute unit (run on eight wavefronts at that grid size)
+    assert plan(F32, False, 2000, 2000, 2000) == ((128, 128, 16), 0, 0, (0, 0, 0))
+    assert plan(F32, False, 2000, 2000, 200) == ((128, 128, 16), 0, 0, (0, 0, 0))
+    assert plan(F32, False, 3000, 2040, 100) == ((128, 64, 16), 0, 0, (0, 0, 0))
+    assert plan(F64, False, 2048, 2048, 2048) == ((64, 128, 16), 0, 0, (0, 0, 0))      # two per compute unit
     assert tile(F32, False, 1024, 1024, 128) == (64, 64, 16)
     assert plan(F32, False, 4000, 2040, 100) == ((128, 128, 16), 0, 0, (0, 0, 0))
     # small problems: quarter-size tiles
@@ -249,14 +252,16 @@ def test_gemm_plan_choice(lib):
     assert lib.distal_gemm_plan(0, 0, 8, 8, 8, 0, 0, *refs) == 2
     assert lib.distal_gemm_plan(0, 0, 8, 8, 8, 1, 0, None, None, None, None) == 1
     # added onto an old C, binary32 keeps the 256 x 256 tile for K >= 4096 and the 256 x 128 one for
-    # K >= 512; binary64 plans do not change
+    # K >= 512; binary64 changes tile only for steps of at most 128 terms
     assert tile(F32, False, 8192, 8192, 1024, accumulate=True) == (256, 128, 16)
     assert tile(F32, False, 16384, 16384, 4096, accumulate=True) == (256, 256, 32)
     assert tile(F32, False, 16384, 16384, 2048, accumulate=True) == (256, 128, 16)
     assert tile(F32, False, 8192, 8192, 256, accumulate=True) == (64, 128, 16)      # thin and bound by C's traffic
     assert tile(F32, False, 8192, 8192, 512, accumulate=True) == (256, 128, 16)
-    for K in (128, 1024, 8192):
+    for K in (256, 1024, 8192):
         assert plan(F64, False, 8192, 8192, K, accumulate=True) == plan(F64, False, 8192, 8192, K)
+    assert tile(F64, False, 8192, 8192, 128, accumulate=True) == (64, 128, 16)      # bound by C's traffic
+    assert tile(F64, False, 8192, 8192, 128) == (128, 128, 16)
 
 
 def test_gemm_plan_invariants_on_random_extents(lib):

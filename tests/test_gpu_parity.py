@@ -100,6 +100,42 @@ def test_gemm_every_tile_by_name(lib, oracle, dtype, tile, M, N, K, ta):
     assert np.all(out2[mask] == 77.0)
 
 
+# The library decides how many wavefronts share a tile from the number of tiles in the grid
+# (a tile alone on a compute unit is cut into more wavefronts).  Grids on both sides of each
+# switch, whole and ragged, left operand stored either way: tile, M, N, what runs.
+WAVEFRONT_SWITCHES = [
+    (np.float32, (128, 128), 2048, 2048, "256 tiles: eight wavefronts"),
+    (np.float32, (128, 128), 2550, 2430, "380 tiles, ragged: eight wavefronts"),
+    (np.float32, (128, 128), 2560, 2560, "400 tiles: four wavefronts"),
+    (np.float32, (128, 128), 2555, 2564, "420 tiles, ragged: four wavefronts"),
+    (np.float64, (128, 128), 2048, 2048, "256 tiles: sixteen wavefronts"),
+    (np.float64, (128, 128), 2040, 2046, "256 tiles, ragged: sixteen wavefronts"),
+    (np.float64, (128, 128), 2048, 2176, "272 tiles: eight wavefronts"),
+    (np.float64, (64, 64), 1408, 1472, "506 tiles: eight wavefronts"),
+    (np.float64, (64, 64), 1400, 1470, "506 tiles, ragged: eight wavefronts"),
+    (np.float64, (64, 64), 1472, 1472, "529 tiles: four wavefronts"),
+    (np.float64, (128, 64), 1024, 1022, "eight wavefronts at every grid size, ragged"),
+    (np.float64, (64, 128), 1022, 1024, "eight wavefronts at every grid size, ragged"),
+]
+
+
+@pytest.mark.parametrize("ta", [False, True])
+@pytest.mark.parametrize("dtype,tile,M,N,what", WAVEFRONT_SWITCHES, ids=[f"{np.dtype(d).name}-{t[0]}x{t[1]}-{m}x{n}" for d, t, m, n, _ in WAVEFRONT_SWITCHES])
+def test_gemm_tiled_wavefront_counts(lib, oracle, dtype, tile, M, N, what, ta):
+    """Every element against the oracle, with K = 72 (four whole slabs and eight trailing terms),
+    then accumulated on top: the result must not depend on how the tile is cut into wavefronts."""
+    K = 72
+    kind = inputs.SMALLINT
+    A, B = U.gen(800 + M, 0, (M, K), dtype, kind), U.gen(800 + M, 1, (K, N), dtype, kind)
+    left = np.ascontiguousarray(A.T) if ta else A
+    C = empty((M, N), dtype)
+    lib.distal_gemm_tiled(tile, U.dev(left), U.dev(B), C, transposed_left=ta)
+    got = U.host(C)
+    assert np.array_equal(got, oracle.gemm(A, B)), what                  # small integers: exact
+    lib.distal_gemm_tiled(tile, U.dev(left), U.dev(B), C, accumulate=True, transposed_left=ta)
+    assert np.array_equal(U.host(C), got * 2), what
+
+
 def test_gemm_tiled_rejects_unknown_tiles(lib):
     import torch
     A = torch.zeros(64, 64, dtype=torch.float64, device="cuda:0")
@@ -140,10 +176,10 @@ def test_gemm_big_tile_configs(lib, oracle, kind, dtype, M, N, K, tile):
 
 # ragged shapes that reach the same launch configurations in their edge-clamping form (M and N
 # not whole tiles, K with trailing terms for the second pass), in the order of BIG_TILE_SHAPES,
-# then 64 x 128 binary32 and a shape whose K is made of whole slabs
+# then 128 x 64 binary32 and a shape whose K is made of whole slabs
 RAGGED_TILE_SHAPES = [(np.float32, 4000, 4000, 1028, (256, 256, 32), 0), (np.float32, 4000, 4090, 520, (256, 128, 16), 0),
                       (np.float64, 4000, 4090, 4100, (256, 128, 16), 0), (np.float64, 4000, 2040, 72, (128, 128, 16), 0),
-                      (np.float32, 2000, 2040, 100, (64, 128, 16), 0), (np.float32, 3900, 4072, 1056, (256, 256, 32), 0),
+                      (np.float32, 3000, 2040, 100, (128, 64, 16), 0), (np.float32, 3900, 4072, 1056, (256, 256, 32), 0),
                       # two launches: whole rounds of large tiles, the rest on small tiles - cut along the
                       # rows (binary32 256 x 256; binary64 128 x 128) and along the columns (binary64 128 x 128)
                       (np.float32, 4200, 4096, 1024, (256, 256, 32), 1), (np.float64, 8200, 8192, 272, (128, 128, 16), 1),
