@@ -14,8 +14,8 @@ configuration the same way and reports them under ``rows``, each with the roofli
 that bounds it and the CPU oracle timed on a bounded sample of the same inputs:
 
     core   gemm_f64 gemm_f32 ttm mttkrp ttv innerprod           (the five expressions)
-    all    core + the k-step leaf shapes of the schedules and one whole SUMMA
-           schedule issued by the schedule driver (summa), mid-size and
+    all    core + the k-step leaf shapes of the schedules (summa), one whole SUMMA
+           schedule issued by the schedule driver (summa_schedule), mid-size and
            misaligned products (gemm_shapes), the binary64 forms of the higher-order
            calls (*_f64), every other mode (ttm_mode*, ttv_mode*, mttkrp_mode*),
            rank-sized factors (ttm_rank32, mttkrp_rank64), the synthetic
@@ -56,7 +56,7 @@ PEAK_TFLOPS = {"f64": 78.6, "f32": 157.3}
 PEAK_HBM_GBS = 8000.0
 
 CORE = ["gemm_f64", "gemm_f32", "ttm", "mttkrp", "ttv", "innerprod"]
-EXTRA = ["summa", "gemm_shapes", "ttv_f64", "innerprod_f64", "ttm_f64", "mttkrp_f64", "ttv_mode0", "ttv_mode1",
+EXTRA = ["summa", "summa_schedule", "gemm_shapes", "ttv_f64", "innerprod_f64", "ttm_f64", "mttkrp_f64", "ttv_mode0", "ttv_mode1",
          "ttm_mode0", "ttm_mode1", "ttm_rank32", "mttkrp_floor", "mttkrp_rank64", "mttkrp_mode1", "mttkrp_mode2", "mfma_peak", "hbm_peak"]
 
 # rocprofv3 summary that covers a row's dominant kernel (HBM traffic per launch is read from it)
@@ -278,7 +278,7 @@ def main():
                     hA, hB = h(A[idx][:, 0:chunk]), h(B[0:chunk, :])
                     baseline(r, lambda: oracle.gemm(hA, hB), lambda: h(C[idx]), 2.0 * 16 * n * chunk, "GFLOP/s",
                              f"16 evenly spaced rows of one k-step's product")
-        if "summa" in want:
+        if "summa_schedule" in want:
             # the whole schedule of one processor's share: K / 512 accumulating k-steps through the
             # schedule driver (one "launch" of this row is the sequence of all of them)
             from paper_2203_08069_amd import schedules
