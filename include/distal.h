@@ -178,8 +178,9 @@ int distal_innerprod_noalloc(distal_dtype dt, int64_t I, int64_t J, int64_t K,
  * distal_gemm with the tile of the output chosen by the caller instead of by distal_gemm_plan:
  * for schedules that fix their leaf tile themselves, for tuning, and for tests that must reach
  * one particular kernel.  bm x bn is one of the tile shapes the dtype has kernels for (the BM x
- * BN pairs distal_gemm_plan can report for it: 256x256 [binary32], 256x128, 128x128, 128x64,
- * 64x128, 64x64, 128x32, 32x256, and 256x64, 64x256 [binary32]); anything else returns
+ * BN pairs distal_gemm_plan can report for it: 256x256 and 128x256 [binary32], 256x128, 128x128,
+ * 128x64, 64x128, 64x64, 128x32, 32x256, and 256x64, 64x256 [binary32]; into how many wavefronts a
+ * tile is cut is the library's choice and does not change a result); anything else returns
  * DISTAL_ERR_SHAPE.  The whole product runs as one launch of that tile (plus the peeled
  * trailing columns and rows described under distal_gemm_plan); K < 16 takes the bounds-checked
  * kernel whatever the tile.  transposed_left != 0: the left operand is stored K x M (lda >= M)

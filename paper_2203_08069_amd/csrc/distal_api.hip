@@ -204,6 +204,9 @@ int launch_by_id(int id, const ContractArgs<T> &a, int64_t batch, hipStream_t st
     case 11:
         if constexpr (sizeof(T) == 4) return launch_tiles<T, 64, 64, 32, 2, 2, TA>(a, batch, stream);
         break;
+    case 12:
+        if constexpr (sizeof(T) == 4) return launch_tiles<T, 128, 256, 16, 2, 4, TA>(a, batch, stream);
+        break;
     default: break;
     }
     // too few larger tiles to give every CU one: quarter-size tiles, four times the workgroups

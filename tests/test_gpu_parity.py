@@ -59,7 +59,7 @@ def test_gemm(lib, oracle, dtype, kind, M, N, K):
 
 
 # every tile shape a dtype has kernels for, reached by name whatever the planner would choose
-TILES = {np.float32: [(256, 256), (256, 128), (128, 128), (128, 64), (64, 128), (64, 64), (256, 64), (128, 32),
+TILES = {np.float32: [(256, 256), (256, 128), (128, 256), (128, 128), (128, 64), (64, 128), (64, 64), (256, 64), (128, 32),
                       (64, 256), (32, 256)],
          np.float64: [(256, 128), (128, 128), (128, 64), (64, 128), (64, 64), (128, 32), (32, 256)]}
 TILE_CASES = [(dt, t) for dt in DT for t in TILES[dt]]
@@ -146,20 +146,24 @@ def test_gemm_tiled_rejects_unknown_tiles(lib):
         assert e.value.status == 2
 
 
-# shapes that reach the large-tile launch configurations (binary32: 256 x 256 tiles with 32-deep
-# slabs, 256 x 128 for k-chunks; binary64: 256 x 128 with sixteen wavefronts, 128 x 128 with eight)
-BIG_TILE_SHAPES = [(np.float32, 4096, 4096, 1024, (256, 256, 32)), (np.float32, 4096, 4096, 512, (256, 128, 16)),
-                   (np.float64, 4096, 4096, 4096, (256, 128, 16)), (np.float64, 4096, 2048, 64, (128, 128, 16))]
+# every large tile at a size that gives each compute unit a tile or more, named by the caller
+# (binary32: 256 x 256 with 32-deep slabs, 256 x 128, 128 x 256; binary64: 256 x 128 with sixteen
+# wavefronts, 128 x 128 with eight), and one shape left to the planner per dtype
+BIG_TILE_SHAPES = [(np.float32, 4096, 4096, 1024, (256, 256)), (np.float32, 4096, 4096, 512, (256, 128)),
+                   (np.float32, 4096, 4096, 512, (128, 256)), (np.float32, 4096, 4096, 1024, None),
+                   (np.float64, 4096, 4096, 4096, (256, 128)), (np.float64, 4096, 2048, 64, (128, 128)),
+                   (np.float64, 4096, 2048, 64, None)]
 
 
 @pytest.mark.parametrize("kind", KINDS)
 @pytest.mark.parametrize("dtype,M,N,K,tile", BIG_TILE_SHAPES)
 def test_gemm_big_tile_configs(lib, oracle, kind, dtype, M, N, K, tile):
     """The oracle recomputes sampled rows of the product (all columns) from the same inputs."""
-    assert lib.gemm_plan(int(dtype == np.float64), False, M, N, K) == (tile, 0, 0, (0, 0, 0))
+    run = (lambda a, b, c, **kw: lib.distal_gemm(a, b, c, **kw)) if tile is None else \
+          (lambda a, b, c, **kw: lib.distal_gemm_tiled(tile, a, b, c, **kw))
     A, B = U.gen(200 + K, 0, (M, K), dtype, kind), U.gen(200 + K, 1, (K, N), dtype, kind)
     C = empty((M, N), dtype)
-    lib.distal_gemm(U.dev(A), U.dev(B), C)
+    run(U.dev(A), U.dev(B), C)
     got = U.host(C)
     assert np.all(np.isfinite(got))
     rows = np.sort(np.random.default_rng(K).choice(M, 24, replace=False))
@@ -167,7 +171,7 @@ def test_gemm_big_tile_configs(lib, oracle, kind, dtype, M, N, K, tile):
     compare(got[rows], oracle.gemm(np.ascontiguousarray(A[rows]), B), dtype, kind, K)
     # accumulate on top of the product: twice it (exactly, unless binary32 terms are added to the
     # old values one by one)
-    lib.distal_gemm(U.dev(A), U.dev(B), C, accumulate=True)
+    run(U.dev(A), U.dev(B), C, accumulate=True)
     if kind == inputs.SMALLINT or dtype == np.float64:
         assert np.array_equal(U.host(C), got * 2)
     else:
@@ -175,14 +179,15 @@ def test_gemm_big_tile_configs(lib, oracle, kind, dtype, M, N, K, tile):
 
 
 # ragged shapes that reach the same launch configurations in their edge-clamping form (M and N
-# not whole tiles, K with trailing terms for the second pass), in the order of BIG_TILE_SHAPES,
-# then 128 x 64 binary32 and a shape whose K is made of whole slabs
-RAGGED_TILE_SHAPES = [(np.float32, 4000, 4000, 1028, (256, 256, 32), 0), (np.float32, 4000, 4090, 520, (256, 128, 16), 0),
+# not whole tiles, K with trailing terms for the second pass).  split None: the tile is named by
+# the caller; otherwise the planner runs the product and must choose this tile and this cut.
+RAGGED_TILE_SHAPES = [(np.float32, 4000, 4000, 1028, (256, 256, 32), None), (np.float32, 4000, 4090, 520, (256, 128, 16), None),
+                      (np.float32, 4000, 4090, 520, (128, 256, 16), 0), (np.float32, 3900, 4072, 1056, (128, 256, 16), 0),
                       (np.float64, 4000, 4090, 4100, (256, 128, 16), 0), (np.float64, 4000, 2040, 72, (128, 128, 16), 0),
-                      (np.float32, 3000, 2040, 100, (128, 64, 16), 0), (np.float32, 3900, 4072, 1056, (256, 256, 32), 0),
+                      (np.float32, 3000, 2040, 100, (128, 64, 16), 0), (np.float32, 3900, 4072, 1056, (256, 256, 32), None),
                       # two launches: whole rounds of large tiles, the rest on small tiles - cut along the
-                      # rows (binary32 256 x 256; binary64 128 x 128) and along the columns (binary64 128 x 128)
-                      (np.float32, 4200, 4096, 1024, (256, 256, 32), 1), (np.float64, 8200, 8192, 272, (128, 128, 16), 1),
+                      # rows (binary32 128 x 256; binary64 128 x 128) and along the columns (binary64 128 x 128)
+                      (np.float32, 4200, 4096, 1024, (128, 256, 16), 1), (np.float64, 8200, 8192, 272, (128, 128, 16), 1),
                       (np.float64, 8192, 8200, 272, (128, 128, 16), 2)]
 
 
@@ -193,12 +198,16 @@ def test_gemm_ragged_edge_tiles(lib, oracle, kind, dtype, M, N, K, tile, split):
     of the edge tiles must not be stored.  The oracle recomputes sampled rows (first, last, some
     of the last tile row) over all columns."""
     vec = 16 // np.dtype(dtype).itemsize
-    assert lib.gemm_plan(int(dtype == np.float64), False, M, N, K)[:2] == (tile, split)
+    if split is None:
+        run = lambda a, b, c, **kw: lib.distal_gemm_tiled(tile[:2], a, b, c, **kw)
+    else:
+        assert lib.gemm_plan(int(dtype == np.float64), False, M, N, K)[:2] == (tile, split)
+        run = lambda a, b, c, **kw: lib.distal_gemm(a, b, c, **kw)
     A, B = U.gen(300 + K, 0, (M, K), dtype, kind), U.gen(300 + K, 1, (K, N), dtype, kind)
     big = np.full((M + 3, N + 2 * vec), 77.0, dtype=dtype)
     dC = U.dev(big)
     view = dC[2:2 + M, vec:vec + N]
-    lib.distal_gemm(U.dev(A), U.dev(B), view)
+    run(U.dev(A), U.dev(B), view)
     out = U.host(dC)
     got = out[2:2 + M, vec:vec + N]
     assert np.all(np.isfinite(got))
@@ -212,7 +221,7 @@ def test_gemm_ragged_edge_tiles(lib, oracle, kind, dtype, M, N, K, tile, split):
     # accumulate on top of the product: twice it (exactly so in binary64, where the product is formed
     # first and then added; binary32 adds the terms to the old values one by one), and still nothing
     # outside
-    lib.distal_gemm(U.dev(A), U.dev(B), view, accumulate=True)
+    run(U.dev(A), U.dev(B), view, accumulate=True)
     out2 = U.host(dC)
     if kind == inputs.SMALLINT or dtype == np.float64:
         assert np.array_equal(out2[2:2 + M, vec:vec + N], got * 2)
