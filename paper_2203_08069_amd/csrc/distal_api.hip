@@ -48,9 +48,9 @@ constexpr int64_t kMaxGridY = 65535;
 // One launch per run of at most kMaxGridY problems of the batch (blockIdx.y picks the problem).
 // KIND: the guarded kernel, the straight-line kernel on whole tiles, or its edge-clamping form.
 enum { kGuarded = 0, kWhole = 1, kEdge = 2, kEdgeK = 3 };
-template <typename T, int BM, int BN, int BK, int WM, int WN, int KIND, bool TA>
+template <typename T, int BM, int BN, int BK, int WM, int WN, int KIND, bool TA, bool FINE = false>
 int launch_contract(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
-    typedef ContractCfg<T, BM, BN, BK, WM, WN, TA> Cfg;
+    typedef ContractCfg<T, BM, BN, BK, WM, WN, TA, FINE> Cfg;
     a.tiles_m = (int)((a.M + BM - 1) / BM);
     a.tiles_n = (int)((a.N + BN - 1) / BN);
     const int64_t nblocks = (int64_t)a.tiles_m * a.tiles_n;
@@ -73,14 +73,14 @@ int launch_contract(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
             if constexpr (kInitForm) {
                 if (a.accumulate && a.K <= 256) {
                     static std::atomic<bool> done_acc[kMaxDevices];
-                    auto kern = contract_fast_kernel<T, BM, BN, BK, WM, WN, TA, EDGE, true>;
+                    auto kern = contract_fast_kernel<T, BM, BN, BK, WM, WN, TA, EDGE, true, FINE>;
                     if (!allow_lds(kern, Cfg::LDS_BYTES, done_acc)) return DISTAL_ERR_LAUNCH;
                     hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
                     launched = true;
                 }
             }
             if (!launched) {
-                auto kern = contract_fast_kernel<T, BM, BN, BK, WM, WN, TA, EDGE, false>;
+                auto kern = contract_fast_kernel<T, BM, BN, BK, WM, WN, TA, EDGE, false, FINE>;
                 if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
                 hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
             }
@@ -97,7 +97,7 @@ int launch_contract(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
 // straddle an edge (K >= BK): whole tiles as they are, ragged M or N through the edge-clamping
 // form, K % BK trailing terms as that form's extra slab - or, where pieces of A would straddle
 // the end of K (no TA, K not a multiple of the vector), by a second, guarded pass over C.
-template <typename T, int BM, int BN, int BK, int WM, int WN, bool TA>
+template <typename T, int BM, int BN, int BK, int WM, int WN, bool TA, bool FINE = false>
 int launch_tiles(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
     constexpr int VEC = 16 / (int)sizeof(T);
     if (a.K < BK) return launch_contract<T, 128, 128, 16, 2, 2, kGuarded, TA>(a, batch, stream);   // no whole slab
@@ -106,12 +106,12 @@ int launch_tiles(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
     if (!slab_offsets_fit((int64_t)sizeof(T), TA, BM, BN, BK, a.lda, a.ldb)) return launch_contract<T, 128, 128, 16, 2, 2, kGuarded, TA>(a, batch, stream);
     const int64_t k_main = a.K / BK * BK, k_tail = a.K - k_main;
     if (k_tail == 0)
-        return (a.M % BM == 0 && a.N % BN == 0) ? launch_contract<T, BM, BN, BK, WM, WN, kWhole, TA>(a, batch, stream)
-                                                : launch_contract<T, BM, BN, BK, WM, WN, kEdge, TA>(a, batch, stream);
-    if (TA || a.K % VEC == 0) return launch_contract<T, BM, BN, BK, WM, WN, kEdgeK, TA>(a, batch, stream);
+        return (a.M % BM == 0 && a.N % BN == 0) ? launch_contract<T, BM, BN, BK, WM, WN, kWhole, TA, FINE>(a, batch, stream)
+                                                : launch_contract<T, BM, BN, BK, WM, WN, kEdge, TA, FINE>(a, batch, stream);
+    if (TA || a.K % VEC == 0) return launch_contract<T, BM, BN, BK, WM, WN, kEdgeK, TA, FINE>(a, batch, stream);
     ContractArgs<T> m = a;
     m.K = k_main;
-    const int rc = launch_contract<T, BM, BN, BK, WM, WN, kEdge, TA>(m, batch, stream);
+    const int rc = launch_contract<T, BM, BN, BK, WM, WN, kEdge, TA, FINE>(m, batch, stream);
     if (rc != DISTAL_OK) return rc;
     ContractArgs<T> t = a;                       // k_main is a multiple of 16: alignment is unchanged
     t.A += k_main;
@@ -154,13 +154,17 @@ int launch_fill(T *out, int64_t rows, int64_t cols, int64_t ld, hipStream_t stre
 // not by the caller: the result does not depend on it (every output sums its terms in the same
 // order whichever wavefront owns it), only the speed does.  A grid that gives a compute unit one
 // tile or two leaves its SIMDs with one wavefront each unless the tile is cut into more of them:
-// binary32 128 x 128 on eight wavefronts of 32 x 64 instead of four of 64 x 64 measures 86.7 against
-// 79.0 % of peak at 2048^3 (256 tiles) and 91.1 against 92.1 at 4096^2 x 2048 (1024 tiles); binary64
-// 128 x 128 on sixteen instead of eight 90.8 against 88.8 at 256 tiles, 91.2 against 93.6 at 512;
-// binary64 64 x 64 on eight instead of four 74.2 against 64.1 at 1024^3 (256 tiles), level from
-// 600 tiles on.  The binary64 128 x 64 and 64 x 128 tiles run on eight wavefronts of 32 x 32 at
-// every grid size (4096^2 x 2048: 93.5 against 88.8 and 94.9 against 92.4 on four); in binary32
-// the same cut loses 1 to 5 points everywhere and is not used.
+// binary64 128 x 128 on sixteen wavefronts instead of eight measures 90.8 against 88.8 % of peak at
+// 256 tiles, 91.2 against 93.6 at 512; binary64 64 x 64 on eight instead of four 74.2 against 64.1
+// at 1024^3 (256 tiles), level from 600 tiles on.  The binary64 128 x 64 and 64 x 128 tiles run on
+// eight wavefronts of 32 x 32 at every grid size (4096^2 x 2048: 93.5 against 88.8 and 94.9
+// against 92.4 on four).  In binary32 a wavefront of 32 x 32 would own a single block of the
+// 32 x 32 x 2 instruction and measured 1 to 5 points slower; the binary32 tiles up to 128 x 128
+// therefore use the 16 x 16 x 4 instruction (FINE), eight wavefronts of 2 x 2 blocks (2 x 4 on
+// 128 x 128, 1 x 2 on 64 x 64), at every grid size - a different instruction sums in a different
+// order, so a tile name stands for one of the two and never both: 64 x 64 x 32 at 4096^2 x 2048
+// 87.9 -> 91.2 % of peak, at 3000^3 82.4 -> 86.2; 128 x 64 at 256 tiles 68.4 -> 81.3; 128 x 128
+// at 8192^3 93.3 -> 96.2.
 template <typename T, bool TA>
 int launch_by_id(int id, const ContractArgs<T> &a, int64_t batch, hipStream_t stream) {
     auto tiles = [&](int bm, int bn) { return ((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn) * batch; };
@@ -177,8 +181,7 @@ int launch_by_id(int id, const ContractArgs<T> &a, int64_t batch, hipStream_t st
         else return launch_tiles<T, 256, 128, 16, 8, 2, TA>(a, batch, stream);
     case 3:
         if constexpr (sizeof(T) == 4) {
-            if (tiles(128, 128) <= 384) return launch_tiles<T, 128, 128, 16, 4, 2, TA>(a, batch, stream);
-            return launch_tiles<T, 128, 128, 16, 2, 2, TA>(a, batch, stream);
+            return launch_tiles<T, 128, 128, 16, 4, 2, TA, true>(a, batch, stream);
         } else {
             if (tiles(128, 128) <= 256) return launch_tiles<T, 128, 128, 16, 8, 2, TA>(a, batch, stream);
             return launch_tiles<T, 128, 128, 16, 4, 2, TA>(a, batch, stream);
@@ -196,13 +199,13 @@ int launch_by_id(int id, const ContractArgs<T> &a, int64_t batch, hipStream_t st
         if constexpr (sizeof(T) == 4) return launch_tiles<T, 32, 256, 32, 1, 4, TA>(a, batch, stream);
         else return launch_tiles<T, 32, 256, 16, 1, 4, TA>(a, batch, stream);
     case 9:
-        if constexpr (sizeof(T) == 4) return launch_tiles<T, 128, 64, 16, 4, 1, TA>(a, batch, stream);
+        if constexpr (sizeof(T) == 4) return launch_tiles<T, 128, 64, 32, 4, 2, TA, true>(a, batch, stream);
         break;
     case 10:
-        if constexpr (sizeof(T) == 4) return launch_tiles<T, 64, 128, 16, 2, 2, TA>(a, batch, stream);
+        if constexpr (sizeof(T) == 4) return launch_tiles<T, 64, 128, 32, 4, 2, TA, true>(a, batch, stream);
         break;
     case 11:
-        if constexpr (sizeof(T) == 4) return launch_tiles<T, 64, 64, 32, 2, 2, TA>(a, batch, stream);
+        if constexpr (sizeof(T) == 4) return launch_tiles<T, 64, 64, 32, 4, 2, TA, true>(a, batch, stream);
         break;
     case 12:
         if constexpr (sizeof(T) == 4) return launch_tiles<T, 128, 256, 16, 2, 4, TA>(a, batch, stream);

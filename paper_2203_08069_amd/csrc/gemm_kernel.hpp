@@ -97,9 +97,22 @@ struct ContractArgs {
     int64_t batch_a, batch_b, batch_c;  // element strides between the problems of a batch (blockIdx.y)
 };
 
-template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TA = false>
+// binary32 also has the 16 x 16 x 4 instruction, at the same rate: four times as many blocks per
+// tile, so a small tile can be cut into eight wavefronts that still own 2 x 2 blocks each (FINE).
+struct MfmaFineF32 {                       // v_mfma_f32_16x16x4_f32
+    static constexpr int MB = 16, NB = 16, KS = 4, NACC = 4;
+    typedef v4f acc_t;
+    static __device__ __forceinline__ acc_t run(float a, float b, acc_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int out_row(int v, int lane) { return 4 * (lane >> 4) + v; }
+};
+template <typename T, bool FINE> struct MfmaPick { typedef Mfma<T> type; };
+template <> struct MfmaPick<float, true> { typedef MfmaFineF32 type; };
+
+template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TA = false, bool FINE = false>
 struct ContractCfg {
-    typedef Mfma<T> MF;
+    typedef typename MfmaPick<T, FINE>::type MF;
     static constexpr int NT = 64 * WAVES_M * WAVES_N;
     static constexpr int VEC = 16 / (int)sizeof(T);      // elements per 16-byte access
     static constexpr int KV = VEC;                        // consecutive k per lane per A read
@@ -156,8 +169,8 @@ __device__ __forceinline__ int sub_tile_row(int mi, int v, int lane) {
 // read positions (a_read_offset / b_read_offset) of that stage.
 template <typename T, typename Cfg, int KG_LO, int KG_HI>
 __device__ __forceinline__ void mfma_groups(const T *as, const T *bs,
-                                            typename Mfma<T>::acc_t (&acc)[Cfg::MI][Cfg::NI]) {
-    typedef Mfma<T> MF;
+                                            typename Cfg::MF::acc_t (&acc)[Cfg::MI][Cfg::NI]) {
+    typedef typename Cfg::MF MF;
     typedef typename VecOf<T, Cfg::VEC>::type vec_t;
     typedef typename VecOf<T, Cfg::CV>::type cvec_t;
     typedef typename VecOf<T, Cfg::RV>::type rvec_t;
@@ -423,11 +436,12 @@ contract_kernel(ContractArgs<T> args) {
 // sit in front of the first multiply with nothing to hide behind), so the host launches this
 // form there only; binary64 shows no gain at any shape and always adds in the epilogue.
 // ---------------------------------------------------------------------------
-template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TA = false, int EDGE = 0, bool ACC_INIT = false>
+template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TA = false, int EDGE = 0, bool ACC_INIT = false,
+          bool FINE = false>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 4 : 2)
 contract_fast_kernel(ContractArgs<T> args) {
-    typedef ContractCfg<T, BM, BN, BK, WAVES_M, WAVES_N, TA> Cfg;
-    typedef Mfma<T> MF;
+    typedef ContractCfg<T, BM, BN, BK, WAVES_M, WAVES_N, TA, FINE> Cfg;
+    typedef typename Cfg::MF MF;
     typedef typename VecOf<T, Cfg::VEC>::type vec_t;
     typedef typename VecOf<T, Cfg::CV>::type cvec_t;
     typedef typename GlobalVecOf<T, Cfg::CV>::type gcvec_t;

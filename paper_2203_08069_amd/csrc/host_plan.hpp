@@ -77,13 +77,15 @@ inline int tile_candidates(bool f64, bool ta, int64_t M, int64_t N, int64_t K, T
         // 128 columns and 64 rows (512-byte runs of C, four workgroups per compute unit) then measure
         // 4..5 points ahead of 128 x 128 and of 128 x 64
         const bool thin_acc = acc && K <= 256;
-        c[2] = {3, !thin_acc, 128, 128, 16, {0.852, 0.884, 0.905, 0.923, 0.933, 0.939}};
+        c[2] = {3, !thin_acc, 128, 128, 16, {0.843, 0.906, 0.919, 0.927, 0.939, 0.950}};
         c[3] = {4, K < 256, 64, 64, 16, {0.628, 0.759, 0.806, 0.829, 0.835, 0.852}};
-        c[4] = {9, !thin_acc, 128, 64, 16, {0.666, 0.830, 0.877, 0.835, 0.880, 0.900}};
-        c[5] = {10, true, 64, 128, 16, {0.666, 0.832, 0.876, 0.877, 0.885, 0.902}};
+        c[4] = {9, !thin_acc && K >= 32, 128, 64, 32, {0.754, 0.849, 0.864, 0.888, 0.889, 0.911}};
+        c[5] = {10, K >= 32, 64, 128, 32, {0.732, 0.842, 0.881, 0.877, 0.888, 0.911}};
+        // (128 x 128, 128 x 64, 64 x 128 and the 32-deep 64 x 64 run on the 16 x 16 x 4 instruction, eight
+        // wavefronts each; see launch_by_id)
         // 64 x 64 with 32-deep slabs: half the barriers per term; pays from K = 256 on (binary32 only:
         // the same in binary64 measured 3..9 % slower)
-        c[6] = {11, K >= 256, 64, 64, 32, {0.614, 0.763, 0.812, 0.828, 0.830, 0.836}};
+        c[6] = {11, K >= 256, 64, 64, 32, {0.699, 0.808, 0.844, 0.841, 0.854, 0.867}};
         c[7] = {5, n64, 256, 64, 16, {}};
         c[8] = {6, n32 && K >= 32, 128, 32, 32, {}};
         c[9] = {7, m64, 64, 256, 16, {}};

@@ -198,7 +198,7 @@ def test_gemm_plan_choice(lib):
     tile, plan = binding.gemm_tile, binding.gemm_plan
     # the headline product in both types, and the benchmark's tensor-times-matrix shape along modes 2, 0, 1
     assert tile(F64, False, 8192, 8192, 8192) == (128, 128, 16)
-    assert tile(F32, False, 8192, 8192, 8192) == (128, 256, 16)
+    assert tile(F32, False, 8192, 8192, 8192) == (128, 128, 16)
     assert tile(F32, False, 1 << 20, 256, 1024) == (256, 256, 32)      # as wide as the output: the tensor is read once
     assert tile(F32, True, 256, 1 << 20, 1024) == (256, 256, 16)
     assert tile(F32, True, 256, 1024, 1024, batch=1024) == (256, 256, 16)
@@ -207,12 +207,12 @@ def test_gemm_plan_choice(lib):
     for K in (256, 512, 1024, 2048):
         assert tile(F64, False, 8192, 8192, K) == (128, 128, 16)
     for K in (128, 256, 512, 1040):
-        assert tile(F32, False, 8192, 8192, K) == (128, 256, 16)
+        assert tile(F32, False, 8192, 8192, K) == (128, 128, 16)
     assert tile(F32, False, 4096, 4096, 4096) == (128, 256, 16)     # two tiles per compute unit
     assert tile(F32, False, 1 << 20, 128, 1024) == (256, 128, 16)   # as wide as the output, and the taller tile
     # rank-sized outputs: a 32- or 64-wide short side on the narrow operand's side
     assert tile(F32, False, 1 << 20, 32, 1024) == (128, 32, 32)
-    assert tile(F32, False, 1 << 20, 64, 1024) == (256, 64, 16)
+    assert tile(F32, False, 1 << 20, 64, 1024) == (128, 64, 32)
     assert tile(F32, True, 32, 1 << 20, 1024) == (32, 256, 32)
     assert tile(F64, False, 1 << 19, 16, 1024) == (128, 32, 16)
     assert tile(F64, True, 64, 1 << 19, 1024) == (64, 128, 16)
@@ -225,12 +225,12 @@ def test_gemm_plan_choice(lib):
     # tile runs below its speed; 2209 tiles of 64 x 64 are nine rounds at full speed
     assert plan(F64, False, 3000, 3000, 3000) == ((64, 64, 16), 0, 0, (0, 0, 0))
     # binary32: 64 x 64 tiles take 32-deep slabs from K = 256 on
-    assert plan(F32, False, 3000, 3000, 3000) == ((128, 256, 16), 1, 2688, (64, 64, 32))
+    assert plan(F32, False, 3000, 3000, 3000) == ((128, 128, 16), 1, 2688, (64, 64, 32))
     assert plan(F32, False, 3500, 3500, 3500) == ((64, 64, 32), 0, 0, (0, 0, 0))
-    # 2000^3: one 128 x 128 tile per compute unit (run on eight wavefronts at that grid size)
-    assert plan(F32, False, 2000, 2000, 2000) == ((128, 128, 16), 0, 0, (0, 0, 0))
-    assert plan(F32, False, 2000, 2000, 200) == ((128, 128, 16), 0, 0, (0, 0, 0))
-    assert plan(F32, False, 3000, 2040, 100) == ((128, 64, 16), 0, 0, (0, 0, 0))
+    # 2000^3: two 128 x 64 tiles per compute unit
+    assert plan(F32, False, 2000, 2000, 2000) == ((128, 64, 32), 0, 0, (0, 0, 0))
+    assert plan(F32, False, 2000, 2000, 200) == ((128, 64, 32), 0, 0, (0, 0, 0))
+    assert plan(F32, False, 3000, 2040, 100) == ((64, 128, 32), 0, 0, (0, 0, 0))
     assert plan(F64, False, 2048, 2048, 2048) == ((64, 128, 16), 0, 0, (0, 0, 0))      # two per compute unit
     assert tile(F32, False, 1024, 1024, 128) == (64, 64, 16)
     assert plan(F32, False, 4000, 2040, 100) == ((128, 128, 16), 0, 0, (0, 0, 0))
@@ -243,7 +243,7 @@ def test_gemm_plan_choice(lib):
     assert plan(F64, False, 8192, 8200, 8192) == ((128, 128, 16), 2, 8192, (64, 64, 16))
     assert plan(F64, False, 5000, 5000, 5000) == ((128, 128, 16), 1, 4864, (64, 64, 16))
     assert plan(F32, False, 4200, 4096, 1024) == ((128, 256, 16), 1, 4096, (64, 64, 32))
-    assert plan(F32, False, 8200, 8192, 8192) == ((128, 256, 16), 1, 8192, (64, 64, 32))
+    assert plan(F32, False, 8200, 8192, 8192) == ((128, 128, 16), 1, 8192, (64, 64, 32))
     tile3, rest3 = (ctypes.c_int * 3)(), (ctypes.c_int * 3)()
     split, cut = ctypes.c_int(), ctypes.c_int64()
     refs = (tile3, ctypes.byref(split), ctypes.byref(cut), rest3)
@@ -251,11 +251,11 @@ def test_gemm_plan_choice(lib):
     assert lib.distal_gemm_plan(0, 0, 0, 8, 8, 1, 0, *refs) == 2
     assert lib.distal_gemm_plan(0, 0, 8, 8, 8, 0, 0, *refs) == 2
     assert lib.distal_gemm_plan(0, 0, 8, 8, 8, 1, 0, None, None, None, None) == 1
-    # added onto an old C, binary32 takes the 128 x 256 tile from K = 512 on and 64 x 128 tiles for thinner
+    # added onto an old C, binary32 takes the 128 x 128 tile from K = 512 on and 64 x 128 tiles for thinner
     # steps; binary64 changes tile only for steps of at most 128 terms
     for K in (512, 1024, 4096):
-        assert tile(F32, False, 8192, 8192, K, accumulate=True) == (128, 256, 16)
-    assert tile(F32, False, 8192, 8192, 256, accumulate=True) == (64, 128, 16)      # thin and bound by C's traffic
+        assert tile(F32, False, 8192, 8192, K, accumulate=True) == (128, 128, 16)
+    assert tile(F32, False, 8192, 8192, 256, accumulate=True) == (64, 128, 32)      # thin and bound by C's traffic
     for K in (256, 1024, 8192):
         assert plan(F64, False, 8192, 8192, K, accumulate=True) == plan(F64, False, 8192, 8192, K)
     assert tile(F64, False, 8192, 8192, 128, accumulate=True) == (64, 128, 16)      # bound by C's traffic

@@ -150,10 +150,13 @@ def test_ttm_1024(lib, oracle):
     got = A.view(I * J, L)[torch.from_numpy(fibres).cuda()].cpu().numpy()
     U.assert_close(got, ref, np.float32, K)
     assert bool(torch.isfinite(A).all())
-    # linear in C: the contraction with 2C is exactly twice the result
-    A2 = torch.empty_like(A[:8])
+    # linear in C: the contraction with 2C is exactly twice the result (the same shape both times:
+    # another shape may run on another tile, whose instruction sums the terms in another order)
+    A1, A2 = torch.empty_like(A[:8]), torch.empty_like(A[:8])
+    lib.distal_ttm(B[:8], C, A1)
     lib.distal_ttm(B[:8], C * 2, A2)
-    assert torch.equal(A2, A[:8] * 2)
+    assert torch.equal(A2, A1 * 2)
+    U.assert_close(A1.cpu().numpy(), A[:8].cpu().numpy().astype(np.float64), np.float32, K)
 
 
 def test_mttkrp_1024(lib, oracle):

@@ -125,7 +125,7 @@ def test_ttm_mode0_ragged_edge_tiles(lib, oracle, dtype, kind, I, J, K, R):
     the transposed-left-operand kernels in their edge-clamping form (128 x 256 binary32 tiles; 128 x 128
     and 256 x 128 binary64 tiles); the last two shapes run as two launches in
     binary32, cut along the columns and along the rows.  Some j-slices are checked in full."""
-    want = {(200, 4080): ((128, 256, 16), (128, 128, 16)), (1028, 4000): ((128, 256, 16), (128, 128, 16)),
+    want = {(200, 4080): ((128, 128, 16), (128, 128, 16)), (1028, 4000): ((128, 256, 16), (128, 128, 16)),
             (4100, 4000): ((128, 256, 16), (256, 128, 16)), (520, 4000): ((128, 256, 16), (128, 128, 16)),
             (1028, 4096): ((128, 256, 16), None),
             (1024, 4200): ((128, 256, 16), None)}[(I, R)][int(dtype == np.float64)]

@@ -100,14 +100,16 @@ def test_gemm_every_tile_by_name(lib, oracle, dtype, tile, M, N, K, ta):
     assert np.all(out2[mask] == 77.0)
 
 
-# The library decides how many wavefronts share a tile from the number of tiles in the grid
-# (a tile alone on a compute unit is cut into more wavefronts).  Grids on both sides of each
-# switch, whole and ragged, left operand stored either way: tile, M, N, what runs.
+# The library decides how many wavefronts share a tile, for some binary64 tiles from the number
+# of tiles in the grid (a tile alone on a compute unit is cut into more wavefronts).  Grids on
+# both sides of each switch and the eight-wavefront binary32 tiles, whole and ragged, left
+# operand stored either way: tile, M, N, what runs.
 WAVEFRONT_SWITCHES = [
-    (np.float32, (128, 128), 2048, 2048, "256 tiles: eight wavefronts"),
-    (np.float32, (128, 128), 2550, 2430, "380 tiles, ragged: eight wavefronts"),
-    (np.float32, (128, 128), 2560, 2560, "400 tiles: four wavefronts"),
-    (np.float32, (128, 128), 2555, 2564, "420 tiles, ragged: four wavefronts"),
+    (np.float32, (128, 128), 2048, 2048, "eight wavefronts of 2 x 4 blocks of the 16 x 16 x 4 instruction"),
+    (np.float32, (128, 128), 2550, 2430, "the same, ragged"),
+    (np.float32, (128, 64), 1024, 1022, "eight wavefronts of 2 x 2 blocks, ragged"),
+    (np.float32, (64, 128), 1022, 1024, "eight wavefronts of 2 x 2 blocks, ragged"),
+    (np.float32, (64, 64), 1400, 1470, "eight wavefronts of 1 x 2 blocks, ragged"),
     (np.float64, (128, 128), 2048, 2048, "256 tiles: sixteen wavefronts"),
     (np.float64, (128, 128), 2040, 2046, "256 tiles, ragged: sixteen wavefronts"),
     (np.float64, (128, 128), 2048, 2176, "272 tiles: eight wavefronts"),
@@ -184,7 +186,7 @@ def test_gemm_big_tile_configs(lib, oracle, kind, dtype, M, N, K, tile):
 RAGGED_TILE_SHAPES = [(np.float32, 4000, 4000, 1028, (256, 256, 32), None), (np.float32, 4000, 4090, 520, (256, 128, 16), None),
                       (np.float32, 4000, 4090, 520, (128, 256, 16), 0), (np.float32, 3900, 4072, 1056, (128, 256, 16), 0),
                       (np.float64, 4000, 4090, 4100, (256, 128, 16), 0), (np.float64, 4000, 2040, 72, (128, 128, 16), 0),
-                      (np.float32, 3000, 2040, 100, (128, 64, 16), 0), (np.float32, 3900, 4072, 1056, (256, 256, 32), None),
+                      (np.float32, 3000, 2040, 100, (64, 128, 32), 0), (np.float32, 3900, 4072, 1056, (256, 256, 32), None),
                       # two launches: whole rounds of large tiles, the rest on small tiles - cut along the
                       # rows (binary32 128 x 256; binary64 128 x 128) and along the columns (binary64 128 x 128)
                       (np.float32, 4200, 4096, 1024, (128, 256, 16), 1), (np.float64, 8200, 8192, 272, (128, 128, 16), 1),
