@@ -92,8 +92,9 @@ inline int tile_candidates(bool f64, bool ta, int64_t M, int64_t N, int64_t K, T
         c[10] = {8, m32 && K >= 32, 32, 256, 32, {}};
         narrow_eff(c[7], 0.891); narrow_eff(c[8], 0.575); narrow_eff(c[9], 0.883); narrow_eff(c[10], 0.585);
         // 128 x 256: two workgroups per compute unit like 256 x 128, with 1 KiB rows of the right operand
-        // and of C; 0.5 to 1.7 points ahead of it at every depth from 128 to 8192 (8192^3: 96.3 against 95.8)
-        c[11] = {12, K >= (acc ? 512 : 128), 128, 256, 16, {0.905, 0.933, 0.937, 0.945, 0.946, 0.954}};
+        // and of C; 0.5 to 1.7 points ahead of it at every depth from 128 to 8192 (8192^3: 96.3 against 95.8),
+        // level with 128 x 128 on large grids and ahead of it at two tiles per compute unit (4096^3)
+        c[11] = {12, K >= (acc ? 512 : 128), 128, 256, 16, {0.905, 0.933, 0.937, 0.945, 0.946, 0.948}};
         return 12;
     }
     c[0] = {2, K >= 2048, 256, 128, 16, {0.863, 0.941, 0.943, 0.941, 0.946, 0.945}};
@@ -123,18 +124,6 @@ inline double rounds_cost(int64_t tiles, const TileCandidate &c) {
     return (double)J * (double)(c.bm * c.bn) / e;
 }
 
-// A tile as wide as the output (or as tall) lets each slab of the long operand be read by exactly
-// one workgroup instead of by two or four that must meet in L2: the tensor-times-matrix shapes
-// (2^20 x 256 x 1024) measure 1.2 to 2 points more on 256 x 256 binary32 tiles than on 256 x 128
-// ones, which are the faster tile on square grids of the same depth.
-// The other operand's panel is then fetched once per tile of the long direction, so the bonus grows with
-// the tile's extent along it (2^20 x 256 x 1024: 90.7 % on 256 x 256 tiles, 90.1 on 128 x 256).
-inline double span_factor(int64_t tm, int64_t tn, int bm, int bn) {
-    if (tn == 1) return 1.0 - 0.025 * (bm >= 256 ? 1.0 : (double)bm / 256.0);
-    if (tm == 1) return 1.0 - 0.025 * (bn >= 256 ? 1.0 : (double)bn / 256.0);
-    return 1.0;
-}
-
 // The tile with the least estimated time for a product run as one launch.
 inline TilePick pick_tile(bool f64, bool ta, int64_t M, int64_t N, int64_t K, int64_t batch, bool acc = false) {
     TileCandidate cand[kMaxTileCandidates];
@@ -143,7 +132,7 @@ inline TilePick pick_tile(bool f64, bool ta, int64_t M, int64_t N, int64_t K, in
     for (int i = 0; i < n; ++i) {
         if (!cand[i].eligible) continue;
         const int64_t tm = (M + cand[i].bm - 1) / cand[i].bm, tn = (N + cand[i].bn - 1) / cand[i].bn;
-        const double c = rounds_cost(tm * tn * batch, cand[i]) * span_factor(tm, tn, cand[i].bm, cand[i].bn);
+        const double c = rounds_cost(tm * tn * batch, cand[i]);
         if (c < pick.cost) pick = TilePick{cand[i].id, cand[i].bm, cand[i].bn, cand[i].bk, c};   // earlier candidates win ties
     }
     return pick;
@@ -174,8 +163,7 @@ inline ProductPlan plan_product(bool f64, bool ta, int64_t M, int64_t N, int64_t
             if (lines < 1 || cut >= (split == 1 ? M : N)) continue;
             const TilePick rest = split == 1 ? pick_tile(f64, ta, M - cut, N, K, batch, acc)
                                              : pick_tile(f64, ta, M, N - cut, K, batch, acc);
-            const double total = rounds_cost(lines * per_line, c) * span_factor(split == 1 ? lines : tm, split == 1 ? tn : lines, c.bm, c.bn)
-                                 + rest.cost + launch_cost;
+            const double total = rounds_cost(lines * per_line, c) + rest.cost + launch_cost;
             if (total < 0.985 * best) {                                             // worth a second launch
                 best = total / 0.985;
                 plan = ProductPlan{TilePick{c.id, c.bm, c.bn, c.bk, total}, split, cut, rest};

@@ -199,9 +199,9 @@ def test_gemm_plan_choice(lib):
     # the headline product in both types, and the benchmark's tensor-times-matrix shape along modes 2, 0, 1
     assert tile(F64, False, 8192, 8192, 8192) == (128, 128, 16)
     assert tile(F32, False, 8192, 8192, 8192) == (128, 128, 16)
-    assert tile(F32, False, 1 << 20, 256, 1024) == (256, 256, 32)      # as wide as the output: the tensor is read once
-    assert tile(F32, True, 256, 1 << 20, 1024) == (256, 256, 16)
-    assert tile(F32, True, 256, 1024, 1024, batch=1024) == (256, 256, 16)
+    assert tile(F32, False, 1 << 20, 256, 1024) == (128, 128, 16)
+    assert tile(F32, True, 256, 1 << 20, 1024) == (128, 128, 16)
+    assert tile(F32, True, 256, 1024, 1024, batch=1024) == (128, 128, 16)
     assert tile(F64, False, 1 << 20, 256, 1024) == (128, 128, 16)
     # SUMMA k-chunks
     for K in (256, 512, 1024, 2048):
@@ -209,7 +209,7 @@ def test_gemm_plan_choice(lib):
     for K in (128, 256, 512, 1040):
         assert tile(F32, False, 8192, 8192, K) == (128, 128, 16)
     assert tile(F32, False, 4096, 4096, 4096) == (128, 256, 16)     # two tiles per compute unit
-    assert tile(F32, False, 1 << 20, 128, 1024) == (256, 128, 16)   # as wide as the output, and the taller tile
+    assert tile(F32, False, 1 << 20, 128, 1024) == (128, 128, 16)
     # rank-sized outputs: a 32- or 64-wide short side on the narrow operand's side
     assert tile(F32, False, 1 << 20, 32, 1024) == (128, 32, 32)
     assert tile(F32, False, 1 << 20, 64, 1024) == (128, 64, 32)
