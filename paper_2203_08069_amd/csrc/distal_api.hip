@@ -132,13 +132,14 @@ int launch_fill(T *out, int64_t rows, int64_t cols, int64_t ld, hipStream_t stre
 }
 
 // ---- matrix multiply ------------------------------------------------------
-// Tile choice depends on the shape only.  What matters most is four wavefronts per SIMD:
-// binary64 wavefronts own 32 x 64 sub-tiles (64 accumulator registers), eight of them on a
-// 128 x 128 tile or, for deep products, sixteen on 256 x 128; binary32 wavefronts own 64 x 64
-// sub-tiles, sixteen on a 256 x 256 tile with 32-deep slabs for deep products, eight on 256 x 128
-// for k-chunks (with one workgroup per CU the epilogue is not hidden, so shallow products want
-// smaller tiles), four on 128 x 128; 128 x 64, 64 x 128 and 64 x 64 tiles for problems too small
-// to fill the part with those.  Among the shapes a product is deep enough for, the one with the
+// Tile choice depends on the shape only.  What matters most is four wavefronts per SIMD (at most
+// 128 registers each) and at least two workgroups per compute unit, so that one's prologue and
+// epilogue run under the other's k-loop: the tile large grids run on is 128 x 128 in both types,
+// eight wavefronts of 32 x 64 (2 x 4 blocks of the 16 x 16 x 4 instruction); binary32 also has
+// 128 x 256 and 256 x 128 on eight wavefronts of 64 x 64 and 256 x 256 on sixteen (32 x 32 x 2
+// blocks, 32-deep slabs), binary64 256 x 128 on sixteen - they win where a compute unit gets one or
+// two tiles; 128 x 64, 64 x 128 and 64 x 64 tiles serve problems too small to fill the part with
+// those.  Among the shapes a product is deep enough for, the one with the
 // least estimated time wins: tiles per compute unit, a partly filled last round counted in
 // full, x tile area / the efficiency measured for that tile at that many tiles per compute
 // unit (tile_candidates() holds the table).  A rank-sized output side (N <= 64, or M <= 64 as
