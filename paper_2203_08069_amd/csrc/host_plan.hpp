@@ -97,7 +97,7 @@ inline int tile_candidates(bool f64, bool ta, int64_t M, int64_t N, int64_t K, T
         c[11] = {12, K >= (acc ? 512 : 128), 128, 256, 16, {0.905, 0.933, 0.937, 0.945, 0.946, 0.948}};
         return 12;
     }
-    c[0] = {2, K >= 2048, 256, 128, 16, {0.863, 0.941, 0.943, 0.941, 0.946, 0.945}};
+    c[0] = {2, K >= 2048, 256, 128, 16, {0.877, 0.938, 0.938, 0.938, 0.939, 0.940}};
     // a step of at most 128 terms added onto an old C is bound by C's traffic: 64 x 128 tiles measure
     // 65.2 % of peak at 8192 x 8192 x 128 against 62.4 on 128 x 128
     const bool thin_acc64 = acc && K <= 128;
