@@ -122,11 +122,11 @@ def test_ttm_mode0_wide_big_tiles(lib, oracle, dtype, kind):
                                      (1028, 60, 70, 4096), (1024, 64, 64, 4200)])
 def test_ttm_mode0_ragged_edge_tiles(lib, oracle, dtype, kind, I, J, K, R):
     """mode 0 with R and J*K that are not whole tiles and a contracted extent with trailing terms:
-    the transposed-left-operand kernels in their edge-clamping form (128 x 256 binary32 tiles; 128 x 128
-    and 256 x 128 binary64 tiles); the last two shapes run as two launches in
+    the transposed-left-operand kernels in their edge-clamping form (128 x 256 and 128 x 128 binary32 tiles;
+    128 x 128 binary64 tiles); the last two shapes run as two launches in
     binary32, cut along the columns and along the rows.  Some j-slices are checked in full."""
     want = {(200, 4080): ((128, 128, 16), (128, 128, 16)), (1028, 4000): ((128, 256, 16), (128, 128, 16)),
-            (4100, 4000): ((128, 256, 16), (256, 128, 16)), (520, 4000): ((128, 256, 16), (128, 128, 16)),
+            (4100, 4000): ((128, 256, 16), (128, 128, 16)), (520, 4000): ((128, 256, 16), (128, 128, 16)),
             (1028, 4096): ((128, 256, 16), None),
             (1024, 4200): ((128, 256, 16), None)}[(I, R)][int(dtype == np.float64)]
     plan = lib.gemm_plan(int(dtype == np.float64), True, R, J * K, I)
