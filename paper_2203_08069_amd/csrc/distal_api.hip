@@ -155,8 +155,8 @@ int launch_fill(T *out, int64_t rows, int64_t cols, int64_t ld, hipStream_t stre
 // not by the caller: the result does not depend on it (every output sums its terms in the same
 // order whichever wavefront owns it), only the speed does.  A grid that gives a compute unit one
 // tile or two leaves its SIMDs with one wavefront each unless the tile is cut into more of them:
-// binary64 128 x 128 on sixteen wavefronts instead of eight measures 90.8 against 88.8 % of peak at
-// 256 tiles, 91.2 against 93.6 at 512; binary64 64 x 64 on eight instead of four 74.2 against 64.1
+// binary64 128 x 128 on sixteen wavefronts of 32 x 32 instead of eight of 32 x 64 measures 92.3
+// against 88.8 % of peak at 256 tiles (sixteen of 16 x 64: 90.8), 91.2 against 93.6 at 512; binary64 64 x 64 on eight instead of four 74.2 against 64.1
 // at 1024^3 (256 tiles), level from 600 tiles on.  The binary64 128 x 64 and 64 x 128 tiles run on
 // eight wavefronts of 32 x 32 at every grid size (4096^2 x 2048: 93.5 against 88.8 and 94.9
 // against 92.4 on four).  In binary32 a wavefront of 32 x 32 would own a single block of the
@@ -184,7 +184,7 @@ int launch_by_id(int id, const ContractArgs<T> &a, int64_t batch, hipStream_t st
         if constexpr (sizeof(T) == 4) {
             return launch_tiles<T, 128, 128, 16, 4, 2, TA, true>(a, batch, stream);
         } else {
-            if (tiles(128, 128) <= 256) return launch_tiles<T, 128, 128, 16, 8, 2, TA>(a, batch, stream);
+            if (tiles(128, 128) <= 256) return launch_tiles<T, 128, 128, 16, 4, 4, TA>(a, batch, stream);
             return launch_tiles<T, 128, 128, 16, 4, 2, TA>(a, batch, stream);
         }
     case 5:
