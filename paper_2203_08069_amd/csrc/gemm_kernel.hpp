@@ -8,7 +8,10 @@
 //            (BM/WAVES_M) x (BN/WAVES_N) sub-tile held in MFMA accumulators
 //   k-loop : BK-deep slabs of both operands, global -> registers -> LDS, two LDS
 //            buffers, one barrier per slab; the next slab's global loads are in
-//            flight while the current one is multiplied
+//            flight while the current one is multiplied (buffer loads: the slab's
+//            base in scalar registers, a fixed 32-bit offset per lane)
+//   MFMA   : binary64 16x16x4; binary32 32x32x2 on the large tiles and 16x16x4 (FINE)
+//            on tiles up to 128 x 128, which are cut into eight wavefronts
 //   two kernels: contract_kernel checks bounds and alignment per tile and serves any
 //            shape; contract_fast_kernel assumes whole aligned tiles and has a
 //            straight-line k-loop
