@@ -314,6 +314,20 @@ def main():
                     hA, hB = h(Av[idx]), h(Bv)
                     baseline(r, lambda: oracle.gemm(hA, hB), lambda: h(Cv[idx]), 2.0 * 8 * N * K, "GFLOP/s",
                              "8 evenly spaced rows of C")
+            # a small output with a long contracted index (the operands viewed as 512 x 131072 and
+            # 131072 x 512): 64 tiles for 256 compute units unless the product is cut along k
+            Mt, Kt = 512, n * n // 512
+            At, Bt, Ct = A.view(Mt, Kt), B.view(Kt, Mt), C[:Mt, :Mt]
+            for tag, fn in (("tallk", lambda: binding.distal_gemm(At, Bt, Ct)), ("tallk_ws", lambda: binding.distal_gemm_ws(At, Bt, Ct))):
+                r = finish(f"{name}_{tag}",
+                           f"C = A B, M=N={Mt}, K={Kt}, {dt}" + (", cut along k with scratch memory (distal_gemm_ws)" if tag.endswith("ws") else ""),
+                           dt, fn, 2.0 * Mt * Mt * Kt, np.dtype(npdt).itemsize * (2.0 * Mt * Kt + Mt * Mt), "mfma")
+                if cpu:
+                    idx = torch.from_numpy(np.linspace(0, Mt - 1, 4).astype(np.int64)).to(dev)
+                    hA, hB = h(At[idx]), h(Bt)
+                    baseline(r, lambda: oracle.gemm(hA, hB), lambda: h(Ct[idx]), 2.0 * 4 * Mt * Kt, "GFLOP/s",
+                             "4 evenly spaced rows of C")
+                    del hA, hB
         del A, B, C
 
     # ---------------------------------------------------------------- TTV + innerprod (configs[2]), all modes, both dtypes

@@ -195,6 +195,28 @@ int distal_gemm_tiled(distal_dtype dt, int transposed_left, int bm, int bn, int6
                       int accumulate, void *stream);
 
 /*
+ * distal_gemm with scratch memory from the caller, for products whose output is small and whose
+ * contracted index is long: such a product has fewer tiles than the part has compute units,
+ * whatever the tile.  It is cut along k into parts - the way the three-dimensional schedules of
+ * the matrix-multiplication case study (Johnson's algorithm, the 2.5D and COSMA schedules) cut
+ * the k loop over processors and reduce - which run as one batch into M x N slabs of the
+ * workspace; a second kernel adds the slabs in the order of k and then onto C, so the result is
+ * a function of the extents only (it differs in rounding from distal_gemm's, which sums each
+ * output in one run of k).
+ *   distal_gemm_workspace_bytes(dt, M, N, K): bytes of workspace distal_gemm_ws needs for these
+ *   extents; 0 where the product is not cut (at least 128 tiles, or K < 2048, or invalid
+ *   arguments): distal_gemm_ws then is distal_gemm and ignores the workspace.
+ *   workspace: DEVICE pointer, 256-byte aligned, at least that many bytes, distinct from the
+ *   operands; its contents on entry do not matter, on return they are unspecified.
+ * Other arguments, ownership and errors as distal_gemm; DISTAL_ERR_WORKSPACE for a missing, small
+ * or misaligned workspace when one is needed.
+ */
+int distal_gemm_ws(distal_dtype dt, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
+                   const void *B, int64_t ldb, void *C, int64_t ldc, int accumulate,
+                   void *workspace, size_t workspace_bytes, void *stream);
+size_t distal_gemm_workspace_bytes(distal_dtype dt, int64_t M, int64_t N, int64_t K);
+
+/*
  * Host-only query (no device work): how the library runs C = A * B with these extents (K >= 16).
  * Bases and leading dimensions need no alignment.  What the plan covers is the part of the
  * output whose 16-byte pieces do not straddle an edge: all but the last N % (16 / sizeof dt)

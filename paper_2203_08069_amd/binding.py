@@ -28,6 +28,7 @@ EXPORTS = (
     "distal_ttv_mode", "distal_ttm_mode", "distal_mttkrp_mode", "distal_mttkrp_mode_workspace_bytes",
     "distal_mttkrp_workspace_bytes", "distal_innerprod_workspace_bytes", "distal_gemm_plan",
     "distal_status_string", "distal_version", "distal_innerprod_noalloc", "distal_gemm_tiled",
+    "distal_gemm_ws", "distal_gemm_workspace_bytes",
 )
 
 
@@ -55,6 +56,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.distal_gemm.argtypes = [ci, i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, vp]
     lib.distal_gemm_tiled.argtypes = [ci, ci, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, vp]
     lib.distal_gemm_tiled.restype = ci
+    lib.distal_gemm_ws.argtypes = [ci, i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, vp, sz, vp]
+    lib.distal_gemm_ws.restype = ci
+    lib.distal_gemm_workspace_bytes.argtypes = [ci, i64, i64, i64]
+    lib.distal_gemm_workspace_bytes.restype = sz
     lib.distal_ttm.argtypes = [ci, i64, i64, i64, i64, vp, vp, vp, vp]
     lib.distal_ttv_mode.argtypes = [ci, ci, i64, i64, i64, vp, vp, vp, vp]
     lib.distal_ttv_mode.restype = ci
@@ -188,6 +193,29 @@ def _workspace(device, nbytes: int):
 
 
 # ------------------------------------------------------------------ the five calls
+
+def gemm_workspace_bytes(dtype_code: int, M: int, N: int, K: int) -> int:
+    """Bytes of scratch distal_gemm_ws needs for these extents (0: the product is not cut along k)."""
+    return int(load_library().distal_gemm_workspace_bytes(dtype_code, M, N, K))
+
+
+def distal_gemm_ws(A, B, C, accumulate: bool = False, workspace=None):
+    """distal_gemm with scratch memory: a small output with a long contracted index is cut along k
+    (see gemm_workspace_bytes); without a `workspace` the binding's scratch of the current stream is used."""
+    dt = _same(A, B, C)
+    lda, ldb, ldc = _ld(A, "A"), _ld(B, "B"), _ld(C, "C")
+    M, K = A.shape
+    K2, N = B.shape
+    if K != K2 or tuple(C.shape) != (M, N):
+        raise ValueError("shapes do not match C(M,N) = A(M,K) B(K,N)")
+    need = gemm_workspace_bytes(dt, M, N, K)
+    ws = workspace if workspace is not None else _workspace(A.device, need)
+    with _torch().cuda.device(A.device):
+        rc = load_library().distal_gemm_ws(dt, M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc,
+                                           int(bool(accumulate)), _ptr(ws), ws.numel() * ws.element_size(), _stream(A))
+    _raise(rc, "distal_gemm_ws")
+    return C
+
 
 def distal_gemm(A, B, C, accumulate: bool = False):
     """C(i,j) = [C(i,j) +] sum_k A(i,k) B(k,j); operands may be row-strided 2-D views."""

@@ -304,6 +304,25 @@ int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
     return rc != DISTAL_OK ? rc : launch_by_id<T, TA>(plan.rest.id, second, batch, stream);
 }
 
+// The product cut along k (plan_split_k): parts of kchunk terms as one batch into the slabs of
+// the scratch W, a shorter last part on its own, then the sum of the slabs onto C.
+template <typename T>
+int gemm_splitk_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B, int64_t ldb, T *C,
+                  int64_t ldc, int accumulate, T *W, const SplitKPlan &p, hipStream_t stream) {
+    const int64_t slab = M * N, whole = K / p.kchunk, rest = K - whole * p.kchunk;   // whole parts, and a shorter last one
+    int rc = gemm_t<T>(M, N, p.kchunk, A, lda, B, ldb, W, N, 0, stream, whole, p.kchunk, p.kchunk * ldb, slab);
+    if (rc != DISTAL_OK) return rc;
+    if (rest > 0) {
+        rc = gemm_t<T>(M, N, rest, A + whole * p.kchunk, lda, B + whole * p.kchunk * ldb, ldb, W + whole * slab, N, 0, stream);
+        if (rc != DISTAL_OK) return rc;
+    }
+    int64_t blocks = (slab + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(splitk_sum_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream, (const T *)W, (int)p.parts, M, N, C,
+                       ldc, accumulate ? 1 : 0);
+    return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
+}
+
 int check_dtype(int dt) { return (dt == DISTAL_F32 || dt == DISTAL_F64) ? DISTAL_OK : DISTAL_ERR_DTYPE; }
 
 size_t elem_size(int dt) { return dt == DISTAL_F64 ? 8 : 4; }
@@ -576,7 +595,7 @@ bool tensor_elems(int64_t I, int64_t J, int64_t K, int64_t *n) {
 
 extern "C" {
 
-int distal_version(void) { return 400; }   // 0.4.0
+int distal_version(void) { return 500; }   // 0.5.0
 
 const char *distal_status_string(int status) {
     switch (status) {
@@ -612,6 +631,39 @@ int distal_gemm(distal_dtype dt, int64_t M, int64_t N, int64_t K, const void *A,
                               accumulate, s);
     return gemm_t<float>(M, N, K, (const float *)A, lda, (const float *)B, ldb, (float *)C, ldc,
                          accumulate, s);
+}
+
+size_t distal_gemm_workspace_bytes(distal_dtype dt, int64_t M, int64_t N, int64_t K) {
+    int64_t t;
+    if (check_dtype(dt) != DISTAL_OK || M <= 0 || N <= 0 || K <= 0 || !mul_ok(M, N, &t)) return 0;
+    const SplitKPlan p = plan_split_k(dt == DISTAL_F64, M, N, K);
+    if (p.parts < 2 || !mul_ok(t, p.parts, &t) || t > (int64_t)(SIZE_MAX / 16)) return 0;
+    return (size_t)t * elem_size(dt);
+}
+
+int distal_gemm_ws(distal_dtype dt, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
+                   int64_t ldb, void *C, int64_t ldc, int accumulate, void *workspace, size_t workspace_bytes,
+                   void *stream) {
+    const size_t need = distal_gemm_workspace_bytes(dt, M, N, K);
+    if (need == 0) return distal_gemm(dt, M, N, K, A, lda, B, ldb, C, ldc, accumulate, stream);
+    // need > 0: the extents are positive and their products fit; the other checks of distal_gemm
+    if (lda < K || ldb < N || ldc < N) return DISTAL_ERR_STRIDE;
+    int64_t t;
+    if ((M > 1 && (!mul_ok(M, lda, &t) || !mul_ok(M, ldc, &t) || t > INT64_MAX / 8)) ||
+        (K > 1 && (!mul_ok(K, ldb, &t) || t > INT64_MAX / 8)))
+        return DISTAL_ERR_SHAPE;
+    if (!A || !B || !C) return DISTAL_ERR_NULL;
+    if (C == A || C == B) return DISTAL_ERR_ALIAS;
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) % kWorkspaceAlign) != 0)
+        return DISTAL_ERR_WORKSPACE;
+    if (workspace == A || workspace == B || workspace == C) return DISTAL_ERR_ALIAS;
+    const SplitKPlan p = plan_split_k(dt == DISTAL_F64, M, N, K);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dt == DISTAL_F64)
+        return gemm_splitk_t<double>(M, N, K, (const double *)A, lda, (const double *)B, ldb, (double *)C, ldc, accumulate,
+                                     (double *)workspace, p, s);
+    return gemm_splitk_t<float>(M, N, K, (const float *)A, lda, (const float *)B, ldb, (float *)C, ldc, accumulate,
+                                (float *)workspace, p, s);
 }
 
 int distal_gemm_tiled(distal_dtype dt, int transposed_left, int bm, int bn, int64_t M, int64_t N, int64_t K,

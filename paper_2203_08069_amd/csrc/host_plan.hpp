@@ -173,6 +173,41 @@ inline ProductPlan plan_product(bool f64, bool ta, int64_t M, int64_t N, int64_t
     return plan;
 }
 
+// A product with a small output and a long contracted index gives fewer tiles than the part has
+// compute units, however the tiles are chosen.  With scratch memory from the caller such a product
+// is cut along k into `parts` products of `kchunk` terms each (the last one shorter), run as one
+// batch into `parts` M x N slabs of the scratch, which a second kernel adds up in the order of k.
+// The number of parts is the one with the least estimated time among a fixed list: the batch on
+// the tile the table picks for it, plus the second kernel's traffic over the slabs at 5 TB/s, plus
+// 3 us per launch; the product is cut only where that beats the single launch by a tenth.
+// parts == 1: not cut (also whenever at least half the compute units have a tile already, or
+// the parts would be shallower than 1024 terms).  kchunk is a multiple of 32, so every part keeps
+// the alignment of the whole.  A function of the extents only.
+struct SplitKPlan { int64_t parts, kchunk; };
+
+inline SplitKPlan plan_split_k(bool f64, int64_t M, int64_t N, int64_t K) {
+    SplitKPlan best{1, K};
+    if (M <= 0 || N <= 0 || K < 2048) return best;
+    const TilePick whole = pick_tile(f64, false, M, N, K, 1);
+    int64_t tiles, outs;
+    if (!mul_ok((M + whole.bm - 1) / whole.bm, (N + whole.bn - 1) / whole.bn, &tiles) || tiles > kComputeUnits / 2) return best;
+    if (!mul_ok(M, N, &outs) || outs > ((int64_t)1 << 40)) return best;
+    const double per_cu = (f64 ? 78.6e12 : 157.3e12) / (double)kComputeUnits, esz = f64 ? 8.0 : 4.0;
+    auto seconds = [&](double cost, int64_t depth) { return cost * 2.0 * (double)depth / per_cu; };
+    double best_time = seconds(whole.cost, K) * 0.9;
+    const int options[] = {2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64};
+    for (int want : options) {
+        if (want > K / 1024) break;
+        const int64_t kchunk = ((K + want - 1) / want + 31) / 32 * 32;
+        const int64_t parts = (K + kchunk - 1) / kchunk;
+        if (parts < 2) continue;
+        const TilePick t = pick_tile(f64, false, M, N, kchunk, parts);
+        const double time = seconds(t.cost, kchunk) + (double)(parts + 1) * (double)outs * esz / 5e12 + 2 * 3e-6;
+        if (time < best_time) { best_time = time; best = SplitKPlan{parts, kchunk}; }
+    }
+    return best;
+}
+
 // Whether unsigned 32-bit byte offsets from a tile's first element reach every 16-byte piece of
 // one slab of it: the straight-line contraction kernels address a slab that way (the slab's base
 // is a 64-bit scalar).  The farthest piece starts at (rows of the slab - 1) x leading dimension +

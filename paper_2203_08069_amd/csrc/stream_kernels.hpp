@@ -664,6 +664,22 @@ gemm_fringe_cols_ta_kernel(const T *__restrict__ A, int64_t lda, const T *__rest
     }
 }
 
+// C(m, n) = [C(m, n) +] W(0, m, n) + W(1, m, n) + ... + W(parts - 1, m, n): the partial products of
+// a matrix product cut along k, dense M x N slabs, added in the order of k (so the result is a
+// function of the extents only) and only then onto the old C.
+template <typename T>
+__global__ void __launch_bounds__(256)
+splitk_sum_kernel(const T *__restrict__ W, int parts, int64_t M, int64_t N, T *__restrict__ C, int64_t ldc,
+                  int accumulate) {
+    const int64_t n = M * N;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < n; e += (int64_t)gridDim.x * 256) {
+        T s = W[e];
+        for (int p = 1; p < parts; ++p) s += W[(int64_t)p * n + e];
+        T *c = C + (e / N) * ldc + (e % N);
+        *c = accumulate ? *c + s : s;
+    }
+}
+
 // Row-strided fill, used where an empty sum must still define its output.
 template <typename T>
 __global__ void __launch_bounds__(256)

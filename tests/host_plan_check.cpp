@@ -154,6 +154,21 @@ int main() {
     CHECK(!slab_offsets_fit(4, false, 256, 128, 16, 8396800, 128), "rows 8.5e9 bytes apart do not");
     CHECK(!slab_offsets_fit(8, true, 128, 128, 16, INT64_MAX, 128), "overflowing product");
 
+    // cuts along k: the parts cover K exactly once, only the last may be shorter, every part keeps
+    // 32-element alignment and at least 1024 terms, and there are at most 64 of them
+    for (int it = 0; it < 300000; ++it) {
+        const bool f64 = rnd() & 1;
+        const int64_t M = extent((int64_t)1 << 24), N = extent((int64_t)1 << 24), K = extent((int64_t)1 << 40);
+        const SplitKPlan p = plan_split_k(f64, M, N, K);
+        CHECK(p.parts >= 1 && p.parts <= 64, "parts %" PRId64, p.parts);
+        if (p.parts == 1) { CHECK(p.kchunk == K, "uncut product with a chunk"); continue; }
+        CHECK(p.kchunk % 32 == 0 && p.kchunk >= 1024, "chunk %" PRId64, p.kchunk);
+        CHECK((p.parts - 1) * p.kchunk < K && K <= p.parts * p.kchunk, "parts %" PRId64 " x %" PRId64 " against K %" PRId64, p.parts, p.kchunk, K);
+        CHECK(((M + 63) / 64) * ((N + 63) / 64) >= 1 && K >= 2048, "cut of a shallow product");
+    }
+    CHECK(plan_split_k(true, 512, 512, 8192).parts == 8 && plan_split_k(true, 512, 512, 8192).kchunk == 1024, "512 x 512 x 8192");
+    CHECK(plan_split_k(true, 1024, 1024, 8192).parts == 1, "a tile per compute unit is not cut");
+
     // MTTKRP plans: extents whose product stays below 2^60, as the entry point demands
     for (int it = 0; it < 300000; ++it) {
         const int dt = (int)(rnd() & 1), mode = (int)(rnd() % 3);

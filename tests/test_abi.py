@@ -349,6 +349,38 @@ def test_gemm_tiled_argument_errors(lib):
     assert f(1, 1, 128, 64, 0, 64, 64, None, 64, None, 64, None, 64, 0, None) == 0   # empty output: nothing to do
 
 
+def test_gemm_ws_workspace_sizes_and_argument_errors(lib):
+    """The product that is cut along k: which extents are cut (and into how many M x N slabs), and
+    the host-side checks of the call; extents that are not cut behave as distal_gemm and ignore
+    the workspace."""
+    F32, F64 = 0, 1
+    wb, f = lib.distal_gemm_workspace_bytes, lib.distal_gemm_ws
+    assert wb(F64, 512, 512, 8192) == 8 * 512 * 512 * 8            # 64 tiles of 64 x 64: eight parts of 1024
+    assert wb(F64, 512, 512, 65536) == 32 * 512 * 512 * 8          # deep enough for 16 tiles of 128 x 128 in 32 parts
+    assert wb(F32, 256, 256, 1 << 20) == 64 * 256 * 256 * 4        # the cap of 64 parts
+    assert wb(F64, 64, 64, 1 << 20) == 64 * 64 * 64 * 8            # one tile: 64 parts
+    assert wb(F64, 100, 100, 3000) == 2 * 100 * 100 * 8            # parts stay at least 1024 deep
+    assert wb(F64, 1024, 1024, 8192) == 0                          # every compute unit has a tile already
+    assert wb(F64, 512, 512, 2047) == 0 and wb(F64, 512, 512, 0) == 0 and wb(F64, 0, 512, 8192) == 0
+    assert wb(7, 512, 512, 8192) == 0 and wb(F64, -1, 512, 8192) == 0
+    a, b, c, w = (P(FAKE + 256 * i) for i in range(4))
+    big = 1 << 40
+    cut = (512, 512, 8192)
+    assert f(F64, *cut, a, 8192, b, 512, c, 512, 0, None, 0, None) == 6
+    assert f(F64, *cut, a, 8192, b, 512, c, 512, 0, w, wb(F64, *cut) - 1, None) == 6
+    assert f(F64, *cut, a, 8192, b, 512, c, 512, 0, P(FAKE + 8), big, None) == 6          # misaligned
+    assert f(F64, *cut, a, 8192, b, 512, c, 512, 0, a, big, None) == 5
+    assert f(F64, *cut, a, 8192, b, 512, a, 512, 0, w, big, None) == 5
+    assert f(F64, *cut, None, 8192, b, 512, c, 512, 0, w, big, None) == 1
+    assert f(F64, *cut, a, 8191, b, 512, c, 512, 0, w, big, None) == 4
+    assert f(F64, *cut, a, 8192, b, 511, c, 512, 0, w, big, None) == 4
+    assert f(9, *cut, a, 8192, b, 512, c, 512, 0, w, big, None) == 3
+    # not cut: distal_gemm's checks, no workspace needed
+    assert f(F64, 64, 64, -1, a, 64, b, 64, c, 64, 0, None, 0, None) == 2
+    assert f(F64, 64, 64, 64, a, 63, b, 64, c, 64, 0, None, 0, None) == 4
+    assert f(F64, 0, 64, 64, None, 64, None, 64, None, 64, 0, None, 0, None) == 0
+
+
 def test_probe_library_exports_and_argument_errors():
     """The measurement aid (include/distal_probe.h) is a library of its own: it loads, exports what
     its header declares and validates on the host before launching."""

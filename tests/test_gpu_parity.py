@@ -138,6 +138,57 @@ def test_gemm_tiled_wavefront_counts(lib, oracle, dtype, tile, M, N, what, ta):
     assert np.array_equal(U.host(C), got * 2), what
 
 
+# small outputs with a long contracted index: cut along k into (parts, the last one shorter or not)
+SPLITK_SHAPES = [(512, 512, 8192), (100, 100, 3000), (300, 200, 5000), (300, 200, 5001), (64, 72, 70000), (130, 31, 4099)]
+
+
+@pytest.mark.parametrize("dtype", DT)
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("M,N,K", SPLITK_SHAPES)
+def test_gemm_ws_cut_along_k(lib, oracle, dtype, kind, M, N, K):
+    """distal_gemm_ws on products it cuts along k: every element against the oracle; operands are
+    views one column off alignment inside larger matrices, C a block between sentinels; then
+    accumulated on top (the parts are summed first and added to the old C once)."""
+    code = int(dtype == np.float64)
+    need = lib.gemm_workspace_bytes(code, M, N, K)
+    assert need > 0 and need % (M * N * np.dtype(dtype).itemsize) == 0
+    import torch
+    A, B = U.gen(900 + M, 0, (M, K), dtype, kind), U.gen(900 + M, 1, (K, N), dtype, kind)
+    bigA, bigB = np.zeros((M, K + 5), dtype=dtype), np.zeros((K, N + 3), dtype=dtype)
+    bigA[:, 1:1 + K], bigB[:, 1:1 + N] = A, B
+    bigC = np.full((M + 2, N + 4), 77.0, dtype=dtype)
+    dA, dB, dC = U.dev(bigA), U.dev(bigB), U.dev(bigC)
+    view = dC[1:1 + M, 2:2 + N]
+    ws = torch.full((need + 256,), 0xAB, dtype=torch.uint8, device="cuda:0")      # whatever it held before
+    lib.distal_gemm_ws(dA[:, 1:1 + K], dB[:, 1:1 + N], view, workspace=ws[:need])
+    out = U.host(dC)
+    got = out[1:1 + M, 2:2 + N]
+    ref = oracle.gemm(A, B)
+    compare(got, ref, dtype, kind, K, lambda: oracle.gemm(np.abs(A), np.abs(B)))
+    mask = np.ones_like(bigC, dtype=bool)
+    mask[1:1 + M, 2:2 + N] = False
+    assert np.all(out[mask] == 77.0)
+    assert bool((ws[need:] == 0xAB).all())                                          # nothing past the stated size
+    lib.distal_gemm_ws(dA[:, 1:1 + K], dB[:, 1:1 + N], view, accumulate=True)        # the binding's own scratch
+    out2 = U.host(dC)
+    if kind == inputs.SMALLINT or dtype == np.float64:
+        assert np.array_equal(out2[1:1 + M, 2:2 + N], got * 2)
+    else:
+        U.assert_close(out2[1:1 + M, 2:2 + N], got.astype(np.float64) * 2, dtype, K)
+    assert np.all(out2[mask] == 77.0)
+
+
+def test_gemm_ws_uncut_is_gemm(lib):
+    """Extents that are not cut: the same bits as distal_gemm, no workspace touched."""
+    import torch
+    A, B = U.dev(U.gen(31, 0, (700, 900), np.float32)), U.dev(U.gen(31, 1, (900, 500), np.float32))
+    assert lib.gemm_workspace_bytes(0, 700, 500, 900) == 0
+    C1, C2 = empty((700, 500), np.float32), empty((700, 500), np.float32)
+    lib.distal_gemm(A, B, C1)
+    lib.distal_gemm_ws(A, B, C2)
+    assert torch.equal(C1, C2)
+
+
 def test_gemm_tiled_rejects_unknown_tiles(lib):
     import torch
     A = torch.zeros(64, 64, dtype=torch.float64, device="cuda:0")
