@@ -218,11 +218,11 @@ size_t distal_gemm_workspace_bytes(distal_dtype dt, int64_t M, int64_t N, int64_
 
 /*
  * Host-only query (no device work): how the library runs C = A * B with these extents (K >= 16).
- * Bases and leading dimensions need no alignment.  What the plan covers is the part of the
- * output whose 16-byte pieces do not straddle an edge: all but the last N % (16 / sizeof dt)
- * columns (those few run as a streaming matrix-vector kernel) and, with a transposed left
- * operand, all but the last M % (16 / sizeof dt) rows (bounds-checked kernel); pass the
- * extents of that part.  K < 16 takes the bounds-checked 128 x 128 kernel.  TTM is such a
+ * Bases and leading dimensions need no alignment.  What the plan covers is the output without
+ * the columns and rows the library peels off: the last distal_gemm_peeled_columns(...) columns
+ * (a streaming matrix-vector kernel) and, with a transposed left operand, the last
+ * M % (16 / sizeof dt) rows (bounds-checked kernel); pass the extents of that part.
+ * K < 16 takes the bounds-checked 128 x 128 kernel.  TTM is such a
  * product: mode 2 is M = I*J, N = L; mode 0 is transposed_left with M = R, N = J*K, K = I;
  * mode 1 the same with batch = I, N = K, K = J.  accumulate as in distal_gemm: a product added
  * onto an old C takes its largest tiles from deeper K on (the tensor calls overwrite: 0).
@@ -236,6 +236,19 @@ size_t distal_gemm_workspace_bytes(distal_dtype dt, int64_t M, int64_t N, int64_
  */
 int distal_gemm_plan(distal_dtype dt, int transposed_left, int64_t M, int64_t N, int64_t K, int64_t batch,
                      int accumulate, int tile[3], int *split, int64_t *cut, int rest_tile[3]);
+
+/*
+ * Host-only query: how many trailing columns of C = A * B the library computes apart from the
+ * tiled launches.  0 when N is a multiple of 16 / sizeof dt.  Otherwise rows of B end inside a
+ * 16-byte piece, and the library either takes them as they are inside the tiled kernels (0:
+ * narrow outputs, where a second pass over the left operand would double the time) or peels
+ * N % (16 / sizeof dt) columns off to a streaming kernel that reads the left operand once more
+ * (wide outputs, where that pass costs a percent and the rest then runs on whole pieces); N
+ * itself when N is narrower than one piece.  A function of the arguments only; -1 for invalid
+ * arguments.  Results do not depend on it beyond rounding order in binary32.
+ */
+int64_t distal_gemm_peeled_columns(distal_dtype dt, int transposed_left, int64_t M, int64_t N, int64_t K,
+                                   int64_t batch, int accumulate);
 
 /* Scratch sizes for the calls that take a workspace (0 for invalid arguments). */
 size_t distal_mttkrp_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L);

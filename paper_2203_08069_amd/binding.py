@@ -28,7 +28,7 @@ EXPORTS = (
     "distal_ttv_mode", "distal_ttm_mode", "distal_mttkrp_mode", "distal_mttkrp_mode_workspace_bytes",
     "distal_mttkrp_workspace_bytes", "distal_innerprod_workspace_bytes", "distal_gemm_plan",
     "distal_status_string", "distal_version", "distal_innerprod_noalloc", "distal_gemm_tiled",
-    "distal_gemm_ws", "distal_gemm_workspace_bytes",
+    "distal_gemm_ws", "distal_gemm_workspace_bytes", "distal_gemm_peeled_columns",
 )
 
 
@@ -79,6 +79,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     ip = ctypes.POINTER(ctypes.c_int)
     lib.distal_gemm_plan.argtypes = [ci, ci, i64, i64, i64, i64, ci, ip, ip, ctypes.POINTER(ctypes.c_int64), ip]
     lib.distal_gemm_plan.restype = ci
+    lib.distal_gemm_peeled_columns.argtypes = [ci, ci, i64, i64, i64, i64, ci]
+    lib.distal_gemm_peeled_columns.restype = i64
     for name in ("distal_gemm", "distal_ttm", "distal_mttkrp", "distal_ttv", "distal_innerprod",
                  "distal_ttm_mode", "distal_mttkrp_mode", "distal_version"):
         getattr(lib, name).restype = ci
@@ -365,6 +367,14 @@ def gemm_plan(dtype_code: int, transposed_left: bool, M: int, N: int, K: int, ba
                                          tile, ctypes.byref(split), ctypes.byref(cut), rest)
     _raise(rc, "distal_gemm_plan")
     return tuple(tile), split.value, cut.value, tuple(rest)
+
+
+def gemm_peeled_columns(dtype_code: int, transposed_left: bool, M: int, N: int, K: int, batch: int = 1,
+                        accumulate: bool = False) -> int:
+    """Trailing columns of the product that run in the streaming kernel instead of the tiled
+    launches (host-only query); -1 for invalid arguments."""
+    return int(load_library().distal_gemm_peeled_columns(dtype_code, int(bool(transposed_left)), M, N, K, batch,
+                                                         int(bool(accumulate))))
 
 
 def gemm_tile(dtype_code: int, transposed_left: bool, M: int, N: int, K: int, batch: int = 1, accumulate: bool = False):

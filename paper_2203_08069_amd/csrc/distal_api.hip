@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <type_traits>
 #include <algorithm>
 #include <cstdint>
 #include <limits>
@@ -46,6 +47,17 @@ bool allow_lds(Kern kern, int bytes, std::atomic<bool> (&done)[kMaxDevices]) {
 constexpr int64_t kMaxGridY = 65535;
 
 // One launch per run of at most kMaxGridY problems of the batch (blockIdx.y picks the problem).
+// One launch of one form of the straight-line kernel (each form raises its LDS limit once per device).
+template <typename T, int BM, int BN, int BK, int WM, int WN, bool TA, int EDGE, bool INIT, bool FINE, bool SHIFT>
+bool launch_fast_form(const dim3 &grid, const ContractArgs<T> &a, hipStream_t stream) {
+    typedef ContractCfg<T, BM, BN, BK, WM, WN, TA, FINE> Cfg;
+    static std::atomic<bool> done[kMaxDevices];
+    auto kern = contract_fast_kernel<T, BM, BN, BK, WM, WN, TA, EDGE, INIT, FINE, SHIFT>;
+    if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return false;
+    hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
+    return true;
+}
+
 // KIND: the guarded kernel, the straight-line kernel on whole tiles, or its edge-clamping form.
 enum { kGuarded = 0, kWhole = 1, kEdge = 2, kEdgeK = 3 };
 template <typename T, int BM, int BN, int BK, int WM, int WN, int KIND, bool TA, bool FINE = false>
@@ -69,21 +81,18 @@ int launch_contract(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
             // 64 x 128 tiles: 59 -> 63 % of peak).  Deeper products and larger tiles add in the epilogue:
             // there the up-front form measured 1..4 % slower at every depth.
             constexpr bool kInitForm = sizeof(T) == 4 && BM * BN <= 128 * 128;
-            bool launched = false;
-            if constexpr (kInitForm) {
-                if (a.accumulate && a.K <= 256) {
-                    static std::atomic<bool> done_acc[kMaxDevices];
-                    auto kern = contract_fast_kernel<T, BM, BN, BK, WM, WN, TA, EDGE, true, FINE>;
-                    if (!allow_lds(kern, Cfg::LDS_BYTES, done_acc)) return DISTAL_ERR_LAUNCH;
-                    hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
-                    launched = true;
-                }
-            }
-            if (!launched) {
-                auto kern = contract_fast_kernel<T, BM, BN, BK, WM, WN, TA, EDGE, false, FINE>;
-                if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
-                hipLaunchKernelGGL(kern, grid, dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
-            }
+            // rows of B that end inside a 16-byte piece take the edge forms that shift the last piece
+            const bool shift = EDGE != 0 && a.N % (16 / (int)sizeof(T)) != 0;
+            const bool init = kInitForm && a.accumulate && a.K <= 256;
+            // (a form the tile has no use for collapses onto the plain one at compile time)
+            auto form = [&](auto init_c, auto shift_c) {
+                constexpr bool I = decltype(init_c)::value && kInitForm, S = decltype(shift_c)::value && EDGE != 0;
+                return launch_fast_form<T, BM, BN, BK, WM, WN, TA, EDGE, I, FINE, S>(grid, a, stream);
+            };
+            const std::true_type yes{};
+            const std::false_type no{};
+            const bool ok = init ? (shift ? form(yes, yes) : form(yes, no)) : (shift ? form(no, yes) : form(no, no));
+            if (!ok) return DISTAL_ERR_LAUNCH;
         }
         if (hipGetLastError() != hipSuccess) return DISTAL_ERR_LAUNCH;
         a.A += count * a.batch_a;
@@ -104,6 +113,8 @@ int launch_tiles(ContractArgs<T> a, int64_t batch, hipStream_t stream) {
     // leading dimensions so large that a slab's rows lie more than 4 GiB apart: the straight-line
     // kernel's 32-bit offsets do not reach, the bounds-checked kernel addresses with pointers
     if (!slab_offsets_fit((int64_t)sizeof(T), TA, BM, BN, BK, a.lda, a.ldb)) return launch_contract<T, 128, 128, 16, 2, 2, kGuarded, TA>(a, batch, stream);
+    // a row of B that ends inside a piece is fetched from column N - VEC: that column must exist
+    if (a.N % VEC != 0 && a.N + a.n_before < VEC) return launch_contract<T, 128, 128, 16, 2, 2, kGuarded, TA>(a, batch, stream);
     const int64_t k_main = a.K / BK * BK, k_tail = a.K - k_main;
     if (k_tail == 0)
         return (a.M % BM == 0 && a.N % BN == 0) ? launch_contract<T, BM, BN, BK, WM, WN, kWhole, TA, FINE>(a, batch, stream)
@@ -249,11 +260,13 @@ int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
     a.b_vec_ok = aligned16(B) && ldb % VEC == 0 && stride_b % VEC == 0;
     a.c_vec_ok = aligned16(C) && ldc % VEC == 0 && stride_c % VEC == 0;
     if (K < 16) return launch_contract<T, 128, 128, 16, 2, 2, kGuarded, TA>(a, batch, stream);
-    // The straight-line kernels move 16-byte pieces that must not straddle an edge of an operand
-    // (alignment does not matter: their global accesses are only element-aligned).  The trailing
-    // N % VEC columns - and, with a transposed left operand, the trailing M % VEC rows - are
-    // therefore peeled off: the columns go to a streaming kernel, the rows to the guarded one.
-    const int64_t nfr = N % VEC, mfr = TA ? M % VEC : 0;
+    // The straight-line kernels move 16-byte pieces (alignment does not matter: their global accesses
+    // are only element-aligned).  A row of B that does not end on a piece is either handled inside
+    // them (the last piece is fetched VEC columns before the end, which takes N >= VEC) or its
+    // trailing N % VEC columns go to a streaming kernel, whichever peeled_columns estimates cheaper.
+    // Pieces of a transposed left operand must not straddle its last column: there the trailing
+    // M % VEC rows of C are peeled off to the guarded kernel.
+    const int64_t nfr = peeled_columns(sizeof(T) == 8, TA, M, N, K, batch, accumulate != 0), mfr = TA ? M % VEC : 0;
     const int64_t Nm = N - nfr, Mm = M - mfr;
     if (nfr > 0) {
         int64_t blocks = TA ? (M + 255) / 256 : (M + 31) / 32;
@@ -299,6 +312,7 @@ int gemm_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
         second.N = Nm - plan.cut;
         second.B += plan.cut;
         second.C += plan.cut;
+        second.n_before = plan.cut;
     }
     const int rc = launch_by_id<T, TA>(plan.main.id, first, batch, stream);
     return rc != DISTAL_OK ? rc : launch_by_id<T, TA>(plan.rest.id, second, batch, stream);
@@ -595,7 +609,7 @@ bool tensor_elems(int64_t I, int64_t J, int64_t K, int64_t *n) {
 
 extern "C" {
 
-int distal_version(void) { return 500; }   // 0.5.0
+int distal_version(void) { return 501; }   // 0.5.1
 
 const char *distal_status_string(int status) {
     switch (status) {
@@ -833,6 +847,14 @@ int distal_gemm_plan(distal_dtype dt, int transposed_left, int64_t M, int64_t N,
     *cut = p.cut;
     rest_tile[0] = p.rest.bm; rest_tile[1] = p.rest.bn; rest_tile[2] = p.rest.bk;
     return DISTAL_OK;
+}
+
+int64_t distal_gemm_peeled_columns(distal_dtype dt, int transposed_left, int64_t M, int64_t N, int64_t K, int64_t batch,
+                                   int accumulate) {
+    if (check_dtype(dt) != DISTAL_OK || M <= 0 || N <= 0 || K <= 0 || batch <= 0) return -1;
+    int64_t tiles;
+    if (!mul_ok((M + 127) / 128, (N + 127) / 128, &tiles) || tiles > std::numeric_limits<int>::max()) return -1;
+    return peeled_columns(dt == DISTAL_F64, transposed_left != 0, M, N, K, batch, accumulate != 0);
 }
 
 size_t distal_innerprod_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, int64_t K) {

@@ -98,6 +98,8 @@ struct ContractArgs {
     int tiles_m, tiles_n;
     int a_vec_ok, b_vec_ok, c_vec_ok;   // 16-byte vector access is legal on that operand
     int64_t batch_a, batch_b, batch_c;  // element strides between the problems of a batch (blockIdx.y)
+    int64_t n_before;    // columns of the same rows of B that lie before B (a product that is the right
+                         // part of a wider one): the straight-line kernel may read back into them
 };
 
 // binary32 also has the 16 x 16 x 4 instruction, at the same rate: four times as many blocks per
@@ -426,7 +428,12 @@ contract_kernel(ContractArgs<T> args) {
 // piece that lies past the edge is fetched from the last valid row (or last valid piece of a
 // row) instead, so every load stays in bounds and the rows and columns it feeds hold values
 // that no valid output depends on; the epilogue stores only what lies inside M x N.
-// Pieces must not straddle an edge: N (and M, when TA) a multiple of the 16-byte vector.
+// Pieces must not straddle an edge: N (and M, when TA) a multiple of the 16-byte vector - except
+// in the SHIFT forms of the edge kernels, which take an N that is not (N % VEC != 0, and N - VEC
+// columns or more exist in B's rows counting those before the pointer): the piece that straddles
+// the end of a row of B is fetched VEC columns before the end and shifted in registers, and the
+// last column of C is accessed on its own.  The shift costs the k-loop about 3 %, which is why
+// it is a form of its own.
 // EDGE = 2 also takes K >= BK that is not a multiple of BK (without TA: a multiple of the
 // vector, pieces of A run along k): the trailing terms are one zero-filled slab after the loop.
 // In the other forms K is a multiple of BK.
@@ -440,7 +447,7 @@ contract_kernel(ContractArgs<T> args) {
 // form there only; binary64 shows no gain at any shape and always adds in the epilogue.
 // ---------------------------------------------------------------------------
 template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool TA = false, int EDGE = 0, bool ACC_INIT = false,
-          bool FINE = false>
+          bool FINE = false, bool SHIFT = false>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N >= 8) ? 4 : 2)
 contract_fast_kernel(ContractArgs<T> args) {
     typedef ContractCfg<T, BM, BN, BK, WAVES_M, WAVES_N, TA, FINE> Cfg;
@@ -484,7 +491,9 @@ contract_fast_kernel(ContractArgs<T> args) {
     int a_off[Cfg::A_PER_T], b_off[Cfg::B_PER_T];
     int a_lds[Cfg::A_PER_T], b_lds[Cfg::B_PER_T];
     const char *a_tile = reinterpret_cast<const char *>(args.A + (TA ? m0 : m0 * args.lda));
-    const char *b_tile = reinterpret_cast<const char *>(args.B + n0);
+    // the B offsets count from column nb: n0, or N - VEC where the last tile is narrower than a piece
+    const int64_t nb = (SHIFT && n0 > args.N - VEC) ? args.N - VEC : n0;
+    const char *b_tile = reinterpret_cast<const char *>(args.B + nb);
 #pragma unroll
     for (int p = 0; p < Cfg::A_PER_T; ++p) {
         const int v = tid + p * NT, r = v / ARL, kv = v % ARL;
@@ -499,14 +508,34 @@ contract_fast_kernel(ContractArgs<T> args) {
         }
         a_lds[p] = r * Cfg::LDA_S + kv * VEC;
     }
+    // N that is not a multiple of the vector (the SHIFT forms, which are EDGE forms): the piece that
+    // holds the last N % VEC columns is fetched from column N - VEC like the pieces past the edge,
+    // and on its way to LDS its values move down by n_shift places, so the valid columns sit where
+    // the multiply expects them (what follows them in the piece feeds columns that are never stored).
+    static_assert(!SHIFT || EDGE != 0, "only the edge forms shift");
+    const int n_shift = SHIFT ? (VEC == 2 ? 1 : (int)(VEC - args.N % VEC)) : 0;     // block-uniform, 1 ... VEC - 1
+    bool b_fix[Cfg::B_PER_T];
 #pragma unroll
     for (int p = 0; p < Cfg::B_PER_T; ++p) {
         const int v = tid + p * NT, r = v / (BN / VEC), cv = v % (BN / VEC);
         int64_t n = n0 + cv * VEC;
+        b_fix[p] = SHIFT && n == args.N - args.N % VEC;
         if (EDGE && n > args.N - VEC) n = args.N - VEC;
-        b_off[p] = (int)(unsigned)(((int64_t)r * args.ldb + (n - n0)) * (int64_t)sizeof(T));
+        b_off[p] = (int)(unsigned)(((int64_t)r * args.ldb + (n - nb)) * (int64_t)sizeof(T));
         b_lds[p] = Cfg::A_ELEMS + r * Cfg::LDB_S + cv * VEC;
     }
+    auto b_piece = [&](const vec_t &x, int p) -> vec_t {       // the piece as it goes to LDS
+        if constexpr (!SHIFT) return x;
+        vec_t y = x;                                            // y[e] = x[e + n_shift] where that exists
+        if constexpr (VEC == 2) {
+            y[0] = x[1];
+        } else {
+            y[0] = n_shift == 1 ? x[1] : (n_shift == 2 ? x[2] : x[3]);
+            y[1] = n_shift == 1 ? x[2] : x[3];
+            y[2] = x[3];
+        }
+        return b_fix[p] ? y : x;
+    };
     // raw buffer, no stride, the full 32-bit range; word 3 is the 32-bit data format of this family
     auto slab_rsrc = [&](const char *base) {
         return __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(base), 0, -1, 0x00020000);
@@ -531,7 +560,7 @@ contract_fast_kernel(ContractArgs<T> args) {
 #pragma unroll
         for (int p = 0; p < Cfg::A_PER_T; ++p) *reinterpret_cast<vec_t *>(st + a_lds[p]) = ra[p];
 #pragma unroll
-        for (int p = 0; p < Cfg::B_PER_T; ++p) *reinterpret_cast<vec_t *>(st + b_lds[p]) = rb[p];
+        for (int p = 0; p < Cfg::B_PER_T; ++p) *reinterpret_cast<vec_t *>(st + b_lds[p]) = b_piece(rb[p], p);
     };
 
     typename MF::acc_t acc[MI][NI];
@@ -550,7 +579,9 @@ contract_fast_kernel(ContractArgs<T> args) {
                     if constexpr (CV == 1) {
                         acc[mi][g][v] = inside ? *cp : T(0);
                     } else {
-                        const cvec_t o = inside ? *reinterpret_cast<const gcvec_t *>(cp) : cvec_t(T(0));
+                        cvec_t o = cvec_t(T(0));
+                        if (inside && (!SHIFT || col + CV <= args.N)) o = *reinterpret_cast<const gcvec_t *>(cp);
+                        else if (inside) o[0] = *cp;            // the row's last column: CV is 2
 #pragma unroll
                         for (int q = 0; q < CV; ++q) acc[mi][g * CV + q][v] = o[q];
                     }
@@ -577,7 +608,7 @@ contract_fast_kernel(ContractArgs<T> args) {
 #pragma unroll
             for (int p = 0; p < Cfg::A_PER_T; ++p) *reinterpret_cast<vec_t *>(st + a_lds[p]) = xa[p];
 #pragma unroll
-            for (int p = 0; p < Cfg::B_PER_T; ++p) *reinterpret_cast<vec_t *>(st + b_lds[p]) = xb[p];
+            for (int p = 0; p < Cfg::B_PER_T; ++p) *reinterpret_cast<vec_t *>(st + b_lds[p]) = b_piece(xb[p], p);
         };
         const T *st0 = lds, *st1 = lds + Cfg::STAGE_ELEMS;
         load_into(ra, rb, 0);
@@ -680,6 +711,12 @@ contract_fast_kernel(ContractArgs<T> args) {
                 } else {
 #pragma unroll
                     for (int q = 0; q < CV; ++q) o[q] = acc[mi][g * CV + q][v];
+                    if (SHIFT && col + CV > args.N) {           // the row's last column on its own: CV is 2
+                        T o0 = o[0];
+                        if (!ACC_INIT && args.accumulate) o0 += __builtin_nontemporal_load(cp);
+                        __builtin_nontemporal_store(o0, cp);
+                        continue;
+                    }
                     if (!ACC_INIT && args.accumulate) o += __builtin_nontemporal_load(reinterpret_cast<const gcvec_t *>(cp));
                     __builtin_nontemporal_store(o, reinterpret_cast<gcvec_t *>(cp));
                 }

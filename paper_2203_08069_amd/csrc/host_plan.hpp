@@ -173,6 +173,27 @@ inline ProductPlan plan_product(bool f64, bool ta, int64_t M, int64_t N, int64_t
     return plan;
 }
 
+// Rows of the right operand that do not end on a 16-byte piece (N not a multiple of 16 / element
+// size).  The straight-line kernels can take such rows as they are - the last piece is fetched one
+// vector before the end of the row and shifted in registers, about 3 % on the whole launch, and
+// N counts with its padding to whole tiles - or the trailing N mod vector columns are peeled off
+// to a streaming kernel that reads the left operand once more (about 4.5 TB/s) while the rest
+// runs on a whole number of pieces.  Returns the number of columns to peel: the cheaper of the two
+// by the estimates of plan_product (a narrow output, where the second pass over the left operand
+// doubles the time, stays whole; a wide one, where that pass is a percent, is peeled); all N columns
+// when N is narrower than one piece.  A function of the extents only.
+inline int64_t peeled_columns(bool f64, bool ta, int64_t M, int64_t N, int64_t K, int64_t batch, bool acc = false) {
+    const int64_t vec = f64 ? 2 : 4;
+    if (N % vec == 0) return 0;
+    if (N < vec) return N;
+    const double per_cu = (f64 ? 78.6e12 : 157.3e12) / (double)kComputeUnits, esz = f64 ? 8.0 : 4.0;
+    const double whole = 1.03 * plan_product(f64, ta, M, N, K, batch, acc).main.cost;
+    // the second pass in units of tile area, as the costs of plan_product are: seconds x rate / (2 K)
+    const double pass = ((double)M * (double)K * (double)batch * esz / 4.5e12 + 3e-6) * per_cu / (2.0 * (double)K);
+    const double peeled = plan_product(f64, ta, M, N - N % vec, K, batch, acc).main.cost + pass;
+    return peeled < whole ? N % vec : 0;
+}
+
 // A product with a small output and a long contracted index gives fewer tiles than the part has
 // compute units, however the tiles are chosen.  With scratch memory from the caller such a product
 // is cut along k into `parts` products of `kchunk` terms each (the last one shorter), run as one

@@ -169,6 +169,19 @@ int main() {
     CHECK(plan_split_k(true, 512, 512, 8192).parts == 8 && plan_split_k(true, 512, 512, 8192).kchunk == 1024, "512 x 512 x 8192");
     CHECK(plan_split_k(true, 1024, 1024, 8192).parts == 1, "a tile per compute unit is not cut");
 
+    // trailing columns peeled off a product: none, the N mod vector, or all of a product narrower than a piece
+    for (int it = 0; it < 300000; ++it) {
+        const bool f64 = rnd() & 1, ta = rnd() & 1, acc = rnd() & 1;
+        const int64_t vec = f64 ? 2 : 4;
+        const int64_t M = extent((int64_t)1 << 24), N = extent((int64_t)1 << 24), K = extent((int64_t)1 << 30);
+        const int64_t batch = 1 + (int64_t)(rnd() % 4) * (int64_t)(rnd() % 300);
+        const int64_t c = peeled_columns(f64, ta, M, N, K, batch, acc);
+        if (N % vec == 0) CHECK(c == 0, "whole pieces peeled: %" PRId64, c);
+        else if (N < vec) CHECK(c == N, "narrower than a piece: %" PRId64 " of %" PRId64, c, N);
+        else CHECK(c == 0 || c == N % vec, "peeled %" PRId64 " of N %" PRId64, c, N);
+        CHECK(N - c == 0 || N - c >= vec, "what remains is narrower than a piece");
+    }
+
     // MTTKRP plans: extents whose product stays below 2^60, as the entry point demands
     for (int it = 0; it < 300000; ++it) {
         const int dt = (int)(rnd() & 1), mode = (int)(rnd() % 3);

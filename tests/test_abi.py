@@ -262,6 +262,28 @@ def test_gemm_plan_choice(lib):
     assert tile(F64, False, 8192, 8192, 128) == (128, 128, 16)
 
 
+def test_gemm_peeled_columns(lib):
+    """Rows of the right operand that end inside a 16-byte piece: a narrow output stays whole (a second
+    pass over the left operand would double the time), a wide one has its trailing columns peeled
+    off (that pass costs a percent and the rest runs on whole pieces); fewer columns than one
+    piece all go to the streaming kernel."""
+    from paper_2203_08069_amd import binding
+    peeled = binding.gemm_peeled_columns
+    F32, F64 = 0, 1
+    for dt, vec in ((F32, 4), (F64, 2)):
+        for N in (vec, 32, 8192):
+            assert peeled(dt, False, 8192, N, 8192) == 0
+        for N in range(1, vec):
+            assert peeled(dt, False, 1 << 20, N, 1000) == N
+        for N in (vec + 1, 31, 33):
+            assert peeled(dt, False, 1000000, N, 1000) == 0, (dt, N)         # rank-sized outputs of TTM
+        for N in (4097, 8191):
+            assert peeled(dt, False, 8192, N, 8192) == N % vec, (dt, N)
+        assert peeled(dt, True, 256, 1000 * 1000 + 1, 1000) in (0, 1)
+    assert peeled(7, False, 8, 8, 8) == -1 and peeled(F32, False, 0, 8, 8) == -1 and peeled(F32, False, 8, 8, 8, batch=0) == -1
+    assert peeled(F32, False, 1 << 40, 1 << 40, 8) == -1
+
+
 def test_gemm_plan_invariants_on_random_extents(lib):
     """Whatever the extents: tiles come from the dtype's set, narrow tiles only serve narrow outputs,
     slabs are no deeper than K allows the kernels to start (K >= BK or the guarded kernel is used),

@@ -76,6 +76,26 @@ TILED_EXTENTS = [(512, 768, 128), (520, 712, 100), (300, 264, 96),
 def test_gemm_every_tile_by_name(lib, oracle, dtype, tile, M, N, K, ta):
     """distal_gemm_tiled with each tile, left operand stored either way, C a block inside a larger
     matrix of sentinels; then accumulated on top.  Every element is compared."""
+    every_tile_case(lib, oracle, dtype, tile, M, N, K, ta)
+
+
+# Rows of the right operand that end inside a 16-byte piece, on outputs narrow enough that the library
+# keeps them inside the tiled kernels (their forms that fetch the last piece one vector early and
+# shift it) instead of peeling the trailing columns off: ragged with whole slabs, with trailing
+# terms, a last tile narrower than one piece (129, 257), an output narrower than every tile (7).
+ODD_N_EXTENTS = [(302, 131, 96), (520, 71, 100), (260, 7, 48), (200, 129, 300), (136, 257, 64), (1100, 35, 528)]
+
+
+@pytest.mark.parametrize("ta", [False, True])
+@pytest.mark.parametrize("M,N,K", ODD_N_EXTENTS)
+@pytest.mark.parametrize("dtype,tile", TILE_CASES)
+def test_gemm_every_tile_rows_ending_inside_a_piece(lib, oracle, dtype, tile, M, N, K, ta):
+    for acc in (False, True):
+        assert lib.gemm_peeled_columns(int(dtype == np.float64), ta, M, N, K, 1, acc) == 0      # what is tested runs in the tiled kernel
+    every_tile_case(lib, oracle, dtype, tile, M, N, K, ta)
+
+
+def every_tile_case(lib, oracle, dtype, tile, M, N, K, ta):
     kind = inputs.SMALLINT if (M + tile[0]) % 3 == 0 else inputs.UNIFORM
     vec = 16 // np.dtype(dtype).itemsize
     A, B = U.gen(700 + M, 0, (M, K), dtype, kind), U.gen(700 + M, 1, (K, N), dtype, kind)
