@@ -250,6 +250,18 @@ int distal_gemm_plan(distal_dtype dt, int transposed_left, int64_t M, int64_t N,
 int64_t distal_gemm_peeled_columns(distal_dtype dt, int transposed_left, int64_t M, int64_t N, int64_t K,
                                    int64_t batch, int accumulate);
 
+/*
+ * Host-only query: which kernel distal_ttm (and distal_ttm_mode along mode 2) runs for a tensor of
+ * `rows` = I*J rows of K elements and a K x L factor whose base is 16-byte aligned.  0: the tiled
+ * matrix product on the (I*J) x K view.  1, 2 or 4: a rank-sized factor (L <= 32) on a long tensor
+ * (at least 65536 rows) whose rows are at most 32 slices of 256 bytes - the factor then stays in
+ * the registers of each workgroup, that many slices per wavefront, while the tensor streams by
+ * once (evaluation section: TTM's leaves are matrix products; this is the one a factorisation's
+ * shapes give).  The two kernels sum the terms of an output in different orders: results agree
+ * within rounding, not bit for bit.  A function of the arguments only; 0 for invalid arguments.
+ */
+int distal_ttm_slices_per_wave(distal_dtype dt, int64_t rows, int64_t K, int64_t L);
+
 /* Scratch sizes for the calls that take a workspace (0 for invalid arguments). */
 size_t distal_mttkrp_workspace_bytes(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L);
 size_t distal_mttkrp_mode_workspace_bytes(distal_dtype dt, int mode, int64_t I, int64_t J, int64_t K,

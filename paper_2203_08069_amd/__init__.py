@@ -5,4 +5,4 @@ loaded on first use of ``paper_2203_08069_amd.binding`` and its absence is an
 error, never a fallback.
 """
 __all__ = ["binding", "inputs"]
-__version__ = "0.5.1"   # distal_version() of the library reports the same (501)
+__version__ = "0.6.0"   # distal_version() of the library reports the same (600)

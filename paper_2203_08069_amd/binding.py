@@ -29,6 +29,7 @@ EXPORTS = (
     "distal_mttkrp_workspace_bytes", "distal_innerprod_workspace_bytes", "distal_gemm_plan",
     "distal_status_string", "distal_version", "distal_innerprod_noalloc", "distal_gemm_tiled",
     "distal_gemm_ws", "distal_gemm_workspace_bytes", "distal_gemm_peeled_columns",
+    "distal_ttm_slices_per_wave",
 )
 
 
@@ -79,6 +80,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     ip = ctypes.POINTER(ctypes.c_int)
     lib.distal_gemm_plan.argtypes = [ci, ci, i64, i64, i64, i64, ci, ip, ip, ctypes.POINTER(ctypes.c_int64), ip]
     lib.distal_gemm_plan.restype = ci
+    lib.distal_ttm_slices_per_wave.argtypes = [ci, i64, i64, i64]
+    lib.distal_ttm_slices_per_wave.restype = ci
     lib.distal_gemm_peeled_columns.argtypes = [ci, ci, i64, i64, i64, i64, ci]
     lib.distal_gemm_peeled_columns.restype = i64
     for name in ("distal_gemm", "distal_ttm", "distal_mttkrp", "distal_ttv", "distal_innerprod",
@@ -375,6 +378,12 @@ def gemm_peeled_columns(dtype_code: int, transposed_left: bool, M: int, N: int, 
     launches (host-only query); -1 for invalid arguments."""
     return int(load_library().distal_gemm_peeled_columns(dtype_code, int(bool(transposed_left)), M, N, K, batch,
                                                          int(bool(accumulate))))
+
+
+def ttm_slices_per_wave(dtype_code: int, rows: int, K: int, L: int) -> int:
+    """Host-only query: 1, 2 or 4 when distal_ttm runs a tensor of `rows` = I*J rows of K elements against
+    a K x L factor in the kernel that keeps the factor in registers, 0 when it runs the tiled product."""
+    return int(load_library().distal_ttm_slices_per_wave(dtype_code, rows, K, L))
 
 
 def gemm_tile(dtype_code: int, transposed_left: bool, M: int, N: int, K: int, batch: int = 1, accumulate: bool = False):

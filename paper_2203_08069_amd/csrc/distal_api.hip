@@ -12,6 +12,7 @@
 #include "host_plan.hpp"
 #include "gemm_kernel.hpp"
 #include "mttkrp_kernel.hpp"
+#include "ttm_kernel.hpp"
 #include "stream_kernels.hpp"
 
 using namespace distal;
@@ -337,6 +338,30 @@ int gemm_splitk_t(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, cons
     return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
 }
 
+// TTM over the last mode with the factor held in registers (ttm_slices_per_wave says where).
+template <typename T, int NS, bool RAGGED>
+int launch_ttm_slices_form(const TtmSlicesArgs<T> &a, hipStream_t stream) {
+    typedef TtmSlicesCfg<T, NS> Cfg;
+    static std::atomic<bool> done[kMaxDevices];
+    auto kern = ttm_slices_kernel<T, NS, RAGGED>;
+    if (!allow_lds(kern, Cfg::LDS_BYTES, done)) return DISTAL_ERR_LAUNCH;
+    const int64_t grid = a.rblocks < kComputeUnits ? a.rblocks : kComputeUnits;      // one workgroup per compute unit
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, a);
+    return hipGetLastError() == hipSuccess ? DISTAL_OK : DISTAL_ERR_LAUNCH;
+}
+
+template <typename T>
+int ttm_slices_t(int ns, int64_t R, int64_t K, int64_t L, const T *B, const T *C, T *A, hipStream_t stream) {
+    TtmSlicesArgs<T> a{B, C, A, R, K, L, (R + 31) / 32};
+    const bool whole = R % 32 == 0 && K == (int64_t)8 * ns * MttkrpCfg<T>::SL;
+    switch (ns) {
+    case 1: return whole ? launch_ttm_slices_form<T, 1, false>(a, stream) : launch_ttm_slices_form<T, 1, true>(a, stream);
+    case 2: return whole ? launch_ttm_slices_form<T, 2, false>(a, stream) : launch_ttm_slices_form<T, 2, true>(a, stream);
+    case 4: return whole ? launch_ttm_slices_form<T, 4, false>(a, stream) : launch_ttm_slices_form<T, 4, true>(a, stream);
+    default: return DISTAL_ERR_SHAPE;
+    }
+}
+
 int check_dtype(int dt) { return (dt == DISTAL_F32 || dt == DISTAL_F64) ? DISTAL_OK : DISTAL_ERR_DTYPE; }
 
 size_t elem_size(int dt) { return dt == DISTAL_F64 ? 8 : 4; }
@@ -609,7 +634,7 @@ bool tensor_elems(int64_t I, int64_t J, int64_t K, int64_t *n) {
 
 extern "C" {
 
-int distal_version(void) { return 501; }   // 0.5.1
+int distal_version(void) { return 600; }   // 0.6.0
 
 const char *distal_status_string(int status) {
     switch (status) {
@@ -731,6 +756,12 @@ int distal_ttm(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L, cons
     // The contraction over the last mode is one matrix product on the (I*J) x K view.
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t ldk = K > 0 ? K : 1, ldl = L > 0 ? L : 1;
+    // a rank-sized factor on a long tensor: the factor stays in registers, the tensor streams by
+    const int ns = aligned16(B) ? ttm_slices_per_wave(dt == DISTAL_F64, ij, K, L) : 0;
+    if (ns != 0) {
+        if (dt == DISTAL_F64) return ttm_slices_t<double>(ns, ij, K, L, (const double *)B, (const double *)C, (double *)A, s);
+        return ttm_slices_t<float>(ns, ij, K, L, (const float *)B, (const float *)C, (float *)A, s);
+    }
     if (dt == DISTAL_F64)
         return gemm_t<double>(ij, L, K, (const double *)B, ldk, (const double *)C, ldl, (double *)A, ldl, 0, s);
     return gemm_t<float>(ij, L, K, (const float *)B, ldk, (const float *)C, ldl, (float *)A, ldl, 0, s);
@@ -847,6 +878,11 @@ int distal_gemm_plan(distal_dtype dt, int transposed_left, int64_t M, int64_t N,
     *cut = p.cut;
     rest_tile[0] = p.rest.bm; rest_tile[1] = p.rest.bn; rest_tile[2] = p.rest.bk;
     return DISTAL_OK;
+}
+
+int distal_ttm_slices_per_wave(distal_dtype dt, int64_t rows, int64_t K, int64_t L) {
+    if (check_dtype(dt) != DISTAL_OK || rows < 0 || K < 0 || L < 0) return 0;
+    return ttm_slices_per_wave(dt == DISTAL_F64, rows, K, L);
 }
 
 int64_t distal_gemm_peeled_columns(distal_dtype dt, int transposed_left, int64_t M, int64_t N, int64_t K, int64_t batch,

@@ -244,6 +244,22 @@ inline bool slab_offsets_fit(int64_t esz, bool ta, int bm, int bn, int bk, int64
     return (a + a_len) * esz < limit && (b + bn) * esz < limit;
 }
 
+// ---- TTM over the last mode with a rank-sized factor -------------------------------------------
+// Slices of the factor per wavefront (1, 2 or 4) for the kernel that keeps the whole factor in the
+// registers of a workgroup's eight wavefronts, or 0 where the tiled contraction runs instead:
+// at most 32 columns, rows of the tensor that are whole 16-byte pieces and at most 8 x 4 slices
+// of 256 bytes long, at least three quarters of the wavefronts' slices in use, and enough blocks
+// of 32 rows to give every compute unit eight.  A function of the extents only.
+inline int ttm_slices_per_wave(bool f64, int64_t R, int64_t K, int64_t L) {
+    const int64_t vec = f64 ? 2 : 4, sl = f64 ? 32 : 64;
+    if (L < 1 || L > 32 || K < 1 || K % vec != 0 || R < (int64_t)32 * kComputeUnits * 8) return 0;
+    const int64_t nslices = (K + sl - 1) / sl;
+    const int ns = nslices <= 8 ? 1 : nslices <= 16 ? 2 : nslices <= 32 ? 4 : 0;
+    if (ns == 0 || nslices * 8 < (int64_t)8 * ns * 7) return 0;
+    if (ns == 4 && (R % 32 != 0 || K != 32 * sl)) return 0;       // the ragged form of four slices spills
+    return ns;
+}
+
 // ---- MTTKRP: ranges of the walked index and partial rows --------------------------------------
 constexpr int64_t kModeTargetBlocks = 768;
 

@@ -159,6 +159,62 @@ def test_ttm_1024(lib, oracle):
     U.assert_close(A1.cpu().numpy(), A[:8].cpu().numpy().astype(np.float64), np.float32, K)
 
 
+# TTM over the last mode with a rank-sized factor on a long tensor: the kernel that keeps the factor
+# in registers (one, two or four 256-byte slices of it per wavefront).  I, J, K, L and what is reached.
+RANK_SIZED_TTM = [
+    (np.float32, 256, 256, 512, 32, "one slice per wavefront, whole"),
+    (np.float32, 256, 256, 1024, 32, "two slices, whole"),
+    (np.float32, 256, 256, 2048, 32, "four slices, whole"),
+    (np.float32, 255, 259, 1000, 32, "two slices, a short last slice, a short last block of rows"),
+    (np.float32, 256, 257, 960, 17, "two slices, the last wavefront's second slice past K, 17 columns"),
+    (np.float32, 300, 300, 452, 1, "one slice, short last slice, one column"),
+    (np.float32, 256, 256, 1024, 8, "two slices, 8 columns"),
+    (np.float64, 256, 256, 256, 32, "one slice, whole"),
+    (np.float64, 256, 256, 512, 32, "two slices, whole"),
+    (np.float64, 256, 256, 1024, 32, "four slices, whole"),
+    (np.float64, 256, 256, 1024, 5, "four slices, 5 columns"),
+    (np.float64, 255, 259, 500, 32, "two slices, ragged"),
+    (np.float64, 256, 257, 480, 31, "two slices, the last wavefront's second slice past K"),
+    (np.float64, 257, 256, 226, 32, "one slice, short last slice"),
+]
+
+
+@pytest.mark.parametrize("dtype,I,J,K,L,what", RANK_SIZED_TTM,
+                         ids=[f"{np.dtype(d).name}-{i}x{j}x{k}-L{l}" for d, i, j, k, l, _ in RANK_SIZED_TTM])
+def test_ttm_rank_sized_factor_on_a_long_tensor(lib, oracle, dtype, I, J, K, L, what):
+    import torch
+    from paper_2203_08069_amd import binding
+    assert binding.ttm_slices_per_wave(int(dtype == np.float64), I * J, K, L) in (1, 2, 4)      # the kernel under test runs
+    B, C = devgen(31, 0, (I, J, K), dtype), devgen(31, 1, (K, L), dtype)
+    tdt = B.dtype
+    # sentinels around the output: nothing outside it is written
+    flat = torch.full((I * J * L + 64,), 77.0, dtype=tdt, device="cuda:0")
+    A = flat[32:32 + I * J * L].view(I, J, L)
+    lib.distal_ttm(B, C, A)
+    assert bool((flat[:32] == 77.0).all()) and bool((flat[32 + I * J * L:] == 77.0).all())
+    assert bool(torch.isfinite(A).all())
+    # two fibres of every block of 32 rows of the (I*J) x L view, and the last rows
+    rng = np.random.default_rng(32)
+    R = I * J
+    starts = np.arange(0, R - 31, 32)
+    fibres = np.unique(np.concatenate([starts + rng.integers(0, 32, starts.size), starts + rng.integers(0, 32, starts.size),
+                                       np.arange(max(R - 40, 0), R)]))
+    hB = host_rows(31, 0, K, fibres, dtype).reshape(1, -1, K)
+    hC = inputs.tensor(31, 1, (K, L), dtype)
+    got = A.view(R, L)[torch.from_numpy(fibres).cuda()].cpu().numpy()
+    U.assert_close(got, oracle.ttm(hB, hC)[0], dtype, K)
+    # the whole output against the tiled contraction on the same view (another summation order)
+    A2 = torch.empty((R, L), dtype=tdt, device="cuda:0")
+    lib.distal_gemm(B.view(R, K), C, A2)
+    U.assert_close(A.view(R, L).cpu().numpy(), A2.cpu().numpy().astype(np.float64), dtype, K)
+    # the same bits on a second call, and exact linearity in the factor
+    A3 = torch.empty_like(A)
+    lib.distal_ttm(B, C, A3)
+    assert torch.equal(A3, A)
+    lib.distal_ttm(B, C * 2, A3)
+    assert torch.equal(A3, A * 2)
+
+
 def test_mttkrp_1024(lib, oracle):
     """configs[4]: A(i,l) = sum_jk B(i,j,k) C(j,l) D(k,l), B 1024^3, rank 32, fp32, seed 4."""
     import torch
