@@ -69,6 +69,7 @@ PROFILE_OF_ROW = {
     "ttm": "contract_fast_kernel_f32_ttm_1024x1024x1024x256.md",
     "ttm_mode0": "contract_fast_kernel_tn_f32_ttm_mode0_1024x1024x1024x256.md",
     "ttm_mode1": "contract_fast_kernel_tn_f32_ttm_mode1_1024x1024x1024x256.md",
+    "ttm_rank32_mode2": "ttm_slices_kernel_f32_1024_rank32.md",
     "mttkrp": "mttkrp_walk_kernel_f32_1024_rank32.md",
     "mttkrp_mode1": "mttkrp_walk_kernel_f32_1024_rank32.md",
     "mttkrp_mode2": "mttkrp_mode2_kernel_f32_1024_rank32.md",
