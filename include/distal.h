@@ -79,6 +79,9 @@ int distal_gemm(distal_dtype dt, int64_t M, int64_t N, int64_t K,
  * Tensor times matrix:  A(i,j,l) = sum_k B(i,j,k) * C(k,l)
  * (evaluation section, list of higher-order expressions).
  *   B: I x J x K, C: K x L, A: I x J x L, all dense.  A is overwritten.
+ * It is the matrix product of the (I*J) x K view of B with C and runs on the tiles
+ * distal_gemm_plan reports for M = I*J, N = L - except for a rank-sized factor on a long tensor,
+ * which has a kernel of its own (distal_ttm_slices_per_wave says when).
  */
 int distal_ttm(distal_dtype dt, int64_t I, int64_t J, int64_t K, int64_t L,
                const void *B, const void *C, void *A, void *stream);
