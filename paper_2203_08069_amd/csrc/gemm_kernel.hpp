@@ -458,7 +458,9 @@ contract_fast_kernel(ContractArgs<T> args) {
     constexpr int VEC = Cfg::VEC, KG = Cfg::KG, MI = Cfg::MI, NI = Cfg::NI;
     constexpr int CV = Cfg::CV, NG = Cfg::NG, NT = Cfg::NT, NKG = BK / KG;
     constexpr int ARL = Cfg::A_ROWLEN / VEC;          // 16-byte pieces per staged A row
-    constexpr bool DEEP = BM == 32 || BN == 32;       // rank-sized tiles: two slabs of loads in flight
+    // rank-sized tiles, and the binary64 64 x 64 tile in its eight-wavefront cut (grids of at most two
+    // tiles per compute unit): two slabs of loads in flight
+    constexpr bool DEEP = BM == 32 || BN == 32 || (sizeof(T) == 8 && BM * BN == 64 * 64 && WAVES_M * WAVES_N == 8);
     static_assert(Cfg::A_VECS % NT == 0 && Cfg::B_VECS % NT == 0, "slab vectors must divide over threads");
 
     args.A += (int64_t)blockIdx.y * args.batch_a;
@@ -599,7 +601,12 @@ contract_fast_kernel(ContractArgs<T> args) {
 
     if constexpr (DEEP) {
         // Narrow tiles do 16 flop per byte of the large operand: the product is bound by HBM, and one
-        // slab in flight per workgroup is too little to cover its latency.  Two register sets: slab
+        // slab in flight per workgroup is too little to cover its latency.  (The same holds for a small
+        // tile that is alone on its compute unit: a slab of a 64 x 64 tile is multiplied in less time
+        // than a load takes.  Measured in one process: binary64 1000^3 59 -> 65 % of peak, 1024 x 1024 x
+        // 8192 82.8 -> 86.5; the four-wavefront cut for larger grids loses two points with it - 3000^3
+        // 86.4 -> 84.4 - and the binary32 tiles neither gain nor lose, so they stay as they were.)
+        // Two register sets: slab
         // t is in LDS buffer t & 1, slab t+1 in one set, slab t+2 in flight into the other, and
         // slab t+3 is requested into the first as soon as it has been copied to LDS.
         vec_t ra2[Cfg::A_PER_T], rb2[Cfg::B_PER_T];
