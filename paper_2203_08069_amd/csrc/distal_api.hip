@@ -47,7 +47,6 @@ bool allow_lds(Kern kern, int bytes, std::atomic<bool> (&done)[kMaxDevices]) {
 
 constexpr int64_t kMaxGridY = 65535;
 
-// One launch per run of at most kMaxGridY problems of the batch (blockIdx.y picks the problem).
 // One launch of one form of the straight-line kernel (each form raises its LDS limit once per device).
 template <typename T, int BM, int BN, int BK, int WM, int WN, bool TA, int EDGE, bool INIT, bool FINE, bool SHIFT>
 bool launch_fast_form(const dim3 &grid, const ContractArgs<T> &a, hipStream_t stream) {
@@ -59,6 +58,7 @@ bool launch_fast_form(const dim3 &grid, const ContractArgs<T> &a, hipStream_t st
     return true;
 }
 
+// One launch per run of at most kMaxGridY problems of the batch (blockIdx.y picks the problem).
 // KIND: the guarded kernel, the straight-line kernel on whole tiles, or its edge-clamping form.
 enum { kGuarded = 0, kWhole = 1, kEdge = 2, kEdgeK = 3 };
 template <typename T, int BM, int BN, int BK, int WM, int WN, int KIND, bool TA, bool FINE = false>
