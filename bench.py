@@ -387,7 +387,7 @@ def main():
     for npdt in (np.float32, np.float64):
         sfx = "" if npdt == np.float32 else "_f64"
         dt, esz = dname(npdt), np.dtype(npdt).itemsize
-        names = {"ttm" + sfx} | ({"ttm_mode0", "ttm_mode1", "ttm_rank32"} if npdt == np.float32 else set())
+        names = {"ttm" + sfx, "ttm_rank32"} | ({"ttm_mode0", "ttm_mode1"} if npdt == np.float32 else set())
         if not (want & names):
             continue
         I = J = K = 1024
@@ -409,8 +409,9 @@ def main():
             del A
         for rank, tag, bound in ((L, "ttm_mode%d", "mfma"), (32, "ttm_rank32_mode%d", "hbm")):
             for mode in ((0, 1) if rank == L else (2, 0, 1)):
-                row = tag % mode
-                if npdt != np.float32 or (row if rank == L else "ttm_rank32") not in want:
+                row = tag % mode + ("" if npdt == np.float32 else "_f64")
+                # binary64: the rank-32 product along the last mode only (the kernel that holds the factor in registers)
+                if (npdt != np.float32 and (rank == L or mode != 2)) or (tag % mode if rank == L else "ttm_rank32") not in want:
                     continue
                 Cr = C if rank == L else C[:, :rank].contiguous()
                 shape = [I, J, K]
