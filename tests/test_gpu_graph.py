@@ -84,3 +84,29 @@ def test_captured_tensor_calls_replay_exactly(lib, oracle):
         torch.cuda.synchronize()
         for got, ref in zip((out_ttv, out_ttm, out_mk, out_ip), want):
             assert torch.equal(got, ref), f"replay {rep}"
+
+
+def test_captured_rank_sized_ttm_replays_exactly(lib):
+    """The TTM kernel that keeps a rank-sized factor in registers (a long tensor, at most 32 columns) under
+    capture: replays with eager work between give the eager call's bits."""
+    import torch
+    I, J, K, L = 256, 256, 512, 32
+    assert lib.ttm_slices_per_wave(0, I * J, K, L) == 1
+    gen = torch.Generator(device="cuda:0").manual_seed(73)
+    B = torch.rand((I, J, K), dtype=torch.float32, device="cuda:0", generator=gen) - 0.5
+    M = torch.rand((K, L), dtype=torch.float32, device="cuda:0", generator=gen) - 0.5
+    out = torch.empty((I, J, L), dtype=torch.float32, device="cuda:0")
+    lib.distal_ttm(B, M, out)
+    torch.cuda.synchronize()
+    want = out.clone()
+    ref = B.view(I * J, K)[:4096].double() @ M.double()
+    assert float((want.view(I * J, L)[:4096].double() - ref).abs().max()) < 1e-4
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lib.distal_ttm(B, M, out)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), f"replay {rep}"
