@@ -256,7 +256,7 @@ int64_t distal_gemm_peeled_columns(distal_dtype dt, int transposed_left, int64_t
 /*
  * Host-only query: which kernel distal_ttm (and distal_ttm_mode along mode 2) runs for a tensor of
  * `rows` = I*J rows of K elements and a K x L factor whose base is 16-byte aligned.  0: the tiled
- * matrix product on the (I*J) x K view.  1, 2 or 4: a rank-sized factor (L <= 32) on a long tensor
+ * matrix product on the (I*J) x K view.  1 ... 4: a rank-sized factor (L <= 32) on a long tensor
  * (at least 65536 rows) whose rows are at most 32 slices of 256 bytes - the factor then stays in
  * the registers of each workgroup, that many slices per wavefront, while the tensor streams by
  * once (evaluation section: TTM's leaves are matrix products; this is the one a factorisation's

@@ -381,7 +381,7 @@ def gemm_peeled_columns(dtype_code: int, transposed_left: bool, M: int, N: int, 
 
 
 def ttm_slices_per_wave(dtype_code: int, rows: int, K: int, L: int) -> int:
-    """Host-only query: 1, 2 or 4 when distal_ttm runs a tensor of `rows` = I*J rows of K elements against
+    """Host-only query: 1 ... 4 when distal_ttm runs a tensor of `rows` = I*J rows of K elements against
     a K x L factor in the kernel that keeps the factor in registers, 0 when it runs the tiled product."""
     return int(load_library().distal_ttm_slices_per_wave(dtype_code, rows, K, L))
 

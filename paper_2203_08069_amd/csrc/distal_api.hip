@@ -357,7 +357,8 @@ int ttm_slices_t(int ns, int64_t R, int64_t K, int64_t L, const T *B, const T *C
     switch (ns) {
     case 1: return whole ? launch_ttm_slices_form<T, 1, false>(a, stream) : launch_ttm_slices_form<T, 1, true>(a, stream);
     case 2: return whole ? launch_ttm_slices_form<T, 2, false>(a, stream) : launch_ttm_slices_form<T, 2, true>(a, stream);
-    case 4: return whole ? launch_ttm_slices_form<T, 4, false>(a, stream) : DISTAL_ERR_SHAPE;   // never planned: the ragged form spills
+    case 3: return whole ? launch_ttm_slices_form<T, 3, false>(a, stream) : DISTAL_ERR_SHAPE;   // never planned: the ragged forms spill
+    case 4: return whole ? launch_ttm_slices_form<T, 4, false>(a, stream) : DISTAL_ERR_SHAPE;
     default: return DISTAL_ERR_SHAPE;
     }
 }

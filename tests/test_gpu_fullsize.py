@@ -160,10 +160,11 @@ def test_ttm_1024(lib, oracle):
 
 
 # TTM over the last mode with a rank-sized factor on a long tensor: the kernel that keeps the factor
-# in registers (one, two or four 256-byte slices of it per wavefront).  I, J, K, L and what is reached.
+# in registers (one to four 256-byte slices of it per wavefront).  I, J, K, L and what is reached.
 RANK_SIZED_TTM = [
     (np.float32, 256, 256, 512, 32, "one slice per wavefront, whole"),
     (np.float32, 256, 256, 1024, 32, "two slices, whole"),
+    (np.float32, 256, 256, 1536, 32, "three slices, whole"),
     (np.float32, 256, 256, 2048, 32, "four slices, whole"),
     (np.float32, 255, 259, 1000, 32, "two slices, a short last slice, a short last block of rows"),
     (np.float32, 256, 257, 960, 17, "two slices, the last wavefront's second slice past K, 17 columns"),
@@ -171,6 +172,7 @@ RANK_SIZED_TTM = [
     (np.float32, 256, 256, 1024, 8, "two slices, 8 columns"),
     (np.float64, 256, 256, 256, 32, "one slice, whole"),
     (np.float64, 256, 256, 512, 32, "two slices, whole"),
+    (np.float64, 256, 256, 768, 30, "three slices, 30 columns"),
     (np.float64, 256, 256, 1024, 32, "four slices, whole"),
     (np.float64, 256, 256, 1024, 5, "four slices, 5 columns"),
     (np.float64, 255, 259, 500, 32, "two slices, ragged"),
@@ -184,7 +186,7 @@ RANK_SIZED_TTM = [
 def test_ttm_rank_sized_factor_on_a_long_tensor(lib, oracle, dtype, I, J, K, L, what):
     import torch
     from paper_2203_08069_amd import binding
-    assert binding.ttm_slices_per_wave(int(dtype == np.float64), I * J, K, L) in (1, 2, 4)      # the kernel under test runs
+    assert binding.ttm_slices_per_wave(int(dtype == np.float64), I * J, K, L) in (1, 2, 3, 4)      # the kernel under test runs
     B, C = devgen(31, 0, (I, J, K), dtype), devgen(31, 1, (K, L), dtype)
     tdt = B.dtype
     # sentinels around the output: nothing outside it is written
