@@ -352,15 +352,21 @@ int launch_ttm_slices_form(const TtmSlicesArgs<T> &a, hipStream_t stream) {
 
 template <typename T>
 int ttm_slices_t(int ns, int64_t R, int64_t K, int64_t L, const T *B, const T *C, T *A, hipStream_t stream) {
-    TtmSlicesArgs<T> a{B, C, A, R, K, L, (R + 31) / 32};
-    const bool whole = R % 32 == 0 && K == (int64_t)8 * ns * MttkrpCfg<T>::SL;
+    const bool kwhole = K == (int64_t)8 * ns * MttkrpCfg<T>::SL;
+    // whole slices: the straight-line form on the whole blocks of 32 rows, the last R % 32 rows as a
+    // small tiled product; a short last slice: the ragged form on all rows
+    const int64_t Rk = kwhole ? R - R % 32 : R;
+    TtmSlicesArgs<T> a{B, C, A, Rk, K, L, (Rk + 31) / 32};
+    int rc;
     switch (ns) {
-    case 1: return whole ? launch_ttm_slices_form<T, 1, false>(a, stream) : launch_ttm_slices_form<T, 1, true>(a, stream);
-    case 2: return whole ? launch_ttm_slices_form<T, 2, false>(a, stream) : launch_ttm_slices_form<T, 2, true>(a, stream);
-    case 3: return whole ? launch_ttm_slices_form<T, 3, false>(a, stream) : DISTAL_ERR_SHAPE;   // never planned: the ragged forms spill
-    case 4: return whole ? launch_ttm_slices_form<T, 4, false>(a, stream) : DISTAL_ERR_SHAPE;
-    default: return DISTAL_ERR_SHAPE;
+    case 1: rc = kwhole ? launch_ttm_slices_form<T, 1, false>(a, stream) : launch_ttm_slices_form<T, 1, true>(a, stream); break;
+    case 2: rc = kwhole ? launch_ttm_slices_form<T, 2, false>(a, stream) : launch_ttm_slices_form<T, 2, true>(a, stream); break;
+    case 3: rc = kwhole ? launch_ttm_slices_form<T, 3, false>(a, stream) : DISTAL_ERR_SHAPE; break;   // never planned: the ragged forms spill
+    case 4: rc = kwhole ? launch_ttm_slices_form<T, 4, false>(a, stream) : DISTAL_ERR_SHAPE; break;
+    default: rc = DISTAL_ERR_SHAPE;
     }
+    if (rc != DISTAL_OK || Rk == R) return rc;
+    return gemm_t<T>(R - Rk, L, K, B + Rk * K, K, C, L, A + Rk * L, L, 0, stream);
 }
 
 int check_dtype(int dt) { return (dt == DISTAL_F32 || dt == DISTAL_F64) ? DISTAL_OK : DISTAL_ERR_DTYPE; }

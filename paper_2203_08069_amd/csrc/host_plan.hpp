@@ -249,8 +249,10 @@ inline bool slab_offsets_fit(int64_t esz, bool ta, int bm, int bn, int bk, int64
 // registers of a workgroup's eight wavefronts, or 0 where the tiled contraction runs instead:
 // at most 32 columns, rows of the tensor that are whole 16-byte pieces and at most 8 x 4 slices
 // of 256 bytes long, at least seven eighths of the wavefronts' slices in use, and enough blocks
-// of 32 rows to give every compute unit eight.  Three and four slices per wavefront only on whole
-// blocks (R % 32 == 0, exactly 24 or 32 slices): their ragged forms spill and are not built.
+// of 32 rows to give every compute unit eight.  Three and four slices per wavefront only for
+// exactly 24 or 32 slices: the forms for a short last slice spill there and are not built.  (Rows
+// beyond a whole number of blocks of 32 are no obstacle: with whole slices the last R mod 32 rows
+// run as a small tiled product of their own.)
 // A function of the extents only.
 inline int ttm_slices_per_wave(bool f64, int64_t R, int64_t K, int64_t L) {
     const int64_t vec = f64 ? 2 : 4, sl = f64 ? 32 : 64;
@@ -258,7 +260,7 @@ inline int ttm_slices_per_wave(bool f64, int64_t R, int64_t K, int64_t L) {
     const int64_t nslices = (K + sl - 1) / sl;
     const int ns = nslices <= 8 ? 1 : nslices <= 16 ? 2 : nslices <= 24 ? 3 : nslices <= 32 ? 4 : 0;
     if (ns == 0 || nslices * 8 < (int64_t)8 * ns * 7) return 0;
-    if (ns >= 3 && (R % 32 != 0 || K != 8 * ns * sl)) return 0;   // the ragged forms of three and four slices spill
+    if (ns >= 3 && K != 8 * ns * sl) return 0;                    // the ragged forms of three and four slices spill
     return ns;
 }
 

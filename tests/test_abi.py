@@ -287,7 +287,7 @@ def test_gemm_peeled_columns(lib):
 def test_ttm_slices_plan(lib):
     """Where the last-mode TTM keeps its factor in registers: at most 32 columns, at least 65536 rows
     of whole 16-byte pieces, at most 32 slices of 256 bytes of which at least seven eighths are used;
-    three and four slices per wavefront only on whole blocks."""
+    three and four slices per wavefront only on whole slices."""
     from paper_2203_08069_amd import binding
     ns = binding.ttm_slices_per_wave
     F32, F64 = 0, 1
@@ -298,8 +298,9 @@ def test_ttm_slices_plan(lib):
     assert ns(F32, R, 768, 32) == 0 and ns(F32, R, 256, 32) == 0        # too many idle wavefronts
     assert ns(F32, R, 4096, 32) == 0 and ns(F64, R, 2048, 32) == 0      # the factor does not fit the registers
     assert ns(F32, R, 1022, 32) == 0 and ns(F64, R, 511, 32) == 0       # rows are not whole 16-byte pieces
-    assert ns(F32, R, 2000, 32) == 0 and ns(F32, R - 1, 2048, 32) == 0 and ns(F64, R, 1000, 32) == 0    # four slices: whole only
-    assert ns(F32, R, 1500, 32) == 0 and ns(F32, R - 1, 1536, 32) == 0 and ns(F64, R, 760, 32) == 0     # and three
+    assert ns(F32, R, 2000, 32) == 0 and ns(F64, R, 1000, 32) == 0      # four slices: whole slices only
+    assert ns(F32, R, 1500, 32) == 0 and ns(F64, R, 760, 32) == 0       # and three
+    assert ns(F32, R - 1, 2048, 32) == 4 and ns(F32, R - 1, 1536, 32) == 3     # rows beyond whole blocks are no obstacle
     assert ns(F32, 65535, 1024, 32) == 0 and ns(F32, 65536, 1024, 32) == 2
     assert ns(7, R, 1024, 32) == 0 and ns(F32, -1, 1024, 32) == 0
 

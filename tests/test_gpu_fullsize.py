@@ -166,6 +166,8 @@ RANK_SIZED_TTM = [
     (np.float32, 256, 256, 1024, 32, "two slices, whole"),
     (np.float32, 256, 256, 1536, 32, "three slices, whole"),
     (np.float32, 256, 256, 2048, 32, "four slices, whole"),
+    (np.float32, 255, 259, 2048, 32, "four slices, the last 29 rows as a tiled product"),
+    (np.float32, 257, 256, 1024, 31, "two whole slices, the last 16 rows as a tiled product"),
     (np.float32, 255, 259, 1000, 32, "two slices, a short last slice, a short last block of rows"),
     (np.float32, 256, 257, 960, 17, "two slices, the last wavefront's second slice past K, 17 columns"),
     (np.float32, 300, 300, 452, 1, "one slice, short last slice, one column"),
@@ -175,6 +177,7 @@ RANK_SIZED_TTM = [
     (np.float64, 256, 256, 768, 30, "three slices, 30 columns"),
     (np.float64, 256, 256, 1024, 32, "four slices, whole"),
     (np.float64, 256, 256, 1024, 5, "four slices, 5 columns"),
+    (np.float64, 255, 259, 768, 32, "three slices, the last 29 rows as a tiled product"),
     (np.float64, 255, 259, 500, 32, "two slices, ragged"),
     (np.float64, 256, 257, 480, 31, "two slices, the last wavefront's second slice past K"),
     (np.float64, 257, 256, 226, 32, "one slice, short last slice"),
