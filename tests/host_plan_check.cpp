@@ -182,6 +182,20 @@ int main() {
         CHECK(N - c == 0 || N - c >= vec, "what remains is narrower than a piece");
     }
 
+    // where the last-mode TTM keeps its factor in registers: the slices fit the wavefronts and mostly fill them
+    for (int it = 0; it < 300000; ++it) {
+        const bool f64 = rnd() & 1;
+        const int64_t vec = f64 ? 2 : 4, sl = f64 ? 32 : 64;
+        const int64_t R = extent((int64_t)1 << 40), K = (rnd() & 3) ? extent(4096) : extent((int64_t)1 << 40), L = extent(40);
+        const int ns = ttm_slices_per_wave(f64, R, K, L);
+        CHECK(ns >= 0 && ns <= 4, "slices per wavefront %d", ns);
+        if (ns == 0) continue;
+        const int64_t nslices = (K + sl - 1) / sl;
+        CHECK(L >= 1 && L <= 32 && K % vec == 0 && R >= 65536, "extents %" PRId64 " %" PRId64 " %" PRId64, R, K, L);
+        CHECK(nslices <= 8 * ns && nslices * 8 >= 56 * ns, "%" PRId64 " slices on %d per wavefront", nslices, ns);
+        CHECK(ns < 3 || K == 8 * ns * sl, "a short last slice with %d slices per wavefront", ns);
+    }
+
     // MTTKRP plans: extents whose product stays below 2^60, as the entry point demands
     for (int it = 0; it < 300000; ++it) {
         const int dt = (int)(rnd() & 1), mode = (int)(rnd() % 3);
