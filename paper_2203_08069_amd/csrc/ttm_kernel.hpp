@@ -13,9 +13,9 @@
 // together 2 KiB contiguous per row; the next slice is in flight during the multiply), turns them
 // into operand layout through its private LDS patch, and multiplies them into one 32 x 32
 // accumulator.  The eight partial blocks are then added through LDS in wavefront order - each
-// wavefront adds and stores four of the 32 rows - so the result does not depend on timing.  The
-// partial blocks are double-buffered where LDS allows (binary32): one workgroup barrier per block
-// of rows; binary64 has one buffer and two barriers.
+// wavefront adds and stores four of the 32 rows - so the result does not depend on timing.  Two
+// workgroup barriers per block of rows, with the next block's loads in flight across them (a
+// second set of partial blocks, which saves one of the barriers, measured no faster).
 //
 // Evaluation section of the paper: TTM is among the higher-order kernels whose leaves are cast to
 // matrix products; this is that product for the shape a factorisation gives it.
@@ -36,8 +36,7 @@ struct TtmSlicesCfg {
     static constexpr int KMAX = NW * NS * SL;                     // deepest product the registers hold the factor for
     static constexpr int LDP = 32 + 1;                            // partial block: row stride (elements), r-major
     static constexpr int PART = RB * LDP;                         // elements per partial block
-    static constexpr bool TWO = sizeof(T) == 4;                   // two sets of partial blocks
-    static constexpr int LDS_BYTES = (NW * MC::PATCH + (TWO ? 2 : 1) * NW * PART) * (int)sizeof(T);
+    static constexpr int LDS_BYTES = (NW * MC::PATCH + NW * PART) * (int)sizeof(T);
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
 };
 
@@ -96,7 +95,7 @@ ttm_slices_kernel(const TtmSlicesArgs<T> args) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane % MF::MB, ls = lane / MF::MB;
     T *patch = reinterpret_cast<T *>(lds_raw) + wave * MC::PATCH;
-    T *parts = reinterpret_cast<T *>(lds_raw) + NW * MC::PATCH;           // [set][wave][r][l]
+    T *parts = reinterpret_cast<T *>(lds_raw) + NW * MC::PATCH;           // [wave][r][l]
     const int64_t R = args.R, K = args.K, L = args.L;
 
     // this wavefront's slices of the factor, for its whole life
@@ -116,7 +115,6 @@ ttm_slices_kernel(const TtmSlicesArgs<T> args) {
     const int64_t first = blockIdx.x, stride = gridDim.x;
     if (first >= args.rblocks) return;                                   // workgroup-uniform
     fetch(first, 0);
-    int set = 0;
     for (int64_t blk = first; blk < args.rblocks; blk += stride) {
         typename MF::acc_t acc[LB][MI];
 #pragma unroll
@@ -136,7 +134,7 @@ ttm_slices_kernel(const TtmSlicesArgs<T> args) {
             wave_lds_fence();
         }
         // this wavefront's partial block, r-major
-        T *mine = parts + (set * NW + wave) * Cfg::PART;
+        T *mine = parts + wave * Cfg::PART;
 #pragma unroll
         for (int lb = 0; lb < LB; ++lb)
 #pragma unroll
@@ -149,7 +147,7 @@ ttm_slices_kernel(const TtmSlicesArgs<T> args) {
         // rows lane / 32 and lane / 32 + 2 (64 lanes store two neighbouring rows of A: 256 contiguous bytes)
         {
             const int l = lane & 31, ra = 4 * wave + (lane >> 5), rb = ra + 2;
-            const T *src = parts + set * NW * Cfg::PART + l;
+            const T *src = parts + l;
             T s0 = src[ra * LDP], s1 = src[rb * LDP];
 #pragma unroll
             for (int p = 1; p < NW; ++p) {
@@ -163,8 +161,7 @@ ttm_slices_kernel(const TtmSlicesArgs<T> args) {
                 if (!RAGGED || row + rb < R) args.A[(row + rb) * L + l] = s1;
             }
         }
-        if constexpr (Cfg::TWO) set ^= 1;
-        else __syncthreads();
+        __syncthreads();                 // the partial blocks are free again
     }
 }
 
