@@ -36,7 +36,8 @@ struct TtmSlicesCfg {
     static constexpr int KMAX = NW * NS * SL;                     // deepest product the registers hold the factor for
     static constexpr int LDP = 32 + 1;                            // partial block: row stride (elements), r-major
     static constexpr int PART = RB * LDP;                         // elements per partial block
-    static constexpr int LDS_BYTES = (NW * MC::PATCH + NW * PART) * (int)sizeof(T);
+    static_assert(PART <= MC::PATCH, "a partial block lies in its wavefront's patch");
+    static constexpr int LDS_BYTES = NW * MC::PATCH * (int)sizeof(T);
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
 };
 
@@ -95,7 +96,7 @@ ttm_slices_kernel(const TtmSlicesArgs<T> args) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane % MF::MB, ls = lane / MF::MB;
     T *patch = reinterpret_cast<T *>(lds_raw) + wave * MC::PATCH;
-    T *parts = reinterpret_cast<T *>(lds_raw) + NW * MC::PATCH;           // [wave][r][l]
+    T *parts = reinterpret_cast<T *>(lds_raw);       // a wavefront's partial block lies in its own patch, free by then
     const int64_t R = args.R, K = args.K, L = args.L;
 
     // this wavefront's slices of the factor, for its whole life
@@ -134,7 +135,7 @@ ttm_slices_kernel(const TtmSlicesArgs<T> args) {
             wave_lds_fence();
         }
         // this wavefront's partial block, r-major
-        T *mine = parts + wave * Cfg::PART;
+        T *mine = parts + wave * MC::PATCH;
 #pragma unroll
         for (int lb = 0; lb < LB; ++lb)
 #pragma unroll
@@ -151,8 +152,8 @@ ttm_slices_kernel(const TtmSlicesArgs<T> args) {
             T s0 = src[ra * LDP], s1 = src[rb * LDP];
 #pragma unroll
             for (int p = 1; p < NW; ++p) {
-                s0 += src[p * Cfg::PART + ra * LDP];
-                s1 += src[p * Cfg::PART + rb * LDP];
+                s0 += src[p * MC::PATCH + ra * LDP];
+                s1 += src[p * MC::PATCH + rb * LDP];
             }
             const int64_t row = blk * RB;
             if (l < L) {
@@ -161,7 +162,7 @@ ttm_slices_kernel(const TtmSlicesArgs<T> args) {
                 if (!RAGGED || row + rb < R) args.A[(row + rb) * L + l] = s1;
             }
         }
-        __syncthreads();                 // the partial blocks are free again
+        __syncthreads();                 // the patches are free again
     }
 }
 
