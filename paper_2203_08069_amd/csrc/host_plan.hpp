@@ -102,7 +102,7 @@ inline int tile_candidates(bool f64, bool ta, int64_t M, int64_t N, int64_t K, T
     // 65.2 % of peak at 8192 x 8192 x 128 against 62.4 on 128 x 128
     const bool thin_acc64 = acc && K <= 128;
     c[1] = {3, !thin_acc64, 128, 128, 16, {0.901, 0.935, 0.937, 0.941, 0.949, 0.954}};
-    c[2] = {4, true, 64, 64, 16, {0.771, 0.854, 0.889, 0.883, 0.917, 0.909}};
+    c[2] = {4, true, 64, 64, 16, {0.796, 0.854, 0.889, 0.883, 0.917, 0.909}};
     c[3] = {5, true, 128, 64, 16, {0.818, 0.898, 0.905, 0.911, 0.919, 0.930}};
     c[4] = {7, true, 64, 128, 16, {0.841, 0.902, 0.908, 0.925, 0.941, 0.939}};
     c[5] = {6, n32, 128, 32, 16, {}};
