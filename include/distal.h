@@ -33,7 +33,8 @@
  *   - Arithmetic: binary64 expressions multiply and accumulate in binary64;
  *     binary32 expressions multiply and accumulate in binary32 or wider.  No
  *     reduced-precision emulation.  Summation order is fixed for a given call
- *     signature, so results are bitwise reproducible run to run.
+ *     signature (dtype, extents, leading dimensions, flags and the 16-byte
+ *     alignment of the operands), so results are bitwise reproducible run to run.
  */
 #ifndef DISTAL_H
 #define DISTAL_H
